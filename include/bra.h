@@ -1,0 +1,109 @@
+/*
+ * libbra -- forward pass of Bi-Level Routing Attention (BRA) on AMD MI355X (gfx950).
+ *
+ * C ABI.  Every data pointer is CALLER-OWNED DEVICE memory (dense, row-major, no
+ * strides); `shape` and `out_bytes` are host pointers.  The library never
+ * allocates, frees or synchronises: scratch memory comes from `ws` (size from
+ * bra_workspace_bytes, 256-byte aligned) and all work is enqueued on `hip_stream`
+ * (a hipStream_t passed as void*; NULL = the default stream).  Outputs are valid
+ * once the caller has synchronised that stream.  Calls that share a workspace must
+ * be ordered on one stream.
+ *
+ * What is computed (paper: "BiFormer: Vision Transformer with Bi-Level Routing
+ * Attention", Sec. 3.2, Eq. 3-7, Algorithm 1; W^o from Eq. 2):
+ *   1. the H x W map of each image is cut into S x S non-overlapping regions of
+ *      n = (H/S)(W/S) tokens; token (y, x) belongs to region (y / (H/S)) * S + x / (W/S);
+ *   2. Q = X W^q, K = X W^k, V = X W^v                                   (Eq. 3);
+ *   3. Q^r, K^r = per-region means of Q, K over all C channels;
+ *      A^r = Q^r (K^r)^T  in [S^2, S^2]                                  (Eq. 4);
+ *   4. I^r = indices of the k largest entries of each row of A^r          (Eq. 5),
+ *      descending by value, equal values in ascending index order; the routing is
+ *      shared by all heads;
+ *   5. each query token of region i attends, per head (head j owns channels
+ *      [j d, (j+1) d), d = C / heads), to the k n key/value tokens of regions
+ *      I^r[i, 0..k) with ONE softmax over that union                      (Eq. 6-7, Eq. 1);
+ *      the gathered K/V tensors of Eq. 6 are never materialised;
+ *   6. LCE(V): 5 x 5 depth-wise cross-correlation of V over the whole H x W map,
+ *      stride 1, zero padding 2, no bias, is added                        (Eq. 7);
+ *   7. Y = (Attention + LCE(V)) W^o                                       (Eq. 2).
+ *
+ * Layouts:
+ *   X, Y   [B, H, W, C]   channels-last (the paper's (H, W, C) with a batch axis)
+ *   Wqkv   [C, 3C]        = [W^q | W^k | W^v] column blocks, used as x * W
+ *   Wo     [C, C]         used as o * Wo
+ *   Wlce   [C, 5, 5]      (channel, ky, kx); out[y,x,c] = sum w[c,ky,kx] V[y+ky-2, x+kx-2, c]
+ *   Ir     [B, S*S, k]    int32 region indices
+ *   Ar     [B, S*S, S*S]  float32, mean-pooled and unscaled as in Eq. 4
+ * dtype is the element type of X, Wqkv, Wo, Wlce and Y; arithmetic accumulates in
+ * float32 in every path, and the routing (steps 3-4) is always computed in float32
+ * from X so that rounding of stored Q/K never decides an index.
+ */
+#ifndef BRA_H_
+#define BRA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { BRA_F32 = 0, BRA_BF16 = 1 };                 /* bra_shape.dtype */
+
+/* bra_shape.path: which kernel family runs.
+ *   AUTO    the fastest family that supports the shape;
+ *   GENERIC scalar (VALU) float32 kernels, any valid shape, float32 intermediates;
+ *   MFMA    bf16 matrix-core kernels (bf16 only, d = 32, region sizes the tiles
+ *           are built for); BRA_ERR_UNSUPPORTED otherwise. */
+enum { BRA_PATH_AUTO = 0, BRA_PATH_GENERIC = 1, BRA_PATH_MFMA = 2 };
+
+enum {
+    BRA_OK = 0,
+    BRA_ERR_NULL = -1,        /* a required pointer is NULL */
+    BRA_ERR_SHAPE = -2,       /* B,H,W,C,heads,S < 1; H % S or W % S or C % heads != 0 */
+    BRA_ERR_K = -3,           /* k < 1 or k > S*S */
+    BRA_ERR_DTYPE = -4,       /* dtype or path is not one of the enums above */
+    BRA_ERR_WORKSPACE = -5,   /* ws is NULL, misaligned (256 B) or too small */
+    BRA_ERR_UNSUPPORTED = -6, /* valid shape outside what the kernels are built for */
+    BRA_ERR_LAUNCH = -7       /* the HIP runtime reported an error at enqueue time */
+};
+
+typedef struct bra_shape {
+    int32_t B, H, W, C;   /* batch, map height, map width, channels */
+    int32_t heads;        /* attention heads; d = C / heads */
+    int32_t S;            /* regions per side; the paper picks S as a divisor of H and W */
+    int32_t k;            /* regions each region attends to, 1 <= k <= S*S */
+    int32_t dtype;        /* BRA_F32 or BRA_BF16 */
+    float scale;          /* softmax logit scale; <= 0 selects 1/sqrt(d) (Eq. 1 on Eq. 2's heads) */
+    int32_t path;         /* BRA_PATH_* */
+} bra_shape;
+
+/* Host-only.  Bytes of scratch bra_route / bra_forward need for `shape` (the
+ * larger of the two).  Errors: NULL, SHAPE, K, DTYPE, UNSUPPORTED. */
+int bra_workspace_bytes(const bra_shape *shape, size_t *out_bytes);
+
+/* Region-to-region routing only (Eq. 4-5).  Writes Ir [B,S*S,k]; if Ar_opt is not
+ * NULL also the affinity matrix [B,S*S,S*S].  Wqkv's W^v block is not read.
+ * All checks run on the host before anything is enqueued. */
+int bra_route(const bra_shape *shape, const void *X, const void *Wqkv, int32_t *Ir,
+              float *Ar_opt, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Whole BRA forward (steps 1-7).  Ir_out_opt (or NULL) receives the routing index
+ * that was used.  Ir_in_opt (or NULL) forces the routing: steps 3-4 are skipped and
+ * these indices are used instead; entries must lie in [0, S*S) and be distinct
+ * within a row (not checked: they are device data; out-of-range values are
+ * undefined behaviour). */
+int bra_forward(const bra_shape *shape, const void *X, const void *Wqkv, const void *Wo,
+                const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
+                void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Static, human-readable text for a return code. */
+const char *bra_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int bra_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BRA_H_ */

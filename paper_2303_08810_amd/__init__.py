@@ -1,0 +1,142 @@
+"""Thin Python binding of libbra (BRA forward on MI355X): argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in
+include/bra.h.  torch is used for device memory and the current stream.  There is
+no CPU fallback: if libbra.so has not been built, importing the entry points fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbra.so")
+
+BRA_F32, BRA_BF16 = 0, 1
+PATH_AUTO, PATH_GENERIC, PATH_MFMA = 0, 1, 2
+_PATHS = {"auto": PATH_AUTO, "generic": PATH_GENERIC, "mfma": PATH_MFMA}
+
+EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_strerror", "bra_version")
+
+
+class BraShape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32),
+                ("C", ctypes.c_int32), ("heads", ctypes.c_int32), ("S", ctypes.c_int32),
+                ("k", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("path", ctypes.c_int32)]
+
+
+class BraError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libbra error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libbra.so (built by paper_2303_08810_amd/build.py); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2303_08810_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        L.bra_workspace_bytes.restype = ctypes.c_int
+        L.bra_workspace_bytes.argtypes = [ctypes.POINTER(BraShape), ctypes.POINTER(sz)]
+        L.bra_route.restype = ctypes.c_int
+        L.bra_route.argtypes = [ctypes.POINTER(BraShape), vp, vp, vp, vp, vp, sz, vp]
+        L.bra_forward.restype = ctypes.c_int
+        L.bra_forward.argtypes = [ctypes.POINTER(BraShape), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.bra_strerror.restype = ctypes.c_char_p
+        L.bra_strerror.argtypes = [ctypes.c_int]
+        L.bra_version.restype = ctypes.c_int
+        L.bra_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().bra_strerror(int(code)).decode()
+
+
+def _check(code: int) -> None:
+    if code != 0:
+        raise BraError(code, strerror(code))
+
+
+def make_shape(B, H, W, C, heads, S, k, dtype, scale=None, path="auto") -> BraShape:
+    dt = {torch.float32: BRA_F32, torch.bfloat16: BRA_BF16}.get(dtype, dtype)
+    return BraShape(B, H, W, C, heads, S, k, int(dt), float(scale) if scale else 0.0, _PATHS[path])
+
+
+def workspace_bytes(shape: BraShape) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().bra_workspace_bytes(ctypes.byref(shape), ctypes.byref(out)))
+    return out.value
+
+
+def alloc_workspace(shape: BraShape, device) -> torch.Tensor:
+    nbytes = max(workspace_bytes(shape), 256)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    assert ws.data_ptr() % 256 == 0
+    return ws
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _stream(device) -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def _check_inputs(X, Wqkv, Wo=None, Wlce=None):
+    B, H, W, C = X.shape
+    for t in (X, Wqkv, Wo, Wlce):
+        if t is None:
+            continue
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == X.dtype and t.device == X.device):
+            raise ValueError("tensors must be contiguous, on one GPU and of one dtype")
+    if tuple(Wqkv.shape) != (C, 3 * C):
+        raise ValueError("Wqkv must be [C, 3C]")
+    if Wo is not None and tuple(Wo.shape) != (C, C):
+        raise ValueError("Wo must be [C, C]")
+    if Wlce is not None and tuple(Wlce.shape) != (C, 5, 5):
+        raise ValueError("Wlce must be [C, 5, 5]")
+    return B, H, W, C
+
+
+def bra_route(X, Wqkv, S, k, heads, *, want_Ar=False, path="auto", ws=None):
+    """Routing index I^r [B, S*S, k] (int32) and, optionally, A^r [B, S*S, S*S] (float32)."""
+    B, H, W, C = _check_inputs(X, Wqkv)
+    shape = make_shape(B, H, W, C, heads, S, k, X.dtype, None, path)
+    if ws is None:
+        ws = alloc_workspace(shape, X.device)
+    Ir = torch.empty((B, S * S, k), dtype=torch.int32, device=X.device)
+    Ar = torch.empty((B, S * S, S * S), dtype=torch.float32, device=X.device) if want_Ar else None
+    _check(lib().bra_route(ctypes.byref(shape), _ptr(X), _ptr(Wqkv), _ptr(Ir), _ptr(Ar), _ptr(ws),
+                           ws.numel(), _stream(X.device)))
+    return (Ir, Ar) if want_Ar else Ir
+
+
+def bra_forward(X, Wqkv, Wo, Wlce, S, k, heads, *, scale=None, Ir_in=None, want_Ir=False,
+                path="auto", ws=None, out=None):
+    """Y [B, H, W, C] = BRA(X); optionally also the routing index that was used."""
+    B, H, W, C = _check_inputs(X, Wqkv, Wo, Wlce)
+    shape = make_shape(B, H, W, C, heads, S, k, X.dtype, scale, path)
+    if ws is None:
+        ws = alloc_workspace(shape, X.device)
+    Y = out if out is not None else torch.empty_like(X)
+    Ir = torch.empty((B, S * S, k), dtype=torch.int32, device=X.device) if want_Ir else None
+    if Ir_in is not None:
+        if not (Ir_in.is_cuda and Ir_in.is_contiguous() and Ir_in.dtype == torch.int32
+                and tuple(Ir_in.shape) == (B, S * S, k)):
+            raise ValueError("Ir_in must be a contiguous int32 [B, S*S, k] device tensor")
+    _check(lib().bra_forward(ctypes.byref(shape), _ptr(X), _ptr(Wqkv), _ptr(Wo), _ptr(Wlce), _ptr(Y),
+                             _ptr(Ir), _ptr(Ir_in), _ptr(ws), ws.numel(), _stream(X.device)))
+    return (Y, Ir) if want_Ir else Y

@@ -1,0 +1,112 @@
+// C-ABI entry points of libbra: argument checks and dispatch to a kernel family.
+#include "bra_common.h"
+
+#include <math.h>
+
+namespace bra {
+
+// Validates `s` and fills D.  Returns a BRA_* code.
+static int make_dims(const bra_shape *s, Dims &D)
+{
+    if (!s) return BRA_ERR_NULL;
+    if (s->B < 1 || s->H < 1 || s->W < 1 || s->C < 1 || s->heads < 1 || s->S < 1) return BRA_ERR_SHAPE;
+    if (s->H % s->S || s->W % s->S || s->C % s->heads) return BRA_ERR_SHAPE;
+    if ((long)s->S * s->S > (1L << 20)) return BRA_ERR_SHAPE;
+    if (s->k < 1 || s->k > s->S * s->S) return BRA_ERR_K;
+    if (s->dtype != BRA_F32 && s->dtype != BRA_BF16) return BRA_ERR_DTYPE;
+    if (s->path != BRA_PATH_AUTO && s->path != BRA_PATH_GENERIC && s->path != BRA_PATH_MFMA)
+        return BRA_ERR_DTYPE;
+    // element counts must stay addressable with the 31-bit token indices the kernels use
+    if ((long)s->H * s->W > (1L << 30) || (long)s->B * s->H * s->W > (1L << 30)) return BRA_ERR_SHAPE;
+    D.B = s->B; D.H = s->H; D.W = s->W; D.C = s->C; D.heads = s->heads; D.S = s->S; D.k = s->k;
+    D.dtype = s->dtype;
+    D.rh = s->H / s->S; D.rw = s->W / s->S; D.n = D.rh * D.rw; D.R = s->S * s->S;
+    D.N = s->H * s->W; D.d = s->C / s->heads; D.kn = D.k * D.n;
+    D.scale = (s->scale > 0.f) ? s->scale : 1.0f / sqrtf((float)D.d);
+    return BRA_OK;
+}
+
+// Picks the kernel family: returns BRA_PATH_GENERIC / BRA_PATH_MFMA or an error.
+static int pick_path(const bra_shape *s, const Dims &D)
+{
+    const bool mfma_ok = mfma_supported(D);
+    if (s->path == BRA_PATH_MFMA) return mfma_ok ? BRA_PATH_MFMA : BRA_ERR_UNSUPPORTED;
+    if (s->path == BRA_PATH_AUTO && mfma_ok) return BRA_PATH_MFMA;
+    return generic_supported(D) ? BRA_PATH_GENERIC : BRA_ERR_UNSUPPORTED;
+}
+
+static bool ws_ok(const void *ws, size_t have, size_t need)
+{
+    return ws && ((uintptr_t)ws % 256 == 0) && have >= need;
+}
+
+}  // namespace bra
+
+using namespace bra;
+
+extern "C" {
+
+int bra_workspace_bytes(const bra_shape *shape, size_t *out_bytes)
+{
+    if (!out_bytes) return BRA_ERR_NULL;
+    Dims D;
+    int rc = make_dims(shape, D);
+    if (rc != BRA_OK) return rc;
+    int path = pick_path(shape, D);
+    if (path < 0) return path;
+    *out_bytes = (path == BRA_PATH_MFMA) ? mfma_workspace_bytes(D) : generic_workspace_bytes(D);
+    return BRA_OK;
+}
+
+int bra_route(const bra_shape *shape, const void *X, const void *Wqkv, int32_t *Ir, float *Ar_opt,
+              void *ws, size_t ws_bytes, void *hip_stream)
+{
+    Dims D;
+    int rc = make_dims(shape, D);
+    if (rc != BRA_OK) return rc;
+    if (!X || !Wqkv || !Ir) return BRA_ERR_NULL;
+    int path = pick_path(shape, D);
+    if (path < 0) return path;
+    size_t need = (path == BRA_PATH_MFMA) ? mfma_workspace_bytes(D) : generic_workspace_bytes(D);
+    if (!ws_ok(ws, ws_bytes, need)) return BRA_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (path == BRA_PATH_MFMA) return mfma_route(D, X, Wqkv, Ir, Ar_opt, ws, st);
+    return generic_route(D, X, Wqkv, Ir, Ar_opt, ws, st);
+}
+
+int bra_forward(const bra_shape *shape, const void *X, const void *Wqkv, const void *Wo,
+                const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws,
+                size_t ws_bytes, void *hip_stream)
+{
+    Dims D;
+    int rc = make_dims(shape, D);
+    if (rc != BRA_OK) return rc;
+    if (!X || !Wqkv || !Wo || !Wlce || !Y) return BRA_ERR_NULL;
+    int path = pick_path(shape, D);
+    if (path < 0) return path;
+    size_t need = (path == BRA_PATH_MFMA) ? mfma_workspace_bytes(D) : generic_workspace_bytes(D);
+    if (!ws_ok(ws, ws_bytes, need)) return BRA_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (path == BRA_PATH_MFMA)
+        return mfma_forward(D, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, st);
+    return generic_forward(D, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, st);
+}
+
+const char *bra_strerror(int code)
+{
+    switch (code) {
+    case BRA_OK: return "ok";
+    case BRA_ERR_NULL: return "a required pointer is NULL";
+    case BRA_ERR_SHAPE: return "invalid shape (sizes must be positive, S must divide H and W, heads must divide C)";
+    case BRA_ERR_K: return "k must satisfy 1 <= k <= S*S";
+    case BRA_ERR_DTYPE: return "unknown dtype or path";
+    case BRA_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";
+    case BRA_ERR_UNSUPPORTED: return "shape not supported by the requested kernel family";
+    case BRA_ERR_LAUNCH: return "HIP runtime error while enqueueing";
+    default: return "unknown error code";
+    }
+}
+
+int bra_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,62 @@
+// Shared host/device declarations of libbra's kernel families (internal header).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/bra.h"
+
+namespace bra {
+
+typedef unsigned short bf16_t;  // raw bf16 bits
+
+// Shape plus everything derived from it (Sec. 3.2: n tokens per region, R regions).
+struct Dims {
+    int B, H, W, C, heads, S, k, dtype;
+    float scale;
+    int rh, rw, n, R, N, d, kn;
+};
+
+__host__ __device__ inline float bf16_to_f32(bf16_t v)
+{
+    union { uint32_t u; float f; } c;
+    c.u = (uint32_t)v << 16;
+    return c.f;
+}
+
+// Round to nearest, ties to even; NaN stays NaN.
+__host__ __device__ inline bf16_t f32_to_bf16(float f)
+{
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    if ((c.u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((c.u >> 16) | 0x40u);
+    uint32_t lsb = (c.u >> 16) & 1u;
+    return (bf16_t)((c.u + 0x7fffu + lsb) >> 16);
+}
+
+__device__ inline float load_f32(const float *p) { return *p; }
+__device__ inline float load_f32(const bf16_t *p) { return bf16_to_f32(*p); }
+__device__ inline void store_from_f32(float *p, float v) { *p = v; }
+__device__ inline void store_from_f32(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Kernel families.  Each returns a BRA_* code; all checks that can fail happen
+// before the first launch.
+size_t generic_workspace_bytes(const Dims &D);
+int generic_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, float *Ar_opt,
+                  void *ws, hipStream_t st);
+int generic_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo,
+                    const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
+                    void *ws, hipStream_t st);
+bool generic_supported(const Dims &D);
+
+bool mfma_supported(const Dims &D);
+size_t mfma_workspace_bytes(const Dims &D);
+int mfma_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, float *Ar_opt, void *ws,
+               hipStream_t st);
+int mfma_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
+                 void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, hipStream_t st);
+
+}  // namespace bra

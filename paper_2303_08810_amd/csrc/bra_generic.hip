@@ -1,0 +1,381 @@
+// Generic kernel family: scalar (VALU) float32 arithmetic, any valid shape.
+//
+// Used for float32 tensors and for shapes the matrix-core kernels are not built
+// for.  All intermediates (Q, K, V, attention output) are kept in float32 in the
+// workspace, whatever the storage type of X and Y.  The steps follow Sec. 3.2:
+// projection (Eq. 3), region pooling + affinity (Eq. 4), top-k (Eq. 5), routed
+// attention straight from the index (Eq. 6-7, no gathered tensor), LCE, W^o (Eq. 2).
+// Region pooling uses mean(X^r) W = mean(X^r W), which is exact in real arithmetic
+// (the mean is linear; same argument as Appendix A).
+#include "bra_common.h"
+
+#include <math.h>
+
+namespace bra {
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kTopkSlots = 16;      // affinity values per lane: R <= 64 * 16
+constexpr int kAttnChunk = 1024;    // keys per online-softmax chunk
+constexpr int kAttnMaxD = 256;      // head width limit of the generic attention kernel
+
+// ---------------------------------------------------------------------------
+// out[M, N] = A[M, K] * Bm[K, N]  (row-major with leading dimensions), float32 FMA,
+// k ascending.  64 x 64 tile per workgroup, 4 x 4 outputs per thread.
+template <typename TA, typename TB, typename TO>
+__global__ __launch_bounds__(256) void gen_gemm(const TA *__restrict__ A, int lda,
+                                                const TB *__restrict__ Bm, int ldb,
+                                                TO *__restrict__ Out, int ldo, int M, int N, int K)
+{
+    __shared__ float As[16][64 + 4];
+    __shared__ float Bs[16][64];
+    const int tid = threadIdx.x;
+    const int tx = tid % 16, ty = tid / 16;
+    const long m0 = (long)blockIdx.x * 64;
+    const int n0 = blockIdx.y * 64;
+    float acc[4][4];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+    for (int k0 = 0; k0 < K; k0 += 16) {
+        for (int i = 0; i < 4; ++i) {
+            int idx = tid + i * 256;
+            int r = idx / 16, kk = idx % 16;
+            long gm = m0 + r;
+            float v = 0.f;
+            if (gm < M && k0 + kk < K) v = load_f32(A + gm * lda + k0 + kk);
+            As[kk][r] = v;
+            int kb = idx / 64, nn = idx % 64;
+            float w = 0.f;
+            if (k0 + kb < K && n0 + nn < N) w = load_f32(Bm + (long)(k0 + kb) * ldb + n0 + nn);
+            Bs[kb][nn] = w;
+        }
+        __syncthreads();
+        for (int kk = 0; kk < 16; ++kk) {
+            float a[4], b[4];
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+            for (int i = 0; i < 4; ++i)
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    for (int i = 0; i < 4; ++i) {
+        long gm = m0 + ty * 4 + i;
+        if (gm >= M) continue;
+        for (int j = 0; j < 4; ++j) {
+            int gn = n0 + tx * 4 + j;
+            if (gn < N) store_from_f32(Out + gm * ldo + gn, acc[i][j]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Xr[b, r, c] = mean over the n tokens of region r of X[b, :, :, c]; tokens are
+// summed in row-major order inside the region.  One workgroup per (b, r).
+template <typename T>
+__global__ void gen_pool(const T *__restrict__ X, float *__restrict__ Xr, Dims D)
+{
+    const int b = blockIdx.x / D.R, r = blockIdx.x % D.R;
+    const int y0 = (r / D.S) * D.rh, x0 = (r % D.S) * D.rw;
+    const T *img = X + (size_t)b * D.N * D.C;
+    for (int c = threadIdx.x; c < D.C; c += blockDim.x) {
+        float s = 0.f;
+        for (int ry = 0; ry < D.rh; ++ry)
+            for (int rx = 0; rx < D.rw; ++rx)
+                s += load_f32(img + ((size_t)(y0 + ry) * D.W + x0 + rx) * D.C + c);
+        Xr[((size_t)b * D.R + r) * D.C + c] = s / (float)D.n;
+    }
+}
+
+// Qr[b, r, :] = Xr[b, r, :] Wq ; Kr[b, r, :] = Xr[b, r, :] Wk.  One workgroup per (b, r).
+template <typename T>
+__global__ void gen_region_qk(const float *__restrict__ Xr, const T *__restrict__ Wqkv,
+                              float *__restrict__ Qr, float *__restrict__ Kr, Dims D)
+{
+    extern __shared__ float xs[];
+    const size_t row = blockIdx.x;
+    for (int c = threadIdx.x; c < D.C; c += blockDim.x) xs[c] = Xr[row * D.C + c];
+    __syncthreads();
+    for (int o = threadIdx.x; o < 2 * D.C; o += blockDim.x) {
+        float acc = 0.f;
+        for (int c = 0; c < D.C; ++c) acc = fmaf(xs[c], load_f32(Wqkv + (size_t)c * 3 * D.C + o), acc);
+        if (o < D.C) Qr[row * D.C + o] = acc;
+        else Kr[row * D.C + o - D.C] = acc;
+    }
+}
+
+// One wavefront per (b, i): row i of A^r = Q^r (K^r)^T (Eq. 4), then k rounds of a
+// wave-wide arg-max (Eq. 5).  Order: larger value first, equal values by smaller
+// index; NaN counts as -inf so that the k indices are always distinct and valid.
+__global__ __launch_bounds__(kWave) void gen_affinity_topk(const float *__restrict__ Qr,
+                                                           const float *__restrict__ Kr,
+                                                           int32_t *__restrict__ Ir,
+                                                           float *__restrict__ Ar_opt, Dims D)
+{
+    extern __shared__ float qs[];
+    const int b = blockIdx.x / D.R, i = blockIdx.x % D.R;
+    const int lane = threadIdx.x;
+    for (int c = lane; c < D.C; c += kWave) qs[c] = Qr[((size_t)b * D.R + i) * D.C + c];
+    __syncthreads();
+    float vals[kTopkSlots];
+#pragma unroll
+    for (int t = 0; t < kTopkSlots; ++t) {
+        const int j = lane + t * kWave;
+        float a = -INFINITY;
+        if (j < D.R) {
+            const float *kr = Kr + ((size_t)b * D.R + j) * D.C;
+            a = 0.f;
+            for (int c = 0; c < D.C; ++c) a = fmaf(qs[c], kr[c], a);
+            if (Ar_opt) Ar_opt[((size_t)b * D.R + i) * D.R + j] = a;
+            if (!(a == a)) a = -INFINITY;
+        }
+        vals[t] = a;
+    }
+    unsigned taken = 0;  // bit t: slot t of this lane already selected
+    for (int p = 0; p < D.k; ++p) {
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int t = 0; t < kTopkSlots; ++t) {
+            const int j = lane + t * kWave;
+            if (j < D.R && !((taken >> t) & 1u)) {
+                if (bi == 0x7fffffff || vals[t] > bv) { bv = vals[t]; bi = j; }
+            }
+        }
+        for (int off = 32; off >= 1; off >>= 1) {
+            float ov = __shfl_xor(bv, off, kWave);
+            int oi = __shfl_xor(bi, off, kWave);
+            bool take = (oi != 0x7fffffff) && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+            if (take) { bv = ov; bi = oi; }
+        }
+        if (bi % kWave == lane) taken |= 1u << (bi / kWave);
+        if (lane == 0) Ir[((size_t)b * D.R + i) * D.k + p] = bi;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Routed attention, one workgroup (4 wavefronts) per (b, region i, head).  Each
+// wavefront owns one query at a time and runs an online softmax over the k n keys
+// of regions Ir[b, i, :] in chunks; keys and values are read in place from the
+// projected map by index.  QKV is [B, N, 3C] float32 (q | k | v per token).
+__global__ __launch_bounds__(256) void gen_attention(const float *__restrict__ QKV,
+                                                     const int32_t *__restrict__ Ir,
+                                                     float *__restrict__ O, Dims D, float scale)
+{
+    __shared__ float qs[4][kAttnMaxD];
+    __shared__ float sc[4][kAttnChunk];
+    __shared__ int tk[4][kAttnChunk];
+    extern __shared__ int regs[];  // k routed regions
+
+    const int hd = blockIdx.x % D.heads;
+    const int i = (blockIdx.x / D.heads) % D.R;
+    const int b = blockIdx.x / (D.heads * D.R);
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int C3 = 3 * D.C;
+    const float *img = QKV + (size_t)b * D.N * C3;
+
+    for (int p = threadIdx.x; p < D.k; p += blockDim.x) regs[p] = Ir[((size_t)b * D.R + i) * D.k + p];
+    __syncthreads();
+
+    const int y0 = (i / D.S) * D.rh, x0 = (i % D.S) * D.rw;
+    const int iters = (D.n + 3) / 4;
+    for (int it = 0; it < iters; ++it) {
+        const int s = it * 4 + wave;
+        const bool active = s < D.n;
+        int qtok = 0;
+        if (active) {
+            qtok = (y0 + s / D.rw) * D.W + x0 + s % D.rw;
+            for (int c = lane; c < D.d; c += kWave) qs[wave][c] = img[(size_t)qtok * C3 + hd * D.d + c];
+        }
+        float m = -INFINITY, l = 0.f;
+        float acc[kAttnMaxD / kWave];
+        for (int t = 0; t < kAttnMaxD / kWave; ++t) acc[t] = 0.f;
+        __syncthreads();
+        for (int c0 = 0; c0 < D.kn; c0 += kAttnChunk) {
+            const int cn = min(kAttnChunk, D.kn - c0);
+            float lm = -INFINITY;
+            if (active) {
+                for (int u = lane; u < cn; u += kWave) {
+                    const int g = c0 + u;
+                    const int j = regs[g / D.n], slot = g % D.n;
+                    const int tok = ((j / D.S) * D.rh + slot / D.rw) * D.W + (j % D.S) * D.rw + slot % D.rw;
+                    const float *kr = img + (size_t)tok * C3 + D.C + hd * D.d;
+                    float a = 0.f;
+                    for (int c = 0; c < D.d; ++c) a = fmaf(qs[wave][c], kr[c], a);
+                    a *= scale;
+                    sc[wave][u] = a;
+                    tk[wave][u] = tok;
+                    lm = fmaxf(lm, a);
+                }
+            }
+            for (int off = 32; off >= 1; off >>= 1) lm = fmaxf(lm, __shfl_xor(lm, off, kWave));
+            const float m_new = fmaxf(m, lm);
+            const float corr = (m == -INFINITY) ? 0.f : expf(m - m_new);
+            float ls = 0.f;
+            if (active) {
+                for (int u = lane; u < cn; u += kWave) {
+                    float pv = expf(sc[wave][u] - m_new);
+                    sc[wave][u] = pv;
+                    ls += pv;
+                }
+            }
+            for (int off = 32; off >= 1; off >>= 1) ls += __shfl_xor(ls, off, kWave);
+            l = l * corr + ls;
+            m = m_new;
+            __syncthreads();
+            if (active) {
+                for (int t = 0; t < kAttnMaxD / kWave; ++t) {
+                    const int c = lane + t * kWave;
+                    if (c < D.d) {
+                        float a = acc[t] * corr;
+                        for (int u = 0; u < cn; ++u)
+                            a = fmaf(sc[wave][u], img[(size_t)tk[wave][u] * C3 + 2 * D.C + hd * D.d + c], a);
+                        acc[t] = a;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        if (active) {
+            for (int t = 0; t < kAttnMaxD / kWave; ++t) {
+                const int c = lane + t * kWave;
+                if (c < D.d) O[((size_t)b * D.N + qtok) * D.C + hd * D.d + c] = acc[t] / l;
+            }
+        }
+    }
+}
+
+// O[b, y, x, c] += sum_{ky,kx} Wlce[c, ky, kx] * V[b, y+ky-2, x+kx-2, c], V = 0 outside.
+template <typename T>
+__global__ void gen_lce_add(const float *__restrict__ QKV, const T *__restrict__ Wlce,
+                            float *__restrict__ O, Dims D)
+{
+    const size_t total = (size_t)D.B * D.N * D.C;
+    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= total) return;
+    const int c = e % D.C;
+    const size_t t = e / D.C;
+    const int x = t % D.W, y = (t / D.W) % D.H;
+    const size_t b = t / D.N;
+    const float *img = QKV + b * D.N * 3 * D.C + 2 * D.C + c;
+    float acc = 0.f;
+    for (int ky = 0; ky < 5; ++ky) {
+        const int yy = y + ky - 2;
+        if (yy < 0 || yy >= D.H) continue;
+        for (int kx = 0; kx < 5; ++kx) {
+            const int xx = x + kx - 2;
+            if (xx < 0 || xx >= D.W) continue;
+            acc = fmaf(load_f32(Wlce + (c * 5 + ky) * 5 + kx), img[((size_t)yy * D.W + xx) * 3 * D.C], acc);
+        }
+    }
+    O[e] += acc;
+}
+
+struct GenericWs {
+    float *qkv, *o, *xr, *qr, *kr;
+    int32_t *ir;
+    size_t bytes;
+};
+
+GenericWs carve(const Dims &D, void *ws)
+{
+    GenericWs w;
+    char *p = (char *)ws;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *q = p ? p + off : nullptr; off += align256(bytes); return q; };
+    const size_t tok = (size_t)D.B * D.N, reg = (size_t)D.B * D.R;
+    w.qkv = (float *)take(tok * 3 * D.C * sizeof(float));
+    w.o = (float *)take(tok * D.C * sizeof(float));
+    w.xr = (float *)take(reg * D.C * sizeof(float));
+    w.qr = (float *)take(reg * D.C * sizeof(float));
+    w.kr = (float *)take(reg * D.C * sizeof(float));
+    w.ir = (int32_t *)take(reg * D.k * sizeof(int32_t));
+    w.bytes = off;
+    return w;
+}
+
+template <typename T>
+void launch_route(const Dims &D, const T *X, const T *Wqkv, int32_t *Ir, float *Ar_opt,
+                  const GenericWs &w, hipStream_t st)
+{
+    const int regs = D.B * D.R;
+    const int pt = D.C < 256 ? ((D.C + 63) / 64) * 64 : 256;
+    hipLaunchKernelGGL(gen_pool<T>, dim3(regs), dim3(pt), 0, st, X, w.xr, D);
+    hipLaunchKernelGGL(gen_region_qk<T>, dim3(regs), dim3(256), D.C * sizeof(float), st, w.xr, Wqkv,
+                       w.qr, w.kr, D);
+    hipLaunchKernelGGL(gen_affinity_topk, dim3(regs), dim3(kWave), D.C * sizeof(float), st, w.qr,
+                       w.kr, Ir, Ar_opt, D);
+}
+
+template <typename T>
+int forward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *Wlce, T *Y,
+              int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, hipStream_t st)
+{
+    GenericWs w = carve(D, ws);
+    const long M = (long)D.B * D.N;
+    const int32_t *Ir = Ir_in_opt;
+    if (!Ir_in_opt) {
+        int32_t *dst = Ir_out_opt ? Ir_out_opt : w.ir;
+        launch_route<T>(D, X, Wqkv, dst, nullptr, w, st);
+        Ir = dst;
+    } else if (Ir_out_opt) {
+        if (hipMemcpyAsync(Ir_out_opt, Ir_in_opt, sizeof(int32_t) * (size_t)D.B * D.R * D.k,
+                           hipMemcpyDeviceToDevice, st) != hipSuccess)
+            return BRA_ERR_LAUNCH;
+    }
+    dim3 g1((unsigned)((M + 63) / 64), (unsigned)((3 * D.C + 63) / 64));
+    hipLaunchKernelGGL((gen_gemm<T, T, float>), g1, dim3(256), 0, st, X, D.C, Wqkv, 3 * D.C, w.qkv,
+                       3 * D.C, (int)M, 3 * D.C, D.C);
+    hipLaunchKernelGGL(gen_attention, dim3(D.B * D.R * D.heads), dim3(256), D.k * sizeof(int), st,
+                       w.qkv, Ir, w.o, D, D.scale);
+    const size_t total = (size_t)M * D.C;
+    hipLaunchKernelGGL(gen_lce_add<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       w.qkv, Wlce, w.o, D);
+    dim3 g2((unsigned)((M + 63) / 64), (unsigned)((D.C + 63) / 64));
+    hipLaunchKernelGGL((gen_gemm<float, T, T>), g2, dim3(256), 0, st, w.o, D.C, Wo, D.C, Y, D.C,
+                       (int)M, D.C, D.C);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+}  // namespace
+
+bool generic_supported(const Dims &D)
+{
+    // grid sizes must fit 31 bits; head width and region count are bounded by the
+    // static buffers of the attention and top-k kernels.
+    if (D.d > kAttnMaxD) return false;
+    if (D.R > kWave * kTopkSlots) return false;
+    if ((long)D.B * D.R * D.heads > 0x7fffffffL) return false;
+    if (((long)D.B * D.N * D.C + 255) / 256 > 0x7fffffffL) return false;
+    if ((size_t)D.k * sizeof(int) > 16 * 1024) return false;
+    if ((size_t)D.C * sizeof(float) > 48 * 1024) return false;
+    return true;
+}
+
+size_t generic_workspace_bytes(const Dims &D) { return carve(D, nullptr).bytes; }
+
+int generic_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, float *Ar_opt,
+                  void *ws, hipStream_t st)
+{
+    GenericWs w = carve(D, ws);
+    if (D.dtype == BRA_F32)
+        launch_route<float>(D, (const float *)X, (const float *)Wqkv, Ir, Ar_opt, w, st);
+    else
+        launch_route<bf16_t>(D, (const bf16_t *)X, (const bf16_t *)Wqkv, Ir, Ar_opt, w, st);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+int generic_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo,
+                    const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
+                    void *ws, hipStream_t st)
+{
+    if (D.dtype == BRA_F32)
+        return forward_t<float>(D, (const float *)X, (const float *)Wqkv, (const float *)Wo,
+                                (const float *)Wlce, (float *)Y, Ir_out_opt, Ir_in_opt, ws, st);
+    return forward_t<bf16_t>(D, (const bf16_t *)X, (const bf16_t *)Wqkv, (const bf16_t *)Wo,
+                             (const bf16_t *)Wlce, (bf16_t *)Y, Ir_out_opt, Ir_in_opt, ws, st);
+}
+
+}  // namespace bra

@@ -1,0 +1,76 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol that
+include/bra.h declares, and turns invalid arguments into error codes before any
+GPU work (none of these calls reaches a kernel launch)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2303_08810_amd as bra
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "bra.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bra_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = bra.lib()
+    names = declared_functions()
+    assert set(names) == set(bra.EXPORTS)
+    for name in names:
+        assert getattr(L, name) is not None
+    assert L.bra_version() >= 100
+
+
+def ws_bytes(**kw):
+    base = dict(B=1, H=28, W=28, C=64, heads=2, S=7, k=4, dtype=bra.BRA_F32, scale=None, path="auto")
+    base.update(kw)
+    shape = bra.make_shape(**base)
+    out = ctypes.c_size_t(0)
+    return bra.lib().bra_workspace_bytes(ctypes.byref(shape), ctypes.byref(out)), out.value
+
+
+def test_workspace_query_and_error_codes():
+    rc, n = ws_bytes()
+    assert rc == 0 and n > 0 and n % 256 == 0
+    assert ws_bytes(S=5)[0] == -2            # S does not divide H
+    assert ws_bytes(heads=3)[0] == -2        # heads does not divide C
+    assert ws_bytes(B=0)[0] == -2
+    assert ws_bytes(k=0)[0] == -3
+    assert ws_bytes(k=50)[0] == -3
+    assert ws_bytes(k=49)[0] == 0
+    assert ws_bytes(dtype=7)[0] == -4
+    assert ws_bytes(path="mfma")[0] == -6    # matrix-core kernels are bf16 only
+    assert bra.lib().bra_workspace_bytes(None, None) == -1
+    for code in range(0, -8, -1):
+        assert bra.strerror(code) != "unknown error code"
+    assert bra.strerror(-99) == "unknown error code"
+
+
+def test_entry_points_reject_bad_arguments_before_launching():
+    L = bra.lib()
+    shape = bra.make_shape(1, 28, 28, 64, 2, 7, 4, bra.BRA_F32)
+    fake = ctypes.c_void_p(4096)             # never dereferenced: checks fail first
+    assert L.bra_forward(ctypes.byref(shape), None, fake, fake, fake, fake, None, None, fake, 1 << 30, None) == -1
+    assert L.bra_route(ctypes.byref(shape), fake, fake, None, None, fake, 1 << 30, None) == -1
+    # workspace NULL / misaligned / too small
+    assert L.bra_forward(ctypes.byref(shape), fake, fake, fake, fake, fake, None, None, None, 1 << 30, None) == -5
+    assert L.bra_forward(ctypes.byref(shape), fake, fake, fake, fake, fake, None, None,
+                         ctypes.c_void_p(4096 + 8), 1 << 30, None) == -5
+    assert L.bra_forward(ctypes.byref(shape), fake, fake, fake, fake, fake, None, None, fake, 16, None) == -5
+    assert L.bra_route(ctypes.byref(shape), fake, fake, fake, None, fake, 16, None) == -5
+    bad = bra.make_shape(1, 28, 28, 64, 2, 7, 50, bra.BRA_F32)
+    assert L.bra_forward(ctypes.byref(bad), fake, fake, fake, fake, fake, None, None, fake, 1 << 30, None) == -3
+    assert L.bra_forward(None, fake, fake, fake, fake, fake, None, None, fake, 1 << 30, None) == -1
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(bra, "_lib", None)
+    monkeypatch.setattr(bra, "LIB_PATH", str(tmp_path / "libbra.so"))
+    with pytest.raises(ImportError):
+        bra.lib()

@@ -1,0 +1,129 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by
+element on the same seeded inputs.
+
+Bars: routing indices bit-exact wherever the oracle's affinity gap exceeds 1e-3
+(parity_util.check_routing); Y within max-abs 1e-4 for float32 tensors and within
+2e-2 of max|Y_ref| for bf16 tensors.  When a near-tie made the GPU pick another
+(equally valid) region, Y is compared against the oracle run on the GPU's routing.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2303_08810_amd as bra
+from parity_util import (check_output, check_routing, run_oracle, to_device, to_numpy)
+from synthetic_inputs import CONFIGS, make_config_inputs, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_forward(Xn, Wqkvn, Won, Wlcen, dtype, S, k, heads, path, scale=None, Ir_in=None):
+    X, Wqkv, Wo, Wlce = (to_device(a, dtype) for a in (Xn, Wqkvn, Won, Wlcen))
+    Iin = torch.from_numpy(np.ascontiguousarray(Ir_in, dtype=np.int32)).cuda() if Ir_in is not None else None
+    Y, Ir = bra.bra_forward(X, Wqkv, Wo, Wlce, S, k, heads, scale=scale, Ir_in=Iin, want_Ir=True,
+                            path=path)
+    Ir2, Ar = bra.bra_route(X, Wqkv, S, k, heads, want_Ar=True, path=path)
+    torch.cuda.synchronize()
+    return to_numpy(Y), Ir.cpu().numpy(), Ir2.cpu().numpy(), Ar.cpu().numpy()
+
+
+def compare(Xn, Wqkvn, Won, Wlcen, dtype, S, k, heads, path, scale=None, images=None):
+    print(f"case dtype={dtype} shape={Xn.shape} S={S} k={k} heads={heads} path={path}", flush=True)
+    Y, Ir, Ir2, Ar = gpu_forward(Xn, Wqkvn, Won, Wlcen, dtype, S, k, heads, path, scale)
+    sel = np.arange(Xn.shape[0]) if images is None else np.asarray(images)
+    kw = dict(S=S, k=k, heads=heads, scale=scale)
+    ref = run_oracle(Xn[sel], Wqkvn, Won, Wlcen, kw)
+    # routing: forward's index and bra_route's index are the same computation
+    np.testing.assert_array_equal(Ir, Ir2)
+    assert np.abs(Ar[sel] - ref["Ar"]).max() < 1e-4
+    diff_rows = check_routing(Ir[sel], ref["Ar"], k)
+    if diff_rows:
+        ref = run_oracle(Xn[sel], Wqkvn, Won, Wlcen, kw, Ir_in=Ir[sel])
+    err = check_output(Y[sel], ref["Y"], dtype)
+    print(f"  rows routed differently (near ties): {diff_rows}; max-abs err {err:.3e}", flush=True)
+    return err
+
+
+SMALL = [  # (B, H, W, C, heads, S, k): ragged tiles, odd head widths, n = 1, k = R, kn > one chunk
+    (2, 12, 12, 48, 3, 3, 2),
+    (3, 10, 15, 40, 5, 5, 7),
+    (2, 7, 7, 64, 2, 7, 49),
+    (1, 16, 8, 64, 1, 2, 4),
+    (2, 14, 14, 96, 3, 7, 16),
+    (1, 64, 64, 32, 1, 2, 2),
+    (1, 24, 24, 130, 2, 4, 5),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,H,W,C,heads,S,k", SMALL)
+def test_generic_path_small_shapes(B, H, W, C, heads, S, k, dtype):
+    X, Wqkv, Wo, Wlce = make_inputs(B, H, W, C, seed=1000 + H + 3 * C + k, dtype=dtype)
+    err = compare(X, Wqkv, Wo, Wlce, dtype, S, k, heads, "generic")
+    # the generic family keeps float32 intermediates: it must be near the oracle even
+    # on bf16 tensors, up to the final rounding of Y to bf16
+    assert err < (1e-4 if dtype == "f32" else 4e-2)
+
+
+def test_generic_scale_argument():
+    X, Wqkv, Wo, Wlce = make_inputs(1, 8, 8, 64, seed=5)
+    compare(X, Wqkv, Wo, Wlce, "f32", 2, 2, 2, "generic", scale=1.0)
+    compare(X, Wqkv, Wo, Wlce, "f32", 2, 2, 2, "generic", scale=0.125)
+
+
+def test_forced_self_routing_is_window_attention():
+    cfg = CONFIGS[1]
+    X, Wqkv, Wo, Wlce = make_config_inputs(cfg)
+    Ir_in = np.broadcast_to(np.arange(cfg.R, dtype=np.int32)[None, :, None], (cfg.B, cfg.R, 1)).copy()
+    Y, Ir, _, _ = gpu_forward(X, Wqkv, Wo, Wlce, "f32", cfg.S, 1, cfg.heads, "auto", Ir_in=Ir_in)
+    np.testing.assert_array_equal(Ir, Ir_in)
+    ref = run_oracle(X, Wqkv, Wo, Wlce, dict(S=cfg.S, k=1, heads=cfg.heads), Ir_in=Ir_in)
+    check_output(Y, ref["Y"], "f32")
+
+
+# The five named workloads at their full sizes, in the launch configuration that
+# bench.py times (path "auto"); the oracle checks a sample of whole images.
+FULL = {1: None, 2: [0, 31, 63], 3: [0, 17, 63], 4: [0, 1, 40, 63], 5: [1]}
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_named_workloads_full_size(idx):
+    cfg = CONFIGS[idx]
+    X, Wqkv, Wo, Wlce = make_config_inputs(cfg)
+    compare(X, Wqkv, Wo, Wlce, cfg.dtype, cfg.S, cfg.k, cfg.heads, "auto", images=FULL[idx])
+
+
+@pytest.mark.parametrize("idx", [2, 4])
+def test_named_workloads_generic_family(idx):
+    cfg = CONFIGS[idx]
+    X, Wqkv, Wo, Wlce = make_config_inputs(cfg, batch=2)
+    compare(X, Wqkv, Wo, Wlce, cfg.dtype, cfg.S, cfg.k, cfg.heads, "generic")
+
+
+def test_repeated_runs_are_bit_identical():
+    cfg = CONFIGS[3]
+    Xn, Wqkvn, Won, Wlcen = make_config_inputs(cfg, batch=4)
+    X, Wqkv, Wo, Wlce = (to_device(a, cfg.dtype) for a in (Xn, Wqkvn, Won, Wlcen))
+    outs = []
+    for _ in range(5):
+        Y, Ir = bra.bra_forward(X, Wqkv, Wo, Wlce, cfg.S, cfg.k, cfg.heads, want_Ir=True)
+        torch.cuda.synchronize()
+        outs.append((Y.view(torch.int16).cpu().numpy().copy(), Ir.cpu().numpy().copy()))
+    for y, i in outs[1:]:
+        np.testing.assert_array_equal(y, outs[0][0])
+        np.testing.assert_array_equal(i, outs[0][1])
+
+
+def test_constant_image_ties_and_zero_input():
+    # constant image: every affinity equal -> indices 0..k-1 ascending (tie rule)
+    H = W = 14; C = 64; S = 7; k = 4; heads = 2
+    _, Wqkv, Wo, Wlce = make_inputs(1, H, W, C, seed=3)
+    x0 = np.linspace(-1, 1, C).astype(np.float32)
+    X = np.broadcast_to(x0, (1, H, W, C)).copy()
+    Y, Ir, _, _ = gpu_forward(X, Wqkv, Wo, Wlce, "f32", S, k, heads, "auto")
+    assert np.all(Ir == np.arange(k))
+    ref = run_oracle(X, Wqkv, Wo, Wlce, dict(S=S, k=k, heads=heads), Ir_in=Ir)
+    check_output(Y, ref["Y"], "f32")
+    Xz = np.zeros_like(X)
+    Y, Ir, _, _ = gpu_forward(Xz, Wqkv, Wo, Wlce, "f32", S, k, heads, "auto")
+    assert np.all(Y == 0) and np.all(Ir == np.arange(k))
