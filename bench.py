@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the BRA forward hot path on one MI355X.
+
+A "step" is one bra_forward call (every step of the path: routing, projections,
+routed attention, LCE, output projection) over one batch of the stage-1 BiFormer
+shape (B=64, 56x56 map, C=64, 2 heads, S=7, k=1, bf16), inputs resident in HBM.
+Prints ONE JSON line.  The line also carries: the roofline figures of the kernel
+that takes the most time (timed live with events on the launch stream), the CPU
+oracle's rate on a bounded sample of the same workload, and the throughput of the
+other named workloads.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "BRA fwd images/sec per stage shape + achieved TFLOP/s and HBM GB/s"
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+VALU_F32_PEAK_TFLOPS = 157.3
+
+
+def flops_per_image(cfg):
+    """Algorithmic flops of one image (2 per multiply-add): projections (Eq. 3),
+    region pooling + routing (Eq. 4), attention (Eq. 7), LCE, W^o (Eq. 2)."""
+    N, C, R, n, kn = cfg.H * cfg.W, cfg.C, cfg.R, cfg.n, cfg.kn
+    proj = 6 * N * C * C
+    pool = N * C + 4 * R * C * C
+    aff = 2 * R * R * C
+    attn = 4 * N * kn * C
+    lce = 50 * N * C
+    wo = 2 * N * C * C
+    return dict(proj=proj, pool=pool, aff=aff, attn=attn, lce=lce, wo=wo,
+                total=proj + pool + aff + attn + lce + wo)
+
+
+def kernel_model(name, cfg):
+    """(bound, work per launch, unit of `achieved`, peak) of one library kernel.
+
+    HBM-bound kernels are priced on their ALGORITHMIC bytes: unit = N*C*eb bytes
+    per image (one pass over a token tensor in the storage type)."""
+    eb = 2 if cfg.dtype == "bf16" else 4
+    unit = cfg.H * cfg.W * cfg.C * eb * cfg.B
+    f = flops_per_image(cfg)
+    B = cfg.B
+    table = {
+        # generic (VALU float32) family
+        "gen_pool": ("hbm", unit, HBM_PEAK_GBS),
+        "gen_region_qk": ("alu", B * 4 * cfg.R * cfg.C * cfg.C, VALU_F32_PEAK_TFLOPS),
+        "gen_affinity_topk": ("alu", B * f["aff"], VALU_F32_PEAK_TFLOPS),
+        "gen_gemm_qkv": ("alu", B * f["proj"], VALU_F32_PEAK_TFLOPS),
+        "gen_attention": ("alu", B * f["attn"], VALU_F32_PEAK_TFLOPS),
+        "gen_lce_add": ("alu", B * f["lce"], VALU_F32_PEAK_TFLOPS),
+        "gen_gemm_wo": ("alu", B * f["wo"], VALU_F32_PEAK_TFLOPS),
+        # matrix-core family
+        "mfma_pool": ("hbm", unit, HBM_PEAK_GBS),                      # reads X once
+        "mfma_route": ("alu", B * (4 * cfg.R * cfg.C * cfg.C + f["aff"]), VALU_F32_PEAK_TFLOPS),
+        "mfma_qkv": ("hbm", 4 * unit, HBM_PEAK_GBS),                   # X in, Q K V out
+        "mfma_attention": ("hbm", 4 * unit, HBM_PEAK_GBS),             # Q K V in, Y out
+        "mfma_fused_k1": ("hbm", 2 * unit, HBM_PEAK_GBS),              # X in, Y out
+    }
+    return table[name]
+
+
+def device_inputs(cfg, sets):
+    import numpy as np
+    import torch
+
+    from synthetic_inputs import bf16_bits, make_config_inputs
+
+    X, Wqkv, Wo, Wlce = make_config_inputs(cfg)
+
+    def dev(a):
+        if cfg.dtype == "bf16":
+            return torch.from_numpy(bf16_bits(a).view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(a).cuda()
+
+    Xd = dev(X)
+    # rotating input/output sets so that the footprint exceeds the 256 MB last-level cache
+    Xs = [Xd] + [torch.roll(Xd, shifts=i, dims=0).contiguous() for i in range(1, sets)]
+    Ys = [torch.empty_like(Xd) for _ in range(sets)]
+    return (X, Wqkv, Wo, Wlce), Xs, Ys, dev(Wqkv), dev(Wo), dev(Wlce)
+
+
+def time_config(cfg, steps, warmup, profile=True):
+    import torch
+
+    import paper_2303_08810_amd as bra
+
+    unit_mb = cfg.B * cfg.H * cfg.W * cfg.C * (2 if cfg.dtype == "bf16" else 4) / 1e6
+    sets = max(2, min(24, int(600 / (2 * unit_mb)) + 1))
+    host, Xs, Ys, Wqkv, Wo, Wlce = device_inputs(cfg, sets)
+    shape = bra.make_shape(cfg.B, cfg.H, cfg.W, cfg.C, cfg.heads, cfg.S, cfg.k, Xs[0].dtype)
+    ws = bra.alloc_workspace(shape, Xs[0].device)
+
+    def step(i):
+        bra.bra_forward(Xs[i % sets], Wqkv, Wo, Wlce, cfg.S, cfg.k, cfg.heads, ws=ws, out=Ys[i % sets])
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = max(wall_ms, ev_ms) / steps
+
+    kernels = {}
+    if profile:
+        # the same K steps again, every kernel launch bracketed by two events on the stream
+        per_step = 16
+        bra.profile_begin(steps * per_step)
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        for name, ms in bra.profile_end(steps * per_step):
+            k = kernels.setdefault(name, [0, 0.0])
+            k[0] += 1
+            k[1] += ms
+    return dict(ms_per_step=ms_per_step, wall_ms=wall_ms, event_ms=ev_ms, kernels=kernels,
+                host=host, sets=sets)
+
+
+def roofline_of(cfg, kernels):
+    if not kernels:
+        return None, {}
+    summary = {n: dict(launches=c, avg_us=1e3 * t / c) for n, (c, t) in kernels.items()}
+    name = max(kernels, key=lambda n: kernels[n][1])
+    bound, work, peak = kernel_model(name, cfg)
+    avg_s = kernels[name][1] / kernels[name][0] / 1e3
+    if bound == "hbm":
+        achieved, unit = work / avg_s / 1e9, "GB/s"
+    else:
+        achieved, unit = work / avg_s / 1e12, "TFLOP/s"
+    roof = dict(kernel=name, bound=bound, achieved=round(achieved, 2), peak=peak, unit=unit,
+                frac=round(achieved / peak, 4), traffic=None,
+                avg_us=round(avg_s * 1e6, 2), work_per_launch=work)
+    return roof, summary
+
+
+def cpu_baseline(cfg, host, budget_s=12.0):
+    """The oracle (float32 instance, as it stands) on the host cores, on whole
+    images taken from the same batch; OpenMP over images."""
+    import numpy as np
+
+    import oracle
+
+    X, Wqkv, Wo, Wlce = host
+    threads = max(1, min(16, os.cpu_count() or 1))
+    kw = dict(S=cfg.S, k=cfg.k, heads=cfg.heads, precision="f32", threads=threads)
+    n0 = min(threads, X.shape[0])
+    t0 = time.perf_counter()
+    oracle.bra_forward(X[:n0], Wqkv, Wo, Wlce, **kw)
+    t_probe = time.perf_counter() - t0
+    n_img = int(min(max(n0, n0 * (budget_s / max(t_probe, 1e-3))), 16 * n0))
+    n_img = max(n0, (n_img // n0) * n0)
+    idx = np.arange(n_img) % X.shape[0]
+    t0 = time.perf_counter()
+    oracle.bra_forward(np.ascontiguousarray(X[idx]), Wqkv, Wo, Wlce, **kw)
+    dt = time.perf_counter() - t0
+    return dict(value=round(n_img / dt, 3), unit="images/s", cores=threads, kind="oracle",
+                sample=f"{n_img} whole images of the same workload (float32 oracle, OpenMP over images), {dt:.1f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, help="named workload index 1..5 (default 2)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the other named workloads")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (images are independent; data "
+              "parallelism over several GPUs needs no exchange and is not part of this build)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from synthetic_inputs import CONFIGS
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = CONFIGS[args.workload]
+    res = time_config(cfg, args.steps, args.warmup)
+    f = flops_per_image(cfg)
+    ms = res["ms_per_step"]
+    value = cfg.B / (ms / 1e3)
+    roof, summary = roofline_of(cfg, res["kernels"])
+    eb = 2 if cfg.dtype == "bf16" else 4
+    line = {
+        "metric": METRIC, "value": round(value, 1), "unit": "images/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} H=W={cfg.H} C={cfg.C} heads={cfg.heads} "
+                               f"S={cfg.S} k={cfg.k} {cfg.dtype}", "rotating_input_sets": res["sets"]},
+        "achieved_tflops": round(cfg.B * f["total"] / (ms / 1e3) / 1e12, 3),
+        "min_traffic_gbs": round(2 * cfg.B * cfg.H * cfg.W * cfg.C * eb / (ms / 1e3) / 1e9, 1),
+        "roofline": roof, "kernels": {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2)}
+                                      for k, v in summary.items()},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, res["host"])
+    if not args.no_others:
+        others = {}
+        for idx, c in CONFIGS.items():
+            if idx == args.workload:
+                continue
+            r = time_config(c, max(20, args.steps // 4), max(5, args.warmup // 2), profile=True)
+            fo = flops_per_image(c)
+            rf, sm = roofline_of(c, r["kernels"])
+            others[c.name] = {
+                "images_per_s": round(c.B / (r["ms_per_step"] / 1e3), 1),
+                "ms_per_step": round(r["ms_per_step"], 5),
+                "achieved_tflops": round(c.B * fo["total"] / (r["ms_per_step"] / 1e3) / 1e12, 3),
+                "dominant": rf,
+                "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in sm.items()},
+            }
+        line["other_workloads"] = others
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

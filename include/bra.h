@@ -97,6 +97,21 @@ int bra_forward(const bra_shape *shape, const void *X, const void *Wqkv, const v
                 const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
                 void *ws, size_t ws_bytes, void *hip_stream);
 
+/* Optional per-launch timing, for benchmarks (Sec. "Limitation": the paper locates
+ * BRA's cost in kernel launches and memory transactions, so the benchmark reports
+ * time per kernel).  Host-only state, one session at a time, not thread-safe.
+ * bra_profile_begin creates 2 * max_records HIP events; from then on every kernel
+ * the library enqueues is bracketed by two events on the caller's stream, until
+ * max_records launches have been recorded.  bra_profile_end waits for the recorded
+ * events, writes up to max_records (kernel id, milliseconds) pairs in launch order
+ * to the HOST arrays ids / ms, stores the count in *n_out and destroys the events.
+ * bra_kernel_name maps a kernel id to a static string.
+ * Errors: SHAPE (begin while active, end while inactive, max_records < 1), NULL,
+ * LAUNCH (event API failure). */
+int bra_profile_begin(int max_records);
+int bra_profile_end(int32_t *ids, float *ms, int max_records, int *n_out);
+const char *bra_kernel_name(int id);
+
 /* Static, human-readable text for a return code. */
 const char *bra_strerror(int code);
 

@@ -18,7 +18,8 @@ BRA_F32, BRA_BF16 = 0, 1
 PATH_AUTO, PATH_GENERIC, PATH_MFMA = 0, 1, 2
 _PATHS = {"auto": PATH_AUTO, "generic": PATH_GENERIC, "mfma": PATH_MFMA}
 
-EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_strerror", "bra_version")
+EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_strerror", "bra_version",
+           "bra_profile_begin", "bra_profile_end", "bra_kernel_name")
 
 
 class BraShape(ctypes.Structure):
@@ -56,6 +57,13 @@ def lib() -> ctypes.CDLL:
         L.bra_strerror.argtypes = [ctypes.c_int]
         L.bra_version.restype = ctypes.c_int
         L.bra_version.argtypes = []
+        L.bra_profile_begin.restype = ctypes.c_int
+        L.bra_profile_begin.argtypes = [ctypes.c_int]
+        L.bra_profile_end.restype = ctypes.c_int
+        L.bra_profile_end.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float),
+                                      ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+        L.bra_kernel_name.restype = ctypes.c_char_p
+        L.bra_kernel_name.argtypes = [ctypes.c_int]
         _lib = L
     return _lib
 
@@ -140,3 +148,17 @@ def bra_forward(X, Wqkv, Wo, Wlce, S, k, heads, *, scale=None, Ir_in=None, want_
     _check(lib().bra_forward(ctypes.byref(shape), _ptr(X), _ptr(Wqkv), _ptr(Wo), _ptr(Wlce), _ptr(Y),
                              _ptr(Ir), _ptr(Ir_in), _ptr(ws), ws.numel(), _stream(X.device)))
     return (Y, Ir) if want_Ir else Y
+
+
+def profile_begin(max_records: int) -> None:
+    """Start per-launch timing of the library's kernels (see include/bra.h)."""
+    _check(lib().bra_profile_begin(int(max_records)))
+
+
+def profile_end(max_records: int):
+    """Stop per-launch timing; returns [(kernel name, milliseconds), ...] in launch order."""
+    ids = (ctypes.c_int32 * max_records)()
+    ms = (ctypes.c_float * max_records)()
+    n = ctypes.c_int(0)
+    _check(lib().bra_profile_end(ids, ms, max_records, ctypes.byref(n)))
+    return [(lib().bra_kernel_name(ids[i]).decode(), float(ms[i])) for i in range(n.value)]

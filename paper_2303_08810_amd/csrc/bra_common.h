@@ -42,6 +42,21 @@ __device__ inline void store_from_f32(bf16_t *p, float v) { *p = f32_to_bf16(v);
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Kernel identifiers for the optional per-launch timing (bra_profile_begin/end).
+enum KernelId {
+    K_GEN_POOL = 0, K_GEN_REGION_QK, K_GEN_TOPK, K_GEN_GEMM_QKV, K_GEN_ATTENTION, K_GEN_LCE,
+    K_GEN_GEMM_WO, K_COUNT
+};
+
+// Brackets the launches issued during its lifetime with two events on `st` when
+// per-launch timing is switched on; does nothing otherwise.
+struct ProfScope {
+    ProfScope(hipStream_t st, int id);
+    ~ProfScope();
+    hipStream_t st_;
+    int slot_;
+};
+
 // Kernel families.  Each returns a BRA_* code; all checks that can fail happen
 // before the first launch.
 size_t generic_workspace_bytes(const Dims &D);

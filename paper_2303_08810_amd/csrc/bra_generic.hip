@@ -302,11 +302,20 @@ void launch_route(const Dims &D, const T *X, const T *Wqkv, int32_t *Ir, float *
 {
     const int regs = D.B * D.R;
     const int pt = D.C < 256 ? ((D.C + 63) / 64) * 64 : 256;
-    hipLaunchKernelGGL(gen_pool<T>, dim3(regs), dim3(pt), 0, st, X, w.xr, D);
-    hipLaunchKernelGGL(gen_region_qk<T>, dim3(regs), dim3(256), D.C * sizeof(float), st, w.xr, Wqkv,
-                       w.qr, w.kr, D);
-    hipLaunchKernelGGL(gen_affinity_topk, dim3(regs), dim3(kWave), D.C * sizeof(float), st, w.qr,
-                       w.kr, Ir, Ar_opt, D);
+    {
+        ProfScope ps(st, K_GEN_POOL);
+        hipLaunchKernelGGL(gen_pool<T>, dim3(regs), dim3(pt), 0, st, X, w.xr, D);
+    }
+    {
+        ProfScope ps(st, K_GEN_REGION_QK);
+        hipLaunchKernelGGL(gen_region_qk<T>, dim3(regs), dim3(256), D.C * sizeof(float), st, w.xr,
+                           Wqkv, w.qr, w.kr, D);
+    }
+    {
+        ProfScope ps(st, K_GEN_TOPK);
+        hipLaunchKernelGGL(gen_affinity_topk, dim3(regs), dim3(kWave), D.C * sizeof(float), st, w.qr,
+                           w.kr, Ir, Ar_opt, D);
+    }
 }
 
 template <typename T>
@@ -326,16 +335,28 @@ int forward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *Wl
             return BRA_ERR_LAUNCH;
     }
     dim3 g1((unsigned)((M + 63) / 64), (unsigned)((3 * D.C + 63) / 64));
-    hipLaunchKernelGGL((gen_gemm<T, T, float>), g1, dim3(256), 0, st, X, D.C, Wqkv, 3 * D.C, w.qkv,
-                       3 * D.C, (int)M, 3 * D.C, D.C);
-    hipLaunchKernelGGL(gen_attention, dim3(D.B * D.R * D.heads), dim3(256), D.k * sizeof(int), st,
-                       w.qkv, Ir, w.o, D, D.scale);
+    {
+        ProfScope ps(st, K_GEN_GEMM_QKV);
+        hipLaunchKernelGGL((gen_gemm<T, T, float>), g1, dim3(256), 0, st, X, D.C, Wqkv, 3 * D.C, w.qkv,
+                           3 * D.C, (int)M, 3 * D.C, D.C);
+    }
+    {
+        ProfScope ps(st, K_GEN_ATTENTION);
+        hipLaunchKernelGGL(gen_attention, dim3(D.B * D.R * D.heads), dim3(256), D.k * sizeof(int), st,
+                           w.qkv, Ir, w.o, D, D.scale);
+    }
     const size_t total = (size_t)M * D.C;
-    hipLaunchKernelGGL(gen_lce_add<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       w.qkv, Wlce, w.o, D);
+    {
+        ProfScope ps(st, K_GEN_LCE);
+        hipLaunchKernelGGL(gen_lce_add<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           w.qkv, Wlce, w.o, D);
+    }
     dim3 g2((unsigned)((M + 63) / 64), (unsigned)((D.C + 63) / 64));
-    hipLaunchKernelGGL((gen_gemm<float, T, T>), g2, dim3(256), 0, st, w.o, D.C, Wo, D.C, Y, D.C,
-                       (int)M, D.C, D.C);
+    {
+        ProfScope ps(st, K_GEN_GEMM_WO);
+        hipLaunchKernelGGL((gen_gemm<float, T, T>), g2, dim3(256), 0, st, w.o, D.C, Wo, D.C, Y, D.C,
+                           (int)M, D.C, D.C);
+    }
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
