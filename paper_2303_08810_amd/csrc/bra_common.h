@@ -45,7 +45,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 // Kernel identifiers for the optional per-launch timing (bra_profile_begin/end).
 enum KernelId {
     K_GEN_POOL = 0, K_GEN_REGION_QK, K_GEN_TOPK, K_GEN_GEMM_QKV, K_GEN_ATTENTION, K_GEN_LCE,
-    K_GEN_GEMM_WO, K_COUNT
+    K_GEN_GEMM_WO, K_MFMA_PREP, K_MFMA_QKV, K_MFMA_ATTENTION, K_COUNT
 };
 
 // Brackets the launches issued during its lifetime with two events on `st` when
@@ -66,6 +66,10 @@ int generic_forward(const Dims &D, const void *X, const void *Wqkv, const void *
                     const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
                     void *ws, hipStream_t st);
 bool generic_supported(const Dims &D);
+
+size_t valu_route_scratch_bytes(const Dims &D);
+int valu_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, float *Ar_opt,
+               void *scratch, hipStream_t st);
 
 bool mfma_supported(const Dims &D);
 size_t mfma_workspace_bytes(const Dims &D);

@@ -400,3 +400,29 @@ int generic_forward(const Dims &D, const void *X, const void *Wqkv, const void *
 }
 
 }  // namespace bra
+
+namespace bra {
+
+// Routing with caller-provided scratch (xr, qr, kr: [B, R, C] float32 each), used by
+// the matrix-core family for shapes its own routing kernels do not cover.
+size_t valu_route_scratch_bytes(const Dims &D)
+{
+    return 3 * align256((size_t)D.B * D.R * D.C * sizeof(float));
+}
+
+int valu_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, float *Ar_opt,
+               void *scratch, hipStream_t st)
+{
+    GenericWs w;
+    const size_t each = align256((size_t)D.B * D.R * D.C * sizeof(float));
+    w.xr = (float *)scratch;
+    w.qr = (float *)((char *)scratch + each);
+    w.kr = (float *)((char *)scratch + 2 * each);
+    if (D.dtype == BRA_F32)
+        launch_route<float>(D, (const float *)X, (const float *)Wqkv, Ir, Ar_opt, w, st);
+    else
+        launch_route<bf16_t>(D, (const bf16_t *)X, (const bf16_t *)Wqkv, Ir, Ar_opt, w, st);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+}  // namespace bra

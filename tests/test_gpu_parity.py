@@ -65,6 +65,33 @@ def test_generic_path_small_shapes(B, H, W, C, heads, S, k, dtype):
     assert err < (1e-4 if dtype == "f32" else 4e-2)
 
 
+MFMA_SHAPES = [  # (B, H, W, C, heads, S, k): regions of n >= 64 tokens, d = 32
+    (2, 16, 16, 64, 2, 2, 1),
+    (2, 16, 16, 64, 2, 2, 3),
+    (3, 32, 16, 128, 4, 2, 4),
+    (1, 64, 64, 64, 2, 2, 2),
+    (2, 24, 24, 64, 2, 3, 9),
+    (1, 32, 32, 128, 4, 4, 5),
+    (5, 56, 56, 64, 2, 7, 1),
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,S,k", MFMA_SHAPES)
+def test_mfma_path_shapes(B, H, W, C, heads, S, k):
+    X, Wqkv, Wo, Wlce = make_inputs(B, H, W, C, seed=2000 + H + 3 * C + k, dtype="bf16")
+    compare(X, Wqkv, Wo, Wlce, "bf16", S, k, heads, "mfma")
+
+
+def test_mfma_scale_and_forced_routing():
+    X, Wqkv, Wo, Wlce = make_inputs(2, 16, 16, 64, seed=77, dtype="bf16")
+    compare(X, Wqkv, Wo, Wlce, "bf16", 2, 2, 2, "mfma", scale=0.05)
+    Ir_in = np.broadcast_to(np.arange(4, dtype=np.int32)[None, :, None], (2, 4, 1)).copy()
+    Y, Ir, _, _ = gpu_forward(X, Wqkv, Wo, Wlce, "bf16", 2, 1, 2, "mfma", Ir_in=Ir_in)
+    np.testing.assert_array_equal(Ir, Ir_in)
+    ref = run_oracle(X, Wqkv, Wo, Wlce, dict(S=2, k=1, heads=2), Ir_in=Ir_in)
+    check_output(Y, ref["Y"], "bf16")
+
+
 def test_generic_scale_argument():
     X, Wqkv, Wo, Wlce = make_inputs(1, 8, 8, 64, seed=5)
     compare(X, Wqkv, Wo, Wlce, "f32", 2, 2, 2, "generic", scale=1.0)
