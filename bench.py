@@ -61,7 +61,8 @@ def kernel_model(name, cfg):
         "gen_gemm_wo": ("alu", B * f["wo"], VALU_F32_PEAK_TFLOPS),
         # matrix-core family
         "mfma_prep": ("hbm", 2 * 4 * cfg.C * cfg.C * eb, HBM_PEAK_GBS),    # weights in and out
-        "mfma_pool": ("hbm", unit, HBM_PEAK_GBS),                      # reads X once
+        "mfma_pool_qk": ("hbm", unit, HBM_PEAK_GBS),                   # reads X once
+        "mfma_route_rows": ("alu", B * f["aff"], VALU_F32_PEAK_TFLOPS),
         "mfma_route": ("alu", B * (4 * cfg.R * cfg.C * cfg.C + f["aff"]), VALU_F32_PEAK_TFLOPS),
         "mfma_qkv": ("hbm", 4 * unit, HBM_PEAK_GBS),                   # X in, Q K V out
         "mfma_attention": ("hbm", 4 * unit, HBM_PEAK_GBS),             # Q K V in, Y out

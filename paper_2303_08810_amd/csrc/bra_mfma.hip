@@ -1,74 +1,158 @@
 // Matrix-core (MFMA) kernel family for bf16 tensors on gfx950, head width d = 32.
 //
-// All contractions use v_mfma_f32_16x16x32_bf16 (64-lane wavefront; lane l = 16 g + i):
-//   A operand: lane holds A[row i][k = 8 g .. 8 g + 7]
-//   B operand: lane holds B[k = 8 g .. 8 g + 7][col i]
-//   D result : lane holds D[row 4 g .. 4 g + 3][col i]
-// so both operands are read as 16-byte runs along the contraction axis, and the
-// contraction may use any key order as long as A and B agree on it.
+// Intermediates Q, K, V (staged kernels) are bf16 tensors in the spatial [B, H, W, C]
+// layout; the region structure of Sec. 3.2 lives in address arithmetic only.  The
+// routed key/value tokens (Eq. 6) are copied by index from that layout into LDS,
+// never into a gathered tensor in memory.
 //
-// Intermediates Q, K, V are bf16 tensors in the spatial [B, H, W, C] layout; the
-// region structure of Sec. 3.2 lives in address arithmetic only.  The routed
-// key/value tokens (Eq. 6) are copied by index from that layout into LDS, never
-// into a gathered tensor in memory.
-#include "bra_common.h"
+// Routing (Eq. 4-5) is computed in float32 from X: a pooling kernel forms the
+// region means of X and from them Q^r and K^r (mean(X^r) W = mean(X^r W), exact in
+// real arithmetic); each attention workgroup then forms its own row of A^r and the
+// top-k of that row, so no separate routing launch sits on the forward path.
+//
+// Two forward pipelines:
+//   staged : k_pool_qk -> k_qkv -> k_attn_big                      (any k)
+//   fused  : k_pool_qk -> k_fused   (projections recomputed per workgroup from X;
+//            used when every region attends to a single 64-token block, i.e. the
+//            k = 1 stage, where recomputing K and V costs less than storing them)
+#include "bra_mfma_dev.h"
+
+#include <stdlib.h>
 
 namespace bra {
 
+using namespace mfma;
+
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr int kWave = 64;
-constexpr int kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
-
-__device__ inline f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
-
-// Two floats -> packed bf16 pair (round to nearest even), low half = a.
-__device__ inline unsigned pack_bf16(float a, float b)
-{
-    f32x2 v = {a, b};
-    bf16x2 r = __builtin_convertvector(v, bf16x2);
-    return __builtin_bit_cast(unsigned, r);
-}
-
-__device__ inline bf16x8 pack8(const float *v)
-{
-    u32x4 u = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]),
-               pack_bf16(v[6], v[7])};
-    return __builtin_bit_cast(bf16x8, u);
-}
-
-// LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane s
-// supplies the address of 4 consecutive 16-bit elements; the four lanes 4 j .. 4 j + 3
-// together supply a row j of 16 elements.  Lane i receives element i of rows 0..3.
-__device__ inline s16x4 lds_read_tr16(const bf16_t *p)
-{
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)p);
-}
 
 // ---------------------------------------------------------------------------
 // WT[o][c] = Wqkv[c][o] (o < 3C) and WoT[o][c] = Wo[c][o]: the weights with the
-// contraction axis contiguous, as the MFMA operands want them.
+// contraction axis contiguous, as the MFMA operands want them.  `e` runs over 4 C^2.
+__device__ inline void prep_weight_element(const bf16_t *__restrict__ Wqkv,
+                                           const bf16_t *__restrict__ Wo, bf16_t *__restrict__ WT,
+                                           bf16_t *__restrict__ WoT, int C, int e)
+{
+    const int o = e / C, c = e % C;
+    if (o < 3 * C) WT[e] = Wqkv[(size_t)c * 3 * C + o];
+    else WoT[(size_t)(o - 3 * C) * C + c] = Wo[(size_t)c * C + (o - 3 * C)];
+}
+
 __global__ void k_prep_weights(const bf16_t *__restrict__ Wqkv, const bf16_t *__restrict__ Wo,
                                bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT, int C)
 {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    const int total = 4 * C * C;
-    if (e >= total) return;
-    const int o = e / C, c = e % C;
-    if (o < 3 * C) WT[e] = Wqkv[(size_t)c * 3 * C + o];
-    else WoT[(size_t)(o - 3 * C) * C + c] = Wo[(size_t)c * C + (o - 3 * C)];
+    if (e < 4 * C * C) prep_weight_element(Wqkv, Wo, WT, WoT, C, e);
+}
+
+// ---------------------------------------------------------------------------
+// Region pooling and region-level projections (Sec. 3.2, "Region-to-region routing").
+// Workgroup (b, sy) reads the band of rh rows that holds regions sy*S .. sy*S + S-1 of
+// image b exactly once, forms their mean tokens in float32 (fixed summation order),
+// and multiplies them by Wq and Wk:  Qr[b, r, :] and KrT[b, :, r] (keys transposed so
+// that a wavefront reads one channel of all regions as one contiguous run).
+// Workgroups beyond `pool_blocks` transpose the projection weights instead.
+template <int C>
+__global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
+                                                 const bf16_t *__restrict__ Wqkv,
+                                                 const bf16_t *__restrict__ Wo,
+                                                 float *__restrict__ Qr, float *__restrict__ KrT,
+                                                 bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT,
+                                                 Dims D, int pool_blocks)
+{
+    __shared__ float part[4096];   // pooling partials, then projection partials
+    __shared__ float xr[kFastRouteMaxS * C];
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x >= pool_blocks) {
+        const int e = ((int)blockIdx.x - pool_blocks) * 256 + tid;
+        if (e < 4 * C * C) prep_weight_element(Wqkv, Wo, WT, WoT, C, e);
+        return;
+    }
+    constexpr int CH = C / 8;
+    const int b = blockIdx.x / D.S, sy = blockIdx.x % D.S;
+    const int items = D.S * CH;                               // (region, 8-channel chunk) pairs
+    const int P = items >= 256 ? 256 : ((items + 63) / 64) * 64;
+    const int SUB = 256 / P;                                   // threads that share one pair
+    const int item = tid % P, sub = tid / P;
+    if (item < items && sub < SUB) {
+        const int sx = item / CH, cc = item % CH;
+        const bf16_t *base = X + (((size_t)b * D.H + (size_t)sy * D.rh) * D.W + (size_t)sx * D.rw) * C + cc * 8;
+        const float rw_inv = 1.0f / (float)D.rw;
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+        for (int slot = sub; slot < D.n; slot += SUB) {
+            const int ry = fast_div(slot, rw_inv), rx = slot - ry * D.rw;
+            const u32x4 v = *(const u32x4 *)(base + ((size_t)ry * D.W + rx) * C);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[2 * e] += bf16_lo(v[e]);
+                acc[2 * e + 1] += bf16_hi(v[e]);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[(sub * items + item) * 8 + e] = acc[e];
+    }
+    __syncthreads();
+    for (int e = tid; e < D.S * C; e += 256) {
+        const int sx = e / C, c = e % C;
+        const int it = sx * CH + c / 8;
+        float s = 0.f;
+        for (int sb = 0; sb < SUB; ++sb) s += part[(sb * items + it) * 8 + c % 8];
+        xr[e] = s / (float)D.n;
+    }
+    __syncthreads();
+    // [Q^r | K^r] = xr [Wq | Wk].  Thread (oc, split) owns output columns 2 oc, 2 oc + 1
+    // over input channels [split * CP, (split + 1) * CP); the SPL partial sums of a
+    // column are added in ascending split order.
+    constexpr int SPL = (C >= 256) ? 1 : 256 / C;
+    constexpr int CP = C / SPL;
+    {
+        const int oc = tid % C, split = tid / C;
+        float acc0[kFastRouteMaxS], acc1[kFastRouteMaxS];
+#pragma unroll
+        for (int sx = 0; sx < kFastRouteMaxS; ++sx) { acc0[sx] = 0.f; acc1[sx] = 0.f; }
+#pragma unroll 16
+        for (int cc = 0; cc < CP; ++cc) {
+            const int c = split * CP + cc;
+            const unsigned w2 = *(const unsigned *)(Wqkv + (size_t)c * 3 * C + 2 * oc);
+            const float w0 = bf16_lo(w2), w1 = bf16_hi(w2);
+#pragma unroll
+            for (int sx = 0; sx < kFastRouteMaxS; ++sx)
+                if (sx < D.S) {
+                    const float x = xr[sx * C + c];
+                    acc0[sx] = fmaf(x, w0, acc0[sx]);
+                    acc1[sx] = fmaf(x, w1, acc1[sx]);
+                }
+        }
+#pragma unroll
+        for (int sx = 0; sx < kFastRouteMaxS; ++sx) {
+            part[(split * kFastRouteMaxS + sx) * 2 * C + 2 * oc] = acc0[sx];
+            part[(split * kFastRouteMaxS + sx) * 2 * C + 2 * oc + 1] = acc1[sx];
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < D.S * 2 * C; e += 256) {
+        const int sx = e / (2 * C), o = e % (2 * C);
+        float v = part[sx * 2 * C + o];
+#pragma unroll
+        for (int sp = 1; sp < SPL; ++sp) v += part[(sp * kFastRouteMaxS + sx) * 2 * C + o];
+        const int r = sy * D.S + sx;
+        if (o < C) Qr[((size_t)b * D.R + r) * C + o] = v;
+        else KrT[((size_t)b * C + (o - C)) * kRpad + r] = v;
+    }
+}
+
+// bra_route: one workgroup per (b, region) writes its row of Ir (and of Ar).
+template <int C>
+__global__ __launch_bounds__(256) void k_route_rows(const float *__restrict__ Qr,
+                                                    const float *__restrict__ KrT,
+                                                    int32_t *__restrict__ Ir, float *__restrict__ Ar,
+                                                    Dims D)
+{
+    __shared__ float part[256];
+    __shared__ int ir_s[kRpad];
+    const int b = blockIdx.x / D.R, reg = blockIdx.x % D.R;
+    route_row<C>(Qr, KrT, b, reg, D.R, D.k, part, ir_s, Ir + ((size_t)b * D.R + reg) * D.k,
+                 Ar ? Ar + ((size_t)b * D.R + reg) * D.R : nullptr);
 }
 
 // ---------------------------------------------------------------------------
@@ -122,255 +206,341 @@ __global__ __launch_bounds__(3 * C) void k_qkv(const bf16_t *__restrict__ X,
             }
             const long t = tok0 + 16 * u + i;
             if (t < M) {
-                u32x4 lo = {pack_bf16(acc[0][0], acc[0][1]), pack_bf16(acc[0][2], acc[0][3]),
-                            pack_bf16(acc[1][0], acc[1][1]), pack_bf16(acc[1][2], acc[1][3])};
-                u32x4 hi = {pack_bf16(acc[2][0], acc[2][1]), pack_bf16(acc[2][2], acc[2][3]),
-                            pack_bf16(acc[3][0], acc[3][1]), pack_bf16(acc[3][2], acc[3][3])};
+                u32x2 p0 = pack4(acc[0]), p1 = pack4(acc[1]), p2 = pack4(acc[2]), p3 = pack4(acc[3]);
                 u32x4 *dst = (u32x4 *)(out + t * C + base + 16 * g);
-                dst[0] = lo;
-                dst[1] = hi;
+                dst[0] = u32x4{p0[0], p0[1], p1[0], p1[1]};
+                dst[1] = u32x4{p2[0], p2[1], p3[0], p3[1]};
             }
         }
     }
 }
 
 // ---------------------------------------------------------------------------
+// LDS map shared by the two attention kernels.  Rows of bf16 tiles have CS = C + 8
+// elements (16-byte pad against bank conflicts), rows of the float32 output tile OS.
+template <int C>
+struct AttnSmem {
+    static constexpr int CS = C + 8;
+    static constexpr int OS = C + 4;
+    static constexpr size_t q_off = 0;                                // Q tile (fused kernel)
+    static constexpr size_t k_off = q_off + (size_t)64 * CS * 2;      // K tile; output tile later
+    static constexpr size_t v_off = k_off + (size_t)64 * CS * 2;      // V tile
+    static constexpr size_t w_off = v_off + (size_t)64 * CS * 2;      // LCE weights [25][C] f32
+    static constexpr size_t p_off = w_off + (size_t)25 * C * 4;       // routing partials
+    static constexpr size_t i_off = p_off + 256 * 4;                  // routed regions
+    static constexpr size_t h_off = i_off + kRpad * 4;                // V halo tile
+    static size_t bytes(int halo_rows) { return h_off + (size_t)halo_rows * CS * 2; }
+};
+
+// Workgroup -> (image, region, query tile).  Consecutive block ids are dealt
+// round-robin to the 8 XCDs; undo that so that the workgroups of one image share an L2.
+__device__ __forceinline__ int swizzled_block()
+{
+    const int per_xcd = gridDim.x / 8;
+    return ((int)blockIdx.x % 8) * per_xcd + (int)blockIdx.x / 8;
+}
+
 // Routed attention + LCE + W^o for regions of n >= 64 tokens (Eq. 6-7, Eq. 2).
 // One workgroup = 64 query tokens (64/rw full rows of one region), all heads,
 // 4 wavefronts; wavefront w owns queries 16 w .. 16 w + 15.  Keys and values of the
 // k routed regions are copied by index, 64 tokens at a time, from the projected
 // maps into LDS; one online softmax runs over all k n keys.
 template <int C>
-struct AttnBigSmem {
-    static constexpr int CS = C + 8;               // bf16 elements per LDS row (16 B pad)
-    static constexpr int OS = C + 4;               // floats per row of the output tile
-    static constexpr size_t q_off = 0;
-    static constexpr size_t k_off = q_off + (size_t)64 * CS * 2;
-    static constexpr size_t v_off = k_off + (size_t)64 * CS * 2;
-    static constexpr size_t h_off = v_off + (size_t)64 * CS * 2;
-    static size_t bytes(int halo_rows) { return h_off + (size_t)halo_rows * CS * 2; }
-};
-
-// Copies `rows` token rows of C bf16 from a [.., W, C] map into LDS rows of CS elements.
-// Row r is token (y0 + r / tw, x0 + r % tw); rows outside the image are zero-filled.
-template <int C, int CS>
-__device__ inline void stage_rows(bf16_t *dst, const bf16_t *__restrict__ img, int y0, int x0,
-                                  int tw, int rows, int H, int W)
+__global__ __launch_bounds__(256) void k_attn_big(AttnArgs A, Dims D)
 {
-    constexpr int CH = C / 8;
-    for (int idx = threadIdx.x; idx < rows * CH; idx += blockDim.x) {
-        const int r = idx / CH, cc = idx % CH;
-        const int y = y0 + r / tw, x = x0 + r % tw;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (y >= 0 && y < H && x >= 0 && x < W) v = *(const u32x4 *)(img + ((size_t)y * W + x) * C + cc * 8);
-        *(u32x4 *)(dst + r * CS + cc * 8) = v;
-    }
-}
-
-template <int C>
-__global__ __launch_bounds__(256) void k_attn_big(const bf16_t *__restrict__ Q,
-                                                  const bf16_t *__restrict__ K,
-                                                  const bf16_t *__restrict__ V,
-                                                  const int32_t *__restrict__ Ir,
-                                                  const bf16_t *__restrict__ Wlce,
-                                                  const bf16_t *__restrict__ WoT,
-                                                  bf16_t *__restrict__ Y, Dims D, float c_exp)
-{
-    typedef AttnBigSmem<C> SM;
-    constexpr int CS = SM::CS, OS = SM::OS, HEADS = C / 32, KS = C / 32;
+    typedef AttnSmem<C> SM;
+    constexpr int CS = SM::CS, OS = SM::OS, HEADS = C / 32, KS = C / 32, CH = C / 8;
+    constexpr int NBT = CH / 4;                 // 16-byte chunks per thread for a 64-row tile
+    constexpr int NBH = 5;                      // halo chunks per thread and batch
+    constexpr bool kPrefetchWo = (C == 64);
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16_t *Qs = (bf16_t *)(smem + SM::q_off);
     bf16_t *Ks = (bf16_t *)(smem + SM::k_off);
     bf16_t *Vs = (bf16_t *)(smem + SM::v_off);
+    float *Wl = (float *)(smem + SM::w_off);
+    float *part = (float *)(smem + SM::p_off);
+    int *ir_s = (int *)(smem + SM::i_off);
     bf16_t *Hs = (bf16_t *)(smem + SM::h_off);
     float *Os = (float *)(smem + SM::k_off);   // reuses the K/V tiles after the key loop
 
+    const int wid = swizzled_block();
+    if (wid >= A.total) return;
+
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
-
     const int chunks = D.n / 64;               // query tiles per region
     const int qh = 64 / D.rw;                  // rows per query tile
-    const int wid = blockIdx.x;
     const int b = wid / (D.R * chunks);
     const int reg = (wid / chunks) % D.R;
     const int ch = wid % chunks;
     const int y0 = (reg / D.S) * D.rh + ch * qh, x0 = (reg % D.S) * D.rw;
     const size_t img_off = (size_t)b * D.N * C;
-    const int32_t *ir = Ir + ((size_t)b * D.R + reg) * D.k;
-
-    stage_rows<C, CS>(Qs, Q + img_off, y0, x0, D.rw, 64, D.H, D.W);
     const int hw = D.rw + 4, hrows = (qh + 4) * hw;
-    stage_rows<C, CS>(Hs, V + img_off, y0 - 2, x0 - 2, hw, hrows, D.H, D.W);
+    const float hw_inv = 1.0f / (float)hw, rw_inv = 1.0f / (float)D.rw;
 
-    float m_run[HEADS], l_run[HEADS];
-    f32x4 acc[HEADS][2];
+    // Everything that does not depend on the routing is requested first: V halo, LCE
+    // weights, this lane's query fragments and (small C) the W^o fragments.
+    u32x4 hreg[NBH];
+    tile_load<C, NBH>(hreg, A.V + img_off, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, 0);
+    LceWeights<C> lw;
+    lw.load(A.Wlce);
+    const int q = 16 * wave + i;
+    const int qy = fast_div(q, rw_inv);
+    const size_t qtok = (size_t)(y0 + qy) * D.W + x0 + q - qy * D.rw;
+    bf16x8 qf[HEADS];
 #pragma unroll
-    for (int h = 0; h < HEADS; ++h) {
-        m_run[h] = -INFINITY;
-        l_run[h] = 0.f;
-        acc[h][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-        acc[h][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int h = 0; h < HEADS; ++h) qf[h] = *(const bf16x8 *)(A.Q + img_off + qtok * C + 32 * h + 8 * g);
+    bf16x8 wof[kPrefetchWo ? 4 : 1][KS];
+    if constexpr (kPrefetchWo) {
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) wof[tt][ks] = wo_fragment<C>(A.WoT, 0, tt, ks, g, i);
     }
 
+    // Routing row of this region (or the caller's / the fallback kernels' index).
+    const int32_t *irp;
+    if (A.Ir_src) {
+        irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
+        if (A.Ir_out && A.Ir_out != A.Ir_src && ch == 0)
+            for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
+    } else {
+        route_row<C>(A.Qr, A.KrT, b, reg, D.R, D.k, part, ir_s,
+                     (A.Ir_out && ch == 0) ? A.Ir_out + ((size_t)b * D.R + reg) * D.k : nullptr, nullptr);
+        irp = ir_s;
+    }
+
+    tile_store<C, CS, NBH>(Hs, hreg, hrows, 0);
+    for (int first = 256 * NBH; first < hrows * CH; first += 256 * NBH) {
+        tile_load<C, NBH>(hreg, A.V + img_off, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, first);
+        tile_store<C, CS, NBH>(Hs, hreg, hrows, first);
+    }
+    lw.store(Wl);
+
+    SoftmaxState<HEADS> st;
+    st.init();
     const int nblocks = D.kn / 64;
     for (int kb = 0; kb < nblocks; ++kb) {
-        const int j = ir[kb / chunks];
+        const int j = irp[kb / chunks];
         const int ky0 = (j / D.S) * D.rh + (kb % chunks) * qh, kx0 = (j % D.S) * D.rw;
-        __syncthreads();   // previous block's readers are done (and Qs/Hs writes are ordered)
-        stage_rows<C, CS>(Ks, K + img_off, ky0, kx0, D.rw, 64, D.H, D.W);
-        stage_rows<C, CS>(Vs, V + img_off, ky0, kx0, D.rw, 64, D.H, D.W);
+        u32x4 kreg[NBT], vreg[NBT];
+        tile_load<C, NBT>(kreg, A.K + img_off, ky0, kx0, D.rw, rw_inv, 64, D.H, D.W, 0);
+        tile_load<C, NBT>(vreg, A.V + img_off, ky0, kx0, D.rw, rw_inv, 64, D.H, D.W, 0);
+        __syncthreads();   // the previous block's readers are done with Ks / Vs
+        tile_store<C, CS, NBT>(Ks, kreg, 64, 0);
+        tile_store<C, CS, NBT>(Vs, vreg, 64, 0);
         __syncthreads();
-#pragma unroll
-        for (int h = 0; h < HEADS; ++h) {
-            const bf16x8 qf = *(const bf16x8 *)(Qs + (16 * wave + i) * CS + 32 * h + 8 * g);
-            f32x4 s[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + 32 * h + 8 * g);
-                s[t] = mfma16(kf, qf, f32x4{0.f, 0.f, 0.f, 0.f});   // S^T[key 16t+4g+j][query i]
-            }
-            float mx = s[0][0];
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) mx = fmaxf(mx, s[t][jj]);
-            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-            const float m_new = fmaxf(m_run[h], mx);
-            const float alpha = __builtin_amdgcn_exp2f((m_run[h] - m_new) * c_exp);
-            const float mc = m_new * c_exp;
-            float p[4][4], ls = 0.f;
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    p[t][jj] = __builtin_amdgcn_exp2f(fmaf(s[t][jj], c_exp, -mc));
-                    ls += p[t][jj];
-                }
-            ls += __shfl_xor(ls, 16, kWave);
-            ls += __shfl_xor(ls, 32, kWave);
-            l_run[h] = l_run[h] * alpha + ls;
-            m_run[h] = m_new;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt) acc[h][dt] *= alpha;
-#pragma unroll
-            for (int tp = 0; tp < 2; ++tp) {
-                float pv[8] = {p[2 * tp][0], p[2 * tp][1], p[2 * tp][2], p[2 * tp][3],
-                               p[2 * tp + 1][0], p[2 * tp + 1][1], p[2 * tp + 1][2], p[2 * tp + 1][3]};
-                const bf16x8 pb = pack8(pv);
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt) {
-                    const int col = 32 * h + 16 * dt + 4 * (i % 4);
-                    const s16x4 v0 = lds_read_tr16(Vs + (32 * tp + 4 * g + i / 4) * CS + col);
-                    const s16x4 v1 = lds_read_tr16(Vs + (32 * tp + 16 + 4 * g + i / 4) * CS + col);
-                    u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
-                    u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
-                    acc[h][dt] = mfma16(__builtin_bit_cast(bf16x8, av), pb, acc[h][dt]);
-                }
-            }
-        }
+        attn_key_block<C, CS>(Ks, Vs, qf, st, A.c_exp, g, i);
     }
     __syncthreads();   // everyone is done with Ks / Vs: the output tile may overwrite them
-#pragma unroll
-    for (int h = 0; h < HEADS; ++h) {
-        const float inv = 1.0f / l_run[h];
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-            f32x4 o = acc[h][dt] * inv;   // O^T[channel 16dt+4g+j][query i]
-            *(f32x4 *)(Os + (16 * wave + i) * OS + 32 * h + 16 * dt + 4 * g) = o;
-        }
-    }
+    attn_write_out<C, OS>(Os, st, wave, g, i);
     __syncthreads();
-
-    // LCE: 5x5 depth-wise cross-correlation of V over the halo tile, added to the
-    // attention output.  One task = (row of the query tile, 8-token segment, channel pair).
-    {
-        const int segs = D.rw / 8, cp_n = C / 2;
-        const int tasks = qh * segs * cp_n;
-        for (int task = threadIdx.x; task < tasks; task += blockDim.x) {
-            const int cp = task % cp_n, seg = (task / cp_n) % segs, r = task / (cp_n * segs);
-            const int c = 2 * cp;
-            float w0[25], w1[25];
-#pragma unroll
-            for (int t = 0; t < 25; ++t) {
-                w0[t] = bf16_to_f32(Wlce[c * 25 + t]);
-                w1[t] = bf16_to_f32(Wlce[(c + 1) * 25 + t]);
-            }
-            float a0[8], a1[8];
-#pragma unroll
-            for (int x = 0; x < 8; ++x) { a0[x] = 0.f; a1[x] = 0.f; }
-#pragma unroll
-            for (int ky = 0; ky < 5; ++ky) {
-                float v0[12], v1[12];
-#pragma unroll
-                for (int x = 0; x < 12; ++x) {
-                    const unsigned u = *(const unsigned *)(Hs + ((r + ky) * hw + seg * 8 + x) * CS + c);
-                    v0[x] = __builtin_bit_cast(float, u << 16);
-                    v1[x] = __builtin_bit_cast(float, u & 0xffff0000u);
-                }
-#pragma unroll
-                for (int x = 0; x < 8; ++x)
-#pragma unroll
-                    for (int kx = 0; kx < 5; ++kx) {
-                        a0[x] = fmaf(w0[ky * 5 + kx], v0[x + kx], a0[x]);
-                        a1[x] = fmaf(w1[ky * 5 + kx], v1[x + kx], a1[x]);
-                    }
-            }
-#pragma unroll
-            for (int x = 0; x < 8; ++x) {
-                f32x2 *o = (f32x2 *)(Os + (r * D.rw + seg * 8 + x) * OS + c);
-                f32x2 cur = *o;
-                cur[0] += a0[x];
-                cur[1] += a1[x];
-                *o = cur;
-            }
-        }
-    }
+    lce_add_valu<C, CS, OS>(Hs, Wl, Os, qh, D.rw, hw);
     __syncthreads();
-
-    // Y = O Wo for the 16 tokens of this wavefront, formed transposed as in k_qkv.
-    {
-        bf16x8 of[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const float *src = Os + (16 * wave + i) * OS + 32 * ks + 8 * g;
-            f32x4 lo = *(const f32x4 *)src, hi = *(const f32x4 *)(src + 4);
-            float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            of[ks] = pack8(v);
-        }
-        const int q = 16 * wave + i;
-        const size_t tok = (size_t)(y0 + q / D.rw) * D.W + x0 + q % D.rw;
-        bf16_t *yrow = Y + img_off + tok * C;
-#pragma unroll
-        for (int cg = 0; cg < C / 64; ++cg) {
-            f32x4 ya[4];
-#pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
-                const int o = cg * 64 + 16 * (i / 4) + 4 * tt + (i % 4);
-                ya[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 wf = *(const bf16x8 *)(WoT + (size_t)o * C + 32 * ks + 8 * g);
-                    ya[tt] = mfma16(wf, of[ks], ya[tt]);
-                }
-            }
-            u32x4 lo = {pack_bf16(ya[0][0], ya[0][1]), pack_bf16(ya[0][2], ya[0][3]),
-                        pack_bf16(ya[1][0], ya[1][1]), pack_bf16(ya[1][2], ya[1][3])};
-            u32x4 hi = {pack_bf16(ya[2][0], ya[2][1]), pack_bf16(ya[2][2], ya[2][3]),
-                        pack_bf16(ya[3][0], ya[3][1]), pack_bf16(ya[3][2], ya[3][3])};
-            u32x4 *dst = (u32x4 *)(yrow + cg * 64 + 16 * g);
-            dst[0] = lo;
-            dst[1] = hi;
-        }
-    }
+    wo_project_store<C, OS, kPrefetchWo>(Os, kPrefetchWo ? wof : nullptr, A.WoT,
+                                         A.Y + img_off + qtok * C, wave, g, i);
 }
 
+// ---------------------------------------------------------------------------
+// Fused forward for one 64-token query tile: Q, the K / V of the routed key blocks and
+// the V halo needed by the LCE are projected from X inside the workgroup (Eq. 3), so
+// Q, K, V never travel through memory.  Wavefront w owns output channels
+// [w C/4, (w+1) C/4) of each projection (weights in registers) for ALL tokens of the
+// workgroup; the projected tiles meet in LDS, then the attention, LCE and W^o phases
+// are those of k_attn_big.  Each routed key block costs one more K/V projection, so
+// this kernel is used when there are few key blocks per query tile (the k = 1 stage).
+template <int C>
+__global__ __launch_bounds__(256) void k_fused(AttnArgs A, Dims D)
+{
+    typedef AttnSmem<C> SM;
+    constexpr int CS = SM::CS, OS = SM::OS, HEADS = C / 32, KS = C / 32;
+    constexpr int NT = C / 64;                  // 16-channel output tiles per wavefront and matrix
+    constexpr int HB = 3;                       // halo token tiles per load batch
+    constexpr bool kPrefetchWo = (C == 64);
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *Qs = (bf16_t *)(smem + SM::q_off);
+    bf16_t *Ks = (bf16_t *)(smem + SM::k_off);
+    bf16_t *Vs = (bf16_t *)(smem + SM::v_off);
+    float *Wl = (float *)(smem + SM::w_off);
+    float *part = (float *)(smem + SM::p_off);
+    int *ir_s = (int *)(smem + SM::i_off);
+    bf16_t *Hs = (bf16_t *)(smem + SM::h_off);
+    float *Os = (float *)(smem + SM::k_off);
+
+    const int wid = swizzled_block();
+    if (wid >= A.total) return;
+
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int g = lane / 16, i = lane % 16;
+    const int chunks = D.n / 64;
+    const int qh = 64 / D.rw;
+    const int b = wid / (D.R * chunks);
+    const int reg = (wid / chunks) % D.R;
+    const int ch = wid % chunks;
+    const int y0 = (reg / D.S) * D.rh + ch * qh, x0 = (reg % D.S) * D.rw;
+    const size_t img_off = (size_t)b * D.N * C;
+    const bf16_t *Ximg = A.X + img_off;
+    const int hw = D.rw + 4, hrows = (qh + 4) * hw;
+    const float hw_inv = 1.0f / (float)hw, rw_inv = 1.0f / (float)D.rw;
+
+    // Weight fragments (A operands): row i of tile t  <->  output channel 16 (w NT + t) + i.
+    bf16x8 wq[NT][KS], wk[NT][KS], wv[NT][KS];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const size_t row = (size_t)(16 * (wave * NT + t) + i) * C + 32 * ks + 8 * g;
+            wq[t][ks] = *(const bf16x8 *)(A.WT + row);
+            wk[t][ks] = *(const bf16x8 *)(A.WT + (size_t)C * C + row);
+            wv[t][ks] = *(const bf16x8 *)(A.WT + (size_t)2 * C * C + row);
+        }
+    // X fragments (B operands) of the 64 query tokens: token 16 u + i, channels 32 ks + 8 g ..
+    bf16x8 xf[4][KS];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int q = 16 * u + i;
+        const int qy = fast_div(q, rw_inv);
+        const bf16_t *row = Ximg + ((size_t)(y0 + qy) * D.W + x0 + q - qy * D.rw) * C + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) xf[u][ks] = *(const bf16x8 *)(row + 32 * ks);
+    }
+    LceWeights<C> lw;
+    lw.load(A.Wlce);
+    bf16x8 wof[kPrefetchWo ? 4 : 1][KS];
+    if constexpr (kPrefetchWo) {
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) wof[tt][ks] = wo_fragment<C>(A.WoT, 0, tt, ks, g, i);
+    }
+
+    const int32_t *irp;
+    if (A.Ir_src) {
+        irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
+        if (A.Ir_out && A.Ir_out != A.Ir_src && ch == 0)
+            for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
+    } else {
+        route_row<C>(A.Qr, A.KrT, b, reg, D.R, D.k, part, ir_s,
+                     (A.Ir_out && ch == 0) ? A.Ir_out + ((size_t)b * D.R + reg) * D.k : nullptr, nullptr);
+        irp = ir_s;
+    }
+    lw.store(Wl);
+
+    // Q tile: D^T[channel 16 tile + 4 g + j][token 16 u + i] -> 8-byte LDS writes.
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) a = mfma16(wq[t][ks], xf[u][ks], a);
+            *(u32x2 *)(Qs + (16 * u + i) * CS + 16 * (wave * NT + t) + 4 * g) = pack4(a);
+        }
+
+    // V over the halo of the query tile (zero outside the image, as V = 0 there).
+    const int nht = (hrows + 15) / 16;
+    for (int hu0 = 0; hu0 < nht; hu0 += HB) {
+        bf16x8 xh[HB][KS];
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) {
+            const int row = 16 * (hu0 + hb) + i;
+            const int hy = fast_div(row, hw_inv);
+            const int y = y0 - 2 + hy, x = x0 - 2 + row - hy * hw;
+            const bool ok = row < hrows && y >= 0 && y < D.H && x >= 0 && x < D.W;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (ok) v = *(const u32x4 *)(Ximg + ((size_t)y * D.W + x) * C + 32 * ks + 8 * g);
+                xh[hb][ks] = __builtin_bit_cast(bf16x8, v);
+            }
+        }
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) {
+            if (hu0 + hb >= nht) break;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) a = mfma16(wv[t][ks], xh[hb][ks], a);
+                *(u32x2 *)(Hs + (16 * (hu0 + hb) + i) * CS + 16 * (wave * NT + t) + 4 * g) = pack4(a);
+            }
+        }
+    }
+
+    SoftmaxState<HEADS> st;
+    st.init();
+    bf16x8 qf[HEADS];
+    const int nblocks = D.kn / 64;
+    for (int kb = 0; kb < nblocks; ++kb) {
+        const int j = irp[kb / chunks];
+        const int ky0 = (j / D.S) * D.rh + (kb % chunks) * qh, kx0 = (j % D.S) * D.rw;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = 16 * u + i;
+            const int qy = fast_div(q, rw_inv);
+            const bf16_t *row = Ximg + ((size_t)(ky0 + qy) * D.W + kx0 + q - qy * D.rw) * C + 8 * g;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) xf[u][ks] = *(const bf16x8 *)(row + 32 * ks);
+        }
+        __syncthreads();   // the previous block's readers are done with Ks / Vs
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                f32x4 ak = {0.f, 0.f, 0.f, 0.f}, av = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    ak = mfma16(wk[t][ks], xf[u][ks], ak);
+                    av = mfma16(wv[t][ks], xf[u][ks], av);
+                }
+                const int off = (16 * u + i) * CS + 16 * (wave * NT + t) + 4 * g;
+                *(u32x2 *)(Ks + off) = pack4(ak);
+                *(u32x2 *)(Vs + off) = pack4(av);
+            }
+        __syncthreads();
+        if (kb == 0) {
+#pragma unroll
+            for (int h = 0; h < HEADS; ++h)
+                qf[h] = *(const bf16x8 *)(Qs + (16 * wave + i) * CS + 32 * h + 8 * g);
+        }
+        attn_key_block<C, CS>(Ks, Vs, qf, st, A.c_exp, g, i);
+    }
+    __syncthreads();
+    attn_write_out<C, OS>(Os, st, wave, g, i);
+    __syncthreads();
+    lce_add_valu<C, CS, OS>(Hs, Wl, Os, qh, D.rw, hw);
+    __syncthreads();
+    const int q = 16 * wave + i;
+    const int qy = fast_div(q, rw_inv);
+    const size_t qtok = (size_t)(y0 + qy) * D.W + x0 + q - qy * D.rw;
+    wo_project_store<C, OS, kPrefetchWo>(Os, kPrefetchWo ? wof : nullptr, A.WoT,
+                                         A.Y + img_off + qtok * C, wave, g, i);
+}
+
+// ---------------------------------------------------------------------------
 struct MfmaWs {
     bf16_t *q, *k, *v, *wt, *wot;
+    float *qr, *krt;
     void *route;
     int32_t *ir;
     size_t bytes;
 };
+
+bool fast_route_ok(const Dims &D) { return D.S <= kFastRouteMaxS; }
+
+int halo_rows(const Dims &D)
+{
+    const int qh = 64 / D.rw;
+    return (qh + 4) * (D.rw + 4);
+}
+
+// The fused pipeline pays one extra K/V projection per routed key block.
+bool fused_ok(const Dims &D)
+{
+    static const bool disabled = getenv("BRA_DISABLE_FUSED") != nullptr;   // benchmarking aid
+    if (disabled || !fast_route_ok(D)) return false;
+    if (D.C != 64 && D.C != 128) return false;
+    return D.kn / 64 <= 1;
+}
 
 MfmaWs carve(const Dims &D, void *ws)
 {
@@ -384,10 +554,36 @@ MfmaWs carve(const Dims &D, void *ws)
     w.v = (bf16_t *)take(tok * D.C * 2);
     w.wt = (bf16_t *)take((size_t)3 * D.C * D.C * 2);
     w.wot = (bf16_t *)take((size_t)D.C * D.C * 2);
-    w.route = take(valu_route_scratch_bytes(D));
+    w.qr = (float *)take((size_t)D.B * D.R * D.C * sizeof(float));
+    w.krt = (float *)take((size_t)D.B * D.C * kRpad * sizeof(float));
+    w.route = take(fast_route_ok(D) ? 0 : valu_route_scratch_bytes(D));
     w.ir = (int32_t *)take((size_t)D.B * D.R * D.k * sizeof(int32_t));
     w.bytes = off;
     return w;
+}
+
+template <int C>
+void launch_pool_qk(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *Wo,
+                    const MfmaWs &w, bool pool, bool prep, hipStream_t st)
+{
+    const int pool_blocks = pool ? D.B * D.S : 0;
+    const int prep_blocks = prep ? (4 * C * C + 255) / 256 : 0;
+    if (pool_blocks + prep_blocks == 0) return;
+    ProfScope ps(st, K_MFMA_POOL_QK);
+    hipLaunchKernelGGL(k_pool_qk<C>, dim3(pool_blocks + prep_blocks), dim3(256), 0, st, X, Wqkv, Wo,
+                       w.qr, w.krt, w.wt, w.wot, D, pool_blocks);
+}
+
+// More than 64 KB of dynamic LDS needs an opt-in, once per kernel.
+template <typename K>
+bool lds_opt_in(K kernel, bool &done)
+{
+    if (done) return true;
+    if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) !=
+        hipSuccess)
+        return false;
+    done = true;
+    return true;
 }
 
 template <int C>
@@ -395,46 +591,63 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
               const bf16_t *Wlce, bf16_t *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
               const MfmaWs &w, hipStream_t st)
 {
-    const int32_t *Ir = Ir_in_opt;
-    if (!Ir_in_opt) {
-        int32_t *dst = Ir_out_opt ? Ir_out_opt : w.ir;
-        int rc = valu_route(D, X, Wqkv, dst, nullptr, w.route, st);
-        if (rc != BRA_OK) return rc;
-        Ir = dst;
-    } else if (Ir_out_opt) {
-        if (hipMemcpyAsync(Ir_out_opt, Ir_in_opt, sizeof(int32_t) * (size_t)D.B * D.R * D.k,
-                           hipMemcpyDeviceToDevice, st) != hipSuccess)
-            return BRA_ERR_LAUNCH;
-    }
-    {
+    const int32_t *Ir_src = Ir_in_opt;
+    if (fast_route_ok(D)) {
+        launch_pool_qk<C>(D, X, Wqkv, Wo, w, /*pool=*/!Ir_in_opt, /*prep=*/true, st);
+    } else {
+        if (!Ir_in_opt) {
+            int32_t *dst = Ir_out_opt ? Ir_out_opt : w.ir;
+            int rc = valu_route(D, X, Wqkv, dst, nullptr, w.route, st);
+            if (rc != BRA_OK) return rc;
+            Ir_src = dst;
+        }
         ProfScope ps(st, K_MFMA_PREP);
         hipLaunchKernelGGL(k_prep_weights, dim3((4 * C * C + 255) / 256), dim3(256), 0, st, Wqkv, Wo,
                            w.wt, w.wot, C);
+    }
+    AttnArgs A;
+    A.X = X; A.WT = w.wt; A.Q = w.q; A.K = w.k; A.V = w.v; A.Qr = w.qr; A.KrT = w.krt;
+    A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = Wlce; A.WoT = w.wot; A.Y = Y;
+    A.c_exp = D.scale * 1.4426950408889634f;
+    A.total = D.B * D.R * (D.n / 64);
+    const int grid = ((A.total + 7) / 8) * 8;
+    const int hrows = halo_rows(D);
+
+    if constexpr (C <= 128) {
+        if (fused_ok(D)) {
+            static bool opted = false;
+            if (!lds_opt_in(k_fused<C>, opted)) return BRA_ERR_LAUNCH;
+            const size_t smem = AttnSmem<C>::bytes(((hrows + 15) / 16) * 16);
+            ProfScope ps(st, K_MFMA_FUSED_K1);
+            hipLaunchKernelGGL(k_fused<C>, dim3(grid), dim3(256), smem, st, A, D);
+            return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+        }
     }
     const long M = (long)D.B * D.N;
     {
         constexpr int NU = (C == 256) ? 1 : 2;
         const long ntiles = (M + 16 * NU - 1) / (16 * NU);
-        const int grid = (int)(ntiles < 2048 ? ntiles : 2048);
+        const int qgrid = (int)(ntiles < 2048 ? ntiles : 2048);
         ProfScope ps(st, K_MFMA_QKV);
-        hipLaunchKernelGGL((k_qkv<C, NU>), dim3(grid), dim3(3 * C), 0, st, X, w.wt, w.q, w.k, w.v, M);
+        hipLaunchKernelGGL((k_qkv<C, NU>), dim3(qgrid), dim3(3 * C), 0, st, X, w.wt, w.q, w.k, w.v, M);
     }
     {
-        const int qh = 64 / D.rw;
-        const size_t smem = AttnBigSmem<C>::bytes((qh + 4) * (D.rw + 4));
-        const int grid = D.B * D.R * (D.n / 64);
-        const float c_exp = D.scale * 1.4426950408889634f;
-        static bool lds_opt_in = false;   // allow more than 64 KB of dynamic LDS, once
-        if (!lds_opt_in) {
-            if (hipFuncSetAttribute((const void *)k_attn_big<C>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) != hipSuccess)
-                return BRA_ERR_LAUNCH;
-            lds_opt_in = true;
-        }
+        static bool opted = false;
+        if (!lds_opt_in(k_attn_big<C>, opted)) return BRA_ERR_LAUNCH;
+        const size_t smem = AttnSmem<C>::bytes(hrows);
         ProfScope ps(st, K_MFMA_ATTENTION);
-        hipLaunchKernelGGL(k_attn_big<C>, dim3(grid), dim3(256), smem, st, w.q, w.k, w.v, Ir, Wlce,
-                           w.wot, Y, D, c_exp);
+        hipLaunchKernelGGL(k_attn_big<C>, dim3(grid), dim3(256), smem, st, A, D);
     }
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+template <int C>
+int route_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, int32_t *Ir, float *Ar_opt,
+            const MfmaWs &w, hipStream_t st)
+{
+    launch_pool_qk<C>(D, X, Wqkv, nullptr, w, /*pool=*/true, /*prep=*/false, st);
+    ProfScope ps(st, K_MFMA_ROUTE_ROWS);
+    hipLaunchKernelGGL(k_route_rows<C>, dim3(D.B * D.R), dim3(256), 0, st, w.qr, w.krt, Ir, Ar_opt, D);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
@@ -444,10 +657,11 @@ bool attn_big_ok(const Dims &D)
     if (D.rw < 8 || 64 % D.rw != 0) return false;
     const int qh = 64 / D.rw;
     if (D.rh % qh != 0) return false;
+    const int halo = ((halo_rows(D) + 15) / 16) * 16;
     size_t smem = 0;
-    if (D.C == 64) smem = AttnBigSmem<64>::bytes((qh + 4) * (D.rw + 4));
-    else if (D.C == 128) smem = AttnBigSmem<128>::bytes((qh + 4) * (D.rw + 4));
-    else smem = AttnBigSmem<256>::bytes((qh + 4) * (D.rw + 4));
+    if (D.C == 64) smem = AttnSmem<64>::bytes(halo);
+    else if (D.C == 128) smem = AttnSmem<128>::bytes(halo);
+    else smem = AttnSmem<256>::bytes(halo);
     return smem <= (size_t)kMaxLds;
 }
 
@@ -457,8 +671,8 @@ bool mfma_supported(const Dims &D)
 {
     if (D.dtype != BRA_BF16 || D.d != 32) return false;
     if (D.C != 64 && D.C != 128 && D.C != 256) return false;
-    if ((long)D.B * D.R * (D.n / 64 + 1) > 0x7fffffffL) return false;
-    if (!generic_supported(D)) return false;   // routing uses the scalar kernels
+    if ((long)D.B * D.R * (D.n / 64 + 1) + 8 > 0x7fffffffL) return false;
+    if (!fast_route_ok(D) && !generic_supported(D)) return false;   // fallback routing kernels
     return attn_big_ok(D);
 }
 
@@ -468,7 +682,14 @@ int mfma_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, floa
                hipStream_t st)
 {
     MfmaWs w = carve(D, ws);
-    return valu_route(D, X, Wqkv, Ir, Ar_opt, w.route, st);
+    if (!fast_route_ok(D)) return valu_route(D, X, Wqkv, Ir, Ar_opt, w.route, st);
+    const bf16_t *x = (const bf16_t *)X, *wq = (const bf16_t *)Wqkv;
+    switch (D.C) {
+    case 64: return route_c<64>(D, x, wq, Ir, Ar_opt, w, st);
+    case 128: return route_c<128>(D, x, wq, Ir, Ar_opt, w, st);
+    case 256: return route_c<256>(D, x, wq, Ir, Ar_opt, w, st);
+    default: return BRA_ERR_UNSUPPORTED;
+    }
 }
 
 int mfma_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,

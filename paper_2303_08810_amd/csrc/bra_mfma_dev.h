@@ -1,0 +1,384 @@
+// Device-side building blocks shared by the matrix-core (MFMA) kernels (internal).
+//
+// All contractions use v_mfma_f32_16x16x32_bf16 (64-lane wavefront; lane l = 16 g + i):
+//   A operand: lane holds A[row i][k = 8 g .. 8 g + 7]
+//   B operand: lane holds B[k = 8 g .. 8 g + 7][col i]
+//   D result : lane holds D[row 4 g .. 4 g + 3][col i]
+// so both operands are read as 16-byte runs along the contraction axis, and the
+// contraction may use any key order as long as A and B agree on it.
+#pragma once
+
+#include "bra_common.h"
+
+namespace bra {
+namespace mfma {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWave = 64;
+constexpr int kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
+constexpr int kRpad = 64;             // row pitch of the transposed region keys (R <= 64)
+constexpr int kFastRouteMaxS = 8;     // the in-kernel routing covers S <= 8 (R <= 64)
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// Two floats -> packed bf16 pair (round to nearest even), low half = a.
+__device__ __forceinline__ unsigned pack_bf16(float a, float b)
+{
+    f32x2 v = {a, b};
+    bf16x2 r = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(unsigned, r);
+}
+
+__device__ __forceinline__ bf16x8 pack8(const float *v)
+{
+    u32x4 u = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]),
+               pack_bf16(v[6], v[7])};
+    return __builtin_bit_cast(bf16x8, u);
+}
+
+__device__ __forceinline__ u32x2 pack4(f32x4 v)
+{
+    return u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+}
+
+__device__ __forceinline__ float bf16_lo(unsigned u) { return __builtin_bit_cast(float, u << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
+
+// row / width without an integer division; exact for the small non-negative values
+// that occur here (row < 2^20).
+__device__ __forceinline__ int fast_div(int row, float width_inv)
+{
+    return (int)(((float)row + 0.5f) * width_inv);
+}
+
+// LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane s
+// supplies the address of 4 consecutive 16-bit elements; the four lanes 4 j .. 4 j + 3
+// together supply a row j of 16 elements.  Lane i receives element i of rows 0..3.
+__device__ __forceinline__ s16x4 lds_read_tr16(const bf16_t *p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)p);
+}
+
+// Row `reg` of A^r = Q^r (K^r)^T (Eq. 4) and the indices of its k largest entries
+// (Eq. 5): larger value first, equal values by smaller index, NaN as -inf.  Called by
+// all 256 threads of a workgroup; R <= 64.  part: 256 floats of LDS; the result is
+// left in ir_s[0..k) (LDS) and, if the pointers are set, written to memory as well.
+template <int C>
+__device__ __forceinline__ void route_row(const float *__restrict__ Qr,
+                                          const float *__restrict__ KrT, int b, int reg, int R,
+                                          int k, float *part, int *ir_s, int32_t *Ir_row_out,
+                                          float *Ar_row_out)
+{
+    const int tid = threadIdx.x, j = tid % kWave, cq = tid / kWave;
+    const float *q = Qr + ((size_t)b * R + reg) * C + cq * (C / 4);
+    const float *kt = KrT + ((size_t)b * C + cq * (C / 4)) * kRpad + j;
+    float a = 0.f;
+#pragma unroll
+    for (int c = 0; c < C / 4; ++c) a = fmaf(q[c], kt[(size_t)c * kRpad], a);
+    part[cq * kWave + j] = a;
+    __syncthreads();
+    if (tid < kWave) {
+        float v = ((part[j] + part[kWave + j]) + part[2 * kWave + j]) + part[3 * kWave + j];
+        if (Ar_row_out && j < R) Ar_row_out[j] = v;
+        if (!(v == v)) v = -INFINITY;
+        bool avail = j < R;
+        for (int p = 0; p < k; ++p) {
+            float bv = avail ? v : -INFINITY;
+            int bi = avail ? j : 0x7fffffff;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const float ov = __shfl_xor(bv, off, kWave);
+                const int oi = __shfl_xor(bi, off, kWave);
+                const bool take = (oi != 0x7fffffff) && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+                if (take) { bv = ov; bi = oi; }
+            }
+            if (bi == j) avail = false;
+            if (j == 0) {
+                ir_s[p] = bi;
+                if (Ir_row_out) Ir_row_out[p] = bi;
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// Global -> register half of a tile copy: chunk idx (16 bytes) is row idx / (C/8) of
+// the tile, token (y0 + row / tw, x0 + row % tw) of the map; chunks past `rows` and
+// tokens outside the image read as zero.
+template <int C, int NB>
+__device__ __forceinline__ void tile_load(u32x4 (&r)[NB], const bf16_t *__restrict__ img, int y0,
+                                          int x0, int tw, float tw_inv, int rows, int H, int W,
+                                          int first)
+{
+    constexpr int CH = C / 8;
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+        const int idx = first + (int)threadIdx.x + 256 * u;
+        const int row = idx / CH, cc = idx % CH;
+        const int ty = fast_div(row, tw_inv);
+        const int y = y0 + ty, x = x0 + row - ty * tw;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (row < rows && y >= 0 && y < H && x >= 0 && x < W)
+            v = *(const u32x4 *)(img + ((size_t)y * W + x) * C + cc * 8);
+        r[u] = v;
+    }
+}
+
+// Register -> LDS half: rows of CS elements.
+template <int C, int CS, int NB>
+__device__ __forceinline__ void tile_store(bf16_t *dst, const u32x4 (&r)[NB], int rows, int first)
+{
+    constexpr int CH = C / 8;
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+        const int idx = first + (int)threadIdx.x + 256 * u;
+        const int row = idx / CH, cc = idx % CH;
+        if (row < rows) *(u32x4 *)(dst + row * CS + cc * 8) = r[u];
+    }
+}
+
+// LCE weights [C][25] bf16 in memory -> [25][C] float32 in LDS, in two halves so that
+// the loads can be issued early and the LDS writes done later.
+template <int C>
+struct LceWeights {
+    static constexpr int NW = (C * 25 / 8 + 255) / 256;   // 16-byte chunks per thread
+    u32x4 r[NW];
+    __device__ __forceinline__ void load(const bf16_t *__restrict__ Wlce)
+    {
+#pragma unroll
+        for (int u = 0; u < NW; ++u) {
+            const int t = threadIdx.x + 256 * u;
+            r[u] = u32x4{0u, 0u, 0u, 0u};
+            if (t < C * 25 / 8) r[u] = *(const u32x4 *)(Wlce + t * 8);
+        }
+    }
+    __device__ __forceinline__ void store(float *Wl) const
+    {
+#pragma unroll
+        for (int u = 0; u < NW; ++u) {
+            const int t = threadIdx.x + 256 * u;
+            if (t < C * 25 / 8) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int idx = t * 8 + e;             // flat (channel, tap)
+                    const unsigned bits = r[u][e / 2];
+                    Wl[(idx % 25) * C + idx / 25] = (e & 1) ? bf16_hi(bits) : bf16_lo(bits);
+                }
+            }
+        }
+    }
+};
+
+// Online-softmax state of one wavefront: 16 queries (one per lane column i), all heads.
+template <int HEADS>
+struct SoftmaxState {
+    float m[HEADS], l[HEADS];
+    f32x4 acc[HEADS][2];     // O^T[channel 16 dt + 4 g + j][query i]
+    __device__ __forceinline__ void init()
+    {
+#pragma unroll
+        for (int h = 0; h < HEADS; ++h) {
+            m[h] = -INFINITY;
+            l[h] = 0.f;
+            acc[h][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+            acc[h][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+};
+
+// One block of 64 keys (rows of Ks / Vs, CS elements per row) against the 16 queries of
+// this wavefront (qf[h] = B operand of head h): S^T = K Q^T, online softmax over the
+// keys (Eq. 1, one softmax over all routed keys), O^T += V^T P^T.
+template <int C, int CS>
+__device__ __forceinline__ void attn_key_block(const bf16_t *Ks, const bf16_t *Vs,
+                                               const bf16x8 (&qf)[C / 32],
+                                               SoftmaxState<C / 32> &st, float c_exp, int g, int i)
+{
+    constexpr int HEADS = C / 32;
+#pragma unroll
+    for (int h = 0; h < HEADS; ++h) {
+        f32x4 s[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + 32 * h + 8 * g);
+            s[t] = mfma16(kf, qf[h], f32x4{0.f, 0.f, 0.f, 0.f});   // S^T[key 16t+4g+j][query i]
+        }
+        float mx = s[0][0];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) mx = fmaxf(mx, s[t][jj]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float m_new = fmaxf(st.m[h], mx);
+        const float alpha = __builtin_amdgcn_exp2f((st.m[h] - m_new) * c_exp);
+        const float mc = m_new * c_exp;
+        float p[4][4], ls = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                p[t][jj] = __builtin_amdgcn_exp2f(fmaf(s[t][jj], c_exp, -mc));
+                ls += p[t][jj];
+            }
+        ls += __shfl_xor(ls, 16, kWave);
+        ls += __shfl_xor(ls, 32, kWave);
+        st.l[h] = st.l[h] * alpha + ls;
+        st.m[h] = m_new;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) st.acc[h][dt] *= alpha;
+#pragma unroll
+        for (int tp = 0; tp < 2; ++tp) {
+            float pv[8] = {p[2 * tp][0], p[2 * tp][1], p[2 * tp][2], p[2 * tp][3],
+                           p[2 * tp + 1][0], p[2 * tp + 1][1], p[2 * tp + 1][2], p[2 * tp + 1][3]};
+            const bf16x8 pb = pack8(pv);
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) {
+                const int col = 32 * h + 16 * dt + 4 * (i % 4);
+                const s16x4 v0 = lds_read_tr16(Vs + (32 * tp + 4 * g + i / 4) * CS + col);
+                const s16x4 v1 = lds_read_tr16(Vs + (32 * tp + 16 + 4 * g + i / 4) * CS + col);
+                u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+                u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
+                st.acc[h][dt] = mfma16(__builtin_bit_cast(bf16x8, av), pb, st.acc[h][dt]);
+            }
+        }
+    }
+}
+
+// Normalised attention output of this wavefront's 16 queries -> rows 16 wave + i of the
+// float32 output tile Os (OS floats per row).
+template <int C, int OS>
+__device__ __forceinline__ void attn_write_out(float *Os, const SoftmaxState<C / 32> &st, int wave,
+                                               int g, int i)
+{
+#pragma unroll
+    for (int h = 0; h < C / 32; ++h) {
+        const float inv = 1.0f / st.l[h];
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+            f32x4 o = st.acc[h][dt] * inv;
+            *(f32x4 *)(Os + (16 * wave + i) * OS + 32 * h + 16 * dt + 4 * g) = o;
+        }
+    }
+}
+
+// LCE (Eq. 7): 5x5 depth-wise cross-correlation of V over the halo tile Hs (rows of CS
+// bf16, (qh + 4) x hw tokens, hw = rw + 4), added to the output tile Os.  One task =
+// (row of the query tile, 8-token segment, channel pair); Wl is [25][C] float32.
+template <int C, int CS, int OS>
+__device__ __forceinline__ void lce_add_valu(const bf16_t *Hs, const float *Wl, float *Os, int qh,
+                                             int rw, int hw)
+{
+    const int segs = rw / 8, cp_n = C / 2;
+    const int tasks = qh * segs * cp_n;
+    for (int task = threadIdx.x; task < tasks; task += 256) {
+        const int cp = task % cp_n, seg = (task / cp_n) % segs, r = task / (cp_n * segs);
+        const int c = 2 * cp;
+        float a0[8], a1[8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) { a0[x] = 0.f; a1[x] = 0.f; }
+#pragma unroll
+        for (int ky = 0; ky < 5; ++ky) {
+            f32x2 wk[5];
+#pragma unroll
+            for (int kx = 0; kx < 5; ++kx) wk[kx] = *(const f32x2 *)(Wl + (ky * 5 + kx) * C + c);
+            float v0[12], v1[12];
+#pragma unroll
+            for (int x = 0; x < 12; ++x) {
+                const unsigned u = *(const unsigned *)(Hs + ((r + ky) * hw + seg * 8 + x) * CS + c);
+                v0[x] = bf16_lo(u);
+                v1[x] = bf16_hi(u);
+            }
+#pragma unroll
+            for (int x = 0; x < 8; ++x)
+#pragma unroll
+                for (int kx = 0; kx < 5; ++kx) {
+                    a0[x] = fmaf(wk[kx][0], v0[x + kx], a0[x]);
+                    a1[x] = fmaf(wk[kx][1], v1[x + kx], a1[x]);
+                }
+        }
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            f32x2 *o = (f32x2 *)(Os + (r * rw + seg * 8 + x) * OS + c);
+            f32x2 cur = *o;
+            cur[0] += a0[x];
+            cur[1] += a1[x];
+            *o = cur;
+        }
+    }
+}
+
+// W^o fragments of output-channel group cg for the transposed product Y^T = Wo^T O^T:
+// tile tt, A row i  <->  output channel 64 cg + 16 (i / 4) + 4 tt + (i % 4), so that a
+// lane ends up with 16 consecutive output channels of one token.
+template <int C>
+__device__ __forceinline__ bf16x8 wo_fragment(const bf16_t *__restrict__ WoT, int cg, int tt, int ks,
+                                              int g, int i)
+{
+    const int o = cg * 64 + 16 * (i / 4) + 4 * tt + (i % 4);
+    return *(const bf16x8 *)(WoT + (size_t)o * C + 32 * ks + 8 * g);
+}
+
+// Y = O Wo (Eq. 2) for the 16 tokens of this wavefront: rows 16 wave + i of Os -> yrow
+// (this lane's token row of Y).  wof: prefetched fragments (C == 64) or unused.
+template <int C, int OS, bool PREFETCHED>
+__device__ __forceinline__ void wo_project_store(const float *Os, const bf16x8 (*wof)[C / 32],
+                                                 const bf16_t *__restrict__ WoT, bf16_t *yrow,
+                                                 int wave, int g, int i)
+{
+    constexpr int KS = C / 32;
+    bf16x8 of[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const float *src = Os + (16 * wave + i) * OS + 32 * ks + 8 * g;
+        f32x4 lo = *(const f32x4 *)src, hi = *(const f32x4 *)(src + 4);
+        float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        of[ks] = pack8(v);
+    }
+#pragma unroll
+    for (int cg = 0; cg < C / 64; ++cg) {
+        f32x4 ya[4];
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+            ya[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                bf16x8 wf;
+                if constexpr (PREFETCHED) wf = wof[tt][ks];
+                else wf = wo_fragment<C>(WoT, cg, tt, ks, g, i);
+                ya[tt] = mfma16(wf, of[ks], ya[tt]);
+            }
+        }
+        u32x2 p0 = pack4(ya[0]), p1 = pack4(ya[1]), p2 = pack4(ya[2]), p3 = pack4(ya[3]);
+        u32x4 *dst = (u32x4 *)(yrow + cg * 64 + 16 * g);
+        dst[0] = u32x4{p0[0], p0[1], p1[0], p1[1]};
+        dst[1] = u32x4{p2[0], p2[1], p3[0], p3[1]};
+    }
+}
+
+// Arguments shared by the attention kernels.
+struct AttnArgs {
+    const bf16_t *X;                // input map [B, H, W, C] (fused kernel)
+    const bf16_t *WT;               // [3C][C] transposed projection weights (fused kernel)
+    const bf16_t *Q, *K, *V;        // projected maps [B, H, W, C] (staged kernel)
+    const float *Qr, *KrT;          // region queries [B, R, C], region keys [B, C, 64]
+    const int32_t *Ir_src;          // routing index in memory, or NULL: route in the kernel
+    int32_t *Ir_out;                // where to report the routing index, or NULL
+    const bf16_t *Wlce, *WoT;
+    bf16_t *Y;
+    float c_exp;                    // softmax scale * log2(e)
+    int total;                      // workgroups that have work
+};
+
+}  // namespace mfma
+}  // namespace bra
