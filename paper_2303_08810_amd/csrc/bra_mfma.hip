@@ -222,9 +222,8 @@ template <int C>
 struct AttnSmem {
     static constexpr int CS = C + 8;
     static constexpr int OS = C + 4;
-    static constexpr size_t q_off = 0;                                // Q tile (fused kernel)
-    static constexpr size_t k_off = q_off + (size_t)64 * CS * 2;      // K tile; output tile later
-    static constexpr size_t v_off = k_off + (size_t)64 * CS * 2;      // V tile
+    static constexpr size_t k_off = 0;                                // K tile; output tile later
+    static constexpr size_t v_off = k_off + (size_t)64 * CS * 2;      // V tile (fused: Q tile first)
     static constexpr size_t w_off = v_off + (size_t)64 * CS * 2;      // LCE weights [25][C] f32
     static constexpr size_t p_off = w_off + (size_t)25 * C * 4;       // routing partials
     static constexpr size_t i_off = p_off + 256 * 4;                  // routed regions
@@ -341,29 +340,44 @@ __global__ __launch_bounds__(256) void k_attn_big(AttnArgs A, Dims D)
 }
 
 // ---------------------------------------------------------------------------
-// Fused forward for one 64-token query tile: Q, the K / V of the routed key blocks and
-// the V halo needed by the LCE are projected from X inside the workgroup (Eq. 3), so
-// Q, K, V never travel through memory.  Wavefront w owns output channels
-// [w C/4, (w+1) C/4) of each projection (weights in registers) for ALL tokens of the
-// workgroup; the projected tiles meet in LDS, then the attention, LCE and W^o phases
-// are those of k_attn_big.  Each routed key block costs one more K/V projection, so
-// this kernel is used when there are few key blocks per query tile (the k = 1 stage).
+// Fused forward for one 64-token query tile whose region attends to a single
+// 64-token key block (the k = 1 stage): Q, the routed K / V and the V halo needed by
+// the LCE are projected from X inside the workgroup (Eq. 3), so Q, K, V never travel
+// through memory.  X tiles are staged once through LDS.  Wavefront w owns output
+// channels [w C/4, (w+1) C/4) of every projection (its weight slices stay in
+// registers) for ALL tokens of the workgroup; the projected tiles replace the X tiles
+// in LDS in place, then attention, LCE and W^o follow as in k_attn_big.
 template <int C>
-__global__ __launch_bounds__(256) void k_fused(AttnArgs A, Dims D)
+struct FusedSmem {
+    static constexpr int CS = C + 8;
+    static constexpr int OS = C + 4;
+    static constexpr int kMaxHaloTiles = 10;                          // 16-row tiles: rw = 8 or 16
+    static constexpr size_t k_off = 0;                                // routed X tile -> K tile
+    static constexpr size_t v_off = k_off + (size_t)64 * CS * 2;      // Q tile -> V tile
+    static constexpr size_t w_off = v_off + (size_t)64 * CS * 2;      // LCE weights [25][C] f32
+    static constexpr size_t p_off = w_off + (size_t)25 * C * 4;       // routing partials
+    static constexpr size_t i_off = p_off + 256 * 4;                  // routed regions
+    static constexpr size_t h_off = i_off + kRpad * 4;                // X halo tile -> V halo tile
+    static size_t bytes(int halo_tiles) { return h_off + (size_t)halo_tiles * 16 * CS * 2; }
+};
+
+template <int C>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void k_fused(AttnArgs A, Dims D)
 {
-    typedef AttnSmem<C> SM;
-    constexpr int CS = SM::CS, OS = SM::OS, HEADS = C / 32, KS = C / 32;
+    typedef FusedSmem<C> SM;
+    constexpr int CS = SM::CS, OS = SM::OS, HEADS = C / 32, KS = C / 32, CH = C / 8;
     constexpr int NT = C / 64;                  // 16-channel output tiles per wavefront and matrix
-    constexpr int HB = 3;                       // halo token tiles per load batch
-    constexpr bool kPrefetchWo = (C == 64);
+    constexpr int NHT = SM::kMaxHaloTiles;
+    constexpr int NBH = (NHT * 16 * CH + 255) / 256;   // halo chunks per thread
+    constexpr int NBT = CH / 4;                 // chunks per thread of a 64-row tile
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16_t *Qs = (bf16_t *)(smem + SM::q_off);
-    bf16_t *Ks = (bf16_t *)(smem + SM::k_off);
-    bf16_t *Vs = (bf16_t *)(smem + SM::v_off);
+    bf16_t *Ks = (bf16_t *)(smem + SM::k_off);   // first the routed X tile
+    bf16_t *Vs = (bf16_t *)(smem + SM::v_off);   // first the Q tile
     float *Wl = (float *)(smem + SM::w_off);
     float *part = (float *)(smem + SM::p_off);
     int *ir_s = (int *)(smem + SM::i_off);
-    bf16_t *Hs = (bf16_t *)(smem + SM::h_off);
+    bf16_t *Hs = (bf16_t *)(smem + SM::h_off);   // first the X halo tile
     float *Os = (float *)(smem + SM::k_off);
 
     const int wid = swizzled_block();
@@ -371,19 +385,19 @@ __global__ __launch_bounds__(256) void k_fused(AttnArgs A, Dims D)
 
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
-    const int chunks = D.n / 64;
-    const int qh = 64 / D.rw;
-    const int b = wid / (D.R * chunks);
-    const int reg = (wid / chunks) % D.R;
-    const int ch = wid % chunks;
-    const int y0 = (reg / D.S) * D.rh + ch * qh, x0 = (reg % D.S) * D.rw;
+    const int qh = 64 / D.rw;                   // n == 64: one query tile per region
+    const int b = wid / D.R, reg = wid % D.R;
+    const int y0 = (reg / D.S) * D.rh, x0 = (reg % D.S) * D.rw;
     const size_t img_off = (size_t)b * D.N * C;
     const bf16_t *Ximg = A.X + img_off;
-    const int hw = D.rw + 4, hrows = (qh + 4) * hw;
+    const int hw = D.rw + 4, hrows = (qh + 4) * hw, nht = (hrows + 15) / 16;
     const float hw_inv = 1.0f / (float)hw, rw_inv = 1.0f / (float)D.rw;
 
-    // Weight fragments (A operands): row i of tile t  <->  output channel 16 (w NT + t) + i.
-    bf16x8 wq[NT][KS], wk[NT][KS], wv[NT][KS];
+    // Requests that do not depend on the routing: X over the halo of the query tile
+    // (it contains the query tile), this wavefront's weight slices, the LCE weights.
+    u32x4 hreg[NBH];
+    tile_load<C, NBH>(hreg, Ximg, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, 0);
+    bf16x8 wq[NT][KS], wk[NT][KS], wv[NT][KS], wo[NT][KS];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -392,128 +406,127 @@ __global__ __launch_bounds__(256) void k_fused(AttnArgs A, Dims D)
             wq[t][ks] = *(const bf16x8 *)(A.WT + row);
             wk[t][ks] = *(const bf16x8 *)(A.WT + (size_t)C * C + row);
             wv[t][ks] = *(const bf16x8 *)(A.WT + (size_t)2 * C * C + row);
+            wo[t][ks] = *(const bf16x8 *)(A.WoT + row);
         }
-    // X fragments (B operands) of the 64 query tokens: token 16 u + i, channels 32 ks + 8 g ..
-    bf16x8 xf[4][KS];
+    LceWeights<C> lw;
+    lw.load(A.Wlce);
+
+    int j;
+    if (A.Ir_src) {
+        j = A.Ir_src[(size_t)b * D.R + reg];
+        if (A.Ir_out && A.Ir_out != A.Ir_src && threadIdx.x == 0) A.Ir_out[(size_t)b * D.R + reg] = j;
+    } else {
+        route_row<C>(A.Qr, A.KrT, b, reg, D.R, 1, part, ir_s,
+                     A.Ir_out ? A.Ir_out + (size_t)b * D.R + reg : nullptr, nullptr);
+        j = ir_s[0];
+    }
+    u32x4 kreg[NBT];
+    tile_load<C, NBT>(kreg, Ximg, (j / D.S) * D.rh, (j % D.S) * D.rw, D.rw, rw_inv, 64, D.H, D.W, 0);
+    tile_store<C, CS, NBH>(Hs, hreg, hrows, 0);
+    lw.store(Wl);
+    tile_store<C, CS, NBT>(Ks, kreg, 64, 0);
+    __syncthreads();
+
+    // Projections of this wavefront's channel slice.  D^T[channel 16 tile + 4 g + jj][token i]:
+    // a lane ends up with 4 consecutive channels of one token (8 bytes of bf16).
+    u32x2 vh[NHT][NT], kk[4][NT], vv[4][NT];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int q = 16 * u + i;
         const int qy = fast_div(q, rw_inv);
-        const bf16_t *row = Ximg + ((size_t)(y0 + qy) * D.W + x0 + q - qy * D.rw) * C + 8 * g;
+        const bf16_t *xq = Hs + ((qy + 2) * hw + q - qy * D.rw + 2) * CS + 8 * g;   // query token in the halo
+        const bf16_t *xk = Ks + q * CS + 8 * g;
+        bf16x8 bq[KS], bk[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) xf[u][ks] = *(const bf16x8 *)(row + 32 * ks);
-    }
-    LceWeights<C> lw;
-    lw.load(A.Wlce);
-    bf16x8 wof[kPrefetchWo ? 4 : 1][KS];
-    if constexpr (kPrefetchWo) {
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) wof[tt][ks] = wo_fragment<C>(A.WoT, 0, tt, ks, g, i);
-    }
-
-    const int32_t *irp;
-    if (A.Ir_src) {
-        irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
-        if (A.Ir_out && A.Ir_out != A.Ir_src && ch == 0)
-            for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
-    } else {
-        route_row<C>(A.Qr, A.KrT, b, reg, D.R, D.k, part, ir_s,
-                     (A.Ir_out && ch == 0) ? A.Ir_out + ((size_t)b * D.R + reg) * D.k : nullptr, nullptr);
-        irp = ir_s;
-    }
-    lw.store(Wl);
-
-    // Q tile: D^T[channel 16 tile + 4 g + j][token 16 u + i] -> 8-byte LDS writes.
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
+        for (int ks = 0; ks < KS; ++ks) {
+            bq[ks] = *(const bf16x8 *)(xq + 32 * ks);
+            bk[ks] = *(const bf16x8 *)(xk + 32 * ks);
+        }
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            f32x4 a = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) a = mfma16(wq[t][ks], xf[u][ks], a);
-            *(u32x2 *)(Qs + (16 * u + i) * CS + 16 * (wave * NT + t) + 4 * g) = pack4(a);
-        }
-
-    // V over the halo of the query tile (zero outside the image, as V = 0 there).
-    const int nht = (hrows + 15) / 16;
-    for (int hu0 = 0; hu0 < nht; hu0 += HB) {
-        bf16x8 xh[HB][KS];
-#pragma unroll
-        for (int hb = 0; hb < HB; ++hb) {
-            const int row = 16 * (hu0 + hb) + i;
-            const int hy = fast_div(row, hw_inv);
-            const int y = y0 - 2 + hy, x = x0 - 2 + row - hy * hw;
-            const bool ok = row < hrows && y >= 0 && y < D.H && x >= 0 && x < D.W;
+            f32x4 aq = {0.f, 0.f, 0.f, 0.f}, ak = {0.f, 0.f, 0.f, 0.f}, av = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (ok) v = *(const u32x4 *)(Ximg + ((size_t)y * D.W + x) * C + 32 * ks + 8 * g);
-                xh[hb][ks] = __builtin_bit_cast(bf16x8, v);
+                aq = mfma16(wq[t][ks], bq[ks], aq);
+                ak = mfma16(wk[t][ks], bk[ks], ak);
+                av = mfma16(wv[t][ks], bk[ks], av);
             }
+            *(u32x2 *)(Vs + q * CS + 16 * (wave * NT + t) + 4 * g) = pack4(aq);   // Q tile
+            kk[u][t] = pack4(ak);
+            vv[u][t] = pack4(av);
         }
+    }
 #pragma unroll
-        for (int hb = 0; hb < HB; ++hb) {
-            if (hu0 + hb >= nht) break;
+    for (int hu = 0; hu < NHT; ++hu) {
+        if (hu < nht) {
+            const bf16_t *xh = Hs + (16 * hu + i) * CS + 8 * g;
+            bf16x8 bh[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) bh[ks] = *(const bf16x8 *)(xh + 32 * ks);
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 f32x4 a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) a = mfma16(wv[t][ks], xh[hb][ks], a);
-                *(u32x2 *)(Hs + (16 * (hu0 + hb) + i) * CS + 16 * (wave * NT + t) + 4 * g) = pack4(a);
+                for (int ks = 0; ks < KS; ++ks) a = mfma16(wv[t][ks], bh[ks], a);
+                vh[hu][t] = pack4(a);
             }
         }
     }
+    __syncthreads();   // every X tile has been read; the Q tile is complete
+    bf16x8 qf[HEADS];
+#pragma unroll
+    for (int h = 0; h < HEADS; ++h) qf[h] = *(const bf16x8 *)(Vs + (16 * wave + i) * CS + 32 * h + 8 * g);
+#pragma unroll
+    for (int hu = 0; hu < NHT; ++hu)
+        if (hu < nht) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                *(u32x2 *)(Hs + (16 * hu + i) * CS + 16 * (wave * NT + t) + 4 * g) = vh[hu][t];
+        }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+            *(u32x2 *)(Ks + (16 * u + i) * CS + 16 * (wave * NT + t) + 4 * g) = kk[u][t];
+    __syncthreads();   // the Q fragments are read: V may take the slot
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+            *(u32x2 *)(Vs + (16 * u + i) * CS + 16 * (wave * NT + t) + 4 * g) = vv[u][t];
+    __syncthreads();
 
     SoftmaxState<HEADS> st;
     st.init();
-    bf16x8 qf[HEADS];
-    const int nblocks = D.kn / 64;
-    for (int kb = 0; kb < nblocks; ++kb) {
-        const int j = irp[kb / chunks];
-        const int ky0 = (j / D.S) * D.rh + (kb % chunks) * qh, kx0 = (j % D.S) * D.rw;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int q = 16 * u + i;
-            const int qy = fast_div(q, rw_inv);
-            const bf16_t *row = Ximg + ((size_t)(ky0 + qy) * D.W + kx0 + q - qy * D.rw) * C + 8 * g;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) xf[u][ks] = *(const bf16x8 *)(row + 32 * ks);
-        }
-        __syncthreads();   // the previous block's readers are done with Ks / Vs
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                f32x4 ak = {0.f, 0.f, 0.f, 0.f}, av = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    ak = mfma16(wk[t][ks], xf[u][ks], ak);
-                    av = mfma16(wv[t][ks], xf[u][ks], av);
-                }
-                const int off = (16 * u + i) * CS + 16 * (wave * NT + t) + 4 * g;
-                *(u32x2 *)(Ks + off) = pack4(ak);
-                *(u32x2 *)(Vs + off) = pack4(av);
-            }
-        __syncthreads();
-        if (kb == 0) {
-#pragma unroll
-            for (int h = 0; h < HEADS; ++h)
-                qf[h] = *(const bf16x8 *)(Qs + (16 * wave + i) * CS + 32 * h + 8 * g);
-        }
-        attn_key_block<C, CS>(Ks, Vs, qf, st, A.c_exp, g, i);
-    }
+    attn_key_block<C, CS>(Ks, Vs, qf, st, A.c_exp, g, i);
     __syncthreads();
     attn_write_out<C, OS>(Os, st, wave, g, i);
     __syncthreads();
     lce_add_valu<C, CS, OS>(Hs, Wl, Os, qh, D.rw, hw);
     __syncthreads();
-    const int q = 16 * wave + i;
-    const int qy = fast_div(q, rw_inv);
-    const size_t qtok = (size_t)(y0 + qy) * D.W + x0 + q - qy * D.rw;
-    wo_project_store<C, OS, kPrefetchWo>(Os, kPrefetchWo ? wof : nullptr, A.WoT,
-                                         A.Y + img_off + qtok * C, wave, g, i);
+
+    // Y^T slice = Wo^T slice * O^T: this wavefront's 16 NT output channels of all 64 tokens.
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int q = 16 * u + i;
+        bf16x8 of[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const float *src = Os + q * OS + 32 * ks + 8 * g;
+            f32x4 lo = *(const f32x4 *)src, hi = *(const f32x4 *)(src + 4);
+            float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            of[ks] = pack8(v);
+        }
+        const int qy = fast_div(q, rw_inv);
+        bf16_t *yrow = A.Y + img_off + ((size_t)(y0 + qy) * D.W + x0 + q - qy * D.rw) * C;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            f32x4 ya = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) ya = mfma16(wo[t][ks], of[ks], ya);
+            *(u32x2 *)(yrow + 16 * (wave * NT + t) + 4 * g) = pack4(ya);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -539,7 +552,8 @@ bool fused_ok(const Dims &D)
     static const bool disabled = getenv("BRA_DISABLE_FUSED") != nullptr;   // benchmarking aid
     if (disabled || !fast_route_ok(D)) return false;
     if (D.C != 64 && D.C != 128) return false;
-    return D.kn / 64 <= 1;
+    if (D.n != 64 || D.k != 1 || (D.rw != 8 && D.rw != 16)) return false;
+    return (halo_rows(D) + 15) / 16 <= FusedSmem<64>::kMaxHaloTiles;
 }
 
 MfmaWs carve(const Dims &D, void *ws)
@@ -617,7 +631,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
         if (fused_ok(D)) {
             static bool opted = false;
             if (!lds_opt_in(k_fused<C>, opted)) return BRA_ERR_LAUNCH;
-            const size_t smem = AttnSmem<C>::bytes(((hrows + 15) / 16) * 16);
+            const size_t smem = FusedSmem<C>::bytes((hrows + 15) / 16);
             ProfScope ps(st, K_MFMA_FUSED_K1);
             hipLaunchKernelGGL(k_fused<C>, dim3(grid), dim3(256), smem, st, A, D);
             return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
