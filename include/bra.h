@@ -112,6 +112,14 @@ int bra_profile_begin(int max_records);
 int bra_profile_end(int32_t *ids, float *ms, int max_records, int *n_out);
 const char *bra_kernel_name(int id);
 
+/* Measurement aids: plain streaming kernels over `bytes` bytes of device memory
+ * (multiple of 16, pointers 16-byte aligned), enqueued on hip_stream.  bra_util_copy
+ * copies src to dst; its known traffic (bytes read + bytes written) is what hardware
+ * byte counters are scaled against.  bra_util_read only reads src (scratch4: 4 bytes
+ * of device memory that are practically never written).  Errors: NULL, SHAPE, LAUNCH. */
+int bra_util_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
+int bra_util_read(const void *src, size_t bytes, void *scratch4, void *hip_stream);
+
 /* Static, human-readable text for a return code. */
 const char *bra_strerror(int code);
 

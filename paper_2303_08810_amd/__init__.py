@@ -19,7 +19,8 @@ PATH_AUTO, PATH_GENERIC, PATH_MFMA = 0, 1, 2
 _PATHS = {"auto": PATH_AUTO, "generic": PATH_GENERIC, "mfma": PATH_MFMA}
 
 EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_strerror", "bra_version",
-           "bra_profile_begin", "bra_profile_end", "bra_kernel_name")
+           "bra_profile_begin", "bra_profile_end", "bra_kernel_name", "bra_util_copy",
+           "bra_util_read")
 
 
 class BraShape(ctypes.Structure):
@@ -64,6 +65,10 @@ def lib() -> ctypes.CDLL:
                                       ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
         L.bra_kernel_name.restype = ctypes.c_char_p
         L.bra_kernel_name.argtypes = [ctypes.c_int]
+        L.bra_util_copy.restype = ctypes.c_int
+        L.bra_util_copy.argtypes = [vp, vp, sz, vp]
+        L.bra_util_read.restype = ctypes.c_int
+        L.bra_util_read.argtypes = [vp, sz, vp, vp]
         _lib = L
     return _lib
 
@@ -162,3 +167,10 @@ def profile_end(max_records: int):
     n = ctypes.c_int(0)
     _check(lib().bra_profile_end(ids, ms, max_records, ctypes.byref(n)))
     return [(lib().bra_kernel_name(ids[i]).decode(), float(ms[i])) for i in range(n.value)]
+
+
+def util_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Plain device copy of src into dst (same byte size), for bandwidth calibration."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib().bra_util_copy(_ptr(dst), _ptr(src), nbytes, _stream(src.device)))

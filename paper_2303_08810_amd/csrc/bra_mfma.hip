@@ -46,9 +46,9 @@ __global__ void k_prep_weights(const bf16_t *__restrict__ Wqkv, const bf16_t *__
 
 // ---------------------------------------------------------------------------
 // Region pooling and region-level projections (Sec. 3.2, "Region-to-region routing").
-// Workgroup (b, sy) reads the band of rh rows that holds regions sy*S .. sy*S + S-1 of
-// image b exactly once, forms their mean tokens in float32 (fixed summation order),
-// and multiplies them by Wq and Wk:  Qr[b, r, :] and KrT[b, :, r] (keys transposed so
+// Workgroup (b, group) handles G consecutive regions of image b: it reads their tokens
+// exactly once, forms the mean tokens in float32 (fixed summation order), and
+// multiplies them by Wq and Wk:  Qr[b, r, :] and KrT[b, :, r] (keys transposed so
 // that a wavefront reads one channel of all regions as one contiguous run).
 // Workgroups beyond `pool_blocks` transpose the projection weights instead.
 template <int C>
@@ -57,10 +57,11 @@ __global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
                                                  const bf16_t *__restrict__ Wo,
                                                  float *__restrict__ Qr, float *__restrict__ KrT,
                                                  bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT,
-                                                 Dims D, int pool_blocks)
+                                                 Dims D, int pool_blocks, int G)
 {
+    constexpr int MAXG = kPoolMaxGroup;
     __shared__ float part[4096];   // pooling partials, then projection partials
-    __shared__ float xr[kFastRouteMaxS * C];
+    __shared__ float xr[MAXG * C];
     const int tid = threadIdx.x;
     if ((int)blockIdx.x >= pool_blocks) {
         const int e = ((int)blockIdx.x - pool_blocks) * 256 + tid;
@@ -68,14 +69,28 @@ __global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
         return;
     }
     constexpr int CH = C / 8;
-    const int b = blockIdx.x / D.S, sy = blockIdx.x % D.S;
-    const int items = D.S * CH;                               // (region, 8-channel chunk) pairs
-    const int P = items >= 256 ? 256 : ((items + 63) / 64) * 64;
+    constexpr int SPL = (C >= 256) ? 1 : 256 / C;   // input-channel splits of the projection
+    constexpr int CP = C / SPL;
+    constexpr bool kPrefetchW = CP <= 32;           // few enough weights to request up front
+    unsigned wpre[kPrefetchW ? CP : 1];
+    if constexpr (kPrefetchW) {
+#pragma unroll
+        for (int cc = 0; cc < CP; ++cc)
+            wpre[cc] = *(const unsigned *)(Wqkv + (size_t)((tid / C) * CP + cc) * 3 * C + 2 * (tid % C));
+    }
+    const int groups = (D.R + G - 1) / G;
+    const int b = blockIdx.x / groups, r0 = (blockIdx.x % groups) * G;
+    const int ng = min(G, D.R - r0);                           // regions of this workgroup
+    const int items = ng * CH;                                 // (region, 8-channel chunk) pairs
+    int P = 8;                                                 // power of two >= items, <= 256
+    while (P < items) P *= 2;
     const int SUB = 256 / P;                                   // threads that share one pair
     const int item = tid % P, sub = tid / P;
     if (item < items && sub < SUB) {
-        const int sx = item / CH, cc = item % CH;
-        const bf16_t *base = X + (((size_t)b * D.H + (size_t)sy * D.rh) * D.W + (size_t)sx * D.rw) * C + cc * 8;
+        const int gi = item / CH, cc = item % CH;
+        const int r = r0 + gi;
+        const int ry0 = (r / D.S) * D.rh, rx0 = (r % D.S) * D.rw;
+        const bf16_t *base = X + (((size_t)b * D.H + ry0) * D.W + rx0) * C + cc * 8;
         const float rw_inv = 1.0f / (float)D.rw;
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
@@ -92,9 +107,9 @@ __global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
         for (int e = 0; e < 8; ++e) part[(sub * items + item) * 8 + e] = acc[e];
     }
     __syncthreads();
-    for (int e = tid; e < D.S * C; e += 256) {
-        const int sx = e / C, c = e % C;
-        const int it = sx * CH + c / 8;
+    for (int e = tid; e < ng * C; e += 256) {
+        const int gi = e / C, c = e % C;
+        const int it = gi * CH + c / 8;
         float s = 0.f;
         for (int sb = 0; sb < SUB; ++sb) s += part[(sb * items + it) * 8 + c % 8];
         xr[e] = s / (float)D.n;
@@ -103,39 +118,39 @@ __global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
     // [Q^r | K^r] = xr [Wq | Wk].  Thread (oc, split) owns output columns 2 oc, 2 oc + 1
     // over input channels [split * CP, (split + 1) * CP); the SPL partial sums of a
     // column are added in ascending split order.
-    constexpr int SPL = (C >= 256) ? 1 : 256 / C;
-    constexpr int CP = C / SPL;
     {
         const int oc = tid % C, split = tid / C;
-        float acc0[kFastRouteMaxS], acc1[kFastRouteMaxS];
+        float acc0[MAXG], acc1[MAXG];
 #pragma unroll
-        for (int sx = 0; sx < kFastRouteMaxS; ++sx) { acc0[sx] = 0.f; acc1[sx] = 0.f; }
-#pragma unroll 16
+        for (int gi = 0; gi < MAXG; ++gi) { acc0[gi] = 0.f; acc1[gi] = 0.f; }
+#pragma unroll (CP <= 32 ? CP : 16)
         for (int cc = 0; cc < CP; ++cc) {
             const int c = split * CP + cc;
-            const unsigned w2 = *(const unsigned *)(Wqkv + (size_t)c * 3 * C + 2 * oc);
+            unsigned w2;
+            if constexpr (kPrefetchW) w2 = wpre[cc];
+            else w2 = *(const unsigned *)(Wqkv + (size_t)c * 3 * C + 2 * oc);
             const float w0 = bf16_lo(w2), w1 = bf16_hi(w2);
 #pragma unroll
-            for (int sx = 0; sx < kFastRouteMaxS; ++sx)
-                if (sx < D.S) {
-                    const float x = xr[sx * C + c];
-                    acc0[sx] = fmaf(x, w0, acc0[sx]);
-                    acc1[sx] = fmaf(x, w1, acc1[sx]);
+            for (int gi = 0; gi < MAXG; ++gi)
+                if (gi < ng) {
+                    const float x = xr[gi * C + c];
+                    acc0[gi] = fmaf(x, w0, acc0[gi]);
+                    acc1[gi] = fmaf(x, w1, acc1[gi]);
                 }
         }
 #pragma unroll
-        for (int sx = 0; sx < kFastRouteMaxS; ++sx) {
-            part[(split * kFastRouteMaxS + sx) * 2 * C + 2 * oc] = acc0[sx];
-            part[(split * kFastRouteMaxS + sx) * 2 * C + 2 * oc + 1] = acc1[sx];
+        for (int gi = 0; gi < MAXG; ++gi) {
+            part[(split * MAXG + gi) * 2 * C + 2 * oc] = acc0[gi];
+            part[(split * MAXG + gi) * 2 * C + 2 * oc + 1] = acc1[gi];
         }
     }
     __syncthreads();
-    for (int e = tid; e < D.S * 2 * C; e += 256) {
-        const int sx = e / (2 * C), o = e % (2 * C);
-        float v = part[sx * 2 * C + o];
+    for (int e = tid; e < ng * 2 * C; e += 256) {
+        const int gi = e / (2 * C), o = e % (2 * C);
+        float v = part[gi * 2 * C + o];
 #pragma unroll
-        for (int sp = 1; sp < SPL; ++sp) v += part[(sp * kFastRouteMaxS + sx) * 2 * C + o];
-        const int r = sy * D.S + sx;
+        for (int sp = 1; sp < SPL; ++sp) v += part[(sp * MAXG + gi) * 2 * C + o];
+        const int r = r0 + gi;
         if (o < C) Qr[((size_t)b * D.R + r) * C + o] = v;
         else KrT[((size_t)b * C + (o - C)) * kRpad + r] = v;
     }
@@ -580,12 +595,14 @@ template <int C>
 void launch_pool_qk(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *Wo,
                     const MfmaWs &w, bool pool, bool prep, hipStream_t st)
 {
-    const int pool_blocks = pool ? D.B * D.S : 0;
+    int G = C <= 128 ? 4 : kPoolMaxGroup;                         // regions per workgroup
+    if (const char *e = getenv("BRA_POOL_GROUP")) { int v = atoi(e); if (v >= 1 && v <= kPoolMaxGroup) G = v; }
+    const int pool_blocks = pool ? D.B * ((D.R + G - 1) / G) : 0;
     const int prep_blocks = prep ? (4 * C * C + 255) / 256 : 0;
     if (pool_blocks + prep_blocks == 0) return;
     ProfScope ps(st, K_MFMA_POOL_QK);
     hipLaunchKernelGGL(k_pool_qk<C>, dim3(pool_blocks + prep_blocks), dim3(256), 0, st, X, Wqkv, Wo,
-                       w.qr, w.krt, w.wt, w.wot, D, pool_blocks);
+                       w.qr, w.krt, w.wt, w.wot, D, pool_blocks, G);
 }
 
 // More than 64 KB of dynamic LDS needs an opt-in, once per kernel.

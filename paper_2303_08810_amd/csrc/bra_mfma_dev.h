@@ -25,6 +25,7 @@ constexpr int kWave = 64;
 constexpr int kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
 constexpr int kRpad = 64;             // row pitch of the transposed region keys (R <= 64)
 constexpr int kFastRouteMaxS = 8;     // the in-kernel routing covers S <= 8 (R <= 64)
+constexpr int kPoolMaxGroup = 8;      // regions pooled by one workgroup, at most
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c)
 {

@@ -1,0 +1,62 @@
+// Plain streaming kernels used to calibrate memory-bandwidth measurements: a copy of
+// known size (against which hardware byte counters are scaled) and a read-only sum.
+#include "bra_common.h"
+
+namespace bra {
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void k_util_copy(u32x4 *__restrict__ dst,
+                                                   const u32x4 *__restrict__ src, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void k_util_read(const u32x4 *__restrict__ src, size_t n16,
+                                                   unsigned *__restrict__ out)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    unsigned acc = 0;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        const u32x4 v = src[i];
+        acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+    }
+    if (acc == 0x9e3779b9u) out[0] = acc;   // practically never taken: keeps the loads alive
+}
+
+}  // namespace
+}  // namespace bra
+
+using namespace bra;
+
+extern "C" {
+
+int bra_util_copy(void *dst, const void *src, size_t bytes, void *hip_stream)
+{
+    if (!dst || !src) return BRA_ERR_NULL;
+    if (bytes % 16 || (uintptr_t)dst % 16 || (uintptr_t)src % 16) return BRA_ERR_SHAPE;
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return BRA_OK;
+    const size_t want = (n16 + 255) / 256;
+    const int grid = (int)(want < 256 * 32 ? want : 256 * 32);
+    hipLaunchKernelGGL(k_util_copy, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream, (u32x4 *)dst,
+                       (const u32x4 *)src, n16);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+int bra_util_read(const void *src, size_t bytes, void *scratch4, void *hip_stream)
+{
+    if (!src || !scratch4) return BRA_ERR_NULL;
+    if (bytes % 16 || (uintptr_t)src % 16) return BRA_ERR_SHAPE;
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return BRA_OK;
+    const size_t want = (n16 + 255) / 256;
+    const int grid = (int)(want < 256 * 32 ? want : 256 * 32);
+    hipLaunchKernelGGL(k_util_read, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const u32x4 *)src, n16, (unsigned *)scratch4);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+}  // extern "C"
