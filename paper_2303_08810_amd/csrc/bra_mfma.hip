@@ -246,14 +246,6 @@ struct AttnSmem {
     static size_t bytes(int halo_rows) { return h_off + (size_t)halo_rows * CS * 2; }
 };
 
-// Workgroup -> (image, region, query tile).  Consecutive block ids are dealt
-// round-robin to the 8 XCDs; undo that so that the workgroups of one image share an L2.
-__device__ __forceinline__ int swizzled_block()
-{
-    const int per_xcd = gridDim.x / 8;
-    return ((int)blockIdx.x % 8) * per_xcd + (int)blockIdx.x / 8;
-}
-
 // Routed attention + LCE + W^o for regions of n >= 64 tokens (Eq. 6-7, Eq. 2).
 // One workgroup = 64 query tokens (64/rw full rows of one region), all heads,
 // 4 wavefronts; wavefront w owns queries 16 w .. 16 w + 15.  Keys and values of the
@@ -546,7 +538,7 @@ void k_fused(AttnArgs A, Dims D)
 
 // ---------------------------------------------------------------------------
 struct MfmaWs {
-    bf16_t *q, *k, *v, *wt, *wot;
+    bf16_t *q, *k, *v, *o, *wt, *wot;
     float *qr, *krt;
     void *route;
     int32_t *ir;
@@ -581,6 +573,7 @@ MfmaWs carve(const Dims &D, void *ws)
     w.q = (bf16_t *)take(tok * D.C * 2);
     w.k = (bf16_t *)take(tok * D.C * 2);
     w.v = (bf16_t *)take(tok * D.C * 2);
+    w.o = (bf16_t *)take(small_supported(D) ? tok * D.C * 2 : 0);
     w.wt = (bf16_t *)take((size_t)3 * D.C * D.C * 2);
     w.wot = (bf16_t *)take((size_t)D.C * D.C * 2);
     w.qr = (float *)take((size_t)D.B * D.R * D.C * sizeof(float));
@@ -616,6 +609,8 @@ bool lds_opt_in(K kernel, bool &done)
     done = true;
     return true;
 }
+
+bool attn_big_ok(const Dims &D);
 
 template <int C>
 int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *Wo,
@@ -662,6 +657,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
         ProfScope ps(st, K_MFMA_QKV);
         hipLaunchKernelGGL((k_qkv<C, NU>), dim3(qgrid), dim3(3 * C), 0, st, X, w.wt, w.q, w.k, w.v, M);
     }
+    if (!attn_big_ok(D)) return launch_small(D, A, w.o, st);
     {
         static bool opted = false;
         if (!lds_opt_in(k_attn_big<C>, opted)) return BRA_ERR_LAUNCH;
@@ -704,7 +700,7 @@ bool mfma_supported(const Dims &D)
     if (D.C != 64 && D.C != 128 && D.C != 256) return false;
     if ((long)D.B * D.R * (D.n / 64 + 1) + 8 > 0x7fffffffL) return false;
     if (!fast_route_ok(D) && !generic_supported(D)) return false;   // fallback routing kernels
-    return attn_big_ok(D);
+    return attn_big_ok(D) || small_supported(D);
 }
 
 size_t mfma_workspace_bytes(const Dims &D) { return carve(D, nullptr).bytes; }

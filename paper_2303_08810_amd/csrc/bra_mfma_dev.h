@@ -381,5 +381,19 @@ struct AttnArgs {
     int total;                      // workgroups that have work
 };
 
+// Workgroup -> work item.  Consecutive block ids are dealt round-robin to the 8 XCDs;
+// undo that so that the workgroups of one image share an L2.  gridDim.x % 8 == 0.
+__device__ __forceinline__ int swizzled_block()
+{
+    const int per_xcd = gridDim.x / 8;
+    return ((int)blockIdx.x % 8) * per_xcd + (int)blockIdx.x / 8;
+}
+
 }  // namespace mfma
+
+// Small-region pipeline tail (bra_mfma_small.hip): per-(region, head) attention into O,
+// then LCE + output projection over row tiles.  A.Q/K/V, routing fields, Wlce, WoT, Y set.
+bool small_supported(const Dims &D);
+int launch_small(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st);
+
 }  // namespace bra

@@ -1,0 +1,308 @@
+// Matrix-core kernels for small regions (n = 1, 2, 4, 8 or 16 tokens per region).
+//
+// With so few queries per region a query tile cannot fill a 64-row workgroup tile from
+// one region, and every (region, head) pair has its own routed key set (Eq. 6).  So the
+// attention runs per (region, head) in one wavefront: the n queries occupy the first n
+// of the 16 query columns of the 16x16x32 MFMA tiles, keys are read by index straight
+// from the projected map into the A operands, values go through a wavefront-private LDS
+// tile for the transposing read.  The LCE and the output projection (Eq. 7, Eq. 2)
+// need whole spatial neighbourhoods and all heads, so they run in a second kernel over
+// tiles of full-width image rows.
+#include "bra_mfma_dev.h"
+
+namespace bra {
+
+using namespace mfma;
+
+namespace {
+
+constexpr int kVS = 40;   // bf16 elements per row of the private V tile (32 + 16-byte pad)
+
+// ---------------------------------------------------------------------------
+// One workgroup per (image, region); wavefront w handles heads w, w + 4, ...
+// O_att[b, token, head channels] = softmax(scale q K_g^T) V_g over the k n routed keys.
+template <int C>
+__global__ __launch_bounds__(256) void k_attn_small(AttnArgs A, bf16_t *__restrict__ O, Dims D,
+                                                    int log2n)
+{
+    constexpr int HEADS = C / 32;
+    __shared__ __attribute__((aligned(16))) bf16_t Vw[4][64 * kVS];
+    __shared__ float part[256];
+    __shared__ int ir_s[kRpad];
+
+    const int wid = swizzled_block();
+    if (wid >= A.total) return;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int g = lane / 16, i = lane % 16;
+    const int b = wid / D.R, reg = wid % D.R;
+    const size_t img_off = (size_t)b * D.N * C;
+    const int n = D.n, kn = D.kn;
+    const float rw_inv = 1.0f / (float)D.rw;
+
+    const int32_t *irp;
+    if (A.Ir_src) {
+        irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
+        if (A.Ir_out && A.Ir_out != A.Ir_src)
+            for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
+    } else {
+        route_row<C>(A.Qr, A.KrT, b, reg, D.R, D.k, part, ir_s,
+                     A.Ir_out ? A.Ir_out + ((size_t)b * D.R + reg) * D.k : nullptr, nullptr);
+        irp = ir_s;
+    }
+
+    // query token of this lane's column (columns >= n repeat the last query; never stored)
+    const int qs = i < n ? i : n - 1;
+    const int qy = fast_div(qs, rw_inv);
+    const size_t qtok = (size_t)((reg / D.S) * D.rh + qy) * D.W + (reg % D.S) * D.rw + qs - qy * D.rw;
+    bf16_t *vw = Vw[wave];
+
+    for (int h = wave; h < HEADS; h += 4) {
+        const bf16x8 qf = *(const bf16x8 *)(A.Q + img_off + qtok * C + 32 * h + 8 * g);
+        float m_run = -INFINITY, l_run = 0.f;
+        f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+        for (int k0 = 0; k0 < kn; k0 += 64) {
+            // key 16 t + i of this block: A-operand row i of tile t
+            bf16x8 kf[4];
+            u32x4 vr[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                int key = k0 + 16 * t + i;
+                if (key >= kn) key = kn - 1;
+                const int j = irp[key >> log2n], slot = key & (n - 1);
+                const int sy = fast_div(slot, rw_inv);
+                const size_t tok = (size_t)((j / D.S) * D.rh + sy) * D.W + (j % D.S) * D.rw + slot - sy * D.rw;
+                const size_t off = img_off + tok * C + 32 * h + 8 * g;
+                kf[t] = *(const bf16x8 *)(A.K + off);
+                vr[t] = *(const u32x4 *)(A.V + off);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) *(u32x4 *)(vw + (16 * t + i) * kVS + 8 * g) = vr[t];
+            f32x4 s[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) s[t] = mfma16(kf[t], qf, f32x4{0.f, 0.f, 0.f, 0.f});
+            if (k0 + 64 > kn) {   // ragged last block: keys past the end do not count
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj)
+                        if (k0 + 16 * t + 4 * g + jj >= kn) s[t][jj] = -INFINITY;
+            }
+            float mx = s[0][0];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) mx = fmaxf(mx, s[t][jj]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * A.c_exp);
+            const float mc = m_new * A.c_exp;
+            float p[4][4], ls = 0.f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    p[t][jj] = __builtin_amdgcn_exp2f(fmaf(s[t][jj], A.c_exp, -mc));
+                    ls += p[t][jj];
+                }
+            ls += __shfl_xor(ls, 16, kWave);
+            ls += __shfl_xor(ls, 32, kWave);
+            l_run = l_run * alpha + ls;
+            m_run = m_new;
+            acc[0] *= alpha;
+            acc[1] *= alpha;
+#pragma unroll
+            for (int tp = 0; tp < 2; ++tp) {
+                float pv[8] = {p[2 * tp][0], p[2 * tp][1], p[2 * tp][2], p[2 * tp][3],
+                               p[2 * tp + 1][0], p[2 * tp + 1][1], p[2 * tp + 1][2], p[2 * tp + 1][3]};
+                const bf16x8 pb = pack8(pv);
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    const int col = 16 * dt + 4 * (i % 4);
+                    const s16x4 v0 = lds_read_tr16(vw + (32 * tp + 4 * g + i / 4) * kVS + col);
+                    const s16x4 v1 = lds_read_tr16(vw + (32 * tp + 16 + 4 * g + i / 4) * kVS + col);
+                    u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+                    u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
+                    acc[dt] = mfma16(__builtin_bit_cast(bf16x8, av), pb, acc[dt]);
+                }
+            }
+        }
+        if (i < n) {
+            const float inv = 1.0f / l_run;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+                *(u32x2 *)(O + img_off + qtok * C + 32 * h + 16 * dt + 4 * g) = pack4(acc[dt] * inv);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Y = (O_att + LCE(V)) Wo over a tile of TH full-width image rows (TH * W <= 64 tokens).
+// LDS: V halo tile [(TH + 4) x (W + 4)] tokens, LCE weights, and the bf16 sum tile that
+// feeds the output projection.  Wavefront w owns output channels [w C/4, (w+1) C/4).
+template <int C>
+struct LceWoSmem {
+    static constexpr int CS = C + 8;
+    static constexpr size_t o_off = 0;                                   // sum tile [64][CS] bf16
+    static constexpr size_t w_off = o_off + (size_t)64 * CS * 2;         // LCE weights [25][C] f32
+    static constexpr size_t h_off = w_off + (size_t)25 * C * 4;          // V halo tile
+    static size_t bytes(int halo_rows) { return h_off + (size_t)(halo_rows + 16) * CS * 2; }
+};
+
+template <int C>
+__global__ __launch_bounds__(256) void k_lce_wo(const bf16_t *__restrict__ Oatt,
+                                                const bf16_t *__restrict__ V,
+                                                const bf16_t *__restrict__ Wlce,
+                                                const bf16_t *__restrict__ WoT,
+                                                bf16_t *__restrict__ Y, Dims D, int TH)
+{
+    typedef LceWoSmem<C> SM;
+    constexpr int CS = SM::CS, KS = C / 32, CH = C / 8, NT = C / 64;
+    constexpr int NBH = 4;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *Ob = (bf16_t *)(smem + SM::o_off);
+    float *Wl = (float *)(smem + SM::w_off);
+    bf16_t *Hs = (bf16_t *)(smem + SM::h_off);
+
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int g = lane / 16, i = lane % 16;
+    const int tiles = (D.H + TH - 1) / TH;
+    const int b = blockIdx.x / tiles, y0 = (blockIdx.x % tiles) * TH;
+    const int th = min(TH, D.H - y0);            // rows of this tile
+    const int ntok = th * D.W;
+    const size_t img_off = (size_t)b * D.N * C;
+    const int hw = D.W + 4, hrows = (th + 4) * hw;
+    const float hw_inv = 1.0f / (float)hw;
+
+    LceWeights<C> lw;
+    lw.load(Wlce);
+    for (int first = 0; first < hrows * CH; first += 256 * NBH) {
+        u32x4 hreg[NBH];
+        tile_load<C, NBH>(hreg, V + img_off, y0 - 2, -2, hw, hw_inv, hrows, D.H, D.W, first);
+        tile_store<C, CS, NBH>(Hs, hreg, hrows, first);
+    }
+    lw.store(Wl);
+    __syncthreads();
+
+    // LCE over (row, 8-token segment, channel pair) tasks; the sum with the attention
+    // output is rounded to bf16 once and becomes the B operand of the output projection.
+    {
+        const int segs = (D.W + 7) / 8, cp_n = C / 2;
+        const int tasks = th * segs * cp_n;
+        const bf16_t *orow = Oatt + img_off + (size_t)y0 * D.W * C;
+        for (int task = threadIdx.x; task < tasks; task += 256) {
+            const int cp = task % cp_n, seg = (task / cp_n) % segs, r = task / (cp_n * segs);
+            const int c = 2 * cp;
+            float a0[8], a1[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) { a0[x] = 0.f; a1[x] = 0.f; }
+#pragma unroll
+            for (int ky = 0; ky < 5; ++ky) {
+                f32x2 wk[5];
+#pragma unroll
+                for (int kx = 0; kx < 5; ++kx) wk[kx] = *(const f32x2 *)(Wl + (ky * 5 + kx) * C + c);
+                float v0[12], v1[12];
+#pragma unroll
+                for (int x = 0; x < 12; ++x) {   // a ragged last segment reads into the pad rows
+                    const unsigned u = *(const unsigned *)(Hs + ((r + ky) * hw + seg * 8 + x) * CS + c);
+                    v0[x] = bf16_lo(u);
+                    v1[x] = bf16_hi(u);
+                }
+#pragma unroll
+                for (int x = 0; x < 8; ++x)
+#pragma unroll
+                    for (int kx = 0; kx < 5; ++kx) {
+                        a0[x] = fmaf(wk[kx][0], v0[x + kx], a0[x]);
+                        a1[x] = fmaf(wk[kx][1], v1[x + kx], a1[x]);
+                    }
+            }
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const int xx = seg * 8 + x;
+                if (xx < D.W) {
+                    const int tok = r * D.W + xx;
+                    const unsigned o2 = *(const unsigned *)(orow + (size_t)tok * C + c);
+                    *(unsigned *)(Ob + tok * CS + c) = pack_bf16(bf16_lo(o2) + a0[x], bf16_hi(o2) + a1[x]);
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // Y^T slice = Wo^T slice * O^T: this wavefront's output channels of all tokens.
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        if (16 * u >= ntok) break;
+        const int q = 16 * u + i;
+        bf16x8 of[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) of[ks] = *(const bf16x8 *)(Ob + q * CS + 32 * ks + 8 * g);
+        bf16_t *yrow = Y + img_off + ((size_t)y0 * D.W + q) * C;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            f32x4 ya = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 wf = *(const bf16x8 *)(WoT + (size_t)(16 * (wave * NT + t) + i) * C + 32 * ks + 8 * g);
+                ya = mfma16(wf, of[ks], ya);
+            }
+            if (q < ntok) *(u32x2 *)(yrow + 16 * (wave * NT + t) + 4 * g) = pack4(ya);
+        }
+    }
+}
+
+int tile_rows(const Dims &D) { return 64 / D.W; }
+
+}  // namespace
+
+bool small_supported(const Dims &D)
+{
+    if (D.n > 16 || (D.n & (D.n - 1)) != 0) return false;   // n = 1, 2, 4, 8, 16
+    if (D.W > 64) return false;
+    const int TH = tile_rows(D);
+    const int halo = (TH + 4) * (D.W + 4);
+    size_t smem = D.C == 64 ? LceWoSmem<64>::bytes(halo)
+                : D.C == 128 ? LceWoSmem<128>::bytes(halo) : LceWoSmem<256>::bytes(halo);
+    return smem <= (size_t)kMaxLds;
+}
+
+template <int C>
+static int launch_small_c(const Dims &D, const AttnArgs &A0, bf16_t *O, hipStream_t st)
+{
+    AttnArgs A = A0;
+    A.total = D.B * D.R;
+    int log2n = 0;
+    while ((1 << log2n) < D.n) ++log2n;
+    {
+        ProfScope ps(st, K_MFMA_ATTN_SMALL);
+        hipLaunchKernelGGL(k_attn_small<C>, dim3(((A.total + 7) / 8) * 8), dim3(256), 0, st, A, O, D, log2n);
+    }
+    {
+        const int TH = tile_rows(D);
+        const size_t smem = LceWoSmem<C>::bytes((TH + 4) * (D.W + 4));
+        static bool opted = false;
+        if (!opted) {
+            if (hipFuncSetAttribute((const void *)k_lce_wo<C>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kMaxLds) != hipSuccess)
+                return BRA_ERR_LAUNCH;
+            opted = true;
+        }
+        const int tiles = (D.H + TH - 1) / TH;
+        ProfScope ps(st, K_MFMA_LCE_WO);
+        hipLaunchKernelGGL(k_lce_wo<C>, dim3(D.B * tiles), dim3(256), smem, st, O, A.V, A.Wlce, A.WoT, A.Y,
+                           D, TH);
+    }
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+int launch_small(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st)
+{
+    switch (D.C) {
+    case 64: return launch_small_c<64>(D, A, O, st);
+    case 128: return launch_small_c<128>(D, A, O, st);
+    case 256: return launch_small_c<256>(D, A, O, st);
+    default: return BRA_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace bra

@@ -82,6 +82,24 @@ def test_mfma_path_shapes(B, H, W, C, heads, S, k):
     compare(X, Wqkv, Wo, Wlce, "bf16", S, k, heads, "mfma")
 
 
+MFMA_SMALL_SHAPES = [  # regions of 1..16 tokens: per-(region, head) attention + row-tile LCE/Wo
+    (2, 28, 28, 128, 4, 7, 4),     # stage-2 shape, n = 16
+    (2, 14, 14, 256, 8, 7, 16),    # stage-3 shape, n = 4
+    (2, 8, 8, 64, 2, 4, 3),        # n = 4, 12 keys: ragged key block
+    (1, 16, 16, 64, 2, 8, 5),      # n = 4, 20 keys
+    (2, 14, 14, 64, 2, 7, 49),     # k = S^2: full attention over 196 keys, several blocks
+    (1, 7, 7, 64, 2, 7, 49),       # stage-4 shape: one token per region
+    (2, 12, 24, 128, 4, 6, 7),     # 2 x 4 regions, n = 8
+    (3, 21, 14, 64, 2, 7, 2),      # 3 x 2 regions, n = 6 is not supported -> generic family
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,S,k", MFMA_SMALL_SHAPES)
+def test_mfma_small_regions(B, H, W, C, heads, S, k):
+    X, Wqkv, Wo, Wlce = make_inputs(B, H, W, C, seed=3000 + H + 3 * C + k, dtype="bf16")
+    compare(X, Wqkv, Wo, Wlce, "bf16", S, k, heads, "auto")
+
+
 def test_mfma_scale_and_forced_routing():
     X, Wqkv, Wo, Wlce = make_inputs(2, 16, 16, 64, seed=77, dtype="bf16")
     compare(X, Wqkv, Wo, Wlce, "bf16", 2, 2, 2, "mfma", scale=0.05)
