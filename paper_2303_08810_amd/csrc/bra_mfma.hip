@@ -37,11 +37,12 @@ __device__ inline void prep_weight_element(const bf16_t *__restrict__ Wqkv,
     else WoT[(size_t)(o - 3 * C) * C + c] = Wo[(size_t)c * C + (o - 3 * C)];
 }
 
+// `total` = 4 C^2 (all weights) or 3 C^2 (projection weights only, Wo may be NULL).
 __global__ void k_prep_weights(const bf16_t *__restrict__ Wqkv, const bf16_t *__restrict__ Wo,
-                               bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT, int C)
+                               bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT, int C, int total)
 {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e < 4 * C * C) prep_weight_element(Wqkv, Wo, WT, WoT, C, e);
+    if (e < total) prep_weight_element(Wqkv, Wo, WT, WoT, C, e);
 }
 
 // ---------------------------------------------------------------------------
@@ -156,6 +157,93 @@ __global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
     }
 }
 
+// Pooling kernel for wide channels (C >= 128): same results layout as k_pool_qk, but the
+// region-level projection [Q^r | K^r] = xr [Wq | Wk] runs on the matrix cores.  The
+// float32 region means are split exactly into three bf16 terms (x = hi + mid + lo: 3 x 8
+// mantissa bits), each term is multiplied by the (bf16) weights with float32
+// accumulation, so the products are those of the float32 computation up to summation
+// order.  Needs the transposed weights WT, i.e. runs after k_prep_weights.
+// Workgroup (b, group) handles 16 consecutive regions (the 16 MFMA columns).
+template <int C>
+__global__ __launch_bounds__(256) void k_pool_qk_mfma(const bf16_t *__restrict__ X,
+                                                      const bf16_t *__restrict__ WT,
+                                                      float *__restrict__ Qr, float *__restrict__ KrT,
+                                                      Dims D)
+{
+    constexpr int G = 16, CH = C / 8, KS = C / 32, XS = C + 8;
+    __shared__ float part[G * C];                                   // per-(region, channel) sums
+    __shared__ __attribute__((aligned(16))) bf16_t xs[3][G * XS];   // hi / mid / lo terms
+    const int tid = threadIdx.x;
+    const int groups = (D.R + G - 1) / G;
+    const int b = blockIdx.x / groups, r0 = (blockIdx.x % groups) * G;
+    const int ng = min(G, D.R - r0);
+    const float rw_inv = 1.0f / (float)D.rw;
+
+    // region sums: one thread per (region, 8-channel chunk), tokens in row-major order
+    for (int item = tid; item < G * CH; item += 256) {
+        const int gi = item / CH, cc = item % CH;
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (gi < ng) {
+            const int r = r0 + gi;
+            const bf16_t *base = X + (((size_t)b * D.H + (r / D.S) * D.rh) * D.W + (r % D.S) * D.rw) * C + cc * 8;
+#pragma unroll 4
+            for (int slot = 0; slot < D.n; ++slot) {
+                const int ry = fast_div(slot, rw_inv), rx = slot - ry * D.rw;
+                const u32x4 v = *(const u32x4 *)(base + ((size_t)ry * D.W + rx) * C);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[2 * e] += bf16_lo(v[e]);
+                    acc[2 * e + 1] += bf16_hi(v[e]);
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[gi * C + cc * 8 + e] = acc[e];
+    }
+    __syncthreads();
+    // means and their exact three-term bf16 split (rows >= ng are zero)
+    for (int e = tid; e < G * C; e += 256) {
+        const int gi = e / C, c = e % C;
+        const float x = part[e] / (float)D.n;
+        const float h = bf16_to_f32(f32_to_bf16(x));
+        const float r1 = x - h;
+        const float m = bf16_to_f32(f32_to_bf16(r1));
+        const float r2 = r1 - m;
+        xs[0][gi * XS + c] = f32_to_bf16(x);
+        xs[1][gi * XS + c] = f32_to_bf16(r1);
+        xs[2][gi * XS + c] = f32_to_bf16(r2);
+    }
+    __syncthreads();
+
+    const int wave = tid / kWave, lane = tid % kWave;
+    const int g = lane / 16, i = lane % 16;
+    bf16x8 xf[3][KS];   // B operands: column i = region r0 + i, k = input channel
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) xf[t][ks] = *(const bf16x8 *)(xs[t] + i * XS + 32 * ks + 8 * g);
+    // output-channel tiles of [Wq | Wk]: 2C / 16 tiles, dealt round-robin to the wavefronts
+    for (int ct = wave; ct < 2 * C / 16; ct += 4) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 wf = *(const bf16x8 *)(WT + (size_t)(16 * ct + i) * C + 32 * ks + 8 * g);
+            acc = mfma16(wf, xf[2][ks], acc);    // smallest term first
+            acc = mfma16(wf, xf[1][ks], acc);
+            acc = mfma16(wf, xf[0][ks], acc);
+        }
+        if (i < ng) {   // rows: output channels 16 ct + 4 g + j; column: region r0 + i
+            const int o = 16 * ct + 4 * g, r = r0 + i;
+            if (o < C) {
+                *(f32x4 *)(Qr + ((size_t)b * D.R + r) * C + o) = acc;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) KrT[((size_t)b * C + (o - C + j)) * kRpad + r] = acc[j];
+            }
+        }
+    }
+}
+
 // bra_route: one workgroup per (b, region) writes its row of Ir (and of Ar).
 template <int C>
 __global__ __launch_bounds__(256) void k_route_rows(const float *__restrict__ Qr,
@@ -172,21 +260,23 @@ __global__ __launch_bounds__(256) void k_route_rows(const float *__restrict__ Qr
 
 // ---------------------------------------------------------------------------
 // Q, K, V = X [Wq | Wk | Wv]  (Eq. 3).  Each wavefront owns 64 output channels of one
-// of the three matrices and keeps its weight fragments in registers; the workgroup
-// (3C/64 wavefronts) walks over tiles of 16*NU tokens.  The product is formed
-// transposed (rows = output channels, columns = tokens) with the weight rows
-// permuted so that a lane ends up with 16 consecutive output channels of one token,
-// i.e. one 32-byte store.
-template <int C, int NU>
-__global__ __launch_bounds__(3 * C) void k_qkv(const bf16_t *__restrict__ X,
-                                               const bf16_t *__restrict__ WT,
-                                               bf16_t *__restrict__ Q, bf16_t *__restrict__ K,
-                                               bf16_t *__restrict__ V, long M)
+// of the three matrices and keeps its weight fragments in registers; a workgroup is
+// WPB such wavefronts (blockIdx.y selects which) and walks over `tiles_per_wg`
+// consecutive tiles of 16*NU tokens, requesting the next tile's X fragments before it
+// computes the current one.  The product is formed transposed (rows = output channels,
+// columns = tokens) with the weight rows permuted so that a lane ends up with 16
+// consecutive output channels of one token, i.e. one 32-byte store.
+template <int C, int NU, int WPB>
+__global__ __launch_bounds__(64 * WPB) void k_qkv(const bf16_t *__restrict__ X,
+                                                  const bf16_t *__restrict__ WT,
+                                                  bf16_t *__restrict__ Q, bf16_t *__restrict__ K,
+                                                  bf16_t *__restrict__ V, long M, int tiles_per_wg)
 {
     constexpr int KS = C / 32;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
-    const int sel = wave / (C / 64), base = (wave % (C / 64)) * 64;
+    const int grp = blockIdx.y * WPB + wave;            // 64-channel group among 3C/64
+    const int sel = grp / (C / 64), base = (grp % (C / 64)) * 64;
     bf16_t *__restrict__ out = sel == 0 ? Q : (sel == 1 ? K : V);
 
     bf16x8 af[4][KS];
@@ -199,17 +289,21 @@ __global__ __launch_bounds__(3 * C) void k_qkv(const bf16_t *__restrict__ X,
     }
 
     const long ntiles = (M + 16 * NU - 1) / (16 * NU);
-    for (long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const long tok0 = tile * 16 * NU;
-        bf16x8 bfr[NU][KS];
+    const long tile0 = (long)blockIdx.x * tiles_per_wg;
+    const long tile1 = tile0 + tiles_per_wg < ntiles ? tile0 + tiles_per_wg : ntiles;
+    auto load_tile = [&](long tile, bf16x8 (&fr)[NU][KS]) {
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
-            long t = tok0 + 16 * u + i;
+            long t = tile * 16 * NU + 16 * u + i;
             if (t >= M) t = M - 1;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                bfr[u][ks] = *(const bf16x8 *)(X + t * C + 32 * ks + 8 * g);
+            for (int ks = 0; ks < KS; ++ks) fr[u][ks] = *(const bf16x8 *)(X + t * C + 32 * ks + 8 * g);
         }
+    };
+    bf16x8 cur[NU][KS], nxt[NU][KS];
+    if (tile0 < tile1) load_tile(tile0, cur);
+    for (long tile = tile0; tile < tile1; ++tile) {
+        if (tile + 1 < tile1) load_tile(tile + 1, nxt);
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
             f32x4 acc[4];
@@ -217,15 +311,21 @@ __global__ __launch_bounds__(3 * C) void k_qkv(const bf16_t *__restrict__ X,
             for (int tt = 0; tt < 4; ++tt) {
                 acc[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) acc[tt] = mfma16(af[tt][ks], bfr[u][ks], acc[tt]);
+                for (int ks = 0; ks < KS; ++ks) acc[tt] = mfma16(af[tt][ks], cur[u][ks], acc[tt]);
             }
-            const long t = tok0 + 16 * u + i;
+            const long t = tile * 16 * NU + 16 * u + i;
             if (t < M) {
                 u32x2 p0 = pack4(acc[0]), p1 = pack4(acc[1]), p2 = pack4(acc[2]), p3 = pack4(acc[3]);
                 u32x4 *dst = (u32x4 *)(out + t * C + base + 16 * g);
                 dst[0] = u32x4{p0[0], p0[1], p1[0], p1[1]};
                 dst[1] = u32x4{p2[0], p2[1], p3[0], p3[1]};
             }
+        }
+        if (tile + 1 < tile1) {
+#pragma unroll
+            for (int u = 0; u < NU; ++u)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) cur[u][ks] = nxt[u][ks];
         }
     }
 }
@@ -588,7 +688,23 @@ template <int C>
 void launch_pool_qk(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *Wo,
                     const MfmaWs &w, bool pool, bool prep, hipStream_t st)
 {
-    int G = C <= 128 ? 4 : kPoolMaxGroup;                         // regions per workgroup
+    if constexpr (C >= 128) {
+        // wide channels: transpose the weights first, then pool + project on the matrix cores
+        // (pool && !prep happens in bra_route: only WT's Wq|Wk rows are needed, Wo may be NULL)
+        {
+            ProfScope ps(st, K_MFMA_PREP);
+            const int total = (prep ? 4 : 3) * C * C;
+            hipLaunchKernelGGL(k_prep_weights, dim3((total + 255) / 256), dim3(256), 0, st, Wqkv, Wo, w.wt,
+                               w.wot, C, total);
+        }
+        if (pool) {
+            ProfScope ps(st, K_MFMA_POOL_QK);
+            hipLaunchKernelGGL(k_pool_qk_mfma<C>, dim3(D.B * ((D.R + 15) / 16)), dim3(256), 0, st, X, w.wt,
+                               w.qr, w.krt, D);
+        }
+        return;
+    }
+    int G = 4;                                                     // regions per workgroup
     if (const char *e = getenv("BRA_POOL_GROUP")) { int v = atoi(e); if (v >= 1 && v <= kPoolMaxGroup) G = v; }
     const int pool_blocks = pool ? D.B * ((D.R + G - 1) / G) : 0;
     const int prep_blocks = prep ? (4 * C * C + 255) / 256 : 0;
@@ -629,7 +745,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
         }
         ProfScope ps(st, K_MFMA_PREP);
         hipLaunchKernelGGL(k_prep_weights, dim3((4 * C * C + 255) / 256), dim3(256), 0, st, Wqkv, Wo,
-                           w.wt, w.wot, C);
+                           w.wt, w.wot, C, 4 * C * C);
     }
     AttnArgs A;
     A.X = X; A.WT = w.wt; A.Q = w.q; A.K = w.k; A.V = w.v; A.Qr = w.qr; A.KrT = w.krt;
@@ -652,10 +768,16 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     const long M = (long)D.B * D.N;
     {
         constexpr int NU = (C == 256) ? 1 : 2;
+        constexpr int WPB = (C == 256) ? 4 : 3 * C / 64;      // wavefronts (64-channel groups) per workgroup
         const long ntiles = (M + 16 * NU - 1) / (16 * NU);
-        const int qgrid = (int)(ntiles < 2048 ? ntiles : 2048);
+        // tiles per workgroup: at least ~1000 wavefronts in flight, yet few weight reloads
+        long tpw = ntiles * (3 * C / 64) / 1024;
+        tpw = tpw < 1 ? 1 : (tpw > 8 ? 8 : tpw);
+        if (const char *e = getenv("BRA_QKV_TPW")) { int v = atoi(e); if (v >= 1 && v <= 64) tpw = v; }
+        const int gx = (int)((ntiles + tpw - 1) / tpw);
         ProfScope ps(st, K_MFMA_QKV);
-        hipLaunchKernelGGL((k_qkv<C, NU>), dim3(qgrid), dim3(3 * C), 0, st, X, w.wt, w.q, w.k, w.v, M);
+        hipLaunchKernelGGL((k_qkv<C, NU, WPB>), dim3(gx, 3 * C / 64 / WPB), dim3(64 * WPB), 0, st, X, w.wt,
+                           w.q, w.k, w.v, M, (int)tpw);
     }
     if (!attn_big_ok(D)) return launch_small(D, A, w.o, st);
     {
