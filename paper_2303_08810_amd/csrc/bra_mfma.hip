@@ -453,38 +453,56 @@ __global__ __launch_bounds__(256) void k_attn_big(AttnArgs A, Dims D)
 // through memory.  X tiles are staged once through LDS.  Wavefront w owns output
 // channels [w C/4, (w+1) C/4) of every projection (its weight slices stay in
 // registers) for ALL tokens of the workgroup; the projected tiles replace the X tiles
-// in LDS in place, then attention, LCE and W^o follow as in k_attn_big.
-template <int C>
+// in LDS in place, then attention and W^o follow as in k_attn_big.
+//
+// LCE (Eq. 7) also runs on the matrix cores.  The V halo of a wavefront's channels is
+// written channel-major (a plane of halo tokens per channel), and the 5x5 depth-wise
+// correlation of one channel becomes a chain of v_mfma_f32_4x4x4_16B_bf16 products:
+// block = channel, D[xi][yj] = out[y0 + yj][x0 + xi], and for every (ky, half-row hh)
+//   A[xi][k] = w[ky][4 hh + k - xi] (zero outside 0..4),  B[k][yj] = V[y0 + yj + ky][x0 + 4 hh + k]
+// (halo coordinates).  4x4x4 lane layout: block l / 4; A row, B / D column l % 4.
+template <int C, int RW>
 struct FusedSmem {
     static constexpr int CS = C + 8;
     static constexpr int OS = C + 4;
-    static constexpr int kMaxHaloTiles = 10;                          // 16-row tiles: rw = 8 or 16
+    static constexpr int QH = 64 / RW;                                // rows of the query tile
+    static constexpr int HW = RW + 4, HROWS = (QH + 4) * HW;          // halo tile
+    static constexpr int NHT = (HROWS + 15) / 16;                     // 16-token tiles of the halo
+    // halo plane pitch (bf16): an odd multiple of 4 32-bit words, so that the 8-byte writes
+    // of 16 planes x 2 token groups (half a wavefront) fall into 64 different banks
+    static constexpr int PS = 2 * ((NHT * 8 / 8) * 8 + 4);
+    static constexpr size_t xh_bytes = (size_t)NHT * 16 * CS * 2;     // X halo, row-major
+    static constexpr size_t vt_bytes = (size_t)C * PS * 2;            // V halo, channel-major
     static constexpr size_t k_off = 0;                                // routed X tile -> K tile
     static constexpr size_t v_off = k_off + (size_t)64 * CS * 2;      // Q tile -> V tile
-    static constexpr size_t w_off = v_off + (size_t)64 * CS * 2;      // LCE weights [25][C] f32
-    static constexpr size_t p_off = w_off + (size_t)25 * C * 4;       // routing partials
+    static constexpr size_t p_off = v_off + (size_t)64 * CS * 2;      // routing partials
     static constexpr size_t i_off = p_off + 256 * 4;                  // routed regions
-    static constexpr size_t h_off = i_off + kRpad * 4;                // X halo tile -> V halo tile
-    static size_t bytes(int halo_tiles) { return h_off + (size_t)halo_tiles * 16 * CS * 2; }
+    static constexpr size_t h_off = i_off + kRpad * 4;                // X halo -> V halo planes
+    static constexpr size_t bytes = h_off + (xh_bytes > vt_bytes ? xh_bytes : vt_bytes);
 };
 
-template <int C>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+__device__ __forceinline__ f32x4 mfma4(s16x4 a, s16x4 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, b, c, 0, 0, 0);
+}
+
+template <int C, int RW>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4)))
 void k_fused(AttnArgs A, Dims D)
 {
-    typedef FusedSmem<C> SM;
+    typedef FusedSmem<C, RW> SM;
     constexpr int CS = SM::CS, OS = SM::OS, HEADS = C / 32, KS = C / 32, CH = C / 8;
     constexpr int NT = C / 64;                  // 16-channel output tiles per wavefront and matrix
-    constexpr int NHT = SM::kMaxHaloTiles;
-    constexpr int NBH = (NHT * 16 * CH + 255) / 256;   // halo chunks per thread
+    constexpr int QH = SM::QH, HW = SM::HW, HROWS = SM::HROWS, NHT = SM::NHT, PS = SM::PS;
+    constexpr int NBH = (HROWS * CH + 255) / 256;      // halo chunks per thread
     constexpr int NBT = CH / 4;                 // chunks per thread of a 64-row tile
+    constexpr int NYB = QH / 4, NXB = RW / 4;   // 4x4 output blocks of the query tile
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)(smem + SM::k_off);   // first the routed X tile
     bf16_t *Vs = (bf16_t *)(smem + SM::v_off);   // first the Q tile
-    float *Wl = (float *)(smem + SM::w_off);
     float *part = (float *)(smem + SM::p_off);
     int *ir_s = (int *)(smem + SM::i_off);
-    bf16_t *Hs = (bf16_t *)(smem + SM::h_off);   // first the X halo tile
+    bf16_t *Hs = (bf16_t *)(smem + SM::h_off);   // first the X halo tile, then the V planes
     float *Os = (float *)(smem + SM::k_off);
 
     const int wid = swizzled_block();
@@ -492,18 +510,16 @@ void k_fused(AttnArgs A, Dims D)
 
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
-    const int qh = 64 / D.rw;                   // n == 64: one query tile per region
     const int b = wid / D.R, reg = wid % D.R;
-    const int y0 = (reg / D.S) * D.rh, x0 = (reg % D.S) * D.rw;
+    const int y0 = (reg / D.S) * D.rh, x0 = (reg % D.S) * RW;
     const size_t img_off = (size_t)b * D.N * C;
     const bf16_t *Ximg = A.X + img_off;
-    const int hw = D.rw + 4, hrows = (qh + 4) * hw, nht = (hrows + 15) / 16;
-    const float hw_inv = 1.0f / (float)hw, rw_inv = 1.0f / (float)D.rw;
+    const float hw_inv = 1.0f / (float)HW, rw_inv = 1.0f / (float)RW;
 
     // Requests that do not depend on the routing: X over the halo of the query tile
-    // (it contains the query tile), this wavefront's weight slices, the LCE weights.
+    // (it contains the query tile), this wavefront's weight slices, its LCE weights.
     u32x4 hreg[NBH];
-    tile_load<C, NBH>(hreg, Ximg, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, 0);
+    tile_load<C, NBH>(hreg, Ximg, y0 - 2, x0 - 2, HW, hw_inv, HROWS, D.H, D.W, 0);
     bf16x8 wq[NT][KS], wk[NT][KS], wv[NT][KS], wo[NT][KS];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -515,8 +531,22 @@ void k_fused(AttnArgs A, Dims D)
             wv[t][ks] = *(const bf16x8 *)(A.WT + (size_t)2 * C * C + row);
             wo[t][ks] = *(const bf16x8 *)(A.WoT + row);
         }
-    LceWeights<C> lw;
-    lw.load(A.Wlce);
+    // LCE weights as 4x4x4 A operands: lane = (channel block lb, output offset xi).
+    const int lb = lane / 4, xi = lane % 4;
+    s16x4 aw[NT][5][2];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const bf16_t *wl = A.Wlce + (16 * (wave * NT + t) + lb) * 25 - xi;
+#pragma unroll
+        for (int ky = 0; ky < 5; ++ky)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const bool ok = hh == 0 ? (k >= xi) : (k <= xi);   // 0 <= 4 hh + k - xi <= 4
+                    aw[t][ky][hh][k] = ok ? (short)wl[ky * 5 + 4 * hh + k] : (short)0;
+                }
+    }
 
     int j;
     if (A.Ir_src) {
@@ -528,20 +558,20 @@ void k_fused(AttnArgs A, Dims D)
         j = ir_s[0];
     }
     u32x4 kreg[NBT];
-    tile_load<C, NBT>(kreg, Ximg, (j / D.S) * D.rh, (j % D.S) * D.rw, D.rw, rw_inv, 64, D.H, D.W, 0);
-    tile_store<C, CS, NBH>(Hs, hreg, hrows, 0);
-    lw.store(Wl);
+    tile_load<C, NBT>(kreg, Ximg, (j / D.S) * D.rh, (j % D.S) * RW, RW, rw_inv, 64, D.H, D.W, 0);
+    tile_store<C, CS, NBH>(Hs, hreg, HROWS, 0);
     tile_store<C, CS, NBT>(Ks, kreg, 64, 0);
     __syncthreads();
 
-    // Projections of this wavefront's channel slice.  D^T[channel 16 tile + 4 g + jj][token i]:
-    // a lane ends up with 4 consecutive channels of one token (8 bytes of bf16).
+    // Projections of this wavefront's channel slice.  Q, K, V: D^T[channel 16 tile + 4 g + jj]
+    // [token i], a lane ends up with 4 consecutive channels of one token.  V halo: operands
+    // swapped, D[token 4 g + jj][channel i], 4 consecutive halo tokens of one channel.
     u32x2 vh[NHT][NT], kk[4][NT], vv[4][NT];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int q = 16 * u + i;
         const int qy = fast_div(q, rw_inv);
-        const bf16_t *xq = Hs + ((qy + 2) * hw + q - qy * D.rw + 2) * CS + 8 * g;   // query token in the halo
+        const bf16_t *xq = Hs + ((qy + 2) * HW + q - qy * RW + 2) * CS + 8 * g;   // query token in the halo
         const bf16_t *xk = Ks + q * CS + 8 * g;
         bf16x8 bq[KS], bk[KS];
 #pragma unroll
@@ -565,18 +595,16 @@ void k_fused(AttnArgs A, Dims D)
     }
 #pragma unroll
     for (int hu = 0; hu < NHT; ++hu) {
-        if (hu < nht) {
-            const bf16_t *xh = Hs + (16 * hu + i) * CS + 8 * g;
-            bf16x8 bh[KS];
+        const bf16_t *xh = Hs + (16 * hu + i) * CS + 8 * g;
+        bf16x8 bh[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) bh[ks] = *(const bf16x8 *)(xh + 32 * ks);
+        for (int ks = 0; ks < KS; ++ks) bh[ks] = *(const bf16x8 *)(xh + 32 * ks);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                f32x4 a = {0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < NT; ++t) {
+            f32x4 a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) a = mfma16(wv[t][ks], bh[ks], a);
-                vh[hu][t] = pack4(a);
-            }
+            for (int ks = 0; ks < KS; ++ks) a = mfma16(bh[ks], wv[t][ks], a);
+            vh[hu][t] = pack4(a);
         }
     }
     __syncthreads();   // every X tile has been read; the Q tile is complete
@@ -585,11 +613,9 @@ void k_fused(AttnArgs A, Dims D)
     for (int h = 0; h < HEADS; ++h) qf[h] = *(const bf16x8 *)(Vs + (16 * wave + i) * CS + 32 * h + 8 * g);
 #pragma unroll
     for (int hu = 0; hu < NHT; ++hu)
-        if (hu < nht) {
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                *(u32x2 *)(Hs + (16 * hu + i) * CS + 16 * (wave * NT + t) + 4 * g) = vh[hu][t];
-        }
+        for (int t = 0; t < NT; ++t)   // plane of channel 16 (w NT + t) + i, halo tokens 16 hu + 4 g ..
+            *(u32x2 *)(Hs + (16 * (wave * NT + t) + i) * PS + 16 * hu + 4 * g) = vh[hu][t];
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -606,10 +632,43 @@ void k_fused(AttnArgs A, Dims D)
     SoftmaxState<HEADS> st;
     st.init();
     attn_key_block<C, CS>(Ks, Vs, qf, st, A.c_exp, g, i);
+
+    // LCE of this wavefront's channels from its own halo planes (no workgroup sync needed
+    // for them): lane = (channel block lb, output row offset yj = xi index of the lane).
+    f32x4 lce[NT][NYB][NXB];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const bf16_t *plane = Hs + (16 * (wave * NT + t) + lb) * PS;
+#pragma unroll
+        for (int yb = 0; yb < NYB; ++yb) {
+#pragma unroll
+            for (int xb = 0; xb < NXB; ++xb) lce[t][yb][xb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ky = 0; ky < 5; ++ky) {
+                const bf16_t *row = plane + (4 * yb + xi + ky) * HW;   // halo row of output row 4 yb + yj
+                s16x4 br[NXB + 1];
+#pragma unroll
+                for (int xb = 0; xb <= NXB; ++xb) br[xb] = *(const s16x4 *)(row + 4 * xb);
+#pragma unroll
+                for (int xb = 0; xb < NXB; ++xb) {
+                    lce[t][yb][xb] = mfma4(aw[t][ky][0], br[xb], lce[t][yb][xb]);
+                    lce[t][yb][xb] = mfma4(aw[t][ky][1], br[xb + 1], lce[t][yb][xb]);
+                }
+            }
+        }
+    }
     __syncthreads();
     attn_write_out<C, OS>(Os, st, wave, g, i);
     __syncthreads();
-    lce_add_valu<C, CS, OS>(Hs, Wl, Os, qh, D.rw, hw);
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int yb = 0; yb < NYB; ++yb)
+#pragma unroll
+            for (int xb = 0; xb < NXB; ++xb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)   // out[row 4 yb + yj][col 4 xb + e] of channel block lb
+                    Os[((4 * yb + xi) * RW + 4 * xb + e) * OS + 16 * (wave * NT + t) + lb] += lce[t][yb][xb][e];
     __syncthreads();
 
     // Y^T slice = Wo^T slice * O^T: this wavefront's 16 NT output channels of all 64 tokens.
@@ -625,7 +684,7 @@ void k_fused(AttnArgs A, Dims D)
             of[ks] = pack8(v);
         }
         const int qy = fast_div(q, rw_inv);
-        bf16_t *yrow = A.Y + img_off + ((size_t)(y0 + qy) * D.W + x0 + q - qy * D.rw) * C;
+        bf16_t *yrow = A.Y + img_off + ((size_t)(y0 + qy) * D.W + x0 + q - qy * RW) * C;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             f32x4 ya = {0.f, 0.f, 0.f, 0.f};
@@ -659,8 +718,7 @@ bool fused_ok(const Dims &D)
     static const bool disabled = getenv("BRA_DISABLE_FUSED") != nullptr;   // benchmarking aid
     if (disabled || !fast_route_ok(D)) return false;
     if (D.C != 64 && D.C != 128) return false;
-    if (D.n != 64 || D.k != 1 || (D.rw != 8 && D.rw != 16)) return false;
-    return (halo_rows(D) + 15) / 16 <= FusedSmem<64>::kMaxHaloTiles;
+    return D.n == 64 && D.k == 1 && (D.rw == 8 || D.rw == 16);
 }
 
 MfmaWs carve(const Dims &D, void *ws)
@@ -757,11 +815,17 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
 
     if constexpr (C <= 128) {
         if (fused_ok(D)) {
-            static bool opted = false;
-            if (!lds_opt_in(k_fused<C>, opted)) return BRA_ERR_LAUNCH;
-            const size_t smem = FusedSmem<C>::bytes((hrows + 15) / 16);
+            static bool opted8 = false, opted16 = false;
             ProfScope ps(st, K_MFMA_FUSED_K1);
-            hipLaunchKernelGGL(k_fused<C>, dim3(grid), dim3(256), smem, st, A, D);
+            if (D.rw == 8) {
+                if (!lds_opt_in(k_fused<C, 8>, opted8)) return BRA_ERR_LAUNCH;
+                const size_t smem = FusedSmem<C, 8>::bytes;
+                hipLaunchKernelGGL((k_fused<C, 8>), dim3(grid), dim3(256), smem, st, A, D);
+            } else {
+                if (!lds_opt_in(k_fused<C, 16>, opted16)) return BRA_ERR_LAUNCH;
+                const size_t smem = FusedSmem<C, 16>::bytes;
+                hipLaunchKernelGGL((k_fused<C, 16>), dim3(grid), dim3(256), smem, st, A, D);
+            }
             return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
         }
     }
