@@ -25,6 +25,23 @@ METRIC = "BRA fwd images/sec per stage shape + achieved TFLOP/s and HBM GB/s"
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 VALU_F32_PEAK_TFLOPS = 157.3
+CALIBRATION_BYTES = 64 << 20
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` on `workload` from the committed rocprofv3 counter
+    summary (profiles/hbm_traffic.txt, written by paper_2303_08810_amd/traffic_summary.py),
+    or None if there is no entry."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for ln in f:
+                parts = ln.split()
+                if len(parts) >= 4 and parts[0] == "traffic" and parts[1] == workload and parts[2] == kernel:
+                    return int(float(parts[3]))
+    except OSError:
+        pass
+    return None
 
 
 def flops_per_image(cfg):
@@ -186,6 +203,9 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="named workload index 1..5 (default 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other named workloads")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run the plain copy kernel (64 MiB, 10 times): the reference against "
+                         "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (images are independent; data "
@@ -195,6 +215,7 @@ def main():
 
     import torch
 
+    import paper_2303_08810_amd as bra
     from synthetic_inputs import CONFIGS
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -204,6 +225,8 @@ def main():
     ms = res["ms_per_step"]
     value = cfg.B / (ms / 1e3)
     roof, summary = roofline_of(cfg, res["kernels"])
+    if roof:
+        roof["traffic"] = measured_traffic(roof["kernel"], cfg.name)
     eb = 2 if cfg.dtype == "bf16" else 4
     line = {
         "metric": METRIC, "value": round(value, 1), "unit": "images/s", "n_gpus": 1,
@@ -235,6 +258,12 @@ def main():
                 "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in sm.items()},
             }
         line["other_workloads"] = others
+    if args.calibrate:
+        src = torch.empty(CALIBRATION_BYTES, dtype=torch.uint8, device="cuda").random_()
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            bra.util_copy(dst, src)
+        torch.cuda.synchronize()
     print(json.dumps(line))
 
 
