@@ -244,18 +244,50 @@ __global__ __launch_bounds__(256) void k_pool_qk_mfma(const bf16_t *__restrict__
     }
 }
 
-// bra_route: one workgroup per (b, region) writes its row of Ir (and of Ar).
+// A^r = Q^r (K^r)^T (Eq. 4) and its row-wise top-k index I^r (Eq. 5) for every region of
+// every image.  A wavefront computes kRouteRows rows: lane j holds entry j of each row, a
+// column of K^r^T is loaded once per lane and used for all its rows, the Q^r values are
+// the same for all lanes (scalar loads).  No LDS, no barriers.
+constexpr int kRouteRows = 2;
+
 template <int C>
-__global__ __launch_bounds__(256) void k_route_rows(const float *__restrict__ Qr,
-                                                    const float *__restrict__ KrT,
-                                                    int32_t *__restrict__ Ir, float *__restrict__ Ar,
-                                                    Dims D)
+__global__ __launch_bounds__(256) void k_route(const float *__restrict__ Qr,
+                                               const float *__restrict__ KrT,
+                                               int32_t *__restrict__ Ir, float *__restrict__ Ar,
+                                               Dims D)
 {
-    __shared__ float part[256];
-    __shared__ int ir_s[kRpad];
-    const int b = blockIdx.x / D.R, reg = blockIdx.x % D.R;
-    route_row<C>(Qr, KrT, b, reg, D.R, D.k, part, ir_s, Ir + ((size_t)b * D.R + reg) * D.k,
-                 Ar ? Ar + ((size_t)b * D.R + reg) * D.R : nullptr);
+    constexpr int NR = kRouteRows, NB = 32;     // NB: channels per batch of loads
+    const int groups = (D.R + 4 * NR - 1) / (4 * NR);
+    const int b = blockIdx.x / groups;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), j = threadIdx.x % kWave;
+    const int r0 = ((blockIdx.x % groups) * 4 + wave) * NR;
+    if (r0 >= D.R) return;
+    const float *kt = KrT + (size_t)b * C * kRpad + j;
+    const float *q[NR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        const int row = r0 + r < D.R ? r0 + r : D.R - 1;     // rows past R repeat the last one; not written
+        q[r] = Qr + ((size_t)b * D.R + row) * C;
+    }
+    float a[NR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) a[r] = 0.f;
+    for (int c0 = 0; c0 < C; c0 += NB) {
+        float kv[NB];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) kv[c] = kt[(size_t)(c0 + c) * kRpad];
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int c = 0; c < NB; ++c) a[r] = fmaf(q[r][c0 + c], kv[c], a[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        if (r0 + r >= D.R) break;
+        const size_t row = (size_t)b * D.R + r0 + r;
+        if (Ar && j < D.R) Ar[row * D.R + j] = a[r];
+        wave_topk(a[r], j, D.R, D.k, Ir + row * D.k);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -340,9 +372,7 @@ struct AttnSmem {
     static constexpr size_t k_off = 0;                                // K tile; output tile later
     static constexpr size_t v_off = k_off + (size_t)64 * CS * 2;      // V tile (fused: Q tile first)
     static constexpr size_t w_off = v_off + (size_t)64 * CS * 2;      // LCE weights [25][C] f32
-    static constexpr size_t p_off = w_off + (size_t)25 * C * 4;       // routing partials
-    static constexpr size_t i_off = p_off + 256 * 4;                  // routed regions
-    static constexpr size_t h_off = i_off + kRpad * 4;                // V halo tile
+    static constexpr size_t h_off = w_off + (size_t)25 * C * 4;       // V halo tile
     static size_t bytes(int halo_rows) { return h_off + (size_t)halo_rows * CS * 2; }
 };
 
@@ -363,8 +393,6 @@ __global__ __launch_bounds__(256) void k_attn_big(AttnArgs A, Dims D)
     bf16_t *Ks = (bf16_t *)(smem + SM::k_off);
     bf16_t *Vs = (bf16_t *)(smem + SM::v_off);
     float *Wl = (float *)(smem + SM::w_off);
-    float *part = (float *)(smem + SM::p_off);
-    int *ir_s = (int *)(smem + SM::i_off);
     bf16_t *Hs = (bf16_t *)(smem + SM::h_off);
     float *Os = (float *)(smem + SM::k_off);   // reuses the K/V tiles after the key loop
 
@@ -403,17 +431,10 @@ __global__ __launch_bounds__(256) void k_attn_big(AttnArgs A, Dims D)
             for (int ks = 0; ks < KS; ++ks) wof[tt][ks] = wo_fragment<C>(A.WoT, 0, tt, ks, g, i);
     }
 
-    // Routing row of this region (or the caller's / the fallback kernels' index).
-    const int32_t *irp;
-    if (A.Ir_src) {
-        irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
-        if (A.Ir_out && A.Ir_out != A.Ir_src && ch == 0)
-            for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
-    } else {
-        route_row<C>(A.Qr, A.KrT, b, reg, D.R, D.k, part, ir_s,
-                     (A.Ir_out && ch == 0) ? A.Ir_out + ((size_t)b * D.R + reg) * D.k : nullptr, nullptr);
-        irp = ir_s;
-    }
+    // Routing row of this region.
+    const int32_t *irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
+    if (A.Ir_out && A.Ir_out != A.Ir_src && ch == 0)
+        for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
 
     tile_store<C, CS, NBH>(Hs, hreg, hrows, 0);
     for (int first = 256 * NBH; first < hrows * CH; first += 256 * NBH) {
@@ -475,9 +496,7 @@ struct FusedSmem {
     static constexpr size_t vt_bytes = (size_t)C * PS * 2;            // V halo, channel-major
     static constexpr size_t k_off = 0;                                // routed X tile -> K tile
     static constexpr size_t v_off = k_off + (size_t)64 * CS * 2;      // Q tile -> V tile
-    static constexpr size_t p_off = v_off + (size_t)64 * CS * 2;      // routing partials
-    static constexpr size_t i_off = p_off + 256 * 4;                  // routed regions
-    static constexpr size_t h_off = i_off + kRpad * 4;                // X halo -> V halo planes
+    static constexpr size_t h_off = v_off + (size_t)64 * CS * 2;      // X halo -> V halo planes
     static constexpr size_t bytes = h_off + (xh_bytes > vt_bytes ? xh_bytes : vt_bytes);
 };
 
@@ -500,8 +519,6 @@ void k_fused(AttnArgs A, Dims D)
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)(smem + SM::k_off);   // first the routed X tile
     bf16_t *Vs = (bf16_t *)(smem + SM::v_off);   // first the Q tile
-    float *part = (float *)(smem + SM::p_off);
-    int *ir_s = (int *)(smem + SM::i_off);
     bf16_t *Hs = (bf16_t *)(smem + SM::h_off);   // first the X halo tile, then the V planes
     float *Os = (float *)(smem + SM::k_off);
 
@@ -548,15 +565,8 @@ void k_fused(AttnArgs A, Dims D)
                 }
     }
 
-    int j;
-    if (A.Ir_src) {
-        j = A.Ir_src[(size_t)b * D.R + reg];
-        if (A.Ir_out && A.Ir_out != A.Ir_src && threadIdx.x == 0) A.Ir_out[(size_t)b * D.R + reg] = j;
-    } else {
-        route_row<C>(A.Qr, A.KrT, b, reg, D.R, 1, part, ir_s,
-                     A.Ir_out ? A.Ir_out + (size_t)b * D.R + reg : nullptr, nullptr);
-        j = ir_s[0];
-    }
+    const int j = A.Ir_src[(size_t)b * D.R + reg];
+    if (A.Ir_out && A.Ir_out != A.Ir_src && threadIdx.x == 0) A.Ir_out[(size_t)b * D.R + reg] = j;
     u32x4 kreg[NBT];
     tile_load<C, NBT>(kreg, Ximg, (j / D.S) * D.rh, (j % D.S) * RW, RW, rw_inv, 64, D.H, D.W, 0);
     tile_store<C, CS, NBH>(Hs, hreg, HROWS, 0);
@@ -772,6 +782,14 @@ void launch_pool_qk(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf
                        w.qr, w.krt, w.wt, w.wot, D, pool_blocks, G);
 }
 
+template <int C>
+void launch_route(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, hipStream_t st)
+{
+    ProfScope ps(st, K_MFMA_ROUTE_ROWS);
+    const int groups = (D.R + 4 * kRouteRows - 1) / (4 * kRouteRows);
+    hipLaunchKernelGGL(k_route<C>, dim3(D.B * groups), dim3(256), 0, st, w.qr, w.krt, Ir, Ar_opt, D);
+}
+
 // More than 64 KB of dynamic LDS needs an opt-in, once per kernel.
 template <typename K>
 bool lds_opt_in(K kernel, bool &done)
@@ -794,6 +812,11 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     const int32_t *Ir_src = Ir_in_opt;
     if (fast_route_ok(D)) {
         launch_pool_qk<C>(D, X, Wqkv, Wo, w, /*pool=*/!Ir_in_opt, /*prep=*/true, st);
+        if (!Ir_in_opt) {
+            int32_t *dst = Ir_out_opt ? Ir_out_opt : w.ir;
+            launch_route<C>(D, w, dst, nullptr, st);
+            Ir_src = dst;
+        }
     } else {
         if (!Ir_in_opt) {
             int32_t *dst = Ir_out_opt ? Ir_out_opt : w.ir;
@@ -806,7 +829,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
                            w.wt, w.wot, C, 4 * C * C);
     }
     AttnArgs A;
-    A.X = X; A.WT = w.wt; A.Q = w.q; A.K = w.k; A.V = w.v; A.Qr = w.qr; A.KrT = w.krt;
+    A.X = X; A.WT = w.wt; A.Q = w.q; A.K = w.k; A.V = w.v;
     A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = Wlce; A.WoT = w.wot; A.Y = Y;
     A.c_exp = D.scale * 1.4426950408889634f;
     A.total = D.B * D.R * (D.n / 64);
@@ -859,8 +882,7 @@ int route_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, int32_t *Ir, flo
             const MfmaWs &w, hipStream_t st)
 {
     launch_pool_qk<C>(D, X, Wqkv, nullptr, w, /*pool=*/true, /*prep=*/false, st);
-    ProfScope ps(st, K_MFMA_ROUTE_ROWS);
-    hipLaunchKernelGGL(k_route_rows<C>, dim3(D.B * D.R), dim3(256), 0, st, w.qr, w.krt, Ir, Ar_opt, D);
+    launch_route<C>(D, w, Ir, Ar_opt, st);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 

@@ -70,47 +70,28 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const bf16_t *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)p);
 }
 
-// Row `reg` of A^r = Q^r (K^r)^T (Eq. 4) and the indices of its k largest entries
-// (Eq. 5): larger value first, equal values by smaller index, NaN as -inf.  Called by
-// all 256 threads of a workgroup; R <= 64.  part: 256 floats of LDS; the result is
-// left in ir_s[0..k) (LDS) and, if the pointers are set, written to memory as well.
-template <int C>
-__device__ __forceinline__ void route_row(const float *__restrict__ Qr,
-                                          const float *__restrict__ KrT, int b, int reg, int R,
-                                          int k, float *part, int *ir_s, int32_t *Ir_row_out,
-                                          float *Ar_row_out)
+// Indices of the k largest entries of one row of A^r (Eq. 5), the row spread over the
+// 64 lanes of a wavefront (lane j holds entry j; entries j >= R do not exist): larger
+// value first, equal values by smaller index, NaN as -inf.  Each lane forms a 64-bit key
+// (value mapped to an unsigned integer of the same order, then 63 - j) that is larger for
+// whatever comes first; a lane's position in the order is the number of larger keys,
+// counted with one lane broadcast per other lane.  The lane at position p < k writes its
+// index to out[p].
+__device__ __forceinline__ void wave_topk(float v, int j, int R, int k, int32_t *out)
 {
-    const int tid = threadIdx.x, j = tid % kWave, cq = tid / kWave;
-    const float *q = Qr + ((size_t)b * R + reg) * C + cq * (C / 4);
-    const float *kt = KrT + ((size_t)b * C + cq * (C / 4)) * kRpad + j;
-    float a = 0.f;
+    if (!(v == v) || j >= R) v = -INFINITY;
+    v += 0.0f;                                              // -0 and +0 are equal values
+    uint32_t u = __builtin_bit_cast(uint32_t, v);
+    u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;
+    const uint64_t key = ((uint64_t)u << 32) | (uint32_t)(kWave - 1 - j);
+    int before = 0;
 #pragma unroll
-    for (int c = 0; c < C / 4; ++c) a = fmaf(q[c], kt[(size_t)c * kRpad], a);
-    part[cq * kWave + j] = a;
-    __syncthreads();
-    if (tid < kWave) {
-        float v = ((part[j] + part[kWave + j]) + part[2 * kWave + j]) + part[3 * kWave + j];
-        if (Ar_row_out && j < R) Ar_row_out[j] = v;
-        if (!(v == v)) v = -INFINITY;
-        bool avail = j < R;
-        for (int p = 0; p < k; ++p) {
-            float bv = avail ? v : -INFINITY;
-            int bi = avail ? j : 0x7fffffff;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const float ov = __shfl_xor(bv, off, kWave);
-                const int oi = __shfl_xor(bi, off, kWave);
-                const bool take = (oi != 0x7fffffff) && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
-                if (take) { bv = ov; bi = oi; }
-            }
-            if (bi == j) avail = false;
-            if (j == 0) {
-                ir_s[p] = bi;
-                if (Ir_row_out) Ir_row_out[p] = bi;
-            }
-        }
+    for (int o = 0; o < kWave; ++o) {
+        const uint32_t uo = (uint32_t)__builtin_amdgcn_readlane((int)u, o);
+        const uint64_t ko = ((uint64_t)uo << 32) | (uint32_t)(kWave - 1 - o);
+        before += ko > key ? 1 : 0;
     }
-    __syncthreads();
+    if (j < R && before < k) out[before] = j;
 }
 
 // Global -> register half of a tile copy: chunk idx (16 bytes) is row idx / (C/8) of
@@ -372,7 +353,6 @@ struct AttnArgs {
     const bf16_t *X;                // input map [B, H, W, C] (fused kernel)
     const bf16_t *WT;               // [3C][C] transposed projection weights (fused kernel)
     const bf16_t *Q, *K, *V;        // projected maps [B, H, W, C] (staged kernel)
-    const float *Qr, *KrT;          // region queries [B, R, C], region keys [B, C, 64]
     const int32_t *Ir_src;          // routing index in memory, or NULL: route in the kernel
     int32_t *Ir_out;                // where to report the routing index, or NULL
     const bf16_t *Wlce, *WoT;

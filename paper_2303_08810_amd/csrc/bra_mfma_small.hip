@@ -27,8 +27,6 @@ __global__ __launch_bounds__(256) void k_attn_small(AttnArgs A, bf16_t *__restri
 {
     constexpr int HEADS = C / 32;
     __shared__ __attribute__((aligned(16))) bf16_t Vw[4][64 * kVS];
-    __shared__ float part[256];
-    __shared__ int ir_s[kRpad];
 
     const int wid = swizzled_block();
     if (wid >= A.total) return;
@@ -39,16 +37,9 @@ __global__ __launch_bounds__(256) void k_attn_small(AttnArgs A, bf16_t *__restri
     const int n = D.n, kn = D.kn;
     const float rw_inv = 1.0f / (float)D.rw;
 
-    const int32_t *irp;
-    if (A.Ir_src) {
-        irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
-        if (A.Ir_out && A.Ir_out != A.Ir_src)
-            for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
-    } else {
-        route_row<C>(A.Qr, A.KrT, b, reg, D.R, D.k, part, ir_s,
-                     A.Ir_out ? A.Ir_out + ((size_t)b * D.R + reg) * D.k : nullptr, nullptr);
-        irp = ir_s;
-    }
+    const int32_t *irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
+    if (A.Ir_out && A.Ir_out != A.Ir_src)
+        for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
 
     // query token of this lane's column (columns >= n repeat the last query; never stored)
     const int qs = i < n ? i : n - 1;
