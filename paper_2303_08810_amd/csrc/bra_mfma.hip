@@ -28,21 +28,40 @@ namespace {
 // ---------------------------------------------------------------------------
 // WT[o][c] = Wqkv[c][o] (o < 3C) and WoT[o][c] = Wo[c][o]: the weights with the
 // contraction axis contiguous, as the MFMA operands want them.  `e` runs over 4 C^2.
+// Elements 4 C^2 .. 4 C^2 + 160 C are the LCE weights (Eq. 7) laid out as the A operands
+// of the 4x4x4 matrix products of the fused kernel: for the 16-channel slice s, the
+// kernel row ky and the half hh of the 8-wide input window, lane 4 lb + xi holds
+//   Wa[s][2 ky + hh][lane][k] = w[16 s + lb][ky][4 hh + k - xi]   (zero outside 0..4),
+// so that one 8-byte load per lane fetches an operand and a wavefront reads 512
+// contiguous bytes.
+constexpr int kLceOperandElems = 160;   // per channel: 5 rows x 2 halves x 4 offsets x 4
+
 __device__ inline void prep_weight_element(const bf16_t *__restrict__ Wqkv,
-                                           const bf16_t *__restrict__ Wo, bf16_t *__restrict__ WT,
-                                           bf16_t *__restrict__ WoT, int C, int e)
+                                           const bf16_t *__restrict__ Wo,
+                                           const bf16_t *__restrict__ Wlce, bf16_t *__restrict__ WT,
+                                           bf16_t *__restrict__ WoT, bf16_t *__restrict__ Wa, int C, int e)
 {
+    if (e >= 4 * C * C) {
+        const int a = e - 4 * C * C;
+        const int k = a % 4, lane = (a / 4) % kWave, r = (a / (4 * kWave)) % 10, s = a / (40 * kWave);
+        const int lb = lane / 4, xi = lane % 4, ky = r / 2, hh = r % 2;
+        const int kx = 4 * hh + k - xi;
+        Wa[a] = (kx >= 0 && kx <= 4) ? Wlce[(16 * s + lb) * 25 + ky * 5 + kx] : (bf16_t)0;
+        return;
+    }
     const int o = e / C, c = e % C;
     if (o < 3 * C) WT[e] = Wqkv[(size_t)c * 3 * C + o];
     else WoT[(size_t)(o - 3 * C) * C + c] = Wo[(size_t)c * C + (o - 3 * C)];
 }
 
-// `total` = 4 C^2 (all weights) or 3 C^2 (projection weights only, Wo may be NULL).
+// `total` = 4 C^2 + 160 C (all weights) or 3 C^2 (projection weights only; Wo and Wlce
+// may be NULL).
 __global__ void k_prep_weights(const bf16_t *__restrict__ Wqkv, const bf16_t *__restrict__ Wo,
-                               bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT, int C, int total)
+                               const bf16_t *__restrict__ Wlce, bf16_t *__restrict__ WT,
+                               bf16_t *__restrict__ WoT, bf16_t *__restrict__ Wa, int C, int total)
 {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e < total) prep_weight_element(Wqkv, Wo, WT, WoT, C, e);
+    if (e < total) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, C, e);
 }
 
 // ---------------------------------------------------------------------------
@@ -56,9 +75,10 @@ template <int C>
 __global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
                                                  const bf16_t *__restrict__ Wqkv,
                                                  const bf16_t *__restrict__ Wo,
+                                                 const bf16_t *__restrict__ Wlce,
                                                  float *__restrict__ Qr, float *__restrict__ KrT,
                                                  bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT,
-                                                 Dims D, int pool_blocks, int G)
+                                                 bf16_t *__restrict__ Wa, Dims D, int pool_blocks, int G)
 {
     constexpr int MAXG = kPoolMaxGroup;
     __shared__ float part[4096];   // pooling partials, then projection partials
@@ -66,7 +86,7 @@ __global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
     const int tid = threadIdx.x;
     if ((int)blockIdx.x >= pool_blocks) {
         const int e = ((int)blockIdx.x - pool_blocks) * 256 + tid;
-        if (e < 4 * C * C) prep_weight_element(Wqkv, Wo, WT, WoT, C, e);
+        if (e < 4 * C * C + kLceOperandElems * C) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, C, e);
         return;
     }
     constexpr int CH = C / 8;
@@ -552,18 +572,10 @@ void k_fused(AttnArgs A, Dims D)
     const int lb = lane / 4, xi = lane % 4;
     s16x4 aw[NT][5][2];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const bf16_t *wl = A.Wlce + (16 * (wave * NT + t) + lb) * 25 - xi;
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int ky = 0; ky < 5; ++ky)
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const bool ok = hh == 0 ? (k >= xi) : (k <= xi);   // 0 <= 4 hh + k - xi <= 4
-                    aw[t][ky][hh][k] = ok ? (short)wl[ky * 5 + 4 * hh + k] : (short)0;
-                }
-    }
+        for (int r = 0; r < 10; ++r)
+            aw[t][r / 2][r % 2] = *(const s16x4 *)(A.Wa + ((size_t)((wave * NT + t) * 10 + r) * kWave + lane) * 4);
 
     const int j = A.Ir_src[(size_t)b * D.R + reg];
     if (A.Ir_out && A.Ir_out != A.Ir_src && threadIdx.x == 0) A.Ir_out[(size_t)b * D.R + reg] = j;
@@ -707,7 +719,7 @@ void k_fused(AttnArgs A, Dims D)
 
 // ---------------------------------------------------------------------------
 struct MfmaWs {
-    bf16_t *q, *k, *v, *o, *wt, *wot;
+    bf16_t *q, *k, *v, *o, *wt, *wot, *wa;
     float *qr, *krt;
     void *route;
     int32_t *ir;
@@ -744,6 +756,7 @@ MfmaWs carve(const Dims &D, void *ws)
     w.o = (bf16_t *)take(small_supported(D) ? tok * D.C * 2 : 0);
     w.wt = (bf16_t *)take((size_t)3 * D.C * D.C * 2);
     w.wot = (bf16_t *)take((size_t)D.C * D.C * 2);
+    w.wa = (bf16_t *)take((size_t)D.C * kLceOperandElems * 2);
     w.qr = (float *)take((size_t)D.B * D.R * D.C * sizeof(float));
     w.krt = (float *)take((size_t)D.B * D.C * kRpad * sizeof(float));
     w.route = take(fast_route_ok(D) ? 0 : valu_route_scratch_bytes(D));
@@ -754,16 +767,16 @@ MfmaWs carve(const Dims &D, void *ws)
 
 template <int C>
 void launch_pool_qk(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *Wo,
-                    const MfmaWs &w, bool pool, bool prep, hipStream_t st)
+                    const bf16_t *Wlce, const MfmaWs &w, bool pool, bool prep, hipStream_t st)
 {
     if constexpr (C >= 128) {
         // wide channels: transpose the weights first, then pool + project on the matrix cores
         // (pool && !prep happens in bra_route: only WT's Wq|Wk rows are needed, Wo may be NULL)
         {
             ProfScope ps(st, K_MFMA_PREP);
-            const int total = (prep ? 4 : 3) * C * C;
-            hipLaunchKernelGGL(k_prep_weights, dim3((total + 255) / 256), dim3(256), 0, st, Wqkv, Wo, w.wt,
-                               w.wot, C, total);
+            const int total = prep ? 4 * C * C + kLceOperandElems * C : 3 * C * C;
+            hipLaunchKernelGGL(k_prep_weights, dim3((total + 255) / 256), dim3(256), 0, st, Wqkv, Wo, Wlce,
+                               w.wt, w.wot, w.wa, C, total);
         }
         if (pool) {
             ProfScope ps(st, K_MFMA_POOL_QK);
@@ -775,11 +788,11 @@ void launch_pool_qk(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf
     int G = 4;                                                     // regions per workgroup
     if (const char *e = getenv("BRA_POOL_GROUP")) { int v = atoi(e); if (v >= 1 && v <= kPoolMaxGroup) G = v; }
     const int pool_blocks = pool ? D.B * ((D.R + G - 1) / G) : 0;
-    const int prep_blocks = prep ? (4 * C * C + 255) / 256 : 0;
+    const int prep_blocks = prep ? (4 * C * C + kLceOperandElems * C + 255) / 256 : 0;
     if (pool_blocks + prep_blocks == 0) return;
     ProfScope ps(st, K_MFMA_POOL_QK);
     hipLaunchKernelGGL(k_pool_qk<C>, dim3(pool_blocks + prep_blocks), dim3(256), 0, st, X, Wqkv, Wo,
-                       w.qr, w.krt, w.wt, w.wot, D, pool_blocks, G);
+                       Wlce, w.qr, w.krt, w.wt, w.wot, w.wa, D, pool_blocks, G);
 }
 
 template <int C>
@@ -811,7 +824,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
 {
     const int32_t *Ir_src = Ir_in_opt;
     if (fast_route_ok(D)) {
-        launch_pool_qk<C>(D, X, Wqkv, Wo, w, /*pool=*/!Ir_in_opt, /*prep=*/true, st);
+        launch_pool_qk<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/!Ir_in_opt, /*prep=*/true, st);
         if (!Ir_in_opt) {
             int32_t *dst = Ir_out_opt ? Ir_out_opt : w.ir;
             launch_route<C>(D, w, dst, nullptr, st);
@@ -825,12 +838,13 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
             Ir_src = dst;
         }
         ProfScope ps(st, K_MFMA_PREP);
-        hipLaunchKernelGGL(k_prep_weights, dim3((4 * C * C + 255) / 256), dim3(256), 0, st, Wqkv, Wo,
-                           w.wt, w.wot, C, 4 * C * C);
+        const int total = 4 * C * C + kLceOperandElems * C;
+        hipLaunchKernelGGL(k_prep_weights, dim3((total + 255) / 256), dim3(256), 0, st, Wqkv, Wo, Wlce,
+                           w.wt, w.wot, w.wa, C, total);
     }
     AttnArgs A;
     A.X = X; A.WT = w.wt; A.Q = w.q; A.K = w.k; A.V = w.v;
-    A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = Wlce; A.WoT = w.wot; A.Y = Y;
+    A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = Wlce; A.Wa = w.wa; A.WoT = w.wot; A.Y = Y;
     A.c_exp = D.scale * 1.4426950408889634f;
     A.total = D.B * D.R * (D.n / 64);
     const int grid = ((A.total + 7) / 8) * 8;
@@ -881,7 +895,7 @@ template <int C>
 int route_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, int32_t *Ir, float *Ar_opt,
             const MfmaWs &w, hipStream_t st)
 {
-    launch_pool_qk<C>(D, X, Wqkv, nullptr, w, /*pool=*/true, /*prep=*/false, st);
+    launch_pool_qk<C>(D, X, Wqkv, nullptr, nullptr, w, /*pool=*/true, /*prep=*/false, st);
     launch_route<C>(D, w, Ir, Ar_opt, st);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }

@@ -356,6 +356,7 @@ struct AttnArgs {
     const int32_t *Ir_src;          // routing index in memory, or NULL: route in the kernel
     int32_t *Ir_out;                // where to report the routing index, or NULL
     const bf16_t *Wlce, *WoT;
+    const bf16_t *Wa;               // LCE weights as 4x4x4 A operands (fused kernel)
     bf16_t *Y;
     float c_exp;                    // softmax scale * log2(e)
     int total;                      // workgroups that have work
