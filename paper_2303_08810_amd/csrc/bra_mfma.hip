@@ -36,11 +36,34 @@ namespace {
 // contiguous bytes.
 constexpr int kLceOperandElems = 160;   // per channel: 5 rows x 2 halves x 4 offsets x 4
 
+// For C = 64 the fused kernel reads all projection weights as ready-made MFMA fragments:
+// 16 "row tiles" x 2 contraction steps x 64 lanes x 8 elements, lane 16 g + i.
+//   row tiles 0..11 ([Wq | Wk | Wv]^T):  Wf = WT[16 rt + i][32 ks + 8 g + s]
+//   row tiles 12..15 (Wo^T, tile tt):    row i is output channel 16 (i / 4) + 4 tt + i % 4,
+//       slot s of lane group g is input channel 32 ks + 16 (s / 4) + 4 g + s % 4
+// (the order in which the fused kernel holds O^T, and the order that gives every lane 16
+// consecutive output channels).
+constexpr int kFusedFragElems = 16 * 2 * 64 * 8;
+
 __device__ inline void prep_weight_element(const bf16_t *__restrict__ Wqkv,
                                            const bf16_t *__restrict__ Wo,
                                            const bf16_t *__restrict__ Wlce, bf16_t *__restrict__ WT,
-                                           bf16_t *__restrict__ WoT, bf16_t *__restrict__ Wa, int C, int e)
+                                           bf16_t *__restrict__ WoT, bf16_t *__restrict__ Wa,
+                                           bf16_t *__restrict__ Wf, int C, int e)
 {
+    if (e >= 4 * C * C + kLceOperandElems * C) {       // only when C == 64
+        const int f = e - (4 * C * C + kLceOperandElems * C);
+        const int s = f % 8, lane = (f / 8) % kWave, ks = (f / 512) % 2, rt = f / 1024;
+        const int g = lane / 16, i = lane % 16;
+        if (rt < 12) {
+            Wf[f] = Wqkv[(size_t)(32 * ks + 8 * g + s) * 3 * C + 16 * rt + i];
+        } else {
+            const int o = 16 * (i / 4) + 4 * (rt - 12) + i % 4;
+            const int c = 32 * ks + 16 * (s / 4) + 4 * g + s % 4;
+            Wf[f] = Wo[(size_t)c * C + o];
+        }
+        return;
+    }
     if (e >= 4 * C * C) {
         const int a = e - 4 * C * C;
         const int k = a % 4, lane = (a / 4) % kWave, r = (a / (4 * kWave)) % 10, s = a / (40 * kWave);
@@ -54,14 +77,21 @@ __device__ inline void prep_weight_element(const bf16_t *__restrict__ Wqkv,
     else WoT[(size_t)(o - 3 * C) * C + c] = Wo[(size_t)c * C + (o - 3 * C)];
 }
 
-// `total` = 4 C^2 + 160 C (all weights) or 3 C^2 (projection weights only; Wo and Wlce
+// Number of prep elements of a forward call.
+__host__ __device__ constexpr int prep_total(int C)
+{
+    return 4 * C * C + kLceOperandElems * C + (C == 64 ? kFusedFragElems : 0);
+}
+
+// `total` = prep_total(C) (all weights) or 3 C^2 (projection weights only; Wo and Wlce
 // may be NULL).
 __global__ void k_prep_weights(const bf16_t *__restrict__ Wqkv, const bf16_t *__restrict__ Wo,
                                const bf16_t *__restrict__ Wlce, bf16_t *__restrict__ WT,
-                               bf16_t *__restrict__ WoT, bf16_t *__restrict__ Wa, int C, int total)
+                               bf16_t *__restrict__ WoT, bf16_t *__restrict__ Wa,
+                               bf16_t *__restrict__ Wf, int C, int total)
 {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e < total) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, C, e);
+    if (e < total) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, Wf, C, e);
 }
 
 // ---------------------------------------------------------------------------
@@ -78,7 +108,8 @@ __global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
                                                  const bf16_t *__restrict__ Wlce,
                                                  float *__restrict__ Qr, float *__restrict__ KrT,
                                                  bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT,
-                                                 bf16_t *__restrict__ Wa, Dims D, int pool_blocks, int G)
+                                                 bf16_t *__restrict__ Wa, bf16_t *__restrict__ Wf,
+                                                 Dims D, int pool_blocks, int G)
 {
     constexpr int MAXG = kPoolMaxGroup;
     __shared__ float part[4096];   // pooling partials, then projection partials
@@ -86,7 +117,7 @@ __global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
     const int tid = threadIdx.x;
     if ((int)blockIdx.x >= pool_blocks) {
         const int e = ((int)blockIdx.x - pool_blocks) * 256 + tid;
-        if (e < 4 * C * C + kLceOperandElems * C) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, C, e);
+        if (e < prep_total(C)) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, Wf, C, e);
         return;
     }
     constexpr int CH = C / 8;
@@ -489,35 +520,59 @@ __global__ __launch_bounds__(256) void k_attn_big(AttnArgs A, Dims D)
 
 // ---------------------------------------------------------------------------
 // Fused forward for one 64-token query tile whose region attends to a single
-// 64-token key block (the k = 1 stage): Q, the routed K / V and the V halo needed by
-// the LCE are projected from X inside the workgroup (Eq. 3), so Q, K, V never travel
-// through memory.  X tiles are staged once through LDS.  Wavefront w owns output
-// channels [w C/4, (w+1) C/4) of every projection (its weight slices stay in
-// registers) for ALL tokens of the workgroup; the projected tiles replace the X tiles
-// in LDS in place, then attention and W^o follow as in k_attn_big.
+// 64-token key block (the k = 1 stage), C = 64: Q, the routed K / V and the V halo
+// needed by the LCE are projected from X inside the workgroup (Eq. 3), so Q, K, V never
+// travel through memory.  X tiles are staged once through LDS.
 //
-// LCE (Eq. 7) also runs on the matrix cores.  The V halo of a wavefront's channels is
-// written channel-major (a plane of halo tokens per channel), and the 5x5 depth-wise
-// correlation of one channel becomes a chain of v_mfma_f32_4x4x4_16B_bf16 products:
-// block = channel, D[xi][yj] = out[y0 + yj][x0 + xi], and for every (ky, half-row hh)
-//   A[xi][k] = w[ky][4 hh + k - xi] (zero outside 0..4),  B[k][yj] = V[y0 + yj + ky][x0 + 4 hh + k]
-// (halo coordinates).  4x4x4 lane layout: block l / 4; A row, B / D column l % 4.
-template <int C, int RW>
+// Work split over the four wavefronts:
+//   * Q, attention and W^o by token: wavefront w owns queries 16 w .. 16 w + 15.  Its Q
+//     comes out of the matrix cores as Q^T[channel 16 ct + 4 g + j][query i]; two such
+//     tiles packed together are the B operand of S^T = K Q^T for one head, with the 32
+//     contraction slots of lane group g standing for channels
+//         32 h + 4 g + (0..3)  and  32 h + 16 + 4 g + (0..3)
+//     instead of 32 h + 8 g + (0..7).  The K operand is read from LDS in the same order
+//     (two 8-byte reads), so Q never passes through LDS.  The attention output O^T has
+//     the same form and feeds Y^T = Wo^T O^T directly, with Wo's fragments permuted to
+//     match (a table the weight-prep blocks write).
+//   * K, V of the routed block, the V halo and the LCE by channel: wavefront w owns
+//     channels 16 w .. 16 w + 15 of all tokens; its weight slices stay in registers.
+//     Neighbouring lane groups swap halves (v_permlane16_swap) so that every lane
+//     writes 16 contiguous bytes of a K / V row or of a V halo plane.
+//   * LCE (Eq. 7) runs on the matrix cores.  The V halo of a wavefront's channels is
+//     stored channel-major (a plane of halo tokens per channel) and the 5x5 depth-wise
+//     correlation of one channel is a chain of v_mfma_f32_4x4x4_16B_bf16 products:
+//     block = channel, D[xi][yj] = out[y0 + yj][x0 + xi], and for every (ky, half hh)
+//       A[xi][k] = w[ky][4 hh + k - xi] (zero outside 0..4),
+//       B[k][yj] = V[y0 + yj + ky][x0 + 4 hh + k]            (halo coordinates).
+//     4x4x4 lane layout: block l / 4; A row, B / D column l % 4.  The result goes to
+//     LDS as a float32 tile [channel][query] and is added to the attention output in
+//     registers by the wavefront that owns the query.
+//
+// LDS row pitches are chosen per access pattern (measured on gfx950): rows read with
+// the transposing read are fastest at 160 bytes, rows read 8 bytes per lane at 144 bytes,
+// the planes (8-byte reads, lane = channel x row offset) at a pitch of 8 x odd words.
+// The X tiles (16-byte reads) would also like 160 bytes, but at 144 bytes the whole map
+// stays under 40 KB and four workgroups fit a compute unit, which is worth more.
+template <int RW>
 struct FusedSmem {
-    static constexpr int CS = C + 8;
-    static constexpr int OS = C + 4;
+    static constexpr int C = 64;
+    static constexpr int XS = C + 8;                                  // X tiles
+    static constexpr int KP = C + 8;                                  // K tile
+    static constexpr int VP = C + 16;                                 // V tile
+    static constexpr int PL = 68;                                     // LCE tile: floats per channel
     static constexpr int QH = 64 / RW;                                // rows of the query tile
     static constexpr int HW = RW + 4, HROWS = (QH + 4) * HW;          // halo tile
     static constexpr int NHT = (HROWS + 15) / 16;                     // 16-token tiles of the halo
-    // halo plane pitch (bf16): an odd multiple of 4 32-bit words, so that the 8-byte writes
-    // of 16 planes x 2 token groups (half a wavefront) fall into 64 different banks
-    static constexpr int PS = 2 * ((NHT * 8 / 8) * 8 + 4);
-    static constexpr size_t xh_bytes = (size_t)NHT * 16 * CS * 2;     // X halo, row-major
-    static constexpr size_t vt_bytes = (size_t)C * PS * 2;            // V halo, channel-major
+    static constexpr int PSW = (NHT % 2) ? NHT * 8 : NHT * 8 + 8;     // plane pitch in 32-bit words
+    static constexpr int PS = 2 * PSW;
     static constexpr size_t k_off = 0;                                // routed X tile -> K tile
-    static constexpr size_t v_off = k_off + (size_t)64 * CS * 2;      // Q tile -> V tile
-    static constexpr size_t h_off = v_off + (size_t)64 * CS * 2;      // X halo -> V halo planes
+    static constexpr size_t v_off = k_off + (size_t)64 * XS * 2;      // V tile
+    static constexpr size_t l_off = 0;                                // LCE tile, over K and V
+    static constexpr size_t h_off = v_off + (size_t)64 * VP * 2;      // X halo -> V halo planes
+    static constexpr size_t xh_bytes = (size_t)NHT * 16 * XS * 2;
+    static constexpr size_t vt_bytes = (size_t)C * PS * 2;
     static constexpr size_t bytes = h_off + (xh_bytes > vt_bytes ? xh_bytes : vt_bytes);
+    static_assert(KP <= XS && (size_t)C * PL * 4 <= h_off, "tiles that share a slot must fit");
 };
 
 __device__ __forceinline__ f32x4 mfma4(s16x4 a, s16x4 b, f32x4 c)
@@ -525,22 +580,34 @@ __device__ __forceinline__ f32x4 mfma4(s16x4 a, s16x4 b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, b, c, 0, 0, 0);
 }
 
-template <int C, int RW>
+// Lane groups g (16 lanes each) hold two 8-byte pieces a, b that continue in the
+// neighbouring group: afterwards {a, b} of an even group is its own a followed by the
+// odd neighbour's a, and {a, b} of an odd group is the even neighbour's b followed by its
+// own b (v_permlane16_swap exchanges the odd rows of its first operand with the even rows
+// of its second).
+__device__ __forceinline__ u32x4 pair_halves(u32x2 a, u32x2 b)
+{
+    const auto lo = __builtin_amdgcn_permlane16_swap(a[0], b[0], false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap(a[1], b[1], false, false);
+    return u32x4{lo[0], hi[0], lo[1], hi[1]};
+}
+
+template <int RW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4)))
 void k_fused(AttnArgs A, Dims D)
 {
-    typedef FusedSmem<C, RW> SM;
-    constexpr int CS = SM::CS, OS = SM::OS, HEADS = C / 32, KS = C / 32, CH = C / 8;
-    constexpr int NT = C / 64;                  // 16-channel output tiles per wavefront and matrix
+    typedef FusedSmem<RW> SM;
+    constexpr int C = 64, HEADS = C / 32, KS = C / 32, CH = C / 8, NCT = C / 16;
+    constexpr int XS = SM::XS, KP = SM::KP, VP = SM::VP, PL = SM::PL;
     constexpr int QH = SM::QH, HW = SM::HW, HROWS = SM::HROWS, NHT = SM::NHT, PS = SM::PS;
     constexpr int NBH = (HROWS * CH + 255) / 256;      // halo chunks per thread
     constexpr int NBT = CH / 4;                 // chunks per thread of a 64-row tile
     constexpr int NYB = QH / 4, NXB = RW / 4;   // 4x4 output blocks of the query tile
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)(smem + SM::k_off);   // first the routed X tile
-    bf16_t *Vs = (bf16_t *)(smem + SM::v_off);   // first the Q tile
+    bf16_t *Vs = (bf16_t *)(smem + SM::v_off);
     bf16_t *Hs = (bf16_t *)(smem + SM::h_off);   // first the X halo tile, then the V planes
-    float *Os = (float *)(smem + SM::k_off);
+    float *Ls = (float *)(smem + SM::l_off);
 
     const int wid = swizzled_block();
     if (wid >= A.total) return;
@@ -553,118 +620,131 @@ void k_fused(AttnArgs A, Dims D)
     const bf16_t *Ximg = A.X + img_off;
     const float hw_inv = 1.0f / (float)HW, rw_inv = 1.0f / (float)RW;
 
-    // Requests that do not depend on the routing: X over the halo of the query tile
-    // (it contains the query tile), this wavefront's weight slices, its LCE weights.
-    u32x4 hreg[NBH];
-    tile_load<C, NBH>(hreg, Ximg, y0 - 2, x0 - 2, HW, hw_inv, HROWS, D.H, D.W, 0);
-    bf16x8 wq[NT][KS], wk[NT][KS], wv[NT][KS], wo[NT][KS];
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const size_t row = (size_t)(16 * (wave * NT + t) + i) * C + 32 * ks + 8 * g;
-            wq[t][ks] = *(const bf16x8 *)(A.WT + row);
-            wk[t][ks] = *(const bf16x8 *)(A.WT + (size_t)C * C + row);
-            wv[t][ks] = *(const bf16x8 *)(A.WT + (size_t)2 * C * C + row);
-            wo[t][ks] = *(const bf16x8 *)(A.WoT + row);
-        }
-    // LCE weights as 4x4x4 A operands: lane = (channel block lb, output offset xi).
-    const int lb = lane / 4, xi = lane % 4;
-    s16x4 aw[NT][5][2];
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-        for (int r = 0; r < 10; ++r)
-            aw[t][r / 2][r % 2] = *(const s16x4 *)(A.Wa + ((size_t)((wave * NT + t) * 10 + r) * kWave + lane) * 4);
-
+    // All requests up front: the routed region, X over the halo of the query tile (it
+    // contains the query tile) and over the routed region, the weight fragments.
     const int j = A.Ir_src[(size_t)b * D.R + reg];
     if (A.Ir_out && A.Ir_out != A.Ir_src && threadIdx.x == 0) A.Ir_out[(size_t)b * D.R + reg] = j;
+    u32x4 hreg[NBH];
+    tile_load<C, NBH>(hreg, Ximg, y0 - 2, x0 - 2, HW, hw_inv, HROWS, D.H, D.W, 0);
+    auto fragment = [&](int rt, int ks) {
+        return *(const bf16x8 *)(A.Wf + ((size_t)(rt * KS + ks) * kWave + lane) * 8);
+    };
+    bf16x8 wq[NCT][KS], wk[KS], wv[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) wq[ct][ks] = fragment(ct, ks);
+        wk[ks] = fragment(NCT + wave, ks);
+        wv[ks] = fragment(2 * NCT + wave, ks);
+    }
+    // LCE weights as 4x4x4 A operands: lane = (channel block lb, output offset xi).
+    const int lb = lane / 4, xi = lane % 4;
+    s16x4 aw[5][2];
+#pragma unroll
+    for (int r = 0; r < 10; ++r)
+        aw[r / 2][r % 2] = *(const s16x4 *)(A.Wa + ((size_t)(wave * 10 + r) * kWave + lane) * 4);
     u32x4 kreg[NBT];
     tile_load<C, NBT>(kreg, Ximg, (j / D.S) * D.rh, (j % D.S) * RW, RW, rw_inv, 64, D.H, D.W, 0);
-    tile_store<C, CS, NBH>(Hs, hreg, HROWS, 0);
-    tile_store<C, CS, NBT>(Ks, kreg, 64, 0);
+    tile_store<C, XS, NBH>(Hs, hreg, HROWS, 0);
+    tile_store<C, XS, NBT>(Ks, kreg, 64, 0);
     __syncthreads();
 
-    // Projections of this wavefront's channel slice.  Q, K, V: D^T[channel 16 tile + 4 g + jj]
-    // [token i], a lane ends up with 4 consecutive channels of one token.  V halo: operands
-    // swapped, D[token 4 g + jj][channel i], 4 consecutive halo tokens of one channel.
-    u32x2 vh[NHT][NT], kk[4][NT], vv[4][NT];
+    // Q of this wavefront's 16 queries, as the B operands of S^T = K Q^T.
+    const int q = 16 * wave + i;
+    const int qy = fast_div(q, rw_inv);
+    bf16x8 qb[HEADS];
+    {
+        const bf16_t *xq = Hs + ((qy + 2) * HW + q - qy * RW + 2) * XS + 8 * g;   // query token in the halo
+        bf16x8 bq[KS];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int q = 16 * u + i;
-        const int qy = fast_div(q, rw_inv);
-        const bf16_t *xq = Hs + ((qy + 2) * HW + q - qy * RW + 2) * CS + 8 * g;   // query token in the halo
-        const bf16_t *xk = Ks + q * CS + 8 * g;
-        bf16x8 bq[KS], bk[KS];
+        for (int ks = 0; ks < KS; ++ks) bq[ks] = *(const bf16x8 *)(xq + 32 * ks);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            bq[ks] = *(const bf16x8 *)(xq + 32 * ks);
-            bk[ks] = *(const bf16x8 *)(xk + 32 * ks);
-        }
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            f32x4 aq = {0.f, 0.f, 0.f, 0.f}, ak = {0.f, 0.f, 0.f, 0.f}, av = {0.f, 0.f, 0.f, 0.f};
+        for (int h = 0; h < HEADS; ++h) {
+            f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                aq = mfma16(wq[t][ks], bq[ks], aq);
-                ak = mfma16(wk[t][ks], bk[ks], ak);
-                av = mfma16(wv[t][ks], bk[ks], av);
+                a0 = mfma16(wq[2 * h][ks], bq[ks], a0);
+                a1 = mfma16(wq[2 * h + 1][ks], bq[ks], a1);
             }
-            *(u32x2 *)(Vs + q * CS + 16 * (wave * NT + t) + 4 * g) = pack4(aq);   // Q tile
-            kk[u][t] = pack4(ak);
-            vv[u][t] = pack4(av);
+            float v[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+            qb[h] = pack8(v);
         }
+    }
+    // W^o fragments (rows and contraction slots permuted) take over the registers of Wq.
+    bf16x8 wo[4][KS];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) wo[tt][ks] = fragment(3 * NCT + tt, ks);
+
+    // K, V of the routed block: D^T[channel 16 w + 4 g + jj][token i], a lane ends up with
+    // 4 consecutive channels of one token.  V halo: operands swapped, D[token 4 g + jj]
+    // [channel i], 4 consecutive halo tokens of one channel.
+    u32x2 vh[NHT], kk[4], vv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const bf16_t *xk = Ks + (16 * u + i) * XS + 8 * g;
+        f32x4 ak = {0.f, 0.f, 0.f, 0.f}, av = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 bk = *(const bf16x8 *)(xk + 32 * ks);
+            ak = mfma16(wk[ks], bk, ak);
+            av = mfma16(wv[ks], bk, av);
+        }
+        kk[u] = pack4(ak);
+        vv[u] = pack4(av);
     }
 #pragma unroll
     for (int hu = 0; hu < NHT; ++hu) {
-        const bf16_t *xh = Hs + (16 * hu + i) * CS + 8 * g;
-        bf16x8 bh[KS];
+        const bf16_t *xh = Hs + (16 * hu + i) * XS + 8 * g;
+        f32x4 a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) bh[ks] = *(const bf16x8 *)(xh + 32 * ks);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            f32x4 a = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) a = mfma16(bh[ks], wv[t][ks], a);
-            vh[hu][t] = pack4(a);
-        }
+        for (int ks = 0; ks < KS; ++ks) a = mfma16(*(const bf16x8 *)(xh + 32 * ks), wv[ks], a);
+        vh[hu] = pack4(a);
     }
-    __syncthreads();   // every X tile has been read; the Q tile is complete
-    bf16x8 qf[HEADS];
+    __syncthreads();   // every X tile has been read
+
+    // Tiles of this wavefront's channels: rows 16 (2 p + g % 2) + i, channels 8 (g / 2) ..
 #pragma unroll
-    for (int h = 0; h < HEADS; ++h) qf[h] = *(const bf16x8 *)(Vs + (16 * wave + i) * CS + 32 * h + 8 * g);
+    for (int p = 0; p < 2; ++p) {
+        const int row = 16 * (2 * p + (g & 1)) + i, col = 16 * wave + 8 * (g >> 1);
+        *(u32x4 *)(Ks + row * KP + col) = pair_halves(kk[2 * p], kk[2 * p + 1]);
+        *(u32x4 *)(Vs + row * VP + col) = pair_halves(vv[2 * p], vv[2 * p + 1]);
+    }
+    {   // plane of channel 16 w + i: halo tokens 16 (2 p + g % 2) + 8 (g / 2) ..
+        bf16_t *plane = Hs + (16 * wave + i) * PS;
 #pragma unroll
-    for (int hu = 0; hu < NHT; ++hu)
-#pragma unroll
-        for (int t = 0; t < NT; ++t)   // plane of channel 16 (w NT + t) + i, halo tokens 16 hu + 4 g ..
-            *(u32x2 *)(Hs + (16 * (wave * NT + t) + i) * PS + 16 * hu + 4 * g) = vh[hu][t];
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-            *(u32x2 *)(Ks + (16 * u + i) * CS + 16 * (wave * NT + t) + 4 * g) = kk[u][t];
-    __syncthreads();   // the Q fragments are read: V may take the slot
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-            *(u32x2 *)(Vs + (16 * u + i) * CS + 16 * (wave * NT + t) + 4 * g) = vv[u][t];
+        for (int p = 0; p < NHT / 2; ++p)
+            *(u32x4 *)(plane + 16 * (2 * p + (g & 1)) + 8 * (g >> 1)) = pair_halves(vh[2 * p], vh[2 * p + 1]);
+        if constexpr (NHT % 2) *(u32x2 *)(plane + 16 * (NHT - 1) + 4 * g) = vh[NHT - 1];
+    }
     __syncthreads();
 
+    // Attention of the 16 queries over the 64 keys (Eq. 1 with one routed block).
     SoftmaxState<HEADS> st;
     st.init();
-    attn_key_block<C, CS>(Ks, Vs, qf, st, A.c_exp, g, i);
-
-    // LCE of this wavefront's channels from its own halo planes (no workgroup sync needed
-    // for them): lane = (channel block lb, output row offset yj = xi index of the lane).
-    f32x4 lce[NT][NYB][NXB];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const bf16_t *plane = Hs + (16 * (wave * NT + t) + lb) * PS;
+    for (int h = 0; h < HEADS; ++h) {
+        f32x4 s[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const bf16_t *kr = Ks + (16 * t + i) * KP + 32 * h + 4 * g;
+            const u32x2 lo = *(const u32x2 *)kr, hi = *(const u32x2 *)(kr + 16);
+            const u32x4 kf = {lo[0], lo[1], hi[0], hi[1]};
+            s[t] = mfma16(__builtin_bit_cast(bf16x8, kf), qb[h], f32x4{0.f, 0.f, 0.f, 0.f});
+        }
+        softmax_pv_block<VP>(Vs, s, st, h, A.c_exp, g, i);
+    }
+
+    // LCE of this wavefront's channels from its own halo planes:
+    // lane = (channel block lb, output row offset yj = xi index of the lane).
+    f32x4 lce[NYB][NXB];
+    {
+        const bf16_t *plane = Hs + (16 * wave + lb) * PS;
 #pragma unroll
         for (int yb = 0; yb < NYB; ++yb) {
 #pragma unroll
-            for (int xb = 0; xb < NXB; ++xb) lce[t][yb][xb] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int xb = 0; xb < NXB; ++xb) lce[yb][xb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ky = 0; ky < 5; ++ky) {
                 const bf16_t *row = plane + (4 * yb + xi + ky) * HW;   // halo row of output row 4 yb + yj
@@ -673,53 +753,51 @@ void k_fused(AttnArgs A, Dims D)
                 for (int xb = 0; xb <= NXB; ++xb) br[xb] = *(const s16x4 *)(row + 4 * xb);
 #pragma unroll
                 for (int xb = 0; xb < NXB; ++xb) {
-                    lce[t][yb][xb] = mfma4(aw[t][ky][0], br[xb], lce[t][yb][xb]);
-                    lce[t][yb][xb] = mfma4(aw[t][ky][1], br[xb + 1], lce[t][yb][xb]);
+                    lce[yb][xb] = mfma4(aw[ky][0], br[xb], lce[yb][xb]);
+                    lce[yb][xb] = mfma4(aw[ky][1], br[xb + 1], lce[yb][xb]);
                 }
             }
         }
     }
-    __syncthreads();
-    attn_write_out<C, OS>(Os, st, wave, g, i);
-    __syncthreads();
+    __syncthreads();   // K and V have been read: the LCE tile may take their place
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int yb = 0; yb < NYB; ++yb)
 #pragma unroll
-        for (int yb = 0; yb < NYB; ++yb)
-#pragma unroll
-            for (int xb = 0; xb < NXB; ++xb)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)   // out[row 4 yb + yj][col 4 xb + e] of channel block lb
-                    Os[((4 * yb + xi) * RW + 4 * xb + e) * OS + 16 * (wave * NT + t) + lb] += lce[t][yb][xb][e];
+        for (int xb = 0; xb < NXB; ++xb)   // queries (row 4 yb + yj, columns 4 xb ..) of channel 16 w + lb
+            *(f32x4 *)(Ls + (16 * wave + lb) * PL + (4 * yb + xi) * RW + 4 * xb) = lce[yb][xb];
     __syncthreads();
 
-    // Y^T slice = Wo^T slice * O^T: this wavefront's 16 NT output channels of all 64 tokens.
+    // O = attention + LCE (Eq. 2, 7) in registers, then Y^T = Wo^T O^T for the 16 queries:
+    // W^o row 4 g + jj of tile tt stands for output channel 16 g + 4 tt + jj, so a lane
+    // ends up with 16 consecutive output channels of its query.
+    bf16x8 ob[HEADS];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int q = 16 * u + i;
-        bf16x8 of[KS];
+    for (int h = 0; h < HEADS; ++h) {
+        const float inv = 1.0f / st.l[h];
+        float v[8];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const float *src = Os + q * OS + 32 * ks + 8 * g;
-            f32x4 lo = *(const f32x4 *)src, hi = *(const f32x4 *)(src + 4);
-            float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            of[ks] = pack8(v);
-        }
-        const int qy = fast_div(q, rw_inv);
-        bf16_t *yrow = A.Y + img_off + ((size_t)(y0 + qy) * D.W + x0 + q - qy * RW) * C;
+        for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            f32x4 ya = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) ya = mfma16(wo[t][ks], of[ks], ya);
-            *(u32x2 *)(yrow + 16 * (wave * NT + t) + 4 * g) = pack4(ya);
-        }
+            for (int jj = 0; jj < 4; ++jj)
+                v[4 * dt + jj] = fmaf(st.acc[h][dt][jj], inv, Ls[(32 * h + 16 * dt + 4 * g + jj) * PL + q]);
+        ob[h] = pack8(v);
     }
+    u32x2 yp[4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+        f32x4 ya = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int h = 0; h < HEADS; ++h) ya = mfma16(wo[tt][h], ob[h], ya);
+        yp[tt] = pack4(ya);
+    }
+    u32x4 *dst = (u32x4 *)(A.Y + img_off + ((size_t)(y0 + qy) * D.W + x0 + q - qy * RW) * C + 16 * g);
+    dst[0] = u32x4{yp[0][0], yp[0][1], yp[1][0], yp[1][1]};
+    dst[1] = u32x4{yp[2][0], yp[2][1], yp[3][0], yp[3][1]};
 }
 
 // ---------------------------------------------------------------------------
 struct MfmaWs {
-    bf16_t *q, *k, *v, *o, *wt, *wot, *wa;
+    bf16_t *q, *k, *v, *o, *wt, *wot, *wa, *wf;
     float *qr, *krt;
     void *route;
     int32_t *ir;
@@ -739,7 +817,7 @@ bool fused_ok(const Dims &D)
 {
     static const bool disabled = getenv("BRA_DISABLE_FUSED") != nullptr;   // benchmarking aid
     if (disabled || !fast_route_ok(D)) return false;
-    if (D.C != 64 && D.C != 128) return false;
+    if (D.C != 64) return false;
     return D.n == 64 && D.k == 1 && (D.rw == 8 || D.rw == 16);
 }
 
@@ -757,6 +835,7 @@ MfmaWs carve(const Dims &D, void *ws)
     w.wt = (bf16_t *)take((size_t)3 * D.C * D.C * 2);
     w.wot = (bf16_t *)take((size_t)D.C * D.C * 2);
     w.wa = (bf16_t *)take((size_t)D.C * kLceOperandElems * 2);
+    w.wf = (bf16_t *)take(D.C == 64 ? (size_t)kFusedFragElems * 2 : 0);
     w.qr = (float *)take((size_t)D.B * D.R * D.C * sizeof(float));
     w.krt = (float *)take((size_t)D.B * D.C * kRpad * sizeof(float));
     w.route = take(fast_route_ok(D) ? 0 : valu_route_scratch_bytes(D));
@@ -774,9 +853,9 @@ void launch_pool_qk(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf
         // (pool && !prep happens in bra_route: only WT's Wq|Wk rows are needed, Wo may be NULL)
         {
             ProfScope ps(st, K_MFMA_PREP);
-            const int total = prep ? 4 * C * C + kLceOperandElems * C : 3 * C * C;
+            const int total = prep ? prep_total(C) : 3 * C * C;
             hipLaunchKernelGGL(k_prep_weights, dim3((total + 255) / 256), dim3(256), 0, st, Wqkv, Wo, Wlce,
-                               w.wt, w.wot, w.wa, C, total);
+                               w.wt, w.wot, w.wa, w.wf, C, total);
         }
         if (pool) {
             ProfScope ps(st, K_MFMA_POOL_QK);
@@ -788,11 +867,11 @@ void launch_pool_qk(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf
     int G = 4;                                                     // regions per workgroup
     if (const char *e = getenv("BRA_POOL_GROUP")) { int v = atoi(e); if (v >= 1 && v <= kPoolMaxGroup) G = v; }
     const int pool_blocks = pool ? D.B * ((D.R + G - 1) / G) : 0;
-    const int prep_blocks = prep ? (4 * C * C + kLceOperandElems * C + 255) / 256 : 0;
+    const int prep_blocks = prep ? (prep_total(C) + 255) / 256 : 0;
     if (pool_blocks + prep_blocks == 0) return;
     ProfScope ps(st, K_MFMA_POOL_QK);
     hipLaunchKernelGGL(k_pool_qk<C>, dim3(pool_blocks + prep_blocks), dim3(256), 0, st, X, Wqkv, Wo,
-                       Wlce, w.qr, w.krt, w.wt, w.wot, w.wa, D, pool_blocks, G);
+                       Wlce, w.qr, w.krt, w.wt, w.wot, w.wa, w.wf, D, pool_blocks, G);
 }
 
 template <int C>
@@ -838,30 +917,28 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
             Ir_src = dst;
         }
         ProfScope ps(st, K_MFMA_PREP);
-        const int total = 4 * C * C + kLceOperandElems * C;
+        const int total = prep_total(C);
         hipLaunchKernelGGL(k_prep_weights, dim3((total + 255) / 256), dim3(256), 0, st, Wqkv, Wo, Wlce,
-                           w.wt, w.wot, w.wa, C, total);
+                           w.wt, w.wot, w.wa, w.wf, C, total);
     }
     AttnArgs A;
     A.X = X; A.WT = w.wt; A.Q = w.q; A.K = w.k; A.V = w.v;
-    A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = Wlce; A.Wa = w.wa; A.WoT = w.wot; A.Y = Y;
+    A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = Wlce; A.Wa = w.wa; A.Wf = w.wf; A.WoT = w.wot; A.Y = Y;
     A.c_exp = D.scale * 1.4426950408889634f;
     A.total = D.B * D.R * (D.n / 64);
     const int grid = ((A.total + 7) / 8) * 8;
     const int hrows = halo_rows(D);
 
-    if constexpr (C <= 128) {
+    if constexpr (C == 64) {
         if (fused_ok(D)) {
             static bool opted8 = false, opted16 = false;
             ProfScope ps(st, K_MFMA_FUSED_K1);
             if (D.rw == 8) {
-                if (!lds_opt_in(k_fused<C, 8>, opted8)) return BRA_ERR_LAUNCH;
-                const size_t smem = FusedSmem<C, 8>::bytes;
-                hipLaunchKernelGGL((k_fused<C, 8>), dim3(grid), dim3(256), smem, st, A, D);
+                if (!lds_opt_in(k_fused<8>, opted8)) return BRA_ERR_LAUNCH;
+                hipLaunchKernelGGL(k_fused<8>, dim3(grid), dim3(256), FusedSmem<8>::bytes, st, A, D);
             } else {
-                if (!lds_opt_in(k_fused<C, 16>, opted16)) return BRA_ERR_LAUNCH;
-                const size_t smem = FusedSmem<C, 16>::bytes;
-                hipLaunchKernelGGL((k_fused<C, 16>), dim3(grid), dim3(256), smem, st, A, D);
+                if (!lds_opt_in(k_fused<16>, opted16)) return BRA_ERR_LAUNCH;
+                hipLaunchKernelGGL(k_fused<16>, dim3(grid), dim3(256), FusedSmem<16>::bytes, st, A, D);
             }
             return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
         }

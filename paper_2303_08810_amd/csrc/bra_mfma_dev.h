@@ -178,9 +178,58 @@ struct SoftmaxState {
     }
 };
 
+// Online-softmax step of head h for one block of 64 keys, given the scores
+// s[t][j] = S^T[key 16 t + 4 g + j][query i] of this wavefront's 16 queries (Eq. 1, one
+// softmax over all routed keys), then O^T += V^T P^T with V read from the rows of Vs (VS
+// elements per row) by the transposing LDS read.
+template <int VS, int HEADS>
+__device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (&s)[4],
+                                                 SoftmaxState<HEADS> &st, int h, float c_exp, int g,
+                                                 int i)
+{
+    float mx = s[0][0];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) mx = fmaxf(mx, s[t][jj]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    const float m_new = fmaxf(st.m[h], mx);
+    const float alpha = __builtin_amdgcn_exp2f((st.m[h] - m_new) * c_exp);
+    const float mc = m_new * c_exp;
+    float p[4][4], ls = 0.f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            p[t][jj] = __builtin_amdgcn_exp2f(fmaf(s[t][jj], c_exp, -mc));
+            ls += p[t][jj];
+        }
+    ls += __shfl_xor(ls, 16, kWave);
+    ls += __shfl_xor(ls, 32, kWave);
+    st.l[h] = st.l[h] * alpha + ls;
+    st.m[h] = m_new;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt) st.acc[h][dt] *= alpha;
+#pragma unroll
+    for (int tp = 0; tp < 2; ++tp) {
+        float pv[8] = {p[2 * tp][0], p[2 * tp][1], p[2 * tp][2], p[2 * tp][3],
+                       p[2 * tp + 1][0], p[2 * tp + 1][1], p[2 * tp + 1][2], p[2 * tp + 1][3]};
+        const bf16x8 pb = pack8(pv);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+            const int col = 32 * h + 16 * dt + 4 * (i % 4);
+            const s16x4 v0 = lds_read_tr16(Vs + (32 * tp + 4 * g + i / 4) * VS + col);
+            const s16x4 v1 = lds_read_tr16(Vs + (32 * tp + 16 + 4 * g + i / 4) * VS + col);
+            u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+            u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
+            st.acc[h][dt] = mfma16(__builtin_bit_cast(bf16x8, av), pb, st.acc[h][dt]);
+        }
+    }
+}
+
 // One block of 64 keys (rows of Ks / Vs, CS elements per row) against the 16 queries of
-// this wavefront (qf[h] = B operand of head h): S^T = K Q^T, online softmax over the
-// keys (Eq. 1, one softmax over all routed keys), O^T += V^T P^T.
+// this wavefront (qf[h] = B operand of head h): S^T = K Q^T, then the softmax / PV step.
 template <int C, int CS>
 __device__ __forceinline__ void attn_key_block(const bf16_t *Ks, const bf16_t *Vs,
                                                const bf16x8 (&qf)[C / 32],
@@ -195,45 +244,7 @@ __device__ __forceinline__ void attn_key_block(const bf16_t *Ks, const bf16_t *V
             const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + 32 * h + 8 * g);
             s[t] = mfma16(kf, qf[h], f32x4{0.f, 0.f, 0.f, 0.f});   // S^T[key 16t+4g+j][query i]
         }
-        float mx = s[0][0];
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) mx = fmaxf(mx, s[t][jj]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        const float m_new = fmaxf(st.m[h], mx);
-        const float alpha = __builtin_amdgcn_exp2f((st.m[h] - m_new) * c_exp);
-        const float mc = m_new * c_exp;
-        float p[4][4], ls = 0.f;
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                p[t][jj] = __builtin_amdgcn_exp2f(fmaf(s[t][jj], c_exp, -mc));
-                ls += p[t][jj];
-            }
-        ls += __shfl_xor(ls, 16, kWave);
-        ls += __shfl_xor(ls, 32, kWave);
-        st.l[h] = st.l[h] * alpha + ls;
-        st.m[h] = m_new;
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) st.acc[h][dt] *= alpha;
-#pragma unroll
-        for (int tp = 0; tp < 2; ++tp) {
-            float pv[8] = {p[2 * tp][0], p[2 * tp][1], p[2 * tp][2], p[2 * tp][3],
-                           p[2 * tp + 1][0], p[2 * tp + 1][1], p[2 * tp + 1][2], p[2 * tp + 1][3]};
-            const bf16x8 pb = pack8(pv);
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt) {
-                const int col = 32 * h + 16 * dt + 4 * (i % 4);
-                const s16x4 v0 = lds_read_tr16(Vs + (32 * tp + 4 * g + i / 4) * CS + col);
-                const s16x4 v1 = lds_read_tr16(Vs + (32 * tp + 16 + 4 * g + i / 4) * CS + col);
-                u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
-                u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
-                st.acc[h][dt] = mfma16(__builtin_bit_cast(bf16x8, av), pb, st.acc[h][dt]);
-            }
-        }
+        softmax_pv_block<CS>(Vs, s, st, h, c_exp, g, i);
     }
 }
 
@@ -357,6 +368,7 @@ struct AttnArgs {
     int32_t *Ir_out;                // where to report the routing index, or NULL
     const bf16_t *Wlce, *WoT;
     const bf16_t *Wa;               // LCE weights as 4x4x4 A operands (fused kernel)
+    const bf16_t *Wf;               // projection weights in fragment order (fused kernel)
     bf16_t *Y;
     float c_exp;                    // softmax scale * log2(e)
     int total;                      // workgroups that have work
