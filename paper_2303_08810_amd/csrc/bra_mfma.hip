@@ -95,41 +95,28 @@ __global__ void k_prep_weights(const bf16_t *__restrict__ Wqkv, const bf16_t *__
 }
 
 // ---------------------------------------------------------------------------
-// Region pooling and region-level projections (Sec. 3.2, "Region-to-region routing").
-// Workgroup (b, group) handles G consecutive regions of image b: it reads their tokens
-// exactly once, forms the mean tokens in float32 (fixed summation order), and
-// multiplies them by Wq and Wk:  Qr[b, r, :] and KrT[b, :, r] (keys transposed so
-// that a wavefront reads one channel of all regions as one contiguous run).
-// Workgroups beyond `pool_blocks` transpose the projection weights instead.
+// Region pooling (Sec. 3.2, "Region-to-region routing"): Xr[b, r, :] = mean of the
+// tokens of region r, in float32 with a fixed summation order.  Workgroup (b, group)
+// handles G consecutive regions of image b and reads their tokens exactly once: a pure
+// streaming pass over X.  Workgroups beyond `pool_blocks` rearrange the weights instead.
 template <int C>
-__global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
-                                                 const bf16_t *__restrict__ Wqkv,
-                                                 const bf16_t *__restrict__ Wo,
-                                                 const bf16_t *__restrict__ Wlce,
-                                                 float *__restrict__ Qr, float *__restrict__ KrT,
-                                                 bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT,
-                                                 bf16_t *__restrict__ Wa, bf16_t *__restrict__ Wf,
-                                                 Dims D, int pool_blocks, int G)
+__global__ __launch_bounds__(256) void k_pool(const bf16_t *__restrict__ X,
+                                              const bf16_t *__restrict__ Wqkv,
+                                              const bf16_t *__restrict__ Wo,
+                                              const bf16_t *__restrict__ Wlce,
+                                              float *__restrict__ Xr, bf16_t *__restrict__ WT,
+                                              bf16_t *__restrict__ WoT, bf16_t *__restrict__ Wa,
+                                              bf16_t *__restrict__ Wf, Dims D, int pool_blocks, int G,
+                                              int prep_elems)
 {
-    constexpr int MAXG = kPoolMaxGroup;
-    __shared__ float part[4096];   // pooling partials, then projection partials
-    __shared__ float xr[MAXG * C];
+    __shared__ float part[2048];   // pooling partials
     const int tid = threadIdx.x;
     if ((int)blockIdx.x >= pool_blocks) {
         const int e = ((int)blockIdx.x - pool_blocks) * 256 + tid;
-        if (e < prep_total(C)) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, Wf, C, e);
+        if (e < prep_elems) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, Wf, C, e);
         return;
     }
     constexpr int CH = C / 8;
-    constexpr int SPL = (C >= 256) ? 1 : 256 / C;   // input-channel splits of the projection
-    constexpr int CP = C / SPL;
-    constexpr bool kPrefetchW = CP <= 32;           // few enough weights to request up front
-    unsigned wpre[kPrefetchW ? CP : 1];
-    if constexpr (kPrefetchW) {
-#pragma unroll
-        for (int cc = 0; cc < CP; ++cc)
-            wpre[cc] = *(const unsigned *)(Wqkv + (size_t)((tid / C) * CP + cc) * 3 * C + 2 * (tid % C));
-    }
     const int groups = (D.R + G - 1) / G;
     const int b = blockIdx.x / groups, r0 = (blockIdx.x % groups) * G;
     const int ng = min(G, D.R - r0);                           // regions of this workgroup
@@ -138,7 +125,7 @@ __global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
     while (P < items) P *= 2;
     const int SUB = 256 / P;                                   // threads that share one pair
     const int item = tid % P, sub = tid / P;
-    if (item < items && sub < SUB) {
+    if (item < items) {
         const int gi = item / CH, cc = item % CH;
         const int r = r0 + gi;
         const int ry0 = (r / D.S) * D.rh, rx0 = (r % D.S) * D.rw;
@@ -164,180 +151,162 @@ __global__ __launch_bounds__(256) void k_pool_qk(const bf16_t *__restrict__ X,
         const int it = gi * CH + c / 8;
         float s = 0.f;
         for (int sb = 0; sb < SUB; ++sb) s += part[(sb * items + it) * 8 + c % 8];
-        xr[e] = s / (float)D.n;
-    }
-    __syncthreads();
-    // [Q^r | K^r] = xr [Wq | Wk].  Thread (oc, split) owns output columns 2 oc, 2 oc + 1
-    // over input channels [split * CP, (split + 1) * CP); the SPL partial sums of a
-    // column are added in ascending split order.
-    {
-        const int oc = tid % C, split = tid / C;
-        float acc0[MAXG], acc1[MAXG];
-#pragma unroll
-        for (int gi = 0; gi < MAXG; ++gi) { acc0[gi] = 0.f; acc1[gi] = 0.f; }
-#pragma unroll (CP <= 32 ? CP : 16)
-        for (int cc = 0; cc < CP; ++cc) {
-            const int c = split * CP + cc;
-            unsigned w2;
-            if constexpr (kPrefetchW) w2 = wpre[cc];
-            else w2 = *(const unsigned *)(Wqkv + (size_t)c * 3 * C + 2 * oc);
-            const float w0 = bf16_lo(w2), w1 = bf16_hi(w2);
-#pragma unroll
-            for (int gi = 0; gi < MAXG; ++gi)
-                if (gi < ng) {
-                    const float x = xr[gi * C + c];
-                    acc0[gi] = fmaf(x, w0, acc0[gi]);
-                    acc1[gi] = fmaf(x, w1, acc1[gi]);
-                }
-        }
-#pragma unroll
-        for (int gi = 0; gi < MAXG; ++gi) {
-            part[(split * MAXG + gi) * 2 * C + 2 * oc] = acc0[gi];
-            part[(split * MAXG + gi) * 2 * C + 2 * oc + 1] = acc1[gi];
-        }
-    }
-    __syncthreads();
-    for (int e = tid; e < ng * 2 * C; e += 256) {
-        const int gi = e / (2 * C), o = e % (2 * C);
-        float v = part[gi * 2 * C + o];
-#pragma unroll
-        for (int sp = 1; sp < SPL; ++sp) v += part[(sp * MAXG + gi) * 2 * C + o];
-        const int r = r0 + gi;
-        if (o < C) Qr[((size_t)b * D.R + r) * C + o] = v;
-        else KrT[((size_t)b * C + (o - C)) * kRpad + r] = v;
+        Xr[((size_t)b * D.R + r0 + gi) * C + c] = s / (float)D.n;
     }
 }
 
-// Pooling kernel for wide channels (C >= 128): same results layout as k_pool_qk, but the
-// region-level projection [Q^r | K^r] = xr [Wq | Wk] runs on the matrix cores.  The
-// float32 region means are split exactly into three bf16 terms (x = hi + mid + lo: 3 x 8
-// mantissa bits), each term is multiplied by the (bf16) weights with float32
-// accumulation, so the products are those of the float32 computation up to summation
-// order.  Needs the transposed weights WT, i.e. runs after k_prep_weights.
-// Workgroup (b, group) handles 16 consecutive regions (the 16 MFMA columns).
-template <int C>
-__global__ __launch_bounds__(256) void k_pool_qk_mfma(const bf16_t *__restrict__ X,
-                                                      const bf16_t *__restrict__ WT,
-                                                      float *__restrict__ Qr, float *__restrict__ KrT,
-                                                      Dims D)
+// Exact split of 8 float32 values into three bf16 terms each (x = hi + mid + lo: 3 x 8
+// mantissa bits), as MFMA operands.
+__device__ __forceinline__ void split3(const float (&x)[8], bf16x8 (&t)[3])
 {
-    constexpr int G = 16, CH = C / 8, KS = C / 32, XS = C + 8;
-    __shared__ float part[G * C];                                   // per-(region, channel) sums
-    __shared__ __attribute__((aligned(16))) bf16_t xs[3][G * XS];   // hi / mid / lo terms
-    const int tid = threadIdx.x;
-    const int groups = (D.R + G - 1) / G;
-    const int b = blockIdx.x / groups, r0 = (blockIdx.x % groups) * G;
-    const int ng = min(G, D.R - r0);
-    const float rw_inv = 1.0f / (float)D.rw;
-
-    // region sums: one thread per (region, 8-channel chunk), tokens in row-major order
-    for (int item = tid; item < G * CH; item += 256) {
-        const int gi = item / CH, cc = item % CH;
-        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (gi < ng) {
-            const int r = r0 + gi;
-            const bf16_t *base = X + (((size_t)b * D.H + (r / D.S) * D.rh) * D.W + (r % D.S) * D.rw) * C + cc * 8;
-#pragma unroll 4
-            for (int slot = 0; slot < D.n; ++slot) {
-                const int ry = fast_div(slot, rw_inv), rx = slot - ry * D.rw;
-                const u32x4 v = *(const u32x4 *)(base + ((size_t)ry * D.W + rx) * C);
+    float h[8], m[8], l[8];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    acc[2 * e] += bf16_lo(v[e]);
-                    acc[2 * e + 1] += bf16_hi(v[e]);
-                }
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) part[gi * C + cc * 8 + e] = acc[e];
+    for (int e = 0; e < 8; ++e) {
+        h[e] = bf16_to_f32(f32_to_bf16(x[e]));
+        const float r1 = x[e] - h[e];
+        m[e] = bf16_to_f32(f32_to_bf16(r1));
+        l[e] = r1 - m[e];
     }
-    __syncthreads();
-    // means and their exact three-term bf16 split (rows >= ng are zero)
-    for (int e = tid; e < G * C; e += 256) {
-        const int gi = e / C, c = e % C;
-        const float x = part[e] / (float)D.n;
-        const float h = bf16_to_f32(f32_to_bf16(x));
-        const float r1 = x - h;
-        const float m = bf16_to_f32(f32_to_bf16(r1));
-        const float r2 = r1 - m;
-        xs[0][gi * XS + c] = f32_to_bf16(x);
-        xs[1][gi * XS + c] = f32_to_bf16(r1);
-        xs[2][gi * XS + c] = f32_to_bf16(r2);
-    }
-    __syncthreads();
-
-    const int wave = tid / kWave, lane = tid % kWave;
-    const int g = lane / 16, i = lane % 16;
-    bf16x8 xf[3][KS];   // B operands: column i = region r0 + i, k = input channel
-#pragma unroll
-    for (int t = 0; t < 3; ++t)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) xf[t][ks] = *(const bf16x8 *)(xs[t] + i * XS + 32 * ks + 8 * g);
-    // output-channel tiles of [Wq | Wk]: 2C / 16 tiles, dealt round-robin to the wavefronts
-    for (int ct = wave; ct < 2 * C / 16; ct += 4) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 wf = *(const bf16x8 *)(WT + (size_t)(16 * ct + i) * C + 32 * ks + 8 * g);
-            acc = mfma16(wf, xf[2][ks], acc);    // smallest term first
-            acc = mfma16(wf, xf[1][ks], acc);
-            acc = mfma16(wf, xf[0][ks], acc);
-        }
-        if (i < ng) {   // rows: output channels 16 ct + 4 g + j; column: region r0 + i
-            const int o = 16 * ct + 4 * g, r = r0 + i;
-            if (o < C) {
-                *(f32x4 *)(Qr + ((size_t)b * D.R + r) * C + o) = acc;
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) KrT[((size_t)b * C + (o - C + j)) * kRpad + r] = acc[j];
-            }
-        }
-    }
+    t[0] = pack8(h);
+    t[1] = pack8(m);
+    t[2] = pack8(l);
 }
 
-// A^r = Q^r (K^r)^T (Eq. 4) and its row-wise top-k index I^r (Eq. 5) for every region of
-// every image.  A wavefront computes kRouteRows rows: lane j holds entry j of each row, a
-// column of K^r^T is loaded once per lane and used for all its rows, the Q^r values are
-// the same for all lanes (scalar loads).  No LDS, no barriers.
-constexpr int kRouteRows = 2;
+// Region-level projections, A^r = Q^r (K^r)^T (Eq. 4) and its row-wise top-k index I^r
+// (Eq. 5).  Workgroup (b, rt) owns the 16 regions 16 rt .. 16 rt + 15 of image b as
+// queries (R <= 64).  Q^r = Xr Wq for those rows and K^r = Xr Wk for all regions of the
+// image run on the matrix cores: the float32 means are split exactly into three bf16
+// terms (once per workgroup, staged in LDS in chunks of 64 channels), each term
+// is multiplied by the bf16 weights with float32 accumulation, so the products are those
+// of the float32 computation.  Wavefront w owns output-channel tiles w, w + 4, ..; the
+// results go to LDS (K^r transposed), then wavefront w forms rows 4 w .. 4 w + 3 of A^r
+// in float32, lane j holding entry j, and ranks them.
+constexpr int kRouteKS = 68;   // floats per channel of the transposed K^r tile in LDS
 
 template <int C>
-__global__ __launch_bounds__(256) void k_route(const float *__restrict__ Qr,
-                                               const float *__restrict__ KrT,
+struct RouteSmem {
+    static constexpr int CK = 64;                       // channels per staged chunk
+    static constexpr int XP = CK + 16;                  // bf16 per row of a staged term
+    static constexpr int QS = C + 4;                    // floats per row of the Q^r tile
+    static constexpr size_t xs_bytes = (size_t)3 * 64 * XP * 2;
+    static constexpr size_t kq_bytes = ((size_t)C * kRouteKS + 16 * QS) * 4;   // takes the place of the terms
+    static constexpr size_t bytes = xs_bytes > kq_bytes ? xs_bytes : kq_bytes;
+};
+
+template <int C>
+__global__ __launch_bounds__(256) void k_route(const float *__restrict__ Xr,
+                                               const bf16_t *__restrict__ WT,
                                                int32_t *__restrict__ Ir, float *__restrict__ Ar,
                                                Dims D)
 {
-    constexpr int NR = kRouteRows, NB = 32;     // NB: channels per batch of loads
-    const int groups = (D.R + 4 * NR - 1) / (4 * NR);
-    const int b = blockIdx.x / groups;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), j = threadIdx.x % kWave;
-    const int r0 = ((blockIdx.x % groups) * 4 + wave) * NR;
-    if (r0 >= D.R) return;
-    const float *kt = KrT + (size_t)b * C * kRpad + j;
-    const float *q[NR];
+    typedef RouteSmem<C> SM;
+    constexpr int CK = SM::CK, XP = SM::XP, QS = SM::QS, KSC = CK / 32, NCW = C / 64;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *xs = (bf16_t *)smem;                  // [3][64][XP]
+    float *Kt = (float *)smem;                    // [C][kRouteKS]
+    float *Qs = Kt + C * kRouteKS;                // [16][QS]
+    const int groups = (D.R + 15) / 16;
+    const int b = blockIdx.x / groups, myrt = blockIdx.x % groups;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int g = lane / 16, i = lane % 16;
+    const int nrt = (D.R + 15) / 16;              // region tiles that exist
+    // staging: thread (row, quarter) splits CK / 4 consecutive channels of one region
+    const int srow = threadIdx.x / 4, sq = threadIdx.x % 4;
+    const float *xsrc = Xr + ((size_t)b * D.R + min(srow, D.R - 1)) * C + sq * (CK / 4);   // rows past R repeat the last region; never used
+
+    f32x4 ak[4][NCW], aq[NCW];
 #pragma unroll
-    for (int r = 0; r < NR; ++r) {
-        const int row = r0 + r < D.R ? r0 + r : D.R - 1;     // rows past R repeat the last one; not written
-        q[r] = Qr + ((size_t)b * D.R + row) * C;
+    for (int cw = 0; cw < NCW; ++cw) {
+        aq[cw] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) ak[rt][cw] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    float a[NR];
+#pragma unroll 1
+    for (int c0 = 0; c0 < C; c0 += CK) {
+        // requests of this chunk: the means to split and this wavefront's weight fragments
+        f32x4 xv[CK / 16];
 #pragma unroll
-    for (int r = 0; r < NR; ++r) a[r] = 0.f;
-    for (int c0 = 0; c0 < C; c0 += NB) {
-        float kv[NB];
+        for (int e = 0; e < CK / 16; ++e) xv[e] = *(const f32x4 *)(xsrc + c0 + 4 * e);
+        bf16x8 wqf[KSC][NCW], wkf[KSC][NCW];
 #pragma unroll
-        for (int c = 0; c < NB; ++c) kv[c] = kt[(size_t)(c0 + c) * kRpad];
+        for (int ksl = 0; ksl < KSC; ++ksl)
 #pragma unroll
-        for (int r = 0; r < NR; ++r)
+            for (int cw = 0; cw < NCW; ++cw) {
+                const size_t off = (size_t)(16 * (wave + 4 * cw) + i) * C + c0 + 32 * ksl + 8 * g;
+                wqf[ksl][cw] = *(const bf16x8 *)(WT + off);
+                wkf[ksl][cw] = *(const bf16x8 *)(WT + (size_t)C * C + off);
+            }
+        if (c0) __syncthreads();                  // the previous chunk's terms have been read
 #pragma unroll
-            for (int c = 0; c < NB; ++c) a[r] = fmaf(q[r][c0 + c], kv[c], a[r]);
+        for (int e0 = 0; e0 < CK / 4; e0 += 8) {
+            const f32x4 lo = xv[e0 / 4], hi = xv[e0 / 4 + 1];
+            const float x[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            bf16x8 t[3];
+            split3(x, t);
+#pragma unroll
+            for (int q = 0; q < 3; ++q) *(bf16x8 *)(xs + (q * 64 + srow) * XP + sq * (CK / 4) + e0) = t[q];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ksl = 0; ksl < KSC; ++ksl) {
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt) {
+                if (rt >= nrt) break;
+                bf16x8 t[3];
+#pragma unroll
+                for (int q = 0; q < 3; ++q)
+                    t[q] = *(const bf16x8 *)(xs + (q * 64 + 16 * rt + i) * XP + 32 * ksl + 8 * g);
+#pragma unroll
+                for (int cw = 0; cw < NCW; ++cw) {
+                    ak[rt][cw] = mfma16(wkf[ksl][cw], t[2], ak[rt][cw]);    // smallest term first
+                    ak[rt][cw] = mfma16(wkf[ksl][cw], t[1], ak[rt][cw]);
+                    ak[rt][cw] = mfma16(wkf[ksl][cw], t[0], ak[rt][cw]);
+                }
+                if (rt == myrt) {
+#pragma unroll
+                    for (int cw = 0; cw < NCW; ++cw) {
+                        aq[cw] = mfma16(wqf[ksl][cw], t[2], aq[cw]);
+                        aq[cw] = mfma16(wqf[ksl][cw], t[1], aq[cw]);
+                        aq[cw] = mfma16(wqf[ksl][cw], t[0], aq[cw]);
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();   // the terms have been read: K^r and Q^r take their place
+    // accumulators hold [channel 16 ct + 4 g + jj][region 16 rt + i]
+#pragma unroll
+    for (int cw = 0; cw < NCW; ++cw) {
+        const int ch = 16 * (wave + 4 * cw) + 4 * g;
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) Kt[(ch + jj) * kRouteKS + 16 * rt + i] = ak[rt][cw][jj];
+        *(f32x4 *)(Qs + i * QS + ch) = aq[cw];
+    }
+    __syncthreads();
+
+    float a[4] = {0.f, 0.f, 0.f, 0.f};
+    const float *qrow = Qs + 4 * wave * QS;
+#pragma unroll 4
+    for (int c = 0; c < C; c += 4) {
+        float kv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) kv[e] = Kt[(c + e) * kRouteKS + lane];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const f32x4 q4 = *(const f32x4 *)(qrow + rr * QS + c);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) a[rr] = fmaf(q4[e], kv[e], a[rr]);
+        }
     }
 #pragma unroll
-    for (int r = 0; r < NR; ++r) {
-        if (r0 + r >= D.R) break;
-        const size_t row = (size_t)b * D.R + r0 + r;
-        if (Ar && j < D.R) Ar[row * D.R + j] = a[r];
-        wave_topk(a[r], j, D.R, D.k, Ir + row * D.k);
+    for (int rr = 0; rr < 4; ++rr) {
+        const int r = 16 * myrt + 4 * wave + rr;
+        if (r >= D.R) break;
+        const size_t row = (size_t)b * D.R + r;
+        if (Ar && lane < D.R) Ar[row * D.R + lane] = a[rr];
+        wave_topk(a[rr], lane, D.R, D.k, Ir + row * D.k);
     }
 }
 
@@ -798,7 +767,7 @@ void k_fused(AttnArgs A, Dims D)
 // ---------------------------------------------------------------------------
 struct MfmaWs {
     bf16_t *q, *k, *v, *o, *wt, *wot, *wa, *wf;
-    float *qr, *krt;
+    float *xr;
     void *route;
     int32_t *ir;
     size_t bytes;
@@ -836,50 +805,11 @@ MfmaWs carve(const Dims &D, void *ws)
     w.wot = (bf16_t *)take((size_t)D.C * D.C * 2);
     w.wa = (bf16_t *)take((size_t)D.C * kLceOperandElems * 2);
     w.wf = (bf16_t *)take(D.C == 64 ? (size_t)kFusedFragElems * 2 : 0);
-    w.qr = (float *)take((size_t)D.B * D.R * D.C * sizeof(float));
-    w.krt = (float *)take((size_t)D.B * D.C * kRpad * sizeof(float));
+    w.xr = (float *)take((size_t)D.B * D.R * D.C * sizeof(float));
     w.route = take(fast_route_ok(D) ? 0 : valu_route_scratch_bytes(D));
     w.ir = (int32_t *)take((size_t)D.B * D.R * D.k * sizeof(int32_t));
     w.bytes = off;
     return w;
-}
-
-template <int C>
-void launch_pool_qk(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *Wo,
-                    const bf16_t *Wlce, const MfmaWs &w, bool pool, bool prep, hipStream_t st)
-{
-    if constexpr (C >= 128) {
-        // wide channels: transpose the weights first, then pool + project on the matrix cores
-        // (pool && !prep happens in bra_route: only WT's Wq|Wk rows are needed, Wo may be NULL)
-        {
-            ProfScope ps(st, K_MFMA_PREP);
-            const int total = prep ? prep_total(C) : 3 * C * C;
-            hipLaunchKernelGGL(k_prep_weights, dim3((total + 255) / 256), dim3(256), 0, st, Wqkv, Wo, Wlce,
-                               w.wt, w.wot, w.wa, w.wf, C, total);
-        }
-        if (pool) {
-            ProfScope ps(st, K_MFMA_POOL_QK);
-            hipLaunchKernelGGL(k_pool_qk_mfma<C>, dim3(D.B * ((D.R + 15) / 16)), dim3(256), 0, st, X, w.wt,
-                               w.qr, w.krt, D);
-        }
-        return;
-    }
-    int G = 4;                                                     // regions per workgroup
-    if (const char *e = getenv("BRA_POOL_GROUP")) { int v = atoi(e); if (v >= 1 && v <= kPoolMaxGroup) G = v; }
-    const int pool_blocks = pool ? D.B * ((D.R + G - 1) / G) : 0;
-    const int prep_blocks = prep ? (prep_total(C) + 255) / 256 : 0;
-    if (pool_blocks + prep_blocks == 0) return;
-    ProfScope ps(st, K_MFMA_POOL_QK);
-    hipLaunchKernelGGL(k_pool_qk<C>, dim3(pool_blocks + prep_blocks), dim3(256), 0, st, X, Wqkv, Wo,
-                       Wlce, w.qr, w.krt, w.wt, w.wot, w.wa, w.wf, D, pool_blocks, G);
-}
-
-template <int C>
-void launch_route(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, hipStream_t st)
-{
-    ProfScope ps(st, K_MFMA_ROUTE_ROWS);
-    const int groups = (D.R + 4 * kRouteRows - 1) / (4 * kRouteRows);
-    hipLaunchKernelGGL(k_route<C>, dim3(D.B * groups), dim3(256), 0, st, w.qr, w.krt, Ir, Ar_opt, D);
 }
 
 // More than 64 KB of dynamic LDS needs an opt-in, once per kernel.
@@ -894,6 +824,48 @@ bool lds_opt_in(K kernel, bool &done)
     return true;
 }
 
+// Regions per pooling workgroup: about 8 loads of 16 bytes per thread, at most 256
+// (region, 8-channel chunk) pairs, and enough workgroups to fill the chip.
+int pool_group(const Dims &D)
+{
+    if (const char *e = getenv("BRA_POOL_GROUP")) {              // benchmarking aid
+        const int v = atoi(e);
+        if (v >= 1 && v <= kPoolMaxGroup && v * (D.C / 8) <= 256) return v;
+    }
+    const int chunks = D.n * (D.C / 8);
+    int G = 2048 / chunks;
+    const int cap = 256 / (D.C / 8) < kPoolMaxGroup ? 256 / (D.C / 8) : kPoolMaxGroup;
+    G = G < 1 ? 1 : (G > cap ? cap : G);
+    while (G > 1 && (long)D.B * ((D.R + G - 1) / G) < 512) G /= 2;
+    return G;
+}
+
+// Pooling (if `pool`) and weight preparation (`prep_elems` leading prep elements) in one launch.
+template <int C>
+void launch_pool(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *Wo,
+                 const bf16_t *Wlce, const MfmaWs &w, bool pool, int prep_elems, hipStream_t st)
+{
+    const int G = pool_group(D);
+    const int pool_blocks = pool ? D.B * ((D.R + G - 1) / G) : 0;
+    const int prep_blocks = (prep_elems + 255) / 256;
+    if (pool_blocks + prep_blocks == 0) return;
+    ProfScope ps(st, K_MFMA_POOL_QK);
+    hipLaunchKernelGGL(k_pool<C>, dim3(pool_blocks + prep_blocks), dim3(256), 0, st, X, Wqkv, Wo, Wlce,
+                       w.xr, w.wt, w.wot, w.wa, w.wf, D, pool_blocks, G, prep_elems);
+}
+
+template <int C>
+int launch_route(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, hipStream_t st)
+{
+    static bool opted = false;
+    if (!lds_opt_in(k_route<C>, opted)) return BRA_ERR_LAUNCH;
+    const size_t smem = RouteSmem<C>::bytes;
+    ProfScope ps(st, K_MFMA_ROUTE_ROWS);
+    hipLaunchKernelGGL(k_route<C>, dim3(D.B * ((D.R + 15) / 16)), dim3(256), smem, st, w.xr, w.wt, Ir,
+                       Ar_opt, D);
+    return BRA_OK;
+}
+
 bool attn_big_ok(const Dims &D);
 
 template <int C>
@@ -903,10 +875,11 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
 {
     const int32_t *Ir_src = Ir_in_opt;
     if (fast_route_ok(D)) {
-        launch_pool_qk<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/!Ir_in_opt, /*prep=*/true, st);
+        launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/!Ir_in_opt, prep_total(C), st);
         if (!Ir_in_opt) {
             int32_t *dst = Ir_out_opt ? Ir_out_opt : w.ir;
-            launch_route<C>(D, w, dst, nullptr, st);
+            const int rc = launch_route<C>(D, w, dst, nullptr, st);
+            if (rc != BRA_OK) return rc;
             Ir_src = dst;
         }
     } else {
@@ -972,8 +945,9 @@ template <int C>
 int route_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, int32_t *Ir, float *Ar_opt,
             const MfmaWs &w, hipStream_t st)
 {
-    launch_pool_qk<C>(D, X, Wqkv, nullptr, nullptr, w, /*pool=*/true, /*prep=*/false, st);
-    launch_route<C>(D, w, Ir, Ar_opt, st);
+    launch_pool<C>(D, X, Wqkv, nullptr, nullptr, w, /*pool=*/true, /*prep: Wq^T, Wk^T*/ 2 * C * C, st);
+    const int rc = launch_route<C>(D, w, Ir, Ar_opt, st);
+    if (rc != BRA_OK) return rc;
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 

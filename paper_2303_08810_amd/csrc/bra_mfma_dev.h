@@ -70,19 +70,53 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const bf16_t *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)p);
 }
 
+// max(x, x of the lane that the DPP control CTRL names), for the rows (of 16 lanes) in
+// the mask ROWS; the other rows keep x.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ uint32_t dpp_umax(uint32_t x)
+{
+    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, ROWS, 0xf, false);
+    return o > x ? o : x;
+}
+
+// Maximum of an unsigned value over the 64 lanes of a wavefront (DPP reduction: within
+// quads, half rows, rows of 16 lanes, then across the rows), returned to every lane.
+__device__ __forceinline__ uint32_t wave_umax(uint32_t v)
+{
+    v = dpp_umax<0xB1, 0xf>(v);     // quad_perm [1,0,3,2]
+    v = dpp_umax<0x4E, 0xf>(v);     // quad_perm [2,3,0,1]
+    v = dpp_umax<0x141, 0xf>(v);    // row_half_mirror
+    v = dpp_umax<0x140, 0xf>(v);    // row_mirror: every lane of a row holds the row's maximum
+    v = dpp_umax<0x142, 0xa>(v);    // row_bcast15: rows 1, 3 take in rows 0, 2
+    v = dpp_umax<0x143, 0xc>(v);    // row_bcast31: rows 2, 3 take in rows 0, 1
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, kWave - 1);
+}
+
 // Indices of the k largest entries of one row of A^r (Eq. 5), the row spread over the
 // 64 lanes of a wavefront (lane j holds entry j; entries j >= R do not exist): larger
-// value first, equal values by smaller index, NaN as -inf.  Each lane forms a 64-bit key
-// (value mapped to an unsigned integer of the same order, then 63 - j) that is larger for
-// whatever comes first; a lane's position in the order is the number of larger keys,
-// counted with one lane broadcast per other lane.  The lane at position p < k writes its
-// index to out[p].
+// value first, equal values by smaller index, NaN as -inf.  The values are mapped to
+// unsigned integers of the same order (never zero).  Small k: k rounds of wavefront
+// maximum, lowest lane that holds it, remove it.  Large k: each lane forms a 64-bit key
+// (mapped value, then 63 - j) that is larger for whatever comes first and counts the
+// larger keys with one lane broadcast per other lane; the lane at position p < k writes
+// its index to out[p].
 __device__ __forceinline__ void wave_topk(float v, int j, int R, int k, int32_t *out)
 {
     if (!(v == v) || j >= R) v = -INFINITY;
     v += 0.0f;                                              // -0 and +0 are equal values
     uint32_t u = __builtin_bit_cast(uint32_t, v);
-    u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;
+    u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;             // -inf -> 0x007fffff, the smallest
+    if (k <= 20) {
+        bool avail = j < R;
+        for (int p = 0; p < k; ++p) {
+            const uint32_t m = wave_umax(avail ? u : 0u);
+            const uint64_t holders = __ballot(avail && u == m);
+            const int best = __builtin_ctzll(holders);      // k <= R: some entry is still available
+            if (j == 0) out[p] = best;
+            if (j == best) avail = false;
+        }
+        return;
+    }
     const uint64_t key = ((uint64_t)u << 32) | (uint32_t)(kWave - 1 - j);
     int before = 0;
 #pragma unroll
