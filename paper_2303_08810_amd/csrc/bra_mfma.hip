@@ -800,7 +800,7 @@ MfmaWs carve(const Dims &D, void *ws)
     w.q = (bf16_t *)take(tok * D.C * 2);
     w.k = (bf16_t *)take(tok * D.C * 2);
     w.v = (bf16_t *)take(tok * D.C * 2);
-    w.o = (bf16_t *)take(small_supported(D) ? tok * D.C * 2 : 0);
+    w.o = (bf16_t *)take(small_supported(D) ? small_scratch_bytes(D) : 0);
     w.wt = (bf16_t *)take((size_t)3 * D.C * D.C * 2);
     w.wot = (bf16_t *)take((size_t)D.C * D.C * 2);
     w.wa = (bf16_t *)take((size_t)D.C * kLceOperandElems * 2);

@@ -421,6 +421,7 @@ __device__ __forceinline__ int swizzled_block()
 // Small-region pipeline tail (bra_mfma_small.hip): per-(region, head) attention into O,
 // then LCE + output projection over row tiles.  A.Q/K/V, routing fields, Wlce, WoT, Y set.
 bool small_supported(const Dims &D);
+size_t small_scratch_bytes(const Dims &D);
 int launch_small(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st);
 
 }  // namespace bra

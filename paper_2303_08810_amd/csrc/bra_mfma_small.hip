@@ -1,13 +1,15 @@
-// Matrix-core kernels for small regions (n = 1, 2, 4, 8 or 16 tokens per region).
+// Matrix-core kernel for small regions (n = 1, 2, 4, 8 or 16 tokens per region).
 //
 // With so few queries per region a query tile cannot fill a 64-row workgroup tile from
-// one region, and every (region, head) pair has its own routed key set (Eq. 6).  So the
-// attention runs per (region, head) in one wavefront: the n queries occupy the first n
-// of the 16 query columns of the 16x16x32 MFMA tiles, keys are read by index straight
-// from the projected map into the A operands, values go through a wavefront-private LDS
-// tile for the transposing read.  The LCE and the output projection (Eq. 7, Eq. 2)
-// need whole spatial neighbourhoods and all heads, so they run in a second kernel over
-// tiles of full-width image rows.
+// one region, and every (region, head) pair has its own routed key set (Eq. 6).  So one
+// workgroup handles one (image, region) and the attention runs per head in one
+// wavefront: the n queries occupy the first n of the 16 query columns of the 16x16x32
+// MFMA tiles, keys are read by index straight from the projected map into the A
+// operands, values go through a wavefront-private LDS tile for the transposing read.
+// For regions of 16 tokens the same workgroup then adds the LCE of its tokens (Eq. 7; 5x5
+// depth-wise correlation of V over the region plus a 2-token halo, staged in LDS) and
+// applies W^o (Eq. 2), so the attention output never travels through memory (k_small).
+// Smaller regions use two kernels (k_attn_small, k_lce_wo).
 #include "bra_mfma_dev.h"
 
 namespace bra {
@@ -16,9 +18,205 @@ using namespace mfma;
 
 namespace {
 
-constexpr int kVS = 40;   // bf16 elements per row of the private V tile (32 + 16-byte pad)
+constexpr int kVS = 40;     // bf16 elements per row of the private V tile (32 + 16-byte pad)
+constexpr int kLTP = 20;    // floats per channel of the LCE tile [C][tokens] (n <= 16)
+constexpr int kMaxLceTasks = 2;   // (row, 4-token segment, channel pair) tasks per thread
+
+// LDS map: the wavefront-private V tiles come first; the LCE tile takes their place once
+// every wavefront has finished its heads.
+template <int C>
+struct SmallSmem {
+    static constexpr int CS = C + 8;
+    static constexpr size_t vw_bytes = (size_t)4 * 64 * kVS * 2;
+    static constexpr size_t lt_bytes = (size_t)C * kLTP * 4;
+    static constexpr size_t v_off = 0;
+    static constexpr size_t o_off = vw_bytes > lt_bytes ? vw_bytes : lt_bytes;   // [16][CS] bf16: O = attention + LCE
+    static constexpr size_t h_off = o_off + (size_t)16 * CS * 2;                 // V halo tile [hrows][CS] bf16
+    static size_t bytes(int hrows) { return h_off + (size_t)hrows * CS * 2; }
+};
+
+template <int C>
+__global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
+{
+    typedef SmallSmem<C> SM;
+    constexpr int HEADS = C / 32, HPW = (HEADS + 3) / 4, CS = SM::CS, KS = C / 32, CH = C / 8;
+    constexpr int NBH = 2;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *Vw = (bf16_t *)(smem + SM::v_off);
+    float *Lt = (float *)(smem + SM::v_off);
+    bf16_t *Ob = (bf16_t *)(smem + SM::o_off);
+    bf16_t *Hs = (bf16_t *)(smem + SM::h_off);
+
+    const int wid = swizzled_block();
+    if (wid >= A.total) return;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int g = lane / 16, i = lane % 16;
+    const int b = wid / D.R, reg = wid % D.R;
+    const size_t img_off = (size_t)b * D.N * C;
+    const int n = D.n, kn = D.kn;
+    const float rw_inv = 1.0f / (float)D.rw;
+    const int y0 = (reg / D.S) * D.rh, x0 = (reg % D.S) * D.rw;
+
+    const int32_t *irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
+    if (A.Ir_out && A.Ir_out != A.Ir_src)
+        for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
+
+    // V over the region and its halo -> LDS (needed only after the attention)
+    const int hw = D.rw + 4, hrows = (D.rh + 4) * hw;
+    {
+        const float hw_inv = 1.0f / (float)hw;
+        for (int first = 0; first < hrows * CH; first += 256 * NBH) {
+            u32x4 hreg[NBH];
+            tile_load<C, NBH>(hreg, A.V + img_off, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, first);
+            tile_store<C, CS, NBH>(Hs, hreg, hrows, first);
+        }
+    }
+
+    // query token of this lane's column (columns >= n repeat the last query; never stored)
+    const int qs = i < n ? i : n - 1;
+    const int qy = fast_div(qs, rw_inv);
+    const size_t qtok = (size_t)(y0 + qy) * D.W + x0 + qs - qy * D.rw;
+    bf16_t *vw = Vw + wave * 64 * kVS;
+
+    f32x4 oacc[HPW][2];     // normalised attention output of this wavefront's heads
+#pragma unroll
+    for (int hh = 0; hh < HPW; ++hh) {
+        const int h = wave + 4 * hh;
+        oacc[hh][0] = oacc[hh][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (h >= HEADS) break;
+        const bf16x8 qf = *(const bf16x8 *)(A.Q + img_off + qtok * C + 32 * h + 8 * g);
+        SoftmaxState<1> st;
+        st.init();
+        for (int k0 = 0; k0 < kn; k0 += 64) {
+            // key 16 t + i of this block: A-operand row i of tile t
+            bf16x8 kf[4];
+            u32x4 vr[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                int key = k0 + 16 * t + i;
+                if (key >= kn) key = kn - 1;
+                const int j = irp[key >> log2n], slot = key & (n - 1);
+                const int sy = fast_div(slot, rw_inv);
+                const size_t tok = (size_t)((j / D.S) * D.rh + sy) * D.W + (j % D.S) * D.rw + slot - sy * D.rw;
+                const size_t off = img_off + tok * C + 32 * h + 8 * g;
+                kf[t] = *(const bf16x8 *)(A.K + off);
+                vr[t] = *(const u32x4 *)(A.V + off);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) *(u32x4 *)(vw + (16 * t + i) * kVS + 8 * g) = vr[t];
+            f32x4 s[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) s[t] = mfma16(kf[t], qf, f32x4{0.f, 0.f, 0.f, 0.f});
+            if (k0 + 64 > kn) {   // ragged last block: keys past the end do not count
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj)
+                        if (k0 + 16 * t + 4 * g + jj >= kn) s[t][jj] = -INFINITY;
+            }
+            softmax_pv_block<kVS>(vw, s, st, 0, A.c_exp, g, i);
+        }
+        const float inv = 1.0f / st.l[0];
+        oacc[hh][0] = st.acc[0][0] * inv;
+        oacc[hh][1] = st.acc[0][1] * inv;
+    }
+
+    // LCE (Eq. 7) of the region's tokens: task = (row r, 4-token segment, channel pair);
+    // a thread keeps its channel pair for all its tasks, so its 2 x 25 weights stay in
+    // registers.
+    const int cp_n = C / 2, segs = (D.rw + 3) / 4;
+    const int tasks = D.rh * segs * cp_n;
+    const int cpair = threadIdx.x % cp_n;
+    unsigned wl[25];        // [W(c, 0..24) | W(c + 1, 0..24)] as 25 packed pairs
+#pragma unroll
+    for (int e = 0; e < 25; ++e) wl[e] = *(const unsigned *)(A.Wlce + (size_t)cpair * 50 + 2 * e);
+    auto tap = [&](int ch, int t) {   // weight of tap t of channel c + ch
+        const int e = 25 * ch + t;
+        return (e & 1) ? bf16_hi(wl[e / 2]) : bf16_lo(wl[e / 2]);
+    };
+    float lce[kMaxLceTasks][2][4];
+    __syncthreads();        // the halo tile is complete
+#pragma unroll
+    for (int tk = 0; tk < kMaxLceTasks; ++tk) {
+        const int task = threadIdx.x + 256 * tk;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) lce[tk][0][x] = lce[tk][1][x] = 0.f;
+        if (task < tasks) {
+            const int seg = (task / cp_n) % segs, r = task / (cp_n * segs);
+#pragma unroll
+            for (int ky = 0; ky < 5; ++ky) {
+                float v0[8], v1[8];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    const int hx = min(seg * 4 + x, hw - 1);    // a ragged segment re-reads the last column; unused
+                    const unsigned u = *(const unsigned *)(Hs + ((r + ky) * hw + hx) * CS + 2 * cpair);
+                    v0[x] = bf16_lo(u);
+                    v1[x] = bf16_hi(u);
+                }
+#pragma unroll
+                for (int kx = 0; kx < 5; ++kx) {
+                    const float w0 = tap(0, ky * 5 + kx), w1 = tap(1, ky * 5 + kx);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        lce[tk][0][x] = fmaf(w0, v0[x + kx], lce[tk][0][x]);
+                        lce[tk][1][x] = fmaf(w1, v1[x + kx], lce[tk][1][x]);
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();        // every wavefront is done with its private V tile
+#pragma unroll
+    for (int tk = 0; tk < kMaxLceTasks; ++tk) {
+        const int task = threadIdx.x + 256 * tk;
+        if (task < tasks) {
+            const int seg = (task / cp_n) % segs, r = task / (cp_n * segs);
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                if (seg * 4 + x < D.rw) {
+                    const int tok = r * D.rw + seg * 4 + x;
+                    Lt[(2 * cpair) * kLTP + tok] = lce[tk][0][x];
+                    Lt[(2 * cpair + 1) * kLTP + tok] = lce[tk][1][x];
+                }
+        }
+    }
+    __syncthreads();
+    // O = attention + LCE, rounded to bf16 once: rows of the B operand of W^o
+#pragma unroll
+    for (int hh = 0; hh < HPW; ++hh) {
+        const int h = wave + 4 * hh;
+        if (h >= HEADS) break;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+            const int ch = 32 * h + 16 * dt + 4 * g;
+            f32x4 o = oacc[hh][dt];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) o[jj] += Lt[(ch + jj) * kLTP + qs];
+            *(u32x2 *)(Ob + i * CS + ch) = pack4(o);     // rows >= n repeat the last query
+        }
+    }
+    __syncthreads();
+    // Y^T = Wo^T O^T: wavefront w owns output-channel tiles w, w + 4, ..
+    bf16x8 of[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) of[ks] = *(const bf16x8 *)(Ob + i * CS + 32 * ks + 8 * g);
+    bf16_t *yrow = A.Y + img_off + qtok * C;
+#pragma unroll
+    for (int ct = wave; ct < C / 16; ct += 4) {
+        f32x4 ya = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 wf = *(const bf16x8 *)(A.WoT + (size_t)(16 * ct + i) * C + 32 * ks + 8 * g);
+            ya = mfma16(wf, of[ks], ya);
+        }
+        if (i < n) *(u32x2 *)(yrow + 16 * ct + 4 * g) = pack4(ya);
+    }
+}
 
 // ---------------------------------------------------------------------------
+// Two-kernel variant for regions of fewer than 16 tokens, where a workgroup per region
+// would re-read all of W^o for a handful of tokens: attention per (image, region) writes
+// O_att to memory, then the LCE and W^o run over tiles of full-width image rows.
 // One workgroup per (image, region); wavefront w handles heads w, w + 4, ...
 // O_att[b, token, head channels] = softmax(scale q K_g^T) V_g over the k n routed keys.
 template <int C>
@@ -244,17 +442,50 @@ __global__ __launch_bounds__(256) void k_lce_wo(const bf16_t *__restrict__ Oatt,
 
 int tile_rows(const Dims &D) { return 64 / D.W; }
 
+int halo_rows_small(const Dims &D) { return (D.rh + 4) * (D.rw + 4); }
+
+template <int C>
+size_t small_smem(const Dims &D) { return SmallSmem<C>::bytes(halo_rows_small(D)); }
+
 }  // namespace
+
+// One kernel per region when a region fills the 16 query columns; else two kernels.
+static bool one_kernel(const Dims &D)
+{
+    if (D.n != 16) return false;
+    return D.rh * ((D.rw + 3) / 4) * (D.C / 2) <= 256 * kMaxLceTasks;
+}
+
+template <int C>
+static size_t lce_wo_smem(const Dims &D) { return LceWoSmem<C>::bytes((tile_rows(D) + 4) * (D.W + 4)); }
 
 bool small_supported(const Dims &D)
 {
     if (D.n > 16 || (D.n & (D.n - 1)) != 0) return false;   // n = 1, 2, 4, 8, 16
-    if (D.W > 64) return false;
-    const int TH = tile_rows(D);
-    const int halo = (TH + 4) * (D.W + 4);
-    size_t smem = D.C == 64 ? LceWoSmem<64>::bytes(halo)
-                : D.C == 128 ? LceWoSmem<128>::bytes(halo) : LceWoSmem<256>::bytes(halo);
+    size_t smem;
+    if (one_kernel(D)) {
+        smem = D.C == 64 ? small_smem<64>(D) : D.C == 128 ? small_smem<128>(D) : small_smem<256>(D);
+    } else {
+        if (D.W > 64) return false;
+        smem = D.C == 64 ? lce_wo_smem<64>(D) : D.C == 128 ? lce_wo_smem<128>(D) : lce_wo_smem<256>(D);
+    }
     return smem <= (size_t)kMaxLds;
+}
+
+size_t small_scratch_bytes(const Dims &D)
+{
+    return one_kernel(D) ? 0 : (size_t)D.B * D.N * D.C * 2;     // O_att between the two kernels
+}
+
+template <typename K>
+static bool opt_in(K kernel, bool &done)
+{
+    if (done) return true;
+    if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) !=
+        hipSuccess)
+        return false;
+    done = true;
+    return true;
 }
 
 template <int C>
@@ -264,24 +495,26 @@ static int launch_small_c(const Dims &D, const AttnArgs &A0, bf16_t *O, hipStrea
     A.total = D.B * D.R;
     int log2n = 0;
     while ((1 << log2n) < D.n) ++log2n;
-    {
+    const int grid = ((A.total + 7) / 8) * 8;
+    if (one_kernel(D)) {
+        static bool opted = false;
+        if (!opt_in(k_small<C>, opted)) return BRA_ERR_LAUNCH;
         ProfScope ps(st, K_MFMA_ATTN_SMALL);
-        hipLaunchKernelGGL(k_attn_small<C>, dim3(((A.total + 7) / 8) * 8), dim3(256), 0, st, A, O, D, log2n);
+        hipLaunchKernelGGL(k_small<C>, dim3(grid), dim3(256), small_smem<C>(D), st, A, D, log2n);
+        return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
     }
     {
-        const int TH = tile_rows(D);
-        const size_t smem = LceWoSmem<C>::bytes((TH + 4) * (D.W + 4));
+        ProfScope ps(st, K_MFMA_ATTN_SMALL);
+        hipLaunchKernelGGL(k_attn_small<C>, dim3(grid), dim3(256), 0, st, A, O, D, log2n);
+    }
+    {
         static bool opted = false;
-        if (!opted) {
-            if (hipFuncSetAttribute((const void *)k_lce_wo<C>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kMaxLds) != hipSuccess)
-                return BRA_ERR_LAUNCH;
-            opted = true;
-        }
+        if (!opt_in(k_lce_wo<C>, opted)) return BRA_ERR_LAUNCH;
+        const int TH = tile_rows(D);
         const int tiles = (D.H + TH - 1) / TH;
         ProfScope ps(st, K_MFMA_LCE_WO);
-        hipLaunchKernelGGL(k_lce_wo<C>, dim3(D.B * tiles), dim3(256), smem, st, O, A.V, A.Wlce, A.WoT, A.Y,
-                           D, TH);
+        hipLaunchKernelGGL(k_lce_wo<C>, dim3(D.B * tiles), dim3(256), lce_wo_smem<C>(D), st, O, A.V, A.Wlce,
+                           A.WoT, A.Y, D, TH);
     }
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
