@@ -314,17 +314,21 @@ __global__ __launch_bounds__(256) void k_route(const float *__restrict__ Xr,
 // Q, K, V = X [Wq | Wk | Wv]  (Eq. 3).  Each wavefront owns 64 output channels of one
 // of the three matrices and keeps its weight fragments in registers; a workgroup is
 // WPB such wavefronts (blockIdx.y selects which) and walks over `tiles_per_wg`
-// consecutive tiles of 16*NU tokens, requesting the next tile's X fragments before it
-// computes the current one.  The product is formed transposed (rows = output channels,
-// columns = tokens) with the weight rows permuted so that a lane ends up with 16
-// consecutive output channels of one token, i.e. one 32-byte store.
-template <int C, int NU, int WPB>
-__global__ __launch_bounds__(64 * WPB) void k_qkv(const bf16_t *__restrict__ X,
-                                                  const bf16_t *__restrict__ WT,
-                                                  bf16_t *__restrict__ Q, bf16_t *__restrict__ K,
-                                                  bf16_t *__restrict__ V, long M, int tiles_per_wg)
+// consecutive tiles of 64 tokens.  A tile of X is fetched once per workgroup with
+// fully coalesced 16-byte loads (one tile ahead, held in registers while the current
+// tile is computed), staged in LDS, and read from there as MFMA operands by all the
+// wavefronts.  The product is formed transposed (rows = output channels, columns =
+// tokens) with the weight rows permuted so that a lane ends up with 16 consecutive
+// output channels of one token, i.e. one 32-byte store.
+template <int C, int WPB>
+__global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, 2)))
+void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ WT, bf16_t *__restrict__ Q,
+           bf16_t *__restrict__ K, bf16_t *__restrict__ V, long M, int tiles_per_wg)
 {
-    constexpr int KS = C / 32;
+    constexpr int KS = C / 32, CH = C / 8, XP = C + 16, NTH = 64 * WPB;
+    constexpr int NL = (64 * CH + NTH - 1) / NTH;       // 16-byte chunks of a tile per thread
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *xs0 = (bf16_t *)smem;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
     const int grp = blockIdx.y * WPB + wave;            // 64-channel group among 3C/64
@@ -340,32 +344,48 @@ __global__ __launch_bounds__(64 * WPB) void k_qkv(const bf16_t *__restrict__ X,
             af[tt][ks] = *(const bf16x8 *)(WT + (size_t)o * C + 32 * ks + 8 * g);
     }
 
-    const long ntiles = (M + 16 * NU - 1) / (16 * NU);
+    const long ntiles = (M + 63) / 64;
     const long tile0 = (long)blockIdx.x * tiles_per_wg;
     const long tile1 = tile0 + tiles_per_wg < ntiles ? tile0 + tiles_per_wg : ntiles;
-    auto load_tile = [&](long tile, bf16x8 (&fr)[NU][KS]) {
+    if (tile0 >= tile1) return;
+    u32x4 xr[NL];
+    auto fetch = [&](long tile) {            // rows past M repeat the last token; their results are not stored
 #pragma unroll
-        for (int u = 0; u < NU; ++u) {
-            long t = tile * 16 * NU + 16 * u + i;
+        for (int u = 0; u < NL; ++u) {
+            const int idx = threadIdx.x + NTH * u;
+            long t = tile * 64 + idx / CH;
             if (t >= M) t = M - 1;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) fr[u][ks] = *(const bf16x8 *)(X + t * C + 32 * ks + 8 * g);
+            xr[u] = u32x4{0u, 0u, 0u, 0u};
+            if (idx < 64 * CH) xr[u] = *(const u32x4 *)(X + t * C + (idx % CH) * 8);
         }
     };
-    bf16x8 cur[NU][KS], nxt[NU][KS];
-    if (tile0 < tile1) load_tile(tile0, cur);
-    for (long tile = tile0; tile < tile1; ++tile) {
-        if (tile + 1 < tile1) load_tile(tile + 1, nxt);
+    auto stage = [&](int b) {
 #pragma unroll
-        for (int u = 0; u < NU; ++u) {
+        for (int u = 0; u < NL; ++u) {
+            const int idx = threadIdx.x + NTH * u;
+            if (idx < 64 * CH) *(u32x4 *)(xs0 + (b * 64 + idx / CH) * XP + (idx % CH) * 8) = xr[u];
+        }
+    };
+    fetch(tile0);
+    stage(0);
+    __syncthreads();
+    int cur = 0;
+    for (long tile = tile0; tile < tile1; ++tile) {
+        const bool more = tile + 1 < tile1;
+        if (more) fetch(tile + 1);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            bf16x8 bf[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) bf[ks] = *(const bf16x8 *)(xs0 + (cur * 64 + 16 * u + i) * XP + 32 * ks + 8 * g);
             f32x4 acc[4];
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
-                acc[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int tt = 0; tt < 4; ++tt) acc[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) acc[tt] = mfma16(af[tt][ks], cur[u][ks], acc[tt]);
-            }
-            const long t = tile * 16 * NU + 16 * u + i;
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) acc[tt] = mfma16(af[tt][ks], bf[ks], acc[tt]);
+            const long t = tile * 64 + 16 * u + i;
             if (t < M) {
                 u32x2 p0 = pack4(acc[0]), p1 = pack4(acc[1]), p2 = pack4(acc[2]), p3 = pack4(acc[3]);
                 u32x4 *dst = (u32x4 *)(out + t * C + base + 16 * g);
@@ -373,12 +393,9 @@ __global__ __launch_bounds__(64 * WPB) void k_qkv(const bf16_t *__restrict__ X,
                 dst[1] = u32x4{p2[0], p2[1], p3[0], p3[1]};
             }
         }
-        if (tile + 1 < tile1) {
-#pragma unroll
-            for (int u = 0; u < NU; ++u)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) cur[u][ks] = nxt[u][ks];
-        }
+        if (more) stage(cur ^ 1);      // the other buffer was last read before the previous barrier
+        __syncthreads();
+        cur ^= 1;
     }
 }
 
@@ -918,17 +935,20 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     }
     const long M = (long)D.B * D.N;
     {
-        constexpr int NU = (C == 256) ? 1 : 2;
         constexpr int WPB = (C == 256) ? 4 : 3 * C / 64;      // wavefronts (64-channel groups) per workgroup
-        const long ntiles = (M + 16 * NU - 1) / (16 * NU);
-        // tiles per workgroup: at least ~1000 wavefronts in flight, yet few weight reloads
-        long tpw = ntiles * (3 * C / 64) / 1024;
-        tpw = tpw < 1 ? 1 : (tpw > 8 ? 8 : tpw);
-        if (const char *e = getenv("BRA_QKV_TPW")) { int v = atoi(e); if (v >= 1 && v <= 64) tpw = v; }
+        const long ntiles = (M + 63) / 64;
+        // about one workgroup per compute unit: every wavefront keeps its weight slice in
+        // registers and the workgroup streams its share of the tokens
+        const int gy = 3 * C / 64 / WPB;
+        long tpw = (ntiles * gy + 255) / 256;
+        if (const char *e = getenv("BRA_QKV_TPW")) { int v = atoi(e); if (v >= 1 && v <= 4096) tpw = v; }
         const int gx = (int)((ntiles + tpw - 1) / tpw);
+        const size_t smem = (size_t)2 * 64 * (C + 16) * 2;
+        static bool opted = false;
+        if (!lds_opt_in(k_qkv<C, WPB>, opted)) return BRA_ERR_LAUNCH;
         ProfScope ps(st, K_MFMA_QKV);
-        hipLaunchKernelGGL((k_qkv<C, NU, WPB>), dim3(gx, 3 * C / 64 / WPB), dim3(64 * WPB), 0, st, X, w.wt,
-                           w.q, w.k, w.v, M, (int)tpw);
+        hipLaunchKernelGGL((k_qkv<C, WPB>), dim3(gx, gy), dim3(64 * WPB), smem, st, X, w.wt, w.q, w.k, w.v, M,
+                           (int)tpw);
     }
     if (!attn_big_ok(D)) return launch_small(D, A, w.o, st);
     {
