@@ -212,14 +212,15 @@ struct SoftmaxState {
     }
 };
 
-// Online-softmax step of head h for one block of 64 keys, given the scores
+// Online-softmax step of one head for one block of 64 keys, given the scores
 // s[t][j] = S^T[key 16 t + 4 g + j][query i] of this wavefront's 16 queries (Eq. 1, one
 // softmax over all routed keys), then O^T += V^T P^T with V read from the rows of Vs (VS
-// elements per row) by the transposing LDS read.
+// elements per row, the head's channels start at column vcol) by the transposing LDS read.
+// The head's running state is slot h of st.
 template <int VS, int HEADS>
 __device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (&s)[4],
-                                                 SoftmaxState<HEADS> &st, int h, float c_exp, int g,
-                                                 int i)
+                                                 SoftmaxState<HEADS> &st, int h, int vcol, float c_exp,
+                                                 int g, int i)
 {
     float mx = s[0][0];
 #pragma unroll
@@ -252,7 +253,7 @@ __device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (
         const bf16x8 pb = pack8(pv);
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
-            const int col = 32 * h + 16 * dt + 4 * (i % 4);
+            const int col = vcol + 16 * dt + 4 * (i % 4);
             const s16x4 v0 = lds_read_tr16(Vs + (32 * tp + 4 * g + i / 4) * VS + col);
             const s16x4 v1 = lds_read_tr16(Vs + (32 * tp + 16 + 4 * g + i / 4) * VS + col);
             u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
@@ -278,7 +279,7 @@ __device__ __forceinline__ void attn_key_block(const bf16_t *Ks, const bf16_t *V
             const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + 32 * h + 8 * g);
             s[t] = mfma16(kf, qf[h], f32x4{0.f, 0.f, 0.f, 0.f});   // S^T[key 16t+4g+j][query i]
         }
-        softmax_pv_block<CS>(Vs, s, st, h, c_exp, g, i);
+        softmax_pv_block<CS>(Vs, s, st, h, 32 * h, c_exp, g, i);
     }
 }
 

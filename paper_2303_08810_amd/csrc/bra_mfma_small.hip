@@ -18,95 +18,70 @@ using namespace mfma;
 
 namespace {
 
-constexpr int kVS = 40;     // bf16 elements per row of the private V tile (32 + 16-byte pad)
 constexpr int kLTP = 20;    // floats per channel of the LCE tile [C][tokens] (n <= 16)
 constexpr int kMaxLceTasks = 2;   // (row, 4-token segment, channel pair) tasks per thread
 
-// LDS map: the wavefront-private V tiles come first; the LCE tile takes their place once
-// every wavefront has finished its heads.
+// ---------------------------------------------------------------------------
+// Attention of one (image, region) over its k n routed keys (Eq. 6, Eq. 1), shared by
+// both variants.  The keys are taken 64 at a time: the workgroup copies the K and V rows
+// of the block (all channels, found by index in the projected maps) into LDS with
+// coalesced 16-byte loads, then wavefront w runs heads w, w + 4, .. on it.  Result:
+// oacc[hh][dt] = normalised O^T[channel 32 h + 16 dt + 4 g + jj][query i], h = w + 4 hh.
+// Ks, Vs: [64][C + 16] bf16 each.  Ends with all wavefronts past their last LDS read only
+// after the caller's next barrier.
 template <int C>
-struct SmallSmem {
-    static constexpr int CS = C + 8;
-    static constexpr size_t vw_bytes = (size_t)4 * 64 * kVS * 2;
-    static constexpr size_t lt_bytes = (size_t)C * kLTP * 4;
-    static constexpr size_t v_off = 0;
-    static constexpr size_t o_off = vw_bytes > lt_bytes ? vw_bytes : lt_bytes;   // [16][CS] bf16: O = attention + LCE
-    static constexpr size_t h_off = o_off + (size_t)16 * CS * 2;                 // V halo tile [hrows][CS] bf16
-    static size_t bytes(int hrows) { return h_off + (size_t)hrows * CS * 2; }
-};
-
-template <int C>
-__global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
+__device__ __forceinline__ void small_attention(const AttnArgs &A, const Dims &D, int log2n,
+                                                size_t img_off, const int32_t *irp, size_t qtok,
+                                                bf16_t *Ks, bf16_t *Vs,
+                                                f32x4 (&oacc)[(C / 32 + 3) / 4][2])
 {
-    typedef SmallSmem<C> SM;
-    constexpr int HEADS = C / 32, HPW = (HEADS + 3) / 4, CS = SM::CS, KS = C / 32, CH = C / 8;
-    constexpr int NBH = 2;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16_t *Vw = (bf16_t *)(smem + SM::v_off);
-    float *Lt = (float *)(smem + SM::v_off);
-    bf16_t *Ob = (bf16_t *)(smem + SM::o_off);
-    bf16_t *Hs = (bf16_t *)(smem + SM::h_off);
-
-    const int wid = swizzled_block();
-    if (wid >= A.total) return;
+    constexpr int HEADS = C / 32, HPW = (HEADS + 3) / 4, XP = C + 16, CH = C / 8;
+    constexpr int NLD = 64 * CH / 256;        // 16-byte chunks of a 64-row tile per thread
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
-    const int b = wid / D.R, reg = wid % D.R;
-    const size_t img_off = (size_t)b * D.N * C;
     const int n = D.n, kn = D.kn;
     const float rw_inv = 1.0f / (float)D.rw;
-    const int y0 = (reg / D.S) * D.rh, x0 = (reg % D.S) * D.rw;
 
-    const int32_t *irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
-    if (A.Ir_out && A.Ir_out != A.Ir_src)
-        for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
-
-    // V over the region and its halo -> LDS (needed only after the attention)
-    const int hw = D.rw + 4, hrows = (D.rh + 4) * hw;
-    {
-        const float hw_inv = 1.0f / (float)hw;
-        for (int first = 0; first < hrows * CH; first += 256 * NBH) {
-            u32x4 hreg[NBH];
-            tile_load<C, NBH>(hreg, A.V + img_off, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, first);
-            tile_store<C, CS, NBH>(Hs, hreg, hrows, first);
-        }
-    }
-
-    // query token of this lane's column (columns >= n repeat the last query; never stored)
-    const int qs = i < n ? i : n - 1;
-    const int qy = fast_div(qs, rw_inv);
-    const size_t qtok = (size_t)(y0 + qy) * D.W + x0 + qs - qy * D.rw;
-    bf16_t *vw = Vw + wave * 64 * kVS;
-
-    f32x4 oacc[HPW][2];     // normalised attention output of this wavefront's heads
+    bf16x8 qf[HPW];
 #pragma unroll
     for (int hh = 0; hh < HPW; ++hh) {
-        const int h = wave + 4 * hh;
-        oacc[hh][0] = oacc[hh][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (h >= HEADS) break;
-        const bf16x8 qf = *(const bf16x8 *)(A.Q + img_off + qtok * C + 32 * h + 8 * g);
-        SoftmaxState<1> st;
-        st.init();
-        for (int k0 = 0; k0 < kn; k0 += 64) {
-            // key 16 t + i of this block: A-operand row i of tile t
-            bf16x8 kf[4];
-            u32x4 vr[4];
+        const int h = min(wave + 4 * hh, HEADS - 1);
+        qf[hh] = *(const bf16x8 *)(A.Q + img_off + qtok * C + 32 * h + 8 * g);
+    }
+    SoftmaxState<HPW> st;
+    st.init();
+    for (int k0 = 0; k0 < kn; k0 += 64) {
+        u32x4 kr[NLD], vr[NLD];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                int key = k0 + 16 * t + i;
-                if (key >= kn) key = kn - 1;
-                const int j = irp[key >> log2n], slot = key & (n - 1);
-                const int sy = fast_div(slot, rw_inv);
-                const size_t tok = (size_t)((j / D.S) * D.rh + sy) * D.W + (j % D.S) * D.rw + slot - sy * D.rw;
-                const size_t off = img_off + tok * C + 32 * h + 8 * g;
-                kf[t] = *(const bf16x8 *)(A.K + off);
-                vr[t] = *(const u32x4 *)(A.V + off);
-            }
+        for (int u = 0; u < NLD; ++u) {
+            const int idx = threadIdx.x + 256 * u;
+            int key = k0 + idx / CH;
+            if (key >= kn) key = kn - 1;           // rows past the end repeat the last key; masked below
+            const int j = irp[key >> log2n], slot = key & (n - 1);
+            const int sy = fast_div(slot, rw_inv);
+            const size_t tok = (size_t)((j / D.S) * D.rh + sy) * D.W + (j % D.S) * D.rw + slot - sy * D.rw;
+            const size_t off = img_off + tok * C + (idx % CH) * 8;
+            kr[u] = *(const u32x4 *)(A.K + off);
+            vr[u] = *(const u32x4 *)(A.V + off);
+        }
+        if (k0) __syncthreads();                   // the previous block has been read
 #pragma unroll
-            for (int t = 0; t < 4; ++t) *(u32x4 *)(vw + (16 * t + i) * kVS + 8 * g) = vr[t];
+        for (int u = 0; u < NLD; ++u) {
+            const int idx = threadIdx.x + 256 * u;
+            *(u32x4 *)(Ks + (idx / CH) * XP + (idx % CH) * 8) = kr[u];
+            *(u32x4 *)(Vs + (idx / CH) * XP + (idx % CH) * 8) = vr[u];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int hh = 0; hh < HPW; ++hh) {
+            const int h = wave + 4 * hh;
+            if (h >= HEADS) break;
             f32x4 s[4];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) s[t] = mfma16(kf[t], qf, f32x4{0.f, 0.f, 0.f, 0.f});
+            for (int t = 0; t < 4; ++t) {
+                const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * XP + 32 * h + 8 * g);
+                s[t] = mfma16(kf, qf[hh], f32x4{0.f, 0.f, 0.f, 0.f});
+            }
             if (k0 + 64 > kn) {   // ragged last block: keys past the end do not count
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
@@ -114,11 +89,76 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
                     for (int jj = 0; jj < 4; ++jj)
                         if (k0 + 16 * t + 4 * g + jj >= kn) s[t][jj] = -INFINITY;
             }
-            softmax_pv_block<kVS>(vw, s, st, 0, A.c_exp, g, i);
+            softmax_pv_block<XP>(Vs, s, st, hh, 32 * h, A.c_exp, g, i);
         }
-        const float inv = 1.0f / st.l[0];
-        oacc[hh][0] = st.acc[0][0] * inv;
-        oacc[hh][1] = st.acc[0][1] * inv;
+    }
+#pragma unroll
+    for (int hh = 0; hh < HPW; ++hh) {
+        const float inv = 1.0f / st.l[hh];         // heads past the end: 1 / 0 times 0, never used
+        oacc[hh][0] = st.acc[hh][0] * inv;
+        oacc[hh][1] = st.acc[hh][1] * inv;
+    }
+}
+
+// LDS map of the one-kernel variant: the K / V key blocks first; once the attention is
+// done, the V halo tile and the LCE tile take their place.
+template <int C>
+struct SmallSmem {
+    static constexpr int CS = C + 8, XP = C + 16;
+    static constexpr size_t kv_bytes = (size_t)2 * 64 * XP * 2;
+    static constexpr size_t lt_bytes = (size_t)C * kLTP * 4;
+    __host__ __device__ static size_t o_off(int hrows)   // [16][CS] bf16: O = attention + LCE
+    {
+        const size_t second = (size_t)hrows * CS * 2 + lt_bytes;
+        return kv_bytes > second ? kv_bytes : second;
+    }
+    static size_t bytes(int hrows) { return o_off(hrows) + (size_t)16 * CS * 2; }
+};
+
+template <int C>
+__global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
+{
+    typedef SmallSmem<C> SM;
+    constexpr int HEADS = C / 32, HPW = (HEADS + 3) / 4, CS = SM::CS, XP = SM::XP, KS = C / 32, CH = C / 8;
+    constexpr int NBH = 4;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int hw = D.rw + 4, hrows = (D.rh + 4) * hw;
+    bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + 64 * XP;
+    bf16_t *Hs = (bf16_t *)smem;                                   // after the attention
+    float *Lt = (float *)(smem + (size_t)hrows * CS * 2);
+    bf16_t *Ob = (bf16_t *)(smem + SM::o_off(hrows));
+
+    const int wid = swizzled_block();
+    if (wid >= A.total) return;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int g = lane / 16, i = lane % 16;
+    const int b = wid / D.R, reg = wid % D.R;
+    const size_t img_off = (size_t)b * D.N * C;
+    const int n = D.n;
+    const float rw_inv = 1.0f / (float)D.rw, hw_inv = 1.0f / (float)hw;
+    const int y0 = (reg / D.S) * D.rh, x0 = (reg % D.S) * D.rw;
+
+    const int32_t *irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
+    if (A.Ir_out && A.Ir_out != A.Ir_src)
+        for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
+
+    // V over the region and its halo: the first chunks are requested now and parked in
+    // registers until the attention has released the LDS
+    u32x4 hreg[NBH];
+    tile_load<C, NBH>(hreg, A.V + img_off, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, 0);
+
+    // query token of this lane's column (columns >= n repeat the last query; never stored)
+    const int qs = i < n ? i : n - 1;
+    const int qy = fast_div(qs, rw_inv);
+    const size_t qtok = (size_t)(y0 + qy) * D.W + x0 + qs - qy * D.rw;
+
+    f32x4 oacc[HPW][2];     // normalised attention output of this wavefront's heads
+    small_attention<C>(A, D, log2n, img_off, irp, qtok, Ks, Vs, oacc);
+    __syncthreads();        // the key blocks have been read: the halo tile takes their place
+    tile_store<C, CS, NBH>(Hs, hreg, hrows, 0);
+    for (int first = 256 * NBH; first < hrows * CH; first += 256 * NBH) {
+        tile_load<C, NBH>(hreg, A.V + img_off, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, first);
+        tile_store<C, CS, NBH>(Hs, hreg, hrows, first);
     }
 
     // LCE (Eq. 7) of the region's tokens: task = (row r, 4-token segment, channel pair);
@@ -165,7 +205,6 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
             }
         }
     }
-    __syncthreads();        // every wavefront is done with its private V tile
 #pragma unroll
     for (int tk = 0; tk < kMaxLceTasks; ++tk) {
         const int task = threadIdx.x + 256 * tk;
@@ -223,8 +262,9 @@ template <int C>
 __global__ __launch_bounds__(256) void k_attn_small(AttnArgs A, bf16_t *__restrict__ O, Dims D,
                                                     int log2n)
 {
-    constexpr int HEADS = C / 32;
-    __shared__ __attribute__((aligned(16))) bf16_t Vw[4][64 * kVS];
+    constexpr int HEADS = C / 32, HPW = (HEADS + 3) / 4, XP = C + 16;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + 64 * XP;
 
     const int wid = swizzled_block();
     if (wid >= A.total) return;
@@ -232,7 +272,7 @@ __global__ __launch_bounds__(256) void k_attn_small(AttnArgs A, bf16_t *__restri
     const int g = lane / 16, i = lane % 16;
     const int b = wid / D.R, reg = wid % D.R;
     const size_t img_off = (size_t)b * D.N * C;
-    const int n = D.n, kn = D.kn;
+    const int n = D.n;
     const float rw_inv = 1.0f / (float)D.rw;
 
     const int32_t *irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
@@ -243,84 +283,17 @@ __global__ __launch_bounds__(256) void k_attn_small(AttnArgs A, bf16_t *__restri
     const int qs = i < n ? i : n - 1;
     const int qy = fast_div(qs, rw_inv);
     const size_t qtok = (size_t)((reg / D.S) * D.rh + qy) * D.W + (reg % D.S) * D.rw + qs - qy * D.rw;
-    bf16_t *vw = Vw[wave];
 
-    for (int h = wave; h < HEADS; h += 4) {
-        const bf16x8 qf = *(const bf16x8 *)(A.Q + img_off + qtok * C + 32 * h + 8 * g);
-        float m_run = -INFINITY, l_run = 0.f;
-        f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-        for (int k0 = 0; k0 < kn; k0 += 64) {
-            // key 16 t + i of this block: A-operand row i of tile t
-            bf16x8 kf[4];
-            u32x4 vr[4];
+    f32x4 oacc[HPW][2];
+    small_attention<C>(A, D, log2n, img_off, irp, qtok, Ks, Vs, oacc);
+    if (i < n) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                int key = k0 + 16 * t + i;
-                if (key >= kn) key = kn - 1;
-                const int j = irp[key >> log2n], slot = key & (n - 1);
-                const int sy = fast_div(slot, rw_inv);
-                const size_t tok = (size_t)((j / D.S) * D.rh + sy) * D.W + (j % D.S) * D.rw + slot - sy * D.rw;
-                const size_t off = img_off + tok * C + 32 * h + 8 * g;
-                kf[t] = *(const bf16x8 *)(A.K + off);
-                vr[t] = *(const u32x4 *)(A.V + off);
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) *(u32x4 *)(vw + (16 * t + i) * kVS + 8 * g) = vr[t];
-            f32x4 s[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) s[t] = mfma16(kf[t], qf, f32x4{0.f, 0.f, 0.f, 0.f});
-            if (k0 + 64 > kn) {   // ragged last block: keys past the end do not count
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj)
-                        if (k0 + 16 * t + 4 * g + jj >= kn) s[t][jj] = -INFINITY;
-            }
-            float mx = s[0][0];
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) mx = fmaxf(mx, s[t][jj]);
-            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * A.c_exp);
-            const float mc = m_new * A.c_exp;
-            float p[4][4], ls = 0.f;
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    p[t][jj] = __builtin_amdgcn_exp2f(fmaf(s[t][jj], A.c_exp, -mc));
-                    ls += p[t][jj];
-                }
-            ls += __shfl_xor(ls, 16, kWave);
-            ls += __shfl_xor(ls, 32, kWave);
-            l_run = l_run * alpha + ls;
-            m_run = m_new;
-            acc[0] *= alpha;
-            acc[1] *= alpha;
-#pragma unroll
-            for (int tp = 0; tp < 2; ++tp) {
-                float pv[8] = {p[2 * tp][0], p[2 * tp][1], p[2 * tp][2], p[2 * tp][3],
-                               p[2 * tp + 1][0], p[2 * tp + 1][1], p[2 * tp + 1][2], p[2 * tp + 1][3]};
-                const bf16x8 pb = pack8(pv);
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt) {
-                    const int col = 16 * dt + 4 * (i % 4);
-                    const s16x4 v0 = lds_read_tr16(vw + (32 * tp + 4 * g + i / 4) * kVS + col);
-                    const s16x4 v1 = lds_read_tr16(vw + (32 * tp + 16 + 4 * g + i / 4) * kVS + col);
-                    u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
-                    u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
-                    acc[dt] = mfma16(__builtin_bit_cast(bf16x8, av), pb, acc[dt]);
-                }
-            }
-        }
-        if (i < n) {
-            const float inv = 1.0f / l_run;
+        for (int hh = 0; hh < HPW; ++hh) {
+            const int h = wave + 4 * hh;
+            if (h >= HEADS) break;
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt)
-                *(u32x2 *)(O + img_off + qtok * C + 32 * h + 16 * dt + 4 * g) = pack4(acc[dt] * inv);
+                *(u32x2 *)(O + img_off + qtok * C + 32 * h + 16 * dt + 4 * g) = pack4(oacc[hh][dt]);
         }
     }
 }
@@ -504,8 +477,10 @@ static int launch_small_c(const Dims &D, const AttnArgs &A0, bf16_t *O, hipStrea
         return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
     }
     {
+        static bool opted = false;
+        if (!opt_in(k_attn_small<C>, opted)) return BRA_ERR_LAUNCH;
         ProfScope ps(st, K_MFMA_ATTN_SMALL);
-        hipLaunchKernelGGL(k_attn_small<C>, dim3(grid), dim3(256), 0, st, A, O, D, log2n);
+        hipLaunchKernelGGL(k_attn_small<C>, dim3(grid), dim3(256), SmallSmem<C>::kv_bytes, st, A, O, D, log2n);
     }
     {
         static bool opted = false;
