@@ -14,9 +14,10 @@ import re
 import sys
 
 COPY_BYTES = 64 << 20
-NAMES = {"k_fused": "mfma_fused_k1", "k_pool_qk_mfma": "mfma_pool_qk", "k_pool_qk": "mfma_pool_qk",
+NAMES = {"k_fused": "mfma_fused_k1", "k_pool": "mfma_pool_qk", "k_route": "mfma_route_rows",
          "k_qkv": "mfma_qkv", "k_attn_big": "mfma_attention", "k_attn_small": "mfma_attn_small",
-         "k_lce_wo": "mfma_lce_wo", "k_prep_weights": "mfma_prep", "k_util_copy": "copy"}
+         "k_small": "mfma_attn_small", "k_lce_wo": "mfma_lce_wo", "k_prep_weights": "mfma_prep",
+         "k_util_copy": "copy"}
 
 
 def averages(directory, counter):
