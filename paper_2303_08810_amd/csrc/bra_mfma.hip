@@ -181,7 +181,42 @@ __device__ __forceinline__ void split3(const float (&x)[8], bf16x8 (&t)[3])
 // of the float32 computation.  Wavefront w owns output-channel tiles w, w + 4, ..; the
 // results go to LDS (K^r transposed), then wavefront w forms rows 4 w .. 4 w + 3 of A^r
 // in float32, lane j holding entry j, and ranks them.
-constexpr int kRouteKS = 68;   // floats per channel of the transposed K^r tile in LDS
+constexpr int kRouteRS = 65;   // regions (float4 slots) per 4-channel group of the K^r tile in LDS
+
+// Rows 4 w .. 4 w + 3 (of the 16 query regions of row tile myrt) of A^r = Q^r (K^r)^T in
+// float32 from the LDS tiles Kt [C / 4][kRouteRS][4] (K^r: channel group, region, channel in
+// the group) and Qs [16][C + 4], lane j
+// holding entry j; then their top-k (Eq. 5) and, if asked for, the rows themselves.
+template <int C>
+__device__ __forceinline__ void route_rows_from_lds(const float *Kt, const float *Qs, int b, int myrt,
+                                                    const Dims &D, int32_t *__restrict__ Ir,
+                                                    float *__restrict__ Ar)
+{
+    constexpr int QS = C + 4;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    float a[4] = {0.f, 0.f, 0.f, 0.f};
+    const float *qrow = Qs + 4 * wave * QS;
+#pragma unroll 4
+    for (int c = 0; c < C; c += 4) {
+        const f32x4 kv = *(const f32x4 *)(Kt + ((c / 4) * kRouteRS + lane) * 4);
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const f32x4 q4 = *(const f32x4 *)(qrow + rr * QS + c);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) a[rr] = fmaf(q4[e], kv[e], a[rr]);
+        }
+    }
+    const int r0 = 16 * myrt + 4 * wave;
+    if (r0 >= D.R) return;
+    const int nrows = min(4, D.R - r0);
+    const size_t row0 = (size_t)b * D.R + r0;
+    if (Ar && lane < D.R) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+            if (rr < nrows) Ar[(row0 + rr) * D.R + lane] = a[rr];
+    }
+    wave_topk_rows<4>(a, nrows, lane, D.R, D.k, Ir + row0 * D.k);
+}
 
 template <int C>
 struct RouteSmem {
@@ -189,7 +224,7 @@ struct RouteSmem {
     static constexpr int XP = CK + 16;                  // bf16 per row of a staged term
     static constexpr int QS = C + 4;                    // floats per row of the Q^r tile
     static constexpr size_t xs_bytes = (size_t)3 * 64 * XP * 2;
-    static constexpr size_t kq_bytes = ((size_t)C * kRouteKS + 16 * QS) * 4;   // takes the place of the terms
+    static constexpr size_t kq_bytes = ((size_t)C * kRouteRS + 16 * QS) * 4;   // takes the place of the terms
     static constexpr size_t bytes = xs_bytes > kq_bytes ? xs_bytes : kq_bytes;
 };
 
@@ -203,8 +238,8 @@ __global__ __launch_bounds__(256) void k_route(const float *__restrict__ Xr,
     constexpr int CK = SM::CK, XP = SM::XP, QS = SM::QS, KSC = CK / 32, NCW = C / 64;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *xs = (bf16_t *)smem;                  // [3][64][XP]
-    float *Kt = (float *)smem;                    // [C][kRouteKS]
-    float *Qs = Kt + C * kRouteKS;                // [16][QS]
+    float *Kt = (float *)smem;                    // [C / 4][kRouteRS][4]
+    float *Qs = Kt + C * kRouteRS;                // [16][QS]
     const int groups = (D.R + 15) / 16;
     const int b = blockIdx.x / groups, myrt = blockIdx.x % groups;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
@@ -279,35 +314,73 @@ __global__ __launch_bounds__(256) void k_route(const float *__restrict__ Xr,
     for (int cw = 0; cw < NCW; ++cw) {
         const int ch = 16 * (wave + 4 * cw) + 4 * g;
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt)
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) Kt[(ch + jj) * kRouteKS + 16 * rt + i] = ak[rt][cw][jj];
+        for (int rt = 0; rt < 4; ++rt) *(f32x4 *)(Kt + ((ch / 4) * kRouteRS + 16 * rt + i) * 4) = ak[rt][cw];
         *(f32x4 *)(Qs + i * QS + ch) = aq[cw];
     }
     __syncthreads();
 
-    float a[4] = {0.f, 0.f, 0.f, 0.f};
-    const float *qrow = Qs + 4 * wave * QS;
-#pragma unroll 4
-    for (int c = 0; c < C; c += 4) {
-        float kv[4];
+    route_rows_from_lds<C>(Kt, Qs, b, myrt, D, Ir, Ar);
+}
+
+// Routing from the partial sums that the projection kernel leaves behind (P[token / group]
+// [2C] = [sum Q | sum K] over `group` = 2^group_log2 consecutive tokens of one region row):
+// Q^r and K^r are the region means of Q and K (Sec. 3.2), i.e. the sum of a region's
+// rh x (rw / group) partial sums in a fixed order, divided by n.  Workgroup (b, rt) as in
+// k_route; no matrix products are left to do here.
+template <int C>
+__global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, int32_t *__restrict__ Ir,
+                                                 float *__restrict__ Ar, Dims D, int group_log2)
+{
+    constexpr int QS = C + 4, C4 = C / 4;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    float *Kt = (float *)smem;                    // [C / 4][kRouteRS][4]
+    float *Qs = Kt + C * kRouteRS;                // [16][QS]
+    const int groups = (D.R + 15) / 16;
+    const int b = blockIdx.x / groups, myrt = blockIdx.x % groups;
+    const int pw = D.W >> group_log2, pc = D.rw >> group_log2;      // partial sums per image row / region row
+    const float inv_n = 1.0f / (float)D.n;
+    // Work items (region, 4 channels): all of K^r, then the 16 query rows of Q^r.  A thread
+    // takes its NI items at once so that their loads are in flight together; the partial sums of
+    // an item are added in the order (row of the region, position in the row).
+    constexpr int NI = (80 * C4 + 255) / 256;       // every item of a workgroup in one round (R <= 64)
+    const int nk = D.R * C4, total = nk + 16 * C4;
+    for (int i0 = threadIdx.x; i0 < total; i0 += 256 * NI) {
+        const float *src[NI];
+        f32x4 acc[NI];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) kv[e] = Kt[(c + e) * kRouteKS + lane];
+        for (int u = 0; u < NI; ++u) {
+            const int idx = min(i0 + 256 * u, total - 1);
+            const bool isq = idx >= nk;
+            const int row = (isq ? idx - nk : idx) / C4, c4 = (isq ? idx - nk : idx) % C4;
+            const int r = isq ? min(16 * myrt + row, D.R - 1) : row;     // rows past R repeat the last region; never used
+            const int ry = r / D.S, rx = r % D.S;
+            src[u] = P + (((size_t)b * D.H + ry * D.rh) * pw + rx * pc) * 2 * C + (isq ? 0 : C) + 4 * c4;
+            acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        for (int yy = 0; yy < D.rh; ++yy)
+            for (int cc = 0; cc < pc; ++cc) {
+                f32x4 v[NI];
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const f32x4 q4 = *(const f32x4 *)(qrow + rr * QS + c);
+                for (int u = 0; u < NI; ++u) v[u] = *(const f32x4 *)(src[u] + ((size_t)yy * pw + cc) * 2 * C);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) a[rr] = fmaf(q4[e], kv[e], a[rr]);
+                for (int u = 0; u < NI; ++u) acc[u] += v[u];
+            }
+#pragma unroll
+        for (int u = 0; u < NI; ++u) {
+            const int idx = i0 + 256 * u;
+            if (idx >= total) break;
+            const f32x4 v = acc[u] * inv_n;
+            if (idx < nk) {
+                const int r = idx / C4, c4 = idx % C4;
+                *(f32x4 *)(Kt + (c4 * kRouteRS + r) * 4) = v;
+            } else {
+                const int row = (idx - nk) / C4, c4 = (idx - nk) % C4;
+                *(f32x4 *)(Qs + row * QS + 4 * c4) = v;
+            }
         }
     }
-#pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-        const int r = 16 * myrt + 4 * wave + rr;
-        if (r >= D.R) break;
-        const size_t row = (size_t)b * D.R + r;
-        if (Ar && lane < D.R) Ar[row * D.R + lane] = a[rr];
-        wave_topk(a[rr], lane, D.R, D.k, Ir + row * D.k);
-    }
+    __syncthreads();
+    route_rows_from_lds<C>(Kt, Qs, b, myrt, D, Ir, Ar);
 }
 
 // ---------------------------------------------------------------------------
@@ -320,10 +393,17 @@ __global__ __launch_bounds__(256) void k_route(const float *__restrict__ Xr,
 // wavefronts.  The product is formed transposed (rows = output channels, columns =
 // tokens) with the weight rows permuted so that a lane ends up with 16 consecutive
 // output channels of one token, i.e. one 32-byte store.
+//
+// Region pooling of Q and K (Sec. 3.2: Q^r, K^r are the per-region means of Q and K)
+// rides along when P is given: the float32 accumulators of `group` = min(rw, 4)
+// consecutive tokens, which always lie in one row of one region, are summed across lanes
+// before the rounding to bf16, and written as P[token / group][2C] = [sum Q | sum K].  The
+// routing kernel adds the few partial sums of each region.
 template <int C, int WPB>
 __global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, 2)))
 void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ WT, bf16_t *__restrict__ Q,
-           bf16_t *__restrict__ K, bf16_t *__restrict__ V, long M, int tiles_per_wg)
+           bf16_t *__restrict__ K, bf16_t *__restrict__ V, float *__restrict__ P, int group_log2, long M,
+           int tiles_per_wg)
 {
     constexpr int KS = C / 32, CH = C / 8, XP = C + 16, NTH = 64 * WPB;
     constexpr int NL = (64 * CH + NTH - 1) / NTH;       // 16-byte chunks of a tile per thread
@@ -334,6 +414,7 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ WT, bf16_t *
     const int grp = blockIdx.y * WPB + wave;            // 64-channel group among 3C/64
     const int sel = grp / (C / 64), base = (grp % (C / 64)) * 64;
     bf16_t *__restrict__ out = sel == 0 ? Q : (sel == 1 ? K : V);
+    const int group = 1 << group_log2;
 
     bf16x8 af[4][KS];
 #pragma unroll
@@ -391,6 +472,15 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ WT, bf16_t *
                 u32x4 *dst = (u32x4 *)(out + t * C + base + 16 * g);
                 dst[0] = u32x4{p0[0], p0[1], p1[0], p1[1]};
                 dst[1] = u32x4{p2[0], p2[1], p3[0], p3[1]};
+            }
+            if (P && sel < 2) {      // M is a multiple of the group: a group is whole or absent
+                if (group_log2 == 1) lane_group_sums<1>(acc);
+                else if (group_log2 == 2) lane_group_sums<2>(acc);
+                if (t < M && (i & (group - 1)) == 0) {
+                    f32x4 *dst = (f32x4 *)(P + (t >> group_log2) * 2 * C + sel * C + base + 16 * g);
+#pragma unroll
+                    for (int tt = 0; tt < 4; ++tt) dst[tt] = acc[tt];
+                }
             }
         }
         if (more) stage(cur ^ 1);      // the other buffer was last read before the previous barrier
@@ -784,7 +874,7 @@ void k_fused(AttnArgs A, Dims D)
 // ---------------------------------------------------------------------------
 struct MfmaWs {
     bf16_t *q, *k, *v, *o, *wt, *wot, *wa, *wf;
-    float *xr;
+    float *xr, *p;
     void *route;
     int32_t *ir;
     size_t bytes;
@@ -807,6 +897,24 @@ bool fused_ok(const Dims &D)
     return D.n == 64 && D.k == 1 && (D.rw == 8 || D.rw == 16);
 }
 
+// Whether the staged pipelines take Q^r, K^r from partial sums written by the projection
+// kernel (few partial sums per region: small regions) or from the pooled X (k_pool, k_route).
+bool pooled_projection(const Dims &D);
+
+// log2 of the number of consecutive tokens whose Q / K accumulators the projection kernel
+// sums: the largest of 1, 2, 4 that divides rw (such tokens lie in one row of one region).
+int pool_group_log2(const Dims &D)
+{
+    int lg = 0;
+    while (lg < 2 && D.rw % (2 << lg) == 0) ++lg;
+    return lg;
+}
+
+bool pooled_projection(const Dims &D)
+{
+    return fast_route_ok(D) && D.rh * (D.rw >> pool_group_log2(D)) <= 8;
+}
+
 MfmaWs carve(const Dims &D, void *ws)
 {
     MfmaWs w;
@@ -823,6 +931,7 @@ MfmaWs carve(const Dims &D, void *ws)
     w.wa = (bf16_t *)take((size_t)D.C * kLceOperandElems * 2);
     w.wf = (bf16_t *)take(D.C == 64 ? (size_t)kFusedFragElems * 2 : 0);
     w.xr = (float *)take((size_t)D.B * D.R * D.C * sizeof(float));
+    w.p = (float *)take(pooled_projection(D) ? (size_t)D.B * D.H * (D.W >> pool_group_log2(D)) * 2 * D.C * sizeof(float) : 0);
     w.route = take(fast_route_ok(D) ? 0 : valu_route_scratch_bytes(D));
     w.ir = (int32_t *)take((size_t)D.B * D.R * D.k * sizeof(int32_t));
     w.bytes = off;
@@ -883,6 +992,39 @@ int launch_route(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, hip
     return BRA_OK;
 }
 
+template <int C>
+int launch_route_p(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, hipStream_t st)
+{
+    static bool opted = false;
+    if (!lds_opt_in(k_route_p<C>, opted)) return BRA_ERR_LAUNCH;
+    ProfScope ps(st, K_MFMA_ROUTE_ROWS);
+    hipLaunchKernelGGL(k_route_p<C>, dim3(D.B * ((D.R + 15) / 16)), dim3(256), RouteSmem<C>::kq_bytes, st,
+                       w.p, Ir, Ar_opt, D, pool_group_log2(D));
+    return BRA_OK;
+}
+
+// Q, K, V of all tokens into the workspace; with `pooled`, also the partial sums of Q and K.
+template <int C>
+int launch_qkv(const Dims &D, const bf16_t *X, const MfmaWs &w, bool pooled, hipStream_t st)
+{
+    const long M = (long)D.B * D.N;
+    constexpr int WPB = (C == 256) ? 4 : 3 * C / 64;      // wavefronts (64-channel groups) per workgroup
+    const long ntiles = (M + 63) / 64;
+    // about one workgroup per compute unit: every wavefront keeps its weight slice in
+    // registers and the workgroup streams its share of the tokens
+    const int gy = 3 * C / 64 / WPB;
+    long tpw = (ntiles * gy + 255) / 256;
+    if (const char *e = getenv("BRA_QKV_TPW")) { int v = atoi(e); if (v >= 1 && v <= 4096) tpw = v; }
+    const int gx = (int)((ntiles + tpw - 1) / tpw);
+    const size_t smem = (size_t)2 * 64 * (C + 16) * 2;
+    static bool opted = false;
+    if (!lds_opt_in(k_qkv<C, WPB>, opted)) return BRA_ERR_LAUNCH;
+    ProfScope ps(st, K_MFMA_QKV);
+    hipLaunchKernelGGL((k_qkv<C, WPB>), dim3(gx, gy), dim3(64 * WPB), smem, st, X, w.wt, w.q, w.k, w.v,
+                       pooled ? w.p : nullptr, pool_group_log2(D), M, (int)tpw);
+    return BRA_OK;
+}
+
 bool attn_big_ok(const Dims &D);
 
 template <int C>
@@ -890,26 +1032,39 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
               const bf16_t *Wlce, bf16_t *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
               const MfmaWs &w, hipStream_t st)
 {
+    // Routing: the k = 1 pipeline pools X and routes before its single kernel; the staged
+    // pipelines pool Q and K inside the projection kernel and route after it.
     const int32_t *Ir_src = Ir_in_opt;
-    if (fast_route_ok(D)) {
-        launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/!Ir_in_opt, prep_total(C), st);
+    int32_t *Ir_dst = Ir_out_opt ? Ir_out_opt : w.ir;
+    const bool fused = C == 64 && fused_ok(D);
+    if (!fast_route_ok(D)) {
         if (!Ir_in_opt) {
-            int32_t *dst = Ir_out_opt ? Ir_out_opt : w.ir;
-            const int rc = launch_route<C>(D, w, dst, nullptr, st);
+            int rc = valu_route(D, X, Wqkv, Ir_dst, nullptr, w.route, st);
             if (rc != BRA_OK) return rc;
-            Ir_src = dst;
-        }
-    } else {
-        if (!Ir_in_opt) {
-            int32_t *dst = Ir_out_opt ? Ir_out_opt : w.ir;
-            int rc = valu_route(D, X, Wqkv, dst, nullptr, w.route, st);
-            if (rc != BRA_OK) return rc;
-            Ir_src = dst;
+            Ir_src = Ir_dst;
         }
         ProfScope ps(st, K_MFMA_PREP);
         const int total = prep_total(C);
         hipLaunchKernelGGL(k_prep_weights, dim3((total + 255) / 256), dim3(256), 0, st, Wqkv, Wo, Wlce,
                            w.wt, w.wot, w.wa, w.wf, C, total);
+    } else {
+        const bool from_x = (fused || !pooled_projection(D)) && !Ir_in_opt;      // pool X, route before the rest
+        launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/from_x, prep_total(C), st);
+        if (from_x) {
+            const int rc = launch_route<C>(D, w, Ir_dst, nullptr, st);
+            if (rc != BRA_OK) return rc;
+            Ir_src = Ir_dst;
+        }
+    }
+    if (!fused) {
+        const bool pooled = pooled_projection(D) && !Ir_in_opt;
+        int rc = launch_qkv<C>(D, X, w, pooled, st);
+        if (rc != BRA_OK) return rc;
+        if (pooled) {
+            rc = launch_route_p<C>(D, w, Ir_dst, nullptr, st);
+            if (rc != BRA_OK) return rc;
+            Ir_src = Ir_dst;
+        }
     }
     AttnArgs A;
     A.X = X; A.WT = w.wt; A.Q = w.q; A.K = w.k; A.V = w.v;
@@ -920,7 +1075,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     const int hrows = halo_rows(D);
 
     if constexpr (C == 64) {
-        if (fused_ok(D)) {
+        if (fused) {
             static bool opted8 = false, opted16 = false;
             ProfScope ps(st, K_MFMA_FUSED_K1);
             if (D.rw == 8) {
@@ -932,23 +1087,6 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
             }
             return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
         }
-    }
-    const long M = (long)D.B * D.N;
-    {
-        constexpr int WPB = (C == 256) ? 4 : 3 * C / 64;      // wavefronts (64-channel groups) per workgroup
-        const long ntiles = (M + 63) / 64;
-        // about one workgroup per compute unit: every wavefront keeps its weight slice in
-        // registers and the workgroup streams its share of the tokens
-        const int gy = 3 * C / 64 / WPB;
-        long tpw = (ntiles * gy + 255) / 256;
-        if (const char *e = getenv("BRA_QKV_TPW")) { int v = atoi(e); if (v >= 1 && v <= 4096) tpw = v; }
-        const int gx = (int)((ntiles + tpw - 1) / tpw);
-        const size_t smem = (size_t)2 * 64 * (C + 16) * 2;
-        static bool opted = false;
-        if (!lds_opt_in(k_qkv<C, WPB>, opted)) return BRA_ERR_LAUNCH;
-        ProfScope ps(st, K_MFMA_QKV);
-        hipLaunchKernelGGL((k_qkv<C, WPB>), dim3(gx, gy), dim3(64 * WPB), smem, st, X, w.wt, w.q, w.k, w.v, M,
-                           (int)tpw);
     }
     if (!attn_big_ok(D)) return launch_small(D, A, w.o, st);
     {
@@ -965,8 +1103,16 @@ template <int C>
 int route_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, int32_t *Ir, float *Ar_opt,
             const MfmaWs &w, hipStream_t st)
 {
-    launch_pool<C>(D, X, Wqkv, nullptr, nullptr, w, /*pool=*/true, /*prep: Wq^T, Wk^T*/ 2 * C * C, st);
-    const int rc = launch_route<C>(D, w, Ir, Ar_opt, st);
+    // the same kernels as bra_forward runs for this shape, so that both give the same index
+    int rc;
+    if ((C == 64 && fused_ok(D)) || !pooled_projection(D)) {
+        launch_pool<C>(D, X, Wqkv, nullptr, nullptr, w, /*pool=*/true, /*prep: Wq^T, Wk^T*/ 2 * C * C, st);
+        rc = launch_route<C>(D, w, Ir, Ar_opt, st);
+    } else {
+        launch_pool<C>(D, X, Wqkv, nullptr, nullptr, w, /*pool=*/false, /*prep: [Wq|Wk|Wv]^T*/ 3 * C * C, st);
+        rc = launch_qkv<C>(D, X, w, /*pooled=*/true, st);
+        if (rc == BRA_OK) rc = launch_route_p<C>(D, w, Ir, Ar_opt, st);
+    }
     if (rc != BRA_OK) return rc;
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }

@@ -79,6 +79,32 @@ __device__ __forceinline__ uint32_t dpp_umax(uint32_t x)
     return o > x ? o : x;
 }
 
+// x + x of the lane that the DPP control CTRL names (all rows; every lane has a source, the
+// zero fill of bound_ctrl only lets the compiler fold the move into the add).
+template <int CTRL>
+__device__ __forceinline__ float dpp_fadd(float x)
+{
+    const int o = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true);
+    return x + __builtin_bit_cast(float, o);
+}
+
+// Sums over aligned groups of 2 or 4 consecutive lanes (STEPS = 1 or 2) of each of the 16
+// accumulators of a projection tile, in a fixed butterfly order; every lane of a group
+// ends up with the group's sum.
+template <int STEPS>
+__device__ __forceinline__ void lane_group_sums(f32x4 (&acc)[4])
+{
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            float v = acc[tt][jj];
+            if (STEPS >= 1) v = dpp_fadd<0xB1>(v);      // quad_perm [1,0,3,2]
+            if (STEPS >= 2) v = dpp_fadd<0x4E>(v);      // quad_perm [2,3,0,1]
+            acc[tt][jj] = v;
+        }
+}
+
 // Maximum of an unsigned value over the 64 lanes of a wavefront (DPP reduction: within
 // quads, half rows, rows of 16 lanes, then across the rows), returned to every lane.
 __device__ __forceinline__ uint32_t wave_umax(uint32_t v)
@@ -100,12 +126,17 @@ __device__ __forceinline__ uint32_t wave_umax(uint32_t v)
 // (mapped value, then 63 - j) that is larger for whatever comes first and counts the
 // larger keys with one lane broadcast per other lane; the lane at position p < k writes
 // its index to out[p].
-__device__ __forceinline__ void wave_topk(float v, int j, int R, int k, int32_t *out)
+__device__ __forceinline__ uint32_t topk_order_key(float v, int j, int R)
 {
     if (!(v == v) || j >= R) v = -INFINITY;
     v += 0.0f;                                              // -0 and +0 are equal values
     uint32_t u = __builtin_bit_cast(uint32_t, v);
-    u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;             // -inf -> 0x007fffff, the smallest
+    return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);     // -inf -> 0x007fffff, the smallest
+}
+
+__device__ __forceinline__ void wave_topk(float v, int j, int R, int k, int32_t *out)
+{
+    const uint32_t u = topk_order_key(v, j, R);
     if (k <= 20) {
         bool avail = j < R;
         for (int p = 0; p < k; ++p) {
@@ -126,6 +157,41 @@ __device__ __forceinline__ void wave_topk(float v, int j, int R, int k, int32_t 
         before += ko > key ? 1 : 0;
     }
     if (j < R && before < k) out[before] = j;
+}
+
+// The same for NR rows held by one wavefront (row rr in v[rr], its index goes to
+// out + rr * k; rows rr >= nrows are not written).  For small k the rounds of the rows
+// are interleaved: each round is a chain of dependent cross-lane steps, and independent
+// chains fill each other's waits.
+template <int NR>
+__device__ __forceinline__ void wave_topk_rows(const float (&v)[NR], int nrows, int j, int R, int k,
+                                               int32_t *out)
+{
+    if (k > 20) {
+#pragma unroll
+        for (int rr = 0; rr < NR; ++rr)
+            if (rr < nrows) wave_topk(v[rr], j, R, k, out + rr * k);
+        return;
+    }
+    uint32_t u[NR];
+    bool avail[NR];
+#pragma unroll
+    for (int rr = 0; rr < NR; ++rr) {
+        u[rr] = topk_order_key(v[rr], j, R);
+        avail[rr] = j < R;
+    }
+    for (int p = 0; p < k; ++p) {
+        uint32_t m[NR];
+#pragma unroll
+        for (int rr = 0; rr < NR; ++rr) m[rr] = wave_umax(avail[rr] ? u[rr] : 0u);
+#pragma unroll
+        for (int rr = 0; rr < NR; ++rr) {
+            const uint64_t holders = __ballot(avail[rr] && u[rr] == m[rr]);
+            const int best = __builtin_ctzll(holders);      // k <= R: some entry is still available
+            if (j == 0 && rr < nrows) out[rr * k + p] = best;
+            if (j == best) avail[rr] = false;
+        }
+    }
 }
 
 // Global -> register half of a tile copy: chunk idx (16 bytes) is row idx / (C/8) of
