@@ -25,6 +25,7 @@ constexpr int kWave = 64;
 constexpr int kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
 constexpr int kRpad = 64;             // row pitch of the transposed region keys (R <= 64)
 constexpr int kFastRouteMaxS = 8;     // the in-kernel routing covers S <= 8 (R <= 64)
+constexpr int kTopkRoundsMax = 4;     // up to this k the top-k runs k wavefront-maximum rounds, beyond it rank counting
 constexpr int kPoolMaxGroup = 8;      // regions pooled by one workgroup, at most
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c)
@@ -137,7 +138,7 @@ __device__ __forceinline__ uint32_t topk_order_key(float v, int j, int R)
 __device__ __forceinline__ void wave_topk(float v, int j, int R, int k, int32_t *out)
 {
     const uint32_t u = topk_order_key(v, j, R);
-    if (k <= 20) {
+    if (k <= kTopkRoundsMax) {
         bool avail = j < R;
         for (int p = 0; p < k; ++p) {
             const uint32_t m = wave_umax(avail ? u : 0u);
@@ -167,7 +168,7 @@ template <int NR>
 __device__ __forceinline__ void wave_topk_rows(const float (&v)[NR], int nrows, int j, int R, int k,
                                                int32_t *out)
 {
-    if (k > 20) {
+    if (k > kTopkRoundsMax) {
 #pragma unroll
         for (int rr = 0; rr < NR; ++rr)
             if (rr < nrows) wave_topk(v[rr], j, R, k, out + rr * k);
