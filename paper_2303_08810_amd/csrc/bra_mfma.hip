@@ -490,11 +490,12 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ WT, bf16_t *
 }
 
 // ---------------------------------------------------------------------------
-// LDS map shared by the two attention kernels.  Rows of bf16 tiles have CS = C + 8
-// elements (16-byte pad against bank conflicts), rows of the float32 output tile OS.
+// LDS map of the staged attention kernel.  Rows of bf16 tiles have CS = C + 16 elements
+// (a pitch of 32 bytes x odd: full rate for the 16-byte operand reads and the transposing
+// reads), rows of the float32 output tile OS.
 template <int C>
 struct AttnSmem {
-    static constexpr int CS = C + 8;
+    static constexpr int CS = C + 16;
     static constexpr int OS = C + 4;
     static constexpr size_t k_off = 0;                                // K tile; output tile later
     static constexpr size_t v_off = k_off + (size_t)64 * CS * 2;      // V tile (fused: Q tile first)
@@ -573,15 +574,21 @@ __global__ __launch_bounds__(256) void k_attn_big(AttnArgs A, Dims D)
     SoftmaxState<HEADS> st;
     st.init();
     const int nblocks = D.kn / 64;
-    for (int kb = 0; kb < nblocks; ++kb) {
+    // K / V blocks of 64 routed tokens: the next block is requested as soon as the current
+    // one has been handed to LDS, so that its latency hides behind the current block's work.
+    u32x4 kreg[NBT], vreg[NBT];
+    auto request = [&](int kb) {
         const int j = irp[kb / chunks];
         const int ky0 = (j / D.S) * D.rh + (kb % chunks) * qh, kx0 = (j % D.S) * D.rw;
-        u32x4 kreg[NBT], vreg[NBT];
         tile_load<C, NBT>(kreg, A.K + img_off, ky0, kx0, D.rw, rw_inv, 64, D.H, D.W, 0);
         tile_load<C, NBT>(vreg, A.V + img_off, ky0, kx0, D.rw, rw_inv, 64, D.H, D.W, 0);
+    };
+    request(0);
+    for (int kb = 0; kb < nblocks; ++kb) {
         __syncthreads();   // the previous block's readers are done with Ks / Vs
         tile_store<C, CS, NBT>(Ks, kreg, 64, 0);
         tile_store<C, CS, NBT>(Vs, vreg, 64, 0);
+        if (kb + 1 < nblocks) request(kb + 1);
         __syncthreads();
         attn_key_block<C, CS>(Ks, Vs, qf, st, A.c_exp, g, i);
     }
