@@ -85,7 +85,8 @@ def kernel_model(name, cfg):
         "mfma_attention": ("hbm", 4 * unit, HBM_PEAK_GBS),             # Q K V in, Y out
         "mfma_fused_k1": ("hbm", 2 * unit, HBM_PEAK_GBS),              # X in, Y out
         "mfma_attn_small": ("hbm", 4 * unit, HBM_PEAK_GBS),            # Q K V in, O out
-        "mfma_lce_wo": ("hbm", 3 * unit, HBM_PEAK_GBS),                # O V in, Y out
+        "mfma_lce_add": ("hbm", 3 * unit, HBM_PEAK_GBS),               # O V in, O out
+        "mfma_wo": ("hbm", 2 * unit, HBM_PEAK_GBS),                    # O in, Y out
     }
     return table[name]
 

@@ -384,8 +384,9 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
 }
 
 // ---------------------------------------------------------------------------
-// Q, K, V = X [Wq | Wk | Wv]  (Eq. 3).  Each wavefront owns 64 output channels of one
-// of the three matrices and keeps its weight fragments in registers; a workgroup is
+// Q, K, V = X [Wq | Wk | Wv]  (Eq. 3; NMAT = 3), or a single projection such as Y = O Wo
+// (Eq. 2; NMAT = 1, every output pointer the same).  Each wavefront owns 64 output channels of one
+// of the NMAT matrices and keeps its weight fragments in registers; a workgroup is
 // WPB such wavefronts (blockIdx.y selects which) and walks over `tiles_per_wg`
 // consecutive tiles of 64 tokens.  A tile of X is fetched once per workgroup with
 // fully coalesced 16-byte loads (one tile ahead, held in registers while the current
@@ -399,7 +400,7 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
 // consecutive tokens, which always lie in one row of one region, are summed across lanes
 // before the rounding to bf16, and written as P[token / group][2C] = [sum Q | sum K].  The
 // routing kernel adds the few partial sums of each region.
-template <int C, int WPB>
+template <int C, int WPB, int NMAT>
 __global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, 2)))
 void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ WT, bf16_t *__restrict__ Q,
            bf16_t *__restrict__ K, bf16_t *__restrict__ V, float *__restrict__ P, int group_log2, long M,
@@ -411,7 +412,7 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ WT, bf16_t *
     bf16_t *xs0 = (bf16_t *)smem;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
-    const int grp = blockIdx.y * WPB + wave;            // 64-channel group among 3C/64
+    const int grp = blockIdx.y * WPB + wave;            // 64-channel group among NMAT C / 64
     const int sel = grp / (C / 64), base = (grp % (C / 64)) * 64;
     bf16_t *__restrict__ out = sel == 0 ? Q : (sel == 1 ? K : V);
     const int group = 1 << group_log2;
@@ -1025,11 +1026,30 @@ int launch_qkv(const Dims &D, const bf16_t *X, const MfmaWs &w, bool pooled, hip
     const int gx = (int)((ntiles + tpw - 1) / tpw);
     const size_t smem = (size_t)2 * 64 * (C + 16) * 2;
     static bool opted = false;
-    if (!lds_opt_in(k_qkv<C, WPB>, opted)) return BRA_ERR_LAUNCH;
+    if (!lds_opt_in(k_qkv<C, WPB, 3>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_QKV);
-    hipLaunchKernelGGL((k_qkv<C, WPB>), dim3(gx, gy), dim3(64 * WPB), smem, st, X, w.wt, w.q, w.k, w.v,
+    hipLaunchKernelGGL((k_qkv<C, WPB, 3>), dim3(gx, gy), dim3(64 * WPB), smem, st, X, w.wt, w.q, w.k, w.v,
                        pooled ? w.p : nullptr, pool_group_log2(D), M, (int)tpw);
     return BRA_OK;
+}
+
+// Y = O Wo (Eq. 2) as a plain projection of a token map: the projection kernel with the
+// rows of Wo^T as its only weight matrix.
+template <int C>
+int launch_wo(const Dims &D, const bf16_t *O, const MfmaWs &w, bf16_t *Y, hipStream_t st)
+{
+    const long M = (long)D.B * D.N;
+    constexpr int WPB = C / 64;
+    const long ntiles = (M + 63) / 64;
+    const long tpw = (ntiles + 511) / 512;
+    const int gx = (int)((ntiles + tpw - 1) / tpw);
+    const size_t smem = (size_t)2 * 64 * (C + 16) * 2;
+    static bool opted = false;
+    if (!lds_opt_in(k_qkv<C, WPB, 1>, opted)) return BRA_ERR_LAUNCH;
+    ProfScope ps(st, K_MFMA_WO);
+    hipLaunchKernelGGL((k_qkv<C, WPB, 1>), dim3(gx, 1), dim3(64 * WPB), smem, st, O, w.wot, Y, Y, Y, nullptr, 0, M,
+                       (int)tpw);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
 bool attn_big_ok(const Dims &D);
@@ -1095,7 +1115,11 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
             return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
         }
     }
-    if (!attn_big_ok(D)) return launch_small(D, A, w.o, st);
+    if (!attn_big_ok(D)) {
+        const int rc = launch_small(D, A, w.o, st);
+        if (rc != BRA_OK || !small_needs_projection(D)) return rc;
+        return launch_wo<C>(D, w.o, w, Y, st);
+    }
     {
         static bool opted = false;
         if (!lds_opt_in(k_attn_big<C>, opted)) return BRA_ERR_LAUNCH;

@@ -486,10 +486,11 @@ __device__ __forceinline__ int swizzled_block()
 
 }  // namespace mfma
 
-// Small-region pipeline tail (bra_mfma_small.hip): per-(region, head) attention into O,
-// then LCE + output projection over row tiles.  A.Q/K/V, routing fields, Wlce, WoT, Y set.
+// Small-region pipeline tail (bra_mfma_small.hip): either everything up to Y in one kernel,
+// or per-(region, head) attention into O and the LCE added in place (then W^o is left).  A.Q/K/V, routing fields, Wlce, WoT, Y set.
 bool small_supported(const Dims &D);
 size_t small_scratch_bytes(const Dims &D);
+bool small_needs_projection(const Dims &D);   // launch_small left O = attention + LCE in its scratch map: Y = O Wo is still to do
 int launch_small(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st);
 
 }  // namespace bra

@@ -9,7 +9,8 @@
 // For regions of 16 tokens the same workgroup then adds the LCE of its tokens (Eq. 7; 5x5
 // depth-wise correlation of V over the region plus a 2-token halo, staged in LDS) and
 // applies W^o (Eq. 2), so the attention output never travels through memory (k_small).
-// Smaller regions use two kernels (k_attn_small, k_lce_wo).
+// Smaller regions use separate kernels: k_attn_small (attention output to memory),
+// k_lce_add (adds the LCE in place), then the projection kernel with W^o.
 #include "bra_mfma_dev.h"
 
 namespace bra {
@@ -299,117 +300,88 @@ __global__ __launch_bounds__(256) void k_attn_small(AttnArgs A, bf16_t *__restri
 }
 
 // ---------------------------------------------------------------------------
-// Y = (O_att + LCE(V)) Wo over a tile of TH full-width image rows (TH * W <= 64 tokens).
-// LDS: V halo tile [(TH + 4) x (W + 4)] tokens, LCE weights, and the bf16 sum tile that
-// feeds the output projection.  Wavefront w owns output channels [w C/4, (w+1) C/4).
-template <int C>
-struct LceWoSmem {
-    static constexpr int CS = C + 8;
-    static constexpr size_t o_off = 0;                                   // sum tile [64][CS] bf16
-    static constexpr size_t w_off = o_off + (size_t)64 * CS * 2;         // LCE weights [25][C] f32
-    static constexpr size_t h_off = w_off + (size_t)25 * C * 4;          // V halo tile
-    static size_t bytes(int halo_rows) { return h_off + (size_t)(halo_rows + 16) * CS * 2; }
-};
+// O <- O_att + LCE(V) (Eq. 7) in place, for workgroup (image, tile of TH full-width image
+// rows, chunk of 64 channels).  LDS holds the V halo tile of the chunk, [(TH + 4) x (W + 4)]
+// tokens x 64 channels; a thread keeps one channel pair for all its (row, 4-token segment)
+// tasks, so its 2 x 25 weights stay in registers.  W^o follows as a plain projection.
+constexpr int kLceChunk = 64, kLcePitch = kLceChunk + 8;
 
 template <int C>
-__global__ __launch_bounds__(256) void k_lce_wo(const bf16_t *__restrict__ Oatt,
-                                                const bf16_t *__restrict__ V,
-                                                const bf16_t *__restrict__ Wlce,
-                                                const bf16_t *__restrict__ WoT,
-                                                bf16_t *__restrict__ Y, Dims D, int TH)
+__global__ __launch_bounds__(256) void k_lce_add(bf16_t *__restrict__ O, const bf16_t *__restrict__ V,
+                                                 const bf16_t *__restrict__ Wlce, Dims D, int TH)
 {
-    typedef LceWoSmem<C> SM;
-    constexpr int CS = SM::CS, KS = C / 32, CH = C / 8, NT = C / 64;
-    constexpr int NBH = 4;
+    constexpr int NCH = C / kLceChunk, CH8 = kLceChunk / 8, NBH = 6;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16_t *Ob = (bf16_t *)(smem + SM::o_off);
-    float *Wl = (float *)(smem + SM::w_off);
-    bf16_t *Hs = (bf16_t *)(smem + SM::h_off);
-
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int g = lane / 16, i = lane % 16;
+    bf16_t *Hs = (bf16_t *)smem;
     const int tiles = (D.H + TH - 1) / TH;
-    const int b = blockIdx.x / tiles, y0 = (blockIdx.x % tiles) * TH;
+    const int cc = blockIdx.x % NCH, tile = (blockIdx.x / NCH) % tiles, b = blockIdx.x / (NCH * tiles);
+    const int y0 = tile * TH;
     const int th = min(TH, D.H - y0);            // rows of this tile
-    const int ntok = th * D.W;
     const size_t img_off = (size_t)b * D.N * C;
     const int hw = D.W + 4, hrows = (th + 4) * hw;
     const float hw_inv = 1.0f / (float)hw;
+    const int c0 = cc * kLceChunk;
 
-    LceWeights<C> lw;
-    lw.load(Wlce);
-    for (int first = 0; first < hrows * CH; first += 256 * NBH) {
+    const int cpair = threadIdx.x % (kLceChunk / 2);
+    unsigned wl[25];        // [W(c, 0..24) | W(c + 1, 0..24)] as 25 packed pairs
+#pragma unroll
+    for (int e = 0; e < 25; ++e) wl[e] = *(const unsigned *)(Wlce + (size_t)(c0 + 2 * cpair) * 25 + 2 * e);
+    auto tap = [&](int ch, int t) {   // weight of tap t of channel c + ch
+        const int e = 25 * ch + t;
+        return (e & 1) ? bf16_hi(wl[e / 2]) : bf16_lo(wl[e / 2]);
+    };
+    for (int first = 0; first < hrows * CH8; first += 256 * NBH) {
         u32x4 hreg[NBH];
-        tile_load<C, NBH>(hreg, V + img_off, y0 - 2, -2, hw, hw_inv, hrows, D.H, D.W, first);
-        tile_store<C, CS, NBH>(Hs, hreg, hrows, first);
+#pragma unroll
+        for (int u = 0; u < NBH; ++u) {
+            const int idx = first + (int)threadIdx.x + 256 * u;
+            const int row = idx / CH8, c8 = idx % CH8;
+            const int ry = fast_div(row, hw_inv);
+            const int y = y0 - 2 + ry, x = row - ry * hw - 2;
+            hreg[u] = u32x4{0u, 0u, 0u, 0u};
+            if (row < hrows && y >= 0 && y < D.H && x >= 0 && x < D.W)
+                hreg[u] = *(const u32x4 *)(V + img_off + ((size_t)y * D.W + x) * C + c0 + c8 * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < NBH; ++u) {
+            const int idx = first + (int)threadIdx.x + 256 * u;
+            if (idx < hrows * CH8) *(u32x4 *)(Hs + (idx / CH8) * kLcePitch + (idx % CH8) * 8) = hreg[u];
+        }
     }
-    lw.store(Wl);
     __syncthreads();
 
-    // LCE over (row, 8-token segment, channel pair) tasks; the sum with the attention
-    // output is rounded to bf16 once and becomes the B operand of the output projection.
-    {
-        const int segs = (D.W + 7) / 8, cp_n = C / 2;
-        const int tasks = th * segs * cp_n;
-        const bf16_t *orow = Oatt + img_off + (size_t)y0 * D.W * C;
-        for (int task = threadIdx.x; task < tasks; task += 256) {
-            const int cp = task % cp_n, seg = (task / cp_n) % segs, r = task / (cp_n * segs);
-            const int c = 2 * cp;
-            float a0[8], a1[8];
+    const int cp_n = kLceChunk / 2, segs = (D.W + 3) / 4;
+    const int tasks = th * segs * cp_n;
+    for (int task = threadIdx.x; task < tasks; task += 256) {
+        const int seg = (task / cp_n) % segs, r = task / (cp_n * segs);
+        float a0[4] = {0.f, 0.f, 0.f, 0.f}, a1[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int x = 0; x < 8; ++x) { a0[x] = 0.f; a1[x] = 0.f; }
-#pragma unroll
-            for (int ky = 0; ky < 5; ++ky) {
-                f32x2 wk[5];
-#pragma unroll
-                for (int kx = 0; kx < 5; ++kx) wk[kx] = *(const f32x2 *)(Wl + (ky * 5 + kx) * C + c);
-                float v0[12], v1[12];
-#pragma unroll
-                for (int x = 0; x < 12; ++x) {   // a ragged last segment reads into the pad rows
-                    const unsigned u = *(const unsigned *)(Hs + ((r + ky) * hw + seg * 8 + x) * CS + c);
-                    v0[x] = bf16_lo(u);
-                    v1[x] = bf16_hi(u);
-                }
-#pragma unroll
-                for (int x = 0; x < 8; ++x)
-#pragma unroll
-                    for (int kx = 0; kx < 5; ++kx) {
-                        a0[x] = fmaf(wk[kx][0], v0[x + kx], a0[x]);
-                        a1[x] = fmaf(wk[kx][1], v1[x + kx], a1[x]);
-                    }
-            }
+        for (int ky = 0; ky < 5; ++ky) {
+            float v0[8], v1[8];
 #pragma unroll
             for (int x = 0; x < 8; ++x) {
-                const int xx = seg * 8 + x;
-                if (xx < D.W) {
-                    const int tok = r * D.W + xx;
-                    const unsigned o2 = *(const unsigned *)(orow + (size_t)tok * C + c);
-                    *(unsigned *)(Ob + tok * CS + c) = pack_bf16(bf16_lo(o2) + a0[x], bf16_hi(o2) + a1[x]);
+                const int hx = min(seg * 4 + x, hw - 1);    // a ragged segment re-reads the last column; unused
+                const unsigned u = *(const unsigned *)(Hs + ((r + ky) * hw + hx) * kLcePitch + 2 * cpair);
+                v0[x] = bf16_lo(u);
+                v1[x] = bf16_hi(u);
+            }
+#pragma unroll
+            for (int kx = 0; kx < 5; ++kx) {
+                const float w0 = tap(0, ky * 5 + kx), w1 = tap(1, ky * 5 + kx);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    a0[x] = fmaf(w0, v0[x + kx], a0[x]);
+                    a1[x] = fmaf(w1, v1[x + kx], a1[x]);
                 }
             }
         }
-    }
-    __syncthreads();
-
-    // Y^T slice = Wo^T slice * O^T: this wavefront's output channels of all tokens.
+        unsigned *orow = (unsigned *)(O + img_off + ((size_t)(y0 + r) * D.W + seg * 4) * C + c0 + 2 * cpair);
+        unsigned o2[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        if (16 * u >= ntok) break;
-        const int q = 16 * u + i;
-        bf16x8 of[KS];
+        for (int x = 0; x < 4; ++x) o2[x] = seg * 4 + x < D.W ? orow[(size_t)x * C / 2] : 0u;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) of[ks] = *(const bf16x8 *)(Ob + q * CS + 32 * ks + 8 * g);
-        bf16_t *yrow = Y + img_off + ((size_t)y0 * D.W + q) * C;
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            f32x4 ya = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 wf = *(const bf16x8 *)(WoT + (size_t)(16 * (wave * NT + t) + i) * C + 32 * ks + 8 * g);
-                ya = mfma16(wf, of[ks], ya);
-            }
-            if (q < ntok) *(u32x2 *)(yrow + 16 * (wave * NT + t) + 4 * g) = pack4(ya);
-        }
+        for (int x = 0; x < 4; ++x)
+            if (seg * 4 + x < D.W) orow[(size_t)x * C / 2] = pack_bf16(bf16_lo(o2[x]) + a0[x], bf16_hi(o2[x]) + a1[x]);
     }
 }
 
@@ -429,8 +401,7 @@ static bool one_kernel(const Dims &D)
     return D.rh * ((D.rw + 3) / 4) * (D.C / 2) <= 256 * kMaxLceTasks;
 }
 
-template <int C>
-static size_t lce_wo_smem(const Dims &D) { return LceWoSmem<C>::bytes((tile_rows(D) + 4) * (D.W + 4)); }
+static size_t lce_add_smem(const Dims &D) { return (size_t)(tile_rows(D) + 4) * (D.W + 4) * kLcePitch * 2; }
 
 bool small_supported(const Dims &D)
 {
@@ -440,10 +411,14 @@ bool small_supported(const Dims &D)
         smem = D.C == 64 ? small_smem<64>(D) : D.C == 128 ? small_smem<128>(D) : small_smem<256>(D);
     } else {
         if (D.W > 64) return false;
-        smem = D.C == 64 ? lce_wo_smem<64>(D) : D.C == 128 ? lce_wo_smem<128>(D) : lce_wo_smem<256>(D);
+        smem = lce_add_smem(D);
+        const size_t attn = D.C == 64 ? SmallSmem<64>::kv_bytes : D.C == 128 ? SmallSmem<128>::kv_bytes : SmallSmem<256>::kv_bytes;
+        if (attn > smem) smem = attn;
     }
     return smem <= (size_t)kMaxLds;
 }
+
+bool small_needs_projection(const Dims &D) { return !one_kernel(D); }
 
 size_t small_scratch_bytes(const Dims &D)
 {
@@ -484,12 +459,12 @@ static int launch_small_c(const Dims &D, const AttnArgs &A0, bf16_t *O, hipStrea
     }
     {
         static bool opted = false;
-        if (!opt_in(k_lce_wo<C>, opted)) return BRA_ERR_LAUNCH;
+        if (!opt_in(k_lce_add<C>, opted)) return BRA_ERR_LAUNCH;
         const int TH = tile_rows(D);
         const int tiles = (D.H + TH - 1) / TH;
-        ProfScope ps(st, K_MFMA_LCE_WO);
-        hipLaunchKernelGGL(k_lce_wo<C>, dim3(D.B * tiles), dim3(256), lce_wo_smem<C>(D), st, O, A.V, A.Wlce,
-                           A.WoT, A.Y, D, TH);
+        ProfScope ps(st, K_MFMA_LCE_ADD);
+        hipLaunchKernelGGL(k_lce_add<C>, dim3(D.B * tiles * (C / kLceChunk)), dim3(256), lce_add_smem(D), st, O,
+                           A.V, A.Wlce, D, TH);
     }
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }

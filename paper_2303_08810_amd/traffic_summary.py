@@ -16,7 +16,7 @@ import sys
 COPY_BYTES = 64 << 20
 NAMES = {"k_fused": "mfma_fused_k1", "k_pool": "mfma_pool_qk", "k_route": "mfma_route_rows",
          "k_qkv": "mfma_qkv", "k_attn_big": "mfma_attention", "k_attn_small": "mfma_attn_small",
-         "k_small": "mfma_attn_small", "k_lce_wo": "mfma_lce_wo", "k_prep_weights": "mfma_prep",
+         "k_small": "mfma_attn_small", "k_lce_add": "mfma_lce_add", "k_prep_weights": "mfma_prep",
          "k_util_copy": "copy"}
 
 
@@ -28,7 +28,10 @@ def averages(directory, counter):
                 continue
             m = re.search(r"(k_[a-z0-9_]+)", row["Kernel_Name"])
             if m and m.group(1) in NAMES:
-                acc[NAMES[m.group(1)]].append(float(row["Counter_Value"]))
+                name = NAMES[m.group(1)]
+                if re.search(r"k_qkv<\d+, \d+, 1>", row["Kernel_Name"]):   # the same kernel with Wo as its only matrix
+                    name = "mfma_wo"
+                acc[name].append(float(row["Counter_Value"]))
     return {k: sum(v) / len(v) for k, v in acc.items()}
 
 
