@@ -73,6 +73,8 @@ MFMA_SHAPES = [  # (B, H, W, C, heads, S, k): regions of n >= 64 tokens, d = 32
     (2, 24, 24, 64, 2, 3, 9),
     (1, 32, 32, 128, 4, 4, 5),
     (5, 56, 56, 64, 2, 7, 1),
+    (2, 8, 32, 64, 2, 2, 1),       # k = 1 with 4 x 16 regions: the fused kernel's wide-region variant
+    (3, 24, 48, 64, 2, 3, 1),      # 8 x 16 regions: 128 tokens per region, staged pipeline with k = 1
 ]
 
 
@@ -159,16 +161,23 @@ def test_repeated_runs_are_bit_identical():
         np.testing.assert_array_equal(i, outs[0][1])
 
 
-def test_constant_image_ties_and_zero_input():
-    # constant image: every affinity equal -> indices 0..k-1 ascending (tie rule)
-    H = W = 14; C = 64; S = 7; k = 4; heads = 2
-    _, Wqkv, Wo, Wlce = make_inputs(1, H, W, C, seed=3)
+@pytest.mark.parametrize("dtype,H,k", [("f32", 14, 4), ("bf16", 14, 4), ("bf16", 14, 9), ("bf16", 56, 1),
+                                       ("bf16", 56, 6)])
+def test_constant_image_ties_and_zero_input(dtype, H, k):
+    # constant image: every affinity equal -> indices 0..k-1 ascending (tie rule), in every
+    # routing kernel: maximum rounds (k <= 4) and rank counting (k > 4), from pooled X and
+    # from the projection kernel's partial sums
+    W = H; C = 64; S = 7; heads = 2
+    _, Wqkv, Wo, Wlce = make_inputs(1, H, W, C, seed=3, dtype=dtype)
     x0 = np.linspace(-1, 1, C).astype(np.float32)
+    if dtype == "bf16":
+        from synthetic_inputs import round_to_bf16
+        x0 = round_to_bf16(x0)
     X = np.broadcast_to(x0, (1, H, W, C)).copy()
-    Y, Ir, _, _ = gpu_forward(X, Wqkv, Wo, Wlce, "f32", S, k, heads, "auto")
+    Y, Ir, _, _ = gpu_forward(X, Wqkv, Wo, Wlce, dtype, S, k, heads, "auto")
     assert np.all(Ir == np.arange(k))
     ref = run_oracle(X, Wqkv, Wo, Wlce, dict(S=S, k=k, heads=heads), Ir_in=Ir)
-    check_output(Y, ref["Y"], "f32")
+    check_output(Y, ref["Y"], dtype)
     Xz = np.zeros_like(X)
-    Y, Ir, _, _ = gpu_forward(Xz, Wqkv, Wo, Wlce, "f32", S, k, heads, "auto")
+    Y, Ir, _, _ = gpu_forward(Xz, Wqkv, Wo, Wlce, dtype, S, k, heads, "auto")
     assert np.all(Y == 0) and np.all(Ir == np.arange(k))
