@@ -241,7 +241,9 @@ __global__ __launch_bounds__(256) void k_route(const float *__restrict__ Xr,
     float *Kt = (float *)smem;                    // [C / 4][kRouteRS][4]
     float *Qs = Kt + C * kRouteRS;                // [16][QS]
     const int groups = (D.R + 15) / 16;
-    const int b = blockIdx.x / groups, myrt = blockIdx.x % groups;
+    const int wid = swizzled_block();          // the workgroups of an image share an XCD (and its L2)
+    if (wid >= D.B * groups) return;
+    const int b = wid / groups, myrt = wid % groups;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
     const int nrt = (D.R + 15) / 16;              // region tiles that exist
@@ -336,7 +338,9 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
     float *Kt = (float *)smem;                    // [C / 4][kRouteRS][4]
     float *Qs = Kt + C * kRouteRS;                // [16][QS]
     const int groups = (D.R + 15) / 16;
-    const int b = blockIdx.x / groups, myrt = blockIdx.x % groups;
+    const int wid = swizzled_block();          // the workgroups of an image share an XCD (and its L2)
+    if (wid >= D.B * groups) return;
+    const int b = wid / groups, myrt = wid % groups;
     const int pw = D.W >> group_log2, pc = D.rw >> group_log2;      // partial sums per image row / region row
     const float inv_n = 1.0f / (float)D.n;
     // Work items (region, 4 channels): all of K^r, then the 16 query rows of Q^r.  A thread
@@ -995,7 +999,7 @@ int launch_route(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, hip
     if (!lds_opt_in(k_route<C>, opted)) return BRA_ERR_LAUNCH;
     const size_t smem = RouteSmem<C>::bytes;
     ProfScope ps(st, K_MFMA_ROUTE_ROWS);
-    hipLaunchKernelGGL(k_route<C>, dim3(D.B * ((D.R + 15) / 16)), dim3(256), smem, st, w.xr, w.wt, Ir,
+    hipLaunchKernelGGL(k_route<C>, dim3((D.B * ((D.R + 15) / 16) + 7) / 8 * 8), dim3(256), smem, st, w.xr, w.wt, Ir,
                        Ar_opt, D);
     return BRA_OK;
 }
@@ -1006,7 +1010,7 @@ int launch_route_p(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, h
     static bool opted = false;
     if (!lds_opt_in(k_route_p<C>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_ROUTE_ROWS);
-    hipLaunchKernelGGL(k_route_p<C>, dim3(D.B * ((D.R + 15) / 16)), dim3(256), RouteSmem<C>::kq_bytes, st,
+    hipLaunchKernelGGL(k_route_p<C>, dim3((D.B * ((D.R + 15) / 16) + 7) / 8 * 8), dim3(256), RouteSmem<C>::kq_bytes, st,
                        w.p, Ir, Ar_opt, D, pool_group_log2(D));
     return BRA_OK;
 }
