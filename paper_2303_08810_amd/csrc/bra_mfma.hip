@@ -83,6 +83,14 @@ __host__ __device__ constexpr int prep_total(int C)
     return 4 * C * C + kLceOperandElems * C + (C == 64 ? kFusedFragElems : 0);
 }
 
+// Everything the weight rearrangement reads and writes, for kernels that carry it along
+// in extra workgroups.
+struct PrepArgs {
+    const bf16_t *Wqkv, *Wo, *Wlce;
+    bf16_t *WT, *WoT, *Wa, *Wf;
+    int elems;                      // leading prep elements to produce (0: none)
+};
+
 // `total` = prep_total(C) (all weights) or 3 C^2 (projection weights only; Wo and Wlce
 // may be NULL).
 __global__ void k_prep_weights(const bf16_t *__restrict__ Wqkv, const bf16_t *__restrict__ Wo,
@@ -392,7 +400,8 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
 // (Eq. 2; NMAT = 1, every output pointer the same).  Each wavefront owns 64 output channels of one
 // of the NMAT matrices and keeps its weight fragments in registers; a workgroup is
 // WPB such wavefronts (blockIdx.y selects which) and walks over `tiles_per_wg`
-// consecutive tiles of 64 tokens.  A tile of X is fetched once per workgroup with
+// consecutive tiles of 64 tokens (blockIdx.x < gx; workgroups beyond that rearrange the
+// weights for the kernels that follow).  A tile of X is fetched once per workgroup with
 // fully coalesced 16-byte loads (one tile ahead, held in registers while the current
 // tile is computed), staged in LDS, and read from there as MFMA operands by all the
 // wavefronts.  The product is formed transposed (rows = output channels, columns =
@@ -406,14 +415,23 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
 // routing kernel adds the few partial sums of each region.
 template <int C, int WPB, int NMAT>
 __global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, 2)))
-void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ WT, bf16_t *__restrict__ Q,
+void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *__restrict__ Q,
            bf16_t *__restrict__ K, bf16_t *__restrict__ V, float *__restrict__ P, int group_log2, long M,
-           int tiles_per_wg)
+           int tiles_per_wg, int gx, PrepArgs prep)
 {
     constexpr int KS = C / 32, CH = C / 8, XP = C + 16, NTH = 64 * WPB;
     constexpr int NL = (64 * CH + NTH - 1) / NTH;       // 16-byte chunks of a tile per thread
+    constexpr int WP = 64 + 8;                          // row pitch of a wavefront's weight staging tile
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *xs0 = (bf16_t *)smem;
+    if ((int)blockIdx.x >= gx) {                        // workgroups past the token tiles rearrange weights
+        if (blockIdx.y == 0) {
+            const int e = ((int)blockIdx.x - gx) * NTH + (int)threadIdx.x;
+            if (e < prep.elems)
+                prep_weight_element(prep.Wqkv, prep.Wo, prep.Wlce, prep.WT, prep.WoT, prep.Wa, prep.Wf, C, e);
+        }
+        return;
+    }
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
     const int grp = blockIdx.y * WPB + wave;            // 64-channel group among NMAT C / 64
@@ -421,13 +439,40 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ WT, bf16_t *
     bf16_t *__restrict__ out = sel == 0 ? Q : (sel == 1 ? K : V);
     const int group = 1 << group_log2;
 
+    // This wavefront's weight slice W[:, sel C + base .. + 63] (row-major [C][NMAT C], as the
+    // caller holds it) -> MFMA A fragments with permuted rows: 64 input channels at a time
+    // are copied with coalesced loads into a wavefront-private LDS tile and come back through
+    // the transposing read (lane i of a 16-lane group supplies the address of 4 columns
+    // 16 (i % 4) + 4 tt .. of row i / 4 and receives column 16 (i / 4) + 4 tt + i % 4 of rows
+    // 0 .. 3).  LDS operations of one wavefront complete in order, so no barrier is needed.
     bf16x8 af[4][KS];
+    {
+        bf16_t *wb = (bf16_t *)(smem + (size_t)2 * 64 * XP * 2) + wave * 64 * WP;
+        const bf16_t *wsrc = W + sel * C + base;
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt) {
-        const int o = sel * C + base + 16 * (i / 4) + 4 * tt + (i % 4);
+        for (int kc = 0; kc < C / 64; ++kc) {
+            u32x4 wr[8];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            af[tt][ks] = *(const bf16x8 *)(WT + (size_t)o * C + 32 * ks + 8 * g);
+            for (int u = 0; u < 8; ++u) {
+                const int idx = lane + 64 * u;
+                wr[u] = *(const u32x4 *)(wsrc + (size_t)(64 * kc + idx / 8) * (NMAT * C) + (idx % 8) * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = lane + 64 * u;
+                *(u32x4 *)(wb + (idx / 8) * WP + (idx % 8) * 8) = wr[u];
+            }
+#pragma unroll
+            for (int kl = 0; kl < 2; ++kl)
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) {
+                    const bf16_t *src = wb + (32 * kl + 8 * g + i / 4) * WP + 16 * (i % 4) + 4 * tt;
+                    const s16x4 v0 = lds_read_tr16(src), v1 = lds_read_tr16(src + 4 * WP);
+                    const u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+                    const u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
+                    af[tt][2 * kc + kl] = __builtin_bit_cast(bf16x8, av);
+                }
+        }
     }
 
     const long ntiles = (M + 63) / 64;
@@ -1015,9 +1060,11 @@ int launch_route_p(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, h
     return BRA_OK;
 }
 
-// Q, K, V of all tokens into the workspace; with `pooled`, also the partial sums of Q and K.
+// Q, K, V of all tokens into the workspace; with `pooled`, also the partial sums of Q and K;
+// with prep.elems > 0, extra workgroups rearrange the weights for the kernels that follow.
 template <int C>
-int launch_qkv(const Dims &D, const bf16_t *X, const MfmaWs &w, bool pooled, hipStream_t st)
+int launch_qkv(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const MfmaWs &w, bool pooled,
+               const PrepArgs &prep, hipStream_t st)
 {
     const long M = (long)D.B * D.N;
     constexpr int WPB = (C == 256) ? 4 : 3 * C / 64;      // wavefronts (64-channel groups) per workgroup
@@ -1028,31 +1075,32 @@ int launch_qkv(const Dims &D, const bf16_t *X, const MfmaWs &w, bool pooled, hip
     long tpw = (ntiles * gy + 255) / 256;
     if (const char *e = getenv("BRA_QKV_TPW")) { int v = atoi(e); if (v >= 1 && v <= 4096) tpw = v; }
     const int gx = (int)((ntiles + tpw - 1) / tpw);
-    const size_t smem = (size_t)2 * 64 * (C + 16) * 2;
+    const int prep_blocks = (prep.elems + 64 * WPB - 1) / (64 * WPB);
+    const size_t smem = (size_t)2 * 64 * (C + 16) * 2 + (size_t)WPB * 64 * 72 * 2;
     static bool opted = false;
     if (!lds_opt_in(k_qkv<C, WPB, 3>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_QKV);
-    hipLaunchKernelGGL((k_qkv<C, WPB, 3>), dim3(gx, gy), dim3(64 * WPB), smem, st, X, w.wt, w.q, w.k, w.v,
-                       pooled ? w.p : nullptr, pool_group_log2(D), M, (int)tpw);
+    hipLaunchKernelGGL((k_qkv<C, WPB, 3>), dim3(gx + prep_blocks, gy), dim3(64 * WPB), smem, st, X, Wqkv, w.q,
+                       w.k, w.v, pooled ? w.p : nullptr, pool_group_log2(D), M, (int)tpw, gx, prep);
     return BRA_OK;
 }
 
-// Y = O Wo (Eq. 2) as a plain projection of a token map: the projection kernel with the
-// rows of Wo^T as its only weight matrix.
+// Y = O Wo (Eq. 2) as a plain projection of a token map: the projection kernel with Wo as
+// its only weight matrix.
 template <int C>
-int launch_wo(const Dims &D, const bf16_t *O, const MfmaWs &w, bf16_t *Y, hipStream_t st)
+int launch_wo(const Dims &D, const bf16_t *O, const bf16_t *Wo, bf16_t *Y, hipStream_t st)
 {
     const long M = (long)D.B * D.N;
     constexpr int WPB = C / 64;
     const long ntiles = (M + 63) / 64;
     const long tpw = (ntiles + 511) / 512;
     const int gx = (int)((ntiles + tpw - 1) / tpw);
-    const size_t smem = (size_t)2 * 64 * (C + 16) * 2;
+    const size_t smem = (size_t)2 * 64 * (C + 16) * 2 + (size_t)WPB * 64 * 72 * 2;
     static bool opted = false;
     if (!lds_opt_in(k_qkv<C, WPB, 1>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_WO);
-    hipLaunchKernelGGL((k_qkv<C, WPB, 1>), dim3(gx, 1), dim3(64 * WPB), smem, st, O, w.wot, Y, Y, Y, nullptr, 0, M,
-                       (int)tpw);
+    hipLaunchKernelGGL((k_qkv<C, WPB, 1>), dim3(gx, 1), dim3(64 * WPB), smem, st, O, Wo, Y, Y, Y, nullptr, 0, M,
+                       (int)tpw, gx, PrepArgs{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0});
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
@@ -1068,6 +1116,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     const int32_t *Ir_src = Ir_in_opt;
     int32_t *Ir_dst = Ir_out_opt ? Ir_out_opt : w.ir;
     const bool fused = C == 64 && fused_ok(D);
+    bool prep_pending = false;      // the weights still have to be rearranged, next to the projection
     if (!fast_route_ok(D)) {
         if (!Ir_in_opt) {
             int rc = valu_route(D, X, Wqkv, Ir_dst, nullptr, w.route, st);
@@ -1079,17 +1128,21 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
         hipLaunchKernelGGL(k_prep_weights, dim3((total + 255) / 256), dim3(256), 0, st, Wqkv, Wo, Wlce,
                            w.wt, w.wot, w.wa, w.wf, C, total);
     } else {
-        const bool from_x = (fused || !pooled_projection(D)) && !Ir_in_opt;      // pool X, route before the rest
-        launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/from_x, prep_total(C), st);
+        // pool X and route before the rest, with the weight rearrangement in the same launch;
+        // the pooled-projection pipelines need neither and rearrange next to the projection
+        const bool from_x = (fused || !pooled_projection(D)) && !Ir_in_opt;
+        if (fused || from_x) launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/from_x, prep_total(C), st);
         if (from_x) {
             const int rc = launch_route<C>(D, w, Ir_dst, nullptr, st);
             if (rc != BRA_OK) return rc;
             Ir_src = Ir_dst;
         }
+        prep_pending = !(fused || from_x);
     }
     if (!fused) {
         const bool pooled = pooled_projection(D) && !Ir_in_opt;
-        int rc = launch_qkv<C>(D, X, w, pooled, st);
+        const PrepArgs prep = {Wqkv, Wo, Wlce, w.wt, w.wot, w.wa, w.wf, prep_pending ? prep_total(C) : 0};
+        int rc = launch_qkv<C>(D, X, Wqkv, w, pooled, prep, st);
         if (rc != BRA_OK) return rc;
         if (pooled) {
             rc = launch_route_p<C>(D, w, Ir_dst, nullptr, st);
@@ -1122,7 +1175,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     if (!attn_big_ok(D)) {
         const int rc = launch_small(D, A, w.o, st);
         if (rc != BRA_OK || !small_needs_projection(D)) return rc;
-        return launch_wo<C>(D, w.o, w, Y, st);
+        return launch_wo<C>(D, w.o, Wo, Y, st);
     }
     {
         static bool opted = false;
@@ -1144,8 +1197,8 @@ int route_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, int32_t *Ir, flo
         launch_pool<C>(D, X, Wqkv, nullptr, nullptr, w, /*pool=*/true, /*prep: Wq^T, Wk^T*/ 2 * C * C, st);
         rc = launch_route<C>(D, w, Ir, Ar_opt, st);
     } else {
-        launch_pool<C>(D, X, Wqkv, nullptr, nullptr, w, /*pool=*/false, /*prep: [Wq|Wk|Wv]^T*/ 3 * C * C, st);
-        rc = launch_qkv<C>(D, X, w, /*pooled=*/true, st);
+        rc = launch_qkv<C>(D, X, Wqkv, w, /*pooled=*/true, PrepArgs{nullptr, nullptr, nullptr, nullptr, nullptr,
+                                                                     nullptr, nullptr, 0}, st);
         if (rc == BRA_OK) rc = launch_route_p<C>(D, w, Ir, Ar_opt, st);
     }
     if (rc != BRA_OK) return rc;
