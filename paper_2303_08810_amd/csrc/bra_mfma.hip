@@ -45,14 +45,33 @@ constexpr int kLceOperandElems = 160;   // per channel: 5 rows x 2 halves x 4 of
 // consecutive output channels).
 constexpr int kFusedFragElems = 16 * 2 * 64 * 8;
 
+// Elements of the small-region kernels' tables (Wo fragments, LCE weights tap-major).
+__host__ __device__ constexpr int small_table_elems(int C) { return C * C + 25 * C; }
+
 __device__ inline void prep_weight_element(const bf16_t *__restrict__ Wqkv,
                                            const bf16_t *__restrict__ Wo,
                                            const bf16_t *__restrict__ Wlce, bf16_t *__restrict__ WT,
                                            bf16_t *__restrict__ WoT, bf16_t *__restrict__ Wa,
                                            bf16_t *__restrict__ Wf, int C, int e)
 {
-    if (e >= 4 * C * C + kLceOperandElems * C) {       // only when C == 64
-        const int f = e - (4 * C * C + kLceOperandElems * C);
+    const int base_elems = 4 * C * C + kLceOperandElems * C;
+    if (e >= base_elems && e < base_elems + small_table_elems(C)) {
+        // tables of the small-region kernels, kept behind Wa: Wo as plain MFMA fragments
+        // WoF[ct][ks][lane 16 g + i][s] = Wo[32 ks + 8 g + s][16 ct + i], then the LCE weights
+        // tap-major, WlT[t][c] = Wlce[c][t]
+        const int f = e - base_elems;
+        bf16_t *tab = Wa + kLceOperandElems * C;
+        if (f < C * C) {
+            const int s = f % 8, lane = (f / 8) % kWave, ks = (f / 512) % (C / 32), ct = f / (512 * (C / 32));
+            tab[f] = Wo[(size_t)(32 * ks + 8 * (lane / 16) + s) * C + 16 * ct + lane % 16];
+        } else {
+            const int t = (f - C * C) / C, c = (f - C * C) % C;
+            tab[f] = Wlce[c * 25 + t];
+        }
+        return;
+    }
+    if (e >= base_elems) {                              // only when C == 64
+        const int f = e - base_elems - small_table_elems(C);
         const int s = f % 8, lane = (f / 8) % kWave, ks = (f / 512) % 2, rt = f / 1024;
         const int g = lane / 16, i = lane % 16;
         if (rt < 12) {
@@ -80,7 +99,7 @@ __device__ inline void prep_weight_element(const bf16_t *__restrict__ Wqkv,
 // Number of prep elements of a forward call.
 __host__ __device__ constexpr int prep_total(int C)
 {
-    return 4 * C * C + kLceOperandElems * C + (C == 64 ? kFusedFragElems : 0);
+    return 4 * C * C + kLceOperandElems * C + small_table_elems(C) + (C == 64 ? kFusedFragElems : 0);
 }
 
 // Everything the weight rearrangement reads and writes, for kernels that carry it along
@@ -985,7 +1004,7 @@ MfmaWs carve(const Dims &D, void *ws)
     w.o = (bf16_t *)take(small_supported(D) ? small_scratch_bytes(D) : 0);
     w.wt = (bf16_t *)take((size_t)3 * D.C * D.C * 2);
     w.wot = (bf16_t *)take((size_t)D.C * D.C * 2);
-    w.wa = (bf16_t *)take((size_t)D.C * kLceOperandElems * 2);
+    w.wa = (bf16_t *)take((size_t)(D.C * kLceOperandElems + small_table_elems(D.C)) * 2);
     w.wf = (bf16_t *)take(D.C == 64 ? (size_t)kFusedFragElems * 2 : 0);
     w.xr = (float *)take((size_t)D.B * D.R * D.C * sizeof(float));
     w.p = (float *)take(pooled_projection(D) ? (size_t)D.B * D.H * (D.W >> pool_group_log2(D)) * 2 * D.C * sizeof(float) : 0);
@@ -1152,7 +1171,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     }
     AttnArgs A;
     A.X = X; A.WT = w.wt; A.Q = w.q; A.K = w.k; A.V = w.v;
-    A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = Wlce; A.Wa = w.wa; A.Wf = w.wf; A.WoT = w.wot; A.Y = Y;
+    A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = Wlce; A.Wa = w.wa; A.WoF = w.wa + kLceOperandElems * C; A.WlT = A.WoF + C * C; A.Wf = w.wf; A.WoT = w.wot; A.Y = Y;
     A.c_exp = D.scale * 1.4426950408889634f;
     A.total = D.B * D.R * (D.n / 64);
     const int grid = ((A.total + 7) / 8) * 8;

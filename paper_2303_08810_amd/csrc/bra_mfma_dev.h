@@ -471,6 +471,7 @@ struct AttnArgs {
     const bf16_t *Wlce, *WoT;
     const bf16_t *Wa;               // LCE weights as 4x4x4 A operands (fused kernel)
     const bf16_t *Wf;               // projection weights in fragment order (fused kernel)
+    const bf16_t *WoF, *WlT;        // Wo as plain fragments, LCE weights [25][C] (small-region kernels)
     bf16_t *Y;
     float c_exp;                    // softmax scale * log2(e)
     int total;                      // workgroups that have work

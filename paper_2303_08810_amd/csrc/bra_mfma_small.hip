@@ -168,13 +168,10 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
     const int cp_n = C / 2, segs = (D.rw + 3) / 4;
     const int tasks = D.rh * segs * cp_n;
     const int cpair = threadIdx.x % cp_n;
-    unsigned wl[25];        // [W(c, 0..24) | W(c + 1, 0..24)] as 25 packed pairs
+    unsigned wl[25];        // tap t of channels (c, c + 1) as a packed pair, from the tap-major table
 #pragma unroll
-    for (int e = 0; e < 25; ++e) wl[e] = *(const unsigned *)(A.Wlce + (size_t)cpair * 50 + 2 * e);
-    auto tap = [&](int ch, int t) {   // weight of tap t of channel c + ch
-        const int e = 25 * ch + t;
-        return (e & 1) ? bf16_hi(wl[e / 2]) : bf16_lo(wl[e / 2]);
-    };
+    for (int t = 0; t < 25; ++t) wl[t] = *(const unsigned *)(A.WlT + (size_t)t * C + 2 * cpair);
+    auto tap = [&](int ch, int t) { return ch ? bf16_hi(wl[t]) : bf16_lo(wl[t]); };
     float lce[kMaxLceTasks][2][4];
     __syncthreads();        // the halo tile is complete
 #pragma unroll
@@ -246,7 +243,7 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
         f32x4 ya = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 wf = *(const bf16x8 *)(A.WoT + (size_t)(16 * ct + i) * C + 32 * ks + 8 * g);
+            const bf16x8 wf = *(const bf16x8 *)(A.WoF + ((size_t)(ct * KS + ks) * kWave + lane) * 8);
             ya = mfma16(wf, of[ks], ya);
         }
         if (i < n) *(u32x2 *)(yrow + 16 * ct + 4 * g) = pack4(ya);
