@@ -579,7 +579,8 @@ struct AttnSmem {
 // k routed regions are copied by index, 64 tokens at a time, from the projected
 // maps into LDS; one online softmax runs over all k n keys.
 template <int C>
-__global__ __launch_bounds__(256) void k_attn_big(AttnArgs A, Dims D)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3)))
+void k_attn_big(AttnArgs A, Dims D)
 {
     typedef AttnSmem<C> SM;
     constexpr int CS = SM::CS, OS = SM::OS, HEADS = C / 32, KS = C / 32, CH = C / 8;
