@@ -52,6 +52,7 @@ SMALL = [  # (B, H, W, C, heads, S, k): ragged tiles, odd head widths, n = 1, k 
     (2, 14, 14, 96, 3, 7, 16),
     (1, 64, 64, 32, 1, 2, 2),
     (1, 24, 24, 130, 2, 4, 5),
+    (2, 6, 9, 32, 1, 1, 1),        # S = 1, one head
 ]
 
 
@@ -75,6 +76,9 @@ MFMA_SHAPES = [  # (B, H, W, C, heads, S, k): regions of n >= 64 tokens, d = 32
     (5, 56, 56, 64, 2, 7, 1),
     (2, 8, 32, 64, 2, 2, 1),       # k = 1 with 4 x 16 regions: the fused kernel's wide-region variant
     (3, 24, 48, 64, 2, 3, 1),      # 8 x 16 regions: 128 tokens per region, staged pipeline with k = 1
+    (2, 8, 8, 64, 2, 1, 1),        # S = 1: one region, plain attention over the whole (tiny) map
+    (1, 16, 16, 128, 4, 1, 1),     # S = 1 with 256 tokens
+    (2, 4, 4, 64, 2, 1, 1),        # S = 1, 16 tokens: the small-region kernel with R = 1
 ]
 
 
