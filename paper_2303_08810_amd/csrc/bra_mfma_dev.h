@@ -210,10 +210,12 @@ __device__ __forceinline__ void tile_load(u32x4 (&r)[NB], const bf16_t *__restri
         const int row = idx / CH, cc = idx % CH;
         const int ty = fast_div(row, tw_inv);
         const int y = y0 + ty, x = x0 + row - ty * tw;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (row < rows && y >= 0 && y < H && x >= 0 && x < W)
-            v = *(const u32x4 *)(img + ((size_t)y * W + x) * C + cc * 8);
-        r[u] = v;
+        // branch-free: a chunk outside the tile or the image reads the first bytes of the
+        // image instead and is zeroed afterwards
+        const bool ok = row < rows && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W;
+        const unsigned off = ok ? (unsigned)((y * W + x) * C + cc * 8) : 0u;
+        const u32x4 v = *(const u32x4 *)(img + off);
+        r[u] = ok ? v : u32x4{0u, 0u, 0u, 0u};
     }
 }
 
