@@ -886,7 +886,7 @@ void k_fused(AttnArgs A, Dims D)
             const u32x4 kf = {lo[0], lo[1], hi[0], hi[1]};
             s[t] = mfma16(__builtin_bit_cast(bf16x8, kf), qb[h], f32x4{0.f, 0.f, 0.f, 0.f});
         }
-        softmax_pv_block<VP>(Vs, s, st, h, 32 * h, A.c_exp, g, i);
+        softmax_pv_block<VP, true>(Vs, s, st, h, 32 * h, A.c_exp, g, i);      // the only key block
     }
 
     // LCE of this wavefront's channels from its own halo planes:

@@ -286,7 +286,9 @@ struct SoftmaxState {
 // softmax over all routed keys), then O^T += V^T P^T with V read from the rows of Vs (VS
 // elements per row, the head's channels start at column vcol) by the transposing LDS read.
 // The head's running state is slot h of st.
-template <int VS, int HEADS>
+// FIRST: this is the head's first block (state as left by init()), so there is nothing to
+// rescale.
+template <int VS, bool FIRST = false, int HEADS>
 __device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (&s)[4],
                                                  SoftmaxState<HEADS> &st, int h, int vcol, float c_exp,
                                                  int g, int i)
@@ -298,8 +300,8 @@ __device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (
         for (int jj = 0; jj < 4; ++jj) mx = fmaxf(mx, s[t][jj]);
     mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
     mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    const float m_new = fmaxf(st.m[h], mx);
-    const float alpha = __builtin_amdgcn_exp2f((st.m[h] - m_new) * c_exp);
+    const float m_new = FIRST ? mx : fmaxf(st.m[h], mx);
+    const float alpha = FIRST ? 0.f : __builtin_amdgcn_exp2f((st.m[h] - m_new) * c_exp);
     const float mc = m_new * c_exp;
     float p[4][4], ls = 0.f;
 #pragma unroll
@@ -311,10 +313,12 @@ __device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (
         }
     ls += __shfl_xor(ls, 16, kWave);
     ls += __shfl_xor(ls, 32, kWave);
-    st.l[h] = st.l[h] * alpha + ls;
+    st.l[h] = FIRST ? ls : st.l[h] * alpha + ls;
     st.m[h] = m_new;
+    if (!FIRST) {
 #pragma unroll
-    for (int dt = 0; dt < 2; ++dt) st.acc[h][dt] *= alpha;
+        for (int dt = 0; dt < 2; ++dt) st.acc[h][dt] *= alpha;
+    }
 #pragma unroll
     for (int tp = 0; tp < 2; ++tp) {
         float pv[8] = {p[2 * tp][0], p[2 * tp][1], p[2 * tp][2], p[2 * tp][3],
