@@ -264,6 +264,29 @@ struct LceWeights {
     }
 };
 
+// Reductions over the four lanes {i, 16 + i, 32 + i, 48 + i} (one per 16-lane row), result
+// in all four: v_permlane16_swap / v_permlane32_swap exchange rows between two copies of
+// the value, so that two register-only steps replace two trips through the LDS crossbar.
+__device__ __forceinline__ float cross_row_max(float x)
+{
+    const int xi = __builtin_bit_cast(int, x);
+    const auto a = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);     // rows (0,1) and (2,3) paired
+    const float m = fmaxf(__builtin_bit_cast(float, (int)a[0]), __builtin_bit_cast(float, (int)a[1]));
+    const int mi = __builtin_bit_cast(int, m);
+    const auto b = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);     // halves paired
+    return fmaxf(__builtin_bit_cast(float, (int)b[0]), __builtin_bit_cast(float, (int)b[1]));
+}
+
+__device__ __forceinline__ float cross_row_sum(float x)
+{
+    const int xi = __builtin_bit_cast(int, x);
+    const auto a = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
+    const float m = __builtin_bit_cast(float, (int)a[0]) + __builtin_bit_cast(float, (int)a[1]);
+    const int mi = __builtin_bit_cast(int, m);
+    const auto b = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
+    return __builtin_bit_cast(float, (int)b[0]) + __builtin_bit_cast(float, (int)b[1]);
+}
+
 // Online-softmax state of one wavefront: 16 queries (one per lane column i), all heads.
 template <int HEADS>
 struct SoftmaxState {
@@ -298,8 +321,7 @@ __device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) mx = fmaxf(mx, s[t][jj]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    mx = cross_row_max(mx);
     const float m_new = FIRST ? mx : fmaxf(st.m[h], mx);
     const float alpha = FIRST ? 0.f : __builtin_amdgcn_exp2f((st.m[h] - m_new) * c_exp);
     const float mc = m_new * c_exp;
@@ -311,8 +333,7 @@ __device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (
             p[t][jj] = __builtin_amdgcn_exp2f(fmaf(s[t][jj], c_exp, -mc));
             ls += p[t][jj];
         }
-    ls += __shfl_xor(ls, 16, kWave);
-    ls += __shfl_xor(ls, 32, kWave);
+    ls = cross_row_sum(ls);
     st.l[h] = FIRST ? ls : st.l[h] * alpha + ls;
     st.m[h] = m_new;
     if (!FIRST) {
