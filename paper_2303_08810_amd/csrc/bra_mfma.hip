@@ -5,16 +5,19 @@
 // routed key/value tokens (Eq. 6) are copied by index from that layout into LDS,
 // never into a gathered tensor in memory.
 //
-// Routing (Eq. 4-5) is computed in float32 from X: a pooling kernel forms the
-// region means of X and from them Q^r and K^r (mean(X^r) W = mean(X^r W), exact in
-// real arithmetic); each attention workgroup then forms its own row of A^r and the
-// top-k of that row, so no separate routing launch sits on the forward path.
+// Routing (Eq. 4-5) is computed in float32, in one of two ways.  From X: a pooling
+// kernel forms the region means of X, a routing kernel projects them to Q^r and K^r on
+// the matrix cores with an exact three-term bf16 split (mean(X^r) W = mean(X^r W), exact
+// in real arithmetic), forms A^r and ranks its rows.  Or from the token projection: the
+// projection kernel also writes partial sums of its float32 Q / K accumulators, and the
+// routing kernel adds them up per region (used when a region has few of them).
 //
-// Two forward pipelines:
-//   staged : k_pool_qk -> k_qkv -> k_attn_big                      (any k)
-//   fused  : k_pool_qk -> k_fused   (projections recomputed per workgroup from X;
-//            used when every region attends to a single 64-token block, i.e. the
-//            k = 1 stage, where recomputing K and V costs less than storing them)
+// Forward pipelines:
+//   fused  : k_pool -> k_route -> k_fused            (k = 1, 64-token regions, C = 64:
+//            projections recomputed per workgroup from X, where recomputing K and V
+//            costs less than storing them)
+//   staged : k_pool -> k_route -> k_qkv -> k_attn_big                 (regions of 64 n tokens)
+//            k_qkv -> k_route_p -> small-region kernels (bra_mfma_small.hip)
 #include "bra_mfma_dev.h"
 
 #include <stdlib.h>
