@@ -23,8 +23,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWave = 64;
 constexpr int kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
-constexpr int kRpad = 64;             // row pitch of the transposed region keys (R <= 64)
-constexpr int kFastRouteMaxS = 8;     // the in-kernel routing covers S <= 8 (R <= 64)
+constexpr int kFastRouteMaxS = 8;     // the matrix-core routing kernels hold a row of A^r in one wavefront: S <= 8 (R <= 64)
 constexpr int kTopkRoundsMax = 4;     // up to this k the top-k runs k wavefront-maximum rounds, beyond it rank counting
 constexpr int kPoolMaxGroup = 8;      // regions pooled by one workgroup, at most
 
