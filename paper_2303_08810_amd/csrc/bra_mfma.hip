@@ -876,6 +876,10 @@ void k_fused(AttnArgs A, Dims D)
     }
     __syncthreads();
 
+    // From here on this wavefront goes first among those of its SIMD: workgroups in their
+    // late phases finish (and free their LDS for the next workgroup) sooner than they would
+    // in a fair interleave with workgroups that have only just started.  Measured: -3 %.
+    __builtin_amdgcn_s_setprio(2);
     // Attention of the 16 queries over the 64 keys (Eq. 1 with one routed block).
     SoftmaxState<HEADS> st;
     st.init();
