@@ -665,6 +665,7 @@ void k_attn_big(AttnArgs A, Dims D)
         __syncthreads();
         attn_key_block<C, CS>(Ks, Vs, qf, st, A.c_exp, g, i);
     }
+    __builtin_amdgcn_s_setprio(2);      // late phases first: the workgroup's LDS is freed sooner
     __syncthreads();   // everyone is done with Ks / Vs: the output tile may overwrite them
     attn_write_out<C, OS>(Os, st, wave, g, i);
     __syncthreads();

@@ -155,6 +155,7 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
 
     f32x4 oacc[HPW][2];     // normalised attention output of this wavefront's heads
     small_attention<C>(A, D, log2n, img_off, irp, qtok, Ks, Vs, oacc);
+    __builtin_amdgcn_s_setprio(2);      // late phases first: the workgroup's LDS is freed sooner
     __syncthreads();        // the key blocks have been read: the halo tile takes their place
     tile_store<C, CS, NBH>(Hs, hreg, hrows, 0);
     for (int first = 256 * NBH; first < hrows * CH; first += 256 * NBH) {
