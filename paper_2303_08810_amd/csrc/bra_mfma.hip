@@ -1039,10 +1039,8 @@ bool lds_opt_in(K kernel, bool &done)
 // (region, 8-channel chunk) pairs, and enough workgroups to fill the chip.
 int pool_group(const Dims &D)
 {
-    if (const char *e = getenv("BRA_POOL_GROUP")) {              // benchmarking aid
-        const int v = atoi(e);
-        if (v >= 1 && v <= kPoolMaxGroup && v * (D.C / 8) <= 256) return v;
-    }
+    static const int forced = getenv("BRA_POOL_GROUP") ? atoi(getenv("BRA_POOL_GROUP")) : 0;   // benchmarking aid
+    if (forced >= 1 && forced <= kPoolMaxGroup && forced * (D.C / 8) <= 256) return forced;
     const int chunks = D.n * (D.C / 8);
     int G = 2048 / chunks;
     const int cap = 256 / (D.C / 8) < kPoolMaxGroup ? 256 / (D.C / 8) : kPoolMaxGroup;
@@ -1101,7 +1099,8 @@ int launch_qkv(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const MfmaWs 
     // registers and the workgroup streams its share of the tokens
     const int gy = 3 * C / 64 / WPB;
     long tpw = (ntiles * gy + 255) / 256;
-    if (const char *e = getenv("BRA_QKV_TPW")) { int v = atoi(e); if (v >= 1 && v <= 4096) tpw = v; }
+    static const int forced = getenv("BRA_QKV_TPW") ? atoi(getenv("BRA_QKV_TPW")) : 0;       // benchmarking aid
+    if (forced >= 1 && forced <= 4096) tpw = forced;
     const int gx = (int)((ntiles + tpw - 1) / tpw);
     const int prep_blocks = (prep.elems + 64 * WPB - 1) / (64 * WPB);
     const size_t smem = (size_t)2 * 64 * (C + 16) * 2 + (size_t)WPB * 64 * 72 * 2;
