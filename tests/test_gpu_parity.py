@@ -151,6 +151,15 @@ def test_named_workloads_generic_family(idx):
     compare(X, Wqkv, Wo, Wlce, cfg.dtype, cfg.S, cfg.k, cfg.heads, "generic")
 
 
+@pytest.mark.parametrize("idx", [2, 3, 5])
+def test_named_workloads_smooth_inputs(idx):
+    # spatially smooth X (every region shifted by its own random vector): routing concentrates
+    # on few regions instead of spreading uniformly
+    cfg = CONFIGS[idx]
+    X, Wqkv, Wo, Wlce = make_config_inputs(cfg, batch=min(cfg.B, 3), smooth=True)
+    compare(X, Wqkv, Wo, Wlce, cfg.dtype, cfg.S, cfg.k, cfg.heads, "auto")
+
+
 def test_repeated_runs_are_bit_identical():
     cfg = CONFIGS[3]
     Xn, Wqkvn, Won, Wlcen = make_config_inputs(cfg, batch=4)
