@@ -732,11 +732,6 @@ struct FusedSmem {
     static_assert(KP <= XS && (size_t)C * PL * 4 <= h_off, "tiles that share a slot must fit");
 };
 
-__device__ __forceinline__ f32x4 mfma4(s16x4 a, s16x4 b, f32x4 c)
-{
-    return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, b, c, 0, 0, 0);
-}
-
 // Lane groups g (16 lanes each) hold two 8-byte pieces a, b that continue in the
 // neighbouring group: afterwards {a, b} of an even group is its own a followed by the
 // odd neighbour's a, and {a, b} of an odd group is the even neighbour's b followed by its

@@ -62,6 +62,14 @@ __device__ __forceinline__ int fast_div(int row, float width_inv)
     return (int)(((float)row + 0.5f) * width_inv);
 }
 
+// v_mfma_f32_4x4x4_16B_bf16: 16 independent 4x4 blocks, 4 contraction elements each.
+// Lane l belongs to block l / 4 and holds row l % 4 of A, column l % 4 of B and of D
+// (D rows in the 4 result registers).
+__device__ __forceinline__ f32x4 mfma4(s16x4 a, s16x4 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, b, c, 0, 0, 0);
+}
+
 // LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane s
 // supplies the address of 4 consecutive 16-bit elements; the four lanes 4 j .. 4 j + 3
 // together supply a row j of 16 elements.  Lane i receives element i of rows 0..3.
@@ -286,6 +294,35 @@ __device__ __forceinline__ float cross_row_sum(float x)
     return __builtin_bit_cast(float, (int)b[0]) + __builtin_bit_cast(float, (int)b[1]);
 }
 
+// The value of the lane that the DPP control CTRL names.
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float x)
+{
+    const int xi = __builtin_bit_cast(int, x);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(xi, xi, CTRL, 0xf, 0xf, false));
+}
+
+// Maxima over the 64 lanes of a wavefront of 4 values per lane at once, to every lane.
+// Lane pairs, then pairs of pairs, split the 4 values between them (each keeps the values
+// it will own and takes in the partner's copies), so the later steps handle one value per
+// lane: over the quads of a 16-lane row by rotation, over the rows by the lane swaps;
+// the lanes of a quad then hand their results round.  No NaN in s (max as a median).
+__device__ __forceinline__ void wave_fmax4(const f32x4 &s, int lane, float (&m)[4])
+{
+    const auto mx = [](float a, float b) { return __builtin_amdgcn_fmed3f(a, b, INFINITY); };
+    const bool odd = lane & 1, hi = lane & 2;
+    float a = mx(odd ? s[2] : s[0], dpp_get<0xB1>(odd ? s[0] : s[2]));      // rows 0 | 2 over lanes l, l ^ 1
+    float b = mx(odd ? s[3] : s[1], dpp_get<0xB1>(odd ? s[1] : s[3]));      // rows 1 | 3
+    float x = mx(hi ? b : a, dpp_get<0x4E>(hi ? a : b));                    // quad lane q owns row 2 (q & 1) + (q >> 1)
+    x = mx(x, dpp_get<0x124>(x));       // row_ror:4
+    x = mx(x, dpp_get<0x128>(x));       // row_ror:8
+    x = cross_row_max(x);
+    m[0] = dpp_get<0x00>(x);            // quad_perm [0,0,0,0]
+    m[1] = dpp_get<0xAA>(x);            // [2,2,2,2]
+    m[2] = dpp_get<0x55>(x);            // [1,1,1,1]
+    m[3] = dpp_get<0xFF>(x);            // [3,3,3,3]
+}
+
 // Online-softmax state of one wavefront: 16 queries (one per lane column i), all heads.
 template <int HEADS>
 struct SoftmaxState {
@@ -305,15 +342,15 @@ struct SoftmaxState {
 
 // Online-softmax step of one head for one block of 64 keys, given the scores
 // s[t][j] = S^T[key 16 t + 4 g + j][query i] of this wavefront's 16 queries (Eq. 1, one
-// softmax over all routed keys), then O^T += V^T P^T with V read from the rows of Vs (VS
-// elements per row, the head's channels start at column vcol) by the transposing LDS read.
-// The head's running state is slot h of st.
+// softmax over all routed keys), then O^T += V^T P^T with V read by the transposing LDS
+// read: the row of key 32 tp + 16 half + 4 g + i / 4 starts vrow(tp, half) elements into
+// Vs, the head's channels at column vcol of it.  The head's running state is slot h of st.
 // FIRST: this is the head's first block (state as left by init()), so there is nothing to
 // rescale.
-template <int VS, bool FIRST = false, int HEADS>
-__device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (&s)[4],
-                                                 SoftmaxState<HEADS> &st, int h, int vcol, float c_exp,
-                                                 int g, int i)
+template <bool FIRST, int HEADS, typename VRow>
+__device__ __forceinline__ void softmax_pv_rows(const bf16_t *Vs, VRow vrow, const f32x4 (&s)[4],
+                                                SoftmaxState<HEADS> &st, int h, int vcol, float c_exp,
+                                                int i)
 {
     float mx = s[0][0];
 #pragma unroll
@@ -347,13 +384,24 @@ __device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
             const int col = vcol + 16 * dt + 4 * (i % 4);
-            const s16x4 v0 = lds_read_tr16(Vs + (32 * tp + 4 * g + i / 4) * VS + col);
-            const s16x4 v1 = lds_read_tr16(Vs + (32 * tp + 16 + 4 * g + i / 4) * VS + col);
+            const s16x4 v0 = lds_read_tr16(Vs + vrow(tp, 0) + col);
+            const s16x4 v1 = lds_read_tr16(Vs + vrow(tp, 1) + col);
             u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
             u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
             st.acc[h][dt] = mfma16(__builtin_bit_cast(bf16x8, av), pb, st.acc[h][dt]);
         }
     }
+}
+
+// The same with the 64 keys in consecutive rows of pitch VS.
+template <int VS, bool FIRST = false, int HEADS>
+__device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (&s)[4],
+                                                 SoftmaxState<HEADS> &st, int h, int vcol, float c_exp,
+                                                 int g, int i)
+{
+    softmax_pv_rows<FIRST>(
+        Vs, [=](int tp, int half) { return (32 * tp + 16 * half + 4 * g + i / 4) * VS; }, s, st, h, vcol,
+        c_exp, i);
 }
 
 // One block of 64 keys (rows of Ks / Vs, CS elements per row) against the 16 queries of

@@ -298,6 +298,253 @@ __global__ __launch_bounds__(256) void k_attn_small(AttnArgs A, bf16_t *__restri
 }
 
 // ---------------------------------------------------------------------------
+// The same attention for maps small enough that one head's K and V of a whole image fit
+// in LDS.  Regions of a few tokens route to many regions (k n keys each), so a workgroup
+// per region would copy every K / V row of the image about k times from the L2; here
+// workgroup (image, head, part) copies the head's 32 channels of all N tokens once and
+// its wavefronts walk over the regions of the part, finding the rows of their keys by
+// index (Eq. 6 as row addresses of LDS reads).  Ks, Vs: [N][kMapPitch] bf16.
+constexpr int kMapPitch = 48;    // 32 channels + 16: rows of 96 bytes
+constexpr int kMapWaves = 8, kMapThreads = kMapWaves * kWave;   // the walk over the regions is latency-bound: many wavefronts
+
+struct MapWork {
+    int b, h, r_begin, r_end;
+    size_t img_off;
+    bf16_t *Ks, *Vs, *Qs;
+    int *rows;       // [R][k]: where the first token of routed region I^r[reg][p] starts in Ks / Vs (elements)
+    int *first;      // [R]: first token of a region
+    int slot_off;    // this lane's token within a routed region, the same way: key l is token l % n
+    char *wave_mem;  // 512 bytes of this wavefront's own
+};
+
+// Stages the head's K / V slice and the image's routing index; false: no work.
+__device__ __forceinline__ bool map_stage(const AttnArgs &A, const Dims &D, int split, char *smem, MapWork &w)
+{
+    constexpr int T = kMapThreads;
+    const int C = D.C, HEADS = C / 32;
+    w.Ks = (bf16_t *)smem;
+    w.Vs = w.Ks + (size_t)D.N * kMapPitch;
+    w.Qs = w.Vs + (size_t)D.N * kMapPitch;
+    w.rows = (int *)(w.Qs + (size_t)D.N * kMapPitch);
+    w.first = w.rows + D.R * D.k;
+    w.wave_mem = (char *)(w.rows + (D.R * D.k + D.R + 3) / 4 * 4) + (threadIdx.x / kWave) * 512;   // 16-byte aligned
+    const int wid = swizzled_block();       // the heads of an image share the memory lines of its K / V rows
+    if (wid >= A.total) return false;
+    const int part = wid % split;
+    w.h = (wid / split) % HEADS;
+    w.b = wid / (split * HEADS);
+    w.img_off = (size_t)w.b * D.N * C;
+    const float rw_inv = 1.0f / (float)D.rw, s_inv = 1.0f / (float)D.S;
+
+    const int chunks = D.N * 4;              // 16-byte chunks of the head's slice
+    for (int first = 0; first < chunks; first += T * 4) {
+        u32x4 kr[4], vr[4], qr[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = min(first + (int)threadIdx.x + T * u, chunks - 1);
+            const size_t off = w.img_off + (size_t)(idx / 4) * C + 32 * w.h + (idx % 4) * 8;
+            kr[u] = *(const u32x4 *)(A.K + off);
+            vr[u] = *(const u32x4 *)(A.V + off);
+            qr[u] = *(const u32x4 *)(A.Q + off);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = first + (int)threadIdx.x + T * u;
+            if (idx < chunks) {
+                *(u32x4 *)(w.Ks + (idx / 4) * kMapPitch + (idx % 4) * 8) = kr[u];
+                *(u32x4 *)(w.Vs + (idx / 4) * kMapPitch + (idx % 4) * 8) = vr[u];
+                *(u32x4 *)(w.Qs + (idx / 4) * kMapPitch + (idx % 4) * 8) = qr[u];
+            }
+        }
+    }
+    const bool copy_ir = A.Ir_out && A.Ir_out != A.Ir_src && w.h == 0 && part == 0;
+    for (int p = threadIdx.x; p < D.R * D.k; p += T) {
+        const int j = A.Ir_src[(size_t)w.b * D.R * D.k + p];
+        const int jy = fast_div(j, s_inv);
+        w.rows[p] = (jy * D.rh * D.W + (j - jy * D.S) * D.rw) * kMapPitch;
+        if (copy_ir) A.Ir_out[(size_t)w.b * D.R * D.k + p] = j;
+    }
+    for (int r = threadIdx.x; r < D.R; r += T) {
+        const int ry = fast_div(r, s_inv);
+        w.first[r] = ry * D.rh * D.W + (r - ry * D.S) * D.rw;
+    }
+    const int slot = (threadIdx.x % kWave) & (D.n - 1), sy = fast_div(slot, rw_inv);
+    w.slot_off = (sy * D.W + slot - sy * D.rw) * kMapPitch;
+    __syncthreads();
+    const int per = (D.R + split - 1) / split;
+    w.r_begin = part * per;
+    w.r_end = min(D.R, (part + 1) * per);
+    return true;
+}
+
+// Regions of 8 tokens: the queries take 8 of the 16 query columns of 16x16x32 tiles;
+// lane l puts the row of key l into a wavefront-private table, the K operand rows and
+// the transposing V reads take their addresses from it.
+__global__ __launch_bounds__(kMapThreads) void k_attn_map(AttnArgs A, bf16_t *__restrict__ O, Dims D, int log2n,
+                                                  int split)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    MapWork w;
+    if (!map_stage(A, D, split, smem, w)) return;
+    const bf16_t *Ks = w.Ks, *Vs = w.Vs;
+    int *tokw = (int *)w.wave_mem;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int g = lane / 16, i = lane % 16;
+    const int C = D.C, h = w.h, n = D.n, kn = D.kn;
+    const float rw_inv = 1.0f / (float)D.rw;
+
+    // query token of this lane's column within its region (columns >= n repeat the last; never stored)
+    const int qs = i < n ? i : n - 1;
+    const int qy = fast_div(qs, rw_inv);
+    const int q_in = qy * D.W + qs - qy * D.rw;
+    for (int reg = w.r_begin + wave; reg < w.r_end; reg += kMapWaves) {
+        const int tok0 = w.first[reg];
+        const bf16x8 qf = *(const bf16x8 *)(w.Qs + (tok0 + q_in) * kMapPitch + 8 * g);
+        SoftmaxState<1> st;
+        st.init();
+        for (int k0 = 0; k0 < kn; k0 += 64) {
+            // rows past the end repeat the last region; masked below
+            tokw[lane] = w.rows[reg * D.k + (min(k0 + lane, kn - 1) >> log2n)] + w.slot_off;
+            f32x4 s[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const bf16x8 kf = *(const bf16x8 *)(Ks + tokw[16 * t + i] + 8 * g);
+                s[t] = mfma16(kf, qf, f32x4{0.f, 0.f, 0.f, 0.f});
+            }
+            if (k0 + 64 > kn) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj)
+                        if (k0 + 16 * t + 4 * g + jj >= kn) s[t][jj] = -INFINITY;
+            }
+            int vrow[2][2];
+#pragma unroll
+            for (int tp = 0; tp < 2; ++tp)
+#pragma unroll
+                for (int half = 0; half < 2; ++half) vrow[tp][half] = tokw[32 * tp + 16 * half + 4 * g + i / 4];
+            softmax_pv_rows<false>(
+                Vs, [&](int tp, int half) { return vrow[tp][half]; }, s, st, 0, 0, A.c_exp, i);
+        }
+        const float inv = 1.0f / st.l[0];
+        if (i < n) {
+            bf16_t *orow = O + w.img_off + (size_t)(tok0 + q_in) * C + 32 * h + 4 * g;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) *(u32x2 *)(orow + 16 * dt) = pack4(st.acc[0][dt] * inv);
+        }
+    }
+}
+
+// Regions of at most 4 tokens: 16 query columns would be three quarters idle and the
+// softmax arithmetic with them.  The scores come from v_mfma_f32_4x4x4_16B_bf16 instead
+// (16 blocks of 4 queries x 4 keys, 4 channels per product, 8 products for d = 32):
+// block l / 4 and column l % 4 make lane l the owner of key l with the scores of the 4
+// queries in its 4 result registers, and the K operand is simply the lane's own key row.
+// Per query: wavefront maximum, 2^x; the probabilities go through 8 bytes per key of
+// wavefront-private LDS and come back, by the transposing read, as the P^T operand of
+// O^T = V^T P^T on 16x16x32 tiles (query columns >= 4 see copies).  A product with an
+// all-ones operand delivers the softmax denominators (of the same bf16-rounded P) to
+// every lane of a query column.
+__global__ __launch_bounds__(kMapThreads) void k_attn_map4(AttnArgs A, bf16_t *__restrict__ O, Dims D, int log2n,
+                                                   int split)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    MapWork w;
+    if (!map_stage(A, D, split, smem, w)) return;
+    const bf16_t *Ks = w.Ks, *Vs = w.Vs;
+    bf16_t *Pw = (bf16_t *)w.wave_mem;          // [64 keys][4 queries]
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int g = lane / 16, i = lane % 16;
+    const int C = D.C, h = w.h, n = D.n, kn = D.kn;
+    const float rw_inv = 1.0f / (float)D.rw;
+    const float c_exp = A.c_exp;
+
+    auto in_region = [&](int q) {   // token offset of query min(q, n - 1) from the region's first token
+        const int qs = q < n ? q : n - 1;
+        const int qy = fast_div(qs, rw_inv);
+        return qy * D.W + qs - qy * D.rw;
+    };
+    const bf16_t *qbase = w.Qs + in_region(lane % 4) * kMapPitch;               // row of the score operand
+    bf16_t *obase = O + w.img_off + in_region(i) * C + 32 * h + 4 * g;          // column of the output tiles
+    const u32x4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    const bool ragged = (kn % 64) != 0;
+    for (int reg = w.r_begin + wave; reg < w.r_end; reg += kMapWaves) {
+        const int tok0 = w.first[reg];
+        u32x4 q4[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) q4[c] = *(const u32x4 *)(qbase + tok0 * kMapPitch + 8 * c);
+        const int *rrow = w.rows + reg * D.k;
+        float m[4];
+        f32x4 acc[2], lacc;
+        // one block of 64 keys; FIRST: the region's first block, nothing to rescale
+        auto key_block = [&](int k0, auto first_tag) {
+            constexpr bool FIRST = decltype(first_tag)::value;
+            int key = k0 + lane;
+            if (ragged) key = min(key, kn - 1);         // rows past the end repeat the last region; masked below
+            const int row = rrow[key >> log2n] + w.slot_off;
+            f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const u32x4 k4 = *(const u32x4 *)(Ks + row + 8 * c);
+                s = mfma4(__builtin_bit_cast(s16x4, u32x2{q4[c][0], q4[c][1]}),
+                          __builtin_bit_cast(s16x4, u32x2{k4[0], k4[1]}), s);
+                s = mfma4(__builtin_bit_cast(s16x4, u32x2{q4[c][2], q4[c][3]}),
+                          __builtin_bit_cast(s16x4, u32x2{k4[2], k4[3]}), s);
+            }
+            if (ragged && k0 + lane >= kn) s = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            float mb[4];
+            wave_fmax4(s, lane, mb);
+            if (!FIRST) {
+                const int qq = i % 4;
+                const float m_old = qq == 0 ? m[0] : qq == 1 ? m[1] : qq == 2 ? m[2] : m[3];
+                const float m_blk = qq == 0 ? mb[0] : qq == 1 ? mb[1] : qq == 2 ? mb[2] : mb[3];
+                const float al = __builtin_amdgcn_exp2f((m_old - fmaxf(m_old, m_blk)) * c_exp);
+                acc[0] *= al;
+                acc[1] *= al;
+                lacc *= al;
+            }
+            f32x4 p;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                m[r] = FIRST ? mb[r] : fmaxf(m[r], mb[r]);
+                p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c_exp, -m[r] * c_exp));
+            }
+            asm volatile("" ::: "memory");      // the reads of the previous block precede this write
+            *(u32x2 *)(Pw + lane * 4) = pack4(p);
+            asm volatile("" ::: "memory");
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int tp = 0; tp < 2; ++tp) {
+                const int kk0 = 32 * tp + 4 * g + i / 4, kk1 = kk0 + 16;    // keys of this lane's operand slots
+                const u32x2 p0 = __builtin_bit_cast(u32x2, lds_read_tr16(Pw + kk0 * 4));
+                const u32x2 p1 = __builtin_bit_cast(u32x2, lds_read_tr16(Pw + kk1 * 4));
+                const bf16x8 pb = __builtin_bit_cast(bf16x8, u32x4{p0[0], p0[1], p1[0], p1[1]});
+                const int r0 = __builtin_amdgcn_ds_bpermute(4 * kk0, row);
+                const int r1 = __builtin_amdgcn_ds_bpermute(4 * kk1, row);
+                const bool fresh = FIRST && tp == 0;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    const int col = 16 * dt + 4 * (i % 4);
+                    const u32x2 v0 = __builtin_bit_cast(u32x2, lds_read_tr16(Vs + r0 + col));
+                    const u32x2 v1 = __builtin_bit_cast(u32x2, lds_read_tr16(Vs + r1 + col));
+                    acc[dt] = mfma16(__builtin_bit_cast(bf16x8, u32x4{v0[0], v0[1], v1[0], v1[1]}), pb,
+                                     fresh ? zero : acc[dt]);
+                }
+                lacc = mfma16(__builtin_bit_cast(bf16x8, ones), pb, fresh ? zero : lacc);
+            }
+        };
+        key_block(0, std::true_type{});
+        for (int k0 = 64; k0 < kn; k0 += 64) key_block(k0, std::false_type{});
+        const float inv = __builtin_amdgcn_rcpf(lacc[0]);
+        if (i < n) {
+            bf16_t *orow = obase + (size_t)tok0 * C;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) *(u32x2 *)(orow + 16 * dt) = pack4(acc[dt] * inv);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // O <- O_att + LCE(V) (Eq. 7) in place, for workgroup (image, tile of TH full-width image
 // rows, chunk of 64 channels).  LDS holds the V halo tile of the chunk, [(TH + 4) x (W + 4)]
 // tokens x 64 channels; a thread keeps one channel pair for all its (row, 4-token segment)
@@ -401,6 +648,24 @@ static bool one_kernel(const Dims &D)
 
 static size_t lce_add_smem(const Dims &D) { return (size_t)(tile_rows(D) + 4) * (D.W + 4) * kLcePitch * 2; }
 
+static size_t map_smem(const Dims &D)
+{
+    return (size_t)3 * D.N * kMapPitch * 2 + (size_t)((D.R * D.k + D.R + 3) / 4 * 4) * 4 + kMapWaves * 512;
+}
+
+// Image-resident attention when a head's K and V of one image fit in LDS.
+static bool map_attention(const Dims &D) { return map_smem(D) <= (size_t)kMaxLds; }
+
+// Parts per (image, head), so that small batches still fill the chip.
+static int map_split(const Dims &D)
+{
+    static const int forced = getenv("BRA_MAP_WGS") ? atoi(getenv("BRA_MAP_WGS")) : 0;   // benchmarking aid
+    const int target = forced >= 1 && forced <= 65536 ? forced : 512;
+    const int wgs = D.B * (D.C / 32);
+    const int split = (target + wgs - 1) / wgs;
+    return std::max(1, std::min(split, D.R / kMapWaves));
+}
+
 bool small_supported(const Dims &D)
 {
     if (D.n > 16 || (D.n & (D.n - 1)) != 0) return false;   // n = 1, 2, 4, 8, 16
@@ -410,7 +675,10 @@ bool small_supported(const Dims &D)
     } else {
         if (D.W > 64) return false;
         smem = lce_add_smem(D);
-        const size_t attn = D.C == 64 ? SmallSmem<64>::kv_bytes : D.C == 128 ? SmallSmem<128>::kv_bytes : SmallSmem<256>::kv_bytes;
+        const size_t attn = map_attention(D) ? map_smem(D)
+                            : D.C == 64      ? SmallSmem<64>::kv_bytes
+                            : D.C == 128     ? SmallSmem<128>::kv_bytes
+                                             : SmallSmem<256>::kv_bytes;
         if (attn > smem) smem = attn;
     }
     return smem <= (size_t)kMaxLds;
@@ -449,7 +717,19 @@ static int launch_small_c(const Dims &D, const AttnArgs &A0, bf16_t *O, hipStrea
         hipLaunchKernelGGL(k_small<C>, dim3(grid), dim3(256), small_smem<C>(D), st, A, D, log2n);
         return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
     }
-    {
+    if (map_attention(D)) {
+        static bool opted = false, opted4 = false;
+        if (!opt_in(k_attn_map, opted) || !opt_in(k_attn_map4, opted4)) return BRA_ERR_LAUNCH;
+        const int split = map_split(D);
+        ProfScope ps(st, K_MFMA_ATTN_SMALL);
+        A.total = D.B * (C / 32) * split;
+        const dim3 grid_map((A.total + 7) / 8 * 8);
+        const size_t smem = map_smem(D);
+        if (D.n <= 4)
+            hipLaunchKernelGGL(k_attn_map4, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
+        else
+            hipLaunchKernelGGL(k_attn_map, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
+    } else {
         static bool opted = false;
         if (!opt_in(k_attn_small<C>, opted)) return BRA_ERR_LAUNCH;
         ProfScope ps(st, K_MFMA_ATTN_SMALL);

@@ -97,6 +97,9 @@ MFMA_SMALL_SHAPES = [  # regions of 1..16 tokens: per-(region, head) attention +
     (1, 7, 7, 64, 2, 7, 49),       # stage-4 shape: one token per region
     (2, 12, 24, 128, 4, 6, 7),     # 2 x 4 regions, n = 8
     (3, 21, 14, 64, 2, 7, 2),      # 3 x 2 regions, n = 6 is not supported -> generic family
+    (1, 32, 32, 64, 2, 16, 3),     # n = 4 on a map too large for one head's K / V in LDS
+    (1, 8, 16, 64, 2, 4, 16),      # n = 8, 128 keys: two key blocks
+    (2, 8, 4, 64, 2, 4, 5),        # 2 x 1 regions, n = 2
 ]
 
 
