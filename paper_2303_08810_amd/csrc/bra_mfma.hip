@@ -124,27 +124,62 @@ __global__ void k_prep_weights(const bf16_t *__restrict__ Wqkv, const bf16_t *__
     if (e < total) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, Wf, C, e);
 }
 
+// Exact split of 8 float32 values into three bf16 terms each (x = hi + mid + lo: 3 x 8
+// mantissa bits), as MFMA operands.
+__device__ __forceinline__ void split3(const float (&x)[8], bf16x8 (&t)[3])
+{
+    u32x4 h, m, l;      // pairs of bf16, rounded by the hardware conversion (nearest even)
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        h[p] = pack_bf16(x[2 * p], x[2 * p + 1]);
+        const float r0 = x[2 * p] - bf16_lo(h[p]), r1 = x[2 * p + 1] - bf16_hi(h[p]);
+        m[p] = pack_bf16(r0, r1);
+        l[p] = pack_bf16(r0 - bf16_lo(m[p]), r1 - bf16_hi(m[p]));
+    }
+    t[0] = __builtin_bit_cast(bf16x8, h);
+    t[1] = __builtin_bit_cast(bf16x8, m);
+    t[2] = __builtin_bit_cast(bf16x8, l);
+}
+
 // ---------------------------------------------------------------------------
 // Region pooling (Sec. 3.2, "Region-to-region routing"): Xr[b, r, :] = mean of the
 // tokens of region r, in float32 with a fixed summation order.  Workgroup (b, group)
 // handles G consecutive regions of image b and reads their tokens exactly once: a pure
 // streaming pass over X.  Workgroups beyond `pool_blocks` rearrange the weights instead.
+//
+// With U (C = 64, k = 1 pipeline) the workgroup also leaves the routing vector of each of
+// its regions: row r of A^r (Eq. 4) is Q^r_r (K^r)^T = (xr_r Wq) (Xr Wk)^T = Xr u_r with
+// u_r = Wk (Wq^T xr_r), so whoever needs that row later only needs u_r and the means, not
+// the region-level projections.  Wq and Wk (bf16, read from Wqkv at kernel start, parked in
+// registers while X streams) pass through LDS; the products are those of float32 arithmetic.
 template <int C>
 __global__ __launch_bounds__(256) void k_pool(const bf16_t *__restrict__ X,
                                               const bf16_t *__restrict__ Wqkv,
                                               const bf16_t *__restrict__ Wo,
                                               const bf16_t *__restrict__ Wlce,
-                                              float *__restrict__ Xr, bf16_t *__restrict__ WT,
+                                              float *__restrict__ Xr, float *__restrict__ U,
+                                              bf16_t *__restrict__ WT,
                                               bf16_t *__restrict__ WoT, bf16_t *__restrict__ Wa,
                                               bf16_t *__restrict__ Wf, Dims D, int pool_blocks, int G,
                                               int prep_elems)
 {
     __shared__ float part[2048];   // pooling partials
+    constexpr bool kWithU = C == 64;
+    __shared__ __attribute__((aligned(16))) bf16_t wqk[kWithU ? 2 * 64 * 64 : 8];   // Wq [e][c], Wk [f][c]
+    __shared__ __attribute__((aligned(16))) float xs[kWithU ? kPoolMaxGroup * 64 : 4], qs[kWithU ? kPoolMaxGroup * 64 : 4];
     const int tid = threadIdx.x;
     if ((int)blockIdx.x >= pool_blocks) {
         const int e = ((int)blockIdx.x - pool_blocks) * 256 + tid;
         if (e < prep_elems) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, Wf, C, e);
         return;
+    }
+    u32x4 wreg[4];
+    if (kWithU && U) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = tid + 256 * (u % 2);             // 16-byte chunk of Wq (u < 2) or Wk
+            wreg[u] = *(const u32x4 *)(Wqkv + (size_t)(idx / 8) * 3 * C + (u / 2) * C + (idx % 8) * 8);
+        }
     }
     constexpr int CH = C / 8;
     const int groups = (D.R + G - 1) / G;
@@ -181,25 +216,124 @@ __global__ __launch_bounds__(256) void k_pool(const bf16_t *__restrict__ X,
         const int it = gi * CH + c / 8;
         float s = 0.f;
         for (int sb = 0; sb < SUB; ++sb) s += part[(sb * items + it) * 8 + c % 8];
-        Xr[((size_t)b * D.R + r0 + gi) * C + c] = s / (float)D.n;
+        const float mean = s / (float)D.n;
+        if (kWithU && U) xs[e] = mean;      // stored below: a barrier would wait for the store to land
+        else Xr[((size_t)b * D.R + r0 + gi) * C + c] = mean;
+    }
+    if (kWithU && U) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            *(u32x4 *)(wqk + (u / 2) * 64 * 64 + (tid + 256 * (u % 2)) * 8) = wreg[u];
+        __syncthreads();
+        // Both products on the matrix cores, the float32 factor split exactly into three
+        // bf16 terms (as the routing kernel does): wavefront w owns output channels
+        // 16 w .. 16 w + 15, the regions are the columns (columns >= ng repeat the last).
+        const int wave = tid / kWave, lane = tid % kWave, g = lane / 16, i = lane % 16;
+        const int col = min(i, ng - 1);
+        const bf16_t *wq_s = wqk, *wk_s = wqk + 64 * 64;
+        auto terms = [&](const float *row, bf16x8 (&t)[3]) {   // 8 consecutive floats -> split operands
+            const f32x4 lo = *(const f32x4 *)row, hi = *(const f32x4 *)(row + 4);
+            const float x[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            split3(x, t);
+        };
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};      // q^T[channel 16 w + 4 g + jj][region i] = sum_e Wq[e][c] xr[e]
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            // Wq^T as the A operand: rows of the LDS tile are e, the transposing read turns them
+            const bf16_t *wp = wq_s + (32 * ks + 8 * g + i / 4) * 64 + 16 * wave + 4 * (i % 4);
+            const u32x2 w0 = __builtin_bit_cast(u32x2, lds_read_tr16(wp));
+            const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 4 * 64));
+            const bf16x8 wf = __builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]});
+            bf16x8 t[3];
+            terms(xs + col * 64 + 32 * ks + 8 * g, t);
+            acc = mfma16(wf, t[2], acc);       // smallest term first
+            acc = mfma16(wf, t[1], acc);
+            acc = mfma16(wf, t[0], acc);
+        }
+        if (i < ng) *(f32x4 *)(qs + i * 64 + 16 * wave + 4 * g) = acc;
+        __syncthreads();
+        acc = f32x4{0.f, 0.f, 0.f, 0.f};       // u^T[f = 16 w + 4 g + jj][region i] = sum_c Wk[f][c] q[c]
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const bf16x8 wf = *(const bf16x8 *)(wk_s + (16 * wave + i) * 64 + 32 * ks + 8 * g);
+            bf16x8 t[3];
+            terms(qs + col * 64 + 32 * ks + 8 * g, t);
+            acc = mfma16(wf, t[2], acc);
+            acc = mfma16(wf, t[1], acc);
+            acc = mfma16(wf, t[0], acc);
+        }
+        if (i < ng) *(f32x4 *)(U + ((size_t)b * D.R + r0 + i) * C + 16 * wave + 4 * g) = acc;
+        for (int e = tid; e < ng * C; e += 256) Xr[((size_t)b * D.R + r0) * C + e] = xs[e];
     }
 }
 
-// Exact split of 8 float32 values into three bf16 terms each (x = hi + mid + lo: 3 x 8
-// mantissa bits), as MFMA operands.
-__device__ __forceinline__ void split3(const float (&x)[8], bf16x8 (&t)[3])
+// Row `reg` of A^r of image b (Eq. 4) from the routing vector u of the region and the means
+// Xr_b [R][64] of the image, by a workgroup of 256 threads, and the index of its largest
+// entry (Eq. 5 for k = 1: ties to the smaller index, NaN as -inf), returned to every thread.
+// Lane group jq = lane / 4 of wavefront w owns region 16 w + jq, its 4 lanes a quarter of
+// the channels each.  Two steps, so that a caller can put other memory requests between
+// the loads and their use.
+struct RouteRowLoads {
+    f32x4 xv[4], uv[4];
+};
+
+__device__ __forceinline__ void route_row_load(const float *__restrict__ Xr_b, const float *__restrict__ u,
+                                               int R, RouteRowLoads &L)
 {
-    float h[8], m[8], l[8];
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int jj = 16 * wave + lane / 4, cq = lane % 4;
+    const float *xrow = Xr_b + (size_t)min(jj, R - 1) * 64 + 4 * cq;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        h[e] = bf16_to_f32(f32_to_bf16(x[e]));
-        const float r1 = x[e] - h[e];
-        m[e] = bf16_to_f32(f32_to_bf16(r1));
-        l[e] = r1 - m[e];
+    for (int e = 0; e < 4; ++e) {
+        L.xv[e] = *(const f32x4 *)(xrow + 16 * e);
+        L.uv[e] = *(const f32x4 *)(u + 4 * cq + 16 * e);
     }
-    t[0] = pack8(h);
-    t[1] = pack8(m);
-    t[2] = pack8(l);
+}
+
+// slot: 8 words of LDS.  Contains a barrier.
+__device__ __forceinline__ int route_row_k1(const RouteRowLoads &L, int R, uint32_t *slot,
+                                            float *__restrict__ Ar_row_opt)
+{
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int jj = 16 * wave + lane / 4, cq = lane % 4;
+    float a = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) a = fmaf(L.xv[e][t], L.uv[e][t], a);
+    a = dpp_fadd<0xB1>(a);
+    a = dpp_fadd<0x4E>(a);
+    if (Ar_row_opt && cq == 0 && jj < R) Ar_row_opt[jj] = a;
+    const uint32_t key = topk_order_key(a, jj, R);
+    const uint32_t kmax = wave_umax(key);
+    const int best = __builtin_ctzll(__ballot(key == kmax)) / 4;
+    if (lane == 0) {
+        slot[2 * wave] = kmax;
+        slot[2 * wave + 1] = (uint32_t)(16 * wave + best);
+    }
+    __syncthreads();
+    uint32_t bk = slot[0];
+    int bj = (int)slot[1];
+#pragma unroll
+    for (int ww = 1; ww < 4; ++ww)
+        if (slot[2 * ww] > bk) {
+            bk = slot[2 * ww];
+            bj = (int)slot[2 * ww + 1];
+        }
+    return bj;
+}
+
+// The routing of the k = 1 pipeline on its own (routing-only calls): workgroup (b, reg).
+__global__ __launch_bounds__(256) void k_route_u(const float *__restrict__ Xr, const float *__restrict__ U,
+                                                 int32_t *__restrict__ Ir, float *__restrict__ Ar, Dims D)
+{
+    __shared__ uint32_t slot[8];
+    const int b = blockIdx.x / D.R, reg = blockIdx.x % D.R;
+    const size_t row = (size_t)b * D.R + reg;
+    RouteRowLoads L;
+    route_row_load(Xr + (size_t)b * D.R * 64, U + row * 64, D.R, L);
+    const int j = route_row_k1(L, D.R, slot, Ar ? Ar + row * D.R : nullptr);
+    if (threadIdx.x == 0) Ir[row] = j;
 }
 
 // Region-level projections, A^r = Q^r (K^r)^T (Eq. 4) and its row-wise top-k index I^r
@@ -728,7 +862,8 @@ struct FusedSmem {
     static constexpr size_t h_off = v_off + (size_t)64 * VP * 2;      // X halo -> V halo planes
     static constexpr size_t xh_bytes = (size_t)NHT * 16 * XS * 2;
     static constexpr size_t vt_bytes = (size_t)C * PS * 2;
-    static constexpr size_t bytes = h_off + (xh_bytes > vt_bytes ? xh_bytes : vt_bytes);
+    static constexpr size_t r_off = h_off + (xh_bytes > vt_bytes ? xh_bytes : vt_bytes);   // routing: 8 words
+    static constexpr size_t bytes = r_off + 32;
     static_assert(KP <= XS && (size_t)C * PL * 4 <= h_off, "tiles that share a slot must fit");
 };
 
@@ -774,10 +909,16 @@ void k_fused(AttnArgs A, Dims D)
 
     // All requests up front: the routed region, X over the halo of the query tile (it
     // contains the query tile) and over the routed region, the weight fragments.
-    const int j = A.Ir_src[(size_t)b * D.R + reg];
-    if (A.Ir_out && A.Ir_out != A.Ir_src && threadIdx.x == 0) A.Ir_out[(size_t)b * D.R + reg] = j;
+    // The routed region: given, or found here from this region's row of A^r; the requests
+    // for that row go first, so that they are back before the tiles.
+    const size_t rrow = (size_t)b * D.R + reg;
+    RouteRowLoads rl;
+    int j = 0;
+    if (A.Ir_src) j = A.Ir_src[rrow];
+    else route_row_load(A.Xr + (size_t)b * D.R * C, A.U + rrow * C, D.R, rl);
     u32x4 hreg[NBH];
     tile_load<C, NBH>(hreg, Ximg, y0 - 2, x0 - 2, HW, hw_inv, HROWS, D.H, D.W, 0);
+    if (!A.Ir_src) j = route_row_k1(rl, D.R, (uint32_t *)(smem + SM::r_off), nullptr);
     auto fragment = [&](int rt, int ks) {
         return *(const bf16x8 *)(A.Wf + ((size_t)(rt * KS + ks) * kWave + lane) * 8);
     };
@@ -949,12 +1090,14 @@ void k_fused(AttnArgs A, Dims D)
     u32x4 *dst = (u32x4 *)(A.Y + img_off + ((size_t)(y0 + qy) * D.W + x0 + q - qy * RW) * C + 16 * g);
     dst[0] = u32x4{yp[0][0], yp[0][1], yp[1][0], yp[1][1]};
     dst[1] = u32x4{yp[2][0], yp[2][1], yp[3][0], yp[3][1]};
+    // reported last: a store ahead of the barriers above would have to land before them
+    if (A.Ir_out && A.Ir_out != A.Ir_src && threadIdx.x == 0) A.Ir_out[rrow] = j;
 }
 
 // ---------------------------------------------------------------------------
 struct MfmaWs {
     bf16_t *q, *k, *v, *o, *wt, *wot, *wa, *wf;
-    float *xr, *p;
+    float *xr, *u, *p;
     void *route;
     int32_t *ir;
     size_t bytes;
@@ -1011,6 +1154,7 @@ MfmaWs carve(const Dims &D, void *ws)
     w.wa = (bf16_t *)take((size_t)(D.C * kLceOperandElems + small_table_elems(D.C)) * 2);
     w.wf = (bf16_t *)take(D.C == 64 ? (size_t)kFusedFragElems * 2 : 0);
     w.xr = (float *)take((size_t)D.B * D.R * D.C * sizeof(float));
+    w.u = (float *)take(D.C == 64 && fused_ok(D) ? (size_t)D.B * D.R * D.C * sizeof(float) : 0);
     w.p = (float *)take(pooled_projection(D) ? (size_t)D.B * D.H * (D.W >> pool_group_log2(D)) * 2 * D.C * sizeof(float) : 0);
     w.route = take(fast_route_ok(D) ? 0 : valu_route_scratch_bytes(D));
     w.ir = (int32_t *)take((size_t)D.B * D.R * D.k * sizeof(int32_t));
@@ -1047,7 +1191,8 @@ int pool_group(const Dims &D)
 // Pooling (if `pool`) and weight preparation (`prep_elems` leading prep elements) in one launch.
 template <int C>
 void launch_pool(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *Wo,
-                 const bf16_t *Wlce, const MfmaWs &w, bool pool, int prep_elems, hipStream_t st)
+                 const bf16_t *Wlce, const MfmaWs &w, bool pool, int prep_elems, hipStream_t st,
+                 bool with_u = false)
 {
     const int G = pool_group(D);
     const int pool_blocks = pool ? D.B * ((D.R + G - 1) / G) : 0;
@@ -1055,7 +1200,7 @@ void launch_pool(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_
     if (pool_blocks + prep_blocks == 0) return;
     ProfScope ps(st, K_MFMA_POOL_QK);
     hipLaunchKernelGGL(k_pool<C>, dim3(pool_blocks + prep_blocks), dim3(256), 0, st, X, Wqkv, Wo, Wlce,
-                       w.xr, w.wt, w.wot, w.wa, w.wf, D, pool_blocks, G, prep_elems);
+                       w.xr, with_u ? w.u : nullptr, w.wt, w.wot, w.wa, w.wf, D, pool_blocks, G, prep_elems);
 }
 
 template <int C>
@@ -1153,8 +1298,9 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
         // pool X and route before the rest, with the weight rearrangement in the same launch;
         // the pooled-projection pipelines need neither and rearrange next to the projection
         const bool from_x = (fused || !pooled_projection(D)) && !Ir_in_opt;
-        if (fused || from_x) launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/from_x, prep_total(C), st);
-        if (from_x) {
+        if (fused || from_x)
+            launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/from_x, prep_total(C), st, /*with_u=*/fused);
+        if (from_x && !fused) {     // the k = 1 kernel routes by itself, from the routing vectors
             const int rc = launch_route<C>(D, w, Ir_dst, nullptr, st);
             if (rc != BRA_OK) return rc;
             Ir_src = Ir_dst;
@@ -1175,6 +1321,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     AttnArgs A;
     A.X = X; A.WT = w.wt; A.Q = w.q; A.K = w.k; A.V = w.v;
     A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = Wlce; A.Wa = w.wa; A.WoF = w.wa + kLceOperandElems * C; A.WlT = A.WoF + C * C; A.Wf = w.wf; A.WoT = w.wot; A.Y = Y;
+    A.Xr = w.xr; A.U = w.u;
     A.c_exp = D.scale * 1.4426950408889634f;
     A.total = D.B * D.R * (D.n / 64);
     const int grid = ((A.total + 7) / 8) * 8;
@@ -1215,7 +1362,12 @@ int route_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, int32_t *Ir, flo
 {
     // the same kernels as bra_forward runs for this shape, so that both give the same index
     int rc;
-    if ((C == 64 && fused_ok(D)) || !pooled_projection(D)) {
+    if (C == 64 && fused_ok(D)) {
+        launch_pool<C>(D, X, Wqkv, nullptr, nullptr, w, /*pool=*/true, 0, st, /*with_u=*/true);
+        ProfScope ps(st, K_MFMA_ROUTE_ROWS);
+        hipLaunchKernelGGL(k_route_u, dim3(D.B * D.R), dim3(256), 0, st, w.xr, w.u, Ir, Ar_opt, D);
+        rc = BRA_OK;
+    } else if (!pooled_projection(D)) {
         launch_pool<C>(D, X, Wqkv, nullptr, nullptr, w, /*pool=*/true, /*prep: Wq^T, Wk^T*/ 2 * C * C, st);
         rc = launch_route<C>(D, w, Ir, Ar_opt, st);
     } else {

@@ -547,6 +547,7 @@ struct AttnArgs {
     const bf16_t *Wf;               // projection weights in fragment order (fused kernel)
     const bf16_t *WoF, *WlT;        // Wo as plain fragments, LCE weights [25][C] (small-region kernels)
     bf16_t *Y;
+    const float *Xr, *U;            // region means and routing vectors (fused kernel, Ir_src == NULL)
     float c_exp;                    // softmax scale * log2(e)
     int total;                      // workgroups that have work
 };

@@ -15,7 +15,8 @@ import sys
 
 COPY_BYTES = 64 << 20
 NAMES = {"k_fused": "mfma_fused_k1", "k_pool": "mfma_pool_qk", "k_route": "mfma_route_rows",
-         "k_route_p": "mfma_route_rows",
+         "k_route_p": "mfma_route_rows", "k_route_u": "mfma_route_rows",
+         "k_attn_map": "mfma_attn_small", "k_attn_map4": "mfma_attn_small",
          "k_qkv": "mfma_qkv", "k_attn_big": "mfma_attention", "k_attn_small": "mfma_attn_small",
          "k_small": "mfma_attn_small", "k_lce_add": "mfma_lce_add", "k_prep_weights": "mfma_prep",
          "k_util_copy": "copy"}
