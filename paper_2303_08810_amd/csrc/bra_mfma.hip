@@ -1297,10 +1297,12 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     } else {
         // pool X and route before the rest, with the weight rearrangement in the same launch;
         // the pooled-projection pipelines need neither and rearrange next to the projection
+        static const bool route_launch = getenv("BRA_FUSED_ROUTE_LAUNCH") != nullptr;   // benchmarking aid
+        const bool inline_route = fused && !route_launch;     // the k = 1 kernel routes by itself, from the routing vectors
         const bool from_x = (fused || !pooled_projection(D)) && !Ir_in_opt;
         if (fused || from_x)
-            launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/from_x, prep_total(C), st, /*with_u=*/fused);
-        if (from_x && !fused) {     // the k = 1 kernel routes by itself, from the routing vectors
+            launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/from_x, prep_total(C), st, /*with_u=*/inline_route);
+        if (from_x && !inline_route) {
             const int rc = launch_route<C>(D, w, Ir_dst, nullptr, st);
             if (rc != BRA_OK) return rc;
             Ir_src = Ir_dst;

@@ -153,6 +153,15 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
     const int qy = fast_div(qs, rw_inv);
     const size_t qtok = (size_t)(y0 + qy) * D.W + x0 + qs - qy * D.rw;
 
+    // LCE task = (row r, 4-token segment, channel pair); a thread keeps its channel pair for
+    // all its tasks, so its 2 x 25 weights stay in registers (requested now, used after the attention)
+    const int cp_n = C / 2, segs = (D.rw + 3) / 4;
+    const int tasks = D.rh * segs * cp_n;
+    const int cpair = threadIdx.x % cp_n;
+    unsigned wl[25];        // tap t of channels (c, c + 1) as a packed pair, from the tap-major table
+#pragma unroll
+    for (int t = 0; t < 25; ++t) wl[t] = *(const unsigned *)(A.WlT + (size_t)t * C + 2 * cpair);
+
     f32x4 oacc[HPW][2];     // normalised attention output of this wavefront's heads
     small_attention<C>(A, D, log2n, img_off, irp, qtok, Ks, Vs, oacc);
     __builtin_amdgcn_s_setprio(2);      // late phases first: the workgroup's LDS is freed sooner
@@ -163,15 +172,7 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
         tile_store<C, CS, NBH>(Hs, hreg, hrows, first);
     }
 
-    // LCE (Eq. 7) of the region's tokens: task = (row r, 4-token segment, channel pair);
-    // a thread keeps its channel pair for all its tasks, so its 2 x 25 weights stay in
-    // registers.
-    const int cp_n = C / 2, segs = (D.rw + 3) / 4;
-    const int tasks = D.rh * segs * cp_n;
-    const int cpair = threadIdx.x % cp_n;
-    unsigned wl[25];        // tap t of channels (c, c + 1) as a packed pair, from the tap-major table
-#pragma unroll
-    for (int t = 0; t < 25; ++t) wl[t] = *(const unsigned *)(A.WlT + (size_t)t * C + 2 * cpair);
+    // LCE (Eq. 7) of the region's tokens
     auto tap = [&](int ch, int t) { return ch ? bf16_hi(wl[t]) : bf16_lo(wl[t]); };
     float lce[kMaxLceTasks][2][4];
     __syncthreads();        // the halo tile is complete
