@@ -222,7 +222,7 @@ def main():
     import torch
 
     import paper_2303_08810_amd as bra
-    from synthetic_inputs import CONFIGS
+    from synthetic_inputs import CONFIGS, NEXT_CONFIGS
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = CONFIGS[args.workload]
@@ -250,7 +250,7 @@ def main():
         line["cpu_baseline"] = cpu_baseline(cfg, res["host"])
     if not args.no_others:
         others = {}
-        for idx, c in CONFIGS.items():
+        for idx, c in {**CONFIGS, **NEXT_CONFIGS}.items():
             if idx == args.workload:
                 continue
             r = time_config(c, max(20, args.steps // 4), max(5, args.warmup // 2), profile=True)

@@ -124,23 +124,6 @@ __global__ void k_prep_weights(const bf16_t *__restrict__ Wqkv, const bf16_t *__
     if (e < total) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, Wf, C, e);
 }
 
-// Exact split of 8 float32 values into three bf16 terms each (x = hi + mid + lo: 3 x 8
-// mantissa bits), as MFMA operands.
-__device__ __forceinline__ void split3(const float (&x)[8], bf16x8 (&t)[3])
-{
-    u32x4 h, m, l;      // pairs of bf16, rounded by the hardware conversion (nearest even)
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        h[p] = pack_bf16(x[2 * p], x[2 * p + 1]);
-        const float r0 = x[2 * p] - bf16_lo(h[p]), r1 = x[2 * p + 1] - bf16_hi(h[p]);
-        m[p] = pack_bf16(r0, r1);
-        l[p] = pack_bf16(r0 - bf16_lo(m[p]), r1 - bf16_hi(m[p]));
-    }
-    t[0] = __builtin_bit_cast(bf16x8, h);
-    t[1] = __builtin_bit_cast(bf16x8, m);
-    t[2] = __builtin_bit_cast(bf16x8, l);
-}
-
 // ---------------------------------------------------------------------------
 // Region pooling (Sec. 3.2, "Region-to-region routing"): Xr[b, r, :] = mean of the
 // tokens of region r, in float32 with a fixed summation order.  Workgroup (b, group)
@@ -1400,17 +1383,22 @@ bool attn_big_ok(const Dims &D)
 bool mfma_supported(const Dims &D)
 {
     if (D.dtype != BRA_BF16 || D.d != 32) return false;
+    if (wide_shape(D)) return wide_supported(D);
     if (D.C != 64 && D.C != 128 && D.C != 256) return false;
     if ((long)D.B * D.R * (D.n / 64 + 1) + 8 > 0x7fffffffL) return false;
     if (!fast_route_ok(D) && !generic_supported(D)) return false;   // fallback routing kernels
     return attn_big_ok(D) || small_supported(D);
 }
 
-size_t mfma_workspace_bytes(const Dims &D) { return carve(D, nullptr).bytes; }
+size_t mfma_workspace_bytes(const Dims &D)
+{
+    return wide_shape(D) ? wide_workspace_bytes(D) : carve(D, nullptr).bytes;
+}
 
 int mfma_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, float *Ar_opt, void *ws,
                hipStream_t st)
 {
+    if (wide_shape(D)) return wide_route(D, X, Wqkv, Ir, Ar_opt, ws, st);
     MfmaWs w = carve(D, ws);
     if (!fast_route_ok(D)) return valu_route(D, X, Wqkv, Ir, Ar_opt, w.route, st);
     const bf16_t *x = (const bf16_t *)X, *wq = (const bf16_t *)Wqkv;
@@ -1425,6 +1413,7 @@ int mfma_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, floa
 int mfma_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
                  void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, hipStream_t st)
 {
+    if (wide_shape(D)) return wide_forward(D, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, st);
     MfmaWs w = carve(D, ws);
     const bf16_t *x = (const bf16_t *)X, *wq = (const bf16_t *)Wqkv, *wo = (const bf16_t *)Wo,
                  *wl = (const bf16_t *)Wlce;

@@ -62,6 +62,23 @@ __device__ __forceinline__ int fast_div(int row, float width_inv)
     return (int)(((float)row + 0.5f) * width_inv);
 }
 
+// Exact split of 8 float32 values into three bf16 terms each (x = hi + mid + lo: 3 x 8
+// mantissa bits), as MFMA operands.
+__device__ __forceinline__ void split3(const float (&x)[8], bf16x8 (&t)[3])
+{
+    u32x4 h, m, l;      // pairs of bf16, rounded by the hardware conversion (nearest even)
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        h[p] = pack_bf16(x[2 * p], x[2 * p + 1]);
+        const float r0 = x[2 * p] - bf16_lo(h[p]), r1 = x[2 * p + 1] - bf16_hi(h[p]);
+        m[p] = pack_bf16(r0, r1);
+        l[p] = pack_bf16(r0 - bf16_lo(m[p]), r1 - bf16_hi(m[p]));
+    }
+    t[0] = __builtin_bit_cast(bf16x8, h);
+    t[1] = __builtin_bit_cast(bf16x8, m);
+    t[2] = __builtin_bit_cast(bf16x8, l);
+}
+
 // v_mfma_f32_4x4x4_16B_bf16: 16 independent 4x4 blocks, 4 contraction elements each.
 // Lane l belongs to block l / 4 and holds row l % 4 of A, column l % 4 of B and of D
 // (D rows in the 4 result registers).
@@ -568,5 +585,19 @@ bool small_supported(const Dims &D);
 size_t small_scratch_bytes(const Dims &D);
 bool small_needs_projection(const Dims &D);   // launch_small left O = attention + LCE in its scratch map: Y = O Wo is still to do
 int launch_small(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st);
+// Attention of regions of 1, 2, 4 or 8 tokens + LCE into O for any C that is a multiple of 64
+// (image-resident attention; A.Q/K/V, Ir_src, Ir_out, Wlce, c_exp set).
+bool map_tail_supported(const Dims &D);
+int launch_map_tail(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st);
+
+// Pipeline for other channel counts (bra_mfma_wide.hip): any multiple of 64 with heads of 32
+// channels, at most 64 regions of 1, 2, 4 or 8 tokens.
+bool wide_shape(const Dims &D);          // not one of the specialised channel counts
+bool wide_supported(const Dims &D);
+size_t wide_workspace_bytes(const Dims &D);
+int wide_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, float *Ar_opt, void *ws,
+               hipStream_t st);
+int wide_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo, const void *Wlce, void *Y,
+                 int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, hipStream_t st);
 
 }  // namespace bra

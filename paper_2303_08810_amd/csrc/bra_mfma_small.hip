@@ -552,11 +552,11 @@ __global__ __launch_bounds__(kMapThreads) void k_attn_map4(AttnArgs A, bf16_t *_
 // tasks, so its 2 x 25 weights stay in registers.  W^o follows as a plain projection.
 constexpr int kLceChunk = 64, kLcePitch = kLceChunk + 8;
 
-template <int C>
 __global__ __launch_bounds__(256) void k_lce_add(bf16_t *__restrict__ O, const bf16_t *__restrict__ V,
                                                  const bf16_t *__restrict__ Wlce, Dims D, int TH)
 {
-    constexpr int NCH = C / kLceChunk, CH8 = kLceChunk / 8, NBH = 6;
+    constexpr int CH8 = kLceChunk / 8, NBH = 6;
+    const int C = D.C, NCH = C / kLceChunk;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Hs = (bf16_t *)smem;
     const int tiles = (D.H + TH - 1) / TH;
@@ -624,10 +624,10 @@ __global__ __launch_bounds__(256) void k_lce_add(bf16_t *__restrict__ O, const b
         unsigned *orow = (unsigned *)(O + img_off + ((size_t)(y0 + r) * D.W + seg * 4) * C + c0 + 2 * cpair);
         unsigned o2[4];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) o2[x] = seg * 4 + x < D.W ? orow[(size_t)x * C / 2] : 0u;
+        for (int x = 0; x < 4; ++x) o2[x] = seg * 4 + x < D.W ? orow[(size_t)x * (C / 2)] : 0u;
 #pragma unroll
         for (int x = 0; x < 4; ++x)
-            if (seg * 4 + x < D.W) orow[(size_t)x * C / 2] = pack_bf16(bf16_lo(o2[x]) + a0[x], bf16_hi(o2[x]) + a1[x]);
+            if (seg * 4 + x < D.W) orow[(size_t)x * (C / 2)] = pack_bf16(bf16_lo(o2[x]) + a0[x], bf16_hi(o2[x]) + a1[x]);
     }
 }
 
@@ -703,6 +703,36 @@ static bool opt_in(K kernel, bool &done)
     return true;
 }
 
+// Image-resident attention of all regions into O.
+static int launch_map(const Dims &D, AttnArgs A, bf16_t *O, int log2n, hipStream_t st)
+{
+    static bool opted = false, opted4 = false;
+    if (!opt_in(k_attn_map, opted) || !opt_in(k_attn_map4, opted4)) return BRA_ERR_LAUNCH;
+    const int split = map_split(D);
+    ProfScope ps(st, K_MFMA_ATTN_SMALL);
+    A.total = D.B * (D.C / 32) * split;
+    const dim3 grid_map((A.total + 7) / 8 * 8);
+    const size_t smem = map_smem(D);
+    if (D.n <= 4)
+        hipLaunchKernelGGL(k_attn_map4, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
+    else
+        hipLaunchKernelGGL(k_attn_map, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
+    return BRA_OK;
+}
+
+// O += LCE(V) in place.
+static int launch_lce_add(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st)
+{
+    static bool opted = false;
+    if (!opt_in(k_lce_add, opted)) return BRA_ERR_LAUNCH;
+    const int TH = tile_rows(D);
+    const int tiles = (D.H + TH - 1) / TH;
+    ProfScope ps(st, K_MFMA_LCE_ADD);
+    hipLaunchKernelGGL(k_lce_add, dim3(D.B * tiles * (D.C / kLceChunk)), dim3(256), lce_add_smem(D), st, O, A.V,
+                       A.Wlce, D, TH);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
 template <int C>
 static int launch_small_c(const Dims &D, const AttnArgs &A0, bf16_t *O, hipStream_t st)
 {
@@ -719,33 +749,33 @@ static int launch_small_c(const Dims &D, const AttnArgs &A0, bf16_t *O, hipStrea
         return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
     }
     if (map_attention(D)) {
-        static bool opted = false, opted4 = false;
-        if (!opt_in(k_attn_map, opted) || !opt_in(k_attn_map4, opted4)) return BRA_ERR_LAUNCH;
-        const int split = map_split(D);
-        ProfScope ps(st, K_MFMA_ATTN_SMALL);
-        A.total = D.B * (C / 32) * split;
-        const dim3 grid_map((A.total + 7) / 8 * 8);
-        const size_t smem = map_smem(D);
-        if (D.n <= 4)
-            hipLaunchKernelGGL(k_attn_map4, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
-        else
-            hipLaunchKernelGGL(k_attn_map, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
+        const int rc = launch_map(D, A, O, log2n, st);
+        if (rc != BRA_OK) return rc;
     } else {
         static bool opted = false;
         if (!opt_in(k_attn_small<C>, opted)) return BRA_ERR_LAUNCH;
         ProfScope ps(st, K_MFMA_ATTN_SMALL);
         hipLaunchKernelGGL(k_attn_small<C>, dim3(grid), dim3(256), SmallSmem<C>::kv_bytes, st, A, O, D, log2n);
     }
-    {
-        static bool opted = false;
-        if (!opt_in(k_lce_add<C>, opted)) return BRA_ERR_LAUNCH;
-        const int TH = tile_rows(D);
-        const int tiles = (D.H + TH - 1) / TH;
-        ProfScope ps(st, K_MFMA_LCE_ADD);
-        hipLaunchKernelGGL(k_lce_add<C>, dim3(D.B * tiles * (C / kLceChunk)), dim3(256), lce_add_smem(D), st, O,
-                           A.V, A.Wlce, D, TH);
-    }
-    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+    return launch_lce_add(D, A, O, st);
+}
+
+// Any C that is a multiple of 64: regions of fewer than 16 tokens on a map that fits the
+// image-resident attention.
+bool map_tail_supported(const Dims &D)
+{
+    if (D.C % 64 != 0 || D.d != 32) return false;
+    if (D.n > 8 || (D.n & (D.n - 1)) != 0 || D.W > 64) return false;
+    return map_attention(D) && lce_add_smem(D) <= (size_t)kMaxLds;
+}
+
+int launch_map_tail(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st)
+{
+    int log2n = 0;
+    while ((1 << log2n) < D.n) ++log2n;
+    const int rc = launch_map(D, A, O, log2n, st);
+    if (rc != BRA_OK) return rc;
+    return launch_lce_add(D, A, O, st);
 }
 
 int launch_small(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st)

@@ -1,0 +1,330 @@
+// Matrix-core pipeline for channel counts beyond the specialised kernels (any C that is a
+// multiple of 64, heads of 32 channels) with small regions, e.g. the last stage of the paper's
+// backbones (7x7 map, S = 7: one token per region, k = S^2, C = 512) and the wider variants'
+// third stage (14x14 map, 4 tokens per region, C = 384).
+//
+//   k_pool_wide   Xr[b, r, :] = mean of the region's tokens, float32            (Sec. 3.2)
+//   k_gemm<true>  Q^r | K^r = Xr [Wq | Wk] in float32: the means are split exactly into three
+//                 bf16 terms, so the products are those of the float32 computation
+//   k_route_qk    rows of A^r = Q^r (K^r)^T (Eq. 4) and their top-k (Eq. 5)
+//   k_gemm<false> Q | K | V = X Wqkv (Eq. 3), bf16 out
+//   image-resident attention + LCE (bra_mfma_small.hip)                         (Eq. 6, 7)
+//   k_gemm<false> Y = O Wo (Eq. 2)
+#include "bra_mfma_dev.h"
+
+namespace bra {
+
+using namespace mfma;
+
+namespace {
+
+// Thread = (image, region, 8-channel chunk); tokens added in row-major order of the region.
+__global__ void k_pool_wide(const bf16_t *__restrict__ X, float *__restrict__ Xr, Dims D)
+{
+    const int CH = D.C / 8;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)D.B * D.R * CH) return;
+    const int cc = (int)(idx % CH), r = (int)((idx / CH) % D.R), b = (int)(idx / ((long)CH * D.R));
+    const bf16_t *base = X + (((size_t)b * D.H + (r / D.S) * D.rh) * D.W + (r % D.S) * D.rw) * D.C + cc * 8;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int y = 0; y < D.rh; ++y)
+        for (int x = 0; x < D.rw; ++x) {
+            const u32x4 v = *(const u32x4 *)(base + ((size_t)y * D.W + x) * D.C);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[2 * e] += bf16_lo(v[e]);
+                acc[2 * e + 1] += bf16_hi(v[e]);
+            }
+        }
+    float *dst = Xr + ((size_t)b * D.R + r) * D.C + cc * 8;
+    const float inv = 1.0f / (float)D.n;
+    *(f32x4 *)dst = f32x4{acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
+    *(f32x4 *)(dst + 4) = f32x4{acc[4] * inv, acc[5] * inv, acc[6] * inv, acc[7] * inv};
+}
+
+// ---------------------------------------------------------------------------
+// Out[m][o] = sum_k In[m][k] W[k][o] (W row-major with ldw columns, as the caller holds it)
+// for a tile of 64 rows m x 128 outputs o per workgroup, the contraction in chunks of 64
+// staged in LDS (the next chunk is requested while the current one is multiplied).
+// Wavefront w owns rows 16 w .. 16 w + 15; the product is formed transposed
+// (D[output 16 t + 4 g + jj][row i]) so that a lane stores 4 consecutive outputs of one row;
+// its W operand (rows = outputs) comes out of the row-major chunk by the transposing LDS read.
+// Output column o goes to buffer o / cols (three buffers of `cols` columns each, e.g. Q, K,
+// V), column o % cols.
+// SPLIT: In is float32 and enters as three exact bf16 terms (smallest first), Out is float32;
+// otherwise both are bf16.
+constexpr int kGemmPitch = 80;      // bf16 per LDS row of In: 64 + 16 (rows of 160 bytes)
+constexpr int kGemmPitchW = 144;    // of W: 128 + 16 (rows of 288 bytes)
+
+struct GemmOut {
+    void *buf[3];
+    int cols;
+};
+
+template <bool SPLIT>
+__global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const bf16_t *__restrict__ W,
+                                              int ldw, int M, int K, int Nout, GemmOut out)
+{
+    constexpr int P = kGemmPitch, PW = kGemmPitchW, NT = SPLIT ? 3 : 1;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *Ws = (bf16_t *)smem;                 // [64 k][PW]
+    bf16_t *Xs = Ws + 64 * PW;                   // [NT][64][P]
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave, g = lane / 16, i = lane % 16;
+    const int otiles = (Nout + 127) / 128;
+    const int m0 = (blockIdx.x / otiles) * 64, o0 = (blockIdx.x % otiles) * 128;
+
+    // this thread's pieces of a chunk: 4 x 16 bytes of W, and 2 x 16 bytes of bf16 In or
+    // 2 x 8 floats of float32 In
+    u32x4 wreg[4], xreg[SPLIT ? 4 : 2];
+    auto request = [&](int k0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = tid + 256 * u;                       // (row k, 8 outputs)
+            const int o = min(o0 + (idx % 16) * 8, Nout - 8);    // columns past the end repeat the last; never stored
+            wreg[u] = *(const u32x4 *)(W + (size_t)(k0 + idx / 16) * ldw + o);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = tid + 256 * u;
+            const int m = min(m0 + idx / 8, M - 1);
+            if (SPLIT) {
+                const float *src = (const float *)In + (size_t)m * K + k0 + (idx % 8) * 8;
+                xreg[2 * u] = *(const u32x4 *)src;
+                xreg[2 * u + 1] = *(const u32x4 *)(src + 4);
+            } else {
+                xreg[u] = *(const u32x4 *)((const bf16_t *)In + (size_t)m * K + k0 + (idx % 8) * 8);
+            }
+        }
+    };
+    auto park = [&]() {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = tid + 256 * u;
+            *(u32x4 *)(Ws + (idx / 16) * PW + (idx % 16) * 8) = wreg[u];
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = tid + 256 * u;
+            bf16_t *dst = Xs + (idx / 8) * P + (idx % 8) * 8;
+            if (SPLIT) {
+                const f32x4 lo = __builtin_bit_cast(f32x4, xreg[2 * u]), hi = __builtin_bit_cast(f32x4, xreg[2 * u + 1]);
+                const float x[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                bf16x8 t[3];
+                split3(x, t);
+#pragma unroll
+                for (int q = 0; q < 3; ++q) *(bf16x8 *)(dst + q * 64 * P) = t[q];
+            } else {
+                *(u32x4 *)dst = xreg[u];
+            }
+        }
+    };
+
+    f32x4 acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    request(0);
+    for (int k0 = 0; k0 < K; k0 += 64) {
+        if (k0) __syncthreads();          // the previous chunk has been read
+        park();
+        __syncthreads();
+        if (k0 + 64 < K) request(k0 + 64);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 xb[NT];
+#pragma unroll
+            for (int q = 0; q < NT; ++q)
+                xb[q] = *(const bf16x8 *)(Xs + (q * 64 + 16 * wave + i) * P + 32 * ks + 8 * g);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const bf16_t *wp = Ws + (32 * ks + 8 * g + i / 4) * PW + 16 * t + 4 * (i % 4);
+                const u32x2 w0 = __builtin_bit_cast(u32x2, lds_read_tr16(wp));
+                const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 4 * PW));
+                const bf16x8 wf = __builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]});
+#pragma unroll
+                for (int q = NT - 1; q >= 0; --q) acc[t] = mfma16(wf, xb[q], acc[t]);
+            }
+        }
+    }
+    const int m = m0 + 16 * wave + i;
+    if (m >= M) return;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const int o = o0 + 16 * t + 4 * g;
+        if (o >= Nout) break;
+        const int which = o / out.cols, col = o % out.cols;
+        if (SPLIT) *(f32x4 *)((float *)out.buf[which] + (size_t)m * out.cols + col) = acc[t];
+        else *(u32x2 *)((bf16_t *)out.buf[which] + (size_t)m * out.cols + col) = pack4(acc[t]);
+    }
+}
+
+constexpr size_t gemm_smem(bool split)
+{
+    return (size_t)64 * kGemmPitchW * 2 + (size_t)(split ? 3 : 1) * 64 * kGemmPitch * 2;
+}
+
+// ---------------------------------------------------------------------------
+// Rows of A^r = Q^r (K^r)^T (Eq. 4) in float32 and their top-k (Eq. 5) for workgroup
+// (image, 16 query regions), R <= 64: the channels pass through LDS 64 at a time (K^r of all
+// regions as [16][kQkRS][4]: channel group, region, channel; Q^r of the 16 rows), wavefront w
+// accumulates rows 4 w .. 4 w + 3 with lane j holding entry j.
+constexpr int kQkRS = 65;
+
+__global__ __launch_bounds__(256) void k_route_qk(const float *__restrict__ Qr, const float *__restrict__ Kr,
+                                                  int32_t *__restrict__ Ir, float *__restrict__ Ar, Dims D)
+{
+    __shared__ __attribute__((aligned(16))) float Kt[16 * kQkRS * 4];
+    __shared__ __attribute__((aligned(16))) float Qs[16 * 68];
+    const int groups = (D.R + 15) / 16;
+    const int b = blockIdx.x / groups, myrt = blockIdx.x % groups;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const size_t img = (size_t)b * D.R * D.C;
+    float a[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 < D.C; c0 += 64) {
+        f32x4 kv[4], qv;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = tid + 256 * u;               // (region, 4-channel group)
+            const int r = min(idx / 16, D.R - 1);        // regions past R repeat the last; never used
+            kv[u] = *(const f32x4 *)(Kr + img + (size_t)r * D.C + c0 + (idx % 16) * 4);
+        }
+        {
+            const int r = min(16 * myrt + tid / 16, D.R - 1);
+            qv = *(const f32x4 *)(Qr + img + (size_t)r * D.C + c0 + (tid % 16) * 4);
+        }
+        if (c0) __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = tid + 256 * u;
+            *(f32x4 *)(Kt + ((idx % 16) * kQkRS + idx / 16) * 4) = kv[u];
+        }
+        *(f32x4 *)(Qs + (tid / 16) * 68 + (tid % 16) * 4) = qv;
+        __syncthreads();
+#pragma unroll 4
+        for (int c4 = 0; c4 < 16; ++c4) {
+            const f32x4 k4 = *(const f32x4 *)(Kt + (c4 * kQkRS + lane) * 4);
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const f32x4 q4 = *(const f32x4 *)(Qs + (4 * wave + rr) * 68 + 4 * c4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[rr] = fmaf(q4[e], k4[e], a[rr]);
+            }
+        }
+    }
+    const int r0 = 16 * myrt + 4 * wave;
+    if (r0 >= D.R) return;
+    const int nrows = min(4, D.R - r0);
+    const size_t row0 = (size_t)b * D.R + r0;
+    if (Ar && lane < D.R) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+            if (rr < nrows) Ar[(row0 + rr) * D.R + lane] = a[rr];
+    }
+    wave_topk_rows<4>(a, nrows, lane, D.R, D.k, Ir + row0 * D.k);
+}
+
+struct WideWs {
+    bf16_t *q, *k, *v, *o;
+    float *xr, *qr, *kr;
+    int32_t *ir;
+    size_t bytes;
+};
+
+WideWs carve(const Dims &D, void *ws)
+{
+    WideWs w;
+    char *p = (char *)ws;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *q = p ? p + off : nullptr; off += align256(bytes); return q; };
+    const size_t tok = (size_t)D.B * D.N, reg = (size_t)D.B * D.R;
+    w.q = (bf16_t *)take(tok * D.C * 2);
+    w.k = (bf16_t *)take(tok * D.C * 2);
+    w.v = (bf16_t *)take(tok * D.C * 2);
+    w.o = (bf16_t *)take(tok * D.C * 2);
+    w.xr = (float *)take(reg * D.C * 4);
+    w.qr = (float *)take(reg * D.C * 4);
+    w.kr = (float *)take(reg * D.C * 4);
+    w.ir = (int32_t *)take(reg * D.k * 4);
+    w.bytes = off;
+    return w;
+}
+
+template <bool SPLIT>
+int launch_gemm(const void *In, const bf16_t *W, int ldw, long M, int K, int Nout, GemmOut out, int kernel_id,
+                hipStream_t st)
+{
+    static bool opted = false;
+    if (!opted) {
+        if (hipFuncSetAttribute((const void *)k_gemm<SPLIT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)gemm_smem(SPLIT)) != hipSuccess)
+            return BRA_ERR_LAUNCH;
+        opted = true;
+    }
+    const long grid = ((M + 63) / 64) * ((Nout + 127) / 128);
+    ProfScope ps(st, kernel_id);
+    hipLaunchKernelGGL(k_gemm<SPLIT>, dim3((unsigned)grid), dim3(256), gemm_smem(SPLIT), st, In, W, ldw, (int)M, K, Nout,
+                       out);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+// Pooling, region-level projections, A^r rows and top-k.
+int route_steps(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const WideWs &w, int32_t *Ir, float *Ar_opt,
+                hipStream_t st)
+{
+    {
+        const long items = (long)D.B * D.R * (D.C / 8);
+        ProfScope ps(st, K_MFMA_POOL_QK);
+        hipLaunchKernelGGL(k_pool_wide, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, X, w.xr, D);
+    }
+    const int rc = launch_gemm<true>(w.xr, Wqkv, 3 * D.C, (long)D.B * D.R, D.C, 2 * D.C, GemmOut{{w.qr, w.kr, nullptr}, D.C},
+                                     K_MFMA_ROUTE_ROWS, st);
+    if (rc != BRA_OK) return rc;
+    ProfScope ps(st, K_MFMA_ROUTE_ROWS);
+    hipLaunchKernelGGL(k_route_qk, dim3(D.B * ((D.R + 15) / 16)), dim3(256), 0, st, w.qr, w.kr, Ir, Ar_opt, D);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+}  // namespace
+
+bool wide_shape(const Dims &D) { return D.C != 64 && D.C != 128 && D.C != 256; }
+
+bool wide_supported(const Dims &D)
+{
+    if (D.dtype != BRA_BF16 || !wide_shape(D)) return false;
+    if (D.S > kFastRouteMaxS || D.C > 4096) return false;                     // R <= 64
+    if (((long)D.B * D.N + 63) / 64 * ((3L * D.C + 127) / 128) > 0x7fffffffL) return false;
+    return map_tail_supported(D);
+}
+
+size_t wide_workspace_bytes(const Dims &D) { return carve(D, nullptr).bytes; }
+
+int wide_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, float *Ar_opt, void *ws,
+               hipStream_t st)
+{
+    const WideWs w = carve(D, ws);
+    return route_steps(D, (const bf16_t *)X, (const bf16_t *)Wqkv, w, Ir, Ar_opt, st);
+}
+
+int wide_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo, const void *Wlce, void *Y,
+                 int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, hipStream_t st)
+{
+    const WideWs w = carve(D, ws);
+    const int32_t *Ir_src = Ir_in_opt;
+    if (!Ir_in_opt) {
+        int32_t *Ir_dst = Ir_out_opt ? Ir_out_opt : w.ir;
+        const int rc = route_steps(D, (const bf16_t *)X, (const bf16_t *)Wqkv, w, Ir_dst, nullptr, st);
+        if (rc != BRA_OK) return rc;
+        Ir_src = Ir_dst;
+    }
+    const long M = (long)D.B * D.N;
+    int rc = launch_gemm<false>(X, (const bf16_t *)Wqkv, 3 * D.C, M, D.C, 3 * D.C, GemmOut{{w.q, w.k, w.v}, D.C}, K_MFMA_QKV, st);
+    if (rc != BRA_OK) return rc;
+    AttnArgs A = {};
+    A.X = (const bf16_t *)X; A.Q = w.q; A.K = w.k; A.V = w.v;
+    A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = (const bf16_t *)Wlce; A.Y = (bf16_t *)Y;
+    A.c_exp = D.scale * 1.4426950408889634f;
+    rc = launch_map_tail(D, A, w.o, st);
+    if (rc != BRA_OK) return rc;
+    return launch_gemm<false>(w.o, (const bf16_t *)Wo, D.C, M, D.C, D.C, GemmOut{{Y, nullptr, nullptr}, D.C}, K_MFMA_WO, st);
+}
+
+}  // namespace bra

@@ -67,6 +67,15 @@ CONFIGS = {
 }
 
 
+# Further operating points of the paper's backbones (not benchmark configurations): the last
+# stage (7x7 map, S = 7: one token per region, k = S^2 is full attention) at C = 512, and the
+# third stage of the wider variant (C = 384).
+NEXT_CONFIGS = {
+    6: BraConfig("next_stage4_224", 6, 64, 7, 7, 512, 16, 7, 49, "bf16"),
+    7: BraConfig("next_wide_stage3_224", 7, 64, 14, 14, 384, 12, 7, 16, "bf16"),
+}
+
+
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """Round float32 values to the nearest bf16 (ties to even); returns float32."""
     a = np.ascontiguousarray(a, dtype=np.float32)

@@ -12,7 +12,7 @@ import torch
 
 import paper_2303_08810_amd as bra
 from parity_util import (check_output, check_routing, run_oracle, to_device, to_numpy)
-from synthetic_inputs import CONFIGS, make_config_inputs, make_inputs
+from synthetic_inputs import CONFIGS, NEXT_CONFIGS, make_config_inputs, make_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -109,6 +109,32 @@ def test_mfma_small_regions(B, H, W, C, heads, S, k):
     compare(X, Wqkv, Wo, Wlce, "bf16", S, k, heads, "auto")
 
 
+WIDE_SHAPES = [  # other channel counts (multiples of 64, heads of 32 channels), small regions
+    (2, 7, 7, 512, 16, 7, 49),     # last-stage shape: one token per region, k = S^2
+    (2, 14, 14, 384, 12, 7, 16),   # third stage of the wide variant, n = 4
+    (1, 8, 8, 192, 6, 4, 3),       # n = 4, ragged key block
+    (2, 7, 7, 320, 10, 7, 5),      # 3 C is not a multiple of the 128-column tile
+    (1, 16, 8, 448, 14, 4, 2),     # 4 x 2 regions, n = 8
+    (3, 6, 6, 768, 24, 3, 9),      # n = 4, k = S^2, 67 rows: ragged row tile
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,S,k", WIDE_SHAPES)
+def test_mfma_wide_channels(B, H, W, C, heads, S, k):
+    X, Wqkv, Wo, Wlce = make_inputs(B, H, W, C, seed=5000 + H + 3 * C + k, dtype="bf16")
+    compare(X, Wqkv, Wo, Wlce, "bf16", S, k, heads, "mfma")
+
+
+def test_mfma_wide_forced_routing():
+    X, Wqkv, Wo, Wlce = make_inputs(2, 8, 8, 192, seed=78, dtype="bf16")
+    r = np.arange(16, dtype=np.int32)
+    Ir_in = np.broadcast_to(np.stack([(r + 1) % 16, (5 * r) % 16], axis=1)[None], (2, 16, 2)).copy()
+    Y, Ir, _, _ = gpu_forward(X, Wqkv, Wo, Wlce, "bf16", 4, 2, 6, "mfma", Ir_in=Ir_in)
+    np.testing.assert_array_equal(Ir, Ir_in)
+    ref = run_oracle(X, Wqkv, Wo, Wlce, dict(S=4, k=2, heads=6), Ir_in=Ir_in)
+    check_output(Y, ref["Y"], "bf16")
+
+
 def test_mfma_scale_and_forced_routing():
     X, Wqkv, Wo, Wlce = make_inputs(2, 16, 16, 64, seed=77, dtype="bf16")
     compare(X, Wqkv, Wo, Wlce, "bf16", 2, 2, 2, "mfma", scale=0.05)
@@ -145,6 +171,13 @@ def test_named_workloads_full_size(idx):
     cfg = CONFIGS[idx]
     X, Wqkv, Wo, Wlce = make_config_inputs(cfg)
     compare(X, Wqkv, Wo, Wlce, cfg.dtype, cfg.S, cfg.k, cfg.heads, "auto", images=FULL[idx])
+
+
+@pytest.mark.parametrize("idx,images", [(6, [0, 33, 63]), (7, [5, 63])])
+def test_next_workloads_full_size(idx, images):
+    cfg = NEXT_CONFIGS[idx]
+    X, Wqkv, Wo, Wlce = make_config_inputs(cfg)
+    compare(X, Wqkv, Wo, Wlce, cfg.dtype, cfg.S, cfg.k, cfg.heads, "mfma", images=images)
 
 
 @pytest.mark.parametrize("idx", [2, 4])
