@@ -694,19 +694,25 @@ struct AttnSmem {
 };
 
 // Routed attention + LCE + W^o for regions of n >= 64 tokens (Eq. 6-7, Eq. 2).
-// One workgroup = 64 query tokens (64/rw full rows of one region), all heads,
-// 4 wavefronts; wavefront w owns queries 16 w .. 16 w + 15.  Keys and values of the
-// k routed regions are copied by index, 64 tokens at a time, from the projected
-// maps into LDS; one online softmax runs over all k n keys.
-template <int C>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3)))
+// One workgroup = 64 query tokens (64/rw full rows of one region), all heads; wavefront
+// w % 4 owns queries 16 (w % 4) .. + 15.  Keys and values of the k routed regions are copied
+// by index, 64 tokens at a time, from the projected maps into LDS; one online softmax runs
+// over all k n keys.
+// HG = 1: 4 wavefronts, each with all heads.  HG = 2 (C = 64): 8 wavefronts, group w / 4 takes
+// half of the heads over the same staged key blocks and, at the end, half of the output
+// channels of W^o: twice the wavefronts per compute unit when there are few workgroups.
+template <int C, int HG = 1>
+__global__ __launch_bounds__(256 * HG) __attribute__((amdgpu_waves_per_eu(2, 2 + HG)))
 void k_attn_big(AttnArgs A, Dims D)
 {
     typedef AttnSmem<C> SM;
-    constexpr int CS = SM::CS, OS = SM::OS, HEADS = C / 32, KS = C / 32, CH = C / 8;
-    constexpr int NBT = CH / 4;                 // 16-byte chunks per thread for a 64-row tile
+    static_assert(HG == 1 || C == 64, "head groups are laid out for two heads");
+    constexpr int CS = SM::CS, OS = SM::OS, HEADS = C / 32, HPG = HEADS / HG, KS = C / 32, CH = C / 8;
+    constexpr int NT = 256 * HG;
+    constexpr int NBT = 64 * CH / NT;           // 16-byte chunks per thread for a 64-row tile
     constexpr int NBH = 5;                      // halo chunks per thread and batch
     constexpr bool kPrefetchWo = (C == 64);
+    constexpr int NWT = 4 / HG;                 // W^o tiles of a wavefront (C == 64)
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)(smem + SM::k_off);
     bf16_t *Vs = (bf16_t *)(smem + SM::v_off);
@@ -717,7 +723,8 @@ void k_attn_big(AttnArgs A, Dims D)
     const int wid = swizzled_block();
     if (wid >= A.total) return;
 
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int wave = (threadIdx.x / kWave) % 4, hg = threadIdx.x / (4 * kWave), lane = threadIdx.x % kWave;
+    const int h0 = hg * HPG;
     const int g = lane / 16, i = lane % 16;
     const int chunks = D.n / 64;               // query tiles per region
     const int qh = 64 / D.rw;                  // rows per query tile
@@ -732,36 +739,36 @@ void k_attn_big(AttnArgs A, Dims D)
     // Everything that does not depend on the routing is requested first: V halo, LCE
     // weights, this lane's query fragments and (small C) the W^o fragments.
     u32x4 hreg[NBH];
-    tile_load<C, NBH>(hreg, A.V + img_off, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, 0);
+    tile_load<C, NBH, NT>(hreg, A.V + img_off, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, 0);
     LceWeights<C> lw;
     lw.load(A.Wlce);
     const int q = 16 * wave + i;
     const int qy = fast_div(q, rw_inv);
     const size_t qtok = (size_t)(y0 + qy) * D.W + x0 + q - qy * D.rw;
-    bf16x8 qf[HEADS];
+    bf16x8 qf[HPG];
 #pragma unroll
-    for (int h = 0; h < HEADS; ++h) qf[h] = *(const bf16x8 *)(A.Q + img_off + qtok * C + 32 * h + 8 * g);
-    bf16x8 wof[kPrefetchWo ? 4 : 1][KS];
+    for (int h = 0; h < HPG; ++h) qf[h] = *(const bf16x8 *)(A.Q + img_off + qtok * C + 32 * (h0 + h) + 8 * g);
+    bf16x8 wof[kPrefetchWo ? NWT : 1][KS];
     if constexpr (kPrefetchWo) {
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt)
+        for (int tt = 0; tt < NWT; ++tt)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) wof[tt][ks] = wo_fragment<C>(A.WoT, 0, tt, ks, g, i);
+            for (int ks = 0; ks < KS; ++ks) wof[tt][ks] = wo_fragment<C>(A.WoT, 0, NWT * hg + tt, ks, g, i);
     }
 
     // Routing row of this region.
     const int32_t *irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
     if (A.Ir_out && A.Ir_out != A.Ir_src && ch == 0)
-        for (int p = threadIdx.x; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
+        for (int p = threadIdx.x; p < D.k; p += NT) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
 
-    tile_store<C, CS, NBH>(Hs, hreg, hrows, 0);
-    for (int first = 256 * NBH; first < hrows * CH; first += 256 * NBH) {
-        tile_load<C, NBH>(hreg, A.V + img_off, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, first);
-        tile_store<C, CS, NBH>(Hs, hreg, hrows, first);
+    tile_store<C, CS, NBH, NT>(Hs, hreg, hrows, 0);
+    for (int first = NT * NBH; first < hrows * CH; first += NT * NBH) {
+        tile_load<C, NBH, NT>(hreg, A.V + img_off, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, first);
+        tile_store<C, CS, NBH, NT>(Hs, hreg, hrows, first);
     }
     lw.store(Wl);
 
-    SoftmaxState<HEADS> st;
+    SoftmaxState<HPG> st;
     st.init();
     const int nblocks = D.kn / 64;
     // K / V blocks of 64 routed tokens: the next block is requested as soon as the current
@@ -770,26 +777,48 @@ void k_attn_big(AttnArgs A, Dims D)
     auto request = [&](int kb) {
         const int j = irp[kb / chunks];
         const int ky0 = (j / D.S) * D.rh + (kb % chunks) * qh, kx0 = (j % D.S) * D.rw;
-        tile_load<C, NBT>(kreg, A.K + img_off, ky0, kx0, D.rw, rw_inv, 64, D.H, D.W, 0);
-        tile_load<C, NBT>(vreg, A.V + img_off, ky0, kx0, D.rw, rw_inv, 64, D.H, D.W, 0);
+        tile_load<C, NBT, NT>(kreg, A.K + img_off, ky0, kx0, D.rw, rw_inv, 64, D.H, D.W, 0);
+        tile_load<C, NBT, NT>(vreg, A.V + img_off, ky0, kx0, D.rw, rw_inv, 64, D.H, D.W, 0);
     };
     request(0);
     for (int kb = 0; kb < nblocks; ++kb) {
         __syncthreads();   // the previous block's readers are done with Ks / Vs
-        tile_store<C, CS, NBT>(Ks, kreg, 64, 0);
-        tile_store<C, CS, NBT>(Vs, vreg, 64, 0);
+        tile_store<C, CS, NBT, NT>(Ks, kreg, 64, 0);
+        tile_store<C, CS, NBT, NT>(Vs, vreg, 64, 0);
         if (kb + 1 < nblocks) request(kb + 1);
         __syncthreads();
-        attn_key_block<C, CS>(Ks, Vs, qf, st, A.c_exp, g, i);
+        attn_key_block<C, CS, HPG>(Ks, Vs, qf, st, A.c_exp, g, i, h0);
     }
     __builtin_amdgcn_s_setprio(2);      // late phases first: the workgroup's LDS is freed sooner
     __syncthreads();   // everyone is done with Ks / Vs: the output tile may overwrite them
-    attn_write_out<C, OS>(Os, st, wave, g, i);
+    attn_write_out<C, OS, HPG>(Os, st, wave, g, i, h0);
     __syncthreads();
-    lce_add_valu<C, CS, OS>(Hs, Wl, Os, qh, D.rw, hw);
+    lce_add_valu<C, CS, OS, NT>(Hs, Wl, Os, qh, D.rw, hw);
     __syncthreads();
-    wo_project_store<C, OS, kPrefetchWo>(Os, kPrefetchWo ? wof : nullptr, A.WoT,
-                                         A.Y + img_off + qtok * C, wave, g, i);
+    if constexpr (HG == 1) {
+        wo_project_store<C, OS, kPrefetchWo>(Os, kPrefetchWo ? wof : nullptr, A.WoT,
+                                             A.Y + img_off + qtok * C, wave, g, i);
+    } else {
+        // group hg forms tiles NWT hg .. of Y^T = Wo^T O^T: 8 of this lane's 16 output channels
+        bf16x8 of[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const float *src = Os + (16 * wave + i) * OS + 32 * ks + 8 * g;
+            const f32x4 lo = *(const f32x4 *)src, hi = *(const f32x4 *)(src + 4);
+            const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            of[ks] = pack8(v);
+        }
+        u32x2 yp[NWT];
+#pragma unroll
+        for (int tt = 0; tt < NWT; ++tt) {
+            f32x4 ya = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) ya = mfma16(wof[tt][ks], of[ks], ya);
+            yp[tt] = pack4(ya);
+        }
+        u32x4 *dst = (u32x4 *)(A.Y + img_off + qtok * C + 16 * g);
+        dst[hg] = u32x4{yp[0][0], yp[0][1], yp[1][0], yp[1][1]};
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1053,7 +1082,7 @@ void k_fused(AttnArgs A, Dims D)
     bf16x8 ob[HEADS];
 #pragma unroll
     for (int h = 0; h < HEADS; ++h) {
-        const float inv = 1.0f / st.l[h];
+        const float inv = 1.0f / st.denom(h);
         float v[8];
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
@@ -1332,11 +1361,21 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
         return launch_wo<C>(D, w.o, Wo, Y, st);
     }
     {
-        static bool opted = false;
-        if (!lds_opt_in(k_attn_big<C>, opted)) return BRA_ERR_LAUNCH;
         const size_t smem = AttnSmem<C>::bytes(hrows);
         ProfScope ps(st, K_MFMA_ATTENTION);
-        hipLaunchKernelGGL(k_attn_big<C>, dim3(grid), dim3(256), smem, st, A, D);
+        if constexpr (C == 64) {
+            // few workgroups: twice the wavefronts each (benchmarking aid: BRA_ATTN_WAVES=4 / 8 forces)
+            static const int forced = getenv("BRA_ATTN_WAVES") ? atoi(getenv("BRA_ATTN_WAVES")) : 0;
+            if (forced == 8 || (forced != 4 && A.total < 1024)) {
+                static bool opted8 = false;
+                if (!lds_opt_in(k_attn_big<64, 2>, opted8)) return BRA_ERR_LAUNCH;
+                hipLaunchKernelGGL((k_attn_big<64, 2>), dim3(grid), dim3(512), smem, st, A, D);
+                return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+            }
+        }
+        static bool opted = false;
+        if (!lds_opt_in(k_attn_big<C, 1>, opted)) return BRA_ERR_LAUNCH;
+        hipLaunchKernelGGL((k_attn_big<C, 1>), dim3(grid), dim3(256), smem, st, A, D);
     }
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }

@@ -221,8 +221,8 @@ __device__ __forceinline__ void wave_topk_rows(const float (&v)[NR], int nrows, 
 
 // Global -> register half of a tile copy: chunk idx (16 bytes) is row idx / (C/8) of
 // the tile, token (y0 + row / tw, x0 + row % tw) of the map; chunks past `rows` and
-// tokens outside the image read as zero.
-template <int C, int NB>
+// tokens outside the image read as zero.  NT: threads of the workgroup.
+template <int C, int NB, int NT = 256>
 __device__ __forceinline__ void tile_load(u32x4 (&r)[NB], const bf16_t *__restrict__ img, int y0,
                                           int x0, int tw, float tw_inv, int rows, int H, int W,
                                           int first)
@@ -230,7 +230,7 @@ __device__ __forceinline__ void tile_load(u32x4 (&r)[NB], const bf16_t *__restri
     constexpr int CH = C / 8;
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
-        const int idx = first + (int)threadIdx.x + 256 * u;
+        const int idx = first + (int)threadIdx.x + NT * u;
         const int row = idx / CH, cc = idx % CH;
         const int ty = fast_div(row, tw_inv);
         const int y = y0 + ty, x = x0 + row - ty * tw;
@@ -244,13 +244,13 @@ __device__ __forceinline__ void tile_load(u32x4 (&r)[NB], const bf16_t *__restri
 }
 
 // Register -> LDS half: rows of CS elements.
-template <int C, int CS, int NB>
+template <int C, int CS, int NB, int NT = 256>
 __device__ __forceinline__ void tile_store(bf16_t *dst, const u32x4 (&r)[NB], int rows, int first)
 {
     constexpr int CH = C / 8;
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
-        const int idx = first + (int)threadIdx.x + 256 * u;
+        const int idx = first + (int)threadIdx.x + NT * u;
         const int row = idx / CH, cc = idx % CH;
         if (row < rows) *(u32x4 *)(dst + row * CS + cc * 8) = r[u];
     }
@@ -343,14 +343,16 @@ __device__ __forceinline__ void wave_fmax4(const f32x4 &s, int lane, float (&m)[
 // Online-softmax state of one wavefront: 16 queries (one per lane column i), all heads.
 template <int HEADS>
 struct SoftmaxState {
-    float m[HEADS], l[HEADS];
+    float m[HEADS];          // reference score of the exponentials (at most 2^8 below the running maximum)
+    f32x4 lacc[HEADS];       // softmax denominator of query i, the same in all four entries
     f32x4 acc[HEADS][2];     // O^T[channel 16 dt + 4 g + j][query i]
+    __device__ __forceinline__ float denom(int h) const { return lacc[h][0]; }
     __device__ __forceinline__ void init()
     {
 #pragma unroll
         for (int h = 0; h < HEADS; ++h) {
             m[h] = -INFINITY;
-            l[h] = 0.f;
+            lacc[h] = f32x4{0.f, 0.f, 0.f, 0.f};
             acc[h][0] = f32x4{0.f, 0.f, 0.f, 0.f};
             acc[h][1] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
@@ -362,6 +364,11 @@ struct SoftmaxState {
 // softmax over all routed keys), then O^T += V^T P^T with V read by the transposing LDS
 // read: the row of key 32 tp + 16 half + 4 g + i / 4 starts vrow(tp, half) elements into
 // Vs, the head's channels at column vcol of it.  The head's running state is slot h of st.
+// The exponentials are taken against a reference score that follows the running maximum
+// lazily: it moves (and the sums are rescaled) only when some query's block maximum exceeds
+// it by more than 2^8 in the exponent, so p <= 256 and most blocks skip the rescaling; the
+// quotient O / denominator does not depend on the reference.  The denominators come from a
+// product of P^T with an all-ones operand, i.e. they sum the same bf16-rounded P as O does.
 // FIRST: this is the head's first block (state as left by init()), so there is nothing to
 // rescale.
 template <bool FIRST, int HEADS, typename VRow>
@@ -375,24 +382,24 @@ __device__ __forceinline__ void softmax_pv_rows(const bf16_t *Vs, VRow vrow, con
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) mx = fmaxf(mx, s[t][jj]);
     mx = cross_row_max(mx);
-    const float m_new = FIRST ? mx : fmaxf(st.m[h], mx);
-    const float alpha = FIRST ? 0.f : __builtin_amdgcn_exp2f((st.m[h] - m_new) * c_exp);
-    const float mc = m_new * c_exp;
-    float p[4][4], ls = 0.f;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            p[t][jj] = __builtin_amdgcn_exp2f(fmaf(s[t][jj], c_exp, -mc));
-            ls += p[t][jj];
-        }
-    ls = cross_row_sum(ls);
-    st.l[h] = FIRST ? ls : st.l[h] * alpha + ls;
-    st.m[h] = m_new;
-    if (!FIRST) {
+    if (FIRST) {
+        st.m[h] = mx;
+    } else if (__builtin_amdgcn_ballot_w64(mx > st.m[h] + 8.0f / c_exp) != 0) {
+        // some query's scores outgrew the reference by 2^8: move it, rescale what has been summed
+        const float m_new = fmaxf(st.m[h], mx);
+        const float alpha = __builtin_amdgcn_exp2f((st.m[h] - m_new) * c_exp);
+        st.m[h] = m_new;
+        st.lacc[h] *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) st.acc[h][dt] *= alpha;
     }
+    const float mc = st.m[h] * c_exp;
+    float p[4][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) p[t][jj] = __builtin_amdgcn_exp2f(fmaf(s[t][jj], c_exp, -mc));
+    const u32x4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
 #pragma unroll
     for (int tp = 0; tp < 2; ++tp) {
         float pv[8] = {p[2 * tp][0], p[2 * tp][1], p[2 * tp][2], p[2 * tp][3],
@@ -407,6 +414,7 @@ __device__ __forceinline__ void softmax_pv_rows(const bf16_t *Vs, VRow vrow, con
             u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
             st.acc[h][dt] = mfma16(__builtin_bit_cast(bf16x8, av), pb, st.acc[h][dt]);
         }
+        st.lacc[h] = mfma16(__builtin_bit_cast(bf16x8, ones), pb, st.lacc[h]);   // sums of the rounded P
     }
 }
 
@@ -423,37 +431,38 @@ __device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (
 
 // One block of 64 keys (rows of Ks / Vs, CS elements per row) against the 16 queries of
 // this wavefront (qf[h] = B operand of head h): S^T = K Q^T, then the softmax / PV step.
-template <int C, int CS>
+// The wavefront handles the HPG heads from h0 on (slot h of qf / st is head h0 + h).
+template <int C, int CS, int HPG = C / 32>
 __device__ __forceinline__ void attn_key_block(const bf16_t *Ks, const bf16_t *Vs,
-                                               const bf16x8 (&qf)[C / 32],
-                                               SoftmaxState<C / 32> &st, float c_exp, int g, int i)
+                                               const bf16x8 (&qf)[HPG],
+                                               SoftmaxState<HPG> &st, float c_exp, int g, int i, int h0 = 0)
 {
-    constexpr int HEADS = C / 32;
 #pragma unroll
-    for (int h = 0; h < HEADS; ++h) {
+    for (int h = 0; h < HPG; ++h) {
+        const int col = 32 * (h0 + h);
         f32x4 s[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + 32 * h + 8 * g);
+            const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + col + 8 * g);
             s[t] = mfma16(kf, qf[h], f32x4{0.f, 0.f, 0.f, 0.f});   // S^T[key 16t+4g+j][query i]
         }
-        softmax_pv_block<CS>(Vs, s, st, h, 32 * h, c_exp, g, i);
+        softmax_pv_block<CS>(Vs, s, st, h, col, c_exp, g, i);
     }
 }
 
 // Normalised attention output of this wavefront's 16 queries -> rows 16 wave + i of the
 // float32 output tile Os (OS floats per row).
-template <int C, int OS>
-__device__ __forceinline__ void attn_write_out(float *Os, const SoftmaxState<C / 32> &st, int wave,
-                                               int g, int i)
+template <int C, int OS, int HPG = C / 32>
+__device__ __forceinline__ void attn_write_out(float *Os, const SoftmaxState<HPG> &st, int wave,
+                                               int g, int i, int h0 = 0)
 {
 #pragma unroll
-    for (int h = 0; h < C / 32; ++h) {
-        const float inv = 1.0f / st.l[h];
+    for (int h = 0; h < HPG; ++h) {
+        const float inv = 1.0f / st.denom(h);
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
             f32x4 o = st.acc[h][dt] * inv;
-            *(f32x4 *)(Os + (16 * wave + i) * OS + 32 * h + 16 * dt + 4 * g) = o;
+            *(f32x4 *)(Os + (16 * wave + i) * OS + 32 * (h0 + h) + 16 * dt + 4 * g) = o;
         }
     }
 }
@@ -461,13 +470,13 @@ __device__ __forceinline__ void attn_write_out(float *Os, const SoftmaxState<C /
 // LCE (Eq. 7): 5x5 depth-wise cross-correlation of V over the halo tile Hs (rows of CS
 // bf16, (qh + 4) x hw tokens, hw = rw + 4), added to the output tile Os.  One task =
 // (row of the query tile, 8-token segment, channel pair); Wl is [25][C] float32.
-template <int C, int CS, int OS>
+template <int C, int CS, int OS, int NT = 256>
 __device__ __forceinline__ void lce_add_valu(const bf16_t *Hs, const float *Wl, float *Os, int qh,
                                              int rw, int hw)
 {
     const int segs = rw / 8, cp_n = C / 2;
     const int tasks = qh * segs * cp_n;
-    for (int task = threadIdx.x; task < tasks; task += 256) {
+    for (int task = threadIdx.x; task < tasks; task += NT) {
         const int cp = task % cp_n, seg = (task / cp_n) % segs, r = task / (cp_n * segs);
         const int c = 2 * cp;
         float a0[8], a1[8];

@@ -95,7 +95,7 @@ __device__ __forceinline__ void small_attention(const AttnArgs &A, const Dims &D
     }
 #pragma unroll
     for (int hh = 0; hh < HPW; ++hh) {
-        const float inv = 1.0f / st.l[hh];         // heads past the end: 1 / 0 times 0, never used
+        const float inv = 1.0f / st.denom(hh);         // heads past the end: 1 / 0 times 0, never used
         oacc[hh][0] = st.acc[hh][0] * inv;
         oacc[hh][1] = st.acc[hh][1] * inv;
     }
@@ -427,7 +427,7 @@ __global__ __launch_bounds__(kMapThreads) void k_attn_map(AttnArgs A, bf16_t *__
             softmax_pv_rows<false>(
                 Vs, [&](int tp, int half) { return vrow[tp][half]; }, s, st, 0, 0, A.c_exp, i);
         }
-        const float inv = 1.0f / st.l[0];
+        const float inv = 1.0f / st.denom(0);
         if (i < n) {
             bf16_t *orow = O + w.img_off + (size_t)(tok0 + q_in) * C + 32 * h + 4 * g;
 #pragma unroll
