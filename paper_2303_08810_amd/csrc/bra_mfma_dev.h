@@ -344,7 +344,7 @@ __device__ __forceinline__ void wave_fmax4(const f32x4 &s, int lane, float (&m)[
 template <int HEADS>
 struct SoftmaxState {
     float m[HEADS];          // reference score of the exponentials (at most 2^8 below the running maximum)
-    f32x4 lacc[HEADS];       // softmax denominator of query i, the same in all four entries
+    f32x4 lacc[HEADS];       // softmax denominator of query i in entry 0 (all four entries when summed by MFMA)
     f32x4 acc[HEADS][2];     // O^T[channel 16 dt + 4 g + j][query i]
     __device__ __forceinline__ float denom(int h) const { return lacc[h][0]; }
     __device__ __forceinline__ void init()
@@ -367,11 +367,13 @@ struct SoftmaxState {
 // The exponentials are taken against a reference score that follows the running maximum
 // lazily: it moves (and the sums are rescaled) only when some query's block maximum exceeds
 // it by more than 2^8 in the exponent, so p <= 256 and most blocks skip the rescaling; the
-// quotient O / denominator does not depend on the reference.  The denominators come from a
-// product of P^T with an all-ones operand, i.e. they sum the same bf16-rounded P as O does.
+// quotient O / denominator does not depend on the reference.  MFMA_SUM: the denominators
+// come from a product of P^T with an all-ones operand (they sum the same bf16-rounded P as O
+// does), which pays when many key blocks follow each other; otherwise they are summed in
+// float32 on the vector unit (entry 0 of the state's denominator only).
 // FIRST: this is the head's first block (state as left by init()), so there is nothing to
 // rescale.
-template <bool FIRST, int HEADS, typename VRow>
+template <bool FIRST, int HEADS, typename VRow, bool MFMA_SUM = false>
 __device__ __forceinline__ void softmax_pv_rows(const bf16_t *Vs, VRow vrow, const f32x4 (&s)[4],
                                                 SoftmaxState<HEADS> &st, int h, int vcol, float c_exp,
                                                 int i)
@@ -400,6 +402,14 @@ __device__ __forceinline__ void softmax_pv_rows(const bf16_t *Vs, VRow vrow, con
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) p[t][jj] = __builtin_amdgcn_exp2f(fmaf(s[t][jj], c_exp, -mc));
     const u32x4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    if (!MFMA_SUM) {
+        float ls = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) ls += p[t][jj];
+        st.lacc[h][0] += cross_row_sum(ls);
+    }
 #pragma unroll
     for (int tp = 0; tp < 2; ++tp) {
         float pv[8] = {p[2 * tp][0], p[2 * tp][1], p[2 * tp][2], p[2 * tp][3],
@@ -414,19 +424,18 @@ __device__ __forceinline__ void softmax_pv_rows(const bf16_t *Vs, VRow vrow, con
             u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
             st.acc[h][dt] = mfma16(__builtin_bit_cast(bf16x8, av), pb, st.acc[h][dt]);
         }
-        st.lacc[h] = mfma16(__builtin_bit_cast(bf16x8, ones), pb, st.lacc[h]);   // sums of the rounded P
+        if (MFMA_SUM) st.lacc[h] = mfma16(__builtin_bit_cast(bf16x8, ones), pb, st.lacc[h]);   // sums of the rounded P
     }
 }
 
 // The same with the 64 keys in consecutive rows of pitch VS.
-template <int VS, bool FIRST = false, int HEADS>
+template <int VS, bool FIRST = false, bool MFMA_SUM = false, int HEADS>
 __device__ __forceinline__ void softmax_pv_block(const bf16_t *Vs, const f32x4 (&s)[4],
                                                  SoftmaxState<HEADS> &st, int h, int vcol, float c_exp,
                                                  int g, int i)
 {
-    softmax_pv_rows<FIRST>(
-        Vs, [=](int tp, int half) { return (32 * tp + 16 * half + 4 * g + i / 4) * VS; }, s, st, h, vcol,
-        c_exp, i);
+    auto vrow = [=](int tp, int half) { return (32 * tp + 16 * half + 4 * g + i / 4) * VS; };
+    softmax_pv_rows<FIRST, HEADS, decltype(vrow), MFMA_SUM>(Vs, vrow, s, st, h, vcol, c_exp, i);
 }
 
 // One block of 64 keys (rows of Ks / Vs, CS elements per row) against the 16 queries of
@@ -446,7 +455,7 @@ __device__ __forceinline__ void attn_key_block(const bf16_t *Ks, const bf16_t *V
             const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + col + 8 * g);
             s[t] = mfma16(kf, qf[h], f32x4{0.f, 0.f, 0.f, 0.f});   // S^T[key 16t+4g+j][query i]
         }
-        softmax_pv_block<CS>(Vs, s, st, h, col, c_exp, g, i);
+        softmax_pv_block<CS, false, true>(Vs, s, st, h, col, c_exp, g, i);
     }
 }
 
