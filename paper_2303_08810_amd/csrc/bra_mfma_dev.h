@@ -391,7 +391,8 @@ __device__ __forceinline__ void softmax_pv_rows(const bf16_t *Vs, VRow vrow, con
         const float m_new = fmaxf(st.m[h], mx);
         const float alpha = __builtin_amdgcn_exp2f((st.m[h] - m_new) * c_exp);
         st.m[h] = m_new;
-        st.lacc[h] *= alpha;
+        if (MFMA_SUM) st.lacc[h] *= alpha;
+        else st.lacc[h][0] *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) st.acc[h][dt] *= alpha;
     }
@@ -455,7 +456,8 @@ __device__ __forceinline__ void attn_key_block(const bf16_t *Ks, const bf16_t *V
             const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + col + 8 * g);
             s[t] = mfma16(kf, qf[h], f32x4{0.f, 0.f, 0.f, 0.f});   // S^T[key 16t+4g+j][query i]
         }
-        softmax_pv_block<CS, false, true>(Vs, s, st, h, col, c_exp, g, i);
+        // denominators by MFMA while the four accumulator registers per head are affordable
+        softmax_pv_block<CS, false, (HPG <= 4)>(Vs, s, st, h, col, c_exp, g, i);
     }
 }
 

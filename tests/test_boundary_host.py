@@ -52,6 +52,29 @@ def test_workspace_query_and_error_codes():
     assert bra.strerror(-99) == "unknown error code"
 
 
+def test_kernel_family_selection_by_shape():
+    """Which shapes the matrix-core family accepts (path "mfma" fails with -6 otherwise)."""
+    def mfma(**kw):
+        return ws_bytes(dtype=bra.BRA_BF16, path="mfma", **kw)[0]
+    # the five named bf16 workloads' shapes
+    assert mfma(B=64, H=56, W=56, C=64, heads=2, S=7, k=1) == 0
+    assert mfma(B=64, H=28, W=28, C=128, heads=4, S=7, k=4) == 0
+    assert mfma(B=64, H=14, W=14, C=256, heads=8, S=7, k=16) == 0
+    assert mfma(B=2, H=128, W=128, C=64, heads=2, S=8, k=4) == 0
+    # other channel counts: multiples of 64 with heads of 32 channels and small regions
+    assert mfma(B=64, H=7, W=7, C=512, heads=16, S=7, k=49) == 0
+    assert mfma(B=2, H=14, W=14, C=384, heads=12, S=7, k=16) == 0
+    assert mfma(B=2, H=28, W=28, C=512, heads=16, S=7, k=4) == -6      # regions of 16 tokens at C = 512
+    assert mfma(B=2, H=14, W=14, C=96, heads=3, S=7, k=4) == -6        # C not a multiple of 64
+    assert mfma(B=2, H=14, W=14, C=384, heads=6, S=7, k=4) == -6       # heads of 64 channels
+    assert mfma(B=1, H=32, W=32, C=64, heads=2, S=16, k=4) == 0        # 256 regions: routed by the generic kernels
+    # every rejected shape still runs on the generic family
+    for kw in (dict(H=28, W=28, C=512, heads=16, S=7, k=4), dict(H=14, W=14, C=96, heads=3, S=7, k=4),
+               dict(H=14, W=14, C=384, heads=6, S=7, k=4)):
+        rc, n = ws_bytes(dtype=bra.BRA_BF16, path="auto", B=2, **kw)
+        assert rc == 0 and n > 0
+
+
 def test_entry_points_reject_bad_arguments_before_launching():
     L = bra.lib()
     shape = bra.make_shape(1, 28, 28, 64, 2, 7, 4, bra.BRA_F32)
