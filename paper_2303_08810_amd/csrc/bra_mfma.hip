@@ -1419,15 +1419,19 @@ bool attn_big_ok(const Dims &D)
 
 }  // namespace
 
-bool mfma_supported(const Dims &D)
+// Shapes of the kernels specialised by channel count.
+static bool specialised(const Dims &D)
 {
     if (D.dtype != BRA_BF16 || D.d != 32) return false;
-    if (wide_shape(D)) return wide_supported(D);
     if (D.C != 64 && D.C != 128 && D.C != 256) return false;
     if ((long)D.B * D.R * (D.n / 64 + 1) + 8 > 0x7fffffffL) return false;
     if (!fast_route_ok(D) && !generic_supported(D)) return false;   // fallback routing kernels
     return attn_big_ok(D) || small_supported(D);
 }
+
+bool wide_shape(const Dims &D) { return !specialised(D); }
+
+bool mfma_supported(const Dims &D) { return specialised(D) || wide_supported(D); }
 
 size_t mfma_workspace_bytes(const Dims &D)
 {

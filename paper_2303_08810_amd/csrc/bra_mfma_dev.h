@@ -609,6 +609,7 @@ int launch_small(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t 
 // (image-resident attention; A.Q/K/V, Ir_src, Ir_out, Wlce, c_exp set).
 bool map_tail_supported(const Dims &D);
 int launch_map_tail(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st);
+int launch_lce_add_any(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st);   // O += LCE(V), any map, C % 64 == 0
 
 // Pipeline for other channel counts (bra_mfma_wide.hip): any multiple of 64 with heads of 32
 // channels, at most 64 regions of 1, 2, 4 or 8 tokens.

@@ -546,25 +546,27 @@ __global__ __launch_bounds__(kMapThreads) void k_attn_map4(AttnArgs A, bf16_t *_
 }
 
 // ---------------------------------------------------------------------------
-// O <- O_att + LCE(V) (Eq. 7) in place, for workgroup (image, tile of TH full-width image
-// rows, chunk of 64 channels).  LDS holds the V halo tile of the chunk, [(TH + 4) x (W + 4)]
-// tokens x 64 channels; a thread keeps one channel pair for all its (row, 4-token segment)
-// tasks, so its 2 x 25 weights stay in registers.  W^o follows as a plain projection.
+// O <- O_att + LCE(V) (Eq. 7) in place, for workgroup (image, tile of TH image rows x TW
+// columns (the full width on narrow maps), chunk of 64 channels).  LDS holds the V halo tile
+// of the chunk, [(TH + 4) x (TW + 4)] tokens x 64 channels; a thread keeps one channel pair for
+// all its (row, 4-token segment) tasks, so its 2 x 25 weights stay in registers.  W^o follows
+// as a plain projection.
 constexpr int kLceChunk = 64, kLcePitch = kLceChunk + 8;
 
 __global__ __launch_bounds__(256) void k_lce_add(bf16_t *__restrict__ O, const bf16_t *__restrict__ V,
-                                                 const bf16_t *__restrict__ Wlce, Dims D, int TH)
+                                                 const bf16_t *__restrict__ Wlce, Dims D, int TH, int TW)
 {
     constexpr int CH8 = kLceChunk / 8, NBH = 6;
     const int C = D.C, NCH = C / kLceChunk;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Hs = (bf16_t *)smem;
-    const int tiles = (D.H + TH - 1) / TH;
-    const int cc = blockIdx.x % NCH, tile = (blockIdx.x / NCH) % tiles, b = blockIdx.x / (NCH * tiles);
-    const int y0 = tile * TH;
-    const int th = min(TH, D.H - y0);            // rows of this tile
+    const int tiles = (D.H + TH - 1) / TH, xtiles = (D.W + TW - 1) / TW;
+    const int cc = blockIdx.x % NCH, xt = (blockIdx.x / NCH) % xtiles;
+    const int tile = (blockIdx.x / (NCH * xtiles)) % tiles, b = blockIdx.x / (NCH * xtiles * tiles);
+    const int y0 = tile * TH, x0 = xt * TW;
+    const int th = min(TH, D.H - y0), tw = min(TW, D.W - x0);     // rows and columns of this tile
     const size_t img_off = (size_t)b * D.N * C;
-    const int hw = D.W + 4, hrows = (th + 4) * hw;
+    const int hw = tw + 4, hrows = (th + 4) * hw;
     const float hw_inv = 1.0f / (float)hw;
     const int c0 = cc * kLceChunk;
 
@@ -583,7 +585,7 @@ __global__ __launch_bounds__(256) void k_lce_add(bf16_t *__restrict__ O, const b
             const int idx = first + (int)threadIdx.x + 256 * u;
             const int row = idx / CH8, c8 = idx % CH8;
             const int ry = fast_div(row, hw_inv);
-            const int y = y0 - 2 + ry, x = row - ry * hw - 2;
+            const int y = y0 - 2 + ry, x = x0 + row - ry * hw - 2;
             hreg[u] = u32x4{0u, 0u, 0u, 0u};
             if (row < hrows && y >= 0 && y < D.H && x >= 0 && x < D.W)
                 hreg[u] = *(const u32x4 *)(V + img_off + ((size_t)y * D.W + x) * C + c0 + c8 * 8);
@@ -596,7 +598,7 @@ __global__ __launch_bounds__(256) void k_lce_add(bf16_t *__restrict__ O, const b
     }
     __syncthreads();
 
-    const int cp_n = kLceChunk / 2, segs = (D.W + 3) / 4;
+    const int cp_n = kLceChunk / 2, segs = (tw + 3) / 4;
     const int tasks = th * segs * cp_n;
     for (int task = threadIdx.x; task < tasks; task += 256) {
         const int seg = (task / cp_n) % segs, r = task / (cp_n * segs);
@@ -621,17 +623,19 @@ __global__ __launch_bounds__(256) void k_lce_add(bf16_t *__restrict__ O, const b
                 }
             }
         }
-        unsigned *orow = (unsigned *)(O + img_off + ((size_t)(y0 + r) * D.W + seg * 4) * C + c0 + 2 * cpair);
+        unsigned *orow = (unsigned *)(O + img_off + ((size_t)(y0 + r) * D.W + x0 + seg * 4) * C + c0 + 2 * cpair);
         unsigned o2[4];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) o2[x] = seg * 4 + x < D.W ? orow[(size_t)x * (C / 2)] : 0u;
+        for (int x = 0; x < 4; ++x) o2[x] = seg * 4 + x < tw ? orow[(size_t)x * (C / 2)] : 0u;
 #pragma unroll
         for (int x = 0; x < 4; ++x)
-            if (seg * 4 + x < D.W) orow[(size_t)x * (C / 2)] = pack_bf16(bf16_lo(o2[x]) + a0[x], bf16_hi(o2[x]) + a1[x]);
+            if (seg * 4 + x < tw) orow[(size_t)x * (C / 2)] = pack_bf16(bf16_lo(o2[x]) + a0[x], bf16_hi(o2[x]) + a1[x]);
     }
 }
 
-int tile_rows(const Dims &D) { return 64 / D.W; }
+// LCE tile: full-width rows on maps up to 64 columns, else 4 rows x 32 columns.
+int tile_cols(const Dims &D) { return D.W <= 64 ? D.W : 32; }
+int tile_rows(const Dims &D) { return D.W <= 64 ? 64 / D.W : 4; }
 
 int halo_rows_small(const Dims &D) { return (D.rh + 4) * (D.rw + 4); }
 
@@ -647,7 +651,7 @@ static bool one_kernel(const Dims &D)
     return D.rh * ((D.rw + 3) / 4) * (D.C / 2) <= 256 * kMaxLceTasks;
 }
 
-static size_t lce_add_smem(const Dims &D) { return (size_t)(tile_rows(D) + 4) * (D.W + 4) * kLcePitch * 2; }
+static size_t lce_add_smem(const Dims &D) { return (size_t)(tile_rows(D) + 4) * (tile_cols(D) + 4) * kLcePitch * 2; }
 
 static size_t map_smem(const Dims &D)
 {
@@ -725,11 +729,11 @@ static int launch_lce_add(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream
 {
     static bool opted = false;
     if (!opt_in(k_lce_add, opted)) return BRA_ERR_LAUNCH;
-    const int TH = tile_rows(D);
-    const int tiles = (D.H + TH - 1) / TH;
+    const int TH = tile_rows(D), TW = tile_cols(D);
+    const long blocks = (long)D.B * ((D.H + TH - 1) / TH) * ((D.W + TW - 1) / TW) * (D.C / kLceChunk);
+    if (blocks > 0x7fffffffL) return BRA_ERR_UNSUPPORTED;
     ProfScope ps(st, K_MFMA_LCE_ADD);
-    hipLaunchKernelGGL(k_lce_add, dim3(D.B * tiles * (D.C / kLceChunk)), dim3(256), lce_add_smem(D), st, O, A.V,
-                       A.Wlce, D, TH);
+    hipLaunchKernelGGL(k_lce_add, dim3((unsigned)blocks), dim3(256), lce_add_smem(D), st, O, A.V, A.Wlce, D, TH, TW);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
@@ -767,6 +771,12 @@ bool map_tail_supported(const Dims &D)
     if (D.C % 64 != 0 || D.d != 32) return false;
     if (D.n > 8 || (D.n & (D.n - 1)) != 0 || D.W > 64) return false;
     return map_attention(D) && lce_add_smem(D) <= (size_t)kMaxLds;
+}
+
+// O += LCE(V) in place for any map (C a multiple of 64).
+int launch_lce_add_any(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st)
+{
+    return launch_lce_add(D, A, O, st);
 }
 
 int launch_map_tail(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st)

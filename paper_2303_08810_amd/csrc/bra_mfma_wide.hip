@@ -1,14 +1,16 @@
-// Matrix-core pipeline for channel counts beyond the specialised kernels (any C that is a
-// multiple of 64, heads of 32 channels) with small regions, e.g. the last stage of the paper's
-// backbones (7x7 map, S = 7: one token per region, k = S^2, C = 512) and the wider variants'
-// third stage (14x14 map, 4 tokens per region, C = 384).
+// Matrix-core pipeline for the shapes that the specialised kernels do not take: any C that is
+// a multiple of 64, heads of 32 or 64 channels, any region size and count, e.g. the last stage
+// of the paper's backbones (7x7 map, S = 7: one token per region, k = S^2, C = 512), the wider
+// variants' stages (C = 384, 768), S = 16 on large maps, and the plain-ViT adaptation of the
+// appendix (32x32 map, S = 8, k = 12, 12 heads of 64 channels).
 //
 //   k_pool_wide   Xr[b, r, :] = mean of the region's tokens, float32            (Sec. 3.2)
 //   k_gemm<true>  Q^r | K^r = Xr [Wq | Wk] in float32: the means are split exactly into three
 //                 bf16 terms, so the products are those of the float32 computation
 //   k_route_qk    rows of A^r = Q^r (K^r)^T (Eq. 4) and their top-k (Eq. 5)
 //   k_gemm<false> Q | K | V = X Wqkv (Eq. 3), bf16 out
-//   image-resident attention + LCE (bra_mfma_small.hip)                         (Eq. 6, 7)
+//   image-resident attention (small maps, regions of up to 8 tokens; bra_mfma_small.hip) or
+//   k_attn_gen (everything else), then LCE added in place                       (Eq. 6, 7)
 //   k_gemm<false> Y = O Wo (Eq. 2)
 #include "bra_mfma_dev.h"
 
@@ -222,12 +224,165 @@ __global__ __launch_bounds__(256) void k_route_qk(const float *__restrict__ Qr, 
     wave_topk_rows<4>(a, nrows, lane, D.R, D.k, Ir + row0 * D.k);
 }
 
+// ---------------------------------------------------------------------------
+// Routed attention (Eq. 6, Eq. 1) for any region size and heads of 32 or 64 channels:
+// workgroup (image, region, tile of 64 queries of the region, group of 64 channels = 2 or
+// 1 heads), wavefront w with queries 16 w .. 16 w + 15 of the tile.  The k n routed keys are
+// taken 64 at a time: their K and V rows (the group's 128 bytes each, found by index in the
+// projected maps) are copied into LDS with coalesced loads, the next block being requested
+// while the current one is worked on; S^T = K Q^T, one softmax over all routed keys (lazy
+// reference, see softmax_pv_rows), O^T += V^T P^T by the transposing LDS read.  Queries past
+// the end of the region and keys past k n repeat the last one and are masked.
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn_gen(AttnArgs A, bf16_t *__restrict__ O, Dims D)
+{
+    constexpr int HPW = 64 / HD;          // heads of this workgroup
+    constexpr int KSD = HD / 32;          // contraction steps of a score
+    constexpr int NDT = HD / 16;          // 16-channel tiles of a head's output
+    constexpr int XP = 64 + 16;
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * XP];
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[64 * XP];
+    const int C = D.C, ncg = C / 64, n = D.n, kn = D.kn;
+    const int qtiles = (n + 63) / 64;
+    const int cg = blockIdx.x % ncg, qt = (blockIdx.x / ncg) % qtiles;
+    const int reg = (blockIdx.x / (ncg * qtiles)) % D.R, b = blockIdx.x / (ncg * qtiles * D.R);
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave, g = lane / 16, i = lane % 16;
+    const float rw_inv = 1.0f / (float)D.rw, n_inv = 1.0f / (float)n, s_inv = 1.0f / (float)D.S;
+    const size_t img_off = (size_t)b * D.N * C + 64 * cg;
+    auto region_origin = [&](int r) {
+        const int ry = fast_div(r, s_inv);
+        return ry * D.rh * D.W + (r - ry * D.S) * D.rw;
+    };
+    auto in_region = [&](int slot) {
+        const int sy = fast_div(slot, rw_inv);
+        return sy * D.W + slot - sy * D.rw;
+    };
+    const int32_t *irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
+    if (A.Ir_out && A.Ir_out != A.Ir_src && qt == 0 && cg == 0)
+        for (int p = tid; p < D.k; p += 256) A.Ir_out[((size_t)b * D.R + reg) * D.k + p] = irp[p];
+
+    const int slot = 64 * qt + 16 * wave + i;
+    const size_t qtok = (size_t)region_origin(reg) + in_region(min(slot, n - 1));
+    bf16x8 qf[HPW][KSD];
+#pragma unroll
+    for (int hh = 0; hh < HPW; ++hh)
+#pragma unroll
+        for (int ks = 0; ks < KSD; ++ks)
+            qf[hh][ks] = *(const bf16x8 *)(A.Q + img_off + qtok * C + HD * hh + 32 * ks + 8 * g);
+
+    u32x4 kreg[2], vreg[2];
+    auto request = [&](int k0) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = tid + 256 * u;                       // (key of the block, 16-byte piece)
+            const int key = min(k0 + idx / 8, kn - 1);
+            const int p = fast_div(key, n_inv);
+            const size_t tok = (size_t)region_origin(irp[p]) + in_region(key - p * n);
+            const size_t off = img_off + tok * C + (idx % 8) * 8;
+            kreg[u] = *(const u32x4 *)(A.K + off);
+            vreg[u] = *(const u32x4 *)(A.V + off);
+        }
+    };
+    float m[HPW], l[HPW];
+    f32x4 acc[HPW][NDT];
+#pragma unroll
+    for (int hh = 0; hh < HPW; ++hh) {
+        m[hh] = -INFINITY;
+        l[hh] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) acc[hh][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const float lim = 8.0f / A.c_exp;
+    request(0);
+    for (int k0 = 0; k0 < kn; k0 += 64) {
+        if (k0) __syncthreads();              // the previous block has been read
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = tid + 256 * u;
+            *(u32x4 *)(Ks + (idx / 8) * XP + (idx % 8) * 8) = kreg[u];
+            *(u32x4 *)(Vs + (idx / 8) * XP + (idx % 8) * 8) = vreg[u];
+        }
+        if (k0 + 64 < kn) request(k0 + 64);
+        __syncthreads();
+#pragma unroll
+        for (int hh = 0; hh < HPW; ++hh) {
+            f32x4 s[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KSD; ++ks) {
+                    const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * XP + HD * hh + 32 * ks + 8 * g);
+                    s[t] = mfma16(kf, qf[hh][ks], s[t]);        // S^T[key 16 t + 4 g + jj][query i]
+                }
+            }
+            if (k0 + 64 > kn) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj)
+                        if (k0 + 16 * t + 4 * g + jj >= kn) s[t][jj] = -INFINITY;
+            }
+            float mx = s[0][0];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) mx = fmaxf(mx, s[t][jj]);
+            mx = cross_row_max(mx);
+            if (__builtin_amdgcn_ballot_w64(mx > m[hh] + lim) != 0) {
+                const float m_new = fmaxf(m[hh], mx);
+                const float alpha = __builtin_amdgcn_exp2f((m[hh] - m_new) * A.c_exp);
+                m[hh] = m_new;
+                l[hh] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt) acc[hh][dt] *= alpha;
+            }
+            const float mc = m[hh] * A.c_exp;
+            float p[4][4], ls = 0.f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    p[t][jj] = __builtin_amdgcn_exp2f(fmaf(s[t][jj], A.c_exp, -mc));
+                    ls += p[t][jj];
+                }
+            l[hh] += cross_row_sum(ls);
+#pragma unroll
+            for (int tp = 0; tp < 2; ++tp) {
+                const float pv[8] = {p[2 * tp][0], p[2 * tp][1], p[2 * tp][2], p[2 * tp][3],
+                                     p[2 * tp + 1][0], p[2 * tp + 1][1], p[2 * tp + 1][2], p[2 * tp + 1][3]};
+                const bf16x8 pb = pack8(pv);
+                const bf16_t *vp = Vs + (32 * tp + 4 * g + i / 4) * XP + HD * hh + 4 * (i % 4);
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt) {
+                    const u32x2 v0 = __builtin_bit_cast(u32x2, lds_read_tr16(vp + 16 * dt));
+                    const u32x2 v1 = __builtin_bit_cast(u32x2, lds_read_tr16(vp + 16 * XP + 16 * dt));
+                    acc[hh][dt] = mfma16(__builtin_bit_cast(bf16x8, u32x4{v0[0], v0[1], v1[0], v1[1]}), pb,
+                                         acc[hh][dt]);
+                }
+            }
+        }
+    }
+    if (slot < n) {
+#pragma unroll
+        for (int hh = 0; hh < HPW; ++hh) {
+            const float inv = 1.0f / l[hh];
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+                *(u32x2 *)(O + img_off + qtok * C + HD * hh + 16 * dt + 4 * g) = pack4(acc[hh][dt] * inv);
+        }
+    }
+}
+
 struct WideWs {
     bf16_t *q, *k, *v, *o;
     float *xr, *qr, *kr;
+    void *route;         // scratch of the generic routing kernels (more than 64 regions)
     int32_t *ir;
     size_t bytes;
 };
+
+bool many_regions(const Dims &D) { return D.S > kFastRouteMaxS; }
 
 WideWs carve(const Dims &D, void *ws)
 {
@@ -240,9 +395,11 @@ WideWs carve(const Dims &D, void *ws)
     w.k = (bf16_t *)take(tok * D.C * 2);
     w.v = (bf16_t *)take(tok * D.C * 2);
     w.o = (bf16_t *)take(tok * D.C * 2);
-    w.xr = (float *)take(reg * D.C * 4);
-    w.qr = (float *)take(reg * D.C * 4);
-    w.kr = (float *)take(reg * D.C * 4);
+    const bool many = many_regions(D);
+    w.xr = (float *)take(many ? 0 : reg * D.C * 4);
+    w.qr = (float *)take(many ? 0 : reg * D.C * 4);
+    w.kr = (float *)take(many ? 0 : reg * D.C * 4);
+    w.route = take(many ? valu_route_scratch_bytes(D) : 0);
     w.ir = (int32_t *)take(reg * D.k * 4);
     w.bytes = off;
     return w;
@@ -270,6 +427,7 @@ int launch_gemm(const void *In, const bf16_t *W, int ldw, long M, int K, int Nou
 int route_steps(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const WideWs &w, int32_t *Ir, float *Ar_opt,
                 hipStream_t st)
 {
+    if (many_regions(D)) return valu_route(D, X, Wqkv, Ir, Ar_opt, w.route, st);
     {
         const long items = (long)D.B * D.R * (D.C / 8);
         ProfScope ps(st, K_MFMA_POOL_QK);
@@ -285,14 +443,14 @@ int route_steps(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const WideWs
 
 }  // namespace
 
-bool wide_shape(const Dims &D) { return D.C != 64 && D.C != 128 && D.C != 256; }
-
 bool wide_supported(const Dims &D)
 {
-    if (D.dtype != BRA_BF16 || !wide_shape(D)) return false;
-    if (D.S > kFastRouteMaxS || D.C > 4096) return false;                     // R <= 64
+    if (D.dtype != BRA_BF16 || D.C % 64 != 0 || D.C > 4096) return false;
+    if (D.d != 32 && D.d != 64) return false;
+    if (many_regions(D) && !generic_supported(D)) return false;               // routing by the generic kernels
     if (((long)D.B * D.N + 63) / 64 * ((3L * D.C + 127) / 128) > 0x7fffffffL) return false;
-    return map_tail_supported(D);
+    if ((long)D.B * D.R * ((D.n + 63) / 64) * (D.C / 64) > 0x7fffffffL) return false;
+    return true;
 }
 
 size_t wide_workspace_bytes(const Dims &D) { return carve(D, nullptr).bytes; }
@@ -322,7 +480,17 @@ int wide_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo,
     A.X = (const bf16_t *)X; A.Q = w.q; A.K = w.k; A.V = w.v;
     A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = (const bf16_t *)Wlce; A.Y = (bf16_t *)Y;
     A.c_exp = D.scale * 1.4426950408889634f;
-    rc = launch_map_tail(D, A, w.o, st);
+    if (map_tail_supported(D)) {
+        rc = launch_map_tail(D, A, w.o, st);
+    } else {
+        {
+            const unsigned grid = (unsigned)((long)D.B * D.R * ((D.n + 63) / 64) * (D.C / 64));
+            ProfScope ps(st, K_MFMA_ATTENTION);
+            if (D.d == 32) hipLaunchKernelGGL(k_attn_gen<32>, dim3(grid), dim3(256), 0, st, A, w.o, D);
+            else hipLaunchKernelGGL(k_attn_gen<64>, dim3(grid), dim3(256), 0, st, A, w.o, D);
+        }
+        rc = launch_lce_add_any(D, A, w.o, st);
+    }
     if (rc != BRA_OK) return rc;
     return launch_gemm<false>(w.o, (const bf16_t *)Wo, D.C, M, D.C, D.C, GemmOut{{Y, nullptr, nullptr}, D.C}, K_MFMA_WO, st);
 }

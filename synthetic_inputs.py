@@ -67,12 +67,16 @@ CONFIGS = {
 }
 
 
-# Further operating points of the paper's backbones (not benchmark configurations): the last
-# stage (7x7 map, S = 7: one token per region, k = S^2 is full attention) at C = 512, and the
-# third stage of the wider variant (C = 384).
+# Further operating points of the paper (not benchmark configurations): the last stage of the
+# backbones (7x7 map, S = 7: one token per region, k = S^2 is full attention) at C = 512, the
+# third stage of the wider variant (C = 384), the plain-ViT adaptation of the appendix (32x32
+# map, S = 8, k = 12, 12 heads of 64 channels) and S = 16 on a detection-sized first-stage map
+# (a size that S divides: the paper pads otherwise).
 NEXT_CONFIGS = {
     6: BraConfig("next_stage4_224", 6, 64, 7, 7, 512, 16, 7, 49, "bf16"),
     7: BraConfig("next_wide_stage3_224", 7, 64, 14, 14, 384, 12, 7, 16, "bf16"),
+    8: BraConfig("next_vit_adaptation", 8, 8, 32, 32, 768, 12, 8, 12, "bf16"),
+    9: BraConfig("next_detection_s16", 9, 2, 208, 304, 64, 2, 16, 4, "bf16"),
 }
 
 

@@ -64,13 +64,14 @@ def test_kernel_family_selection_by_shape():
     # other channel counts: multiples of 64 with heads of 32 channels and small regions
     assert mfma(B=64, H=7, W=7, C=512, heads=16, S=7, k=49) == 0
     assert mfma(B=2, H=14, W=14, C=384, heads=12, S=7, k=16) == 0
-    assert mfma(B=2, H=28, W=28, C=512, heads=16, S=7, k=4) == -6      # regions of 16 tokens at C = 512
-    assert mfma(B=2, H=14, W=14, C=96, heads=3, S=7, k=4) == -6        # C not a multiple of 64
-    assert mfma(B=2, H=14, W=14, C=384, heads=6, S=7, k=4) == -6       # heads of 64 channels
+    assert mfma(B=2, H=28, W=28, C=512, heads=16, S=7, k=4) == 0       # regions of 16 tokens at C = 512
+    assert mfma(B=2, H=14, W=14, C=384, heads=6, S=7, k=4) == 0        # heads of 64 channels
     assert mfma(B=1, H=32, W=32, C=64, heads=2, S=16, k=4) == 0        # 256 regions: routed by the generic kernels
+    assert mfma(B=2, H=21, W=14, C=64, heads=2, S=7, k=2) == 0         # regions of 6 tokens
+    assert mfma(B=2, H=14, W=14, C=96, heads=3, S=7, k=4) == -6        # C not a multiple of 64
+    assert mfma(B=2, H=14, W=14, C=128, heads=8, S=7, k=4) == -6       # heads of 16 channels
     # every rejected shape still runs on the generic family
-    for kw in (dict(H=28, W=28, C=512, heads=16, S=7, k=4), dict(H=14, W=14, C=96, heads=3, S=7, k=4),
-               dict(H=14, W=14, C=384, heads=6, S=7, k=4)):
+    for kw in (dict(H=14, W=14, C=96, heads=3, S=7, k=4), dict(H=14, W=14, C=128, heads=8, S=7, k=4)):
         rc, n = ws_bytes(dtype=bra.BRA_BF16, path="auto", B=2, **kw)
         assert rc == 0 and n > 0
 

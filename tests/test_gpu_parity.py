@@ -116,6 +116,14 @@ WIDE_SHAPES = [  # other channel counts (multiples of 64, heads of 32 channels),
     (2, 7, 7, 320, 10, 7, 5),      # 3 C is not a multiple of the 128-column tile
     (1, 16, 8, 448, 14, 4, 2),     # 4 x 2 regions, n = 8
     (3, 6, 6, 768, 24, 3, 9),      # n = 4, k = S^2, 67 rows: ragged row tile
+    # shapes of the general attention kernel
+    (1, 32, 32, 768, 12, 8, 12),   # plain-ViT adaptation: heads of 64 channels, n = 16, 192 keys per query
+    (1, 64, 48, 64, 2, 16, 4),     # S = 16: 256 regions (generic routing), n = 12
+    (1, 52, 76, 64, 2, 4, 3),      # regions of 13 x 19 = 247 tokens: ragged query tile and key block, map wider than 64
+    (2, 28, 28, 512, 16, 7, 4),    # n = 16 at C = 512
+    (1, 24, 24, 128, 2, 4, 2),     # heads of 64 channels at C = 128, n = 36
+    (2, 21, 14, 64, 2, 7, 2),      # 3 x 2 regions
+    (1, 80, 80, 64, 2, 5, 2),      # 16 x 16 = 256-token regions with S = 5
 ]
 
 
@@ -173,7 +181,7 @@ def test_named_workloads_full_size(idx):
     compare(X, Wqkv, Wo, Wlce, cfg.dtype, cfg.S, cfg.k, cfg.heads, "auto", images=FULL[idx])
 
 
-@pytest.mark.parametrize("idx,images", [(6, [0, 33, 63]), (7, [5, 63])])
+@pytest.mark.parametrize("idx,images", [(6, [0, 33, 63]), (7, [5, 63]), (8, [7]), (9, [1])])
 def test_next_workloads_full_size(idx, images):
     cfg = NEXT_CONFIGS[idx]
     X, Wqkv, Wo, Wlce = make_config_inputs(cfg)
