@@ -69,6 +69,10 @@ int generic_forward(const Dims &D, const void *X, const void *Wqkv, const void *
 bool generic_supported(const Dims &D);
 
 size_t valu_route_scratch_bytes(const Dims &D);
+// Rows of A^r = Q^r (K^r)^T and their top-k from float32 Q^r, K^r [B, R, C] (any region count
+// that generic_supported accepts).
+int valu_affinity_topk(const Dims &D, const float *Qr, const float *Kr, int32_t *Ir, float *Ar_opt,
+                       hipStream_t st);
 int valu_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, float *Ar_opt,
                void *scratch, hipStream_t st);
 

@@ -410,6 +410,15 @@ size_t valu_route_scratch_bytes(const Dims &D)
     return 3 * align256((size_t)D.B * D.R * D.C * sizeof(float));
 }
 
+int valu_affinity_topk(const Dims &D, const float *Qr, const float *Kr, int32_t *Ir, float *Ar_opt,
+                       hipStream_t st)
+{
+    ProfScope ps(st, K_GEN_TOPK);
+    hipLaunchKernelGGL(gen_affinity_topk, dim3(D.B * D.R), dim3(kWave), D.C * sizeof(float), st, Qr, Kr, Ir,
+                       Ar_opt, D);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
 int valu_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, float *Ar_opt,
                void *scratch, hipStream_t st)
 {

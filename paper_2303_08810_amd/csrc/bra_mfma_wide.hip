@@ -20,28 +20,40 @@ using namespace mfma;
 
 namespace {
 
-// Thread = (image, region, 8-channel chunk); tokens added in row-major order of the region.
-__global__ void k_pool_wide(const bf16_t *__restrict__ X, float *__restrict__ Xr, Dims D)
+// SUB (1, 2, 4 or 8) consecutive lanes share one (image, region, 8-channel chunk): lane s adds
+// tokens s, s + SUB, .. of the region (row-major), then the partial sums are combined pairwise
+// in a fixed order.
+__global__ __launch_bounds__(256) void k_pool_wide(const bf16_t *__restrict__ X, float *__restrict__ Xr, Dims D,
+                                                   int SUB)
 {
     const int CH = D.C / 8;
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (long)D.B * D.R * CH) return;
-    const int cc = (int)(idx % CH), r = (int)((idx / CH) % D.R), b = (int)(idx / ((long)CH * D.R));
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    const long item = idx / SUB;
+    const int sub = (int)(idx % SUB);
+    const bool valid = item < (long)D.B * D.R * CH;
+    const long it = valid ? item : 0;
+    const int cc = (int)(it % CH), r = (int)((it / CH) % D.R), b = (int)(it / ((long)CH * D.R));
     const bf16_t *base = X + (((size_t)b * D.H + (r / D.S) * D.rh) * D.W + (r % D.S) * D.rw) * D.C + cc * 8;
+    const float rw_inv = 1.0f / (float)D.rw;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int y = 0; y < D.rh; ++y)
-        for (int x = 0; x < D.rw; ++x) {
-            const u32x4 v = *(const u32x4 *)(base + ((size_t)y * D.W + x) * D.C);
+    for (int slot = sub; slot < D.n; slot += SUB) {
+        const int y = fast_div(slot, rw_inv), x = slot - y * D.rw;
+        const u32x4 v = *(const u32x4 *)(base + ((size_t)y * D.W + x) * D.C);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                acc[2 * e] += bf16_lo(v[e]);
-                acc[2 * e + 1] += bf16_hi(v[e]);
-            }
+        for (int e = 0; e < 4; ++e) {
+            acc[2 * e] += bf16_lo(v[e]);
+            acc[2 * e + 1] += bf16_hi(v[e]);
         }
-    float *dst = Xr + ((size_t)b * D.R + r) * D.C + cc * 8;
-    const float inv = 1.0f / (float)D.n;
-    *(f32x4 *)dst = f32x4{acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
-    *(f32x4 *)(dst + 4) = f32x4{acc[4] * inv, acc[5] * inv, acc[6] * inv, acc[7] * inv};
+    }
+    for (int off = 1; off < SUB; off *= 2)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], off);
+    if (valid && sub == 0) {
+        float *dst = Xr + ((size_t)b * D.R + r) * D.C + cc * 8;
+        const float inv = 1.0f / (float)D.n;
+        *(f32x4 *)dst = f32x4{acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
+        *(f32x4 *)(dst + 4) = f32x4{acc[4] * inv, acc[5] * inv, acc[6] * inv, acc[7] * inv};
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -377,7 +389,6 @@ __global__ __launch_bounds__(256) void k_attn_gen(AttnArgs A, bf16_t *__restrict
 struct WideWs {
     bf16_t *q, *k, *v, *o;
     float *xr, *qr, *kr;
-    void *route;         // scratch of the generic routing kernels (more than 64 regions)
     int32_t *ir;
     size_t bytes;
 };
@@ -395,11 +406,9 @@ WideWs carve(const Dims &D, void *ws)
     w.k = (bf16_t *)take(tok * D.C * 2);
     w.v = (bf16_t *)take(tok * D.C * 2);
     w.o = (bf16_t *)take(tok * D.C * 2);
-    const bool many = many_regions(D);
-    w.xr = (float *)take(many ? 0 : reg * D.C * 4);
-    w.qr = (float *)take(many ? 0 : reg * D.C * 4);
-    w.kr = (float *)take(many ? 0 : reg * D.C * 4);
-    w.route = take(many ? valu_route_scratch_bytes(D) : 0);
+    w.xr = (float *)take(reg * D.C * 4);
+    w.qr = (float *)take(reg * D.C * 4);
+    w.kr = (float *)take(reg * D.C * 4);
     w.ir = (int32_t *)take(reg * D.k * 4);
     w.bytes = off;
     return w;
@@ -427,15 +436,17 @@ int launch_gemm(const void *In, const bf16_t *W, int ldw, long M, int K, int Nou
 int route_steps(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const WideWs &w, int32_t *Ir, float *Ar_opt,
                 hipStream_t st)
 {
-    if (many_regions(D)) return valu_route(D, X, Wqkv, Ir, Ar_opt, w.route, st);
     {
-        const long items = (long)D.B * D.R * (D.C / 8);
+        int sub = 1;                                           // lanes per (region, chunk)
+        while (sub < 8 && 2 * sub <= D.n) sub *= 2;
+        const long items = (long)D.B * D.R * (D.C / 8) * sub;
         ProfScope ps(st, K_MFMA_POOL_QK);
-        hipLaunchKernelGGL(k_pool_wide, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, X, w.xr, D);
+        hipLaunchKernelGGL(k_pool_wide, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, X, w.xr, D, sub);
     }
     const int rc = launch_gemm<true>(w.xr, Wqkv, 3 * D.C, (long)D.B * D.R, D.C, 2 * D.C, GemmOut{{w.qr, w.kr, nullptr}, D.C},
                                      K_MFMA_ROUTE_ROWS, st);
     if (rc != BRA_OK) return rc;
+    if (many_regions(D)) return valu_affinity_topk(D, w.qr, w.kr, Ir, Ar_opt, st);   // more than one entry per lane
     ProfScope ps(st, K_MFMA_ROUTE_ROWS);
     hipLaunchKernelGGL(k_route_qk, dim3(D.B * ((D.R + 15) / 16)), dim3(256), 0, st, w.qr, w.kr, Ir, Ar_opt, D);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
@@ -447,7 +458,7 @@ bool wide_supported(const Dims &D)
 {
     if (D.dtype != BRA_BF16 || D.C % 64 != 0 || D.C > 4096) return false;
     if (D.d != 32 && D.d != 64) return false;
-    if (many_regions(D) && !generic_supported(D)) return false;               // routing by the generic kernels
+    if (many_regions(D) && !generic_supported(D)) return false;               // top-k by the generic kernel
     if (((long)D.B * D.N + 63) / 64 * ((3L * D.C + 127) / 128) > 0x7fffffffL) return false;
     if ((long)D.B * D.R * ((D.n + 63) / 64) * (D.C / 64) > 0x7fffffffL) return false;
     return true;
