@@ -155,8 +155,95 @@ __global__ __launch_bounds__(kWave) void gen_affinity_topk(const float *__restri
     }
 }
 
+// Routed attention (Eq. 6, Eq. 1) for heads of at most 64 channels, with the keys staged in
+// LDS; QKV is [B, N, 3C] float32 (q | k | v per token).
+// Workgroup (b, region, head) takes its queries 16 at a time (4 per wavefront) and, per pass,
+// the routed keys 64 at a time: K and V rows of the block are copied into LDS with
+// consecutive lanes on consecutive channels, then lane u scores key u against each of the
+// wavefront's queries (Eq. 1, scaled), the online softmax state of a query lives in
+// registers, and lane c accumulates channel c of P V.
+constexpr int kAttnLdsD = 64;
+
+__global__ __launch_bounds__(256) void gen_attention_lds(const float *__restrict__ QKV,
+                                                         const int32_t *__restrict__ Ir,
+                                                         float *__restrict__ O, Dims D, float scale)
+{
+    __shared__ float Ks[64][kAttnLdsD + 1];
+    __shared__ float Vs[64][kAttnLdsD + 1];
+    __shared__ float qs[16][kAttnLdsD];
+    __shared__ float sc[16][64];
+    const int hd = blockIdx.x % D.heads;
+    const int reg = (blockIdx.x / D.heads) % D.R;
+    const int b = blockIdx.x / (D.heads * D.R);
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int C3 = 3 * D.C, d = D.d;
+    const float *img = QKV + (size_t)b * D.N * C3;
+    const int32_t *irp = Ir + ((size_t)b * D.R + reg) * D.k;
+    const int y0 = (reg / D.S) * D.rh, x0 = (reg % D.S) * D.rw;
+
+    for (int s0 = 0; s0 < D.n; s0 += 16) {
+        // the 16 queries of this pass (past the end: the last one again; never stored)
+        for (int e = tid; e < 16 * d; e += 256) {
+            const int s = min(s0 + e / d, D.n - 1);
+            const int qtok = (y0 + s / D.rw) * D.W + x0 + s % D.rw;
+            qs[e / d][e % d] = img[(size_t)qtok * C3 + hd * d + e % d];
+        }
+        float m[4], l[4], acc[4];
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) {
+            m[qq] = -INFINITY;
+            l[qq] = 0.f;
+            acc[qq] = 0.f;
+        }
+        for (int k0 = 0; k0 < D.kn; k0 += 64) {
+            const int cn = min(64, D.kn - k0);
+            __syncthreads();               // queries staged; the previous block has been read
+            for (int e = tid; e < 64 * d; e += 256) {
+                const int u = e / d, c = e % d;
+                const int key = min(k0 + u, D.kn - 1);
+                const int j = irp[key / D.n], slot = key % D.n;
+                const int tok = ((j / D.S) * D.rh + slot / D.rw) * D.W + (j % D.S) * D.rw + slot % D.rw;
+                const float *row = img + (size_t)tok * C3 + hd * d + c;
+                Ks[u][c] = row[D.C];
+                Vs[u][c] = row[2 * D.C];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                const float *q = qs[4 * wave + qq];
+                float a = 0.f;
+                for (int c = 0; c < d; ++c) a = fmaf(q[c], Ks[lane][c], a);
+                a = lane < cn ? a * scale : -INFINITY;
+                float mx = a;
+                for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+                const float m_new = fmaxf(m[qq], mx);
+                const float corr = (m[qq] == -INFINITY) ? 0.f : expf(m[qq] - m_new);
+                const float pv = lane < cn ? expf(a - m_new) : 0.f;
+                float ls = pv;
+                for (int off = 32; off >= 1; off >>= 1) ls += __shfl_xor(ls, off, kWave);
+                l[qq] = l[qq] * corr + ls;
+                m[qq] = m_new;
+                sc[4 * wave + qq][lane] = pv;      // read back by this wavefront only
+                float o = acc[qq] * corr;
+                if (lane < d)
+                    for (int u = 0; u < cn; ++u) o = fmaf(sc[4 * wave + qq][u], Vs[u][lane], o);
+                acc[qq] = o;
+            }
+        }
+        __syncthreads();                   // the next pass replaces the queries
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) {
+            const int s = s0 + 4 * wave + qq;
+            if (s < D.n && lane < d) {
+                const int qtok = (y0 + s / D.rw) * D.W + x0 + s % D.rw;
+                O[((size_t)b * D.N + qtok) * D.C + hd * d + lane] = acc[qq] / l[qq];
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
-// Routed attention, one workgroup (4 wavefronts) per (b, region i, head).  Each
+// Routed attention for wider heads, one workgroup (4 wavefronts) per (b, region i, head).  Each
 // wavefront owns one query at a time and runs an online softmax over the k n keys
 // of regions Ir[b, i, :] in chunks; keys and values are read in place from the
 // projected map by index.  QKV is [B, N, 3C] float32 (q | k | v per token).
@@ -342,8 +429,12 @@ int forward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *Wl
     }
     {
         ProfScope ps(st, K_GEN_ATTENTION);
-        hipLaunchKernelGGL(gen_attention, dim3(D.B * D.R * D.heads), dim3(256), D.k * sizeof(int), st,
-                           w.qkv, Ir, w.o, D, D.scale);
+        if (D.d <= kAttnLdsD)
+            hipLaunchKernelGGL(gen_attention_lds, dim3(D.B * D.R * D.heads), dim3(256), 0, st, w.qkv, Ir, w.o, D,
+                               D.scale);
+        else
+            hipLaunchKernelGGL(gen_attention, dim3(D.B * D.R * D.heads), dim3(256), D.k * sizeof(int), st,
+                               w.qkv, Ir, w.o, D, D.scale);
     }
     const size_t total = (size_t)M * D.C;
     {
