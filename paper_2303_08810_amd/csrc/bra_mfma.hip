@@ -330,39 +330,41 @@ __global__ __launch_bounds__(256) void k_route_u(const float *__restrict__ Xr, c
 // in float32, lane j holding entry j, and ranks them.
 constexpr int kRouteRS = 65;   // regions (float4 slots) per 4-channel group of the K^r tile in LDS
 
-// Rows 4 w .. 4 w + 3 (of the 16 query regions of row tile myrt) of A^r = Q^r (K^r)^T in
+// Rows NR w .. NR w + NR - 1 (of the 4 NR query regions of row tile myrt) of A^r = Q^r (K^r)^T in
 // float32 from the LDS tiles Kt [C / 4][kRouteRS][4] (K^r: channel group, region, channel in
-// the group) and Qs [16][C + 4], lane j
+// the group) and Qs [4 NR][C + 4], lane j
 // holding entry j; then their top-k (Eq. 5) and, if asked for, the rows themselves.
-template <int C>
+template <int C, int NR = 4>
 __device__ __forceinline__ void route_rows_from_lds(const float *Kt, const float *Qs, int b, int myrt,
                                                     const Dims &D, int32_t *__restrict__ Ir,
                                                     float *__restrict__ Ar)
 {
     constexpr int QS = C + 4;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    float a[4] = {0.f, 0.f, 0.f, 0.f};
-    const float *qrow = Qs + 4 * wave * QS;
+    float a[NR];
+#pragma unroll
+    for (int rr = 0; rr < NR; ++rr) a[rr] = 0.f;
+    const float *qrow = Qs + NR * wave * QS;
 #pragma unroll 4
     for (int c = 0; c < C; c += 4) {
         const f32x4 kv = *(const f32x4 *)(Kt + ((c / 4) * kRouteRS + lane) * 4);
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
+        for (int rr = 0; rr < NR; ++rr) {
             const f32x4 q4 = *(const f32x4 *)(qrow + rr * QS + c);
 #pragma unroll
             for (int e = 0; e < 4; ++e) a[rr] = fmaf(q4[e], kv[e], a[rr]);
         }
     }
-    const int r0 = 16 * myrt + 4 * wave;
+    const int r0 = 4 * NR * myrt + NR * wave;
     if (r0 >= D.R) return;
-    const int nrows = min(4, D.R - r0);
+    const int nrows = min(NR, D.R - r0);
     const size_t row0 = (size_t)b * D.R + r0;
     if (Ar && lane < D.R) {
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr)
+        for (int rr = 0; rr < NR; ++rr)
             if (rr < nrows) Ar[(row0 + rr) * D.R + lane] = a[rr];
     }
-    wave_topk_rows<4>(a, nrows, lane, D.R, D.k, Ir + row0 * D.k);
+    wave_topk_rows<NR>(a, nrows, lane, D.R, D.k, Ir + row0 * D.k);
 }
 
 template <int C>
@@ -476,25 +478,25 @@ __global__ __launch_bounds__(256) void k_route(const float *__restrict__ Xr,
 // Q^r and K^r are the region means of Q and K (Sec. 3.2), i.e. the sum of a region's
 // rh x (rw / group) partial sums in a fixed order, divided by n.  Workgroup (b, rt) as in
 // k_route; no matrix products are left to do here.
-template <int C>
+template <int C, int NR>
 __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, int32_t *__restrict__ Ir,
                                                  float *__restrict__ Ar, Dims D, int group_log2)
 {
-    constexpr int QS = C + 4, C4 = C / 4;
+    constexpr int QS = C + 4, C4 = C / 4, QR = 4 * NR;     // query regions of a workgroup
     extern __shared__ __attribute__((aligned(16))) char smem[];
     float *Kt = (float *)smem;                    // [C / 4][kRouteRS][4]
-    float *Qs = Kt + C * kRouteRS;                // [16][QS]
-    const int groups = (D.R + 15) / 16;
+    float *Qs = Kt + C * kRouteRS;                // [QR][QS]
+    const int groups = (D.R + QR - 1) / QR;
     const int wid = swizzled_block();          // the workgroups of an image share an XCD (and its L2)
     if (wid >= D.B * groups) return;
     const int b = wid / groups, myrt = wid % groups;
     const int pw = D.W >> group_log2, pc = D.rw >> group_log2;      // partial sums per image row / region row
     const float inv_n = 1.0f / (float)D.n;
-    // Work items (region, 4 channels): all of K^r, then the 16 query rows of Q^r.  A thread
+    // Work items (region, 4 channels): all of K^r, then the QR query rows of Q^r.  A thread
     // takes its NI items at once so that their loads are in flight together; the partial sums of
     // an item are added in the order (row of the region, position in the row).
-    constexpr int NI = (80 * C4 + 255) / 256;       // every item of a workgroup in one round (R <= 64)
-    const int nk = D.R * C4, total = nk + 16 * C4;
+    constexpr int NI = ((64 + QR) * C4 + 255) / 256;       // every item of a workgroup in one round (R <= 64)
+    const int nk = D.R * C4, total = nk + QR * C4;
     for (int i0 = threadIdx.x; i0 < total; i0 += 256 * NI) {
         const float *src[NI];
         f32x4 acc[NI];
@@ -503,7 +505,7 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
             const int idx = min(i0 + 256 * u, total - 1);
             const bool isq = idx >= nk;
             const int row = (isq ? idx - nk : idx) / C4, c4 = (isq ? idx - nk : idx) % C4;
-            const int r = isq ? min(16 * myrt + row, D.R - 1) : row;     // rows past R repeat the last region; never used
+            const int r = isq ? min(QR * myrt + row, D.R - 1) : row;     // rows past R repeat the last region; never used
             const int ry = r / D.S, rx = r % D.S;
             src[u] = P + (((size_t)b * D.H + ry * D.rh) * pw + rx * pc) * 2 * C + (isq ? 0 : C) + 4 * c4;
             acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -531,7 +533,7 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
         }
     }
     __syncthreads();
-    route_rows_from_lds<C>(Kt, Qs, b, myrt, D, Ir, Ar);
+    route_rows_from_lds<C, NR>(Kt, Qs, b, myrt, D, Ir, Ar);
 }
 
 // ---------------------------------------------------------------------------
@@ -1230,11 +1232,23 @@ int launch_route(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, hip
 template <int C>
 int launch_route_p(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, hipStream_t st)
 {
-    static bool opted = false;
-    if (!lds_opt_in(k_route_p<C>, opted)) return BRA_ERR_LAUNCH;
+    // 8 query regions per workgroup (2 per wavefront) where two workgroups fit a compute unit
+    // (the K^r tile takes C x 260 bytes of LDS): twice the workgroups, half the serial affinity /
+    // top-k work in each.  Measured: C = 128 12.6 -> 10.8 us, C = 256 (one per unit) 17.3 -> 22.1 us.
+    static const int forced = getenv("BRA_ROUTE_ROWS") ? atoi(getenv("BRA_ROUTE_ROWS")) : 0;   // benchmarking aid
+    const bool rows8 = forced ? forced == 8 : 2 * RouteSmem<C>::kq_bytes <= (size_t)kMaxLds;
     ProfScope ps(st, K_MFMA_ROUTE_ROWS);
-    hipLaunchKernelGGL(k_route_p<C>, dim3((D.B * ((D.R + 15) / 16) + 7) / 8 * 8), dim3(256), RouteSmem<C>::kq_bytes, st,
-                       w.p, Ir, Ar_opt, D, pool_group_log2(D));
+    if (rows8) {
+        static bool opted = false;
+        if (!lds_opt_in(k_route_p<C, 2>, opted)) return BRA_ERR_LAUNCH;
+        hipLaunchKernelGGL((k_route_p<C, 2>), dim3((D.B * ((D.R + 7) / 8) + 7) / 8 * 8), dim3(256),
+                           RouteSmem<C>::kq_bytes, st, w.p, Ir, Ar_opt, D, pool_group_log2(D));
+    } else {
+        static bool opted = false;
+        if (!lds_opt_in(k_route_p<C, 4>, opted)) return BRA_ERR_LAUNCH;
+        hipLaunchKernelGGL((k_route_p<C, 4>), dim3((D.B * ((D.R + 15) / 16) + 7) / 8 * 8), dim3(256),
+                           RouteSmem<C>::kq_bytes, st, w.p, Ir, Ar_opt, D, pool_group_log2(D));
+    }
     return BRA_OK;
 }
 
