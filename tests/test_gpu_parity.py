@@ -143,6 +143,34 @@ def test_mfma_wide_forced_routing():
     check_output(Y, ref["Y"], "bf16")
 
 
+def random_shapes(count, seed):
+    """Seeded draw of valid bf16 shapes for the matrix-core family: region grids 1..16, region
+    sides 1..19 (not only powers of two), heads of 32 or 64 channels, C a multiple of 64."""
+    import random
+
+    rng = random.Random(seed)
+    out = []
+    while len(out) < count:
+        S = rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 16])
+        rh, rw = rng.choice([1, 2, 3, 4, 5, 8, 13, 16]), rng.choice([1, 2, 3, 4, 6, 8, 16, 19])
+        d, heads = rng.choice([32, 32, 32, 64]), rng.choice([1, 2, 3, 4, 6, 8, 12])
+        C, R = d * heads, S * S
+        k = rng.choice([1, 2, 3, 4, min(R, 12), R])
+        if C % 64 or C > 768 or k > R:
+            continue
+        H, W, B = S * rh, S * rw, rng.choice([1, 2, 3])
+        if H * W * C > 600000 or H * W * k * rh * rw * C > 3e8:
+            continue
+        out.append((B, H, W, C, heads, S, k))
+    return out
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,S,k", random_shapes(24, 20230308))
+def test_mfma_random_shapes(B, H, W, C, heads, S, k):
+    X, Wqkv, Wo, Wlce = make_inputs(B, H, W, C, seed=9000 + H * 31 + W + C + k, dtype="bf16")
+    compare(X, Wqkv, Wo, Wlce, "bf16", S, k, heads, "mfma")
+
+
 def test_mfma_scale_and_forced_routing():
     X, Wqkv, Wo, Wlce = make_inputs(2, 16, 16, 64, seed=77, dtype="bf16")
     compare(X, Wqkv, Wo, Wlce, "bf16", 2, 2, 2, "mfma", scale=0.05)
