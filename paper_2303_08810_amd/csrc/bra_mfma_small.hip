@@ -305,7 +305,8 @@ __global__ __launch_bounds__(256) void k_attn_small(AttnArgs A, bf16_t *__restri
 // workgroup (image, head, part) copies the head's 32 channels of all N tokens once and
 // its wavefronts walk over the regions of the part, finding the rows of their keys by
 // index (Eq. 6 as row addresses of LDS reads).  Ks, Vs: [N][kMapPitch] bf16.
-constexpr int kMapPitch = 48;    // 32 channels + 16: rows of 96 bytes
+constexpr int kMapPitch = 40;    // 32 channels + 8: rows of 80 bytes (random-row access: the pitch matters little)
+constexpr int kMapLcePitch = 32; // floats per token of the LCE tile
 constexpr int kMapWaves = 8, kMapThreads = kMapWaves * kWave;   // the walk over the regions is latency-bound: many wavefronts
 
 struct MapWork {
@@ -316,6 +317,7 @@ struct MapWork {
     int *first;      // [R]: first token of a region
     int slot_off;    // this lane's token within a routed region, the same way: key l is token l % n
     char *wave_mem;  // 512 bytes of this wavefront's own
+    float *Ls;       // [N][kMapLcePitch]: LCE of the head's channels (variants that add it)
 };
 
 // Stages the head's K / V slice and the image's routing index; false: no work.
@@ -329,6 +331,7 @@ __device__ __forceinline__ bool map_stage(const AttnArgs &A, const Dims &D, int 
     w.rows = (int *)(w.Qs + (size_t)D.N * kMapPitch);
     w.first = w.rows + D.R * D.k;
     w.wave_mem = (char *)(w.rows + (D.R * D.k + D.R + 3) / 4 * 4) + (threadIdx.x / kWave) * 512;   // 16-byte aligned
+    w.Ls = (float *)((char *)(w.rows + (D.R * D.k + D.R + 3) / 4 * 4) + kMapWaves * 512);
     const int wid = swizzled_block();       // the heads of an image share the memory lines of its K / V rows
     if (wid >= A.total) return false;
     const int part = wid % split;
@@ -378,15 +381,66 @@ __device__ __forceinline__ bool map_stage(const AttnArgs &A, const Dims &D, int 
     return true;
 }
 
+// LCE (Eq. 7) of the head's 32 channels over the whole image, from the V slice in LDS into
+// w.Ls (float32): thread = (channel pair, group); a group takes (image row, 4-token segment)
+// items, the 2 x 25 weights of the pair stay in registers.  Tokens outside the image are zero.
+__device__ __forceinline__ void map_lce(const AttnArgs &A, const Dims &D, const MapWork &w)
+{
+    const int cpair = threadIdx.x % 16, grp = threadIdx.x / 16;
+    unsigned wl[25];        // [W(c, 0..24) | W(c + 1, 0..24)] as 25 packed pairs
+#pragma unroll
+    for (int e = 0; e < 25; ++e) wl[e] = *(const unsigned *)(A.Wlce + (size_t)(32 * w.h + 2 * cpair) * 25 + 2 * e);
+    auto tap = [&](int ch, int t) {
+        const int e = 25 * ch + t;
+        return (e & 1) ? bf16_hi(wl[e / 2]) : bf16_lo(wl[e / 2]);
+    };
+    const int segs = (D.W + 3) / 4;
+    for (int item = grp; item < D.H * segs; item += kMapThreads / 16) {
+        const int y = item / segs, x0 = (item % segs) * 4;
+        float a0[4] = {0.f, 0.f, 0.f, 0.f}, a1[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ky = 0; ky < 5; ++ky) {
+            const int yy = y + ky - 2;
+            const bool row_ok = yy >= 0 && yy < D.H;
+            float v0[8], v1[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const int xx = x0 + x - 2;
+                const bool ok = row_ok && xx >= 0 && xx < D.W;
+                const unsigned u = *(const unsigned *)(w.Vs + (ok ? yy * D.W + xx : 0) * kMapPitch + 2 * cpair);
+                v0[x] = ok ? bf16_lo(u) : 0.f;
+                v1[x] = ok ? bf16_hi(u) : 0.f;
+            }
+#pragma unroll
+            for (int kx = 0; kx < 5; ++kx) {
+                const float w0 = tap(0, ky * 5 + kx), w1 = tap(1, ky * 5 + kx);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    a0[x] = fmaf(w0, v0[x + kx], a0[x]);
+                    a1[x] = fmaf(w1, v1[x + kx], a1[x]);
+                }
+            }
+        }
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+            if (x0 + x < D.W) *(f32x2 *)(w.Ls + (y * D.W + x0 + x) * kMapLcePitch + 2 * cpair) = f32x2{a0[x], a1[x]};
+    }
+    __syncthreads();
+}
+
 // Regions of 8 tokens: the queries take 8 of the 16 query columns of 16x16x32 tiles;
 // lane l puts the row of key l into a wavefront-private table, the K operand rows and
 // the transposing V reads take their addresses from it.
+// LCE: the LCE of the head's channels is computed from the V slice first and added to the
+// attention output (no separate LCE pass over memory).
+template <bool LCE>
 __global__ __launch_bounds__(kMapThreads) void k_attn_map(AttnArgs A, bf16_t *__restrict__ O, Dims D, int log2n,
                                                   int split)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     MapWork w;
     if (!map_stage(A, D, split, smem, w)) return;
+    if (LCE) map_lce(A, D, w);
     const bf16_t *Ks = w.Ks, *Vs = w.Vs;
     int *tokw = (int *)w.wave_mem;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
@@ -431,7 +485,11 @@ __global__ __launch_bounds__(kMapThreads) void k_attn_map(AttnArgs A, bf16_t *__
         if (i < n) {
             bf16_t *orow = O + w.img_off + (size_t)(tok0 + q_in) * C + 32 * h + 4 * g;
 #pragma unroll
-            for (int dt = 0; dt < 2; ++dt) *(u32x2 *)(orow + 16 * dt) = pack4(st.acc[0][dt] * inv);
+            for (int dt = 0; dt < 2; ++dt) {
+                f32x4 o = st.acc[0][dt] * inv;
+                if (LCE) o += *(const f32x4 *)(w.Ls + (tok0 + q_in) * kMapLcePitch + 16 * dt + 4 * g);
+                *(u32x2 *)(orow + 16 * dt) = pack4(o);
+            }
         }
     }
 }
@@ -446,12 +504,14 @@ __global__ __launch_bounds__(kMapThreads) void k_attn_map(AttnArgs A, bf16_t *__
 // O^T = V^T P^T on 16x16x32 tiles (query columns >= 4 see copies).  A product with an
 // all-ones operand delivers the softmax denominators (of the same bf16-rounded P) to
 // every lane of a query column.
+template <bool LCE>
 __global__ __launch_bounds__(kMapThreads) void k_attn_map4(AttnArgs A, bf16_t *__restrict__ O, Dims D, int log2n,
                                                    int split)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     MapWork w;
     if (!map_stage(A, D, split, smem, w)) return;
+    if (LCE) map_lce(A, D, w);
     const bf16_t *Ks = w.Ks, *Vs = w.Vs;
     bf16_t *Pw = (bf16_t *)w.wave_mem;          // [64 keys][4 queries]
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
@@ -466,7 +526,8 @@ __global__ __launch_bounds__(kMapThreads) void k_attn_map4(AttnArgs A, bf16_t *_
         return qy * D.W + qs - qy * D.rw;
     };
     const bf16_t *qbase = w.Qs + in_region(lane % 4) * kMapPitch;               // row of the score operand
-    bf16_t *obase = O + w.img_off + in_region(i) * C + 32 * h + 4 * g;          // column of the output tiles
+    const int qo_in = in_region(i);                                             // column of the output tiles
+    bf16_t *obase = O + w.img_off + qo_in * C + 32 * h + 4 * g;
     const u32x4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
     const bool ragged = (kn % 64) != 0;
     for (int reg = w.r_begin + wave; reg < w.r_end; reg += kMapWaves) {
@@ -540,7 +601,11 @@ __global__ __launch_bounds__(kMapThreads) void k_attn_map4(AttnArgs A, bf16_t *_
         if (i < n) {
             bf16_t *orow = obase + (size_t)tok0 * C;
 #pragma unroll
-            for (int dt = 0; dt < 2; ++dt) *(u32x2 *)(orow + 16 * dt) = pack4(acc[dt] * inv);
+            for (int dt = 0; dt < 2; ++dt) {
+                f32x4 o = acc[dt] * inv;
+                if (LCE) o += *(const f32x4 *)(w.Ls + (tok0 + qo_in) * kMapLcePitch + 16 * dt + 4 * g);
+                *(u32x2 *)(orow + 16 * dt) = pack4(o);
+            }
         }
     }
 }
@@ -653,9 +718,18 @@ static bool one_kernel(const Dims &D)
 
 static size_t lce_add_smem(const Dims &D) { return (size_t)(tile_rows(D) + 4) * (tile_cols(D) + 4) * kLcePitch * 2; }
 
-static size_t map_smem(const Dims &D)
+static size_t map_smem(const Dims &D, bool lce = false)
 {
-    return (size_t)3 * D.N * kMapPitch * 2 + (size_t)((D.R * D.k + D.R + 3) / 4 * 4) * 4 + kMapWaves * 512;
+    return (size_t)3 * D.N * kMapPitch * 2 + (size_t)((D.R * D.k + D.R + 3) / 4 * 4) * 4 + kMapWaves * 512 +
+           (lce ? (size_t)D.N * kMapLcePitch * 4 : 0);
+}
+
+// The LCE rides along in the attention kernel when its float32 tile fits and does not cost
+// the second workgroup of a compute unit.
+static bool map_adds_lce(const Dims &D)
+{
+    const size_t with = map_smem(D, true), half = (size_t)kMaxLds / 2;
+    return with <= (size_t)kMaxLds && (with <= half || map_smem(D) > half);
 }
 
 // Image-resident attention when a head's K and V of one image fit in LDS.
@@ -710,17 +784,23 @@ static bool opt_in(K kernel, bool &done)
 // Image-resident attention of all regions into O.
 static int launch_map(const Dims &D, AttnArgs A, bf16_t *O, int log2n, hipStream_t st)
 {
-    static bool opted = false, opted4 = false;
-    if (!opt_in(k_attn_map, opted) || !opt_in(k_attn_map4, opted4)) return BRA_ERR_LAUNCH;
+    static bool opted[4] = {false, false, false, false};
+    if (!opt_in(k_attn_map<false>, opted[0]) || !opt_in(k_attn_map4<false>, opted[1]) ||
+        !opt_in(k_attn_map<true>, opted[2]) || !opt_in(k_attn_map4<true>, opted[3]))
+        return BRA_ERR_LAUNCH;
     const int split = map_split(D);
+    const bool lce = map_adds_lce(D);
     ProfScope ps(st, K_MFMA_ATTN_SMALL);
     A.total = D.B * (D.C / 32) * split;
     const dim3 grid_map((A.total + 7) / 8 * 8);
-    const size_t smem = map_smem(D);
-    if (D.n <= 4)
-        hipLaunchKernelGGL(k_attn_map4, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
-    else
-        hipLaunchKernelGGL(k_attn_map, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
+    const size_t smem = map_smem(D, lce);
+    if (D.n <= 4) {
+        if (lce) hipLaunchKernelGGL(k_attn_map4<true>, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
+        else hipLaunchKernelGGL(k_attn_map4<false>, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
+    } else {
+        if (lce) hipLaunchKernelGGL(k_attn_map<true>, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
+        else hipLaunchKernelGGL(k_attn_map<false>, grid_map, dim3(kMapThreads), smem, st, A, O, D, log2n, split);
+    }
     return BRA_OK;
 }
 
@@ -754,7 +834,7 @@ static int launch_small_c(const Dims &D, const AttnArgs &A0, bf16_t *O, hipStrea
     }
     if (map_attention(D)) {
         const int rc = launch_map(D, A, O, log2n, st);
-        if (rc != BRA_OK) return rc;
+        if (rc != BRA_OK || map_adds_lce(D)) return rc;
     } else {
         static bool opted = false;
         if (!opt_in(k_attn_small<C>, opted)) return BRA_ERR_LAUNCH;
@@ -784,7 +864,7 @@ int launch_map_tail(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st)
     int log2n = 0;
     while ((1 << log2n) < D.n) ++log2n;
     const int rc = launch_map(D, A, O, log2n, st);
-    if (rc != BRA_OK) return rc;
+    if (rc != BRA_OK || map_adds_lce(D)) return rc;
     return launch_lce_add(D, A, O, st);
 }
 
