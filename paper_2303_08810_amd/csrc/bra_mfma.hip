@@ -12,10 +12,13 @@
 // projection kernel also writes partial sums of its float32 Q / K accumulators, and the
 // routing kernel adds them up per region (used when a region has few of them).
 //
-// Forward pipelines:
-//   fused  : k_pool -> k_route -> k_fused            (k = 1, 64-token regions, C = 64:
+// For k = 1 neither Q^r nor K^r is formed: the pooling kernel leaves u_r = Wk (Wq^T mean(X^r))
+// per region, and row r of A^r is the means of the image times u_r.
+//
+// Forward pipelines (C = 64, 128, 256; every other shape: bra_mfma_wide.hip):
+//   fused  : k_pool -> k_fused                       (k = 1, 64-token regions, C = 64:
 //            projections recomputed per workgroup from X, where recomputing K and V
-//            costs less than storing them)
+//            costs less than storing them; the workgroup finds its routed region itself)
 //   staged : k_pool -> k_route -> k_qkv -> k_attn_big                 (regions of 64 n tokens)
 //            k_qkv -> k_route_p -> small-region kernels (bra_mfma_small.hip)
 #include "bra_mfma_dev.h"

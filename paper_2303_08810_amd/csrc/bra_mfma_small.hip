@@ -9,8 +9,10 @@
 // For regions of 16 tokens the same workgroup then adds the LCE of its tokens (Eq. 7; 5x5
 // depth-wise correlation of V over the region plus a 2-token halo, staged in LDS) and
 // applies W^o (Eq. 2), so the attention output never travels through memory (k_small).
-// Smaller regions use separate kernels: k_attn_small (attention output to memory),
-// k_lce_add (adds the LCE in place), then the projection kernel with W^o.
+// Smaller regions use separate kernels: on small maps the image-resident attention
+// k_attn_map / k_attn_map4 (a head's Q, K, V of a whole image in LDS, the LCE added from the
+// same V slice), else k_attn_small (attention output to memory) and k_lce_add (adds the LCE
+// in place); then the projection kernel with W^o.
 #include "bra_mfma_dev.h"
 
 namespace bra {
