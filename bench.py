@@ -91,13 +91,13 @@ def kernel_model(name, cfg):
     return table[name]
 
 
-def device_inputs(cfg, sets):
+def device_inputs(cfg, sets, smooth=False):
     import numpy as np
     import torch
 
     from synthetic_inputs import bf16_bits, make_config_inputs
 
-    X, Wqkv, Wo, Wlce = make_config_inputs(cfg)
+    X, Wqkv, Wo, Wlce = make_config_inputs(cfg, smooth=smooth)
 
     def dev(a):
         if cfg.dtype == "bf16":
@@ -155,6 +155,61 @@ def time_config(cfg, steps, warmup, profile=True):
                 host=host, sets=sets)
 
 
+def time_variants(cfg, steps, warmup):
+    """Further timings of the same workload, for context (none of them is `value`): repeats of
+    the K-step measurement, spatially smooth inputs (concentrated routing), a single input
+    set (everything stays in the last-level cache) and replay of a HIP graph that holds one
+    pass over the rotating input sets."""
+    import statistics
+
+    import torch
+
+    import paper_2303_08810_amd as bra
+
+    def measure(sets, smooth=False, graph=False):
+        host, Xs, Ys, Wqkv, Wo, Wlce = device_inputs(cfg, sets, smooth=smooth)
+        shape = bra.make_shape(cfg.B, cfg.H, cfg.W, cfg.C, cfg.heads, cfg.S, cfg.k, Xs[0].dtype)
+        ws = bra.alloc_workspace(shape, Xs[0].device)
+
+        def step(i):
+            bra.bra_forward(Xs[i % sets], Wqkv, Wo, Wlce, cfg.S, cfg.k, cfg.heads, ws=ws, out=Ys[i % sets])
+
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        launch, per_launch = step, 1
+        if graph:
+            side = torch.cuda.Stream()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(g, stream=side):
+                    for i in range(sets):
+                        step(i)
+            torch.cuda.synchronize()
+            launch, per_launch = (lambda i: g.replay()), sets
+        times = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n = max(1, steps // per_launch)
+            e0.record()
+            for i in range(n):
+                launch(i)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) / (n * per_launch))
+        return times
+
+    unit_mb = cfg.B * cfg.H * cfg.W * cfg.C * (2 if cfg.dtype == "bf16" else 4) / 1e6
+    sets = max(2, min(24, int(600 / (2 * unit_mb)) + 1))
+    rot = measure(sets)
+    out = {"repeats_ms_per_step": [round(t, 5) for t in rot],
+           "median_ms_per_step": round(statistics.median(rot), 5), "min_ms_per_step": round(min(rot), 5),
+           "smooth_inputs_median_ms_per_step": round(statistics.median(measure(sets, smooth=True)), 5),
+           "hot_cache_median_ms_per_step": round(statistics.median(measure(1)), 5),
+           "graph_replay_median_ms_per_step": round(statistics.median(measure(sets, graph=True)), 5)}
+    return out
+
+
 def roofline_of(cfg, kernels):
     if not kernels:
         return None, {}
@@ -205,10 +260,12 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=500)     # about 25 ms: the clocks have settled
     ap.add_argument("--workload", type=int, default=2, help="named workload index 1..5 (default 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other named workloads")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the context timings (repeats, smooth inputs, hot cache, graph replay)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run the plain copy kernel (64 MiB, 10 times): the reference against "
                          "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -246,6 +303,8 @@ def main():
         "roofline": roof, "kernels": {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2)}
                                       for k, v in summary.items()},
     }
+    if not args.no_variants:
+        line["variants"] = time_variants(cfg, args.steps, args.warmup)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, res["host"])
     if not args.no_others:
