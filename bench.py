@@ -210,6 +210,39 @@ def time_variants(cfg, steps, warmup):
     return out
 
 
+def measured_peaks():
+    """What plain probe kernels reach on this GPU, beside the published peaks the roofline
+    uses: a copy and a read of 512 MiB (twice the last-level cache), and a register-only loop
+    of dense bf16 matrix products."""
+    import torch
+
+    import paper_2303_08810_amd as bra
+
+    nbytes = 512 << 20
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").random_()
+    dst = torch.empty_like(src)
+    scratch = torch.zeros(4, dtype=torch.float32, device="cuda")
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps / 1e3
+
+    t_copy = timed(lambda: bra.util_copy(dst, src), 20)
+    t_read = timed(lambda: bra.util_read(src, scratch), 20)
+    wgs, iters = 256 * 8, 4000
+    t_mfma = timed(lambda: bra.util_mfma(wgs, iters, scratch), 5)
+    return {"hbm_copy_GBs": round(2 * nbytes / t_copy / 1e9, 1), "hbm_read_GBs": round(nbytes / t_read / 1e9, 1),
+            "mfma_bf16_TFLOPs": round(wgs * 4 * 8 * iters * 16384 / t_mfma / 1e12, 1)}
+
+
 def roofline_of(cfg, kernels):
     if not kernels:
         return None, {}
@@ -305,6 +338,7 @@ def main():
     }
     if not args.no_variants:
         line["variants"] = time_variants(cfg, args.steps, args.warmup)
+        line["measured_peaks"] = measured_peaks()
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, res["host"])
     if not args.no_others:

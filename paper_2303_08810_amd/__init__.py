@@ -20,7 +20,7 @@ _PATHS = {"auto": PATH_AUTO, "generic": PATH_GENERIC, "mfma": PATH_MFMA}
 
 EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_strerror", "bra_version",
            "bra_profile_begin", "bra_profile_end", "bra_kernel_name", "bra_util_copy",
-           "bra_util_read")
+           "bra_util_read", "bra_util_mfma")
 
 
 class BraShape(ctypes.Structure):
@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.bra_util_copy.argtypes = [vp, vp, sz, vp]
         L.bra_util_read.restype = ctypes.c_int
         L.bra_util_read.argtypes = [vp, sz, vp, vp]
+        L.bra_util_mfma.restype = ctypes.c_int
+        L.bra_util_mfma.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
         _lib = L
     return _lib
 
@@ -167,6 +169,16 @@ def profile_end(max_records: int):
     n = ctypes.c_int(0)
     _check(lib().bra_profile_end(ids, ms, max_records, ctypes.byref(n)))
     return [(lib().bra_kernel_name(ids[i]).decode(), float(ms[i])) for i in range(n.value)]
+
+
+def util_mfma(workgroups: int, iters: int, scratch: torch.Tensor) -> None:
+    """Matrix-core throughput probe: workgroups x 4 wavefronts x 8 iters dense bf16 16x16x32 products."""
+    _check(lib().bra_util_mfma(int(workgroups), int(iters), _ptr(scratch), _stream(scratch.device)))
+
+
+def util_read(src: torch.Tensor, scratch: torch.Tensor) -> None:
+    """Plain read-only pass over src, for bandwidth calibration."""
+    _check(lib().bra_util_read(_ptr(src), src.numel() * src.element_size(), _ptr(scratch), _stream(src.device)))
 
 
 def util_copy(dst: torch.Tensor, src: torch.Tensor) -> None:

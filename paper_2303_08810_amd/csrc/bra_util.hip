@@ -1,5 +1,5 @@
-// Plain streaming kernels used to calibrate memory-bandwidth measurements: a copy of
-// known size (against which hardware byte counters are scaled) and a read-only sum.
+// Plain kernels used to calibrate measurements: a copy of known size (against which hardware
+// byte counters are scaled), a read-only sum, and a matrix-core throughput probe.
 #include "bra_common.h"
 
 namespace bra {
@@ -24,6 +24,28 @@ __global__ __launch_bounds__(256) void k_util_read(const u32x4 *__restrict__ src
         acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
     }
     if (acc == 0x9e3779b9u) out[0] = acc;   // practically never taken: keeps the loads alive
+}
+
+// Matrix-core throughput probe: every wavefront runs `iters` rounds of 8 independent
+// v_mfma_f32_16x16x32_bf16 accumulation chains on register operands.
+typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void k_util_mfma(int iters, float *__restrict__ out)
+{
+    const u32x4 bits = {0x3f803f80u + threadIdx.x, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    const bf16x8v a = __builtin_bit_cast(bf16x8v, bits), b = a;
+    f32x4v acc[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = f32x4v{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[c], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) s += acc[c][0];
+    if (s == 12345.678f) out[0] = s;       // practically never taken: keeps the chains alive
 }
 
 }  // namespace
@@ -56,6 +78,15 @@ int bra_util_read(const void *src, size_t bytes, void *scratch4, void *hip_strea
     const int grid = (int)(want < 256 * 32 ? want : 256 * 32);
     hipLaunchKernelGGL(k_util_read, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream,
                        (const u32x4 *)src, n16, (unsigned *)scratch4);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+int bra_util_mfma(int workgroups, int iters, void *scratch4, void *hip_stream)
+{
+    if (!scratch4) return BRA_ERR_NULL;
+    if (workgroups < 1 || iters < 1) return BRA_ERR_SHAPE;
+    hipLaunchKernelGGL(k_util_mfma, dim3(workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters,
+                       (float *)scratch4);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
