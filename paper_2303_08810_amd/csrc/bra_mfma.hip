@@ -1439,6 +1439,8 @@ bool attn_big_ok(const Dims &D)
 // Shapes of the kernels specialised by channel count.
 static bool specialised(const Dims &D)
 {
+    static const bool general_only = getenv("BRA_GENERAL_PIPELINE") != nullptr;   // benchmarking aid
+    if (general_only) return false;
     if (D.dtype != BRA_BF16 || D.d != 32) return false;
     if (D.C != 64 && D.C != 128 && D.C != 256) return false;
     if ((long)D.B * D.R * (D.n / 64 + 1) + 8 > 0x7fffffffL) return false;
