@@ -736,7 +736,9 @@ void k_attn_big(AttnArgs A, Dims D)
     const int b = wid / (D.R * chunks);
     const int reg = (wid / chunks) % D.R;
     const int ch = wid % chunks;
-    const int y0 = (reg / D.S) * D.rh + ch * qh, x0 = (reg % D.S) * D.rw;
+    const float s_inv = 1.0f / (float)D.S;
+    const int regy = fast_div(reg, s_inv);
+    const int y0 = regy * D.rh + ch * qh, x0 = (reg - regy * D.S) * D.rw;
     const size_t img_off = (size_t)b * D.N * C;
     const int hw = D.rw + 4, hrows = (qh + 4) * hw;
     const float hw_inv = 1.0f / (float)hw, rw_inv = 1.0f / (float)D.rw;
@@ -781,7 +783,8 @@ void k_attn_big(AttnArgs A, Dims D)
     u32x4 kreg[NBT], vreg[NBT];
     auto request = [&](int kb) {
         const int j = irp[kb / chunks];
-        const int ky0 = (j / D.S) * D.rh + (kb % chunks) * qh, kx0 = (j % D.S) * D.rw;
+        const int jy = fast_div(j, s_inv);
+        const int ky0 = jy * D.rh + (kb % chunks) * qh, kx0 = (j - jy * D.S) * D.rw;
         tile_load<C, NBT, NT>(kreg, A.K + img_off, ky0, kx0, D.rw, rw_inv, 64, D.H, D.W, 0);
         tile_load<C, NBT, NT>(vreg, A.V + img_off, ky0, kx0, D.rw, rw_inv, 64, D.H, D.W, 0);
     };
@@ -919,7 +922,9 @@ void k_fused(AttnArgs A, Dims D)
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
     const int b = wid / D.R, reg = wid % D.R;
-    const int y0 = (reg / D.S) * D.rh, x0 = (reg % D.S) * RW;
+    const float s_inv = 1.0f / (float)D.S;
+    const int regy = fast_div(reg, s_inv);
+    const int y0 = regy * D.rh, x0 = (reg - regy * D.S) * RW;
     const size_t img_off = (size_t)b * D.N * C;
     const bf16_t *Ximg = A.X + img_off;
     const float hw_inv = 1.0f / (float)HW, rw_inv = 1.0f / (float)RW;
@@ -954,7 +959,8 @@ void k_fused(AttnArgs A, Dims D)
     for (int r = 0; r < 10; ++r)
         aw[r / 2][r % 2] = *(const s16x4 *)(A.Wa + ((size_t)(wave * 10 + r) * kWave + lane) * 4);
     u32x4 kreg[NBT];
-    tile_load<C, NBT>(kreg, Ximg, (j / D.S) * D.rh, (j % D.S) * RW, RW, rw_inv, 64, D.H, D.W, 0);
+    const int jy = fast_div(j, s_inv);
+    tile_load<C, NBT>(kreg, Ximg, jy * D.rh, (j - jy * D.S) * RW, RW, rw_inv, 64, D.H, D.W, 0);
     tile_store<C, XS, NBH>(Hs, hreg, HROWS, 0);
     tile_store<C, XS, NBT>(Ks, kreg, 64, 0);
     __syncthreads();

@@ -43,7 +43,7 @@ __device__ __forceinline__ void small_attention(const AttnArgs &A, const Dims &D
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
     const int n = D.n, kn = D.kn;
-    const float rw_inv = 1.0f / (float)D.rw;
+    const float rw_inv = 1.0f / (float)D.rw, s_inv = 1.0f / (float)D.S;
 
     bf16x8 qf[HPW];
 #pragma unroll
@@ -61,8 +61,8 @@ __device__ __forceinline__ void small_attention(const AttnArgs &A, const Dims &D
             int key = k0 + idx / CH;
             if (key >= kn) key = kn - 1;           // rows past the end repeat the last key; masked below
             const int j = irp[key >> log2n], slot = key & (n - 1);
-            const int sy = fast_div(slot, rw_inv);
-            const size_t tok = (size_t)((j / D.S) * D.rh + sy) * D.W + (j % D.S) * D.rw + slot - sy * D.rw;
+            const int sy = fast_div(slot, rw_inv), jy = fast_div(j, s_inv);
+            const size_t tok = (size_t)(jy * D.rh + sy) * D.W + (j - jy * D.S) * D.rw + slot - sy * D.rw;
             const size_t off = img_off + tok * C + (idx % CH) * 8;
             kr[u] = *(const u32x4 *)(A.K + off);
             vr[u] = *(const u32x4 *)(A.V + off);
@@ -139,7 +139,8 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
     const size_t img_off = (size_t)b * D.N * C;
     const int n = D.n;
     const float rw_inv = 1.0f / (float)D.rw, hw_inv = 1.0f / (float)hw;
-    const int y0 = (reg / D.S) * D.rh, x0 = (reg % D.S) * D.rw;
+    const int regy = fast_div(reg, 1.0f / (float)D.S);
+    const int y0 = regy * D.rh, x0 = (reg - regy * D.S) * D.rw;
 
     const int32_t *irp = A.Ir_src + ((size_t)b * D.R + reg) * D.k;
     if (A.Ir_out && A.Ir_out != A.Ir_src)
@@ -284,7 +285,8 @@ __global__ __launch_bounds__(256) void k_attn_small(AttnArgs A, bf16_t *__restri
     // query token of this lane's column (columns >= n repeat the last query; never stored)
     const int qs = i < n ? i : n - 1;
     const int qy = fast_div(qs, rw_inv);
-    const size_t qtok = (size_t)((reg / D.S) * D.rh + qy) * D.W + (reg % D.S) * D.rw + qs - qy * D.rw;
+    const int regy = fast_div(reg, 1.0f / (float)D.S);
+    const size_t qtok = (size_t)(regy * D.rh + qy) * D.W + (reg - regy * D.S) * D.rw + qs - qy * D.rw;
 
     f32x4 oacc[HPW][2];
     small_attention<C>(A, D, log2n, img_off, irp, qtok, Ks, Vs, oacc);
