@@ -91,8 +91,10 @@ int bra_route(const bra_shape *shape, const void *X, const void *Wqkv, int32_t *
 /* Whole BRA forward (steps 1-7).  Ir_out_opt (or NULL) receives the routing index
  * that was used.  Ir_in_opt (or NULL) forces the routing: steps 3-4 are skipped and
  * these indices are used instead; entries must lie in [0, S*S) and be distinct
- * within a row (not checked: they are device data; out-of-range values are
- * undefined behaviour). */
+ * within a row (not checked on the host: they are device data).  The kernels clamp
+ * an out-of-range entry into [0, S*S) where they read it, so a wrong index gives a
+ * wrong result, never an access outside the tensors; Ir_out_opt receives the
+ * entries as given. */
 int bra_forward(const bra_shape *shape, const void *X, const void *Wqkv, const void *Wo,
                 const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
                 void *ws, size_t ws_bytes, void *hip_stream);

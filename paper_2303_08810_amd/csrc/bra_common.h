@@ -42,6 +42,10 @@ __device__ inline void store_from_f32(bf16_t *p, float v) { *p = f32_to_bf16(v);
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// A routing index as the kernels use it: entries of a caller-supplied index outside
+// [0, R) (never produced by the library) are clamped instead of addressing outside the map.
+__host__ __device__ inline int region_index(int j, int R) { return j < 0 ? 0 : (j >= R ? R - 1 : j); }
+
 // Kernel identifiers for the optional per-launch timing (bra_profile_begin/end).
 enum KernelId {
     K_GEN_POOL = 0, K_GEN_REGION_QK, K_GEN_TOPK, K_GEN_GEMM_QKV, K_GEN_ATTENTION, K_GEN_LCE,

@@ -201,7 +201,7 @@ __global__ __launch_bounds__(256) void gen_attention_lds(const float *__restrict
             for (int e = tid; e < 64 * d; e += 256) {
                 const int u = e / d, c = e % d;
                 const int key = min(k0 + u, D.kn - 1);
-                const int j = irp[key / D.n], slot = key % D.n;
+                const int j = region_index(irp[key / D.n], D.R), slot = key % D.n;
                 const int tok = ((j / D.S) * D.rh + slot / D.rw) * D.W + (j % D.S) * D.rw + slot % D.rw;
                 const float *row = img + (size_t)tok * C3 + hd * d + c;
                 Ks[u][c] = row[D.C];
@@ -263,7 +263,7 @@ __global__ __launch_bounds__(256) void gen_attention(const float *__restrict__ Q
     const int C3 = 3 * D.C;
     const float *img = QKV + (size_t)b * D.N * C3;
 
-    for (int p = threadIdx.x; p < D.k; p += blockDim.x) regs[p] = Ir[((size_t)b * D.R + i) * D.k + p];
+    for (int p = threadIdx.x; p < D.k; p += blockDim.x) regs[p] = region_index(Ir[((size_t)b * D.R + i) * D.k + p], D.R);
     __syncthreads();
 
     const int y0 = (i / D.S) * D.rh, x0 = (i % D.S) * D.rw;

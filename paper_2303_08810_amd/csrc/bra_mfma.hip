@@ -782,7 +782,7 @@ void k_attn_big(AttnArgs A, Dims D)
     // one has been handed to LDS, so that its latency hides behind the current block's work.
     u32x4 kreg[NBT], vreg[NBT];
     auto request = [&](int kb) {
-        const int j = irp[kb / chunks];
+        const int j = region_index(irp[kb / chunks], D.R);
         const int jy = fast_div(j, s_inv);
         const int ky0 = jy * D.rh + (kb % chunks) * qh, kx0 = (j - jy * D.S) * D.rw;
         tile_load<C, NBT, NT>(kreg, A.K + img_off, ky0, kx0, D.rw, rw_inv, 64, D.H, D.W, 0);
@@ -936,7 +936,11 @@ void k_fused(AttnArgs A, Dims D)
     const size_t rrow = (size_t)b * D.R + reg;
     RouteRowLoads rl;
     int j = 0;
-    if (A.Ir_src) j = A.Ir_src[rrow];
+    int j_given = 0;            // reported as given, used clamped
+    if (A.Ir_src) {
+        j_given = A.Ir_src[rrow];
+        j = region_index(j_given, D.R);
+    }
     else route_row_load(A.Xr + (size_t)b * D.R * C, A.U + rrow * C, D.R, rl);
     u32x4 hreg[NBH];
     tile_load<C, NBH>(hreg, Ximg, y0 - 2, x0 - 2, HW, hw_inv, HROWS, D.H, D.W, 0);
@@ -1114,7 +1118,7 @@ void k_fused(AttnArgs A, Dims D)
     dst[0] = u32x4{yp[0][0], yp[0][1], yp[1][0], yp[1][1]};
     dst[1] = u32x4{yp[2][0], yp[2][1], yp[3][0], yp[3][1]};
     // reported last: a store ahead of the barriers above would have to land before them
-    if (A.Ir_out && A.Ir_out != A.Ir_src && threadIdx.x == 0) A.Ir_out[rrow] = j;
+    if (A.Ir_out && A.Ir_out != A.Ir_src && threadIdx.x == 0) A.Ir_out[rrow] = A.Ir_src ? j_given : j;
 }
 
 // ---------------------------------------------------------------------------

@@ -60,7 +60,7 @@ __device__ __forceinline__ void small_attention(const AttnArgs &A, const Dims &D
             const int idx = threadIdx.x + 256 * u;
             int key = k0 + idx / CH;
             if (key >= kn) key = kn - 1;           // rows past the end repeat the last key; masked below
-            const int j = irp[key >> log2n], slot = key & (n - 1);
+            const int j = region_index(irp[key >> log2n], D.R), slot = key & (n - 1);
             const int sy = fast_div(slot, rw_inv), jy = fast_div(j, s_inv);
             const size_t tok = (size_t)(jy * D.rh + sy) * D.W + (j - jy * D.S) * D.rw + slot - sy * D.rw;
             const size_t off = img_off + tok * C + (idx % CH) * 8;
@@ -367,10 +367,11 @@ __device__ __forceinline__ bool map_stage(const AttnArgs &A, const Dims &D, int 
     }
     const bool copy_ir = A.Ir_out && A.Ir_out != A.Ir_src && w.h == 0 && part == 0;
     for (int p = threadIdx.x; p < D.R * D.k; p += T) {
-        const int j = A.Ir_src[(size_t)w.b * D.R * D.k + p];
+        const int j_given = A.Ir_src[(size_t)w.b * D.R * D.k + p];
+        const int j = region_index(j_given, D.R);
         const int jy = fast_div(j, s_inv);
         w.rows[p] = (jy * D.rh * D.W + (j - jy * D.S) * D.rw) * kMapPitch;
-        if (copy_ir) A.Ir_out[(size_t)w.b * D.R * D.k + p] = j;
+        if (copy_ir) A.Ir_out[(size_t)w.b * D.R * D.k + p] = j_given;
     }
     for (int r = threadIdx.x; r < D.R; r += T) {
         const int ry = fast_div(r, s_inv);

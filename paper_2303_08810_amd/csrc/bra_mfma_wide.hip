@@ -289,7 +289,7 @@ __global__ __launch_bounds__(256) void k_attn_gen(AttnArgs A, bf16_t *__restrict
             const int idx = tid + 256 * u;                       // (key of the block, 16-byte piece)
             const int key = min(k0 + idx / 8, kn - 1);
             const int p = fast_div(key, n_inv);
-            const size_t tok = (size_t)region_origin(irp[p]) + in_region(key - p * n);
+            const size_t tok = (size_t)region_origin(region_index(irp[p], D.R)) + in_region(key - p * n);
             const size_t off = img_off + tok * C + (idx % 8) * 8;
             kreg[u] = *(const u32x4 *)(A.K + off);
             vreg[u] = *(const u32x4 *)(A.V + off);

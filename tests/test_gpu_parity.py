@@ -171,6 +171,24 @@ def test_mfma_random_shapes(B, H, W, C, heads, S, k):
     compare(X, Wqkv, Wo, Wlce, "bf16", S, k, heads, "mfma")
 
 
+@pytest.mark.parametrize("shape,path,dtype", [((2, 16, 16, 64, 2, 2, 1), "mfma", "bf16"), ((2, 14, 14, 256, 8, 7, 4), "mfma", "bf16"),
+                                              ((1, 28, 28, 128, 4, 7, 2), "mfma", "bf16"), ((1, 32, 32, 64, 2, 2, 2), "mfma", "bf16"),
+                                              ((1, 12, 12, 192, 6, 3, 2), "mfma", "bf16"), ((1, 10, 10, 320, 5, 5, 2), "mfma", "bf16"),
+                                              ((1, 12, 12, 48, 3, 3, 2), "generic", "f32")])
+def test_out_of_range_routing_entries_are_clamped(shape, path, dtype):
+    """A forced index with entries outside [0, S*S) behaves like its clamped version."""
+    B, H, W, C, heads, S, k = shape
+    X, Wqkv, Wo, Wlce = make_inputs(B, H, W, C, seed=4242 + C, dtype=dtype)
+    R = S * S
+    rng = np.random.default_rng(7)
+    bad = rng.integers(-3 * R, 4 * R, size=(B, R, k)).astype(np.int32)
+    good = np.clip(bad, 0, R - 1)
+    Y_bad, Ir_bad, _, _ = gpu_forward(X, Wqkv, Wo, Wlce, dtype, S, k, heads, path, Ir_in=bad)
+    Y_good, _, _, _ = gpu_forward(X, Wqkv, Wo, Wlce, dtype, S, k, heads, path, Ir_in=good)
+    np.testing.assert_array_equal(Ir_bad, bad)
+    np.testing.assert_array_equal(Y_bad, Y_good)
+
+
 def test_mfma_scale_and_forced_routing():
     X, Wqkv, Wo, Wlce = make_inputs(2, 16, 16, 64, seed=77, dtype="bf16")
     compare(X, Wqkv, Wo, Wlce, "bf16", 2, 2, 2, "mfma", scale=0.05)
