@@ -65,17 +65,18 @@ __global__ __launch_bounds__(256) void k_pool_wide(const bf16_t *__restrict__ X,
 // its W operand (rows = outputs) comes out of the row-major chunk by the transposing LDS read.
 // Output column o goes to buffer o / cols (three buffers of `cols` columns each, e.g. Q, K,
 // V), column o % cols.
-// SPLIT: In is float32 and enters as three exact bf16 terms (smallest first), Out is float32;
-// otherwise both are bf16.
+// SPLIT: In is float32 and enters as three exact bf16 terms (smallest first); otherwise In is
+// bf16.  F32OUT: Out is float32, else bf16.
 constexpr int kGemmPitch = 80;      // bf16 per LDS row of In: 64 + 16 (rows of 160 bytes)
 constexpr int kGemmPitchW = 144;    // of W: 128 + 16 (rows of 288 bytes)
 
 struct GemmOut {
     void *buf[3];
     int cols;
+    float *f32[2];      // optional float32 copies of the results that go to buf[0] and buf[1] (bf16 output only)
 };
 
-template <bool SPLIT>
+template <bool SPLIT, bool F32OUT = SPLIT>
 __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const bf16_t *__restrict__ W,
                                               int ldw, int M, int K, int Nout, GemmOut out)
 {
@@ -166,8 +167,12 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
         const int o = o0 + 16 * t + 4 * g;
         if (o >= Nout) break;
         const int which = o / out.cols, col = o % out.cols;
-        if (SPLIT) *(f32x4 *)((float *)out.buf[which] + (size_t)m * out.cols + col) = acc[t];
-        else *(u32x2 *)((bf16_t *)out.buf[which] + (size_t)m * out.cols + col) = pack4(acc[t]);
+        if (F32OUT) {
+            *(f32x4 *)((float *)out.buf[which] + (size_t)m * out.cols + col) = acc[t];
+        } else {
+            *(u32x2 *)((bf16_t *)out.buf[which] + (size_t)m * out.cols + col) = pack4(acc[t]);
+            if (which < 2 && out.f32[which]) *(f32x4 *)(out.f32[which] + (size_t)m * out.cols + col) = acc[t];
+        }
     }
 }
 
@@ -178,62 +183,68 @@ constexpr size_t gemm_smem(bool split)
 
 // ---------------------------------------------------------------------------
 // Rows of A^r = Q^r (K^r)^T (Eq. 4) in float32 and their top-k (Eq. 5) for workgroup
-// (image, 16 query regions), R <= 64: the channels pass through LDS 64 at a time (K^r of all
-// regions as [16][kQkRS][4]: channel group, region, channel; Q^r of the 16 rows), wavefront w
-// accumulates rows 4 w .. 4 w + 3 with lane j holding entry j.
+// (image, 4 NR query regions), R <= 64: the channels pass through LDS 64 at a time (K^r of all
+// regions as [16][kQkRS][4]: channel group, region, channel; Q^r of the workgroup's rows),
+// wavefront w accumulates rows NR w .. NR w + NR - 1 with lane j holding entry j.
 constexpr int kQkRS = 65;
 
+template <int NR>
 __global__ __launch_bounds__(256) void k_route_qk(const float *__restrict__ Qr, const float *__restrict__ Kr,
                                                   int32_t *__restrict__ Ir, float *__restrict__ Ar, Dims D)
 {
     __shared__ __attribute__((aligned(16))) float Kt[16 * kQkRS * 4];
     __shared__ __attribute__((aligned(16))) float Qs[16 * 68];
-    const int groups = (D.R + 15) / 16;
+    constexpr int QR = 4 * NR;
+    const int groups = (D.R + QR - 1) / QR;
     const int b = blockIdx.x / groups, myrt = blockIdx.x % groups;
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const size_t img = (size_t)b * D.R * D.C;
-    float a[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int c0 = 0; c0 < D.C; c0 += 64) {
-        f32x4 kv[4], qv;
+    float a[NR];
+#pragma unroll
+    for (int rr = 0; rr < NR; ++rr) a[rr] = 0.f;
+    f32x4 kv[4], qv;
+    auto request = [&](int c0) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int idx = tid + 256 * u;               // (region, 4-channel group)
             const int r = min(idx / 16, D.R - 1);        // regions past R repeat the last; never used
             kv[u] = *(const f32x4 *)(Kr + img + (size_t)r * D.C + c0 + (idx % 16) * 4);
         }
-        {
-            const int r = min(16 * myrt + tid / 16, D.R - 1);
-            qv = *(const f32x4 *)(Qr + img + (size_t)r * D.C + c0 + (tid % 16) * 4);
-        }
+        const int r = min(QR * myrt + (tid / 16) % QR, D.R - 1);
+        qv = *(const f32x4 *)(Qr + img + (size_t)r * D.C + c0 + (tid % 16) * 4);
+    };
+    request(0);
+    for (int c0 = 0; c0 < D.C; c0 += 64) {
         if (c0) __syncthreads();
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int idx = tid + 256 * u;
             *(f32x4 *)(Kt + ((idx % 16) * kQkRS + idx / 16) * 4) = kv[u];
         }
-        *(f32x4 *)(Qs + (tid / 16) * 68 + (tid % 16) * 4) = qv;
+        if (tid / 16 < QR) *(f32x4 *)(Qs + (tid / 16) * 68 + (tid % 16) * 4) = qv;
         __syncthreads();
+        if (c0 + 64 < D.C) request(c0 + 64);      // the next chunk travels while this one is multiplied
 #pragma unroll 4
         for (int c4 = 0; c4 < 16; ++c4) {
             const f32x4 k4 = *(const f32x4 *)(Kt + (c4 * kQkRS + lane) * 4);
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-                const f32x4 q4 = *(const f32x4 *)(Qs + (4 * wave + rr) * 68 + 4 * c4);
+            for (int rr = 0; rr < NR; ++rr) {
+                const f32x4 q4 = *(const f32x4 *)(Qs + (NR * wave + rr) * 68 + 4 * c4);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) a[rr] = fmaf(q4[e], k4[e], a[rr]);
             }
         }
     }
-    const int r0 = 16 * myrt + 4 * wave;
+    const int r0 = QR * myrt + NR * wave;
     if (r0 >= D.R) return;
-    const int nrows = min(4, D.R - r0);
+    const int nrows = min(NR, D.R - r0);
     const size_t row0 = (size_t)b * D.R + r0;
     if (Ar && lane < D.R) {
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr)
+        for (int rr = 0; rr < NR; ++rr)
             if (rr < nrows) Ar[(row0 + rr) * D.R + lane] = a[rr];
     }
-    wave_topk_rows<4>(a, nrows, lane, D.R, D.k, Ir + row0 * D.k);
+    wave_topk_rows<NR>(a, nrows, lane, D.R, D.k, Ir + row0 * D.k);
 }
 
 // ---------------------------------------------------------------------------
@@ -414,21 +425,37 @@ WideWs carve(const Dims &D, void *ws)
     return w;
 }
 
-template <bool SPLIT>
+template <bool SPLIT, bool F32OUT = SPLIT>
 int launch_gemm(const void *In, const bf16_t *W, int ldw, long M, int K, int Nout, GemmOut out, int kernel_id,
                 hipStream_t st)
 {
     static bool opted = false;
     if (!opted) {
-        if (hipFuncSetAttribute((const void *)k_gemm<SPLIT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute((const void *)k_gemm<SPLIT, F32OUT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)gemm_smem(SPLIT)) != hipSuccess)
             return BRA_ERR_LAUNCH;
         opted = true;
     }
     const long grid = ((M + 63) / 64) * ((Nout + 127) / 128);
     ProfScope ps(st, kernel_id);
-    hipLaunchKernelGGL(k_gemm<SPLIT>, dim3((unsigned)grid), dim3(256), gemm_smem(SPLIT), st, In, W, ldw, (int)M, K, Nout,
-                       out);
+    hipLaunchKernelGGL((k_gemm<SPLIT, F32OUT>), dim3((unsigned)grid), dim3(256), gemm_smem(SPLIT), st, In, W, ldw,
+                       (int)M, K, Nout, out);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+// A^r rows and top-k from the float32 Q^r, K^r in the workspace.
+int affinity_steps(const Dims &D, const WideWs &w, int32_t *Ir, float *Ar_opt, hipStream_t st)
+{
+    if (many_regions(D)) return valu_affinity_topk(D, w.qr, w.kr, Ir, Ar_opt, st);   // more than one entry per lane
+    ProfScope ps(st, K_MFMA_ROUTE_ROWS);
+    // 16 query regions per workgroup when that already fills the chip, else 8 or 4
+    const long wgs16 = (long)D.B * ((D.R + 15) / 16);
+    if (wgs16 >= 1024)
+        hipLaunchKernelGGL(k_route_qk<4>, dim3((unsigned)wgs16), dim3(256), 0, st, w.qr, w.kr, Ir, Ar_opt, D);
+    else if (2 * wgs16 >= 1024)
+        hipLaunchKernelGGL(k_route_qk<2>, dim3(D.B * ((D.R + 7) / 8)), dim3(256), 0, st, w.qr, w.kr, Ir, Ar_opt, D);
+    else
+        hipLaunchKernelGGL(k_route_qk<1>, dim3(D.B * ((D.R + 3) / 4)), dim3(256), 0, st, w.qr, w.kr, Ir, Ar_opt, D);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
@@ -436,6 +463,14 @@ int launch_gemm(const void *In, const bf16_t *W, int ldw, long M, int K, int Nou
 int route_steps(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const WideWs &w, int32_t *Ir, float *Ar_opt,
                 hipStream_t st)
 {
+    if (D.n == 1) {
+        // one token per region: the means are the (bf16) tokens themselves, so Q^r | K^r is the
+        // plain projection of X with float32 results: no pooling, no split
+        const int rc = launch_gemm<false, true>(X, Wqkv, 3 * D.C, (long)D.B * D.R, D.C, 2 * D.C,
+                                                GemmOut{{w.qr, w.kr, nullptr}, D.C, {nullptr, nullptr}}, K_MFMA_ROUTE_ROWS, st);
+        if (rc != BRA_OK) return rc;
+        return affinity_steps(D, w, Ir, Ar_opt, st);
+    }
     {
         int sub = 1;                                           // lanes per (region, chunk)
         while (sub < 8 && 2 * sub <= D.n) sub *= 2;
@@ -443,13 +478,10 @@ int route_steps(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const WideWs
         ProfScope ps(st, K_MFMA_POOL_QK);
         hipLaunchKernelGGL(k_pool_wide, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, X, w.xr, D, sub);
     }
-    const int rc = launch_gemm<true>(w.xr, Wqkv, 3 * D.C, (long)D.B * D.R, D.C, 2 * D.C, GemmOut{{w.qr, w.kr, nullptr}, D.C},
+    const int rc = launch_gemm<true>(w.xr, Wqkv, 3 * D.C, (long)D.B * D.R, D.C, 2 * D.C, GemmOut{{w.qr, w.kr, nullptr}, D.C, {nullptr, nullptr}},
                                      K_MFMA_ROUTE_ROWS, st);
     if (rc != BRA_OK) return rc;
-    if (many_regions(D)) return valu_affinity_topk(D, w.qr, w.kr, Ir, Ar_opt, st);   // more than one entry per lane
-    ProfScope ps(st, K_MFMA_ROUTE_ROWS);
-    hipLaunchKernelGGL(k_route_qk, dim3(D.B * ((D.R + 15) / 16)), dim3(256), 0, st, w.qr, w.kr, Ir, Ar_opt, D);
-    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+    return affinity_steps(D, w, Ir, Ar_opt, st);
 }
 
 }  // namespace
@@ -478,15 +510,24 @@ int wide_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo,
 {
     const WideWs w = carve(D, ws);
     const int32_t *Ir_src = Ir_in_opt;
-    if (!Ir_in_opt) {
-        int32_t *Ir_dst = Ir_out_opt ? Ir_out_opt : w.ir;
+    int32_t *Ir_dst = Ir_out_opt ? Ir_out_opt : w.ir;
+    // one token per region: Q^r, K^r are Q, K before their rounding to bf16, which the token
+    // projection leaves as float32 copies; the routing then follows the projection
+    const bool route_after = !Ir_in_opt && D.n == 1;
+    if (!Ir_in_opt && !route_after) {
         const int rc = route_steps(D, (const bf16_t *)X, (const bf16_t *)Wqkv, w, Ir_dst, nullptr, st);
         if (rc != BRA_OK) return rc;
         Ir_src = Ir_dst;
     }
     const long M = (long)D.B * D.N;
-    int rc = launch_gemm<false>(X, (const bf16_t *)Wqkv, 3 * D.C, M, D.C, 3 * D.C, GemmOut{{w.q, w.k, w.v}, D.C}, K_MFMA_QKV, st);
+    float *fq = route_after ? w.qr : nullptr, *fk = route_after ? w.kr : nullptr;
+    int rc = launch_gemm<false>(X, (const bf16_t *)Wqkv, 3 * D.C, M, D.C, 3 * D.C, GemmOut{{w.q, w.k, w.v}, D.C, {fq, fk}}, K_MFMA_QKV, st);
     if (rc != BRA_OK) return rc;
+    if (route_after) {
+        rc = affinity_steps(D, w, Ir_dst, nullptr, st);
+        if (rc != BRA_OK) return rc;
+        Ir_src = Ir_dst;
+    }
     AttnArgs A = {};
     A.X = (const bf16_t *)X; A.Q = w.q; A.K = w.k; A.V = w.v;
     A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = (const bf16_t *)Wlce; A.Y = (bf16_t *)Y;
@@ -503,7 +544,7 @@ int wide_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo,
         rc = launch_lce_add_any(D, A, w.o, st);
     }
     if (rc != BRA_OK) return rc;
-    return launch_gemm<false>(w.o, (const bf16_t *)Wo, D.C, M, D.C, D.C, GemmOut{{Y, nullptr, nullptr}, D.C}, K_MFMA_WO, st);
+    return launch_gemm<false>(w.o, (const bf16_t *)Wo, D.C, M, D.C, D.C, GemmOut{{Y, nullptr, nullptr}, D.C, {nullptr, nullptr}}, K_MFMA_WO, st);
 }
 
 }  // namespace bra
