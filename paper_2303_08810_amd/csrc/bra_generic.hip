@@ -38,20 +38,29 @@ __global__ __launch_bounds__(256) void gen_gemm(const TA *__restrict__ A, int ld
     for (int i = 0; i < 4; ++i)
         for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
 
-    for (int k0 = 0; k0 < K; k0 += 16) {
+    // the next 16-deep slice is requested while the current one is multiplied
+    float ra[4], rb[4];
+    auto fetch = [&](int k0) {
+#pragma unroll
         for (int i = 0; i < 4; ++i) {
-            int idx = tid + i * 256;
-            int r = idx / 16, kk = idx % 16;
-            long gm = m0 + r;
-            float v = 0.f;
-            if (gm < M && k0 + kk < K) v = load_f32(A + gm * lda + k0 + kk);
-            As[kk][r] = v;
-            int kb = idx / 64, nn = idx % 64;
-            float w = 0.f;
-            if (k0 + kb < K && n0 + nn < N) w = load_f32(Bm + (long)(k0 + kb) * ldb + n0 + nn);
-            Bs[kb][nn] = w;
+            const int idx = tid + i * 256;
+            const int r = idx / 16, kk = idx % 16;
+            const long gm = m0 + r;
+            ra[i] = (gm < M && k0 + kk < K) ? load_f32(A + gm * lda + k0 + kk) : 0.f;
+            const int kb = idx / 64, nn = idx % 64;
+            rb[i] = (k0 + kb < K && n0 + nn < N) ? load_f32(Bm + (long)(k0 + kb) * ldb + n0 + nn) : 0.f;
+        }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + i * 256;
+            As[idx % 16][idx / 16] = ra[i];
+            Bs[idx / 64][idx % 64] = rb[i];
         }
         __syncthreads();
+        if (k0 + 16 < K) fetch(k0 + 16);
         for (int kk = 0; kk < 16; ++kk) {
             float a[4], b[4];
             for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
