@@ -140,3 +140,44 @@ def make_config_inputs(cfg: BraConfig, *, batch=None, smooth=False):
     if batch is not None and batch < B:
         X = np.ascontiguousarray(X[:batch])
     return X, Wqkv, Wo, Wlce
+
+
+def make_block_params(C, hidden, *, seed, dtype="f32"):
+    """Draw the parameters a whole BiFormer block has beyond BRA's own (Sec. 3.4): the 3x3
+    depth-wise position encoding, two LayerNorms and the 2-layer MLP (hidden = e C channels).
+
+    rng = numpy Generator(PCG64(seed)); drawn in this order as float32: Wpos[C,3,3] ~ N(0,1)/3,
+    bpos[C] ~ 0.1 N(0,1), ln1_g = 1 + 0.1 N(0,1), ln1_b ~ 0.1 N(0,1), ln2_g, ln2_b likewise,
+    W1[C,hidden] ~ N(0,1)/sqrt(C), b1[hidden] ~ 0.1 N(0,1), W2[hidden,C] ~ N(0,1)/sqrt(hidden),
+    b2[C] ~ 0.1 N(0,1).  The matrices (Wpos, W1, W2) are rounded to bf16 for bf16 workloads; the
+    vectors stay float32 on both sides.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    n = lambda *shape: rng.standard_normal(shape, dtype=np.float32)
+    P = {}
+    P["Wpos"] = n(C, 3, 3) / np.float32(3.0)
+    P["bpos"] = np.float32(0.1) * n(C)
+    P["ln1_g"] = np.float32(1.0) + np.float32(0.1) * n(C)
+    P["ln1_b"] = np.float32(0.1) * n(C)
+    P["ln2_g"] = np.float32(1.0) + np.float32(0.1) * n(C)
+    P["ln2_b"] = np.float32(0.1) * n(C)
+    P["W1"] = n(C, hidden) / np.float32(np.sqrt(C))
+    P["b1"] = np.float32(0.1) * n(hidden)
+    P["W2"] = n(hidden, C) / np.float32(np.sqrt(hidden))
+    P["b2"] = np.float32(0.1) * n(C)
+    if dtype == "bf16":
+        for key in ("Wpos", "W1", "W2"):
+            P[key] = round_to_bf16(P[key])
+    elif dtype != "f32":
+        raise ValueError(dtype)
+    return {key: np.ascontiguousarray(v, dtype=np.float32) for key, v in P.items()}
+
+
+def make_block_inputs(cfg: BraConfig, *, batch=None, expansion=3):
+    """X and all parameters of one block at a named workload's shape (MLP expansion ratio
+    e = 3, Sec. 3.4): BRA's tensors from make_config_inputs, the rest from make_block_params
+    with seed BASE_SEED + 1000 + index."""
+    X, Wqkv, Wo, Wlce = make_config_inputs(cfg, batch=batch)
+    P = make_block_params(cfg.C, expansion * cfg.C, seed=BASE_SEED + 1000 + cfg.index, dtype=cfg.dtype)
+    P.update(Wqkv=Wqkv, Wo=Wo, Wlce=Wlce)
+    return X, P
