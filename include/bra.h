@@ -99,6 +99,44 @@ int bra_forward(const bra_shape *shape, const void *X, const void *Wqkv, const v
                 const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
                 void *ws, size_t ws_bytes, void *hip_stream);
 
+/* One whole BiFormer block around BRA (Sec. 3.4): a 3x3 depth-wise convolution at the start
+ * encodes relative position, then the BRA module and a 2-layer MLP (expansion ratio e,
+ * hidden = e C channels) follow.  The figure that fixes normalisation and residual links is
+ * read as the pre-norm residual form of the works that section cites:
+ *     X1   = X  + DWConv3x3(X) + bpos          cross-correlation, stride 1, zero padding 1
+ *     X2   = X1 + BRA(LayerNorm1(X1))          steps 1-7 above
+ *     Xout = X2 + GELU(LayerNorm2(X2) W1 + b1) W2 + b2
+ * LayerNorm: per token over its C channels, biased variance, eps inside the square root,
+ * then gamma, beta.  GELU(t) = t Phi(t) (the exact form; evaluated with an erf approximation
+ * of absolute error < 1.5e-7).
+ * bra_block_params is a HOST struct of DEVICE pointers, all required:
+ *   Wpos [C,3,3] (channel, ky, kx), W1 [C, hidden], W2 [hidden, C], Wqkv, Wo, Wlce as above,
+ *   all of shape->dtype; the vectors bpos, ln*_gamma, ln*_beta, b2 [C] and b1 [hidden] float32.
+ * Built for dtype BRA_BF16, C a multiple of 64 up to 4096 and hidden a multiple of 64; the
+ * BRA stage runs on the family that bra_forward would pick for `shape` (shape->path applies).
+ * Intermediate tensors (X1, LayerNorm1's output, BRA's output, X2, the hidden layer) live in
+ * `ws` in bf16; arithmetic is float32.  Xout may be the same buffer as X.  Ir_out_opt /
+ * Ir_in_opt as in bra_forward.  Errors: as bra_forward; UNSUPPORTED for other dtypes / sizes,
+ * SHAPE for hidden < 1 or eps < 0. */
+typedef struct bra_block_params {
+    const void *Wpos;
+    const float *bpos;
+    const float *ln1_gamma, *ln1_beta;
+    const void *Wqkv, *Wo, *Wlce;
+    const float *ln2_gamma, *ln2_beta;
+    const void *W1;
+    const float *b1;
+    const void *W2;
+    const float *b2;
+} bra_block_params;
+
+/* Host-only: bytes of scratch bra_block_forward needs. */
+int bra_block_workspace_bytes(const bra_shape *shape, int32_t hidden, size_t *out_bytes);
+
+int bra_block_forward(const bra_shape *shape, int32_t hidden, float eps, const void *X,
+                      const bra_block_params *params, void *Xout, int32_t *Ir_out_opt,
+                      const int32_t *Ir_in_opt, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Optional per-launch timing, for benchmarks (Sec. "Limitation": the paper locates
  * BRA's cost in kernel launches and memory transactions, so the benchmark reports
  * time per kernel).  Host-only state, one session at a time, not thread-safe.

@@ -18,7 +18,8 @@ BRA_F32, BRA_BF16 = 0, 1
 PATH_AUTO, PATH_GENERIC, PATH_MFMA = 0, 1, 2
 _PATHS = {"auto": PATH_AUTO, "generic": PATH_GENERIC, "mfma": PATH_MFMA}
 
-EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_strerror", "bra_version",
+EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_block_workspace_bytes",
+           "bra_block_forward", "bra_strerror", "bra_version",
            "bra_profile_begin", "bra_profile_end", "bra_kernel_name", "bra_util_copy",
            "bra_util_read", "bra_util_mfma")
 
@@ -28,6 +29,13 @@ class BraShape(ctypes.Structure):
                 ("C", ctypes.c_int32), ("heads", ctypes.c_int32), ("S", ctypes.c_int32),
                 ("k", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("path", ctypes.c_int32)]
+
+
+class BraBlockParams(ctypes.Structure):
+    """bra_block_params: device pointers, in the order of include/bra.h."""
+    FIELDS = ("Wpos", "bpos", "ln1_g", "ln1_b", "Wqkv", "Wo", "Wlce", "ln2_g", "ln2_b", "W1", "b1", "W2", "b2")
+    MATRICES = ("Wpos", "Wqkv", "Wo", "Wlce", "W1", "W2")
+    _fields_ = [(name, ctypes.c_void_p) for name in FIELDS]
 
 
 class BraError(RuntimeError):
@@ -54,6 +62,11 @@ def lib() -> ctypes.CDLL:
         L.bra_route.argtypes = [ctypes.POINTER(BraShape), vp, vp, vp, vp, vp, sz, vp]
         L.bra_forward.restype = ctypes.c_int
         L.bra_forward.argtypes = [ctypes.POINTER(BraShape), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.bra_block_workspace_bytes.restype = ctypes.c_int
+        L.bra_block_workspace_bytes.argtypes = [ctypes.POINTER(BraShape), ctypes.c_int32, ctypes.POINTER(sz)]
+        L.bra_block_forward.restype = ctypes.c_int
+        L.bra_block_forward.argtypes = [ctypes.POINTER(BraShape), ctypes.c_int32, ctypes.c_float, vp,
+                                        ctypes.POINTER(BraBlockParams), vp, vp, vp, vp, sz, vp]
         L.bra_strerror.restype = ctypes.c_char_p
         L.bra_strerror.argtypes = [ctypes.c_int]
         L.bra_version.restype = ctypes.c_int
@@ -155,6 +168,46 @@ def bra_forward(X, Wqkv, Wo, Wlce, S, k, heads, *, scale=None, Ir_in=None, want_
     _check(lib().bra_forward(ctypes.byref(shape), _ptr(X), _ptr(Wqkv), _ptr(Wo), _ptr(Wlce), _ptr(Y),
                              _ptr(Ir), _ptr(Ir_in), _ptr(ws), ws.numel(), _stream(X.device)))
     return (Y, Ir) if want_Ir else Y
+
+
+def block_workspace_bytes(shape: BraShape, hidden: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().bra_block_workspace_bytes(ctypes.byref(shape), int(hidden), ctypes.byref(out)))
+    return out.value
+
+
+def bra_block_forward(X, params, S, k, heads, *, eps=1e-6, scale=None, Ir_in=None, want_Ir=False,
+                      path="auto", ws=None, out=None):
+    """One whole BiFormer block (position encoding, LayerNorm, BRA, LayerNorm, MLP with residual
+    links; see include/bra.h).  `params`: dict of device tensors named as BraBlockParams.FIELDS;
+    the matrices in X's dtype, the vectors float32."""
+    B, H, W, C = X.shape
+    hidden = int(params["W1"].shape[1])
+    want = {"Wpos": (C, 3, 3), "bpos": (C,), "ln1_g": (C,), "ln1_b": (C,), "Wqkv": (C, 3 * C), "Wo": (C, C),
+            "Wlce": (C, 5, 5), "ln2_g": (C,), "ln2_b": (C,), "W1": (C, hidden), "b1": (hidden,),
+            "W2": (hidden, C), "b2": (C,)}
+    if not (X.is_cuda and X.is_contiguous()):
+        raise ValueError("X must be a contiguous device tensor")
+    for name in BraBlockParams.FIELDS:
+        t = params[name]
+        dt = X.dtype if name in BraBlockParams.MATRICES else torch.float32
+        if not (t.is_cuda and t.is_contiguous() and t.device == X.device and t.dtype == dt
+                and tuple(t.shape) == want[name]):
+            raise ValueError(f"{name} must be a contiguous {dt} device tensor of shape {want[name]}")
+    shape = make_shape(B, H, W, C, heads, S, k, X.dtype, scale, path)
+    if ws is None:
+        ws = torch.empty(max(block_workspace_bytes(shape, hidden), 256), dtype=torch.uint8, device=X.device)
+        assert ws.data_ptr() % 256 == 0
+    Xout = out if out is not None else torch.empty_like(X)
+    Ir = torch.empty((B, S * S, k), dtype=torch.int32, device=X.device) if want_Ir else None
+    if Ir_in is not None:
+        if not (Ir_in.is_cuda and Ir_in.is_contiguous() and Ir_in.dtype == torch.int32
+                and tuple(Ir_in.shape) == (B, S * S, k)):
+            raise ValueError("Ir_in must be a contiguous int32 [B, S*S, k] device tensor")
+    P = BraBlockParams(*[params[name].data_ptr() for name in BraBlockParams.FIELDS])
+    _check(lib().bra_block_forward(ctypes.byref(shape), hidden, float(eps), _ptr(X), ctypes.byref(P), _ptr(Xout),
+                                   _ptr(Ir), _ptr(Ir_in), _ptr(ws), ws.numel(), _stream(X.device)))
+    return (Xout, Ir) if want_Ir else Xout
 
 
 def profile_begin(max_records: int) -> None:

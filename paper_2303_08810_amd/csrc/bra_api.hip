@@ -92,6 +92,42 @@ int bra_forward(const bra_shape *shape, const void *X, const void *Wqkv, const v
     return generic_forward(D, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, st);
 }
 
+int bra_block_workspace_bytes(const bra_shape *shape, int32_t hidden, size_t *out_bytes)
+{
+    if (!out_bytes) return BRA_ERR_NULL;
+    Dims D;
+    int rc = make_dims(shape, D);
+    if (rc != BRA_OK) return rc;
+    if (hidden < 1) return BRA_ERR_SHAPE;
+    if (!block_supported(D, hidden)) return BRA_ERR_UNSUPPORTED;
+    int path = pick_path(shape, D);
+    if (path < 0) return path;
+    const size_t inner = (path == BRA_PATH_MFMA) ? mfma_workspace_bytes(D) : generic_workspace_bytes(D);
+    *out_bytes = block_workspace_bytes(D, hidden, inner);
+    return BRA_OK;
+}
+
+int bra_block_forward(const bra_shape *shape, int32_t hidden, float eps, const void *X,
+                      const bra_block_params *p, void *Xout, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
+                      void *ws, size_t ws_bytes, void *hip_stream)
+{
+    Dims D;
+    int rc = make_dims(shape, D);
+    if (rc != BRA_OK) return rc;
+    if (hidden < 1 || !(eps >= 0.f)) return BRA_ERR_SHAPE;
+    if (!X || !p || !Xout) return BRA_ERR_NULL;
+    if (!p->Wpos || !p->bpos || !p->ln1_gamma || !p->ln1_beta || !p->Wqkv || !p->Wo || !p->Wlce ||
+        !p->ln2_gamma || !p->ln2_beta || !p->W1 || !p->b1 || !p->W2 || !p->b2)
+        return BRA_ERR_NULL;
+    if (!block_supported(D, hidden)) return BRA_ERR_UNSUPPORTED;
+    int path = pick_path(shape, D);
+    if (path < 0) return path;
+    const size_t inner = (path == BRA_PATH_MFMA) ? mfma_workspace_bytes(D) : generic_workspace_bytes(D);
+    if (!ws_ok(ws, ws_bytes, block_workspace_bytes(D, hidden, inner))) return BRA_ERR_WORKSPACE;
+    return block_forward(D, hidden, eps, X, *p, Xout, Ir_out_opt, Ir_in_opt, ws, inner, path,
+                         (hipStream_t)hip_stream);
+}
+
 const char *bra_strerror(int code)
 {
     switch (code) {

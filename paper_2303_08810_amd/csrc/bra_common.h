@@ -50,7 +50,8 @@ __host__ __device__ inline int region_index(int j, int R) { return j < 0 ? 0 : (
 enum KernelId {
     K_GEN_POOL = 0, K_GEN_REGION_QK, K_GEN_TOPK, K_GEN_GEMM_QKV, K_GEN_ATTENTION, K_GEN_LCE,
     K_GEN_GEMM_WO, K_MFMA_PREP, K_MFMA_QKV, K_MFMA_ATTENTION, K_MFMA_POOL_QK, K_MFMA_ROUTE_ROWS,
-    K_MFMA_FUSED_K1, K_MFMA_ATTN_SMALL, K_MFMA_LCE_ADD, K_MFMA_WO, K_COUNT
+    K_MFMA_FUSED_K1, K_MFMA_ATTN_SMALL, K_MFMA_LCE_ADD, K_MFMA_WO,
+    K_BLK_POS_LN, K_BLK_ADD_LN, K_BLK_MLP_IN, K_BLK_MLP_OUT, K_COUNT
 };
 
 // Brackets the launches issued during its lifetime with two events on `st` when
@@ -86,5 +87,19 @@ int mfma_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, floa
                hipStream_t st);
 int mfma_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
                  void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, hipStream_t st);
+
+// Out[m][o] = act(sum_k In[m][k] W[k][o] + bias[o]) + res[m][o] on the matrix cores; In [M, K],
+// W [K, Nout], Out and res [M, Nout] bf16, bias float32; bias and res may be NULL, act is GELU
+// or the identity.  K must be a multiple of 64, Nout of 8.
+int gemm_bf16(const bf16_t *In, const bf16_t *W, long M, int K, int Nout, bf16_t *Out, const float *bias,
+              const bf16_t *res, bool gelu, int kernel_id, hipStream_t st);
+
+// Whole block around BRA (bra_block.hip).  `path` is the kernel family of the BRA stage
+// (BRA_PATH_GENERIC or BRA_PATH_MFMA), `bra_bytes` that family's workspace size.
+bool block_supported(const Dims &D, int hidden);
+size_t block_workspace_bytes(const Dims &D, int hidden, size_t bra_bytes);
+int block_forward(const Dims &D, int hidden, float eps, const void *X, const bra_block_params &p, void *Xout,
+                  int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, size_t bra_bytes, int path,
+                  hipStream_t st);
 
 }  // namespace bra

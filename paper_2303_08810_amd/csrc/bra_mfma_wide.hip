@@ -74,7 +74,27 @@ struct GemmOut {
     void *buf[3];
     int cols;
     float *f32[2];      // optional float32 copies of the results that go to buf[0] and buf[1] (bf16 output only)
+    // bf16 output only, all optional: bias[o] is added, then GELU is applied, then res[m][o]
+    // (the layout of buf[0]) is added.
+    const float *bias;
+    const bf16_t *res;
+    int gelu;
 };
+
+// GELU(t) = t Phi(t).  erf by the rational-exponential approximation of Abramowitz & Stegun
+// 7.1.26 (absolute error below 1.5e-7, far inside what a bf16 result resolves).
+__device__ __forceinline__ float gelu_f32(float t)
+{
+    const float x = fabsf(t) * 0.70710678f;
+    const float u = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    float p = fmaf(1.061405429f, u, -1.453152027f);
+    p = fmaf(p, u, 1.421413741f);
+    p = fmaf(p, u, -0.284496736f);
+    p = fmaf(p, u, 0.254829592f);
+    const float tail = p * u * __expf(-x * x);        // 1 - erf(x), x >= 0
+    const float phi = t < 0.f ? 0.5f * tail : 1.0f - 0.5f * tail;
+    return t * phi;
+}
 
 template <bool SPLIT, bool F32OUT = SPLIT>
 __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const bf16_t *__restrict__ W,
@@ -170,7 +190,17 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
         if (F32OUT) {
             *(f32x4 *)((float *)out.buf[which] + (size_t)m * out.cols + col) = acc[t];
         } else {
-            *(u32x2 *)((bf16_t *)out.buf[which] + (size_t)m * out.cols + col) = pack4(acc[t]);
+            f32x4 v = acc[t];
+            if (out.bias) {
+                const f32x4 bv = *(const f32x4 *)(out.bias + o);
+                v = f32x4{v[0] + bv[0], v[1] + bv[1], v[2] + bv[2], v[3] + bv[3]};
+            }
+            if (out.gelu) v = f32x4{gelu_f32(v[0]), gelu_f32(v[1]), gelu_f32(v[2]), gelu_f32(v[3])};
+            if (out.res) {
+                const u32x2 rv = *(const u32x2 *)(out.res + (size_t)m * out.cols + col);
+                v = f32x4{v[0] + bf16_lo(rv[0]), v[1] + bf16_hi(rv[0]), v[2] + bf16_lo(rv[1]), v[3] + bf16_hi(rv[1])};
+            }
+            *(u32x2 *)((bf16_t *)out.buf[which] + (size_t)m * out.cols + col) = pack4(v);
             if (which < 2 && out.f32[which]) *(f32x4 *)(out.f32[which] + (size_t)m * out.cols + col) = acc[t];
         }
     }
@@ -485,6 +515,14 @@ int route_steps(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const WideWs
 }
 
 }  // namespace
+
+int gemm_bf16(const bf16_t *In, const bf16_t *W, long M, int K, int Nout, bf16_t *Out, const float *bias,
+              const bf16_t *res, bool gelu, int kernel_id, hipStream_t st)
+{
+    if (M < 1 || M > 0x7fffffffL || K < 64 || K % 64 || Nout < 8 || Nout % 8) return BRA_ERR_UNSUPPORTED;
+    GemmOut out{{Out, nullptr, nullptr}, Nout, {nullptr, nullptr}, bias, res, gelu ? 1 : 0};
+    return launch_gemm<false>(In, W, Nout, M, K, Nout, out, kernel_id, st);
+}
 
 bool wide_supported(const Dims &D)
 {

@@ -1,0 +1,132 @@
+"""GPU parity of the whole-block entry point (bra_block_forward, through the C ABI) against
+the float64 block oracle on the same seeded inputs.
+
+Bars: the routing index obeys parity_util.check_routing against the oracle's affinities
+(computed, like the kernel's, from LayerNorm1's output rounded to bf16); with the GPU's routing
+given to the oracle, the block's update Xout - X is within 2e-2 of max|Xout_ref - X| (the bf16
+bar, taken on the update so that the residual copy of X cannot hide an error in a branch).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2303_08810_amd as bra
+from oracle import block as ob
+from parity_util import TOL_BF16_REL, check_routing, to_device, to_numpy
+from synthetic_inputs import (BASE_SEED, CONFIGS, NEXT_CONFIGS, make_block_inputs, make_block_params,
+                              make_inputs)
+
+pytestmark = pytest.mark.gpu
+
+EPS = 1e-6
+
+
+def device_params(P):
+    out = {}
+    for name in bra.BraBlockParams.FIELDS:
+        if name in bra.BraBlockParams.MATRICES:
+            out[name] = to_device(P[name], "bf16")
+        else:
+            out[name] = torch.from_numpy(np.ascontiguousarray(P[name], dtype=np.float32)).cuda()
+    return out
+
+
+def compare_block(Xn, P, S, k, heads, path="auto", images=None, in_place=False, forced=None):
+    print(f"block case shape={Xn.shape} hidden={P['W1'].shape[1]} S={S} k={k} heads={heads} path={path} "
+          f"in_place={in_place} forced={forced is not None}", flush=True)
+    X = to_device(Xn, "bf16")
+    dP = device_params(P)
+    Iin = torch.from_numpy(np.ascontiguousarray(forced, dtype=np.int32)).cuda() if forced is not None else None
+    Xout, Ir = bra.bra_block_forward(X, dP, S, k, heads, eps=EPS, want_Ir=True, path=path, Ir_in=Iin,
+                                     out=X if in_place else None)
+    torch.cuda.synchronize()
+    got, Ir = to_numpy(Xout), Ir.cpu().numpy()
+    sel = np.arange(Xn.shape[0]) if images is None else np.asarray(images)
+    kw = dict(S=S, k=k, heads=heads, eps=EPS, store="bf16", threads=8)
+    if forced is None:
+        free = ob.block_forward(Xn[sel], P, **kw)
+        check_routing(Ir[sel], free["Ar"], k)
+    else:
+        np.testing.assert_array_equal(Ir, forced)
+    ref = ob.block_forward(Xn[sel], P, Ir_in=Ir[sel], **kw)
+    upd_ref = ref["Xout"] - Xn[sel]
+    upd = got[sel].astype(np.float64) - Xn[sel]
+    rel = float(np.abs(upd - upd_ref).max() / np.abs(upd_ref).max())
+    assert rel <= TOL_BF16_REL, f"max|d(Xout - X)| / max|Xout_ref - X| = {rel:.3e} > {TOL_BF16_REL}"
+    return rel
+
+
+def inputs(B, H, W, C, seed, expansion=3):
+    X, Wqkv, Wo, Wlce = make_inputs(B, H, W, C, seed=seed, dtype="bf16")
+    P = make_block_params(C, expansion * C, seed=seed + 1, dtype="bf16")
+    P.update(Wqkv=Wqkv, Wo=Wo, Wlce=Wlce)
+    return X, P
+
+
+# (B, H, W, C, heads, S, k, expansion): one chunk per lane (C <= 512) and several (C = 192, 384,
+# 768, 1024), heads of 32 and 64 channels, token counts that leave a ragged last workgroup,
+# H != W, every BRA pipeline (fused k = 1, 256- and 64-token regions, small regions, general)
+BLOCK_SHAPES = [
+    (2, 28, 28, 64, 2, 7, 4, 3),
+    (3, 56, 56, 64, 2, 7, 1, 3),
+    (1, 14, 14, 256, 8, 7, 16, 3),
+    (2, 28, 28, 128, 4, 7, 4, 4),
+    (1, 64, 32, 64, 2, 4, 2, 3),
+    (3, 7, 7, 512, 16, 7, 49, 3),
+    (1, 14, 14, 384, 12, 7, 16, 3),
+    (1, 12, 20, 192, 6, 4, 3, 3),
+    (1, 16, 16, 768, 12, 8, 12, 3),
+    (1, 8, 8, 1024, 16, 4, 5, 1),
+    (5, 6, 10, 64, 2, 2, 3, 3),
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,S,k,e", BLOCK_SHAPES)
+def test_block_shapes(B, H, W, C, heads, S, k, e):
+    X, P = inputs(B, H, W, C, seed=4000 + C + H + k, expansion=e)
+    compare_block(X, P, S, k, heads)
+
+
+def test_block_generic_family_for_bra():
+    X, P = inputs(2, 14, 14, 64, seed=4100)
+    compare_block(X, P, 7, 4, 2, path="generic")
+
+
+def test_block_in_place_and_forced_routing():
+    X, P = inputs(2, 28, 28, 64, seed=4200)
+    compare_block(X, P, 7, 4, 2, in_place=True)
+    r = np.random.Generator(np.random.PCG64(4201))
+    forced = np.stack([np.stack([r.permutation(49)[:4] for _ in range(49)]) for _ in range(2)]).astype(np.int32)
+    compare_block(X, P, 7, 4, 2, forced=forced)
+
+
+def test_block_repeated_runs_are_bit_identical():
+    X, P = inputs(2, 28, 28, 128, seed=4300)
+    Xd, dP = to_device(X, "bf16"), device_params(P)
+    outs = []
+    for _ in range(4):
+        o = bra.bra_block_forward(Xd, dP, 7, 4, 4, eps=EPS)
+        torch.cuda.synchronize()
+        outs.append(o.view(torch.int16).cpu().numpy().copy())
+    for o in outs[1:]:
+        np.testing.assert_array_equal(o, outs[0])
+
+
+@pytest.mark.parametrize("idx,images", [(2, [0, 31, 63]), (3, [0, 63]), (4, [5, 63]), (6, [0, 1, 62, 63]),
+                                        (8, [7])])
+def test_block_named_workloads_full_size(idx, images):
+    cfg = CONFIGS.get(idx) or NEXT_CONFIGS[idx]
+    X, P = make_block_inputs(cfg)
+    compare_block(X, P, cfg.S, cfg.k, cfg.heads, images=images)
+
+
+def test_block_rejects_what_it_is_not_built_for():
+    X, P = inputs(1, 14, 14, 64, seed=4400)
+    Xd, dP = to_device(X, "bf16"), device_params(P)
+    with pytest.raises(bra.BraError) as e:
+        bra.bra_block_forward(Xd.float(), {k: (v.float() if k in bra.BraBlockParams.MATRICES else v)
+                                           for k, v in dP.items()}, 7, 4, 2)
+    assert e.value.code == -6
+    with pytest.raises(bra.BraError) as e:
+        bra.bra_block_forward(Xd, dP, 7, 4, 2, eps=-1.0)
+    assert e.value.code == -2
