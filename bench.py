@@ -155,6 +155,61 @@ def time_config(cfg, steps, warmup, profile=True):
                 host=host, sets=sets)
 
 
+def time_block(cfg, steps, warmup, expansion=3):
+    """One whole block (position encoding, LayerNorm, BRA, LayerNorm, MLP with e = 3) at a named
+    workload's shape: context beside the headline figure, never `value`."""
+    import numpy as np
+    import torch
+
+    import paper_2303_08810_amd as bra
+    from synthetic_inputs import bf16_bits, make_block_inputs
+
+    X, P = make_block_inputs(cfg, expansion=expansion)
+    bf = lambda a: torch.from_numpy(bf16_bits(a).view(np.int16)).view(torch.bfloat16).cuda()
+    dP = {n: (bf(P[n]) if n in bra.BraBlockParams.MATRICES else torch.from_numpy(P[n]).cuda())
+          for n in bra.BraBlockParams.FIELDS}
+    Xd = bf(X)
+    unit_mb = Xd.numel() * 2 / 1e6
+    sets = max(2, min(24, int(600 / (2 * unit_mb)) + 1))
+    Xs = [Xd] + [torch.roll(Xd, shifts=i, dims=0).contiguous() for i in range(1, sets)]
+    Ys = [torch.empty_like(Xd) for _ in range(sets)]
+    shape = bra.make_shape(cfg.B, cfg.H, cfg.W, cfg.C, cfg.heads, cfg.S, cfg.k, Xd.dtype)
+    hidden = expansion * cfg.C
+    ws = torch.empty(bra.block_workspace_bytes(shape, hidden), dtype=torch.uint8, device="cuda")
+
+    def step(i):
+        bra.bra_block_forward(Xs[i % sets], dP, cfg.S, cfg.k, cfg.heads, ws=ws, out=Ys[i % sets])
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = max((time.perf_counter() - t0) * 1e3, e0.elapsed_time(e1)) / steps
+    bra.profile_begin(steps * 24)
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    kernels = {}
+    for name, t in bra.profile_end(steps * 24):
+        kernels[name] = kernels.get(name, 0.0) + t
+    tokens = cfg.B * cfg.H * cfg.W
+    mlp_flops = 4.0 * tokens * cfg.C * hidden
+    bra_flops = cfg.B * flops_per_image(cfg)["total"]
+    # algorithmic traffic: X in, Xout out; everything between them could stay on the chip
+    return {
+        "images_per_s": round(cfg.B / (ms / 1e3), 1), "ms_per_step": round(ms, 5), "expansion": expansion,
+        "achieved_tflops": round((mlp_flops + bra_flops) / (ms / 1e3) / 1e12, 3),
+        "min_traffic_gbs": round(2 * Xd.numel() * 2 / (ms / 1e3) / 1e9, 1),
+        "kernels_avg_us": {k: round(1e3 * v / steps, 2) for k, v in kernels.items()},
+    }
+
+
 def time_variants(cfg, steps, warmup):
     """Further timings of the same workload, for context (none of them is `value`): repeats of
     the K-step measurement, spatially smooth inputs (concentrated routing), a single input

@@ -2,6 +2,8 @@
 //
 //   k_token_ln<POS>   X1 = X + DWConv3x3(X) + bpos,  Xn = LayerNorm1(X1)      one pass over X
 //   BRA               Y  = BRA(Xn)                   (Eq. 2-7; the kernel family picked for the shape)
+//   C = 64:  k_mlp_fused64     Xout = X2 + MLP(LayerNorm2(X2)), X2 = X1 + Y, in one kernel
+//   otherwise:
 //   k_token_ln<ADD>   X2 = X1 + Y,                   Xn = LayerNorm2(X2)
 //   gemm_bf16         Hd = GELU(Xn W1 + b1)          bias and activation in the product's epilogue
 //   gemm_bf16         Xout = X2 + Hd W2 + b2         bias and residual in the epilogue
@@ -9,6 +11,8 @@
 // The normalisation and residual links follow the pre-norm residual reading stated with the
 // entry point's declaration.
 #include "bra_mfma_dev.h"
+
+#include <stdlib.h>
 
 namespace bra {
 
@@ -21,13 +25,13 @@ constexpr int kPos = 0, kAdd = 1;
 // A token's C channels are shared by G consecutive lanes (G a power of two that divides
 // C / 8, at most 64): lane `sub` owns the 8-channel chunks sub, sub + G, ..  A workgroup has
 // 256 / G token slots and walks `iters` consecutive groups of that many tokens.
-// ONE (C / 8 == G): a lane owns one chunk for every token, so its convolution weights, bias,
-// gamma and beta stay in registers and a token's values never leave them.  Otherwise the
+// ONE (C / 8 == G): a lane owns one chunk for every token, so its bias, gamma and beta stay in
+// registers (the convolution weights in LDS) and a token's values never leave the registers.  Otherwise the
 // values of a lane's chunks wait in a per-lane strip of LDS between the passes.
 // Sum = the pre-norm tensor (X1 or X2), Norm = its LayerNorm; the statistics use the float32
 // values, not the rounded ones that are stored.  Sum may be A itself (ADD): a lane reads the
 // elements it overwrites before it writes them.
-template <int MODE, bool ONE>
+template <int MODE, bool ONE, bool WLDS>
 __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t *__restrict__ Badd,
                                                   const bf16_t *__restrict__ Wpos, const float *__restrict__ bpos,
                                                   const float *__restrict__ gamma, const float *__restrict__ beta,
@@ -39,18 +43,31 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
     const int CH = C / 8, NC = CH / G;
     float *strip = (float *)smem + (size_t)slot * C;       // this token slot's values (not ONE)
     const float c_inv = 1.0f / (float)C;
+    const float *wlds = (const float *)smem + 8 * sub;     // ONE: this lane's weights, [tap][C] in LDS
 
     // the 3x3 weights of 8 channels are 72 consecutive bf16: channel-major, (ky, kx) inside
-    auto load_w = [&](int c0, float (&w)[8][9]) {
+    // they stay packed in 36 registers and are widened where they are used
+    auto load_w = [&](int c0, unsigned (&raw)[36]) {
         const u32x4 *src = (const u32x4 *)(Wpos + (size_t)c0 * 9);
-        unsigned raw[36];
 #pragma unroll
         for (int q = 0; q < 9; ++q) {
             const u32x4 v = src[q];
             raw[4 * q] = v[0]; raw[4 * q + 1] = v[1]; raw[4 * q + 2] = v[2]; raw[4 * q + 3] = v[3];
         }
+    };
+    auto weight = [&](const unsigned (&raw)[36], int e, int t) {
+        const int idx = 9 * e + t;
+        return (idx & 1) ? bf16_hi(raw[idx / 2]) : bf16_lo(raw[idx / 2]);
+    };
+    // the 8 weights of tap t: from the LDS table (ONE) or from the packed registers
+    auto tap_weights = [&](const unsigned (&raw)[36], const float *table, int t, float (&wt)[8]) {
+        if (ONE && WLDS) {
+            const f32x4 a = *(const f32x4 *)(table + t * C), b = *(const f32x4 *)(table + t * C + 4);
+            wt[0] = a[0]; wt[1] = a[1]; wt[2] = a[2]; wt[3] = a[3]; wt[4] = b[0]; wt[5] = b[1]; wt[6] = b[2]; wt[7] = b[3];
+        } else {
 #pragma unroll
-        for (int e = 0; e < 72; ++e) w[e / 9][e % 9] = (e & 1) ? bf16_hi(raw[e / 2]) : bf16_lo(raw[e / 2]);
+            for (int e = 0; e < 8; ++e) wt[e] = weight(raw, e, t);
+        }
     };
     auto load8 = [&](const float *p, float (&v)[8]) {
         const f32x4 a = *(const f32x4 *)p, b = *(const f32x4 *)(p + 4);
@@ -61,7 +78,7 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
         for (int e = 0; e < 4; ++e) { v[2 * e] = bf16_lo(t[e]); v[2 * e + 1] = bf16_hi(t[e]); }
     };
     // the pre-norm values of chunk c0 of token (img, y, x)
-    auto values = [&](long tok, int y, int x, int c0, const float (&w)[8][9], const float (&bias)[8], float (&v)[8]) {
+    auto values = [&](long tok, int y, int x, int c0, const unsigned (&w)[36], const float (&bias)[8], float (&v)[8]) {
         const bf16_t *centre = A + (size_t)tok * C + c0;
         float xc[8];
         unpack(*(const u32x4 *)centre, xc);
@@ -72,21 +89,33 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
             for (int e = 0; e < 8; ++e) v[e] = xc[e] + yv[e];
             return;
         }
+        // all eight neighbours are requested at once from clamped coordinates; those outside
+        // the map (zero padding) are blanked after they arrive
+        u32x4 nb[9];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = fmaf(w[e][4], xc[e], xc[e] + bias[e]);
+        for (int t = 0; t < 9; ++t) {
+            if (t == 4) continue;
+            const int dy = t / 3 - 1, dx = t % 3 - 1;
+            const int yy = min(max(y + dy, 0), H - 1), xx = min(max(x + dx, 0), W - 1);
+            nb[t] = *(const u32x4 *)(centre + ((long)(yy - y) * W + (xx - x)) * C);
+        }
+        {
+            float wt[8];
+            tap_weights(w, wlds, 4, wt);
 #pragma unroll
-        for (int ky = 0; ky < 3; ++ky) {
-            const int yy = y + ky - 1;
-            if (yy < 0 || yy >= H) continue;
+            for (int e = 0; e < 8; ++e) v[e] = fmaf(wt[e], xc[e], xc[e] + bias[e]);
+        }
 #pragma unroll
-            for (int kx = 0; kx < 3; ++kx) {
-                const int xx = x + kx - 1;
-                if ((ky == 1 && kx == 1) || xx < 0 || xx >= W) continue;
-                float nb[8];
-                unpack(*(const u32x4 *)(centre + ((long)(ky - 1) * W + (kx - 1)) * C), nb);
+        for (int t = 0; t < 9; ++t) {
+            if (t == 4) continue;
+            const int dy = t / 3 - 1, dx = t % 3 - 1;
+            const bool inside = (unsigned)(y + dy) < (unsigned)H && (unsigned)(x + dx) < (unsigned)W;
+            const u32x4 z = inside ? nb[t] : u32x4{0u, 0u, 0u, 0u};
+            float f[8], wt[8];
+            unpack(z, f);
+            tap_weights(w, wlds, t, wt);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = fmaf(w[e][3 * ky + kx], nb[e], v[e]);
-            }
+            for (int e = 0; e < 8; ++e) v[e] = fmaf(wt[e], f[e], v[e]);
         }
     };
     auto group_sum = [&](float s) {
@@ -94,13 +123,25 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
         return s;
     };
 
-    float w[8][9], bias[8], gm[8], bt[8];
+    // consecutive workgroups (neighbouring rows of the map) run on one XCD and meet in its L2
+    const long first = (long)swizzled_block() * slots * iters;
+    if (first >= tokens) return;
+    unsigned w[36];
+    float bias[8], gm[8], bt[8];
     if (ONE) {
-        if (MODE == kPos) { load_w(8 * sub, w); load8(bpos + 8 * sub, bias); }
+        if (MODE == kPos) {
+            load8(bpos + 8 * sub, bias);
+            if (WLDS) {
+                // the whole weight tensor waits in LDS as float32 [tap][channel] (at most 18 KB)
+                for (int q = tid; q < C * 9; q += 256) ((float *)smem)[(q % 9) * C + q / 9] = bf16_to_f32(Wpos[q]);
+                __syncthreads();
+            } else {
+                load_w(8 * sub, w);
+            }
+        }
         load8(gamma + 8 * sub, gm);
         load8(beta + 8 * sub, bt);
     }
-    const long first = (long)blockIdx.x * slots * iters;
     for (int it = 0; it < iters; ++it) {
         const long tok_raw = first + (long)it * slots + slot;
         const bool valid = tok_raw < tokens;
@@ -109,6 +150,13 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
         const int y = ry % H;
 
         if (ONE) {
+            // the weights are read again for every token (the address is re-declared as changed,
+            // so that the reads are not moved out of the loop into long-lived registers)
+            if (MODE == kPos && WLDS) asm volatile("" : "+v"(wlds));
+            if (MODE == kPos && !WLDS) {
+#pragma unroll
+                for (int q = 0; q < 36; ++q) asm volatile("" : "+v"(w[q]));
+            }
             float v[8];
             values(tok, y, x, 8 * sub, w, bias, v);
             float s = 0.f;
@@ -162,6 +210,192 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
     }
 }
 
+// X2 = X1 + Y, LayerNorm2, both MLP layers and the last residual link in one kernel for C = 64,
+// hidden = 64 HT: nothing between X1, Y and Xout passes through memory.
+// A wavefront owns 16 tokens at a time, lane (g, i) = token i; everything is formed transposed
+// (outputs x tokens) so that the matrix cores' result layout (rows 4 g .. 4 g + 3 of column i)
+// is again an operand layout:
+//   * the lane reads channels 32 ks + 8 g + (0..7) of X1 and Y (ks = 0, 1), adds and normalises
+//     them (sums over the four lane groups of a token) and packs them: the B operands of
+//     Hd^T = W1^T Xn^T, whose A operands (W1's fragments, contraction slot (g, e) = channel
+//     32 ks + 8 g + e) wait in LDS;
+//   * two result tiles of Hd^T (hidden units 16 t1 + 4 g + jj), after bias and GELU, are packed
+//     as they are: slot (g, e) of contraction step ks2 stands for hidden unit
+//     16 (2 ks2 + e / 4) + 4 g + e % 4, and W2's fragments are laid out to match;
+//   * row 4 g + jj of output tile t stands for channel 32 (t / 2) + 8 g + 4 (t % 2) + jj, so the
+//     lane ends up with the channels it started with: X2 is still in its registers for the
+//     residual link and it stores 16 contiguous bytes per step.
+// The fragments are built in LDS once per workgroup; the wavefronts then walk the 16-token
+// tiles in a grid-stride loop, requesting the next tile's rows before they work on the current.
+template <int HT>
+__global__ __launch_bounds__(256) void k_mlp_fused64(const bf16_t *__restrict__ X1, const bf16_t *__restrict__ Y,
+                                                     const bf16_t *__restrict__ W1, const float *__restrict__ b1,
+                                                     const bf16_t *__restrict__ W2, const float *__restrict__ b2,
+                                                     const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                     bf16_t *__restrict__ Xout, long tokens, float eps)
+{
+    constexpr int C = 64, HID = 64 * HT, NK2 = HID / 32;      // HID / 16 result tiles of the first layer
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *W1f = (bf16_t *)smem;                    // [NT1][2][64 lanes][8]
+    bf16_t *W2f = W1f + (size_t)HID * C;             // [4][NK2][64 lanes][8]
+    float *b1s = (float *)(W2f + (size_t)HID * C);   // [HID]
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave, g = lane / 16, i = lane % 16;
+
+    for (int q = tid; q < C * (HID / 8); q += 256) {             // W1 [C][HID]: row k, columns 8 cg ..
+        const int k = q / (HID / 8), cg = q % (HID / 8);
+        const u32x4 v = *(const u32x4 *)(W1 + (size_t)k * HID + 8 * cg);
+        const int ks = k / 32, kg = (k % 32) / 8, e = k % 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int col = 8 * cg + j, t1 = col / 16, ci = col % 16;
+            const unsigned word = v[j / 2];
+            W1f[(((t1 * 2 + ks) * 64) + 16 * kg + ci) * 8 + e] = (bf16_t)((j & 1) ? word >> 16 : word & 0xffffu);
+        }
+    }
+    for (int q = tid; q < HID * (C / 8); q += 256) {             // W2 [HID][C]: row hid, columns 8 cg ..
+        const int hid = q / (C / 8), cg = q % (C / 8);
+        const u32x4 v = *(const u32x4 *)(W2 + (size_t)hid * C + 8 * cg);
+        const int ks2 = hid / 32, r = hid % 32, kg = (r % 16) / 4, e = 4 * (r / 16) + r % 4;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int out = 8 * cg + j, rem = out % 32;
+            const int t = 2 * (out / 32) + (rem % 8) / 4, ci = 4 * (rem / 8) + rem % 4;
+            const unsigned word = v[j / 2];
+            W2f[(((t * NK2 + ks2) * 64) + 16 * kg + ci) * 8 + e] = (bf16_t)((j & 1) ? word >> 16 : word & 0xffffu);
+        }
+    }
+    for (int q = tid; q < HID; q += 256) b1s[q] = b1[q];
+
+    // this lane's channels 32 ks + 8 g + e: gamma, beta, b2
+    float gm[2][8], bt[2][8], bo[2][8];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int c0 = 32 * ks + 8 * g + 4 * h;
+            const f32x4 a = *(const f32x4 *)(gamma + c0), b = *(const f32x4 *)(beta + c0), c = *(const f32x4 *)(b2 + c0);
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) { gm[ks][4 * h + jj] = a[jj]; bt[ks][4 * h + jj] = b[jj]; bo[ks][4 * h + jj] = c[jj]; }
+        }
+    __syncthreads();
+
+    const long tiles = (tokens + 15) / 16, stride = (long)gridDim.x * 4;
+    long wt = (long)blockIdx.x * 4 + wave;
+    u32x4 xa[2], ya[2];
+    auto request = [&](long tile) {
+        const long tok = min(tile * 16 + i, tokens - 1);         // rows past the end repeat the last; never stored
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            xa[ks] = *(const u32x4 *)(X1 + (size_t)tok * C + 32 * ks + 8 * g);
+            ya[ks] = *(const u32x4 *)(Y + (size_t)tok * C + 32 * ks + 8 * g);
+        }
+    };
+    if (wt < tiles) request(wt);
+    for (; wt < tiles; wt += stride) {
+        // the fragments are read where they are used, tile after tile: the lane's offset is
+        // re-declared as changed so that the reads do not move out of the loop into 200 registers
+        int frag = lane * 8;
+        asm volatile("" : "+v"(frag));
+        float x2[2][8];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x2[ks][2 * e] = bf16_lo(xa[ks][e]) + bf16_lo(ya[ks][e]);
+                x2[ks][2 * e + 1] = bf16_hi(xa[ks][e]) + bf16_hi(ya[ks][e]);
+            }
+        const long tok = wt * 16 + i;
+        if (wt + stride < tiles) request(wt + stride);
+
+        // LayerNorm2 over the token's 64 channels: 16 here, the rest in lanes i + 16, 32, 48
+        float s = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += x2[ks][e];
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        const float mean = s * (1.0f / C);
+        float qq = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { const float d = x2[ks][e] - mean; qq = fmaf(d, d, qq); }
+        qq += __shfl_xor(qq, 16);
+        qq += __shfl_xor(qq, 32);
+        const float rstd = 1.0f / sqrtf(qq * (1.0f / C) + eps);
+        bf16x8 bx[2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = fmaf((x2[ks][e] - mean) * rstd, gm[ks][e], bt[ks][e]);
+            bx[ks] = pack8(v);
+        }
+
+        f32x4 acc2[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc2[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks2 = 0; ks2 < NK2; ++ks2) {
+            float hv[8];
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int t1 = 2 * ks2 + half;
+                f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+                    a = mfma16(*(const bf16x8 *)(W1f + (t1 * 2 + ks) * 512 + frag), bx[ks], a);
+                const f32x4 bv = *(const f32x4 *)(b1s + 16 * t1 + 4 * g);
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) hv[4 * half + jj] = gelu_f32(a[jj] + bv[jj]);
+            }
+            const bf16x8 hb = pack8(hv);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                acc2[t] = mfma16(*(const bf16x8 *)(W2f + (t * NK2 + ks2) * 512 + frag), hb, acc2[t]);
+        }
+        if (tok < tokens) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = acc2[2 * ks + e / 4][e % 4] + bo[ks][e] + x2[ks][e];
+                *(bf16x8 *)(Xout + (size_t)tok * C + 32 * ks + 8 * g) = pack8(v);
+            }
+        }
+    }
+}
+
+template <int HT>
+int launch_mlp_fused64(const Dims &D, const bf16_t *X1, const bf16_t *Y, const bra_block_params &p, bf16_t *Xout,
+                       float eps, hipStream_t st)
+{
+    constexpr size_t smem = (size_t)2 * 64 * HT * 64 * sizeof(bf16_t) + (size_t)64 * HT * sizeof(float);
+    static bool opted = false;
+    if (!opted) {
+        if (hipFuncSetAttribute((const void *)k_mlp_fused64<HT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)smem) != hipSuccess)
+            return BRA_ERR_LAUNCH;
+        opted = true;
+    }
+    const long tokens = (long)D.B * D.N, tiles = (tokens + 15) / 16;
+    const int per_cu = (int)(160 * 1024 / (smem + 1024));            // workgroups that share a compute unit's LDS
+    long grid = 256L * (per_cu < 1 ? 1 : per_cu);
+    if (grid > (tiles + 3) / 4) grid = (tiles + 3) / 4;
+    ProfScope ps(st, K_BLK_MLP_FUSED);
+    hipLaunchKernelGGL((k_mlp_fused64<HT>), dim3((unsigned)grid), dim3(256), smem, st, X1, Y, (const bf16_t *)p.W1, p.b1,
+                       (const bf16_t *)p.W2, p.b2, p.ln2_gamma, p.ln2_beta, Xout, tokens, eps);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+// The single-kernel MLP half exists for C = 64 and hidden = 64, 128, 192 or 256.
+bool mlp_fused_shape(const Dims &D, int hidden)
+{
+    static const bool off = getenv("BRA_BLOCK_UNFUSED") != nullptr;
+    return !off && D.C == 64 && hidden % 64 == 0 && hidden <= 256;
+}
+
 // lanes per token: the largest power of two that divides C / 8, at most 64
 int lanes_per_token(int C)
 {
@@ -178,20 +412,19 @@ int launch_token_ln(const Dims &D, const bf16_t *A, const bf16_t *Badd, const br
     const int G = lanes_per_token(D.C), slots = 256 / G;
     const bool one = D.C / 8 == G;
     // enough workgroups to fill the chip several times over, up to 8 token groups each
-    long iters = tokens / ((long)slots * 4096);
+    static const long target = getenv("BRA_LN_WGS") ? atol(getenv("BRA_LN_WGS")) : 4096;
+    long iters = tokens / ((long)slots * target);
     iters = iters < 1 ? 1 : (iters > 8 ? 8 : iters);
-    const long grid = (tokens + slots * iters - 1) / (slots * iters);
+    const long grid = ((tokens + slots * iters - 1) / (slots * iters) + 7) / 8 * 8;      // whole rounds over the XCDs
+    static const bool wlds = getenv("BRA_LN_WLDS") != nullptr;
     ProfScope ps(st, MODE == kPos ? K_BLK_POS_LN : K_BLK_ADD_LN);
-    if (one) {
-        hipLaunchKernelGGL((k_token_ln<MODE, true>), dim3((unsigned)grid), dim3(256), 0, st, A, Badd,
-                           (const bf16_t *)p.Wpos, p.bpos, gamma, beta, Sum, Norm, D.H, D.W, D.C, tokens, G,
-                           (int)iters, eps);
-    } else {
-        const size_t smem = (size_t)slots * D.C * sizeof(float);      // at most 4 x 4096 floats
-        hipLaunchKernelGGL((k_token_ln<MODE, false>), dim3((unsigned)grid), dim3(256), smem, st, A, Badd,
-                           (const bf16_t *)p.Wpos, p.bpos, gamma, beta, Sum, Norm, D.H, D.W, D.C, tokens, G,
-                           (int)iters, eps);
-    }
+    auto launch = [&](auto kernel, size_t smem) {
+        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), smem, st, A, Badd, (const bf16_t *)p.Wpos, p.bpos,
+                           gamma, beta, Sum, Norm, D.H, D.W, D.C, tokens, G, (int)iters, eps);
+    };
+    if (one && MODE == kPos && wlds) launch(k_token_ln<MODE, true, true>, (size_t)D.C * 9 * sizeof(float));
+    else if (one) launch(k_token_ln<MODE, true, false>, 0);
+    else launch(k_token_ln<MODE, false, false>, (size_t)slots * D.C * sizeof(float));      // at most 4 x 4096 floats
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
@@ -245,6 +478,14 @@ int block_forward(const Dims &D, int hidden, float eps, const void *X, const bra
              ? mfma_forward(D, w.xn, p.Wqkv, p.Wo, p.Wlce, w.y, Ir_out_opt, Ir_in_opt, w.inner, st)
              : generic_forward(D, w.xn, p.Wqkv, p.Wo, p.Wlce, w.y, Ir_out_opt, Ir_in_opt, w.inner, st);
     if (rc != BRA_OK) return rc;
+    if (mlp_fused_shape(D, hidden)) {
+        switch (hidden / 64) {
+        case 1: return launch_mlp_fused64<1>(D, w.x1, w.y, p, (bf16_t *)Xout, eps, st);
+        case 2: return launch_mlp_fused64<2>(D, w.x1, w.y, p, (bf16_t *)Xout, eps, st);
+        case 3: return launch_mlp_fused64<3>(D, w.x1, w.y, p, (bf16_t *)Xout, eps, st);
+        default: return launch_mlp_fused64<4>(D, w.x1, w.y, p, (bf16_t *)Xout, eps, st);
+        }
+    }
     // X2 takes X1's place: every lane reads the elements it overwrites
     rc = launch_token_ln<kAdd>(D, w.x1, w.y, p, p.ln2_gamma, p.ln2_beta, w.x1, w.xn, eps, st);
     if (rc != BRA_OK) return rc;

@@ -51,7 +51,7 @@ enum KernelId {
     K_GEN_POOL = 0, K_GEN_REGION_QK, K_GEN_TOPK, K_GEN_GEMM_QKV, K_GEN_ATTENTION, K_GEN_LCE,
     K_GEN_GEMM_WO, K_MFMA_PREP, K_MFMA_QKV, K_MFMA_ATTENTION, K_MFMA_POOL_QK, K_MFMA_ROUTE_ROWS,
     K_MFMA_FUSED_K1, K_MFMA_ATTN_SMALL, K_MFMA_LCE_ADD, K_MFMA_WO,
-    K_BLK_POS_LN, K_BLK_ADD_LN, K_BLK_MLP_IN, K_BLK_MLP_OUT, K_COUNT
+    K_BLK_POS_LN, K_BLK_ADD_LN, K_BLK_MLP_IN, K_BLK_MLP_OUT, K_BLK_MLP_FUSED, K_COUNT
 };
 
 // Brackets the launches issued during its lifetime with two events on `st` when

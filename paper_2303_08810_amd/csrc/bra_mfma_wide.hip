@@ -81,21 +81,6 @@ struct GemmOut {
     int gelu;
 };
 
-// GELU(t) = t Phi(t).  erf by the rational-exponential approximation of Abramowitz & Stegun
-// 7.1.26 (absolute error below 1.5e-7, far inside what a bf16 result resolves).
-__device__ __forceinline__ float gelu_f32(float t)
-{
-    const float x = fabsf(t) * 0.70710678f;
-    const float u = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
-    float p = fmaf(1.061405429f, u, -1.453152027f);
-    p = fmaf(p, u, 1.421413741f);
-    p = fmaf(p, u, -0.284496736f);
-    p = fmaf(p, u, 0.254829592f);
-    const float tail = p * u * __expf(-x * x);        // 1 - erf(x), x >= 0
-    const float phi = t < 0.f ? 0.5f * tail : 1.0f - 0.5f * tail;
-    return t * phi;
-}
-
 template <bool SPLIT, bool F32OUT = SPLIT>
 __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const bf16_t *__restrict__ W,
                                               int ldw, int M, int K, int Nout, GemmOut out)

@@ -78,6 +78,10 @@ BLOCK_SHAPES = [
     (1, 16, 16, 768, 12, 8, 12, 3),
     (1, 8, 8, 1024, 16, 4, 5, 1),
     (5, 6, 10, 64, 2, 2, 3, 3),
+    (2, 14, 14, 64, 2, 7, 4, 1),
+    (1, 21, 14, 64, 2, 7, 2, 2),
+    (3, 14, 28, 64, 2, 7, 4, 4),
+    (1, 28, 28, 64, 2, 7, 4, 5),
 ]
 
 
