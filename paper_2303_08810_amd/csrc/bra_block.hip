@@ -217,54 +217,52 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
 // is again an operand layout:
 //   * the lane reads channels 32 ks + 8 g + (0..7) of X1 and Y (ks = 0, 1), adds and normalises
 //     them (sums over the four lane groups of a token) and packs them: the B operands of
-//     Hd^T = W1^T Xn^T, whose A operands (W1's fragments, contraction slot (g, e) = channel
-//     32 ks + 8 g + e) wait in LDS;
+//     Hd^T = W1^T Xn^T, whose A operands (contraction slot (g, e) = channel 32 ks + 8 g + e)
+//     come out of a row-major copy of W1 in LDS by the transposing read;
 //   * two result tiles of Hd^T (hidden units 16 t1 + 4 g + jj), after bias and GELU, are packed
 //     as they are: slot (g, e) of contraction step ks2 stands for hidden unit
-//     16 (2 ks2 + e / 4) + 4 g + e % 4, and W2's fragments are laid out to match;
+//     16 (2 ks2 + e / 4) + 4 g + e % 4, and W2's fragments are read from its LDS copy to match;
 //   * row 4 g + jj of output tile t stands for channel 32 (t / 2) + 8 g + 4 (t % 2) + jj, so the
 //     lane ends up with the channels it started with: X2 is still in its registers for the
 //     residual link and it stores 16 contiguous bytes per step.
-// The fragments are built in LDS once per workgroup; the wavefronts then walk the 16-token
+// The weights are copied to LDS once per workgroup; the wavefronts then walk the 16-token
 // tiles in a grid-stride loop, requesting the next tile's rows before they work on the current.
+constexpr int kMlpWaves = 8;
+
 template <int HT>
-__global__ __launch_bounds__(256) void k_mlp_fused64(const bf16_t *__restrict__ X1, const bf16_t *__restrict__ Y,
-                                                     const bf16_t *__restrict__ W1, const float *__restrict__ b1,
-                                                     const bf16_t *__restrict__ W2, const float *__restrict__ b2,
-                                                     const float *__restrict__ gamma, const float *__restrict__ beta,
-                                                     bf16_t *__restrict__ Xout, long tokens, float eps)
+struct MlpSmem {
+    static constexpr int HID = 64 * HT;
+    static constexpr int P1 = HID + 16;      // row pitch of W1 [64][HID] in LDS (bf16 elements)
+    static constexpr int P2 = 64 + 16;       // of W2 [HID][64]
+    static constexpr size_t w2_off = (size_t)64 * P1 * 2;
+    static constexpr size_t b1_off = w2_off + (size_t)HID * P2 * 2;
+    static constexpr size_t bytes = b1_off + (size_t)HID * 4;
+};
+
+template <int HT>
+__global__ __launch_bounds__(64 * kMlpWaves) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void k_mlp_fused64(const bf16_t *__restrict__ X1, const bf16_t *__restrict__ Y, const bf16_t *__restrict__ W1,
+                   const float *__restrict__ b1, const bf16_t *__restrict__ W2, const float *__restrict__ b2,
+                   const float *__restrict__ gamma, const float *__restrict__ beta, bf16_t *__restrict__ Xout,
+                   long tokens, float eps)
 {
-    constexpr int C = 64, HID = 64 * HT, NK2 = HID / 32;      // HID / 16 result tiles of the first layer
+    typedef MlpSmem<HT> SM;
+    constexpr int C = 64, HID = SM::HID, NK2 = HID / 32, P1 = SM::P1, P2 = SM::P2, NTH = 64 * kMlpWaves;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16_t *W1f = (bf16_t *)smem;                    // [NT1][2][64 lanes][8]
-    bf16_t *W2f = W1f + (size_t)HID * C;             // [4][NK2][64 lanes][8]
-    float *b1s = (float *)(W2f + (size_t)HID * C);   // [HID]
+    bf16_t *W1s = (bf16_t *)smem;                       // row-major copies of the weights; the operand
+    bf16_t *W2s = (bf16_t *)(smem + SM::w2_off);        // fragments come out of them by the transposing read
+    float *b1s = (float *)(smem + SM::b1_off);
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave, g = lane / 16, i = lane % 16;
 
-    for (int q = tid; q < C * (HID / 8); q += 256) {             // W1 [C][HID]: row k, columns 8 cg ..
+    for (int q = tid; q < C * (HID / 8); q += NTH) {
         const int k = q / (HID / 8), cg = q % (HID / 8);
-        const u32x4 v = *(const u32x4 *)(W1 + (size_t)k * HID + 8 * cg);
-        const int ks = k / 32, kg = (k % 32) / 8, e = k % 8;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int col = 8 * cg + j, t1 = col / 16, ci = col % 16;
-            const unsigned word = v[j / 2];
-            W1f[(((t1 * 2 + ks) * 64) + 16 * kg + ci) * 8 + e] = (bf16_t)((j & 1) ? word >> 16 : word & 0xffffu);
-        }
+        *(u32x4 *)(W1s + k * P1 + 8 * cg) = *(const u32x4 *)(W1 + (size_t)k * HID + 8 * cg);
     }
-    for (int q = tid; q < HID * (C / 8); q += 256) {             // W2 [HID][C]: row hid, columns 8 cg ..
+    for (int q = tid; q < HID * (C / 8); q += NTH) {
         const int hid = q / (C / 8), cg = q % (C / 8);
-        const u32x4 v = *(const u32x4 *)(W2 + (size_t)hid * C + 8 * cg);
-        const int ks2 = hid / 32, r = hid % 32, kg = (r % 16) / 4, e = 4 * (r / 16) + r % 4;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int out = 8 * cg + j, rem = out % 32;
-            const int t = 2 * (out / 32) + (rem % 8) / 4, ci = 4 * (rem / 8) + rem % 4;
-            const unsigned word = v[j / 2];
-            W2f[(((t * NK2 + ks2) * 64) + 16 * kg + ci) * 8 + e] = (bf16_t)((j & 1) ? word >> 16 : word & 0xffffu);
-        }
+        *(u32x4 *)(W2s + hid * P2 + 8 * cg) = *(const u32x4 *)(W2 + (size_t)hid * C + 8 * cg);
     }
-    for (int q = tid; q < HID; q += 256) b1s[q] = b1[q];
+    for (int q = tid; q < HID; q += NTH) b1s[q] = b1[q];
 
     // this lane's channels 32 ks + 8 g + e: gamma, beta, b2
     float gm[2][8], bt[2][8], bo[2][8];
@@ -279,8 +277,8 @@ __global__ __launch_bounds__(256) void k_mlp_fused64(const bf16_t *__restrict__ 
         }
     __syncthreads();
 
-    const long tiles = (tokens + 15) / 16, stride = (long)gridDim.x * 4;
-    long wt = (long)blockIdx.x * 4 + wave;
+    const long tiles = (tokens + 15) / 16, stride = (long)gridDim.x * kMlpWaves;
+    long wt = (long)blockIdx.x * kMlpWaves + wave;
     u32x4 xa[2], ya[2];
     auto request = [&](long tile) {
         const long tok = min(tile * 16 + i, tokens - 1);         // rows past the end repeat the last; never stored
@@ -292,10 +290,15 @@ __global__ __launch_bounds__(256) void k_mlp_fused64(const bf16_t *__restrict__ 
     };
     if (wt < tiles) request(wt);
     for (; wt < tiles; wt += stride) {
-        // the fragments are read where they are used, tile after tile: the lane's offset is
-        // re-declared as changed so that the reads do not move out of the loop into 200 registers
-        int frag = lane * 8;
-        asm volatile("" : "+v"(frag));
+        // The lane's piece of a transposing read (16 lanes hand in 4 rows x 4 pieces of 4
+        // elements, lane i receives column i of the 4 rows): row i / 4, piece i % 4.
+        //   W1, step ks, tile t1:  rows 32 ks + 8 g + (0..3 | 4..7), columns 16 t1 + (0..15)
+        //   W2, step ks2, tile t:  rows 32 ks2 + 4 g + (0..3) and + 16, columns = the channels
+        //                          32 (t / 2) + 8 (i / 4) + 4 (t % 2) + i % 4 of result row i
+        // The offsets are re-declared as changed for every tile, so that the reads stay where
+        // they are used instead of moving out of the loop into 200 registers.
+        int off1 = (8 * g + i / 4) * P1 + 4 * (i % 4), off2 = (4 * g + i / 4) * P2 + 8 * (i % 4);
+        asm volatile("" : "+v"(off1), "+v"(off2));
         float x2[2][8];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
@@ -333,34 +336,44 @@ __global__ __launch_bounds__(256) void k_mlp_fused64(const bf16_t *__restrict__ 
             bx[ks] = pack8(v);
         }
 
+        // the accumulators start from the biases (and, for the output, from X2)
         f32x4 acc2[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) acc2[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) acc2[t][jj] = bo[t / 2][4 * (t % 2) + jj] + x2[t / 2][4 * (t % 2) + jj];
 #pragma unroll
         for (int ks2 = 0; ks2 < NK2; ++ks2) {
             float hv[8];
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int t1 = 2 * ks2 + half;
-                f32x4 a = {0.f, 0.f, 0.f, 0.f};
+                f32x4 a = *(const f32x4 *)(b1s + 16 * t1 + 4 * g);
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-                    a = mfma16(*(const bf16x8 *)(W1f + (t1 * 2 + ks) * 512 + frag), bx[ks], a);
-                const f32x4 bv = *(const f32x4 *)(b1s + 16 * t1 + 4 * g);
+                for (int ks = 0; ks < 2; ++ks) {
+                    const bf16_t *wp = W1s + off1 + 32 * ks * P1 + 16 * t1;
+                    const u32x2 w0 = __builtin_bit_cast(u32x2, lds_read_tr16(wp));
+                    const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 4 * P1));
+                    a = mfma16(__builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]}), bx[ks], a);
+                }
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) hv[4 * half + jj] = gelu_f32(a[jj] + bv[jj]);
+                for (int jj = 0; jj < 4; ++jj) hv[4 * half + jj] = gelu_f32(a[jj]);
             }
             const bf16x8 hb = pack8(hv);
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
-                acc2[t] = mfma16(*(const bf16x8 *)(W2f + (t * NK2 + ks2) * 512 + frag), hb, acc2[t]);
+            for (int t = 0; t < 4; ++t) {
+                const bf16_t *wp = W2s + off2 + 32 * ks2 * P2 + 32 * (t / 2) + 4 * (t % 2);
+                const u32x2 w0 = __builtin_bit_cast(u32x2, lds_read_tr16(wp));
+                const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 16 * P2));
+                acc2[t] = mfma16(__builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]}), hb, acc2[t]);
+            }
         }
         if (tok < tokens) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 float v[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = acc2[2 * ks + e / 4][e % 4] + bo[ks][e] + x2[ks][e];
+                for (int e = 0; e < 8; ++e) v[e] = acc2[2 * ks + e / 4][e % 4];
                 *(bf16x8 *)(Xout + (size_t)tok * C + 32 * ks + 8 * g) = pack8(v);
             }
         }
@@ -371,7 +384,7 @@ template <int HT>
 int launch_mlp_fused64(const Dims &D, const bf16_t *X1, const bf16_t *Y, const bra_block_params &p, bf16_t *Xout,
                        float eps, hipStream_t st)
 {
-    constexpr size_t smem = (size_t)2 * 64 * HT * 64 * sizeof(bf16_t) + (size_t)64 * HT * sizeof(float);
+    constexpr size_t smem = MlpSmem<HT>::bytes;
     static bool opted = false;
     if (!opted) {
         if (hipFuncSetAttribute((const void *)k_mlp_fused64<HT>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -380,12 +393,11 @@ int launch_mlp_fused64(const Dims &D, const bf16_t *X1, const bf16_t *Y, const b
         opted = true;
     }
     const long tokens = (long)D.B * D.N, tiles = (tokens + 15) / 16;
-    const int per_cu = (int)(160 * 1024 / (smem + 1024));            // workgroups that share a compute unit's LDS
-    long grid = 256L * (per_cu < 1 ? 1 : per_cu);
-    if (grid > (tiles + 3) / 4) grid = (tiles + 3) / 4;
+    long grid = 256L * 2;                                        // two workgroups of 8 wavefronts share a compute unit
+    if (grid > (tiles + kMlpWaves - 1) / kMlpWaves) grid = (tiles + kMlpWaves - 1) / kMlpWaves;
     ProfScope ps(st, K_BLK_MLP_FUSED);
-    hipLaunchKernelGGL((k_mlp_fused64<HT>), dim3((unsigned)grid), dim3(256), smem, st, X1, Y, (const bf16_t *)p.W1, p.b1,
-                       (const bf16_t *)p.W2, p.b2, p.ln2_gamma, p.ln2_beta, Xout, tokens, eps);
+    hipLaunchKernelGGL((k_mlp_fused64<HT>), dim3((unsigned)grid), dim3(64 * kMlpWaves), smem, st, X1, Y,
+                       (const bf16_t *)p.W1, p.b1, (const bf16_t *)p.W2, p.b2, p.ln2_gamma, p.ln2_beta, Xout, tokens, eps);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 

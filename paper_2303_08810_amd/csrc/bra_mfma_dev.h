@@ -55,19 +55,20 @@ __device__ __forceinline__ u32x2 pack4(f32x4 v)
 __device__ __forceinline__ float bf16_lo(unsigned u) { return __builtin_bit_cast(float, u << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
 
-// GELU(t) = t Phi(t).  erf by the rational-exponential approximation of Abramowitz & Stegun
-// 7.1.26 (absolute error below 1.5e-7, far inside what a bf16 result resolves).
+// GELU(t) = t Phi(t) = max(t, 0) - |t| (1 - erf(|t| / sqrt 2)) / 2.  erf by the
+// rational-exponential approximation of Abramowitz & Stegun 7.1.26 (absolute error below
+// 1.5e-7, far inside what a bf16 result resolves), with the constant factors folded in.
 __device__ __forceinline__ float gelu_f32(float t)
 {
-    const float x = fabsf(t) * 0.70710678f;
-    const float u = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
-    float p = fmaf(1.061405429f, u, -1.453152027f);
-    p = fmaf(p, u, 1.421413741f);
-    p = fmaf(p, u, -0.284496736f);
-    p = fmaf(p, u, 0.254829592f);
-    const float half_tail = p * u * (0.5f * __builtin_amdgcn_exp2f(t * t * -0.72134752f));   // (1 - erf(x)) / 2, x >= 0: exp(-x^2) = 2^(-t^2 log2(e) / 2)
-    const float th = t * half_tail;
-    return t < 0.f ? th : t - th;
+    const float a = fabsf(t);
+    const float u = __builtin_amdgcn_rcpf(fmaf(a, 0.3275911f * 0.70710678f, 1.0f));
+    float p = fmaf(0.5f * 1.061405429f, u, 0.5f * -1.453152027f);
+    p = fmaf(p, u, 0.5f * 1.421413741f);
+    p = fmaf(p, u, 0.5f * -0.284496736f);
+    p = fmaf(p, u, 0.5f * 0.254829592f);
+    const float w = t * 0.84932180f;                              // w^2 = t^2 log2(e) / 2
+    const float half_tail = (p * u) * __builtin_amdgcn_exp2f(-(w * w));
+    return fmaxf(t, 0.f) - a * half_tail;
 }
 
 // row / width without an integer division; exact for the small non-negative values
