@@ -108,7 +108,7 @@ int bra_forward(const bra_shape *shape, const void *X, const void *Wqkv, const v
  *     Xout = X2 + GELU(LayerNorm2(X2) W1 + b1) W2 + b2
  * LayerNorm: per token over its C channels, biased variance, eps inside the square root,
  * then gamma, beta.  GELU(t) = t Phi(t) (the exact form; evaluated with an erf approximation
- * of absolute error < 1.5e-7).
+ * of absolute error < 3e-7).
  * bra_block_params is a HOST struct of DEVICE pointers, all required:
  *   Wpos [C,3,3] (channel, ky, kx), W1 [C, hidden], W2 [hidden, C], Wqkv, Wo, Wlce as above,
  *   all of shape->dtype; the vectors bpos, ln*_gamma, ln*_beta, b2 [C] and b1 [hidden] float32.

@@ -229,14 +229,24 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
 // tiles in a grid-stride loop, requesting the next tile's rows before they work on the current.
 constexpr int kMlpWaves = 8;
 
+// LDS copies of the weights, laid out so that a transposing read (per 16 lanes: 4 rows x 4
+// pieces of 8 bytes) of 32 lanes touches every bank once (64 banks of 4 bytes):
+//   W1 [64][HID]: row pitch = 160 bytes modulo 256 (rows 0..3 start 40 banks apart, their four
+//                 adjacent pieces fill 8 banks each), and 128 bytes more after every 8 rows
+//                 (the neighbouring lane group reads 8 rows further on);
+//   W2 [HID][64]: row pitch 192 bytes (its pieces are 16 bytes apart and fill half of a 64-byte
+//                 span), and 8 bytes more after every 4 rows (the neighbouring lane group, 4 rows
+//                 further on, fills the other half).
 template <int HT>
 struct MlpSmem {
     static constexpr int HID = 64 * HT;
-    static constexpr int P1 = HID + 16;      // row pitch of W1 [64][HID] in LDS (bf16 elements)
-    static constexpr int P2 = 64 + 16;       // of W2 [HID][64]
-    static constexpr size_t w2_off = (size_t)64 * P1 * 2;
-    static constexpr size_t b1_off = w2_off + (size_t)HID * P2 * 2;
+    static constexpr int P1 = HID + ((HT % 2) ? 16 : 80);      // bf16 elements
+    static constexpr int G1 = 64;                              // extra elements per 8 rows
+    static constexpr int P2 = 96, G2 = 4;                      // W2: pitch, extra elements per 4 rows
+    static constexpr size_t w2_off = (size_t)(64 * P1 + 8 * G1) * 2;
+    static constexpr size_t b1_off = w2_off + (size_t)(HID * P2 + (HID / 4) * G2) * 2;
     static constexpr size_t bytes = b1_off + (size_t)HID * 4;
+    static_assert((P1 / 2) % 64 == 40 && w2_off % 16 == 0 && b1_off % 16 == 0, "layout");
 };
 
 template <int HT>
@@ -247,7 +257,8 @@ void k_mlp_fused64(const bf16_t *__restrict__ X1, const bf16_t *__restrict__ Y, 
                    long tokens, float eps)
 {
     typedef MlpSmem<HT> SM;
-    constexpr int C = 64, HID = SM::HID, NK2 = HID / 32, P1 = SM::P1, P2 = SM::P2, NTH = 64 * kMlpWaves;
+    constexpr int C = 64, HID = SM::HID, NK2 = HID / 32, P1 = SM::P1, G1 = SM::G1, P2 = SM::P2, G2 = SM::G2;
+    constexpr int NTH = 64 * kMlpWaves;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *W1s = (bf16_t *)smem;                       // row-major copies of the weights; the operand
     bf16_t *W2s = (bf16_t *)(smem + SM::w2_off);        // fragments come out of them by the transposing read
@@ -256,11 +267,14 @@ void k_mlp_fused64(const bf16_t *__restrict__ X1, const bf16_t *__restrict__ Y, 
 
     for (int q = tid; q < C * (HID / 8); q += NTH) {
         const int k = q / (HID / 8), cg = q % (HID / 8);
-        *(u32x4 *)(W1s + k * P1 + 8 * cg) = *(const u32x4 *)(W1 + (size_t)k * HID + 8 * cg);
+        *(u32x4 *)(W1s + k * P1 + (k / 8) * G1 + 8 * cg) = *(const u32x4 *)(W1 + (size_t)k * HID + 8 * cg);
     }
     for (int q = tid; q < HID * (C / 8); q += NTH) {
         const int hid = q / (C / 8), cg = q % (C / 8);
-        *(u32x4 *)(W2s + hid * P2 + 8 * cg) = *(const u32x4 *)(W2 + (size_t)hid * C + 8 * cg);
+        const u32x4 v = *(const u32x4 *)(W2 + (size_t)hid * C + 8 * cg);
+        u32x2 *dst = (u32x2 *)(W2s + hid * P2 + (hid / 4) * G2 + 8 * cg);      // 8-byte aligned only
+        dst[0] = u32x2{v[0], v[1]};
+        dst[1] = u32x2{v[2], v[3]};
     }
     for (int q = tid; q < HID; q += NTH) b1s[q] = b1[q];
 
@@ -278,7 +292,9 @@ void k_mlp_fused64(const bf16_t *__restrict__ X1, const bf16_t *__restrict__ Y, 
     __syncthreads();
 
     const long tiles = (tokens + 15) / 16, stride = (long)gridDim.x * kMlpWaves;
-    long wt = (long)blockIdx.x * kMlpWaves + wave;
+    // tile = round * (8 grid) + wave * grid + block: the tiles of the last, partial round go to
+    // one wavefront each of as many workgroups as possible, not to all wavefronts of a few
+    long wt = (long)wave * gridDim.x + blockIdx.x;
     u32x4 xa[2], ya[2];
     auto request = [&](long tile) {
         const long tok = min(tile * 16 + i, tokens - 1);         // rows past the end repeat the last; never stored
@@ -297,7 +313,7 @@ void k_mlp_fused64(const bf16_t *__restrict__ X1, const bf16_t *__restrict__ Y, 
         //                          32 (t / 2) + 8 (i / 4) + 4 (t % 2) + i % 4 of result row i
         // The offsets are re-declared as changed for every tile, so that the reads stay where
         // they are used instead of moving out of the loop into 200 registers.
-        int off1 = (8 * g + i / 4) * P1 + 4 * (i % 4), off2 = (4 * g + i / 4) * P2 + 8 * (i % 4);
+        int off1 = (8 * g + i / 4) * P1 + g * G1 + 4 * (i % 4), off2 = (4 * g + i / 4) * P2 + g * G2 + 8 * (i % 4);
         asm volatile("" : "+v"(off1), "+v"(off2));
         float x2[2][8];
 #pragma unroll
@@ -351,7 +367,7 @@ void k_mlp_fused64(const bf16_t *__restrict__ X1, const bf16_t *__restrict__ Y, 
                 f32x4 a = *(const f32x4 *)(b1s + 16 * t1 + 4 * g);
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
-                    const bf16_t *wp = W1s + off1 + 32 * ks * P1 + 16 * t1;
+                    const bf16_t *wp = W1s + off1 + ks * (32 * P1 + 4 * G1) + 16 * t1;
                     const u32x2 w0 = __builtin_bit_cast(u32x2, lds_read_tr16(wp));
                     const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 4 * P1));
                     a = mfma16(__builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]}), bx[ks], a);
@@ -362,9 +378,9 @@ void k_mlp_fused64(const bf16_t *__restrict__ X1, const bf16_t *__restrict__ Y, 
             const bf16x8 hb = pack8(hv);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const bf16_t *wp = W2s + off2 + 32 * ks2 * P2 + 32 * (t / 2) + 4 * (t % 2);
+                const bf16_t *wp = W2s + off2 + ks2 * (32 * P2 + 8 * G2) + 32 * (t / 2) + 4 * (t % 2);
                 const u32x2 w0 = __builtin_bit_cast(u32x2, lds_read_tr16(wp));
-                const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 16 * P2));
+                const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 16 * P2 + 4 * G2));
                 acc2[t] = mfma16(__builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]}), hb, acc2[t]);
             }
         }
@@ -424,7 +440,7 @@ int launch_token_ln(const Dims &D, const bf16_t *A, const bf16_t *Badd, const br
     const int G = lanes_per_token(D.C), slots = 256 / G;
     const bool one = D.C / 8 == G;
     // enough workgroups to fill the chip several times over, up to 8 token groups each
-    static const long target = getenv("BRA_LN_WGS") ? atol(getenv("BRA_LN_WGS")) : 4096;
+    static const long target = getenv("BRA_LN_WGS") ? atol(getenv("BRA_LN_WGS")) : 2048;
     long iters = tokens / ((long)slots * target);
     iters = iters < 1 ? 1 : (iters > 8 ? 8 : iters);
     const long grid = ((tokens + slots * iters - 1) / (slots * iters) + 7) / 8 * 8;      // whole rounds over the XCDs

@@ -55,20 +55,25 @@ __device__ __forceinline__ u32x2 pack4(f32x4 v)
 __device__ __forceinline__ float bf16_lo(unsigned u) { return __builtin_bit_cast(float, u << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
 
-// GELU(t) = t Phi(t) = max(t, 0) - |t| (1 - erf(|t| / sqrt 2)) / 2.  erf by the
-// rational-exponential approximation of Abramowitz & Stegun 7.1.26 (absolute error below
-// 1.5e-7, far inside what a bf16 result resolves), with the constant factors folded in.
+// GELU(t) = t Phi(t) = t / 2 + |t| (1 - erfc(|t| / sqrt 2)) / 2.  erfc by the approximation of
+// Abramowitz & Stegun 7.1.28, erfc(x) = (1 + a1 x + .. + a6 x^6)^-16 (absolute error below
+// 3e-7, far inside what a bf16 result resolves; one reciprocal is its only slow instruction);
+// the coefficients below are a_k / 2^(k/2), so that the polynomial takes |t| itself.
 __device__ __forceinline__ float gelu_f32(float t)
 {
     const float a = fabsf(t);
-    const float u = __builtin_amdgcn_rcpf(fmaf(a, 0.3275911f * 0.70710678f, 1.0f));
-    float p = fmaf(0.5f * 1.061405429f, u, 0.5f * -1.453152027f);
-    p = fmaf(p, u, 0.5f * 1.421413741f);
-    p = fmaf(p, u, 0.5f * -0.284496736f);
-    p = fmaf(p, u, 0.5f * 0.254829592f);
-    const float w = t * 0.84932180f;                              // w^2 = t^2 log2(e) / 2
-    const float half_tail = (p * u) * __builtin_amdgcn_exp2f(-(w * w));
-    return fmaxf(t, 0.f) - a * half_tail;
+    float p = fmaf(5.382975000e-06f, a, 4.889063564e-05f);
+    p = fmaf(p, a, 3.800357500e-05f);
+    p = fmaf(p, a, 3.277626324e-03f);
+    p = fmaf(p, a, 2.114100615e-02f);
+    p = fmaf(p, a, 4.986734697e-02f);
+    p = fmaf(p, a, 1.0f);
+    p *= p;
+    p *= p;
+    p *= p;
+    p *= p;                                                  // overflows to infinity for large |t|: erfc = 0
+    const float q = fmaf(__builtin_amdgcn_rcpf(p), -0.5f, 0.5f);
+    return fmaf(a, q, 0.5f * t);
 }
 
 // row / width without an integer division; exact for the small non-negative values
