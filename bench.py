@@ -352,6 +352,8 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="named workload index 1..5 (default 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other named workloads")
+    ap.add_argument("--no-block", action="store_true",
+                    help="skip the whole-block timings (position encoding, LayerNorm, BRA, MLP)")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip the context timings (repeats, smooth inputs, hot cache, graph replay)")
     ap.add_argument("--calibrate", action="store_true",
@@ -412,6 +414,15 @@ def main():
                 "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in sm.items()},
             }
         line["other_workloads"] = others
+    if not args.no_block:
+        # one whole block around BRA at the bf16 workloads' shapes (context, never `value`)
+        blocks = {}
+        for idx, c in {**CONFIGS, **NEXT_CONFIGS}.items():
+            if c.dtype != "bf16":
+                continue
+            n = args.steps if idx == args.workload else max(20, args.steps // 4)
+            blocks[c.name] = time_block(c, n, n)
+        line["block_forward"] = blocks
     if args.calibrate:
         src = torch.empty(CALIBRATION_BYTES, dtype=torch.uint8, device="cuda").random_()
         dst = torch.empty_like(src)

@@ -25,13 +25,13 @@ constexpr int kPos = 0, kAdd = 1;
 // A token's C channels are shared by G consecutive lanes (G a power of two that divides
 // C / 8, at most 64): lane `sub` owns the 8-channel chunks sub, sub + G, ..  A workgroup has
 // 256 / G token slots and walks `iters` consecutive groups of that many tokens.
-// ONE (C / 8 == G): a lane owns one chunk for every token, so its bias, gamma and beta stay in
-// registers (the convolution weights in LDS) and a token's values never leave the registers.  Otherwise the
+// ONE (C / 8 == G): a lane owns one chunk for every token, so its convolution weights (packed),
+// bias, gamma and beta stay in registers and a token's values never leave them.  Otherwise the
 // values of a lane's chunks wait in a per-lane strip of LDS between the passes.
 // Sum = the pre-norm tensor (X1 or X2), Norm = its LayerNorm; the statistics use the float32
 // values, not the rounded ones that are stored.  Sum may be A itself (ADD): a lane reads the
 // elements it overwrites before it writes them.
-template <int MODE, bool ONE, bool WLDS>
+template <int MODE, bool ONE>
 __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t *__restrict__ Badd,
                                                   const bf16_t *__restrict__ Wpos, const float *__restrict__ bpos,
                                                   const float *__restrict__ gamma, const float *__restrict__ beta,
@@ -43,7 +43,6 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
     const int CH = C / 8, NC = CH / G;
     float *strip = (float *)smem + (size_t)slot * C;       // this token slot's values (not ONE)
     const float c_inv = 1.0f / (float)C;
-    const float *wlds = (const float *)smem + 8 * sub;     // ONE: this lane's weights, [tap][C] in LDS
 
     // the 3x3 weights of 8 channels are 72 consecutive bf16: channel-major, (ky, kx) inside
     // they stay packed in 36 registers and are widened where they are used
@@ -59,15 +58,9 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
         const int idx = 9 * e + t;
         return (idx & 1) ? bf16_hi(raw[idx / 2]) : bf16_lo(raw[idx / 2]);
     };
-    // the 8 weights of tap t: from the LDS table (ONE) or from the packed registers
-    auto tap_weights = [&](const unsigned (&raw)[36], const float *table, int t, float (&wt)[8]) {
-        if (ONE && WLDS) {
-            const f32x4 a = *(const f32x4 *)(table + t * C), b = *(const f32x4 *)(table + t * C + 4);
-            wt[0] = a[0]; wt[1] = a[1]; wt[2] = a[2]; wt[3] = a[3]; wt[4] = b[0]; wt[5] = b[1]; wt[6] = b[2]; wt[7] = b[3];
-        } else {
+    auto tap_weights = [&](const unsigned (&raw)[36], int t, float (&wt)[8]) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) wt[e] = weight(raw, e, t);
-        }
+        for (int e = 0; e < 8; ++e) wt[e] = weight(raw, e, t);
     };
     auto load8 = [&](const float *p, float (&v)[8]) {
         const f32x4 a = *(const f32x4 *)p, b = *(const f32x4 *)(p + 4);
@@ -89,31 +82,30 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
             for (int e = 0; e < 8; ++e) v[e] = xc[e] + yv[e];
             return;
         }
-        // all eight neighbours are requested at once from clamped coordinates; those outside
-        // the map (zero padding) are blanked after they arrive
+        // all eight neighbours are requested at once; one outside the map (zero padding) is
+        // read from the nearest row / column inside instead and blanked after it arrives
+        const bool in_y[3] = {y > 0, true, y < H - 1}, in_x[3] = {x > 0, true, x < W - 1};
+        const int off_y[3] = {in_y[0] ? -W * C : 0, 0, in_y[2] ? W * C : 0};
+        const int off_x[3] = {in_x[0] ? -C : 0, 0, in_x[2] ? C : 0};
         u32x4 nb[9];
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
             if (t == 4) continue;
-            const int dy = t / 3 - 1, dx = t % 3 - 1;
-            const int yy = min(max(y + dy, 0), H - 1), xx = min(max(x + dx, 0), W - 1);
-            nb[t] = *(const u32x4 *)(centre + ((long)(yy - y) * W + (xx - x)) * C);
+            nb[t] = *(const u32x4 *)(centre + (off_y[t / 3] + off_x[t % 3]));
         }
         {
             float wt[8];
-            tap_weights(w, wlds, 4, wt);
+            tap_weights(w, 4, wt);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = fmaf(wt[e], xc[e], xc[e] + bias[e]);
         }
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
             if (t == 4) continue;
-            const int dy = t / 3 - 1, dx = t % 3 - 1;
-            const bool inside = (unsigned)(y + dy) < (unsigned)H && (unsigned)(x + dx) < (unsigned)W;
-            const u32x4 z = inside ? nb[t] : u32x4{0u, 0u, 0u, 0u};
+            const u32x4 z = (in_y[t / 3] && in_x[t % 3]) ? nb[t] : u32x4{0u, 0u, 0u, 0u};
             float f[8], wt[8];
             unpack(z, f);
-            tap_weights(w, wlds, t, wt);
+            tap_weights(w, t, wt);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = fmaf(wt[e], f[e], v[e]);
         }
@@ -131,13 +123,7 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
     if (ONE) {
         if (MODE == kPos) {
             load8(bpos + 8 * sub, bias);
-            if (WLDS) {
-                // the whole weight tensor waits in LDS as float32 [tap][channel] (at most 18 KB)
-                for (int q = tid; q < C * 9; q += 256) ((float *)smem)[(q % 9) * C + q / 9] = bf16_to_f32(Wpos[q]);
-                __syncthreads();
-            } else {
-                load_w(8 * sub, w);
-            }
+            load_w(8 * sub, w);
         }
         load8(gamma + 8 * sub, gm);
         load8(beta + 8 * sub, bt);
@@ -150,10 +136,9 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
         const int y = ry % H;
 
         if (ONE) {
-            // the weights are read again for every token (the address is re-declared as changed,
-            // so that the reads are not moved out of the loop into long-lived registers)
-            if (MODE == kPos && WLDS) asm volatile("" : "+v"(wlds));
-            if (MODE == kPos && !WLDS) {
+            if (MODE == kPos) {
+                // the packed weights are re-declared as changed, so that their widened forms
+                // (72 more registers) are formed where they are used instead of kept across tokens
 #pragma unroll
                 for (int q = 0; q < 36; ++q) asm volatile("" : "+v"(w[q]));
             }
@@ -444,15 +429,13 @@ int launch_token_ln(const Dims &D, const bf16_t *A, const bf16_t *Badd, const br
     long iters = tokens / ((long)slots * target);
     iters = iters < 1 ? 1 : (iters > 8 ? 8 : iters);
     const long grid = ((tokens + slots * iters - 1) / (slots * iters) + 7) / 8 * 8;      // whole rounds over the XCDs
-    static const bool wlds = getenv("BRA_LN_WLDS") != nullptr;
     ProfScope ps(st, MODE == kPos ? K_BLK_POS_LN : K_BLK_ADD_LN);
     auto launch = [&](auto kernel, size_t smem) {
         hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), smem, st, A, Badd, (const bf16_t *)p.Wpos, p.bpos,
                            gamma, beta, Sum, Norm, D.H, D.W, D.C, tokens, G, (int)iters, eps);
     };
-    if (one && MODE == kPos && wlds) launch(k_token_ln<MODE, true, true>, (size_t)D.C * 9 * sizeof(float));
-    else if (one) launch(k_token_ln<MODE, true, false>, 0);
-    else launch(k_token_ln<MODE, false, false>, (size_t)slots * D.C * sizeof(float));      // at most 4 x 4096 floats
+    if (one) launch(k_token_ln<MODE, true>, 0);
+    else launch(k_token_ln<MODE, false>, (size_t)slots * D.C * sizeof(float));      // at most 4 x 4096 floats
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
