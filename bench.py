@@ -210,6 +210,35 @@ def time_block(cfg, steps, warmup, expansion=3):
     }
 
 
+def time_padded(steps, warmup):
+    """bra_forward_padded on a detection-like first-stage map that S = 16 does not divide
+    (B = 2, 200 x 300, C = 64, k = 4; padded to 208 x 304 inside): context, never `value`."""
+    import numpy as np
+    import torch
+
+    import paper_2303_08810_amd as bra
+    from synthetic_inputs import BASE_SEED, bf16_bits, make_inputs
+
+    B, H, W, C, heads, S, k = 2, 200, 300, 64, 2, 16, 4
+    arrs = make_inputs(B, H, W, C, seed=BASE_SEED + 100, dtype="bf16")
+    X, Wqkv, Wo, Wlce = (torch.from_numpy(bf16_bits(a).view(np.int16)).view(torch.bfloat16).cuda() for a in arrs)
+
+    def step():
+        bra.bra_forward_padded(X, Wqkv, Wo, Wlce, S, k, heads)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    return {"workload": f"B={B} H={H} W={W} C={C} heads={heads} S={S} k={k} bf16, padded to 208x304",
+            "images_per_s": round(B / (ms / 1e3), 1), "ms_per_step": round(ms, 5),
+            "note": "includes the binding's workspace and output allocation per call"}
+
+
 def time_variants(cfg, steps, warmup):
     """Further timings of the same workload, for context (none of them is `value`): repeats of
     the K-step measurement, spatially smooth inputs (concentrated routing), a single input
@@ -423,6 +452,7 @@ def main():
             n = args.steps if idx == args.workload else max(20, args.steps // 4)
             blocks[c.name] = time_block(c, n, n)
         line["block_forward"] = blocks
+        line["padded_forward"] = time_padded(max(20, args.steps // 4), max(20, args.steps // 4))
     if args.calibrate:
         src = torch.empty(CALIBRATION_BYTES, dtype=torch.uint8, device="cuda").random_()
         dst = torch.empty_like(src)

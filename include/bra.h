@@ -99,6 +99,20 @@ int bra_forward(const bra_shape *shape, const void *X, const void *Wqkv, const v
                 const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
                 void *ws, size_t ws_bytes, void *hip_stream);
 
+/* BRA on a map whose sides S does not divide (appendix on the choice of S and k: S is picked
+ * as a divisor of the training size so that no padding is needed; other sizes are padded).
+ * shape->H, shape->W are the caller's map and need not be multiples of S.  Reading of the
+ * padding, which the paper does not spell out: zero tokens are appended at the bottom and at
+ * the right up to Hp = ceil(H / S) S, Wp = ceil(W / S) S; steps 1-7 run on the padded map
+ * (a zero token has zero Q, K, V: it takes part in its region's means, is a key with logit 0 and
+ * value 0, and LCE sees it like its own zero padding); Y [B, H, W, C] is the top-left part of
+ * the result.  Ir [B, S*S, k] indexes the regions of the padded map.  When S divides H and W this
+ * is bra_forward.  Workspace size from bra_padded_workspace_bytes.  Errors as bra_forward. */
+int bra_padded_workspace_bytes(const bra_shape *shape, size_t *out_bytes);
+int bra_forward_padded(const bra_shape *shape, const void *X, const void *Wqkv, const void *Wo,
+                       const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
+                       void *ws, size_t ws_bytes, void *hip_stream);
+
 /* One whole BiFormer block around BRA (Sec. 3.4): a 3x3 depth-wise convolution at the start
  * encodes relative position, then the BRA module and a 2-layer MLP (expansion ratio e,
  * hidden = e C channels) follow.  The figure that fixes normalisation and residual links is

@@ -96,3 +96,18 @@ def bra_forward(X, Wqkv, Wo, Wlce, *, S, k, heads, scale=None, Ir_in=None, preci
     if Lce is not None:
         out["Lce"] = Lce
     return out
+
+
+def bra_forward_padded(X, Wqkv, Wo, Wlce, *, S, k, heads, scale=None, Ir_in=None, precision="f64", threads=1):
+    """BRA on a map whose sides S does not divide (appendix on the choice of S and k: other sizes
+    than multiples of S are padded).  Reading: zero tokens are appended at the bottom and at the
+    right up to the next multiples of S, the layer runs on the padded map, and the top-left
+    H x W part of its output is returned; "Ir" and "Ar" refer to the padded map's regions."""
+    X = np.asarray(X)
+    B, H, W, C = X.shape
+    ph, pw = (-H) % S, (-W) % S
+    Xp = np.pad(X, ((0, 0), (0, ph), (0, pw), (0, 0)))
+    out = bra_forward(Xp, Wqkv, Wo, Wlce, S=S, k=k, heads=heads, scale=scale, Ir_in=Ir_in, precision=precision,
+                      threads=threads)
+    out["Y"] = np.ascontiguousarray(out["Y"][:, :H, :W, :])
+    return out

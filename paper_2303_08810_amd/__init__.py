@@ -18,7 +18,8 @@ BRA_F32, BRA_BF16 = 0, 1
 PATH_AUTO, PATH_GENERIC, PATH_MFMA = 0, 1, 2
 _PATHS = {"auto": PATH_AUTO, "generic": PATH_GENERIC, "mfma": PATH_MFMA}
 
-EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_block_workspace_bytes",
+EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_padded_workspace_bytes",
+           "bra_forward_padded", "bra_block_workspace_bytes",
            "bra_block_forward", "bra_strerror", "bra_version",
            "bra_profile_begin", "bra_profile_end", "bra_kernel_name", "bra_util_copy",
            "bra_util_read", "bra_util_mfma")
@@ -62,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.bra_route.argtypes = [ctypes.POINTER(BraShape), vp, vp, vp, vp, vp, sz, vp]
         L.bra_forward.restype = ctypes.c_int
         L.bra_forward.argtypes = [ctypes.POINTER(BraShape), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.bra_padded_workspace_bytes.restype = ctypes.c_int
+        L.bra_padded_workspace_bytes.argtypes = [ctypes.POINTER(BraShape), ctypes.POINTER(sz)]
+        L.bra_forward_padded.restype = ctypes.c_int
+        L.bra_forward_padded.argtypes = [ctypes.POINTER(BraShape), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.bra_block_workspace_bytes.restype = ctypes.c_int
         L.bra_block_workspace_bytes.argtypes = [ctypes.POINTER(BraShape), ctypes.c_int32, ctypes.POINTER(sz)]
         L.bra_block_forward.restype = ctypes.c_int
@@ -167,6 +172,25 @@ def bra_forward(X, Wqkv, Wo, Wlce, S, k, heads, *, scale=None, Ir_in=None, want_
             raise ValueError("Ir_in must be a contiguous int32 [B, S*S, k] device tensor")
     _check(lib().bra_forward(ctypes.byref(shape), _ptr(X), _ptr(Wqkv), _ptr(Wo), _ptr(Wlce), _ptr(Y),
                              _ptr(Ir), _ptr(Ir_in), _ptr(ws), ws.numel(), _stream(X.device)))
+    return (Y, Ir) if want_Ir else Y
+
+
+def bra_forward_padded(X, Wqkv, Wo, Wlce, S, k, heads, *, scale=None, Ir_in=None, want_Ir=False, path="auto"):
+    """BRA on a map whose sides S need not divide: zero tokens are appended at the bottom and right,
+    Y is the top-left H x W part of the result (see include/bra.h)."""
+    B, H, W, C = _check_inputs(X, Wqkv, Wo, Wlce)
+    shape = make_shape(B, H, W, C, heads, S, k, X.dtype, scale, path)
+    need = ctypes.c_size_t(0)
+    _check(lib().bra_padded_workspace_bytes(ctypes.byref(shape), ctypes.byref(need)))
+    ws = torch.empty(max(need.value, 256), dtype=torch.uint8, device=X.device)
+    Y = torch.empty_like(X)
+    Ir = torch.empty((B, S * S, k), dtype=torch.int32, device=X.device) if want_Ir else None
+    if Ir_in is not None:
+        if not (Ir_in.is_cuda and Ir_in.is_contiguous() and Ir_in.dtype == torch.int32
+                and tuple(Ir_in.shape) == (B, S * S, k)):
+            raise ValueError("Ir_in must be a contiguous int32 [B, S*S, k] device tensor")
+    _check(lib().bra_forward_padded(ctypes.byref(shape), _ptr(X), _ptr(Wqkv), _ptr(Wo), _ptr(Wlce), _ptr(Y),
+                                    _ptr(Ir), _ptr(Ir_in), _ptr(ws), ws.numel(), _stream(X.device)))
     return (Y, Ir) if want_Ir else Y
 
 

@@ -35,6 +35,18 @@ static int pick_path(const bra_shape *s, const Dims &D)
     return generic_supported(D) ? BRA_PATH_GENERIC : BRA_ERR_UNSUPPORTED;
 }
 
+// The shape with H and W rounded up to multiples of S (the map after zero padding).
+static int make_padded_dims(const bra_shape *s, Dims &Dp)
+{
+    if (!s) return BRA_ERR_NULL;
+    if (s->H < 1 || s->W < 1 || s->S < 1 || s->S > 1024) return BRA_ERR_SHAPE;
+    if (s->H > (1 << 24) || s->W > (1 << 24)) return BRA_ERR_SHAPE;
+    bra_shape p = *s;
+    p.H = (s->H + s->S - 1) / s->S * s->S;
+    p.W = (s->W + s->S - 1) / s->S * s->S;
+    return make_dims(&p, Dp);
+}
+
 static bool ws_ok(const void *ws, size_t have, size_t need)
 {
     return ws && ((uintptr_t)ws % 256 == 0) && have >= need;
@@ -90,6 +102,41 @@ int bra_forward(const bra_shape *shape, const void *X, const void *Wqkv, const v
     if (path == BRA_PATH_MFMA)
         return mfma_forward(D, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, st);
     return generic_forward(D, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, st);
+}
+
+int bra_padded_workspace_bytes(const bra_shape *shape, size_t *out_bytes)
+{
+    if (!out_bytes) return BRA_ERR_NULL;
+    Dims Dp;
+    int rc = make_padded_dims(shape, Dp);
+    if (rc != BRA_OK) return rc;
+    bra_shape ps = *shape;
+    ps.H = Dp.H; ps.W = Dp.W;
+    int path = pick_path(&ps, Dp);
+    if (path < 0) return path;
+    const size_t inner = (path == BRA_PATH_MFMA) ? mfma_workspace_bytes(Dp) : generic_workspace_bytes(Dp);
+    *out_bytes = (Dp.H == shape->H && Dp.W == shape->W) ? inner : padded_workspace_bytes(Dp, inner);
+    return BRA_OK;
+}
+
+int bra_forward_padded(const bra_shape *shape, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
+                       void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, size_t ws_bytes,
+                       void *hip_stream)
+{
+    Dims Dp;
+    int rc = make_padded_dims(shape, Dp);
+    if (rc != BRA_OK) return rc;
+    if (!X || !Wqkv || !Wo || !Wlce || !Y) return BRA_ERR_NULL;
+    bra_shape ps = *shape;
+    ps.H = Dp.H; ps.W = Dp.W;
+    if (Dp.H == shape->H && Dp.W == shape->W)
+        return bra_forward(&ps, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, ws_bytes, hip_stream);
+    int path = pick_path(&ps, Dp);
+    if (path < 0) return path;
+    const size_t inner = (path == BRA_PATH_MFMA) ? mfma_workspace_bytes(Dp) : generic_workspace_bytes(Dp);
+    if (!ws_ok(ws, ws_bytes, padded_workspace_bytes(Dp, inner))) return BRA_ERR_WORKSPACE;
+    return padded_forward(Dp, shape->H, shape->W, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, path,
+                          (hipStream_t)hip_stream);
 }
 
 int bra_block_workspace_bytes(const bra_shape *shape, int32_t hidden, size_t *out_bytes)

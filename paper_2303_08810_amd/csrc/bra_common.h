@@ -94,6 +94,11 @@ int mfma_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo,
 int gemm_bf16(const bf16_t *In, const bf16_t *W, long M, int K, int Nout, bf16_t *Out, const float *bias,
               const bf16_t *res, bool gelu, int kernel_id, hipStream_t st);
 
+// Maps whose sides S does not divide (bra_pad.hip): Dp describes the zero-padded map.
+size_t padded_workspace_bytes(const Dims &Dp, size_t bra_bytes);
+int padded_forward(const Dims &Dp, int H, int W, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
+                   void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, int path, hipStream_t st);
+
 // Whole block around BRA (bra_block.hip).  `path` is the kernel family of the BRA stage
 // (BRA_PATH_GENERIC or BRA_PATH_MFMA), `bra_bytes` that family's workspace size.
 bool block_supported(const Dims &D, int hidden);
