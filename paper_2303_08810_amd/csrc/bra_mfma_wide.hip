@@ -89,6 +89,7 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ws = (bf16_t *)smem;                 // [64 k][PW]
     bf16_t *Xs = Ws + 64 * PW;                   // [NT][64][P]
+    float *bs = (float *)(Xs + NT * 64 * P);     // [128]: the tile's slice of the bias
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave, g = lane / 16, i = lane % 16;
     const int otiles = (Nout + 127) / 128;
     const int m0 = (blockIdx.x / otiles) * 64, o0 = (blockIdx.x % otiles) * 128;
@@ -142,6 +143,7 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
     f32x4 acc[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (!F32OUT && out.bias && tid < 128) bs[tid] = out.bias[min(o0 + tid, Nout - 1)];   // read after the loop's barriers
     request(0);
     for (int k0 = 0; k0 < K; k0 += 64) {
         if (k0) __syncthreads();          // the previous chunk has been read
@@ -167,6 +169,16 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
     }
     const int m = m0 + 16 * wave + i;
     if (m >= M) return;
+    // the residual's pieces are requested together, ahead of the arithmetic (one by one behind
+    // the loop's exit test their latencies would add up)
+    u32x2 rv[8];
+    if (!F32OUT && out.res) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int o = min(o0 + 16 * t + 4 * g, Nout - 4);
+            rv[t] = *(const u32x2 *)(out.res + (size_t)m * out.cols + o);
+        }
+    }
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         const int o = o0 + 16 * t + 4 * g;
@@ -177,14 +189,13 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
         } else {
             f32x4 v = acc[t];
             if (out.bias) {
-                const f32x4 bv = *(const f32x4 *)(out.bias + o);
+                const f32x4 bv = *(const f32x4 *)(bs + 16 * t + 4 * g);
                 v = f32x4{v[0] + bv[0], v[1] + bv[1], v[2] + bv[2], v[3] + bv[3]};
             }
             if (out.gelu) v = f32x4{gelu_f32(v[0]), gelu_f32(v[1]), gelu_f32(v[2]), gelu_f32(v[3])};
-            if (out.res) {
-                const u32x2 rv = *(const u32x2 *)(out.res + (size_t)m * out.cols + col);
-                v = f32x4{v[0] + bf16_lo(rv[0]), v[1] + bf16_hi(rv[0]), v[2] + bf16_lo(rv[1]), v[3] + bf16_hi(rv[1])};
-            }
+            if (out.res)
+                v = f32x4{v[0] + bf16_lo(rv[t][0]), v[1] + bf16_hi(rv[t][0]), v[2] + bf16_lo(rv[t][1]),
+                          v[3] + bf16_hi(rv[t][1])};
             *(u32x2 *)((bf16_t *)out.buf[which] + (size_t)m * out.cols + col) = pack4(v);
             if (which < 2 && out.f32[which]) *(f32x4 *)(out.f32[which] + (size_t)m * out.cols + col) = acc[t];
         }
@@ -193,7 +204,7 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
 
 constexpr size_t gemm_smem(bool split)
 {
-    return (size_t)64 * kGemmPitchW * 2 + (size_t)(split ? 3 : 1) * 64 * kGemmPitch * 2;
+    return (size_t)64 * kGemmPitchW * 2 + (size_t)(split ? 3 : 1) * 64 * kGemmPitch * 2 + 128 * sizeof(float);
 }
 
 // ---------------------------------------------------------------------------
