@@ -195,6 +195,129 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
     }
 }
 
+// Position encoding + LayerNorm1 for C <= 512 (one 8-channel chunk per lane, G = C / 8 lanes per
+// token): a workgroup owns 256 / G neighbouring columns of one image and walks down `rows`
+// rows.  A lane keeps the three rows around its token (each: left, own, right chunk) in a
+// sliding window of registers, so every row is requested once per lane, one row ahead of its
+// first use: per thread two rows are in flight, where a kernel that requests a token's nine
+// chunks and then uses them has one token in flight and is bound by that latency (measured:
+// neither its neighbour traffic nor its arithmetic mattered).  Rows and columns outside the map
+// (zero padding) are blanked as they enter the window.  gamma and beta wait in LDS.
+__global__ __launch_bounds__(256) void k_pos_ln_rows(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Wpos,
+                                                     const float *__restrict__ bpos, const float *__restrict__ gamma,
+                                                     const float *__restrict__ beta, bf16_t *__restrict__ X1,
+                                                     bf16_t *__restrict__ Xn, int H, int W, int C, int G, int rows,
+                                                     int col_groups, int row_blocks, int items, float eps)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    float *gb = (float *)smem;                        // gamma [C], beta [C]
+    const int tid = threadIdx.x, sub = tid % G, slot = tid / G, slots = 256 / G;
+    for (int q = tid; q < C; q += 256) { gb[q] = gamma[q]; gb[C + q] = beta[q]; }
+    const int item = swizzled_block();                // neighbouring row blocks meet in one XCD's L2
+    const bool live = item < items;
+    const int it = live ? item : 0;
+    const int rb = it % row_blocks, cg = (it / row_blocks) % col_groups, b = it / (row_blocks * col_groups);
+    const int y0 = rb * rows, x_raw = cg * slots + slot;
+    const bool active = live && x_raw < W;
+    const int x = min(x_raw, W - 1);
+    const int y_end = min(y0 + rows, H);
+    const bool in_l = x > 0, in_r = x < W - 1;
+    const bf16_t *img = X + (size_t)b * H * W * C + 8 * sub;
+    const int dxl = in_l ? -C : 0, dxr = in_r ? C : 0;
+
+    unsigned w[36];
+    {
+        const u32x4 *src = (const u32x4 *)(Wpos + (size_t)sub * 72);
+#pragma unroll
+        for (int q = 0; q < 9; ++q) {
+            const u32x4 v = src[q];
+            w[4 * q] = v[0]; w[4 * q + 1] = v[1]; w[4 * q + 2] = v[2]; w[4 * q + 3] = v[3];
+        }
+    }
+    float bias[8];
+    {
+        const f32x4 a = *(const f32x4 *)(bpos + 8 * sub), c = *(const f32x4 *)(bpos + 8 * sub + 4);
+        bias[0] = a[0]; bias[1] = a[1]; bias[2] = a[2]; bias[3] = a[3]; bias[4] = c[0]; bias[5] = c[1]; bias[6] = c[2]; bias[7] = c[3];
+    }
+    auto request = [&](int yy, u32x4 (&r)[3]) {       // row yy (clamped into the map): left, own, right
+        const bf16_t *p = img + ((size_t)min(max(yy, 0), H - 1) * W + x) * C;
+        r[0] = *(const u32x4 *)(p + dxl);
+        r[1] = *(const u32x4 *)p;
+        r[2] = *(const u32x4 *)(p + dxr);
+    };
+    auto blank = [&](int yy, u32x4 (&r)[3]) {         // what lies outside the map is zero
+        const bool in_y = yy >= 0 && yy < H;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        r[0] = (in_y && in_l) ? r[0] : z;
+        r[1] = in_y ? r[1] : z;
+        r[2] = (in_y && in_r) ? r[2] : z;
+    };
+    auto weight = [&](int e, int t) {
+        const int idx = 9 * e + t;
+        return (idx & 1) ? bf16_hi(w[idx / 2]) : bf16_lo(w[idx / 2]);
+    };
+    u32x4 win[3][3], nxt[3];
+    request(y0 - 1, win[0]);
+    request(y0, win[1]);
+    request(y0 + 1, win[2]);
+    request(y0 + 2, nxt);
+    __syncthreads();                                  // gamma, beta are in LDS
+    blank(y0 - 1, win[0]);
+    blank(y0, win[1]);
+    blank(y0 + 1, win[2]);
+    const float c_inv = 1.0f / (float)C;
+    for (int y = y0; y < y_end; ++y) {
+        // the packed weights are re-declared as changed, so that their widened forms (72 more
+        // registers) are formed where they are used instead of kept across rows
+#pragma unroll
+        for (int q = 0; q < 36; ++q) asm volatile("" : "+v"(w[q]));
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[2 * e] = bf16_lo(win[1][1][e]) + bias[2 * e];
+            v[2 * e + 1] = bf16_hi(win[1][1][e]) + bias[2 * e + 1];
+        }
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+            for (int kx = 0; kx < 3; ++kx)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[2 * e] = fmaf(weight(2 * e, 3 * ky + kx), bf16_lo(win[ky][kx][e]), v[2 * e]);
+                    v[2 * e + 1] = fmaf(weight(2 * e + 1, 3 * ky + kx), bf16_hi(win[ky][kx][e]), v[2 * e + 1]);
+                }
+        // the window moves down one row; the row after next is requested
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx) { win[0][kx] = win[1][kx]; win[1][kx] = win[2][kx]; win[2][kx] = nxt[kx]; }
+        blank(y + 2, win[2]);
+        if (y + 1 < y_end) request(y + 3, nxt);
+
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += v[e];
+        for (int off = 1; off < G; off *= 2) s += __shfl_xor(s, off);
+        const float mean = s * c_inv;
+        float q2 = 0.f, d[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { d[e] = v[e] - mean; q2 = fmaf(d[e], d[e], q2); }
+        for (int off = 1; off < G; off *= 2) q2 += __shfl_xor(q2, off);
+        const float rstd = 1.0f / sqrtf(q2 * c_inv + eps);
+        const f32x4 g0 = *(const f32x4 *)(gb + 8 * sub), g1 = *(const f32x4 *)(gb + 8 * sub + 4);
+        const f32x4 b0 = *(const f32x4 *)(gb + C + 8 * sub), b1 = *(const f32x4 *)(gb + C + 8 * sub + 4);
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o[e] = fmaf(d[e] * rstd, g0[e], b0[e]);
+            o[4 + e] = fmaf(d[4 + e] * rstd, g1[e], b1[e]);
+        }
+        if (active) {
+            const size_t at = (((size_t)b * H + y) * W + x) * C + 8 * sub;
+            *(bf16x8 *)(X1 + at) = pack8(v);
+            *(bf16x8 *)(Xn + at) = pack8(o);
+        }
+    }
+}
+
 // X2 = X1 + Y, LayerNorm2, both MLP layers and the last residual link in one kernel for C = 64,
 // hidden = 64 HT: nothing between X1, Y and Xout passes through memory.
 // A wavefront owns 16 tokens at a time, lane (g, i) = token i; everything is formed transposed
@@ -402,6 +525,192 @@ int launch_mlp_fused64(const Dims &D, const bf16_t *X1, const bf16_t *Y, const b
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
+// The same single-kernel MLP half for C = 64 CT (CT = 1..4) and any hidden = 64 NB: the weights
+// no longer fit in LDS, so the hidden layer is walked in blocks of 64 units.  Per block the
+// workgroup (4 wavefronts, 16 tokens each, one tile per wavefront) holds the 64 columns of W1
+// and the 64 rows of W2 in LDS (requested into registers one block ahead), forms
+// GELU(Xn W1[:, block] + b1[block]) for its tokens and adds its product with W2[block, :] to the
+// output accumulators, which start from X2 + b2.  Operand layouts, fragment reads and LDS
+// pitches as in k_mlp_fused64 (W1's block has 64 columns: its pitch is that kernel's for
+// hidden = 64; W2's rows are C wide: pitch C + 32 elements = 64 bytes modulo 256).
+template <int CT>
+struct MlpStreamSmem {
+    static constexpr int C = 64 * CT;
+    static constexpr int P1 = 80, G1 = 64;                    // W1 block [C][64]
+    static constexpr int P2 = C + 32, G2 = 4;                 // W2 block [64][C]
+    static constexpr size_t w2_off = (size_t)(C * P1 + (C / 8) * G1) * 2;
+    static constexpr size_t v_off = w2_off + (size_t)(64 * P2 + 16 * G2) * 2;      // gamma, beta, b2 [C] each, then b1
+    static_assert(w2_off % 16 == 0 && v_off % 16 == 0, "layout");
+    static size_t bytes(int hidden) { return v_off + (size_t)(3 * C + hidden) * 4; }
+};
+
+template <int CT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(CT <= 2 ? 3 : 2, 4))) void k_mlp_stream(const bf16_t *__restrict__ X1, const bf16_t *__restrict__ Y,
+                                                    const bf16_t *__restrict__ W1, const float *__restrict__ b1,
+                                                    const bf16_t *__restrict__ W2, const float *__restrict__ b2,
+                                                    const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                    bf16_t *__restrict__ Xout, long tokens, int hidden, float eps)
+{
+    typedef MlpStreamSmem<CT> SM;
+    constexpr int C = SM::C, KS = C / 32, NT = C / 16, P1 = SM::P1, G1 = SM::G1, P2 = SM::P2, G2 = SM::G2;
+    constexpr int NP = C / 32;          // 16-byte pieces per thread of one block of W1 (8 C pieces), and of W2
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *W1s = (bf16_t *)smem;
+    bf16_t *W2s = (bf16_t *)(smem + SM::w2_off);
+    float *gms = (float *)(smem + SM::v_off), *bts = gms + C, *b2s = bts + C, *b1s = b2s + C;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave, g = lane / 16, i = lane % 16;
+    const int NB = hidden / 64;
+
+    for (int q = tid; q < C; q += 256) { gms[q] = gamma[q]; bts[q] = beta[q]; b2s[q] = b2[q]; }
+    for (int q = tid; q < hidden; q += 256) b1s[q] = b1[q];
+
+    // this thread's pieces of a block: W1 rows k (8 pieces of 8 columns each), W2 rows of C / 8 pieces
+    u32x4 r1[NP], r2[NP];
+    auto request = [&](int nb) {
+#pragma unroll
+        for (int u = 0; u < NP; ++u) {
+            const int q = tid + 256 * u;
+            r1[u] = *(const u32x4 *)(W1 + (size_t)(q / 8) * hidden + 64 * nb + 8 * (q % 8));
+            r2[u] = *(const u32x4 *)(W2 + (size_t)(64 * nb + q / (C / 8)) * C + 8 * (q % (C / 8)));
+        }
+    };
+    auto park = [&]() {
+#pragma unroll
+        for (int u = 0; u < NP; ++u) {
+            const int q = tid + 256 * u;
+            const int k = q / 8, h = q / (C / 8);
+            *(u32x4 *)(W1s + k * P1 + (k / 8) * G1 + 8 * (q % 8)) = r1[u];
+            u32x2 *dst = (u32x2 *)(W2s + h * P2 + (h / 4) * G2 + 8 * (q % (C / 8)));      // 8-byte aligned only
+            dst[0] = u32x2{r2[u][0], r2[u][1]};
+            dst[1] = u32x2{r2[u][2], r2[u][3]};
+        }
+    };
+    request(0);
+
+    const long tile = (long)blockIdx.x * 4 + wave;
+    const long tok = tile * 16 + i;
+    const long tok_c = min(tok, tokens - 1);                    // rows past the end repeat the last; never stored
+    float x2[KS][8];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const u32x4 xa = *(const u32x4 *)(X1 + (size_t)tok_c * C + 32 * ks + 8 * g);
+        const u32x4 ya = *(const u32x4 *)(Y + (size_t)tok_c * C + 32 * ks + 8 * g);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x2[ks][2 * e] = bf16_lo(xa[e]) + bf16_lo(ya[e]);
+            x2[ks][2 * e + 1] = bf16_hi(xa[e]) + bf16_hi(ya[e]);
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += x2[ks][e];
+    s += __shfl_xor(s, 16);
+    s += __shfl_xor(s, 32);
+    const float mean = s * (1.0f / C);
+    float qq = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const float d = x2[ks][e] - mean; qq = fmaf(d, d, qq); }
+    qq += __shfl_xor(qq, 16);
+    qq += __shfl_xor(qq, 32);
+    const float rstd = 1.0f / sqrtf(qq * (1.0f / C) + eps);
+    __syncthreads();                                            // the vectors are in LDS
+
+    bf16x8 bx[KS];
+    f32x4 acc2[NT];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const int c0 = 32 * ks + 8 * g;
+        float v[8];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const f32x4 gv = *(const f32x4 *)(gms + c0 + 4 * h), bv = *(const f32x4 *)(bts + c0 + 4 * h);
+            const f32x4 ov = *(const f32x4 *)(b2s + c0 + 4 * h);
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                v[4 * h + jj] = fmaf((x2[ks][4 * h + jj] - mean) * rstd, gv[jj], bv[jj]);
+                acc2[2 * ks + h][jj] = x2[ks][4 * h + jj] + ov[jj];      // output tile 2 ks + h, row 4 g + jj
+            }
+        }
+        bx[ks] = pack8(v);
+    }
+
+    const int off1 = (8 * g + i / 4) * P1 + g * G1 + 4 * (i % 4), off2 = (4 * g + i / 4) * P2 + g * G2 + 8 * (i % 4);
+    for (int nb = 0; nb < NB; ++nb) {
+        if (nb) __syncthreads();                                // the previous block has been read
+        park();
+        __syncthreads();
+        if (nb + 1 < NB) request(nb + 1);
+#pragma unroll 1
+        for (int ks2 = 0; ks2 < 2; ++ks2) {
+            float hv[8];
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int t1 = 2 * ks2 + half;
+                f32x4 a = *(const f32x4 *)(b1s + 64 * nb + 16 * t1 + 4 * g);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16_t *wp = W1s + off1 + ks * (32 * P1 + 4 * G1) + 16 * t1;
+                    const u32x2 w0 = __builtin_bit_cast(u32x2, lds_read_tr16(wp));
+                    const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 4 * P1));
+                    a = mfma16(__builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]}), bx[ks], a);
+                }
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) hv[4 * half + jj] = gelu_f32(a[jj]);
+            }
+            const bf16x8 hb = pack8(hv);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const bf16_t *wp = W2s + off2 + ks2 * (32 * P2 + 8 * G2) + 32 * (t / 2) + 4 * (t % 2);
+                const u32x2 w0 = __builtin_bit_cast(u32x2, lds_read_tr16(wp));
+                const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 16 * P2 + 4 * G2));
+                acc2[t] = mfma16(__builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]}), hb, acc2[t]);
+            }
+        }
+    }
+    if (tok < tokens) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = acc2[2 * ks + e / 4][e % 4];
+            *(bf16x8 *)(Xout + (size_t)tok * C + 32 * ks + 8 * g) = pack8(v);
+        }
+    }
+}
+
+template <int CT>
+int launch_mlp_stream(const Dims &D, int hidden, const bf16_t *X1, const bf16_t *Y, const bra_block_params &p,
+                      bf16_t *Xout, float eps, hipStream_t st)
+{
+    const size_t smem = MlpStreamSmem<CT>::bytes(hidden);
+    static size_t opted = 0;
+    if (smem > opted) {
+        if (hipFuncSetAttribute((const void *)k_mlp_stream<CT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)smem) != hipSuccess)
+            return BRA_ERR_LAUNCH;
+        opted = smem;
+    }
+    const long tokens = (long)D.B * D.N, grid = (tokens + 63) / 64;
+    ProfScope ps(st, K_BLK_MLP_FUSED);
+    hipLaunchKernelGGL((k_mlp_stream<CT>), dim3((unsigned)grid), dim3(256), smem, st, X1, Y, (const bf16_t *)p.W1,
+                       p.b1, (const bf16_t *)p.W2, p.b2, p.ln2_gamma, p.ln2_beta, Xout, tokens, hidden, eps);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+// C = 64 .. 256 with any hidden that fits the LDS budget takes the block-streaming kernel.
+bool mlp_stream_shape(const Dims &D, int hidden)
+{
+    static const bool off = getenv("BRA_BLOCK_UNFUSED") != nullptr;
+    if (off || D.C % 64 || D.C > 256 || hidden % 64) return false;
+    const size_t fixed[5] = {0, MlpStreamSmem<1>::v_off, MlpStreamSmem<2>::v_off, MlpStreamSmem<3>::v_off,
+                             MlpStreamSmem<4>::v_off};
+    return fixed[D.C / 64] + (size_t)(3 * D.C + hidden) * 4 <= 160 * 1024;
+}
+
 // The single-kernel MLP half exists for C = 64 and hidden = 64, 128, 192 or 256.
 bool mlp_fused_shape(const Dims &D, int hidden)
 {
@@ -436,6 +745,27 @@ int launch_token_ln(const Dims &D, const bf16_t *A, const bf16_t *Badd, const br
     };
     if (one) launch(k_token_ln<MODE, true>, 0);
     else launch(k_token_ln<MODE, false>, (size_t)slots * D.C * sizeof(float));      // at most 4 x 4096 floats
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+// Position encoding + LayerNorm1: the row-walking kernel where a lane owns one chunk per token.
+int launch_pos_ln(const Dims &D, const bf16_t *X, const bra_block_params &p, bf16_t *X1, bf16_t *Xn, float eps,
+                  hipStream_t st)
+{
+    const int G = lanes_per_token(D.C);
+    static const bool plain = getenv("BRA_POS_PLAIN") != nullptr;
+    if (D.C / 8 != G || plain) return launch_token_ln<kPos>(D, X, nullptr, p, p.ln1_gamma, p.ln1_beta, X1, Xn, eps, st);
+    static const int want_rows = getenv("BRA_POS_ROWS") ? atoi(getenv("BRA_POS_ROWS")) : 8;
+    const int slots = 256 / G, col_groups = (D.W + slots - 1) / slots;
+    const int rows = want_rows < 1 ? 1 : (want_rows > D.H ? D.H : want_rows);
+    const int row_blocks = (D.H + rows - 1) / rows;
+    const long items = (long)D.B * col_groups * row_blocks;
+    if (items > 0x7ffffff0L) return BRA_ERR_SHAPE;
+    const long grid = (items + 7) / 8 * 8;
+    ProfScope ps(st, K_BLK_POS_LN);
+    hipLaunchKernelGGL(k_pos_ln_rows, dim3((unsigned)grid), dim3(256), (size_t)2 * D.C * sizeof(float), st, X,
+                       (const bf16_t *)p.Wpos, p.bpos, p.ln1_gamma, p.ln1_beta, X1, Xn, D.H, D.W, D.C, G, rows,
+                       col_groups, row_blocks, (int)items, eps);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
@@ -483,7 +813,7 @@ int block_forward(const Dims &D, int hidden, float eps, const void *X, const bra
 {
     const BlockWs w = carve_block(D, hidden, bra_bytes, ws);
     const long M = (long)D.B * D.N;
-    int rc = launch_token_ln<kPos>(D, (const bf16_t *)X, nullptr, p, p.ln1_gamma, p.ln1_beta, w.x1, w.xn, eps, st);
+    int rc = launch_pos_ln(D, (const bf16_t *)X, p, w.x1, w.xn, eps, st);
     if (rc != BRA_OK) return rc;
     rc = (path == BRA_PATH_MFMA)
              ? mfma_forward(D, w.xn, p.Wqkv, p.Wo, p.Wlce, w.y, Ir_out_opt, Ir_in_opt, w.inner, st)
@@ -495,6 +825,14 @@ int block_forward(const Dims &D, int hidden, float eps, const void *X, const bra
         case 2: return launch_mlp_fused64<2>(D, w.x1, w.y, p, (bf16_t *)Xout, eps, st);
         case 3: return launch_mlp_fused64<3>(D, w.x1, w.y, p, (bf16_t *)Xout, eps, st);
         default: return launch_mlp_fused64<4>(D, w.x1, w.y, p, (bf16_t *)Xout, eps, st);
+        }
+    }
+    if (mlp_stream_shape(D, hidden)) {
+        switch (D.C / 64) {
+        case 1: return launch_mlp_stream<1>(D, hidden, w.x1, w.y, p, (bf16_t *)Xout, eps, st);
+        case 2: return launch_mlp_stream<2>(D, hidden, w.x1, w.y, p, (bf16_t *)Xout, eps, st);
+        case 3: return launch_mlp_stream<3>(D, hidden, w.x1, w.y, p, (bf16_t *)Xout, eps, st);
+        default: return launch_mlp_stream<4>(D, hidden, w.x1, w.y, p, (bf16_t *)Xout, eps, st);
         }
     }
     // X2 takes X1's place: every lane reads the elements it overwrites
