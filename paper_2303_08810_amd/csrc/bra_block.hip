@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
         for (int e = 0; e < 4; ++e) { v[2 * e] = bf16_lo(t[e]); v[2 * e + 1] = bf16_hi(t[e]); }
     };
     // the pre-norm values of chunk c0 of token (img, y, x)
-    auto values = [&](long tok, int y, int x, int c0, const unsigned (&w)[36], const float (&bias)[8], float (&v)[8]) {
+    auto values = [&](long tok, bool ok, int y, int x, int c0, const unsigned (&w)[36], const float (&bias)[8], float (&v)[8]) {
         const bf16_t *centre = A + (size_t)tok * C + c0;
         float xc[8];
         unpack(*(const u32x4 *)centre, xc);
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
         }
         // all eight neighbours are requested at once; one outside the map (zero padding) is
         // read from the nearest row / column inside instead and blanked after it arrives
-        const bool in_y[3] = {y > 0, true, y < H - 1}, in_x[3] = {x > 0, true, x < W - 1};
+        const bool in_y[3] = {y > 0, true, ok && y < H - 1}, in_x[3] = {x > 0, true, ok && x < W - 1};
         const int off_y[3] = {in_y[0] ? -W * C : 0, 0, in_y[2] ? W * C : 0};
         const int off_x[3] = {in_x[0] ? -C : 0, 0, in_x[2] ? C : 0};
         u32x4 nb[9];
@@ -118,6 +118,9 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
     // consecutive workgroups (neighbouring rows of the map) run on one XCD and meet in its L2
     const long first = (long)swizzled_block() * slots * iters;
     if (first >= tokens) return;
+    const long row_first = first / W;
+    const int x_first = (int)(first - row_first * W), y_first = (int)(row_first % H);
+    const float w_inv = 1.0f / (float)W, h_inv = 1.0f / (float)H;
     unsigned w[36];
     float bias[8], gm[8], bt[8];
     if (ONE) {
@@ -132,8 +135,13 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
         const long tok_raw = first + (long)it * slots + slot;
         const bool valid = tok_raw < tokens;
         const long tok = valid ? tok_raw : tokens - 1;          // lanes past the end redo the last token, store nothing
-        const int ry = (int)tok / W, x = (int)tok - ry * W;    // tokens < 2^31 (checked on the host)
-        const int y = ry % H;
+        // coordinates from the workgroup's first token (uniform: scalar arithmetic) plus this
+        // lane's small distance from it; a lane past the end stands on the map's first token for
+        // the neighbour tests (it reads the last token only and stores nothing)
+        const int xs = valid ? x_first + it * slots + slot : 0;
+        const int qx = fast_div(xs, w_inv), x = xs - qx * W;
+        const int ys = valid ? y_first + qx : 0;
+        const int y = ys - fast_div(ys, h_inv) * H;
 
         if (ONE) {
             if (MODE == kPos) {
@@ -143,7 +151,7 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
                 for (int q = 0; q < 36; ++q) asm volatile("" : "+v"(w[q]));
             }
             float v[8];
-            values(tok, y, x, 8 * sub, w, bias, v);
+            values(tok, valid, y, x, 8 * sub, w, bias, v);
             float s = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) s += v[e];
@@ -151,7 +159,7 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
             float q = 0.f, d[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) { d[e] = v[e] - mean; q = fmaf(d[e], d[e], q); }
-            const float rstd = 1.0f / sqrtf(group_sum(q) * c_inv + eps);
+            const float rstd = __builtin_amdgcn_rsqf(group_sum(q) * c_inv + eps);
             float o[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = fmaf(d[e] * rstd, gm[e], bt[e]);
@@ -165,7 +173,7 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
                 const int c0 = 8 * (sub + G * q);
                 if (MODE == kPos) { load_w(c0, w); load8(bpos + c0, bias); }
                 float v[8];
-                values(tok, y, x, c0, w, bias, v);
+                values(tok, valid, y, x, c0, w, bias, v);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) s += v[e];
                 *(f32x4 *)(strip + c0) = f32x4{v[0], v[1], v[2], v[3]};
@@ -180,7 +188,7 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { const float d = v[e] - mean; qq = fmaf(d, d, qq); }
             }
-            const float rstd = 1.0f / sqrtf(group_sum(qq) * c_inv + eps);
+            const float rstd = __builtin_amdgcn_rsqf(group_sum(qq) * c_inv + eps);
             for (int q = 0; q < NC; ++q) {
                 const int c0 = 8 * (sub + G * q);
                 float v[8], o[8];
@@ -191,129 +199,6 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
                 for (int e = 0; e < 8; ++e) o[e] = fmaf((v[e] - mean) * rstd, gm[e], bt[e]);
                 if (valid) *(bf16x8 *)(Norm + (size_t)tok * C + c0) = pack8(o);
             }
-        }
-    }
-}
-
-// Position encoding + LayerNorm1 for C <= 512 (one 8-channel chunk per lane, G = C / 8 lanes per
-// token): a workgroup owns 256 / G neighbouring columns of one image and walks down `rows`
-// rows.  A lane keeps the three rows around its token (each: left, own, right chunk) in a
-// sliding window of registers, so every row is requested once per lane, one row ahead of its
-// first use: per thread two rows are in flight, where a kernel that requests a token's nine
-// chunks and then uses them has one token in flight and is bound by that latency (measured:
-// neither its neighbour traffic nor its arithmetic mattered).  Rows and columns outside the map
-// (zero padding) are blanked as they enter the window.  gamma and beta wait in LDS.
-__global__ __launch_bounds__(256) void k_pos_ln_rows(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Wpos,
-                                                     const float *__restrict__ bpos, const float *__restrict__ gamma,
-                                                     const float *__restrict__ beta, bf16_t *__restrict__ X1,
-                                                     bf16_t *__restrict__ Xn, int H, int W, int C, int G, int rows,
-                                                     int col_groups, int row_blocks, int items, float eps)
-{
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    float *gb = (float *)smem;                        // gamma [C], beta [C]
-    const int tid = threadIdx.x, sub = tid % G, slot = tid / G, slots = 256 / G;
-    for (int q = tid; q < C; q += 256) { gb[q] = gamma[q]; gb[C + q] = beta[q]; }
-    const int item = swizzled_block();                // neighbouring row blocks meet in one XCD's L2
-    const bool live = item < items;
-    const int it = live ? item : 0;
-    const int rb = it % row_blocks, cg = (it / row_blocks) % col_groups, b = it / (row_blocks * col_groups);
-    const int y0 = rb * rows, x_raw = cg * slots + slot;
-    const bool active = live && x_raw < W;
-    const int x = min(x_raw, W - 1);
-    const int y_end = min(y0 + rows, H);
-    const bool in_l = x > 0, in_r = x < W - 1;
-    const bf16_t *img = X + (size_t)b * H * W * C + 8 * sub;
-    const int dxl = in_l ? -C : 0, dxr = in_r ? C : 0;
-
-    unsigned w[36];
-    {
-        const u32x4 *src = (const u32x4 *)(Wpos + (size_t)sub * 72);
-#pragma unroll
-        for (int q = 0; q < 9; ++q) {
-            const u32x4 v = src[q];
-            w[4 * q] = v[0]; w[4 * q + 1] = v[1]; w[4 * q + 2] = v[2]; w[4 * q + 3] = v[3];
-        }
-    }
-    float bias[8];
-    {
-        const f32x4 a = *(const f32x4 *)(bpos + 8 * sub), c = *(const f32x4 *)(bpos + 8 * sub + 4);
-        bias[0] = a[0]; bias[1] = a[1]; bias[2] = a[2]; bias[3] = a[3]; bias[4] = c[0]; bias[5] = c[1]; bias[6] = c[2]; bias[7] = c[3];
-    }
-    auto request = [&](int yy, u32x4 (&r)[3]) {       // row yy (clamped into the map): left, own, right
-        const bf16_t *p = img + ((size_t)min(max(yy, 0), H - 1) * W + x) * C;
-        r[0] = *(const u32x4 *)(p + dxl);
-        r[1] = *(const u32x4 *)p;
-        r[2] = *(const u32x4 *)(p + dxr);
-    };
-    auto blank = [&](int yy, u32x4 (&r)[3]) {         // what lies outside the map is zero
-        const bool in_y = yy >= 0 && yy < H;
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        r[0] = (in_y && in_l) ? r[0] : z;
-        r[1] = in_y ? r[1] : z;
-        r[2] = (in_y && in_r) ? r[2] : z;
-    };
-    auto weight = [&](int e, int t) {
-        const int idx = 9 * e + t;
-        return (idx & 1) ? bf16_hi(w[idx / 2]) : bf16_lo(w[idx / 2]);
-    };
-    u32x4 win[3][3], nxt[3];
-    request(y0 - 1, win[0]);
-    request(y0, win[1]);
-    request(y0 + 1, win[2]);
-    request(y0 + 2, nxt);
-    __syncthreads();                                  // gamma, beta are in LDS
-    blank(y0 - 1, win[0]);
-    blank(y0, win[1]);
-    blank(y0 + 1, win[2]);
-    const float c_inv = 1.0f / (float)C;
-    for (int y = y0; y < y_end; ++y) {
-        // the packed weights are re-declared as changed, so that their widened forms (72 more
-        // registers) are formed where they are used instead of kept across rows
-#pragma unroll
-        for (int q = 0; q < 36; ++q) asm volatile("" : "+v"(w[q]));
-        float v[8];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            v[2 * e] = bf16_lo(win[1][1][e]) + bias[2 * e];
-            v[2 * e + 1] = bf16_hi(win[1][1][e]) + bias[2 * e + 1];
-        }
-#pragma unroll
-        for (int ky = 0; ky < 3; ++ky)
-#pragma unroll
-            for (int kx = 0; kx < 3; ++kx)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    v[2 * e] = fmaf(weight(2 * e, 3 * ky + kx), bf16_lo(win[ky][kx][e]), v[2 * e]);
-                    v[2 * e + 1] = fmaf(weight(2 * e + 1, 3 * ky + kx), bf16_hi(win[ky][kx][e]), v[2 * e + 1]);
-                }
-        // the window moves down one row; the row after next is requested
-#pragma unroll
-        for (int kx = 0; kx < 3; ++kx) { win[0][kx] = win[1][kx]; win[1][kx] = win[2][kx]; win[2][kx] = nxt[kx]; }
-        blank(y + 2, win[2]);
-        if (y + 1 < y_end) request(y + 3, nxt);
-
-        float s = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s += v[e];
-        for (int off = 1; off < G; off *= 2) s += __shfl_xor(s, off);
-        const float mean = s * c_inv;
-        float q2 = 0.f, d[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { d[e] = v[e] - mean; q2 = fmaf(d[e], d[e], q2); }
-        for (int off = 1; off < G; off *= 2) q2 += __shfl_xor(q2, off);
-        const float rstd = 1.0f / sqrtf(q2 * c_inv + eps);
-        const f32x4 g0 = *(const f32x4 *)(gb + 8 * sub), g1 = *(const f32x4 *)(gb + 8 * sub + 4);
-        const f32x4 b0 = *(const f32x4 *)(gb + C + 8 * sub), b1 = *(const f32x4 *)(gb + C + 8 * sub + 4);
-        float o[8];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            o[e] = fmaf(d[e] * rstd, g0[e], b0[e]);
-            o[4 + e] = fmaf(d[4 + e] * rstd, g1[e], b1[e]);
-        }
-        if (active) {
-            const size_t at = (((size_t)b * H + y) * W + x) * C + 8 * sub;
-            *(bf16x8 *)(X1 + at) = pack8(v);
-            *(bf16x8 *)(Xn + at) = pack8(o);
         }
     }
 }
@@ -450,7 +335,7 @@ void k_mlp_fused64(const bf16_t *__restrict__ X1, const bf16_t *__restrict__ Y, 
             for (int e = 0; e < 8; ++e) { const float d = x2[ks][e] - mean; qq = fmaf(d, d, qq); }
         qq += __shfl_xor(qq, 16);
         qq += __shfl_xor(qq, 32);
-        const float rstd = 1.0f / sqrtf(qq * (1.0f / C) + eps);
+        const float rstd = __builtin_amdgcn_rsqf(qq * (1.0f / C) + eps);
         bf16x8 bx[2];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
@@ -616,7 +501,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(CT <= 2 ? 3
         for (int e = 0; e < 8; ++e) { const float d = x2[ks][e] - mean; qq = fmaf(d, d, qq); }
     qq += __shfl_xor(qq, 16);
     qq += __shfl_xor(qq, 32);
-    const float rstd = 1.0f / sqrtf(qq * (1.0f / C) + eps);
+    const float rstd = __builtin_amdgcn_rsqf(qq * (1.0f / C) + eps);
     __syncthreads();                                            // the vectors are in LDS
 
     bf16x8 bx[KS];
@@ -748,27 +633,6 @@ int launch_token_ln(const Dims &D, const bf16_t *A, const bf16_t *Badd, const br
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
-// Position encoding + LayerNorm1: the row-walking kernel where a lane owns one chunk per token.
-int launch_pos_ln(const Dims &D, const bf16_t *X, const bra_block_params &p, bf16_t *X1, bf16_t *Xn, float eps,
-                  hipStream_t st)
-{
-    const int G = lanes_per_token(D.C);
-    static const bool plain = getenv("BRA_POS_PLAIN") != nullptr;
-    if (D.C / 8 != G || plain) return launch_token_ln<kPos>(D, X, nullptr, p, p.ln1_gamma, p.ln1_beta, X1, Xn, eps, st);
-    static const int want_rows = getenv("BRA_POS_ROWS") ? atoi(getenv("BRA_POS_ROWS")) : 8;
-    const int slots = 256 / G, col_groups = (D.W + slots - 1) / slots;
-    const int rows = want_rows < 1 ? 1 : (want_rows > D.H ? D.H : want_rows);
-    const int row_blocks = (D.H + rows - 1) / rows;
-    const long items = (long)D.B * col_groups * row_blocks;
-    if (items > 0x7ffffff0L) return BRA_ERR_SHAPE;
-    const long grid = (items + 7) / 8 * 8;
-    ProfScope ps(st, K_BLK_POS_LN);
-    hipLaunchKernelGGL(k_pos_ln_rows, dim3((unsigned)grid), dim3(256), (size_t)2 * D.C * sizeof(float), st, X,
-                       (const bf16_t *)p.Wpos, p.bpos, p.ln1_gamma, p.ln1_beta, X1, Xn, D.H, D.W, D.C, G, rows,
-                       col_groups, row_blocks, (int)items, eps);
-    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
-}
-
 struct BlockWs {
     bf16_t *x1, *xn, *y, *hd;
     void *inner;
@@ -813,7 +677,7 @@ int block_forward(const Dims &D, int hidden, float eps, const void *X, const bra
 {
     const BlockWs w = carve_block(D, hidden, bra_bytes, ws);
     const long M = (long)D.B * D.N;
-    int rc = launch_pos_ln(D, (const bf16_t *)X, p, w.x1, w.xn, eps, st);
+    int rc = launch_token_ln<kPos>(D, (const bf16_t *)X, nullptr, p, p.ln1_gamma, p.ln1_beta, w.x1, w.xn, eps, st);
     if (rc != BRA_OK) return rc;
     rc = (path == BRA_PATH_MFMA)
              ? mfma_forward(D, w.xn, p.Wqkv, p.Wo, p.Wlce, w.y, Ir_out_opt, Ir_in_opt, w.inner, st)
