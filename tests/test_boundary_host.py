@@ -93,6 +93,46 @@ def test_entry_points_reject_bad_arguments_before_launching():
     assert L.bra_forward(None, fake, fake, fake, fake, fake, None, None, fake, 1 << 30, None) == -1
 
 
+def test_block_and_padded_workspace_queries():
+    L = bra.lib()
+    out = ctypes.c_size_t(0)
+
+    def block(hidden, **kw):
+        base = dict(B=2, H=28, W=28, C=64, heads=2, S=7, k=4, dtype=bra.BRA_BF16, scale=None, path="auto")
+        base.update(kw)
+        shape = bra.make_shape(**base)
+        return L.bra_block_workspace_bytes(ctypes.byref(shape), hidden, ctypes.byref(out)), out.value
+
+    rc, n = block(192)
+    inner = ws_bytes(B=2, dtype=bra.BRA_BF16)[1]
+    tokens = 2 * 28 * 28
+    # X1, LayerNorm1's output, BRA's output, the hidden layer, BRA's own workspace
+    assert rc == 0 and n % 256 == 0 and n >= inner + tokens * (3 * 64 + 192) * 2
+    assert block(0)[0] == -2 and block(-64)[0] == -2                  # hidden < 1
+    assert block(100)[0] == -6                                        # hidden not a multiple of 64
+    assert block(192, dtype=bra.BRA_F32)[0] == -6                     # float32 tensors
+    assert block(144, C=48, heads=3)[0] == -6                         # C not a multiple of 64
+    assert block(192, H=30)[0] == -2 and block(192, k=50)[0] == -3    # BRA's own checks come first
+    assert L.bra_block_workspace_bytes(None, 192, ctypes.byref(out)) == -1
+
+    def padded(**kw):
+        base = dict(B=1, H=30, W=45, C=64, heads=2, S=7, k=4, dtype=bra.BRA_BF16, scale=None, path="auto")
+        base.update(kw)
+        shape = bra.make_shape(**base)
+        return L.bra_padded_workspace_bytes(ctypes.byref(shape), ctypes.byref(out)), out.value
+
+    rc, n = padded()
+    inner = ws_bytes(H=35, W=49, dtype=bra.BRA_BF16)[1]
+    assert rc == 0 and n >= inner + 2 * 35 * 49 * 64 * 2                # padded X and Y beside BRA's workspace
+    assert padded(H=35, W=49) == (0, inner)                           # S divides: no copies, bra_forward's size
+    assert padded(H=0)[0] == -2 and padded(k=50)[0] == -3 and padded(S=0)[0] == -2
+    # the padded call turns the same invalid arguments into codes before any launch
+    shape = bra.make_shape(1, 30, 45, 64, 2, 7, 4, bra.BRA_BF16)
+    assert L.bra_forward_padded(ctypes.byref(shape), None, None, None, None, None, None, None, None, 0, None) == -1
+    fake = ctypes.c_void_p(256)
+    assert L.bra_forward_padded(ctypes.byref(shape), fake, fake, fake, fake, fake, None, None, None, 0, None) == -5
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(bra, "_lib", None)
     monkeypatch.setattr(bra, "LIB_PATH", str(tmp_path / "libbra.so"))
