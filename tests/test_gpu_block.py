@@ -91,6 +91,32 @@ def test_block_shapes(B, H, W, C, heads, S, k, e):
     compare_block(X, P, S, k, heads)
 
 
+def random_block_shapes(count, seed):
+    """Seeded random shapes within what the block is built for (C a multiple of 64, heads of 32 or
+    64 channels), sized for the oracle."""
+    import random
+    rng = random.Random(seed)
+    out = []
+    while len(out) < count:
+        S = rng.choice([1, 2, 3, 4, 5, 7, 8])
+        H, W = S * rng.choice([1, 2, 3, 4, 5, 8, 13]), S * rng.choice([1, 2, 3, 4, 6, 8, 11])
+        heads = rng.choice([1, 2, 3, 4, 6, 8, 10, 12, 16])
+        C = rng.choice([32, 32, 64]) * heads
+        k = rng.choice([1, 2, 3, 4, min(S * S, 12), S * S])
+        B, e = rng.choice([1, 2, 3]), rng.choice([1, 2, 3, 3, 4, 5])
+        n = (H // S) * (W // S)
+        if C % 64 or C > 1024 or k > S * S or H * W * C > 400000 or H * W * k * n * C > 2e8 or B * H * W * C * e * C > 3e9:
+            continue
+        out.append((B, H, W, C, heads, S, k, e))
+    return out
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,S,k,e", random_block_shapes(16, seed=20230309))
+def test_block_random_shapes(B, H, W, C, heads, S, k, e):
+    X, P = inputs(B, H, W, C, seed=4500 + H * W + C + e, expansion=e)
+    compare_block(X, P, S, k, heads)
+
+
 def test_block_generic_family_for_bra():
     X, P = inputs(2, 14, 14, 64, seed=4100)
     compare_block(X, P, 7, 4, 2, path="generic")

@@ -42,6 +42,30 @@ def test_padded_forward(dtype, B, H, W, C, heads, S, k, path):
     check_output(Y, ref["Y"], dtype)
 
 
+def random_padded_shapes(count, seed):
+    import random
+    rng = random.Random(seed)
+    out = []
+    while len(out) < count:
+        S = rng.choice([2, 3, 4, 5, 7, 8, 16])
+        H, W = rng.randint(max(1, S // 2), 70), rng.randint(max(1, S // 2), 70)
+        dtype = rng.choice(["bf16", "bf16", "f32"])
+        heads = rng.choice([1, 2, 4, 8])
+        C = rng.choice([16, 32, 32, 64]) * heads
+        k = rng.choice([1, 2, 3, 4, min(S * S, 9)])
+        Hp, Wp = -(-H // S) * S, -(-W // S) * S
+        n = (Hp // S) * (Wp // S)
+        if C > 512 or Hp * Wp * C > 500000 or Hp * Wp * k * n * C > 2e8:
+            continue
+        out.append((dtype, rng.choice([1, 2]), H, W, C, heads, S, k, "auto"))
+    return out
+
+
+@pytest.mark.parametrize("dtype,B,H,W,C,heads,S,k,path", random_padded_shapes(16, seed=20230310))
+def test_padded_forward_random_shapes(dtype, B, H, W, C, heads, S, k, path):
+    test_padded_forward(dtype, B, H, W, C, heads, S, k, path)
+
+
 def test_padded_forward_forced_routing():
     B, H, W, C, heads, S, k = 2, 20, 26, 64, 2, 4, 3
     Xn, Wqkvn, Won, Wlcen = make_inputs(B, H, W, C, seed=5100, dtype="bf16")
