@@ -165,11 +165,14 @@ def time_block(cfg, steps, warmup, expansion=3):
     from synthetic_inputs import bf16_bits, make_block_inputs
 
     X, P = make_block_inputs(cfg, expansion=expansion)
-    bf = lambda a: torch.from_numpy(bf16_bits(a).view(np.int16)).view(torch.bfloat16).cuda()
+    if cfg.dtype == "bf16":
+        bf = lambda a: torch.from_numpy(bf16_bits(a).view(np.int16)).view(torch.bfloat16).cuda()
+    else:
+        bf = lambda a: torch.from_numpy(a).cuda()
     dP = {n: (bf(P[n]) if n in bra.BraBlockParams.MATRICES else torch.from_numpy(P[n]).cuda())
           for n in bra.BraBlockParams.FIELDS}
     Xd = bf(X)
-    unit_mb = Xd.numel() * 2 / 1e6
+    unit_mb = Xd.numel() * Xd.element_size() / 1e6
     sets = max(2, min(24, int(600 / (2 * unit_mb)) + 1))
     Xs = [Xd] + [torch.roll(Xd, shifts=i, dims=0).contiguous() for i in range(1, sets)]
     Ys = [torch.empty_like(Xd) for _ in range(sets)]
@@ -205,7 +208,7 @@ def time_block(cfg, steps, warmup, expansion=3):
     return {
         "images_per_s": round(cfg.B / (ms / 1e3), 1), "ms_per_step": round(ms, 5), "expansion": expansion,
         "achieved_tflops": round((mlp_flops + bra_flops) / (ms / 1e3) / 1e12, 3),
-        "min_traffic_gbs": round(2 * Xd.numel() * 2 / (ms / 1e3) / 1e9, 1),
+        "min_traffic_gbs": round(2 * Xd.numel() * Xd.element_size() / (ms / 1e3) / 1e9, 1),
         "kernels_avg_us": {k: round(1e3 * v / steps, 2) for k, v in kernels.items()},
     }
 
@@ -444,11 +447,9 @@ def main():
             }
         line["other_workloads"] = others
     if not args.no_block:
-        # one whole block around BRA at the bf16 workloads' shapes (context, never `value`)
+        # one whole block around BRA at every workload's shape (context, never `value`)
         blocks = {}
         for idx, c in {**CONFIGS, **NEXT_CONFIGS}.items():
-            if c.dtype != "bf16":
-                continue
             n = args.steps if idx == args.workload else max(20, args.steps // 4)
             blocks[c.name] = time_block(c, n, n)
         line["block_forward"] = blocks

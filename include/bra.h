@@ -126,12 +126,12 @@ int bra_forward_padded(const bra_shape *shape, const void *X, const void *Wqkv, 
  * bra_block_params is a HOST struct of DEVICE pointers, all required:
  *   Wpos [C,3,3] (channel, ky, kx), W1 [C, hidden], W2 [hidden, C], Wqkv, Wo, Wlce as above,
  *   all of shape->dtype; the vectors bpos, ln*_gamma, ln*_beta, b2 [C] and b1 [hidden] float32.
- * Built for dtype BRA_BF16, C a multiple of 64 up to 4096 and hidden a multiple of 64; the
+ * bf16 tensors with C and hidden multiples of 64 run on matrix-core kernels; float32 tensors and
+ * all other sizes on scalar float32 kernels (C up to 4096).  The
  * BRA stage runs on the family that bra_forward would pick for `shape` (shape->path applies).
  * Intermediate tensors (X1, LayerNorm1's output, BRA's output, X2, the hidden layer) live in
- * `ws` in bf16; arithmetic is float32.  Xout may be the same buffer as X.  Ir_out_opt /
- * Ir_in_opt as in bra_forward.  Errors: as bra_forward; UNSUPPORTED for other dtypes / sizes,
- * SHAPE for hidden < 1 or eps < 0. */
+ * `ws` in shape->dtype; arithmetic is float32.  Xout may be the same buffer as X.  Ir_out_opt /
+ * Ir_in_opt as in bra_forward.  Errors: as bra_forward; SHAPE for hidden < 1 or eps < 0. */
 typedef struct bra_block_params {
     const void *Wpos;
     const float *bpos;

@@ -661,20 +661,31 @@ BlockWs carve_block(const Dims &D, int hidden, size_t bra_bytes, void *ws)
 
 }  // namespace
 
+// The matrix-core kernels of this file take bf16 tensors with C and hidden multiples of 64;
+// everything else runs on the scalar kernels.
+static bool block_fast(const Dims &D, int hidden)
+{
+    static const bool off = getenv("BRA_BLOCK_GENERIC") != nullptr;
+    return !off && D.dtype == BRA_BF16 && D.C % 64 == 0 && D.C <= 4096 && hidden % 64 == 0 && hidden <= (1 << 16);
+}
+
 bool block_supported(const Dims &D, int hidden)
 {
-    return D.dtype == BRA_BF16 && D.C % 64 == 0 && D.C <= 4096 && hidden % 64 == 0 && hidden <= (1 << 16) &&
-           (long)D.B * D.N <= 0x7fffffffL / 64;
+    if ((long)D.B * D.N > 0x7fffffffL / 64 || hidden > (1 << 20)) return false;
+    return block_fast(D, hidden) || (size_t)D.C * sizeof(float) * 4 <= 64 * 1024;
 }
 
 size_t block_workspace_bytes(const Dims &D, int hidden, size_t bra_bytes)
 {
+    if (!block_fast(D, hidden)) return generic_block_workspace_bytes(D, hidden, bra_bytes);
     return carve_block(D, hidden, bra_bytes, nullptr).bytes;
 }
 
 int block_forward(const Dims &D, int hidden, float eps, const void *X, const bra_block_params &p, void *Xout,
                   int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, size_t bra_bytes, int path, hipStream_t st)
 {
+    if (!block_fast(D, hidden))
+        return generic_block_forward(D, hidden, eps, X, p, Xout, Ir_out_opt, Ir_in_opt, ws, bra_bytes, path, st);
     const BlockWs w = carve_block(D, hidden, bra_bytes, ws);
     const long M = (long)D.B * D.N;
     int rc = launch_token_ln<kPos>(D, (const bf16_t *)X, nullptr, p, p.ln1_gamma, p.ln1_beta, w.x1, w.xn, eps, st);

@@ -40,6 +40,27 @@ __device__ inline float load_f32(const bf16_t *p) { return bf16_to_f32(*p); }
 __device__ inline void store_from_f32(float *p, float v) { *p = v; }
 __device__ inline void store_from_f32(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 
+// GELU(t) = t Phi(t) = t / 2 + |t| (1 - erfc(|t| / sqrt 2)) / 2.  erfc by the approximation of
+// Abramowitz & Stegun 7.1.28, erfc(x) = (1 + a1 x + .. + a6 x^6)^-16 (absolute error below
+// 3e-7, far inside what a bf16 result resolves; one reciprocal is its only slow instruction);
+// the coefficients below are a_k / 2^(k/2), so that the polynomial takes |t| itself.
+__device__ __forceinline__ float gelu_f32(float t)
+{
+    const float a = fabsf(t);
+    float p = fmaf(5.382975000e-06f, a, 4.889063564e-05f);
+    p = fmaf(p, a, 3.800357500e-05f);
+    p = fmaf(p, a, 3.277626324e-03f);
+    p = fmaf(p, a, 2.114100615e-02f);
+    p = fmaf(p, a, 4.986734697e-02f);
+    p = fmaf(p, a, 1.0f);
+    p *= p;
+    p *= p;
+    p *= p;
+    p *= p;                                                  // overflows to infinity for large |t|: erfc = 0
+    const float q = fmaf(__builtin_amdgcn_rcpf(p), -0.5f, 0.5f);
+    return fmaf(a, q, 0.5f * t);
+}
+
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // A routing index as the kernels use it: entries of a caller-supplied index outside
@@ -98,6 +119,12 @@ int gemm_bf16(const bf16_t *In, const bf16_t *W, long M, int K, int Nout, bf16_t
 size_t padded_workspace_bytes(const Dims &Dp, size_t bra_bytes);
 int padded_forward(const Dims &Dp, int H, int W, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
                    void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, int path, hipStream_t st);
+
+// Whole block with the scalar float32 kernels (bra_generic.hip): any dtype, C and hidden.
+size_t generic_block_workspace_bytes(const Dims &D, int hidden, size_t bra_bytes);
+int generic_block_forward(const Dims &D, int hidden, float eps, const void *X, const bra_block_params &p, void *Xout,
+                          int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, size_t bra_bytes, int path,
+                          hipStream_t st);
 
 // Whole block around BRA (bra_block.hip).  `path` is the kernel family of the BRA stage
 // (BRA_PATH_GENERIC or BRA_PATH_MFMA), `bra_bytes` that family's workspace size.

@@ -26,7 +26,9 @@ constexpr int kAttnMaxD = 256;      // head width limit of the generic attention
 template <typename TA, typename TB, typename TO>
 __global__ __launch_bounds__(256) void gen_gemm(const TA *__restrict__ A, int lda,
                                                 const TB *__restrict__ Bm, int ldb,
-                                                TO *__restrict__ Out, int ldo, int M, int N, int K)
+                                                TO *__restrict__ Out, int ldo, int M, int N, int K,
+                                                const float *__restrict__ bias = nullptr,
+                                                const TO *__restrict__ res = nullptr, int gelu = 0)
 {
     __shared__ float As[16][64 + 4];
     __shared__ float Bs[16][64];
@@ -75,7 +77,13 @@ __global__ __launch_bounds__(256) void gen_gemm(const TA *__restrict__ A, int ld
         if (gm >= M) continue;
         for (int j = 0; j < 4; ++j) {
             int gn = n0 + tx * 4 + j;
-            if (gn < N) store_from_f32(Out + gm * ldo + gn, acc[i][j]);
+            if (gn >= N) continue;
+            // optional epilogue: + bias[column], GELU, + res[row][column] (the layout of Out)
+            float v = acc[i][j];
+            if (bias) v += bias[gn];
+            if (gelu) v = gelu_f32(v);
+            if (res) v += load_f32(res + gm * ldo + gn);
+            store_from_f32(Out + gm * ldo + gn, v);
         }
     }
 }
@@ -460,7 +468,140 @@ int forward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *Wl
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
+// ---------------------------------------------------------------------------
+// Whole block (Sec. 3.4) with scalar kernels.  One wavefront per token; lane l owns channels
+// l, l + 64, ..  POS: Sum = A + DWConv3x3(A) + bpos (cross-correlation, zero padding 1);
+// otherwise Sum = A + Badd.  Norm = LayerNorm(Sum) over the token's C channels from the
+// float32 values (biased variance, eps inside the root), which wait in LDS between the passes.
+template <typename T, bool POS>
+__global__ __launch_bounds__(256) void gen_token_ln(const T *A, const T *__restrict__ Badd, const T *__restrict__ Wpos,
+                                                    const float *__restrict__ bpos, const float *__restrict__ gamma,
+                                                    const float *__restrict__ beta, T *Sum, T *__restrict__ Norm,
+                                                    int H, int W, int C, long tokens, float eps)
+{
+    extern __shared__ float strips[];                 // [4 wavefronts][C]
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    float *strip = strips + (size_t)wave * C;
+    const long tok = (long)blockIdx.x * 4 + wave;
+    if (tok >= tokens) return;                        // whole wavefronts leave; no barrier follows
+    const int x = (int)(tok % W), y = (int)((tok / W) % H);
+    const T *centre = A + (size_t)tok * C;
+    float s = 0.f;
+    for (int c = lane; c < C; c += kWave) {
+        float v = load_f32(centre + c);
+        if (POS) {
+            float acc = v + bpos[c];
+            for (int ky = 0; ky < 3; ++ky) {
+                const int yy = y + ky - 1;
+                if (yy < 0 || yy >= H) continue;
+                for (int kx = 0; kx < 3; ++kx) {
+                    const int xx = x + kx - 1;
+                    if (xx < 0 || xx >= W) continue;
+                    acc = fmaf(load_f32(Wpos + (size_t)c * 9 + 3 * ky + kx),
+                               load_f32(centre + ((long)(ky - 1) * W + (kx - 1)) * C + c), acc);
+                }
+            }
+            v = acc;
+        } else {
+            v += load_f32(Badd + (size_t)tok * C + c);
+        }
+        strip[c] = v;
+        s += v;
+    }
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    const float mean = s / (float)C;
+    float q = 0.f;
+    for (int c = lane; c < C; c += kWave) { const float d = strip[c] - mean; q = fmaf(d, d, q); }
+    for (int off = 32; off > 0; off >>= 1) q += __shfl_xor(q, off);
+    const float rstd = 1.0f / sqrtf(q / (float)C + eps);
+    for (int c = lane; c < C; c += kWave) {
+        const float v = strip[c];
+        store_from_f32(Sum + (size_t)tok * C + c, v);             // may overwrite A: this lane has read it
+        store_from_f32(Norm + (size_t)tok * C + c, fmaf((v - mean) * rstd, gamma[c], beta[c]));
+    }
+}
+
+struct GenBlockWs {
+    void *x1, *xn, *y, *hd, *inner;
+    size_t bytes;
+};
+
+GenBlockWs carve_gen_block(const Dims &D, int hidden, size_t bra_bytes, void *ws)
+{
+    char *base = (char *)ws;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        void *ptr = base ? base + off : nullptr;
+        off += align256(bytes);
+        return ptr;
+    };
+    const size_t es = D.dtype == BRA_BF16 ? 2 : 4, tokens = (size_t)D.B * D.N;
+    GenBlockWs w;
+    w.x1 = take(tokens * D.C * es);
+    w.xn = take(tokens * D.C * es);
+    w.y = take(tokens * D.C * es);
+    w.hd = take(tokens * hidden * es);
+    w.inner = take(bra_bytes);
+    w.bytes = off;
+    return w;
+}
+
+template <typename T>
+int block_t(const Dims &D, int hidden, float eps, const T *X, const bra_block_params &p, T *Xout, int32_t *Ir_out_opt,
+            const int32_t *Ir_in_opt, void *ws, size_t bra_bytes, int path, hipStream_t st)
+{
+    const GenBlockWs w = carve_gen_block(D, hidden, bra_bytes, ws);
+    T *x1 = (T *)w.x1, *xn = (T *)w.xn, *y = (T *)w.y, *hd = (T *)w.hd;
+    const long M = (long)D.B * D.N;
+    const unsigned tgrid = (unsigned)((M + 3) / 4);
+    const size_t strip = (size_t)4 * D.C * sizeof(float);
+    {
+        ProfScope ps(st, K_BLK_POS_LN);
+        hipLaunchKernelGGL((gen_token_ln<T, true>), dim3(tgrid), dim3(256), strip, st, X, (const T *)nullptr,
+                           (const T *)p.Wpos, p.bpos, p.ln1_gamma, p.ln1_beta, x1, xn, D.H, D.W, D.C, M, eps);
+    }
+    if (hipGetLastError() != hipSuccess) return BRA_ERR_LAUNCH;
+    int rc = (path == BRA_PATH_MFMA)
+                 ? mfma_forward(D, xn, p.Wqkv, p.Wo, p.Wlce, y, Ir_out_opt, Ir_in_opt, w.inner, st)
+                 : generic_forward(D, xn, p.Wqkv, p.Wo, p.Wlce, y, Ir_out_opt, Ir_in_opt, w.inner, st);
+    if (rc != BRA_OK) return rc;
+    {
+        ProfScope ps(st, K_BLK_ADD_LN);
+        hipLaunchKernelGGL((gen_token_ln<T, false>), dim3(tgrid), dim3(256), strip, st, x1, y, (const T *)nullptr,
+                           (const float *)nullptr, p.ln2_gamma, p.ln2_beta, x1, xn, D.H, D.W, D.C, M, eps);
+    }
+    {
+        ProfScope ps(st, K_BLK_MLP_IN);
+        dim3 g((unsigned)((M + 63) / 64), (unsigned)((hidden + 63) / 64));
+        hipLaunchKernelGGL((gen_gemm<T, T, T>), g, dim3(256), 0, st, xn, D.C, (const T *)p.W1, hidden, hd, hidden,
+                           (int)M, hidden, D.C, p.b1, (const T *)nullptr, 1);
+    }
+    {
+        ProfScope ps(st, K_BLK_MLP_OUT);
+        dim3 g((unsigned)((M + 63) / 64), (unsigned)((D.C + 63) / 64));
+        hipLaunchKernelGGL((gen_gemm<T, T, T>), g, dim3(256), 0, st, hd, hidden, (const T *)p.W2, D.C, Xout, D.C,
+                           (int)M, D.C, hidden, p.b2, x1, 0);
+    }
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
 }  // namespace
+
+size_t generic_block_workspace_bytes(const Dims &D, int hidden, size_t bra_bytes)
+{
+    return carve_gen_block(D, hidden, bra_bytes, nullptr).bytes;
+}
+
+int generic_block_forward(const Dims &D, int hidden, float eps, const void *X, const bra_block_params &p, void *Xout,
+                          int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, size_t bra_bytes, int path,
+                          hipStream_t st)
+{
+    if (D.dtype == BRA_BF16)
+        return block_t<bf16_t>(D, hidden, eps, (const bf16_t *)X, p, (bf16_t *)Xout, Ir_out_opt, Ir_in_opt, ws,
+                               bra_bytes, path, st);
+    return block_t<float>(D, hidden, eps, (const float *)X, p, (float *)Xout, Ir_out_opt, Ir_in_opt, ws, bra_bytes,
+                          path, st);
+}
 
 bool generic_supported(const Dims &D)
 {

@@ -55,27 +55,6 @@ __device__ __forceinline__ u32x2 pack4(f32x4 v)
 __device__ __forceinline__ float bf16_lo(unsigned u) { return __builtin_bit_cast(float, u << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
 
-// GELU(t) = t Phi(t) = t / 2 + |t| (1 - erfc(|t| / sqrt 2)) / 2.  erfc by the approximation of
-// Abramowitz & Stegun 7.1.28, erfc(x) = (1 + a1 x + .. + a6 x^6)^-16 (absolute error below
-// 3e-7, far inside what a bf16 result resolves; one reciprocal is its only slow instruction);
-// the coefficients below are a_k / 2^(k/2), so that the polynomial takes |t| itself.
-__device__ __forceinline__ float gelu_f32(float t)
-{
-    const float a = fabsf(t);
-    float p = fmaf(5.382975000e-06f, a, 4.889063564e-05f);
-    p = fmaf(p, a, 3.800357500e-05f);
-    p = fmaf(p, a, 3.277626324e-03f);
-    p = fmaf(p, a, 2.114100615e-02f);
-    p = fmaf(p, a, 4.986734697e-02f);
-    p = fmaf(p, a, 1.0f);
-    p *= p;
-    p *= p;
-    p *= p;
-    p *= p;                                                  // overflows to infinity for large |t|: erfc = 0
-    const float q = fmaf(__builtin_amdgcn_rcpf(p), -0.5f, 0.5f);
-    return fmaf(a, q, 0.5f * t);
-}
-
 // row / width without an integer division; exact for the small non-negative values
 // that occur here (row < 2^20).
 __device__ __forceinline__ int fast_div(int row, float width_inv)

@@ -13,7 +13,7 @@ import torch
 
 import paper_2303_08810_amd as bra
 from oracle import block as ob
-from parity_util import TOL_BF16_REL, check_routing, to_device, to_numpy
+from parity_util import TOL_BF16_REL, TOL_F32_ABS, check_routing, to_device, to_numpy
 from synthetic_inputs import (BASE_SEED, CONFIGS, NEXT_CONFIGS, make_block_inputs, make_block_params,
                               make_inputs)
 
@@ -22,34 +22,40 @@ pytestmark = pytest.mark.gpu
 EPS = 1e-6
 
 
-def device_params(P):
+def device_params(P, dtype="bf16"):
     out = {}
     for name in bra.BraBlockParams.FIELDS:
         if name in bra.BraBlockParams.MATRICES:
-            out[name] = to_device(P[name], "bf16")
+            out[name] = to_device(P[name], dtype)
         else:
             out[name] = torch.from_numpy(np.ascontiguousarray(P[name], dtype=np.float32)).cuda()
     return out
 
 
-def compare_block(Xn, P, S, k, heads, path="auto", images=None, in_place=False, forced=None):
-    print(f"block case shape={Xn.shape} hidden={P['W1'].shape[1]} S={S} k={k} heads={heads} path={path} "
-          f"in_place={in_place} forced={forced is not None}", flush=True)
-    X = to_device(Xn, "bf16")
-    dP = device_params(P)
+def compare_block(Xn, P, S, k, heads, path="auto", images=None, in_place=False, forced=None, dtype="bf16"):
+    print(f"block case dtype={dtype} shape={Xn.shape} hidden={P['W1'].shape[1]} S={S} k={k} heads={heads} "
+          f"path={path} in_place={in_place} forced={forced is not None}", flush=True)
+    X = to_device(Xn, dtype)
+    dP = device_params(P, dtype)
     Iin = torch.from_numpy(np.ascontiguousarray(forced, dtype=np.int32)).cuda() if forced is not None else None
     Xout, Ir = bra.bra_block_forward(X, dP, S, k, heads, eps=EPS, want_Ir=True, path=path, Ir_in=Iin,
                                      out=X if in_place else None)
     torch.cuda.synchronize()
     got, Ir = to_numpy(Xout), Ir.cpu().numpy()
     sel = np.arange(Xn.shape[0]) if images is None else np.asarray(images)
-    kw = dict(S=S, k=k, heads=heads, eps=EPS, store="bf16", threads=8)
+    kw = dict(S=S, k=k, heads=heads, eps=EPS, store="bf16" if dtype == "bf16" else "f64", threads=8)
     if forced is None:
         free = ob.block_forward(Xn[sel], P, **kw)
         check_routing(Ir[sel], free["Ar"], k)
     else:
         np.testing.assert_array_equal(Ir, forced)
     ref = ob.block_forward(Xn[sel], P, Ir_in=Ir[sel], **kw)
+    if dtype == "f32":
+        # float32 tensors: the bar of the float32 BRA path, max-abs 1e-4, on the block's output
+        err = float(np.abs(got[sel].astype(np.float64) - ref["Xout"]).max())
+        print(f"  max-abs error {err:.3e}", flush=True)
+        assert err <= TOL_F32_ABS, f"max-abs error {err:.3e} > {TOL_F32_ABS}"
+        return err
     upd_ref = ref["Xout"] - Xn[sel]
     upd = got[sel].astype(np.float64) - Xn[sel]
     rel = float(np.abs(upd - upd_ref).max() / np.abs(upd_ref).max())
@@ -63,9 +69,9 @@ def compare_block(Xn, P, S, k, heads, path="auto", images=None, in_place=False, 
     return rel
 
 
-def inputs(B, H, W, C, seed, expansion=3):
-    X, Wqkv, Wo, Wlce = make_inputs(B, H, W, C, seed=seed, dtype="bf16")
-    P = make_block_params(C, expansion * C, seed=seed + 1, dtype="bf16")
+def inputs(B, H, W, C, seed, expansion=3, dtype="bf16", hidden=None):
+    X, Wqkv, Wo, Wlce = make_inputs(B, H, W, C, seed=seed, dtype=dtype)
+    P = make_block_params(C, hidden or expansion * C, seed=seed + 1, dtype=dtype)
     P.update(Wqkv=Wqkv, Wo=Wo, Wlce=Wlce)
     return X, P
 
@@ -124,6 +130,32 @@ def test_block_random_shapes(B, H, W, C, heads, S, k, e):
     compare_block(X, P, S, k, heads)
 
 
+# (dtype, B, H, W, C, heads, S, k, hidden): the scalar kernels take float32 tensors and the bf16
+# shapes the matrix-core kernels are not built for (C or hidden not a multiple of 64)
+SCALAR_BLOCK_SHAPES = [
+    ("f32", 1, 28, 28, 64, 2, 7, 4, 192),
+    ("f32", 2, 12, 20, 48, 3, 4, 3, 100),
+    ("f32", 1, 7, 7, 130, 2, 7, 49, 260),
+    ("f32", 3, 6, 9, 32, 1, 3, 2, 32),
+    ("bf16", 2, 12, 12, 48, 3, 3, 2, 144),
+    ("bf16", 1, 14, 14, 64, 2, 7, 4, 100),
+]
+
+
+@pytest.mark.parametrize("dtype,B,H,W,C,heads,S,k,hidden", SCALAR_BLOCK_SHAPES)
+def test_block_scalar_kernels(dtype, B, H, W, C, heads, S, k, hidden):
+    X, P = inputs(B, H, W, C, seed=4600 + C + hidden, dtype=dtype, hidden=hidden)
+    compare_block(X, P, S, k, heads, dtype=dtype)
+
+
+def test_block_float32_in_place_and_forced_routing():
+    X, P = inputs(2, 14, 14, 64, seed=4700, dtype="f32")
+    compare_block(X, P, 7, 4, 2, dtype="f32", in_place=True)
+    r = np.random.Generator(np.random.PCG64(4701))
+    forced = np.stack([np.stack([r.permutation(49)[:4] for _ in range(49)]) for _ in range(2)]).astype(np.int32)
+    compare_block(X, P, 7, 4, 2, dtype="f32", forced=forced)
+
+
 def test_block_generic_family_for_bra():
     X, P = inputs(2, 14, 14, 64, seed=4100)
     compare_block(X, P, 7, 4, 2, path="generic")
@@ -157,13 +189,14 @@ def test_block_named_workloads_full_size(idx, images):
     compare_block(X, P, cfg.S, cfg.k, cfg.heads, images=images)
 
 
-def test_block_rejects_what_it_is_not_built_for():
+def test_block_rejects_invalid_arguments():
     X, P = inputs(1, 14, 14, 64, seed=4400)
     Xd, dP = to_device(X, "bf16"), device_params(P)
     with pytest.raises(bra.BraError) as e:
-        bra.bra_block_forward(Xd.float(), {k: (v.float() if k in bra.BraBlockParams.MATRICES else v)
-                                           for k, v in dP.items()}, 7, 4, 2)
-    assert e.value.code == -6
-    with pytest.raises(bra.BraError) as e:
         bra.bra_block_forward(Xd, dP, 7, 4, 2, eps=-1.0)
     assert e.value.code == -2
+    with pytest.raises(bra.BraError) as e:
+        bra.bra_block_forward(Xd, dP, 7, 50, 2)
+    assert e.value.code == -3
+    with pytest.raises(ValueError):
+        bra.bra_block_forward(Xd, {**dP, "W1": dP["W1"].float()}, 7, 4, 2)
