@@ -60,8 +60,8 @@ __global__ __launch_bounds__(256) void k_pool_wide(const bf16_t *__restrict__ X,
 // Out[m][o] = sum_k In[m][k] W[k][o] (W row-major with ldw columns, as the caller holds it)
 // for a tile of 64 rows m x 128 outputs o per workgroup, the contraction in chunks of 64
 // staged in LDS (the next chunk is requested while the current one is multiplied).
-// Wavefront w owns rows 16 w .. 16 w + 15; the product is formed transposed
-// (D[output 16 t + 4 g + jj][row i]) so that a lane stores 4 consecutive outputs of one row;
+// The four wavefronts split the tile 2 x 2 (32 rows x 64 outputs each); the product is formed
+// transposed (D[output 16 t + 4 g + jj][row i]) so that a lane stores 4 consecutive outputs of one row;
 // its W operand (rows = outputs) comes out of the row-major chunk by the transposing LDS read.
 // Output column o goes to buffer o / cols (three buffers of `cols` columns each, e.g. Q, K,
 // V), column o % cols.
@@ -140,9 +140,14 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
         }
     };
 
-    f32x4 acc[8];
+    // wavefront (wr, wc) owns rows 32 wr .. 32 wr + 31 (two 16-row tiles) and outputs 64 wc ..
+    // 64 wc + 63 (four tiles) of the workgroup's 64 x 128: a W fragment serves two row tiles
+    const int wr = wave / 2, wc = wave % 2;
+    f32x4 acc[2][4];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[rt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     if (!F32OUT && out.bias && tid < 128) bs[tid] = out.bias[min(o0 + tid, Nout - 1)];   // read after the loop's barriers
     request(0);
     for (int k0 = 0; k0 < K; k0 += 64) {
@@ -152,52 +157,59 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
         if (k0 + 64 < K) request(k0 + 64);
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            bf16x8 xb[NT];
+            bf16x8 xb[2][NT];
 #pragma unroll
-            for (int q = 0; q < NT; ++q)
-                xb[q] = *(const bf16x8 *)(Xs + (q * 64 + 16 * wave + i) * P + 32 * ks + 8 * g);
+            for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const bf16_t *wp = Ws + (32 * ks + 8 * g + i / 4) * PW + 16 * t + 4 * (i % 4);
+                for (int q = 0; q < NT; ++q)
+                    xb[rt][q] = *(const bf16x8 *)(Xs + (q * 64 + 32 * wr + 16 * rt + i) * P + 32 * ks + 8 * g);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const bf16_t *wp = Ws + (32 * ks + 8 * g + i / 4) * PW + 64 * wc + 16 * t + 4 * (i % 4);
                 const u32x2 w0 = __builtin_bit_cast(u32x2, lds_read_tr16(wp));
                 const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 4 * PW));
                 const bf16x8 wf = __builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]});
 #pragma unroll
-                for (int q = NT - 1; q >= 0; --q) acc[t] = mfma16(wf, xb[q], acc[t]);
+                for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                    for (int q = NT - 1; q >= 0; --q) acc[rt][t] = mfma16(wf, xb[rt][q], acc[rt][t]);
             }
         }
     }
-    const int m = m0 + 16 * wave + i;
-    if (m >= M) return;
-    // the residual's pieces are requested together, ahead of the arithmetic (one by one behind
-    // the loop's exit test their latencies would add up)
-    u32x2 rv[8];
-    if (!F32OUT && out.res) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int o = min(o0 + 16 * t + 4 * g, Nout - 4);
-            rv[t] = *(const u32x2 *)(out.res + (size_t)m * out.cols + o);
-        }
-    }
+    for (int rt = 0; rt < 2; ++rt) {
+        const int m = m0 + 32 * wr + 16 * rt + i;
+        if (m >= M) continue;
+        // the residual's pieces are requested together, ahead of the arithmetic (one by one
+        // behind the loop's exit test their latencies would add up)
+        u32x2 rv[4];
+        if (!F32OUT && out.res) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        const int o = o0 + 16 * t + 4 * g;
-        if (o >= Nout) break;
-        const int which = o / out.cols, col = o % out.cols;
-        if (F32OUT) {
-            *(f32x4 *)((float *)out.buf[which] + (size_t)m * out.cols + col) = acc[t];
-        } else {
-            f32x4 v = acc[t];
-            if (out.bias) {
-                const f32x4 bv = *(const f32x4 *)(bs + 16 * t + 4 * g);
-                v = f32x4{v[0] + bv[0], v[1] + bv[1], v[2] + bv[2], v[3] + bv[3]};
+            for (int t = 0; t < 4; ++t) {
+                const int o = min(o0 + 64 * wc + 16 * t + 4 * g, Nout - 4);
+                rv[t] = *(const u32x2 *)(out.res + (size_t)m * out.cols + o);
             }
-            if (out.gelu) v = f32x4{gelu_f32(v[0]), gelu_f32(v[1]), gelu_f32(v[2]), gelu_f32(v[3])};
-            if (out.res)
-                v = f32x4{v[0] + bf16_lo(rv[t][0]), v[1] + bf16_hi(rv[t][0]), v[2] + bf16_lo(rv[t][1]),
-                          v[3] + bf16_hi(rv[t][1])};
-            *(u32x2 *)((bf16_t *)out.buf[which] + (size_t)m * out.cols + col) = pack4(v);
-            if (which < 2 && out.f32[which]) *(f32x4 *)(out.f32[which] + (size_t)m * out.cols + col) = acc[t];
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int o = o0 + 64 * wc + 16 * t + 4 * g;
+            if (o >= Nout) break;
+            const int which = o / out.cols, col = o % out.cols;
+            if (F32OUT) {
+                *(f32x4 *)((float *)out.buf[which] + (size_t)m * out.cols + col) = acc[rt][t];
+            } else {
+                f32x4 v = acc[rt][t];
+                if (out.bias) {
+                    const f32x4 bv = *(const f32x4 *)(bs + 64 * wc + 16 * t + 4 * g);
+                    v = f32x4{v[0] + bv[0], v[1] + bv[1], v[2] + bv[2], v[3] + bv[3]};
+                }
+                if (out.gelu) v = f32x4{gelu_f32(v[0]), gelu_f32(v[1]), gelu_f32(v[2]), gelu_f32(v[3])};
+                if (out.res)
+                    v = f32x4{v[0] + bf16_lo(rv[t][0]), v[1] + bf16_hi(rv[t][0]), v[2] + bf16_lo(rv[t][1]),
+                              v[3] + bf16_hi(rv[t][1])};
+                *(u32x2 *)((bf16_t *)out.buf[which] + (size_t)m * out.cols + col) = pack4(v);
+                if (which < 2 && out.f32[which]) *(f32x4 *)(out.f32[which] + (size_t)m * out.cols + col) = acc[rt][t];
+            }
         }
     }
 }
