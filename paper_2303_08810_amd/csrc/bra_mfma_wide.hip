@@ -69,6 +69,8 @@ __global__ __launch_bounds__(256) void k_pool_wide(const bf16_t *__restrict__ X,
 // bf16.  F32OUT: Out is float32, else bf16.
 constexpr int kGemmPitch = 80;      // bf16 per LDS row of In: 64 + 16 (rows of 160 bytes)
 constexpr int kGemmPitchW = 144;    // of W: 128 + 16 (rows of 288 bytes)
+constexpr int kGemmGroupW = 64;     // and 128 bytes more after every 8 rows: the neighbouring lane group of a
+                                    // transposing read (8 rows further on) then meets the other half of the banks
 
 struct GemmOut {
     void *buf[3];
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
     constexpr int P = kGemmPitch, PW = kGemmPitchW, NT = SPLIT ? 3 : 1;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ws = (bf16_t *)smem;                 // [64 k][PW]
-    bf16_t *Xs = Ws + 64 * PW;                   // [NT][64][P]
+    bf16_t *Xs = Ws + 64 * PW + 8 * kGemmGroupW; // [NT][64][P]
     float *bs = (float *)(Xs + NT * 64 * P);     // [128]: the tile's slice of the bias
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave, g = lane / 16, i = lane % 16;
     const int otiles = (Nout + 127) / 128;
@@ -121,7 +123,7 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int idx = tid + 256 * u;
-            *(u32x4 *)(Ws + (idx / 16) * PW + (idx % 16) * 8) = wreg[u];
+            *(u32x4 *)(Ws + (idx / 16) * PW + (idx / 128) * kGemmGroupW + (idx % 16) * 8) = wreg[u];
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -165,7 +167,8 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
                     xb[rt][q] = *(const bf16x8 *)(Xs + (q * 64 + 32 * wr + 16 * rt + i) * P + 32 * ks + 8 * g);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const bf16_t *wp = Ws + (32 * ks + 8 * g + i / 4) * PW + 64 * wc + 16 * t + 4 * (i % 4);
+                const bf16_t *wp = Ws + (32 * ks + 8 * g + i / 4) * PW + (4 * ks + g) * kGemmGroupW + 64 * wc + 16 * t +
+                                   4 * (i % 4);
                 const u32x2 w0 = __builtin_bit_cast(u32x2, lds_read_tr16(wp));
                 const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 4 * PW));
                 const bf16x8 wf = __builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]});
@@ -216,7 +219,8 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
 
 constexpr size_t gemm_smem(bool split)
 {
-    return (size_t)64 * kGemmPitchW * 2 + (size_t)(split ? 3 : 1) * 64 * kGemmPitch * 2 + 128 * sizeof(float);
+    return (size_t)(64 * kGemmPitchW + 8 * kGemmGroupW) * 2 + (size_t)(split ? 3 : 1) * 64 * kGemmPitch * 2 +
+           128 * sizeof(float);
 }
 
 // ---------------------------------------------------------------------------
