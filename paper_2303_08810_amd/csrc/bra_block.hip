@@ -2,14 +2,16 @@
 //
 //   k_token_ln<POS>   X1 = X + DWConv3x3(X) + bpos,  Xn = LayerNorm1(X1)      one pass over X
 //   BRA               Y  = BRA(Xn)                   (Eq. 2-7; the kernel family picked for the shape)
-//   C = 64:  k_mlp_fused64     Xout = X2 + MLP(LayerNorm2(X2)), X2 = X1 + Y, in one kernel
+//   C <= 256:  k_mlp_fused64 (C = 64, weights resident in LDS) or k_mlp_stream (weights streamed):
+//                     Xout = X2 + MLP(LayerNorm2(X2)), X2 = X1 + Y, in one kernel
 //   otherwise:
 //   k_token_ln<ADD>   X2 = X1 + Y,                   Xn = LayerNorm2(X2)
 //   gemm_bf16         Hd = GELU(Xn W1 + b1)          bias and activation in the product's epilogue
 //   gemm_bf16         Xout = X2 + Hd W2 + b2         bias and residual in the epilogue
 //
 // The normalisation and residual links follow the pre-norm residual reading stated with the
-// entry point's declaration.
+// entry point's declaration.  float32 tensors and sizes that are not multiples of 64 go to the
+// scalar kernels of the generic family instead.
 #include "bra_mfma_dev.h"
 
 #include <stdlib.h>
