@@ -14,6 +14,8 @@
 //   k_gemm<false> Y = O Wo (Eq. 2)
 #include "bra_mfma_dev.h"
 
+#include <stdlib.h>
+
 namespace bra {
 
 using namespace mfma;
@@ -58,18 +60,17 @@ __global__ __launch_bounds__(256) void k_pool_wide(const bf16_t *__restrict__ X,
 
 // ---------------------------------------------------------------------------
 // Out[m][o] = sum_k In[m][k] W[k][o] (W row-major with ldw columns, as the caller holds it)
-// for a tile of 64 rows m x 128 outputs o per workgroup, the contraction in chunks of 64
+// for a tile of 64 rows m x 32 CW outputs o (128 or 64) per workgroup, the contraction in chunks of 64
 // staged in LDS (the next chunk is requested while the current one is multiplied).
-// The four wavefronts split the tile 2 x 2 (32 rows x 64 outputs each); the product is formed
+// The four wavefronts split the tile 2 x 2 (32 rows x 16 CW outputs each); the product is formed
 // transposed (D[output 16 t + 4 g + jj][row i]) so that a lane stores 4 consecutive outputs of one row;
 // its W operand (rows = outputs) comes out of the row-major chunk by the transposing LDS read.
 // Output column o goes to buffer o / cols (three buffers of `cols` columns each, e.g. Q, K,
 // V), column o % cols.
 // SPLIT: In is float32 and enters as three exact bf16 terms (smallest first); otherwise In is
 // bf16.  F32OUT: Out is float32, else bf16.
-constexpr int kGemmPitch = 80;      // bf16 per LDS row of In: 64 + 16 (rows of 160 bytes)
-constexpr int kGemmPitchW = 144;    // of W: 128 + 16 (rows of 288 bytes)
-constexpr int kGemmGroupW = 64;     // and 128 bytes more after every 8 rows: the neighbouring lane group of a
+constexpr int kGemmPitch = 80;      // bf16 per LDS row of In: 64 + 16 (rows of 160 bytes); W: the tile's width + 16
+constexpr int kGemmGroupW = 64;     // W: 128 bytes more after every 8 rows: the neighbouring lane group of a
                                     // transposing read (8 rows further on) then meets the other half of the banks
 
 struct GemmOut {
@@ -83,28 +84,28 @@ struct GemmOut {
     int gelu;
 };
 
-template <bool SPLIT, bool F32OUT = SPLIT>
+template <bool SPLIT, bool F32OUT = SPLIT, int CW = 4>
 __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const bf16_t *__restrict__ W,
                                               int ldw, int M, int K, int Nout, GemmOut out)
 {
-    constexpr int P = kGemmPitch, PW = kGemmPitchW, NT = SPLIT ? 3 : 1;
+    constexpr int P = kGemmPitch, NT = SPLIT ? 3 : 1, COLS = 32 * CW, PW = COLS + 16;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ws = (bf16_t *)smem;                 // [64 k][PW]
     bf16_t *Xs = Ws + 64 * PW + 8 * kGemmGroupW; // [NT][64][P]
     float *bs = (float *)(Xs + NT * 64 * P);     // [128]: the tile's slice of the bias
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave, g = lane / 16, i = lane % 16;
-    const int otiles = (Nout + 127) / 128;
-    const int m0 = (blockIdx.x / otiles) * 64, o0 = (blockIdx.x % otiles) * 128;
+    const int otiles = (Nout + COLS - 1) / COLS;
+    const int m0 = (blockIdx.x / otiles) * 64, o0 = (blockIdx.x % otiles) * COLS;
 
     // this thread's pieces of a chunk: 4 x 16 bytes of W, and 2 x 16 bytes of bf16 In or
     // 2 x 8 floats of float32 In
-    u32x4 wreg[4], xreg[SPLIT ? 4 : 2];
+    u32x4 wreg[CW], xreg[SPLIT ? 4 : 2];
     auto request = [&](int k0) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < CW; ++u) {
             const int idx = tid + 256 * u;                       // (row k, 8 outputs)
-            const int o = min(o0 + (idx % 16) * 8, Nout - 8);    // columns past the end repeat the last; never stored
-            wreg[u] = *(const u32x4 *)(W + (size_t)(k0 + idx / 16) * ldw + o);
+            const int o = min(o0 + (idx % (COLS / 8)) * 8, Nout - 8);    // columns past the end repeat the last; never stored
+            wreg[u] = *(const u32x4 *)(W + (size_t)(k0 + idx / (COLS / 8)) * ldw + o);
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -121,9 +122,10 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
     };
     auto park = [&]() {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < CW; ++u) {
             const int idx = tid + 256 * u;
-            *(u32x4 *)(Ws + (idx / 16) * PW + (idx / 128) * kGemmGroupW + (idx % 16) * 8) = wreg[u];
+            const int row = idx / (COLS / 8);
+            *(u32x4 *)(Ws + row * PW + (row / 8) * kGemmGroupW + (idx % (COLS / 8)) * 8) = wreg[u];
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -145,12 +147,12 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
     // wavefront (wr, wc) owns rows 32 wr .. 32 wr + 31 (two 16-row tiles) and outputs 64 wc ..
     // 64 wc + 63 (four tiles) of the workgroup's 64 x 128: a W fragment serves two row tiles
     const int wr = wave / 2, wc = wave % 2;
-    f32x4 acc[2][4];
+    f32x4 acc[2][CW];
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) acc[rt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (!F32OUT && out.bias && tid < 128) bs[tid] = out.bias[min(o0 + tid, Nout - 1)];   // read after the loop's barriers
+        for (int t = 0; t < CW; ++t) acc[rt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (!F32OUT && out.bias && tid < COLS) bs[tid] = out.bias[min(o0 + tid, Nout - 1)];   // read after the loop's barriers
     request(0);
     for (int k0 = 0; k0 < K; k0 += 64) {
         if (k0) __syncthreads();          // the previous chunk has been read
@@ -166,8 +168,8 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
                 for (int q = 0; q < NT; ++q)
                     xb[rt][q] = *(const bf16x8 *)(Xs + (q * 64 + 32 * wr + 16 * rt + i) * P + 32 * ks + 8 * g);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const bf16_t *wp = Ws + (32 * ks + 8 * g + i / 4) * PW + (4 * ks + g) * kGemmGroupW + 64 * wc + 16 * t +
+            for (int t = 0; t < CW; ++t) {
+                const bf16_t *wp = Ws + (32 * ks + 8 * g + i / 4) * PW + (4 * ks + g) * kGemmGroupW + 16 * CW * wc + 16 * t +
                                    4 * (i % 4);
                 const u32x2 w0 = __builtin_bit_cast(u32x2, lds_read_tr16(wp));
                 const u32x2 w1 = __builtin_bit_cast(u32x2, lds_read_tr16(wp + 4 * PW));
@@ -185,17 +187,17 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
         if (m >= M) continue;
         // the residual's pieces are requested together, ahead of the arithmetic (one by one
         // behind the loop's exit test their latencies would add up)
-        u32x2 rv[4];
+        u32x2 rv[CW];
         if (!F32OUT && out.res) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int o = min(o0 + 64 * wc + 16 * t + 4 * g, Nout - 4);
+            for (int t = 0; t < CW; ++t) {
+                const int o = min(o0 + 16 * CW * wc + 16 * t + 4 * g, Nout - 4);
                 rv[t] = *(const u32x2 *)(out.res + (size_t)m * out.cols + o);
             }
         }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int o = o0 + 64 * wc + 16 * t + 4 * g;
+        for (int t = 0; t < CW; ++t) {
+            const int o = o0 + 16 * CW * wc + 16 * t + 4 * g;
             if (o >= Nout) break;
             const int which = o / out.cols, col = o % out.cols;
             if (F32OUT) {
@@ -203,7 +205,7 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
             } else {
                 f32x4 v = acc[rt][t];
                 if (out.bias) {
-                    const f32x4 bv = *(const f32x4 *)(bs + 64 * wc + 16 * t + 4 * g);
+                    const f32x4 bv = *(const f32x4 *)(bs + 16 * CW * wc + 16 * t + 4 * g);
                     v = f32x4{v[0] + bv[0], v[1] + bv[1], v[2] + bv[2], v[3] + bv[3]};
                 }
                 if (out.gelu) v = f32x4{gelu_f32(v[0]), gelu_f32(v[1]), gelu_f32(v[2]), gelu_f32(v[3])};
@@ -217,9 +219,9 @@ __global__ __launch_bounds__(256) void k_gemm(const void *__restrict__ In, const
     }
 }
 
-constexpr size_t gemm_smem(bool split)
+constexpr size_t gemm_smem(bool split, int cw = 4)
 {
-    return (size_t)(64 * kGemmPitchW + 8 * kGemmGroupW) * 2 + (size_t)(split ? 3 : 1) * 64 * kGemmPitch * 2 +
+    return (size_t)(64 * (32 * cw + 16) + 8 * kGemmGroupW) * 2 + (size_t)(split ? 3 : 1) * 64 * kGemmPitch * 2 +
            128 * sizeof(float);
 }
 
@@ -467,22 +469,35 @@ WideWs carve(const Dims &D, void *ws)
     return w;
 }
 
+template <bool SPLIT, bool F32OUT, int CW>
+int launch_gemm_tile(const void *In, const bf16_t *W, int ldw, long M, int K, int Nout, GemmOut out, int kernel_id,
+                     hipStream_t st)
+{
+    static bool opted = false;
+    if (!opted) {
+        if (hipFuncSetAttribute((const void *)k_gemm<SPLIT, F32OUT, CW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)gemm_smem(SPLIT, CW)) != hipSuccess)
+            return BRA_ERR_LAUNCH;
+        opted = true;
+    }
+    const long grid = ((M + 63) / 64) * ((Nout + 32 * CW - 1) / (32 * CW));
+    ProfScope ps(st, kernel_id);
+    hipLaunchKernelGGL((k_gemm<SPLIT, F32OUT, CW>), dim3((unsigned)grid), dim3(256), gemm_smem(SPLIT, CW), st, In, W,
+                       ldw, (int)M, K, Nout, out);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
 template <bool SPLIT, bool F32OUT = SPLIT>
 int launch_gemm(const void *In, const bf16_t *W, int ldw, long M, int K, int Nout, GemmOut out, int kernel_id,
                 hipStream_t st)
 {
-    static bool opted = false;
-    if (!opted) {
-        if (hipFuncSetAttribute((const void *)k_gemm<SPLIT, F32OUT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)gemm_smem(SPLIT)) != hipSuccess)
-            return BRA_ERR_LAUNCH;
-        opted = true;
-    }
-    const long grid = ((M + 63) / 64) * ((Nout + 127) / 128);
-    ProfScope ps(st, kernel_id);
-    hipLaunchKernelGGL((k_gemm<SPLIT, F32OUT>), dim3((unsigned)grid), dim3(256), gemm_smem(SPLIT), st, In, W, ldw,
-                       (int)M, K, Nout, out);
-    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+    // 64 x 64 tiles (twice the workgroups, six wavefronts per SIMD instead of four) where 64 x 128
+    // tiles would leave the chip under-filled; measured: the narrow tile wins below a few hundred
+    // wide tiles and loses above about a thousand
+    static const long narrow_below = getenv("BRA_GEMM_NARROW") ? atol(getenv("BRA_GEMM_NARROW")) : 400;
+    if (((M + 63) / 64) * ((Nout + 127) / 128) < narrow_below)
+        return launch_gemm_tile<SPLIT, F32OUT, 2>(In, W, ldw, M, K, Nout, out, kernel_id, st);
+    return launch_gemm_tile<SPLIT, F32OUT, 4>(In, W, ldw, M, K, Nout, out, kernel_id, st);
 }
 
 // A^r rows and top-k from the float32 Q^r, K^r in the workspace.
