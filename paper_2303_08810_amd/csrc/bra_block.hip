@@ -27,7 +27,7 @@ constexpr int kPos = 0, kAdd = 1;
 // A token's C channels are shared by G consecutive lanes (G a power of two that divides
 // C / 8, at most 64): lane `sub` owns the 8-channel chunks sub, sub + G, ..  A workgroup has
 // 256 / G token slots and walks `iters` consecutive groups of that many tokens.
-// ONE (C / 8 == G): a lane owns one chunk for every token, so its convolution weights (packed),
+// ONE (C / 8 <= G): a lane owns one chunk for every token, so its convolution weights (packed),
 // bias, gamma and beta stay in registers and a token's values never leave them.  Otherwise the
 // values of a lane's chunks wait in a per-lane strip of LDS between the passes.
 // Sum = the pre-norm tensor (X1 or X2), Norm = its LayerNorm; the statistics use the float32
@@ -125,13 +125,17 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
     const float w_inv = 1.0f / (float)W, h_inv = 1.0f / (float)H;
     unsigned w[36];
     float bias[8], gm[8], bt[8];
+    // ONE: lanes sub >= C / 8 of a token's group (C / 8 not a power of two) carry no chunk: they
+    // stand on the last chunk, add nothing to the sums and store nothing
+    const bool lane_on = sub < CH;
+    const int c_one = 8 * min(sub, CH - 1);
     if (ONE) {
         if (MODE == kPos) {
-            load8(bpos + 8 * sub, bias);
-            load_w(8 * sub, w);
+            load8(bpos + c_one, bias);
+            load_w(c_one, w);
         }
-        load8(gamma + 8 * sub, gm);
-        load8(beta + 8 * sub, bt);
+        load8(gamma + c_one, gm);
+        load8(beta + c_one, bt);
     }
     for (int it = 0; it < iters; ++it) {
         const long tok_raw = first + (long)it * slots + slot;
@@ -153,21 +157,21 @@ __global__ __launch_bounds__(256) void k_token_ln(const bf16_t *A, const bf16_t 
                 for (int q = 0; q < 36; ++q) asm volatile("" : "+v"(w[q]));
             }
             float v[8];
-            values(tok, valid, y, x, 8 * sub, w, bias, v);
+            values(tok, valid, y, x, c_one, w, bias, v);
             float s = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) s += v[e];
-            const float mean = group_sum(s) * c_inv;
+            const float mean = group_sum(lane_on ? s : 0.f) * c_inv;
             float q = 0.f, d[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) { d[e] = v[e] - mean; q = fmaf(d[e], d[e], q); }
-            const float rstd = __builtin_amdgcn_rsqf(group_sum(q) * c_inv + eps);
+            const float rstd = __builtin_amdgcn_rsqf(group_sum(lane_on ? q : 0.f) * c_inv + eps);
             float o[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = fmaf(d[e] * rstd, gm[e], bt[e]);
-            if (valid) {
-                *(bf16x8 *)(Sum + (size_t)tok * C + 8 * sub) = pack8(v);
-                *(bf16x8 *)(Norm + (size_t)tok * C + 8 * sub) = pack8(o);
+            if (valid && lane_on) {
+                *(bf16x8 *)(Sum + (size_t)tok * C + c_one) = pack8(v);
+                *(bf16x8 *)(Norm + (size_t)tok * C + c_one) = pack8(o);
             }
         } else {
             float s = 0.f;
@@ -613,13 +617,25 @@ int lanes_per_token(int C)
     return G;
 }
 
+// One chunk per lane with some lanes idle: the power of two that holds C / 8 chunks, where the
+// idle share is at most a third (C = 192, 320, 384 ..); 0 where that does not apply.
+int lanes_one_chunk(int C)
+{
+    const int CH = C / 8;
+    if (CH > 64) return 0;
+    int G = 1;
+    while (G < CH) G *= 2;
+    return 3 * (G - CH) <= G ? G : 0;
+}
+
 template <int MODE>
 int launch_token_ln(const Dims &D, const bf16_t *A, const bf16_t *Badd, const bra_block_params &p, const float *gamma,
                     const float *beta, bf16_t *Sum, bf16_t *Norm, float eps, hipStream_t st)
 {
     const long tokens = (long)D.B * D.N;
-    const int G = lanes_per_token(D.C), slots = 256 / G;
-    const bool one = D.C / 8 == G;
+    const int g_one = lanes_one_chunk(D.C);
+    const int G = g_one ? g_one : lanes_per_token(D.C), slots = 256 / G;
+    const bool one = D.C / 8 <= G;
     // enough workgroups to fill the chip several times over, up to 8 token groups each
     static const long target = getenv("BRA_LN_WGS") ? atol(getenv("BRA_LN_WGS")) : 2048;
     long iters = tokens / ((long)slots * target);
