@@ -245,8 +245,8 @@ def time_padded(steps, warmup):
 def time_variants(cfg, steps, warmup):
     """Further timings of the same workload, for context (none of them is `value`): repeats of
     the K-step measurement, spatially smooth inputs (concentrated routing), a single input
-    set (everything stays in the last-level cache) and replay of a HIP graph that holds one
-    pass over the rotating input sets."""
+    set (everything stays in the last-level cache), replay of a HIP graph that holds one
+    pass over the rotating input sets, and independent forwards alternating between two streams."""
     import statistics
 
     import torch
@@ -286,6 +286,32 @@ def time_variants(cfg, steps, warmup):
             times.append(e0.elapsed_time(e1) / (n * per_launch))
         return times
 
+    def measure_two_streams(sets):
+        """Independent forwards alternate between two streams, each with a workspace of its own:
+        one call's drain overlaps the next call's fill (what a serving loop with two requests in
+        flight would see).  Wall-clock over all steps, both streams drained at both ends."""
+        host, Xs, Ys, Wqkv, Wo, Wlce = device_inputs(cfg, sets)
+        shape = bra.make_shape(cfg.B, cfg.H, cfg.W, cfg.C, cfg.heads, cfg.S, cfg.k, Xs[0].dtype)
+        wss = [bra.alloc_workspace(shape, Xs[0].device) for _ in range(2)]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]       # default priority
+
+        def run(n):
+            for i in range(n):
+                with torch.cuda.stream(streams[i % 2]):
+                    bra.bra_forward(Xs[i % sets], Wqkv, Wo, Wlce, cfg.S, cfg.k, cfg.heads, ws=wss[i % 2],
+                                    out=Ys[i % sets])
+
+        torch.cuda.synchronize()
+        run(warmup)
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(5):
+            t0 = time.perf_counter()
+            run(steps)
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - t0) * 1e3 / steps)
+        return times
+
     unit_mb = cfg.B * cfg.H * cfg.W * cfg.C * (2 if cfg.dtype == "bf16" else 4) / 1e6
     sets = max(2, min(24, int(600 / (2 * unit_mb)) + 1))
     rot = measure(sets)
@@ -293,7 +319,8 @@ def time_variants(cfg, steps, warmup):
            "median_ms_per_step": round(statistics.median(rot), 5), "min_ms_per_step": round(min(rot), 5),
            "smooth_inputs_median_ms_per_step": round(statistics.median(measure(sets, smooth=True)), 5),
            "hot_cache_median_ms_per_step": round(statistics.median(measure(1)), 5),
-           "graph_replay_median_ms_per_step": round(statistics.median(measure(sets, graph=True)), 5)}
+           "graph_replay_median_ms_per_step": round(statistics.median(measure(sets, graph=True)), 5),
+           "two_streams_median_ms_per_step": round(statistics.median(measure_two_streams(sets)), 5)}
     return out
 
 
