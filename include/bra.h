@@ -151,6 +151,25 @@ int bra_block_forward(const bra_shape *shape, int32_t hidden, float eps, const v
                       const bra_block_params *params, void *Xout, int32_t *Ir_out_opt,
                       const int32_t *Ir_in_opt, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* Backward pass of the layer with the routing held fixed (the top-k of Eq. 5 has no derivative:
+ * training goes through the token-level attention of Eq. 6-7 only).  Given dY = dLoss/dY
+ * [B,H,W,C] and the routing index Ir [B,S*S,k] that the forward used, with O = Attention +
+ * LCE(V) and, per query token t of region i and head h, P = softmax over the keys of its
+ * routed regions:
+ *     dO = dY Wo^T,  dWo = O^T dY,  dV += LCE^T(dO),  dWlce[c,ky,kx] = sum dO[y,x,c] V[y+ky-2,x+kx-2,c],
+ *     dP_j = dO_h[t] . V_h[j],  dS_j = P_j (dP_j - sum_u P_u dP_u),
+ *     dQ_h[t] = scale sum_j dS_j K_h[j],  dK_h[j] += scale dS_j Q_h[t],  dV_h[j] += P_j dO_h[t],
+ *     dX = [dQ|dK|dV] Wqkv^T,  dWqkv = X^T [dQ|dK|dV].
+ * The forward intermediates are recomputed from X.  dX [B,H,W,C] has shape->dtype; the weight
+ * gradients dWqkv [C,3C], dWo [C,C], dWlce [C,5,5] are float32, summed over the batch and
+ * OVERWRITTEN.  Sums over tokens use float32 atomic adds: results are reproducible to rounding,
+ * not bit for bit.  Scalar float32 kernels (any dtype; heads up to 64 channels wide);
+ * shape->path is ignored.  Errors as bra_forward. */
+int bra_backward_workspace_bytes(const bra_shape *shape, size_t *out_bytes);
+int bra_backward(const bra_shape *shape, const void *X, const void *Wqkv, const void *Wo,
+                 const void *Wlce, const int32_t *Ir, const void *dY, void *dX, float *dWqkv,
+                 float *dWo, float *dWlce, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Optional per-launch timing, for benchmarks (Sec. "Limitation": the paper locates
  * BRA's cost in kernel launches and memory transactions, so the benchmark reports
  * time per kernel).  Host-only state, one session at a time, not thread-safe.

@@ -19,7 +19,7 @@ PATH_AUTO, PATH_GENERIC, PATH_MFMA = 0, 1, 2
 _PATHS = {"auto": PATH_AUTO, "generic": PATH_GENERIC, "mfma": PATH_MFMA}
 
 EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_padded_workspace_bytes",
-           "bra_forward_padded", "bra_block_workspace_bytes",
+           "bra_forward_padded", "bra_backward_workspace_bytes", "bra_backward", "bra_block_workspace_bytes",
            "bra_block_forward", "bra_strerror", "bra_version",
            "bra_profile_begin", "bra_profile_end", "bra_kernel_name", "bra_util_copy",
            "bra_util_read", "bra_util_mfma")
@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.bra_padded_workspace_bytes.argtypes = [ctypes.POINTER(BraShape), ctypes.POINTER(sz)]
         L.bra_forward_padded.restype = ctypes.c_int
         L.bra_forward_padded.argtypes = [ctypes.POINTER(BraShape), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.bra_backward_workspace_bytes.restype = ctypes.c_int
+        L.bra_backward_workspace_bytes.argtypes = [ctypes.POINTER(BraShape), ctypes.POINTER(sz)]
+        L.bra_backward.restype = ctypes.c_int
+        L.bra_backward.argtypes = [ctypes.POINTER(BraShape)] + [vp] * 11 + [sz, vp]
         L.bra_block_workspace_bytes.restype = ctypes.c_int
         L.bra_block_workspace_bytes.argtypes = [ctypes.POINTER(BraShape), ctypes.c_int32, ctypes.POINTER(sz)]
         L.bra_block_forward.restype = ctypes.c_int
@@ -192,6 +196,29 @@ def bra_forward_padded(X, Wqkv, Wo, Wlce, S, k, heads, *, scale=None, Ir_in=None
     _check(lib().bra_forward_padded(ctypes.byref(shape), _ptr(X), _ptr(Wqkv), _ptr(Wo), _ptr(Wlce), _ptr(Y),
                                     _ptr(Ir), _ptr(Ir_in), _ptr(ws), ws.numel(), _stream(X.device)))
     return (Y, Ir) if want_Ir else Y
+
+
+def bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, S, heads, *, scale=None, ws=None):
+    """Gradients of the layer for fixed routing Ir [B, S*S, k] (see include/bra.h): returns
+    (dX in X's dtype, dWqkv, dWo, dWlce in float32)."""
+    B, H, W, C = _check_inputs(X, Wqkv, Wo, Wlce)
+    k = int(Ir.shape[-1])
+    if not (Ir.is_cuda and Ir.is_contiguous() and Ir.dtype == torch.int32 and tuple(Ir.shape) == (B, S * S, k)):
+        raise ValueError("Ir must be a contiguous int32 [B, S*S, k] device tensor")
+    if not (dY.is_cuda and dY.is_contiguous() and dY.dtype == X.dtype and dY.shape == X.shape):
+        raise ValueError("dY must match X")
+    shape = make_shape(B, H, W, C, heads, S, k, X.dtype, scale, "auto")
+    if ws is None:
+        need = ctypes.c_size_t(0)
+        _check(lib().bra_backward_workspace_bytes(ctypes.byref(shape), ctypes.byref(need)))
+        ws = torch.empty(max(need.value, 256), dtype=torch.uint8, device=X.device)
+    dX = torch.empty_like(X)
+    dWqkv = torch.empty((C, 3 * C), dtype=torch.float32, device=X.device)
+    dWo = torch.empty((C, C), dtype=torch.float32, device=X.device)
+    dWlce = torch.empty((C, 5, 5), dtype=torch.float32, device=X.device)
+    _check(lib().bra_backward(ctypes.byref(shape), _ptr(X), _ptr(Wqkv), _ptr(Wo), _ptr(Wlce), _ptr(Ir), _ptr(dY),
+                              _ptr(dX), _ptr(dWqkv), _ptr(dWo), _ptr(dWlce), _ptr(ws), ws.numel(), _stream(X.device)))
+    return dX, dWqkv, dWo, dWlce
 
 
 def block_workspace_bytes(shape: BraShape, hidden: int) -> int:

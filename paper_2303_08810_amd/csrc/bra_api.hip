@@ -139,6 +139,30 @@ int bra_forward_padded(const bra_shape *shape, const void *X, const void *Wqkv, 
                           (hipStream_t)hip_stream);
 }
 
+int bra_backward_workspace_bytes(const bra_shape *shape, size_t *out_bytes)
+{
+    if (!out_bytes) return BRA_ERR_NULL;
+    Dims D;
+    int rc = make_dims(shape, D);
+    if (rc != BRA_OK) return rc;
+    if (!generic_backward_supported(D)) return BRA_ERR_UNSUPPORTED;
+    *out_bytes = generic_backward_workspace_bytes(D);
+    return BRA_OK;
+}
+
+int bra_backward(const bra_shape *shape, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
+                 const int32_t *Ir, const void *dY, void *dX, float *dWqkv, float *dWo, float *dWlce, void *ws,
+                 size_t ws_bytes, void *hip_stream)
+{
+    Dims D;
+    int rc = make_dims(shape, D);
+    if (rc != BRA_OK) return rc;
+    if (!X || !Wqkv || !Wo || !Wlce || !Ir || !dY || !dX || !dWqkv || !dWo || !dWlce) return BRA_ERR_NULL;
+    if (!generic_backward_supported(D)) return BRA_ERR_UNSUPPORTED;
+    if (!ws_ok(ws, ws_bytes, generic_backward_workspace_bytes(D))) return BRA_ERR_WORKSPACE;
+    return generic_backward(D, X, Wqkv, Wo, Wlce, Ir, dY, dX, dWqkv, dWo, dWlce, ws, (hipStream_t)hip_stream);
+}
+
 int bra_block_workspace_bytes(const bra_shape *shape, int32_t hidden, size_t *out_bytes)
 {
     if (!out_bytes) return BRA_ERR_NULL;

@@ -72,7 +72,7 @@ enum KernelId {
     K_GEN_POOL = 0, K_GEN_REGION_QK, K_GEN_TOPK, K_GEN_GEMM_QKV, K_GEN_ATTENTION, K_GEN_LCE,
     K_GEN_GEMM_WO, K_MFMA_PREP, K_MFMA_QKV, K_MFMA_ATTENTION, K_MFMA_POOL_QK, K_MFMA_ROUTE_ROWS,
     K_MFMA_FUSED_K1, K_MFMA_ATTN_SMALL, K_MFMA_LCE_ADD, K_MFMA_WO,
-    K_BLK_POS_LN, K_BLK_ADD_LN, K_BLK_MLP_IN, K_BLK_MLP_OUT, K_BLK_MLP_FUSED, K_COUNT
+    K_BLK_POS_LN, K_BLK_ADD_LN, K_BLK_MLP_IN, K_BLK_MLP_OUT, K_BLK_MLP_FUSED, K_GEN_BACKWARD, K_COUNT
 };
 
 // Brackets the launches issued during its lifetime with two events on `st` when
@@ -119,6 +119,13 @@ int gemm_bf16(const bf16_t *In, const bf16_t *W, long M, int K, int Nout, bf16_t
 size_t padded_workspace_bytes(const Dims &Dp, size_t bra_bytes);
 int padded_forward(const Dims &Dp, int H, int W, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
                    void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, int path, hipStream_t st);
+
+// Backward pass with fixed routing, scalar float32 kernels (bra_generic.hip).
+bool generic_backward_supported(const Dims &D);
+size_t generic_backward_workspace_bytes(const Dims &D);
+int generic_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
+                     const int32_t *Ir, const void *dY, void *dX, float *dWqkv, float *dWo, float *dWlce, void *ws,
+                     hipStream_t st);
 
 // Whole block with the scalar float32 kernels (bra_generic.hip): any dtype, C and hidden.
 size_t generic_block_workspace_bytes(const Dims &D, int hidden, size_t bra_bytes);

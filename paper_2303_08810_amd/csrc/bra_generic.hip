@@ -23,7 +23,8 @@ constexpr int kAttnMaxD = 256;      // head width limit of the generic attention
 // ---------------------------------------------------------------------------
 // out[M, N] = A[M, K] * Bm[K, N]  (row-major with leading dimensions), float32 FMA,
 // k ascending.  64 x 64 tile per workgroup, 4 x 4 outputs per thread.
-template <typename TA, typename TB, typename TO>
+// BT: B is read transposed (B[k][n] = Bm[n * ldb + k]).
+template <typename TA, typename TB, typename TO, bool BT = false>
 __global__ __launch_bounds__(256) void gen_gemm(const TA *__restrict__ A, int lda,
                                                 const TB *__restrict__ Bm, int ldb,
                                                 TO *__restrict__ Out, int ldo, int M, int N, int K,
@@ -50,7 +51,9 @@ __global__ __launch_bounds__(256) void gen_gemm(const TA *__restrict__ A, int ld
             const long gm = m0 + r;
             ra[i] = (gm < M && k0 + kk < K) ? load_f32(A + gm * lda + k0 + kk) : 0.f;
             const int kb = idx / 64, nn = idx % 64;
-            rb[i] = (k0 + kb < K && n0 + nn < N) ? load_f32(Bm + (long)(k0 + kb) * ldb + n0 + nn) : 0.f;
+            rb[i] = (k0 + kb < K && n0 + nn < N)
+                        ? load_f32(BT ? Bm + (long)(n0 + nn) * ldb + k0 + kb : Bm + (long)(k0 + kb) * ldb + n0 + nn)
+                        : 0.f;
         }
     };
     fetch(0);
@@ -585,6 +588,256 @@ int block_t(const Dims &D, int hidden, float eps, const T *X, const bra_block_pa
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
+// ---------------------------------------------------------------------------
+// Backward pass with fixed routing (the top-k of Eq. 5 has no derivative), scalar kernels.
+// With dO = dY Wo^T and, per query token t of region i and head h, P = softmax over the keys G_i:
+//   dP_j = dO_h[t] . V_h[j],  dS_j = P_j (dP_j - sum_u P_u dP_u),
+//   dQ_h[t] = scale sum_j dS_j K_h[j],  dK_h[j] += scale dS_j Q_h[t],  dV_h[j] += P_j dO_h[t].
+
+__global__ void gen_fill_zero(float *__restrict__ p, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+// Out[i][j] += sum_m A[m][i] B[m][j] over this workgroup's slice of the rows m (atomic adds into
+// float32 Out [KA][N], zeroed beforehand): the weight gradients, a contraction over all tokens.
+template <typename TA, typename TB>
+__global__ __launch_bounds__(256) void gen_gemm_tn(const TA *__restrict__ A, int lda, const TB *__restrict__ Bm,
+                                                   int ldb, float *__restrict__ Out, int ldo, long M, int KA, int N,
+                                                   long rows_per_wg)
+{
+    __shared__ float As[16][64 + 4];
+    __shared__ float Bs[16][64];
+    const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+    const int i0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+    const long m_begin = (long)blockIdx.z * rows_per_wg, m_end = min(M, m_begin + rows_per_wg);
+    float acc[4][4];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+    for (long m0 = m_begin; m0 < m_end; m0 += 16) {
+        for (int u = 0; u < 4; ++u) {
+            const int idx = tid + u * 256;
+            const int mm = idx / 64, cc = idx % 64;
+            const long gm = m0 + mm;
+            As[mm][cc] = (gm < m_end && i0 + cc < KA) ? load_f32(A + gm * lda + i0 + cc) : 0.f;
+            Bs[mm][cc] = (gm < m_end && n0 + cc < N) ? load_f32(Bm + gm * ldb + n0 + cc) : 0.f;
+        }
+        __syncthreads();
+        for (int mm = 0; mm < 16; ++mm) {
+            float a[4], b[4];
+            for (int i = 0; i < 4; ++i) a[i] = As[mm][ty * 4 + i];
+            for (int j = 0; j < 4; ++j) b[j] = Bs[mm][tx * 4 + j];
+            for (int i = 0; i < 4; ++i)
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j) {
+            const int gi = i0 + ty * 4 + i, gn = n0 + tx * 4 + j;
+            if (gi < KA && gn < N) atomicAdd(Out + (size_t)gi * ldo + gn, acc[i][j]);
+        }
+}
+
+// One wavefront per (image, region, head), one query token after the other.  Phase A, a lane per
+// key: scores, their maximum, the unnormalised weights e_j and e_j dP_j summed over the
+// wavefront; P_j and dS_j wait in LDS.  Phase B, a lane per channel of the head: dQ of the query
+// (stored), and the query's share of dK, dV of every key (atomic adds: many queries meet in a key).
+constexpr int kBwdMaxD = 64;
+
+__global__ __launch_bounds__(kWave) void gen_attention_bwd(const float *__restrict__ QKV,
+                                                           const int32_t *__restrict__ Ir,
+                                                           const float *__restrict__ dO, float *__restrict__ dQKV,
+                                                           Dims D, float scale)
+{
+    extern __shared__ float lds[];                     // P [kn], dS [kn], q [d], do [d]
+    float *Pw = lds, *dSw = lds + D.kn, *qv = dSw + D.kn, *dov = qv + D.d;
+    const int hd = blockIdx.x % D.heads;
+    const int reg = (blockIdx.x / D.heads) % D.R;
+    const int b = blockIdx.x / (D.heads * D.R);
+    const int lane = threadIdx.x, C3 = 3 * D.C, d = D.d;
+    const float *img = QKV + (size_t)b * D.N * C3;
+    float *dimg = dQKV + (size_t)b * D.N * C3;
+    const int32_t *irp = Ir + ((size_t)b * D.R + reg) * D.k;
+    const int y0 = (reg / D.S) * D.rh, x0 = (reg % D.S) * D.rw;
+    auto key_token = [&](int key) {
+        const int j = region_index(irp[key / D.n], D.R), slot = key % D.n;
+        return ((j / D.S) * D.rh + slot / D.rw) * D.W + (j % D.S) * D.rw + slot % D.rw;
+    };
+    for (int s = 0; s < D.n; ++s) {
+        const int qtok = (y0 + s / D.rw) * D.W + x0 + s % D.rw;
+        __syncthreads();                               // the previous query's phase B has read LDS
+        if (lane < d) {
+            qv[lane] = img[(size_t)qtok * C3 + hd * d + lane];
+            dov[lane] = dO[((size_t)b * D.N + qtok) * D.C + hd * d + lane];
+        }
+        __syncthreads();
+        float mx = -INFINITY;
+        for (int key = lane; key < D.kn; key += kWave) {
+            const float *row = img + (size_t)key_token(key) * C3 + hd * d;
+            float a = 0.f, g = 0.f;
+            for (int c = 0; c < d; ++c) {
+                a = fmaf(qv[c], row[D.C + c], a);
+                g = fmaf(dov[c], row[2 * D.C + c], g);
+            }
+            Pw[key] = a * scale;
+            dSw[key] = g;
+            mx = fmaxf(mx, a * scale);
+        }
+        for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+        float l = 0.f, dn = 0.f;
+        for (int key = lane; key < D.kn; key += kWave) {
+            const float e = expf(Pw[key] - mx);
+            Pw[key] = e;
+            l += e;
+            dn = fmaf(e, dSw[key], dn);
+        }
+        for (int off = 32; off >= 1; off >>= 1) {
+            l += __shfl_xor(l, off, kWave);
+            dn += __shfl_xor(dn, off, kWave);
+        }
+        const float inv = 1.0f / l, dsum = dn * inv;
+        for (int key = lane; key < D.kn; key += kWave) {
+            const float pj = Pw[key] * inv;
+            Pw[key] = pj;
+            dSw[key] = pj * (dSw[key] - dsum);
+        }
+        __syncthreads();
+        if (lane < d) {
+            const float qc = qv[lane], doc = dov[lane];
+            float dq = 0.f;
+            for (int key = 0; key < D.kn; ++key) {
+                const size_t at = (size_t)key_token(key) * C3 + hd * d + lane;
+                const float ds = dSw[key] * scale;
+                dq = fmaf(ds, img[at + D.C], dq);
+                atomicAdd(dimg + at + D.C, ds * qc);
+                atomicAdd(dimg + at + 2 * D.C, Pw[key] * doc);
+            }
+            dimg[(size_t)qtok * C3 + hd * d + lane] = dq;         // every query has one owner
+        }
+    }
+}
+
+// dV += LCE^T(dO): dV[y, x, c] += sum w[c, ky, kx] dO[y - ky + 2, x - kx + 2, c]   (after the attention part)
+template <typename T>
+__global__ void gen_lce_bwd_dv(const float *__restrict__ dO, const T *__restrict__ Wlce, float *__restrict__ dQKV,
+                               Dims D)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t total = (size_t)D.B * D.N * D.C;
+    if (idx >= total) return;
+    const int c = (int)(idx % D.C);
+    const size_t tok = idx / D.C;
+    const int x = (int)(tok % D.W), y = (int)((tok / D.W) % D.H);
+    const size_t b = tok / D.N;
+    float acc = 0.f;
+    for (int ky = 0; ky < 5; ++ky) {
+        const int yy = y - ky + 2;
+        if (yy < 0 || yy >= D.H) continue;
+        for (int kx = 0; kx < 5; ++kx) {
+            const int xx = x - kx + 2;
+            if (xx < 0 || xx >= D.W) continue;
+            acc = fmaf(load_f32(Wlce + (size_t)c * 25 + ky * 5 + kx), dO[((b * D.H + yy) * D.W + xx) * D.C + c], acc);
+        }
+    }
+    dQKV[tok * 3 * D.C + 2 * D.C + c] += acc;
+}
+
+// dWlce[c, ky, kx] += sum over this workgroup's tokens of dO[y, x, c] V[y + ky - 2, x + kx - 2, c]:
+// blockIdx.y = tap, a thread per channel, atomic adds into the zeroed gradient.
+__global__ __launch_bounds__(256) void gen_lce_bwd_dw(const float *__restrict__ dO, const float *__restrict__ QKV,
+                                                      float *__restrict__ dW, Dims D, long tokens_per_wg)
+{
+    const int tap = blockIdx.y, ky = tap / 5, kx = tap % 5;
+    const long t_begin = (long)blockIdx.x * tokens_per_wg, t_end = min((long)D.B * D.N, t_begin + tokens_per_wg);
+    for (int c = threadIdx.x; c < D.C; c += 256) {
+        float acc = 0.f;
+        for (long tok = t_begin; tok < t_end; ++tok) {
+            const int x = (int)(tok % D.W), y = (int)((tok / D.W) % D.H);
+            const int yy = y + ky - 2, xx = x + kx - 2;
+            if (yy < 0 || yy >= D.H || xx < 0 || xx >= D.W) continue;
+            const long vt = tok + (long)(ky - 2) * D.W + (kx - 2);
+            acc = fmaf(dO[(size_t)tok * D.C + c], QKV[(size_t)vt * 3 * D.C + 2 * D.C + c], acc);
+        }
+        atomicAdd(dW + (size_t)c * 25 + tap, acc);
+    }
+}
+
+struct BwdWs {
+    float *qkv, *o, *dO, *dqkv;
+    size_t bytes;
+};
+
+BwdWs carve_bwd(const Dims &D, void *ws)
+{
+    char *base = (char *)ws;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        void *ptr = base ? base + off : nullptr;
+        off += align256(bytes);
+        return ptr;
+    };
+    const size_t tok = (size_t)D.B * D.N;
+    BwdWs w;
+    w.qkv = (float *)take(tok * 3 * D.C * sizeof(float));
+    w.o = (float *)take(tok * D.C * sizeof(float));
+    w.dO = (float *)take(tok * D.C * sizeof(float));
+    w.dqkv = (float *)take(tok * 3 * D.C * sizeof(float));
+    w.bytes = off;
+    return w;
+}
+
+void fill_zero(float *p, size_t n, hipStream_t st)
+{
+    hipLaunchKernelGGL(gen_fill_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n);
+}
+
+template <typename T>
+int backward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *Wlce, const int32_t *Ir, const T *dY,
+               T *dX, float *dWqkv, float *dWo, float *dWlce, void *ws, hipStream_t st)
+{
+    const BwdWs w = carve_bwd(D, ws);
+    const long M = (long)D.B * D.N;
+    const int C = D.C, C3 = 3 * D.C;
+    const size_t total = (size_t)M * C;
+    ProfScope ps(st, K_GEN_BACKWARD);
+    // forward intermediates again: Q | K | V and O = attention + LCE(V)
+    hipLaunchKernelGGL((gen_gemm<T, T, float>), dim3((unsigned)((M + 63) / 64), (unsigned)((C3 + 63) / 64)), dim3(256), 0,
+                       st, X, C, Wqkv, C3, w.qkv, C3, (int)M, C3, C);
+    if (D.d <= kAttnLdsD)
+        hipLaunchKernelGGL(gen_attention_lds, dim3(D.B * D.R * D.heads), dim3(256), 0, st, w.qkv, Ir, w.o, D, D.scale);
+    else
+        hipLaunchKernelGGL(gen_attention, dim3(D.B * D.R * D.heads), dim3(256), D.k * sizeof(int), st, w.qkv, Ir, w.o, D,
+                           D.scale);
+    hipLaunchKernelGGL(gen_lce_add<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w.qkv, Wlce, w.o, D);
+    // dO = dY Wo^T, dWo = O^T dY
+    hipLaunchKernelGGL((gen_gemm<T, T, float, true>), dim3((unsigned)((M + 63) / 64), (unsigned)((C + 63) / 64)), dim3(256),
+                       0, st, dY, C, Wo, C, w.dO, C, (int)M, C, C);
+    fill_zero(dWo, (size_t)C * C, st);
+    fill_zero(dWqkv, (size_t)C * C3, st);
+    fill_zero(dWlce, (size_t)C * 25, st);
+    fill_zero(w.dqkv, (size_t)M * C3, st);
+    long splits = (M + 2047) / 2048;
+    splits = splits > 1024 ? 1024 : splits;
+    const long rows = ((M + splits - 1) / splits + 15) / 16 * 16;
+    hipLaunchKernelGGL((gen_gemm_tn<float, T>), dim3((unsigned)((C + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)splits),
+                       dim3(256), 0, st, w.o, C, dY, C, dWo, C, M, C, C, rows);
+    // attention: dQ, dK, dV; then the LCE parts
+    hipLaunchKernelGGL(gen_attention_bwd, dim3(D.B * D.R * D.heads), dim3(kWave),
+                       (size_t)(2 * D.kn + 2 * D.d) * sizeof(float), st, w.qkv, Ir, w.dO, w.dqkv, D, D.scale);
+    hipLaunchKernelGGL(gen_lce_bwd_dv<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w.dO, Wlce, w.dqkv, D);
+    const long tpw = 512;
+    hipLaunchKernelGGL(gen_lce_bwd_dw, dim3((unsigned)((M + tpw - 1) / tpw), 25), dim3(256), 0, st, w.dO, w.qkv, dWlce, D,
+                       tpw);
+    // dX = [dQ | dK | dV] Wqkv^T, dWqkv = X^T [dQ | dK | dV]
+    hipLaunchKernelGGL((gen_gemm<float, T, T, true>), dim3((unsigned)((M + 63) / 64), (unsigned)((C + 63) / 64)), dim3(256),
+                       0, st, w.dqkv, C3, Wqkv, C3, dX, C, (int)M, C, C3);
+    hipLaunchKernelGGL((gen_gemm_tn<T, float>), dim3((unsigned)((C + 63) / 64), (unsigned)((C3 + 63) / 64), (unsigned)splits),
+                       dim3(256), 0, st, X, C, w.dqkv, C3, dWqkv, C3, M, C, C3, rows);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
 }  // namespace
 
 size_t generic_block_workspace_bytes(const Dims &D, int hidden, size_t bra_bytes)
@@ -601,6 +854,25 @@ int generic_block_forward(const Dims &D, int hidden, float eps, const void *X, c
                                bra_bytes, path, st);
     return block_t<float>(D, hidden, eps, (const float *)X, p, (float *)Xout, Ir_out_opt, Ir_in_opt, ws, bra_bytes,
                           path, st);
+}
+
+bool generic_backward_supported(const Dims &D)
+{
+    return generic_supported(D) && D.d <= kBwdMaxD && (size_t)(2 * D.kn + 2 * D.d) * sizeof(float) <= 64 * 1024 &&
+           ((long)D.B * D.N + 511) / 512 <= 65535;
+}
+
+size_t generic_backward_workspace_bytes(const Dims &D) { return carve_bwd(D, nullptr).bytes; }
+
+int generic_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
+                     const int32_t *Ir, const void *dY, void *dX, float *dWqkv, float *dWo, float *dWlce, void *ws,
+                     hipStream_t st)
+{
+    if (D.dtype == BRA_BF16)
+        return backward_t<bf16_t>(D, (const bf16_t *)X, (const bf16_t *)Wqkv, (const bf16_t *)Wo, (const bf16_t *)Wlce,
+                                  Ir, (const bf16_t *)dY, (bf16_t *)dX, dWqkv, dWo, dWlce, ws, st);
+    return backward_t<float>(D, (const float *)X, (const float *)Wqkv, (const float *)Wo, (const float *)Wlce, Ir,
+                             (const float *)dY, (float *)dX, dWqkv, dWo, dWlce, ws, st);
 }
 
 bool generic_supported(const Dims &D)

@@ -16,7 +16,7 @@ const char *const kNames[K_COUNT] = {
     "gen_pool", "gen_region_qk", "gen_affinity_topk", "gen_gemm_qkv", "gen_attention", "gen_lce_add",
     "gen_gemm_wo", "mfma_prep", "mfma_qkv", "mfma_attention", "mfma_pool_qk", "mfma_route_rows",
     "mfma_fused_k1", "mfma_attn_small", "mfma_lce_add", "mfma_wo",
-    "block_pos_ln", "block_add_ln", "block_mlp_in", "block_mlp_out", "block_mlp_fused",
+    "block_pos_ln", "block_add_ln", "block_mlp_in", "block_mlp_out", "block_mlp_fused", "gen_backward",
 };
 }  // namespace
 

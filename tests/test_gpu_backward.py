@@ -1,0 +1,62 @@
+"""GPU parity of bra_backward (through the C ABI) against the float64 backward oracle, with the
+routing index given to both sides.  Bars: float32 tensors, every gradient within 1e-4 of
+max|gradient| (the float32 bar relative to the gradient's scale: sums over up to B*H*W tokens);
+bf16 tensors (float32 arithmetic on bf16 inputs, dX rounded to bf16) within 2e-2 of max|gradient|
+for dX and 1e-3 for the float32 weight gradients."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2303_08810_amd as bra
+from oracle import backward as obw
+from parity_util import to_device, to_numpy
+from synthetic_inputs import make_inputs, round_to_bf16
+
+pytestmark = pytest.mark.gpu
+
+# (dtype, B, H, W, C, heads, S, k)
+SHAPES = [
+    ("f32", 1, 28, 28, 64, 2, 7, 4),
+    ("f32", 2, 12, 20, 48, 3, 4, 3),
+    ("f32", 2, 7, 7, 64, 1, 7, 49),
+    ("f32", 3, 6, 9, 40, 5, 3, 2),
+    ("f32", 1, 16, 16, 32, 1, 2, 4),
+    ("bf16", 2, 14, 14, 64, 2, 7, 4),
+    ("bf16", 1, 16, 24, 96, 3, 4, 2),
+]
+
+
+@pytest.mark.parametrize("dtype,B,H,W,C,heads,S,k", SHAPES)
+def test_backward(dtype, B, H, W, C, heads, S, k):
+    print(f"backward case dtype={dtype} shape={(B, H, W, C)} heads={heads} S={S} k={k}", flush=True)
+    Xn, Wqkvn, Won, Wlcen = make_inputs(B, H, W, C, seed=6000 + H * W + C + k, dtype=dtype)
+    r = np.random.Generator(np.random.PCG64(6001 + C))
+    dYn = r.standard_normal(Xn.shape).astype(np.float32)
+    if dtype == "bf16":
+        dYn = round_to_bf16(dYn)
+    Irn = np.stack([np.stack([r.permutation(S * S)[:k] for _ in range(S * S)]) for _ in range(B)]).astype(np.int32)
+    X, Wqkv, Wo, Wlce, dY = (to_device(a, dtype) for a in (Xn, Wqkvn, Won, Wlcen, dYn))
+    got = bra.bra_backward(X, Wqkv, Wo, Wlce, torch.from_numpy(Irn).cuda(), dY, S, heads)
+    torch.cuda.synchronize()
+    ref = obw.bra_backward(Xn, Wqkvn, Won, Wlcen, dYn, Irn, S=S, heads=heads)
+    names = ("dX", "dWqkv", "dWo", "dWlce")
+    for name, g in zip(names, got):
+        gn = to_numpy(g).astype(np.float64).reshape(ref[name].shape)
+        rel = float(np.abs(gn - ref[name]).max() / np.abs(ref[name]).max())
+        tol = 1e-4 if dtype == "f32" else (2e-2 if name == "dX" else 1e-3)
+        print(f"  {name}: max error {rel:.3e} of max|gradient|", flush=True)
+        assert rel <= tol, f"{name}: {rel:.3e} > {tol}"
+
+
+def test_backward_after_forward_uses_its_routing():
+    B, H, W, C, heads, S, k = 2, 14, 14, 64, 2, 7, 4
+    Xn, Wqkvn, Won, Wlcen = make_inputs(B, H, W, C, seed=6100)
+    X, Wqkv, Wo, Wlce = (to_device(a, "f32") for a in (Xn, Wqkvn, Won, Wlcen))
+    Y, Ir = bra.bra_forward(X, Wqkv, Wo, Wlce, S, k, heads, want_Ir=True)
+    dY = torch.ones_like(Y)
+    dX, dWqkv, dWo, dWlce = bra.bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, S, heads)
+    torch.cuda.synchronize()
+    ref = obw.bra_backward(Xn, Wqkvn, Won, Wlcen, np.ones_like(Xn), Ir.cpu().numpy(), S=S, heads=heads)
+    assert np.abs(to_numpy(Y) - ref["Y"]).max() < 1e-4
+    assert np.abs(to_numpy(dX) - ref["dX"]).max() <= 1e-4 * np.abs(ref["dX"]).max()
+    assert np.abs(to_numpy(dWo) - ref["dWo"]).max() <= 1e-4 * np.abs(ref["dWo"]).max()
