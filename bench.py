@@ -242,6 +242,38 @@ def time_padded(steps, warmup):
             "note": "includes the binding's workspace and output allocation per call"}
 
 
+def time_backward(cfg, steps, warmup):
+    """bra_backward (fixed routing, scalar float32 kernels) at a named workload's shape: context,
+    never `value`."""
+    import numpy as np
+    import torch
+
+    import paper_2303_08810_amd as bra
+
+    host, Xs, Ys, Wqkv, Wo, Wlce = device_inputs(cfg, 2)
+    X = Xs[0]
+    Y, Ir = bra.bra_forward(X, Wqkv, Wo, Wlce, cfg.S, cfg.k, cfg.heads, want_Ir=True)
+    dY = torch.ones_like(Y)
+    shape = bra.make_shape(cfg.B, cfg.H, cfg.W, cfg.C, cfg.heads, cfg.S, cfg.k, X.dtype)
+    import ctypes
+    need = ctypes.c_size_t(0)
+    bra._check(bra.lib().bra_backward_workspace_bytes(ctypes.byref(shape), ctypes.byref(need)))
+    ws = torch.empty(need.value, dtype=torch.uint8, device="cuda")
+    for _ in range(warmup):
+        bra.bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, cfg.S, cfg.heads, ws=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        bra.bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, cfg.S, cfg.heads, ws=ws)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    f = flops_per_image(cfg)
+    # the backward pass recomputes the forward (1x) and does about twice its arithmetic again
+    return {"images_per_s": round(cfg.B / (ms / 1e3), 1), "ms_per_step": round(ms, 4),
+            "achieved_tflops": round(3 * cfg.B * f["total"] / (ms / 1e3) / 1e12, 3),
+            "note": "scalar float32 kernels with atomic scatter-add; includes the binding's output allocations"}
+
+
 def time_variants(cfg, steps, warmup):
     """Further timings of the same workload, for context (none of them is `value`): repeats of
     the K-step measurement, spatially smooth inputs (concentrated routing), a single input
@@ -481,6 +513,7 @@ def main():
             blocks[c.name] = time_block(c, n, n)
         line["block_forward"] = blocks
         line["padded_forward"] = time_padded(max(20, args.steps // 4), max(20, args.steps // 4))
+        line["backward"] = {CONFIGS[i].name: time_backward(CONFIGS[i], 5, 2) for i in (1, 2, 3)}
     if args.calibrate:
         src = torch.empty(CALIBRATION_BYTES, dtype=torch.uint8, device="cuda").random_()
         dst = torch.empty_like(src)
