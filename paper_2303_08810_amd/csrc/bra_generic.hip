@@ -636,87 +636,147 @@ __global__ __launch_bounds__(256) void gen_gemm_tn(const TA *__restrict__ A, int
     for (int i = 0; i < 4; ++i)
         for (int j = 0; j < 4; ++j) {
             const int gi = i0 + ty * 4 + i, gn = n0 + tx * 4 + j;
-            if (gi < KA && gn < N) atomicAdd(Out + (size_t)gi * ldo + gn, acc[i][j]);
+            if (gi < KA && gn < N) unsafeAtomicAdd(Out + (size_t)gi * ldo + gn, acc[i][j]);
         }
 }
 
-// One wavefront per (image, region, head), one query token after the other.  Phase A, a lane per
-// key: scores, their maximum, the unnormalised weights e_j and e_j dP_j summed over the
-// wavefront; P_j and dS_j wait in LDS.  Phase B, a lane per channel of the head: dQ of the query
-// (stored), and the query's share of dK, dV of every key (atomic adds: many queries meet in a key).
+// One workgroup per (image, region, head); 16 queries per pass (wavefront w owns 4 of them), the
+// routed keys in blocks of 64 staged in LDS.  D_q = sum_j P_j dP_j = dO_h[q] . Oatt_h[q] comes from
+// the attention output (before LCE is added to it).  Sweep 1 over the key blocks: the softmax
+// maximum and denominator of each query.  Sweep 2: per block, a lane per key forms P_j and dS_j;
+// then a lane per channel adds the query's share to dQ (registers) and to the block's dK, dV in LDS
+// (LDS atomics: the wavefronts' queries meet there); the block's dK, dV go to memory with one
+// atomic add per element (other regions route to the same keys).
 constexpr int kBwdMaxD = 64;
 
-__global__ __launch_bounds__(kWave) void gen_attention_bwd(const float *__restrict__ QKV,
-                                                           const int32_t *__restrict__ Ir,
-                                                           const float *__restrict__ dO, float *__restrict__ dQKV,
-                                                           Dims D, float scale)
+__global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict__ QKV,
+                                                         const int32_t *__restrict__ Ir,
+                                                         const float *__restrict__ Oatt,
+                                                         const float *__restrict__ dO, float *__restrict__ dQKV,
+                                                         Dims D, float scale)
 {
-    extern __shared__ float lds[];                     // P [kn], dS [kn], q [d], do [d]
-    float *Pw = lds, *dSw = lds + D.kn, *qv = dSw + D.kn, *dov = qv + D.d;
+    extern __shared__ float lds[];
+    const int d = D.d, dp = d + 1;
+    float *Ks = lds, *Vs = Ks + 64 * dp, *dKs = Vs + 64 * dp, *dVs = dKs + 64 * d;
+    float *qs = dVs + 64 * d, *dos = qs + 16 * d, *Psc = dos + 16 * d, *dSsc = Psc + 16 * 64;
     const int hd = blockIdx.x % D.heads;
     const int reg = (blockIdx.x / D.heads) % D.R;
     const int b = blockIdx.x / (D.heads * D.R);
-    const int lane = threadIdx.x, C3 = 3 * D.C, d = D.d;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int C3 = 3 * D.C;
     const float *img = QKV + (size_t)b * D.N * C3;
     float *dimg = dQKV + (size_t)b * D.N * C3;
     const int32_t *irp = Ir + ((size_t)b * D.R + reg) * D.k;
     const int y0 = (reg / D.S) * D.rh, x0 = (reg % D.S) * D.rw;
+    auto query_token = [&](int s) { return (y0 + s / D.rw) * D.W + x0 + s % D.rw; };
     auto key_token = [&](int key) {
         const int j = region_index(irp[key / D.n], D.R), slot = key % D.n;
         return ((j / D.S) * D.rh + slot / D.rw) * D.W + (j % D.S) * D.rw + slot % D.rw;
     };
-    for (int s = 0; s < D.n; ++s) {
-        const int qtok = (y0 + s / D.rw) * D.W + x0 + s % D.rw;
-        __syncthreads();                               // the previous query's phase B has read LDS
-        if (lane < d) {
-            qv[lane] = img[(size_t)qtok * C3 + hd * d + lane];
-            dov[lane] = dO[((size_t)b * D.N + qtok) * D.C + hd * d + lane];
+    auto stage_keys = [&](int k0, bool with_v) {
+        for (int e = tid; e < 64 * d; e += 256) {
+            const int u = e / d, c = e % d;
+            const float *row = img + (size_t)key_token(min(k0 + u, D.kn - 1)) * C3 + hd * d + c;
+            Ks[u * dp + c] = row[D.C];
+            if (with_v) {
+                Vs[u * dp + c] = row[2 * D.C];
+                dKs[u * d + c] = 0.f;
+                dVs[u * d + c] = 0.f;
+            }
+        }
+    };
+
+    for (int s0 = 0; s0 < D.n; s0 += 16) {
+        __syncthreads();                               // the previous pass is done with the queries
+        for (int e = tid; e < 16 * d; e += 256) {
+            const int s = min(s0 + e / d, D.n - 1);      // past the end: the last query again; it adds nothing
+            const int qtok = query_token(s);
+            qs[e] = img[(size_t)qtok * C3 + hd * d + e % d];
+            dos[e] = dO[((size_t)b * D.N + qtok) * D.C + hd * d + e % d];
         }
         __syncthreads();
-        float mx = -INFINITY;
-        for (int key = lane; key < D.kn; key += kWave) {
-            const float *row = img + (size_t)key_token(key) * C3 + hd * d;
-            float a = 0.f, g = 0.f;
-            for (int c = 0; c < d; ++c) {
-                a = fmaf(qv[c], row[D.C + c], a);
-                g = fmaf(dov[c], row[2 * D.C + c], g);
+        float m[4], l[4], Dq[4], dq[4];
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) {
+            const int s = min(s0 + 4 * wave + qq, D.n - 1);
+            float t = 0.f;
+            if (lane < d)
+                t = dos[(4 * wave + qq) * d + lane] * Oatt[((size_t)b * D.N + query_token(s)) * D.C + hd * d + lane];
+            for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off, kWave);
+            Dq[qq] = t;
+            m[qq] = -INFINITY;
+            l[qq] = 0.f;
+            dq[qq] = 0.f;
+        }
+        for (int k0 = 0; k0 < D.kn; k0 += 64) {        // sweep 1: maximum and denominator
+            const int cn = min(64, D.kn - k0);
+            __syncthreads();
+            stage_keys(k0, false);
+            __syncthreads();
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                const float *q = qs + (4 * wave + qq) * d;
+                float a = 0.f;
+                for (int c = 0; c < d; ++c) a = fmaf(q[c], Ks[lane * dp + c], a);
+                a = lane < cn ? a * scale : -INFINITY;
+                float mx = a;
+                for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+                const float m_new = fmaxf(m[qq], mx);
+                float e = lane < cn ? expf(a - m_new) : 0.f;
+                for (int off = 32; off >= 1; off >>= 1) e += __shfl_xor(e, off, kWave);
+                l[qq] = l[qq] * ((m[qq] == -INFINITY) ? 0.f : expf(m[qq] - m_new)) + e;
+                m[qq] = m_new;
             }
-            Pw[key] = a * scale;
-            dSw[key] = g;
-            mx = fmaxf(mx, a * scale);
         }
-        for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-        float l = 0.f, dn = 0.f;
-        for (int key = lane; key < D.kn; key += kWave) {
-            const float e = expf(Pw[key] - mx);
-            Pw[key] = e;
-            l += e;
-            dn = fmaf(e, dSw[key], dn);
-        }
-        for (int off = 32; off >= 1; off >>= 1) {
-            l += __shfl_xor(l, off, kWave);
-            dn += __shfl_xor(dn, off, kWave);
-        }
-        const float inv = 1.0f / l, dsum = dn * inv;
-        for (int key = lane; key < D.kn; key += kWave) {
-            const float pj = Pw[key] * inv;
-            Pw[key] = pj;
-            dSw[key] = pj * (dSw[key] - dsum);
-        }
-        __syncthreads();
-        if (lane < d) {
-            const float qc = qv[lane], doc = dov[lane];
-            float dq = 0.f;
-            for (int key = 0; key < D.kn; ++key) {
-                const size_t at = (size_t)key_token(key) * C3 + hd * d + lane;
-                const float ds = dSw[key] * scale;
-                dq = fmaf(ds, img[at + D.C], dq);
-                atomicAdd(dimg + at + D.C, ds * qc);
-                atomicAdd(dimg + at + 2 * D.C, Pw[key] * doc);
+        for (int k0 = 0; k0 < D.kn; k0 += 64) {        // sweep 2: gradients
+            const int cn = min(64, D.kn - k0);
+            __syncthreads();
+            stage_keys(k0, true);
+            __syncthreads();
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                if (s0 + 4 * wave + qq >= D.n) break;            // uniform in the wavefront
+                const float *q = qs + (4 * wave + qq) * d, *dov = dos + (4 * wave + qq) * d;
+                float *Pw = Psc + (4 * wave + qq) * 64, *dSw = dSsc + (4 * wave + qq) * 64;
+                float a = 0.f, gsum = 0.f;
+                for (int c = 0; c < d; ++c) {
+                    a = fmaf(q[c], Ks[lane * dp + c], a);
+                    gsum = fmaf(dov[c], Vs[lane * dp + c], gsum);
+                }
+                const float pj = lane < cn ? expf(a * scale - m[qq]) / l[qq] : 0.f;
+                Pw[lane] = pj;                                   // read back by this wavefront only
+                dSw[lane] = pj * (gsum - Dq[qq]) * scale;
+                if (lane < d) {
+                    const float qc = q[lane], doc = dov[lane];
+                    float acc = dq[qq];
+                    for (int u = 0; u < cn; ++u) {
+                        const float ds = dSw[u];
+                        acc = fmaf(ds, Ks[u * dp + lane], acc);
+                        unsafeAtomicAdd(dKs + u * d + lane, ds * qc);
+                        unsafeAtomicAdd(dVs + u * d + lane, Pw[u] * doc);
+                    }
+                    dq[qq] = acc;
+                }
             }
-            dimg[(size_t)qtok * C3 + hd * d + lane] = dq;         // every query has one owner
+            __syncthreads();
+            for (int e = tid; e < cn * d; e += 256) {            // the block's dK, dV: other regions add to the same keys
+                const int u = e / d, c = e % d;
+                const size_t at = (size_t)key_token(k0 + u) * C3 + hd * d + c;
+                unsafeAtomicAdd(dimg + at + D.C, dKs[u * d + c]);
+                unsafeAtomicAdd(dimg + at + 2 * D.C, dVs[u * d + c]);
+            }
+        }
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) {
+            const int s = s0 + 4 * wave + qq;
+            if (s < D.n && lane < d) dimg[(size_t)query_token(s) * C3 + hd * d + lane] = dq[qq];   // every query has one owner
         }
     }
+}
+
+inline size_t attention_bwd_smem(int d)
+{
+    return (size_t)(2 * 64 * (d + 1) + 2 * 64 * d + 2 * 16 * d + 2 * 16 * 64) * sizeof(float);
 }
 
 // dV += LCE^T(dO): dV[y, x, c] += sum w[c, ky, kx] dO[y - ky + 2, x - kx + 2, c]   (after the attention part)
@@ -760,7 +820,7 @@ __global__ __launch_bounds__(256) void gen_lce_bwd_dw(const float *__restrict__ 
             const long vt = tok + (long)(ky - 2) * D.W + (kx - 2);
             acc = fmaf(dO[(size_t)tok * D.C + c], QKV[(size_t)vt * 3 * D.C + 2 * D.C + c], acc);
         }
-        atomicAdd(dW + (size_t)c * 25 + tap, acc);
+        unsafeAtomicAdd(dW + (size_t)c * 25 + tap, acc);
     }
 }
 
@@ -801,8 +861,17 @@ int backward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *W
     const long M = (long)D.B * D.N;
     const int C = D.C, C3 = 3 * D.C;
     const size_t total = (size_t)M * C;
+    if (attention_bwd_smem(D.d) > 64 * 1024) {
+        static bool opted = false;
+        if (!opted) {
+            if (hipFuncSetAttribute((const void *)gen_attention_bwd, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)attention_bwd_smem(kBwdMaxD)) != hipSuccess)
+                return BRA_ERR_LAUNCH;
+            opted = true;
+        }
+    }
     ProfScope ps(st, K_GEN_BACKWARD);
-    // forward intermediates again: Q | K | V and O = attention + LCE(V)
+    // forward intermediates again: Q | K | V and the attention output (LCE is added further down)
     hipLaunchKernelGGL((gen_gemm<T, T, float>), dim3((unsigned)((M + 63) / 64), (unsigned)((C3 + 63) / 64)), dim3(256), 0,
                        st, X, C, Wqkv, C3, w.qkv, C3, (int)M, C3, C);
     if (D.d <= kAttnLdsD)
@@ -810,22 +879,23 @@ int backward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *W
     else
         hipLaunchKernelGGL(gen_attention, dim3(D.B * D.R * D.heads), dim3(256), D.k * sizeof(int), st, w.qkv, Ir, w.o, D,
                            D.scale);
-    hipLaunchKernelGGL(gen_lce_add<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w.qkv, Wlce, w.o, D);
-    // dO = dY Wo^T, dWo = O^T dY
+    // dO = dY Wo^T
     hipLaunchKernelGGL((gen_gemm<T, T, float, true>), dim3((unsigned)((M + 63) / 64), (unsigned)((C + 63) / 64)), dim3(256),
                        0, st, dY, C, Wo, C, w.dO, C, (int)M, C, C);
     fill_zero(dWo, (size_t)C * C, st);
     fill_zero(dWqkv, (size_t)C * C3, st);
     fill_zero(dWlce, (size_t)C * 25, st);
     fill_zero(w.dqkv, (size_t)M * C3, st);
+    // attention: dQ, dK, dV from the attention output alone; then O = attention + LCE(V) for dWo
+    hipLaunchKernelGGL(gen_attention_bwd, dim3(D.B * D.R * D.heads), dim3(256), attention_bwd_smem(D.d), st, w.qkv, Ir,
+                       w.o, w.dO, w.dqkv, D, D.scale);
+    hipLaunchKernelGGL(gen_lce_add<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w.qkv, Wlce, w.o, D);
     long splits = (M + 2047) / 2048;
     splits = splits > 1024 ? 1024 : splits;
     const long rows = ((M + splits - 1) / splits + 15) / 16 * 16;
     hipLaunchKernelGGL((gen_gemm_tn<float, T>), dim3((unsigned)((C + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)splits),
                        dim3(256), 0, st, w.o, C, dY, C, dWo, C, M, C, C, rows);
-    // attention: dQ, dK, dV; then the LCE parts
-    hipLaunchKernelGGL(gen_attention_bwd, dim3(D.B * D.R * D.heads), dim3(kWave),
-                       (size_t)(2 * D.kn + 2 * D.d) * sizeof(float), st, w.qkv, Ir, w.dO, w.dqkv, D, D.scale);
+    // the LCE parts
     hipLaunchKernelGGL(gen_lce_bwd_dv<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w.dO, Wlce, w.dqkv, D);
     const long tpw = 512;
     hipLaunchKernelGGL(gen_lce_bwd_dw, dim3((unsigned)((M + tpw - 1) / tpw), 25), dim3(256), 0, st, w.dO, w.qkv, dWlce, D,
@@ -858,8 +928,7 @@ int generic_block_forward(const Dims &D, int hidden, float eps, const void *X, c
 
 bool generic_backward_supported(const Dims &D)
 {
-    return generic_supported(D) && D.d <= kBwdMaxD && (size_t)(2 * D.kn + 2 * D.d) * sizeof(float) <= 64 * 1024 &&
-           ((long)D.B * D.N + 511) / 512 <= 65535;
+    return generic_supported(D) && D.d <= kBwdMaxD;
 }
 
 size_t generic_backward_workspace_bytes(const Dims &D) { return carve_bwd(D, nullptr).bytes; }
