@@ -643,10 +643,11 @@ __global__ __launch_bounds__(256) void gen_gemm_tn(const TA *__restrict__ A, int
 // One workgroup per (image, region, head); 16 queries per pass (wavefront w owns 4 of them), the
 // routed keys in blocks of 64 staged in LDS.  D_q = sum_j P_j dP_j = dO_h[q] . Oatt_h[q] comes from
 // the attention output (before LCE is added to it).  Sweep 1 over the key blocks: the softmax
-// maximum and denominator of each query.  Sweep 2: per block, a lane per key forms P_j and dS_j;
-// then a lane per channel adds the query's share to dQ (registers) and to the block's dK, dV in LDS
-// (LDS atomics: the wavefronts' queries meet there); the block's dK, dV go to memory with one
-// atomic add per element (other regions route to the same keys).
+// maximum and denominator of each query.  Sweep 2: per block, a lane per key forms P_j and dS_j
+// (kept in LDS for the pass's 16 queries), a lane per channel adds the query's share to dQ
+// (registers), then a thread per (key, channel) sums the 16 queries' shares of dK, dV and adds them
+// to memory with one atomic add each (other passes and regions route to the same keys).  LDS
+// atomics for that sum were measured at about one lane per clock: eight times slower.
 constexpr int kBwdMaxD = 64;
 
 __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict__ QKV,
@@ -657,8 +658,8 @@ __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict
 {
     extern __shared__ float lds[];
     const int d = D.d, dp = d + 1;
-    float *Ks = lds, *Vs = Ks + 64 * dp, *dKs = Vs + 64 * dp, *dVs = dKs + 64 * d;
-    float *qs = dVs + 64 * d, *dos = qs + 16 * d, *Psc = dos + 16 * d, *dSsc = Psc + 16 * 64;
+    float *Ks = lds, *Vs = Ks + 64 * dp;
+    float *qs = Vs + 64 * dp, *dos = qs + 16 * d, *Psc = dos + 16 * d, *dSsc = Psc + 16 * 64;
     const int hd = blockIdx.x % D.heads;
     const int reg = (blockIdx.x / D.heads) % D.R;
     const int b = blockIdx.x / (D.heads * D.R);
@@ -678,11 +679,7 @@ __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict
             const int u = e / d, c = e % d;
             const float *row = img + (size_t)key_token(min(k0 + u, D.kn - 1)) * C3 + hd * d + c;
             Ks[u * dp + c] = row[D.C];
-            if (with_v) {
-                Vs[u * dp + c] = row[2 * D.C];
-                dKs[u * d + c] = 0.f;
-                dVs[u * d + c] = 0.f;
-            }
+            if (with_v) Vs[u * dp + c] = row[2 * D.C];
         }
     };
 
@@ -735,7 +732,7 @@ __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict
             __syncthreads();
 #pragma unroll
             for (int qq = 0; qq < 4; ++qq) {
-                if (s0 + 4 * wave + qq >= D.n) break;            // uniform in the wavefront
+                const bool live = s0 + 4 * wave + qq < D.n;      // uniform in the wavefront
                 const float *q = qs + (4 * wave + qq) * d, *dov = dos + (4 * wave + qq) * d;
                 float *Pw = Psc + (4 * wave + qq) * 64, *dSw = dSsc + (4 * wave + qq) * 64;
                 float a = 0.f, gsum = 0.f;
@@ -743,27 +740,30 @@ __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict
                     a = fmaf(q[c], Ks[lane * dp + c], a);
                     gsum = fmaf(dov[c], Vs[lane * dp + c], gsum);
                 }
-                const float pj = lane < cn ? expf(a * scale - m[qq]) / l[qq] : 0.f;
-                Pw[lane] = pj;                                   // read back by this wavefront only
+                const float pj = (live && lane < cn) ? expf(a * scale - m[qq]) / l[qq] : 0.f;
+                Pw[lane] = pj;
                 dSw[lane] = pj * (gsum - Dq[qq]) * scale;
-                if (lane < d) {
-                    const float qc = q[lane], doc = dov[lane];
+                if (live && lane < d) {
                     float acc = dq[qq];
-                    for (int u = 0; u < cn; ++u) {
-                        const float ds = dSw[u];
-                        acc = fmaf(ds, Ks[u * dp + lane], acc);
-                        unsafeAtomicAdd(dKs + u * d + lane, ds * qc);
-                        unsafeAtomicAdd(dVs + u * d + lane, Pw[u] * doc);
-                    }
+                    for (int u = 0; u < cn; ++u) acc = fmaf(dSw[u], Ks[u * dp + lane], acc);   // this wavefront's rows only
                     dq[qq] = acc;
                 }
             }
             __syncthreads();
-            for (int e = tid; e < cn * d; e += 256) {            // the block's dK, dV: other regions add to the same keys
+            // dK[u][c] += sum_q dS[q][u] Q[q][c], dV[u][c] += sum_q P[q][u] dO[q][c] over the pass's 16
+            // queries: a thread per (key, channel), then one atomic add each (other passes and other
+            // regions add to the same keys)
+            for (int e = tid; e < cn * d; e += 256) {
                 const int u = e / d, c = e % d;
+                float ak = 0.f, av = 0.f;
+#pragma unroll
+                for (int qi = 0; qi < 16; ++qi) {
+                    ak = fmaf(dSsc[qi * 64 + u], qs[qi * d + c], ak);
+                    av = fmaf(Psc[qi * 64 + u], dos[qi * d + c], av);
+                }
                 const size_t at = (size_t)key_token(k0 + u) * C3 + hd * d + c;
-                unsafeAtomicAdd(dimg + at + D.C, dKs[u * d + c]);
-                unsafeAtomicAdd(dimg + at + 2 * D.C, dVs[u * d + c]);
+                unsafeAtomicAdd(dimg + at + D.C, ak);
+                unsafeAtomicAdd(dimg + at + 2 * D.C, av);
             }
         }
 #pragma unroll
@@ -776,7 +776,7 @@ __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict
 
 inline size_t attention_bwd_smem(int d)
 {
-    return (size_t)(2 * 64 * (d + 1) + 2 * 64 * d + 2 * 16 * d + 2 * 16 * 64) * sizeof(float);
+    return (size_t)(2 * 64 * (d + 1) + 2 * 16 * d + 2 * 16 * 64) * sizeof(float);
 }
 
 // dV += LCE^T(dO): dV[y, x, c] += sum w[c, ky, kx] dO[y - ky + 2, x - kx + 2, c]   (after the attention part)
