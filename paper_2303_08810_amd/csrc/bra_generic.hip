@@ -811,9 +811,12 @@ __global__ __launch_bounds__(256) void gen_lce_bwd_dw(const float *__restrict__ 
 {
     const int tap = blockIdx.y, ky = tap / 5, kx = tap % 5;
     const long t_begin = (long)blockIdx.x * tokens_per_wg, t_end = min((long)D.B * D.N, t_begin + tokens_per_wg);
-    for (int c = threadIdx.x; c < D.C; c += 256) {
+    // 256 / C groups of threads share the workgroup's tokens when C < 256
+    const int cw = D.C < 256 ? D.C : 256, groups = 256 / cw, grp = threadIdx.x / cw;
+    if (grp >= groups) return;
+    for (int c = threadIdx.x % cw; c < D.C; c += cw) {
         float acc = 0.f;
-        for (long tok = t_begin; tok < t_end; ++tok) {
+        for (long tok = t_begin + grp; tok < t_end; tok += groups) {
             const int x = (int)(tok % D.W), y = (int)((tok / D.W) % D.H);
             const int yy = y + ky - 2, xx = x + kx - 2;
             if (yy < 0 || yy >= D.H || xx < 0 || xx >= D.W) continue;
@@ -890,8 +893,8 @@ int backward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *W
     hipLaunchKernelGGL(gen_attention_bwd, dim3(D.B * D.R * D.heads), dim3(256), attention_bwd_smem(D.d), st, w.qkv, Ir,
                        w.o, w.dO, w.dqkv, D, D.scale);
     hipLaunchKernelGGL(gen_lce_add<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w.qkv, Wlce, w.o, D);
-    long splits = (M + 2047) / 2048;
-    splits = splits > 1024 ? 1024 : splits;
+    long splits = (M + 255) / 256;                 // enough workgroups to fill the chip
+    splits = splits > 4096 ? 4096 : splits;
     const long rows = ((M + splits - 1) / splits + 15) / 16 * 16;
     hipLaunchKernelGGL((gen_gemm_tn<float, T>), dim3((unsigned)((C + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)splits),
                        dim3(256), 0, st, w.o, C, dY, C, dWo, C, M, C, C, rows);
