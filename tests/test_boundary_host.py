@@ -133,6 +133,24 @@ def test_block_and_padded_workspace_queries():
     assert L.bra_forward_padded(ctypes.byref(shape), fake, fake, fake, fake, fake, None, None, None, 0, None) == -5
 
 
+def test_backward_workspace_query_and_error_codes():
+    L = bra.lib()
+    out = ctypes.c_size_t(0)
+    shape = bra.make_shape(2, 28, 28, 64, 2, 7, 4, bra.BRA_F32)
+    assert L.bra_backward_workspace_bytes(ctypes.byref(shape), ctypes.byref(out)) == 0
+    # Q|K|V, O, dO and dQ|dK|dV in float32: 8 C floats per token
+    assert out.value >= 2 * 28 * 28 * 8 * 64 * 4 and out.value % 256 == 0
+    wide = bra.make_shape(1, 8, 8, 256, 2, 2, 2, bra.BRA_F32)          # heads of 128 channels
+    assert L.bra_backward_workspace_bytes(ctypes.byref(wide), ctypes.byref(out)) == -6
+    bad = bra.make_shape(1, 28, 28, 64, 2, 7, 50, bra.BRA_F32)
+    assert L.bra_backward_workspace_bytes(ctypes.byref(bad), ctypes.byref(out)) == -3
+    fake = ctypes.c_void_p(4096)
+    args = [fake] * 11
+    assert L.bra_backward(ctypes.byref(shape), *args, 16, None) == -5          # workspace too small
+    args[4] = None                                                              # Ir missing
+    assert L.bra_backward(ctypes.byref(shape), *args, 1 << 30, None) == -1
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(bra, "_lib", None)
     monkeypatch.setattr(bra, "LIB_PATH", str(tmp_path / "libbra.so"))

@@ -48,6 +48,28 @@ def test_backward(dtype, B, H, W, C, heads, S, k):
         assert rel <= tol, f"{name}: {rel:.3e} > {tol}"
 
 
+def random_backward_shapes(count, seed):
+    import random
+    rng = random.Random(seed)
+    out = []
+    while len(out) < count:
+        S = rng.choice([1, 2, 3, 4, 5, 7])
+        H, W = S * rng.choice([1, 2, 3, 4, 5, 9]), S * rng.choice([1, 2, 3, 4, 6])
+        heads = rng.choice([1, 2, 3, 4])
+        C = rng.choice([8, 16, 24, 32, 64]) * heads
+        k = rng.choice([1, 2, 3, min(S * S, 5), S * S])
+        n = (H // S) * (W // S)
+        if k > S * S or H * W * C > 60000 or H * W * k * n * C > 3e7:
+            continue
+        out.append((rng.choice(["f32", "f32", "bf16"]), rng.choice([1, 2, 3]), H, W, C, heads, S, k))
+    return out
+
+
+@pytest.mark.parametrize("dtype,B,H,W,C,heads,S,k", random_backward_shapes(12, seed=20230311))
+def test_backward_random_shapes(dtype, B, H, W, C, heads, S, k):
+    test_backward(dtype, B, H, W, C, heads, S, k)
+
+
 def test_backward_after_forward_uses_its_routing():
     B, H, W, C, heads, S, k = 2, 14, 14, 64, 2, 7, 4
     Xn, Wqkvn, Won, Wlcen = make_inputs(B, H, W, C, seed=6100)
