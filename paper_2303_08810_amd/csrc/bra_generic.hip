@@ -640,7 +640,7 @@ __global__ __launch_bounds__(256) void gen_gemm_tn(const TA *__restrict__ A, int
         }
 }
 
-// One workgroup per (image, region, head); 16 queries per pass (wavefront w owns 4 of them), the
+// One workgroup per (image, region, head, pass of 16 queries: wavefront w owns 4 of them), the
 // routed keys in blocks of 64 staged in LDS.  D_q = sum_j P_j dP_j = dO_h[q] . Oatt_h[q] comes from
 // the attention output (before LCE is added to it).  Sweep 1 over the key blocks: the softmax
 // maximum and denominator of each query.  Sweep 2: per block, a lane per key forms P_j and dS_j
@@ -660,9 +660,11 @@ __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict
     const int d = D.d, dp = d + 1;
     float *Ks = lds, *Vs = Ks + 64 * dp;
     float *qs = Vs + 64 * dp, *dos = qs + 16 * d, *Psc = dos + 16 * d, *dSsc = Psc + 16 * 64;
-    const int hd = blockIdx.x % D.heads;
-    const int reg = (blockIdx.x / D.heads) % D.R;
-    const int b = blockIdx.x / (D.heads * D.R);
+    const int passes = (D.n + 15) / 16;
+    const int pass = blockIdx.x % passes, rest = blockIdx.x / passes;
+    const int hd = rest % D.heads;
+    const int reg = (rest / D.heads) % D.R;
+    const int b = rest / (D.heads * D.R);
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int C3 = 3 * D.C;
     const float *img = QKV + (size_t)b * D.N * C3;
@@ -683,8 +685,8 @@ __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict
         }
     };
 
-    for (int s0 = 0; s0 < D.n; s0 += 16) {
-        __syncthreads();                               // the previous pass is done with the queries
+    {
+        const int s0 = 16 * pass;
         for (int e = tid; e < 16 * d; e += 256) {
             const int s = min(s0 + e / d, D.n - 1);      // past the end: the last query again; it adds nothing
             const int qtok = query_token(s);
@@ -890,7 +892,8 @@ int backward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *W
     fill_zero(dWlce, (size_t)C * 25, st);
     fill_zero(w.dqkv, (size_t)M * C3, st);
     // attention: dQ, dK, dV from the attention output alone; then O = attention + LCE(V) for dWo
-    hipLaunchKernelGGL(gen_attention_bwd, dim3(D.B * D.R * D.heads), dim3(256), attention_bwd_smem(D.d), st, w.qkv, Ir,
+    hipLaunchKernelGGL(gen_attention_bwd, dim3((unsigned)((long)D.B * D.R * D.heads * ((D.n + 15) / 16))), dim3(256),
+                       attention_bwd_smem(D.d), st, w.qkv, Ir,
                        w.o, w.dO, w.dqkv, D, D.scale);
     hipLaunchKernelGGL(gen_lce_add<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w.qkv, Wlce, w.o, D);
     long splits = (M + 255) / 256;                 // enough workgroups to fill the chip
@@ -931,7 +934,7 @@ int generic_block_forward(const Dims &D, int hidden, float eps, const void *X, c
 
 bool generic_backward_supported(const Dims &D)
 {
-    return generic_supported(D) && D.d <= kBwdMaxD;
+    return generic_supported(D) && D.d <= kBwdMaxD && (long)D.B * D.R * D.heads * ((D.n + 15) / 16) <= 0x7fffffffL;
 }
 
 size_t generic_backward_workspace_bytes(const Dims &D) { return carve_bwd(D, nullptr).bytes; }
