@@ -641,9 +641,9 @@ __global__ __launch_bounds__(256) void gen_gemm_tn(const TA *__restrict__ A, int
 }
 
 // One workgroup per (image, region, head, pass of 16 queries: wavefront w owns 4 of them), the
-// routed keys in blocks of 64 staged in LDS.  D_q = sum_j P_j dP_j = dO_h[q] . Oatt_h[q] comes from
-// the attention output (before LCE is added to it).  Sweep 1 over the key blocks: the softmax
-// maximum and denominator of each query.  Sweep 2: per block, a lane per key forms P_j and dS_j
+// routed keys in blocks of 64 staged in LDS.  Sweep 1 over the key blocks: the softmax maximum and
+// denominator of each query and, rescaled along with them, sum_j e_j dP_j, which gives
+// D_q = sum_j P_j dP_j.  The attention output itself (needed for dWo) falls out of sweep 2.  Sweep 2: per block, a lane per key forms P_j and dS_j
 // (kept in LDS for the pass's 16 queries), a lane per channel adds the query's share to dQ
 // (registers), then a thread per (key, channel) sums the 16 queries' shares of dK, dV and adds them
 // to memory with one atomic add each (other passes and regions route to the same keys).  LDS
@@ -652,7 +652,7 @@ constexpr int kBwdMaxD = 64;
 
 __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict__ QKV,
                                                          const int32_t *__restrict__ Ir,
-                                                         const float *__restrict__ Oatt,
+                                                         float *__restrict__ Oatt,
                                                          const float *__restrict__ dO, float *__restrict__ dQKV,
                                                          Dims D, float scale)
 {
@@ -694,39 +694,46 @@ __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict
             dos[e] = dO[((size_t)b * D.N + qtok) * D.C + hd * d + e % d];
         }
         __syncthreads();
-        float m[4], l[4], Dq[4], dq[4];
+        float m[4], l[4], Dq[4], dq[4], oa[4];
 #pragma unroll
         for (int qq = 0; qq < 4; ++qq) {
-            const int s = min(s0 + 4 * wave + qq, D.n - 1);
-            float t = 0.f;
-            if (lane < d)
-                t = dos[(4 * wave + qq) * d + lane] * Oatt[((size_t)b * D.N + query_token(s)) * D.C + hd * d + lane];
-            for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off, kWave);
-            Dq[qq] = t;
             m[qq] = -INFINITY;
             l[qq] = 0.f;
+            Dq[qq] = 0.f;          // sum_j e_j dP_j until the end of sweep 1, then divided by l
             dq[qq] = 0.f;
+            oa[qq] = 0.f;
         }
-        for (int k0 = 0; k0 < D.kn; k0 += 64) {        // sweep 1: maximum and denominator
+        for (int k0 = 0; k0 < D.kn; k0 += 64) {        // sweep 1: maximum, denominator and sum_j e_j dP_j
             const int cn = min(64, D.kn - k0);
             __syncthreads();
-            stage_keys(k0, false);
+            stage_keys(k0, true);
             __syncthreads();
 #pragma unroll
             for (int qq = 0; qq < 4; ++qq) {
-                const float *q = qs + (4 * wave + qq) * d;
-                float a = 0.f;
-                for (int c = 0; c < d; ++c) a = fmaf(q[c], Ks[lane * dp + c], a);
+                const float *q = qs + (4 * wave + qq) * d, *dov = dos + (4 * wave + qq) * d;
+                float a = 0.f, gsum = 0.f;
+                for (int c = 0; c < d; ++c) {
+                    a = fmaf(q[c], Ks[lane * dp + c], a);
+                    gsum = fmaf(dov[c], Vs[lane * dp + c], gsum);
+                }
                 a = lane < cn ? a * scale : -INFINITY;
                 float mx = a;
                 for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
                 const float m_new = fmaxf(m[qq], mx);
                 float e = lane < cn ? expf(a - m_new) : 0.f;
-                for (int off = 32; off >= 1; off >>= 1) e += __shfl_xor(e, off, kWave);
-                l[qq] = l[qq] * ((m[qq] == -INFINITY) ? 0.f : expf(m[qq] - m_new)) + e;
+                float eg = e * gsum;
+                for (int off = 32; off >= 1; off >>= 1) {
+                    e += __shfl_xor(e, off, kWave);
+                    eg += __shfl_xor(eg, off, kWave);
+                }
+                const float corr = (m[qq] == -INFINITY) ? 0.f : expf(m[qq] - m_new);
+                l[qq] = l[qq] * corr + e;
+                Dq[qq] = Dq[qq] * corr + eg;
                 m[qq] = m_new;
             }
         }
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) Dq[qq] /= l[qq];
         for (int k0 = 0; k0 < D.kn; k0 += 64) {        // sweep 2: gradients
             const int cn = min(64, D.kn - k0);
             __syncthreads();
@@ -746,9 +753,13 @@ __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict
                 Pw[lane] = pj;
                 dSw[lane] = pj * (gsum - Dq[qq]) * scale;
                 if (live && lane < d) {
-                    float acc = dq[qq];
-                    for (int u = 0; u < cn; ++u) acc = fmaf(dSw[u], Ks[u * dp + lane], acc);   // this wavefront's rows only
+                    float acc = dq[qq], o = oa[qq];
+                    for (int u = 0; u < cn; ++u) {               // this wavefront's rows only
+                        acc = fmaf(dSw[u], Ks[u * dp + lane], acc);
+                        o = fmaf(Pw[u], Vs[u * dp + lane], o);
+                    }
                     dq[qq] = acc;
+                    oa[qq] = o;
                 }
             }
             __syncthreads();
@@ -771,7 +782,10 @@ __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict
 #pragma unroll
         for (int qq = 0; qq < 4; ++qq) {
             const int s = s0 + 4 * wave + qq;
-            if (s < D.n && lane < d) dimg[(size_t)query_token(s) * C3 + hd * d + lane] = dq[qq];   // every query has one owner
+            if (s < D.n && lane < d) {                           // every query has one owner
+                dimg[(size_t)query_token(s) * C3 + hd * d + lane] = dq[qq];
+                Oatt[((size_t)b * D.N + query_token(s)) * D.C + hd * d + lane] = oa[qq];
+            }
         }
     }
 }
@@ -876,14 +890,9 @@ int backward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *W
         }
     }
     ProfScope ps(st, K_GEN_BACKWARD);
-    // forward intermediates again: Q | K | V and the attention output (LCE is added further down)
+    // forward intermediates again: Q | K | V (the attention output comes out of the backward kernel)
     hipLaunchKernelGGL((gen_gemm<T, T, float>), dim3((unsigned)((M + 63) / 64), (unsigned)((C3 + 63) / 64)), dim3(256), 0,
                        st, X, C, Wqkv, C3, w.qkv, C3, (int)M, C3, C);
-    if (D.d <= kAttnLdsD)
-        hipLaunchKernelGGL(gen_attention_lds, dim3(D.B * D.R * D.heads), dim3(256), 0, st, w.qkv, Ir, w.o, D, D.scale);
-    else
-        hipLaunchKernelGGL(gen_attention, dim3(D.B * D.R * D.heads), dim3(256), D.k * sizeof(int), st, w.qkv, Ir, w.o, D,
-                           D.scale);
     // dO = dY Wo^T
     hipLaunchKernelGGL((gen_gemm<T, T, float, true>), dim3((unsigned)((M + 63) / 64), (unsigned)((C + 63) / 64)), dim3(256),
                        0, st, dY, C, Wo, C, w.dO, C, (int)M, C, C);
@@ -891,7 +900,7 @@ int backward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *W
     fill_zero(dWqkv, (size_t)C * C3, st);
     fill_zero(dWlce, (size_t)C * 25, st);
     fill_zero(w.dqkv, (size_t)M * C3, st);
-    // attention: dQ, dK, dV from the attention output alone; then O = attention + LCE(V) for dWo
+    // attention: dQ, dK, dV and the attention output; then O = attention + LCE(V) for dWo
     hipLaunchKernelGGL(gen_attention_bwd, dim3((unsigned)((long)D.B * D.R * D.heads * ((D.n + 15) / 16))), dim3(256),
                        attention_bwd_smem(D.d), st, w.qkv, Ir,
                        w.o, w.dO, w.dqkv, D, D.scale);
