@@ -93,11 +93,15 @@ __global__ __launch_bounds__(256) void gen_gemm(const TA *__restrict__ A, int ld
 
 // ---------------------------------------------------------------------------
 // Xr[b, r, c] = mean over the n tokens of region r of X[b, :, :, c]; tokens are
-// summed in row-major order inside the region.  One workgroup per (b, r).
+// summed in row-major order inside the region; one workgroup per (b, r),
+// and Qr[b, r, :] = Xr[b, r, :] Wq, Kr[b, r, :] = Xr[b, r, :] Wk from the means in LDS (Sec. 3.2).
 template <typename T>
-__global__ void gen_pool(const T *__restrict__ X, float *__restrict__ Xr, Dims D)
+__global__ void gen_pool_qk(const T *__restrict__ X, const T *__restrict__ Wqkv, float *__restrict__ Xr,
+                            float *__restrict__ Qr, float *__restrict__ Kr, Dims D)
 {
+    extern __shared__ float xs[];
     const int b = blockIdx.x / D.R, r = blockIdx.x % D.R;
+    const size_t row = blockIdx.x;
     const int y0 = (r / D.S) * D.rh, x0 = (r % D.S) * D.rw;
     const T *img = X + (size_t)b * D.N * D.C;
     for (int c = threadIdx.x; c < D.C; c += blockDim.x) {
@@ -105,18 +109,9 @@ __global__ void gen_pool(const T *__restrict__ X, float *__restrict__ Xr, Dims D
         for (int ry = 0; ry < D.rh; ++ry)
             for (int rx = 0; rx < D.rw; ++rx)
                 s += load_f32(img + ((size_t)(y0 + ry) * D.W + x0 + rx) * D.C + c);
-        Xr[((size_t)b * D.R + r) * D.C + c] = s / (float)D.n;
+        xs[c] = s / (float)D.n;
+        Xr[row * D.C + c] = xs[c];
     }
-}
-
-// Qr[b, r, :] = Xr[b, r, :] Wq ; Kr[b, r, :] = Xr[b, r, :] Wk.  One workgroup per (b, r).
-template <typename T>
-__global__ void gen_region_qk(const float *__restrict__ Xr, const T *__restrict__ Wqkv,
-                              float *__restrict__ Qr, float *__restrict__ Kr, Dims D)
-{
-    extern __shared__ float xs[];
-    const size_t row = blockIdx.x;
-    for (int c = threadIdx.x; c < D.C; c += blockDim.x) xs[c] = Xr[row * D.C + c];
     __syncthreads();
     for (int o = threadIdx.x; o < 2 * D.C; o += blockDim.x) {
         float acc = 0.f;
@@ -408,15 +403,9 @@ void launch_route(const Dims &D, const T *X, const T *Wqkv, int32_t *Ir, float *
                   const GenericWs &w, hipStream_t st)
 {
     const int regs = D.B * D.R;
-    const int pt = D.C < 256 ? ((D.C + 63) / 64) * 64 : 256;
     {
         ProfScope ps(st, K_GEN_POOL);
-        hipLaunchKernelGGL(gen_pool<T>, dim3(regs), dim3(pt), 0, st, X, w.xr, D);
-    }
-    {
-        ProfScope ps(st, K_GEN_REGION_QK);
-        hipLaunchKernelGGL(gen_region_qk<T>, dim3(regs), dim3(256), D.C * sizeof(float), st, w.xr,
-                           Wqkv, w.qr, w.kr, D);
+        hipLaunchKernelGGL(gen_pool_qk<T>, dim3(regs), dim3(256), D.C * sizeof(float), st, X, Wqkv, w.xr, w.qr, w.kr, D);
     }
     {
         ProfScope ps(st, K_GEN_TOPK);
