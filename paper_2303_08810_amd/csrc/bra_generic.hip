@@ -725,9 +725,11 @@ __global__ __launch_bounds__(256) void gen_attention_bwd(const float *__restrict
         for (int qq = 0; qq < 4; ++qq) Dq[qq] /= l[qq];
         for (int k0 = 0; k0 < D.kn; k0 += 64) {        // sweep 2: gradients
             const int cn = min(64, D.kn - k0);
-            __syncthreads();
-            stage_keys(k0, true);
-            __syncthreads();
+            if (D.kn > 64) {                           // a single block is still in LDS from sweep 1
+                __syncthreads();
+                stage_keys(k0, true);
+                __syncthreads();
+            }
 #pragma unroll
             for (int qq = 0; qq < 4; ++qq) {
                 const bool live = s0 + 4 * wave + qq < D.n;      // uniform in the wavefront
