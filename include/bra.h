@@ -53,8 +53,10 @@ enum { BRA_F32 = 0, BRA_BF16 = 1 };                 /* bra_shape.dtype */
 /* bra_shape.path: which kernel family runs.
  *   AUTO    the fastest family that supports the shape;
  *   GENERIC scalar (VALU) float32 kernels, any valid shape, float32 intermediates;
- *   MFMA    bf16 matrix-core kernels (bf16 only, d = 32, region sizes the tiles
- *           are built for); BRA_ERR_UNSUPPORTED otherwise. */
+ *   MFMA    bf16 matrix-core kernels: bf16 tensors, C a multiple of 64, heads of 32 or
+ *           64 channels (specialised kernels for C = 64, 128, 256 with heads of 32
+ *           and the region sizes of the paper's stages; a general pipeline for the
+ *           rest); BRA_ERR_UNSUPPORTED otherwise. */
 enum { BRA_PATH_AUTO = 0, BRA_PATH_GENERIC = 1, BRA_PATH_MFMA = 2 };
 
 enum {
