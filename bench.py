@@ -445,6 +445,8 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the other named workloads")
     ap.add_argument("--no-block", action="store_true",
                     help="skip the whole-block timings (position encoding, LayerNorm, BRA, MLP)")
+    ap.add_argument("--block-same", action="store_true",
+                    help="whole-block and backward timings for the chosen workload only (for counter runs)")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip the context timings (repeats, smooth inputs, hot cache, graph replay)")
     ap.add_argument("--calibrate", action="store_true",
@@ -509,11 +511,15 @@ def main():
         # one whole block around BRA at every workload's shape (context, never `value`)
         blocks = {}
         for idx, c in {**CONFIGS, **NEXT_CONFIGS}.items():
+            if args.block_same and idx != args.workload:
+                continue
             n = args.steps if idx == args.workload else max(20, args.steps // 4)
             blocks[c.name] = time_block(c, n, n)
         line["block_forward"] = blocks
-        line["padded_forward"] = time_padded(max(20, args.steps // 4), max(20, args.steps // 4))
-        line["backward"] = {CONFIGS[i].name: time_backward(CONFIGS[i], 5, 2) for i in (1, 2, 3)}
+        if not args.block_same:
+            line["padded_forward"] = time_padded(max(20, args.steps // 4), max(20, args.steps // 4))
+        line["backward"] = {CONFIGS[i].name: time_backward(CONFIGS[i], 5, 2)
+                            for i in ((args.workload,) if args.block_same else (1, 2, 3))}
     if args.calibrate:
         src = torch.empty(CALIBRATION_BYTES, dtype=torch.uint8, device="cuda").random_()
         dst = torch.empty_like(src)

@@ -19,6 +19,7 @@ NAMES = {"k_fused": "mfma_fused_k1", "k_pool": "mfma_pool_qk", "k_route": "mfma_
          "k_attn_map": "mfma_attn_small", "k_attn_map4": "mfma_attn_small",
          "k_qkv": "mfma_qkv", "k_attn_big": "mfma_attention", "k_attn_small": "mfma_attn_small",
          "k_small": "mfma_attn_small", "k_lce_add": "mfma_lce_add", "k_prep_weights": "mfma_prep",
+         "k_token_ln": "block_ln", "k_mlp_fused64": "block_mlp_fused", "k_mlp_stream": "block_mlp_fused",
          "k_util_copy": "copy"}
 
 
@@ -33,6 +34,8 @@ def averages(directory, counter):
                 name = NAMES[m.group(1)]
                 if re.search(r"k_qkv<\d+, \d+, 1>", row["Kernel_Name"]):   # the same kernel with Wo as its only matrix
                     name = "mfma_wo"
+                if m.group(1) == "k_token_ln":                               # position encoding (0) or residual (1) + LayerNorm
+                    name = "block_pos_ln" if "k_token_ln<0" in row["Kernel_Name"] else "block_add_ln"
                 acc[name].append(float(row["Counter_Value"]))
     return {k: sum(v) / len(v) for k, v in acc.items()}
 
