@@ -3,17 +3,23 @@
  * Attention (BRA), "BiFormer: Vision Transformer with Bi-Level Routing Attention".
  *
  * This file is included twice by bra_oracle.c, once with REAL = float and once
- * with REAL = double.  It is a plain, slow, step-by-step transcription of the
- * method's definition (Sec. 3.2, Eq. 3-7, and the data flow of Algorithm 1),
- * with every intermediate tensor the paper names materialised, including the
- * gathered key/value tensors of Eq. 6.  No blocking, fusion or reordering.
+ * with REAL = double.  It writes out the DEFINITION of the layer (Sec. 3.2, Eq. 3-7,
+ * with the per-head attention and W^o of Eq. 1-2) token by token on the H x W map:
+ * nothing is re-laid-out, blocked, fused or reordered, and no tensor other than the
+ * ones the equations name (Q, K, V, Q^r, K^r, A^r, I^r, the output) is formed.  The
+ * gathered key/value set of Eq. 6 appears as what it is, a set of tokens: for a query
+ * of region i, the tokens of the regions listed in row i of I^r.
  * It shares no code with the HIP library and must never be called by it.
+ *
+ * Notation: token t = (y, x) of the map; rh = H / S, rw = W / S; region(t) =
+ * (y / rh) S + x / rw (Sec. 3.2, "Region partition and input projection");
+ * n = rh rw tokens per region; R = S^2 regions; head h owns channels [h d, (h+1) d).
  *
  * Conventions where the paper is silent (all listed in the design notes):
  *   - softmax scale is an argument (default chosen by the caller: 1/sqrt(C/heads),
  *     Eq. 1 applied to the per-head operands of Eq. 2);
  *   - routing (Eq. 4-5) uses all C channels and is shared by the heads;
- *   - top-k rows are ordered by descending affinity, ties to the smaller index;
+ *   - row i of I^r lists regions by descending affinity, equal values by ascending index;
  *   - LCE (Eq. 7) is a 5x5 depth-wise cross-correlation of V on the H x W map,
  *     stride 1, zero padding 2, no bias;
  *   - Y = (Attention + LCE(V)) W^o  (Eq. 7 followed by the W^o of Eq. 2), no bias.
@@ -23,63 +29,46 @@
 #define CAT(a, b) CAT_(a, b)
 #define FN(name) CAT(name, SUFFIX)
 
-/* Region partition (Sec. 3.2 "Region partition and input projection"; first step of
- * Algorithm 1): (H, W, C) -> (S^2, HW/S^2, C); token (y, x) goes to region
- * (y / rh) * S + (x / rw), slot (y % rh) * rw + (x % rw). */
-static void FN(patchify_)(const REAL *in, REAL *out, int H, int W, int C, int S)
+/* Eq. 3 for one of the three projections: out[t, o] = sum_c X[t, c] W[c, col0 + o], where W is
+ * the [C, ldw] matrix that holds the projection's weights in columns col0 .. col0 + C - 1. */
+static void FN(project_)(const REAL *X, const REAL *Wmat, int ldw, int col0, REAL *out, int N, int C)
 {
-    int rh = H / S, rw = W / S, n = rh * rw;
-    for (int y = 0; y < H; ++y)
-        for (int x = 0; x < W; ++x) {
-            int r = (y / rh) * S + (x / rw);
-            int s = (y % rh) * rw + (x % rw);
-            memcpy(out + ((size_t)r * n + s) * C, in + ((size_t)y * W + x) * C, sizeof(REAL) * C);
-        }
-}
-
-/* Inverse of patchify (last step of Algorithm 1). */
-static void FN(unpatchify_)(const REAL *in, REAL *out, int H, int W, int C, int S)
-{
-    int rh = H / S, rw = W / S, n = rh * rw;
-    for (int y = 0; y < H; ++y)
-        for (int x = 0; x < W; ++x) {
-            int r = (y / rh) * S + (x / rw);
-            int s = (y % rh) * rw + (x % rw);
-            memcpy(out + ((size_t)y * W + x) * C, in + ((size_t)r * n + s) * C, sizeof(REAL) * C);
-        }
-}
-
-/* out[M, N] = a[M, K] * b[K, N], row-major; returns the number of multiply-adds. */
-static int64_t FN(matmul_)(const REAL *a, const REAL *b, REAL *out, int M, int K, int N)
-{
-    for (int i = 0; i < M; ++i)
-        for (int j = 0; j < N; ++j) {
+    for (int t = 0; t < N; ++t)
+        for (int o = 0; o < C; ++o) {
             REAL acc = 0;
-            for (int c = 0; c < K; ++c)
-                acc += a[(size_t)i * K + c] * b[(size_t)c * N + j];
-            out[(size_t)i * N + j] = acc;
+            for (int c = 0; c < C; ++c) acc += X[(size_t)t * C + c] * Wmat[(size_t)c * ldw + col0 + o];
+            out[(size_t)t * C + o] = acc;
         }
-    return (int64_t)M * K * N;
 }
 
-/* Row-wise top-k index (Eq. 5): k largest entries of each row of A[R, R], in
- * descending order; equal values are taken in ascending index order. */
-static void FN(topk_index_)(const REAL *A, int32_t *I, int R, int k)
+/* Region-level queries / keys (Sec. 3.2, "Region-to-region routing"): mean[r, c] = average of
+ * T[t, c] over the tokens t of region r. */
+static void FN(region_mean_)(const REAL *T, REAL *mean, int H, int W, int C, int S)
 {
-    char *taken = (char *)malloc((size_t)R);
-    for (int i = 0; i < R; ++i) {
-        memset(taken, 0, (size_t)R);
-        for (int p = 0; p < k; ++p) {
-            int best = -1;
-            for (int j = 0; j < R; ++j) {
-                if (taken[j]) continue;
-                if (best < 0 || A[(size_t)i * R + j] > A[(size_t)i * R + best]) best = j;
-            }
-            taken[best] = 1;
-            I[(size_t)i * k + p] = best;
+    const int rh = H / S, rw = W / S, R = S * S;
+    for (int r = 0; r < R; ++r)
+        for (int c = 0; c < C; ++c) {
+            REAL sum = 0;       /* region r covers rows (r / S) rh .., columns (r % S) rw .. */
+            for (int y = (r / S) * rh; y < (r / S + 1) * rh; ++y)
+                for (int x = (r % S) * rw; x < (r % S + 1) * rw; ++x) sum += T[((size_t)y * W + x) * C + c];
+            mean[(size_t)r * C + c] = sum / (REAL)(rh * rw);
         }
-    }
-    free(taken);
+}
+
+/* Eq. 5: row i of I^r holds the indices of the k largest entries of row i of A^r.  Written as a
+ * ranking: entry j stands at position (number of entries that come before it), where j' comes
+ * before j if it is larger, or equal with a smaller index. */
+static void FN(routing_index_)(const REAL *A, int32_t *I, int R, int k)
+{
+    for (int i = 0; i < R; ++i)
+        for (int j = 0; j < R; ++j) {
+            int before = 0;
+            for (int jj = 0; jj < R; ++jj) {
+                const REAL a = A[(size_t)i * R + jj], b = A[(size_t)i * R + j];
+                if (a > b || (a == b && jj < j)) ++before;
+            }
+            if (before < k) I[(size_t)i * k + before] = j;
+        }
 }
 
 /* One image.  Pointers marked opt may be NULL. */
@@ -94,135 +83,105 @@ static void FN(bra_image_)(int H, int W, int C, int heads, int S, int k, REAL sc
     const int kn = k * n;
     const size_t NC = (size_t)N * C;
 
-    REAL *xr = (REAL *)malloc(sizeof(REAL) * NC);
-    REAL *qkv = (REAL *)malloc(sizeof(REAL) * NC * 3);
-    REAL *q = (REAL *)malloc(sizeof(REAL) * NC);
-    REAL *kk = (REAL *)malloc(sizeof(REAL) * NC);
-    REAL *v = (REAL *)malloc(sizeof(REAL) * NC);
-    REAL *q_r = (REAL *)malloc(sizeof(REAL) * (size_t)R * C);
-    REAL *k_r = (REAL *)malloc(sizeof(REAL) * (size_t)R * C);
-    REAL *k_rT = (REAL *)malloc(sizeof(REAL) * (size_t)R * C);
-    REAL *A_r = (REAL *)malloc(sizeof(REAL) * (size_t)R * R);
-    int32_t *I_r = (int32_t *)malloc(sizeof(int32_t) * (size_t)R * k);
-    REAL *k_g = (REAL *)malloc(sizeof(REAL) * (size_t)R * kn * C);
-    REAL *v_g = (REAL *)malloc(sizeof(REAL) * (size_t)R * kn * C);
-    REAL *att = (REAL *)malloc(sizeof(REAL) * (size_t)kn);
-    REAL *out_r = (REAL *)malloc(sizeof(REAL) * NC);   /* region layout */
-    REAL *v_map = (REAL *)malloc(sizeof(REAL) * NC);   /* V on the H x W map */
-    REAL *lce_map = (REAL *)malloc(sizeof(REAL) * NC);
-    REAL *lce_r = (REAL *)malloc(sizeof(REAL) * NC);
-    REAL *o_map = (REAL *)malloc(sizeof(REAL) * NC);
+    REAL *Q = (REAL *)malloc(sizeof(REAL) * NC);
+    REAL *K = (REAL *)malloc(sizeof(REAL) * NC);
+    REAL *V = (REAL *)malloc(sizeof(REAL) * NC);
+    REAL *Qr = (REAL *)malloc(sizeof(REAL) * (size_t)R * C);
+    REAL *Kr = (REAL *)malloc(sizeof(REAL) * (size_t)R * C);
+    REAL *Ar = (REAL *)malloc(sizeof(REAL) * (size_t)R * R);
+    int32_t *Ir = (int32_t *)malloc(sizeof(int32_t) * (size_t)R * k);
+    int *keys = (int *)malloc(sizeof(int) * (size_t)kn);     /* the tokens a query attends to */
+    REAL *w = (REAL *)malloc(sizeof(REAL) * (size_t)kn);      /* their softmax weights */
+    REAL *O = (REAL *)malloc(sizeof(REAL) * NC);              /* Attention(..) + LCE(V) of Eq. 7 */
 
-    /* patchify, then the fused linear projection and its split into q, k, v
-     * (Eq. 3; W^q, W^k, W^v are the three column blocks of Wqkv). */
-    FN(patchify_)(X, xr, H, W, C, S);
-    macs[0] += FN(matmul_)(xr, Wqkv, qkv, N, C, 3 * C);
-    for (int t = 0; t < N; ++t)
-        for (int c = 0; c < C; ++c) {
-            q[(size_t)t * C + c] = qkv[(size_t)t * 3 * C + c];
-            kk[(size_t)t * C + c] = qkv[(size_t)t * 3 * C + C + c];
-            v[(size_t)t * C + c] = qkv[(size_t)t * 3 * C + 2 * C + c];
+    /* Eq. 3: Q = X W^q, K = X W^k, V = X W^v; the three weights are the column blocks of Wqkv. */
+    FN(project_)(X, Wqkv, 3 * C, 0, Q, N, C);
+    FN(project_)(X, Wqkv, 3 * C, C, K, N, C);
+    FN(project_)(X, Wqkv, 3 * C, 2 * C, V, N, C);
+    macs[0] += (int64_t)3 * N * C * C;
+
+    /* Q^r, K^r: per-region averages; Eq. 4: A^r = Q^r (K^r)^T. */
+    FN(region_mean_)(Q, Qr, H, W, C, S);
+    FN(region_mean_)(K, Kr, H, W, C, S);
+    for (int i = 0; i < R; ++i)
+        for (int j = 0; j < R; ++j) {
+            REAL acc = 0;
+            for (int c = 0; c < C; ++c) acc += Qr[(size_t)i * C + c] * Kr[(size_t)j * C + c];
+            Ar[(size_t)i * R + j] = acc;
         }
+    macs[1] += (int64_t)R * R * C;
+    if (Ar_out) memcpy(Ar_out, Ar, sizeof(REAL) * (size_t)R * R);
 
-    /* region-level queries and keys: per-region average over the n tokens. */
-    for (int r = 0; r < R; ++r)
-        for (int c = 0; c < C; ++c) {
-            REAL sq = 0, sk = 0;
-            for (int s = 0; s < n; ++s) {
-                sq += q[((size_t)r * n + s) * C + c];
-                sk += kk[((size_t)r * n + s) * C + c];
-            }
-            q_r[(size_t)r * C + c] = sq / (REAL)n;
-            k_r[(size_t)r * C + c] = sk / (REAL)n;
-        }
-
-    /* region affinity graph A^r = Q^r (K^r)^T (Eq. 4). */
-    for (int r = 0; r < R; ++r)
-        for (int c = 0; c < C; ++c)
-            k_rT[(size_t)c * R + r] = k_r[(size_t)r * C + c];
-    macs[1] += FN(matmul_)(q_r, k_rT, A_r, R, C, R);
-    if (Ar_out) memcpy(Ar_out, A_r, sizeof(REAL) * (size_t)R * R);
-
-    /* routing index (Eq. 5), or the caller's forced routing. */
+    /* Eq. 5, or the caller's forced routing. */
     if (Ir_in)
-        memcpy(I_r, Ir_in, sizeof(int32_t) * (size_t)R * k);
+        memcpy(Ir, Ir_in, sizeof(int32_t) * (size_t)R * k);
     else
-        FN(topk_index_)(A_r, I_r, R, k);
-    if (Ir_out) memcpy(Ir_out, I_r, sizeof(int32_t) * (size_t)R * k);
+        FN(routing_index_)(Ar, Ir, R, k);
+    if (Ir_out) memcpy(Ir_out, Ir, sizeof(int32_t) * (size_t)R * k);
 
-    /* gather the key/value tokens of the routed regions (Eq. 6):
-     * K^g[i] = concat_p K[I^r[i, p]]  ->  (S^2, k n, C). */
-    for (int i = 0; i < R; ++i)
-        for (int p = 0; p < k; ++p) {
-            int j = I_r[(size_t)i * k + p];
-            memcpy(k_g + ((size_t)i * kn + (size_t)p * n) * C, kk + (size_t)j * n * C,
-                   sizeof(REAL) * (size_t)n * C);
-            memcpy(v_g + ((size_t)i * kn + (size_t)p * n) * C, v + (size_t)j * n * C,
-                   sizeof(REAL) * (size_t)n * C);
-        }
-
-    /* token-to-token attention (Eq. 7 with Eq. 1 per head, heads = channel chunks
-     * of width d as in Eq. 2): one softmax over all k n gathered keys. */
-    for (int i = 0; i < R; ++i)
-        for (int hd = 0; hd < heads; ++hd)
-            for (int s = 0; s < n; ++s) {
-                const REAL *qv = q + ((size_t)i * n + s) * C + (size_t)hd * d;
-                REAL mx = 0;
+    /* Eq. 6-7 with Eq. 1 per head (Eq. 2): the query token (y, x) of region i attends to every
+     * token of the regions I^r[i, 0..k): one softmax over that whole set, then the weighted sum
+     * of their values.  The set is listed region by region in the order of row i, tokens of a
+     * region in row-major order (the order only fixes where a weight lands in P_out). */
+    for (int y = 0; y < H; ++y)
+        for (int x = 0; x < W; ++x) {
+            const int t = y * W + x;
+            const int i = (y / rh) * S + x / rw;
+            int cnt = 0;
+            for (int p = 0; p < k; ++p) {
+                const int j = Ir[(size_t)i * k + p], jy = j / S, jx = j % S;
+                for (int sy = 0; sy < rh; ++sy)
+                    for (int sx = 0; sx < rw; ++sx) keys[cnt++] = (jy * rh + sy) * W + jx * rw + sx;
+            }
+            for (int hd = 0; hd < heads; ++hd) {
+                const REAL *q = Q + (size_t)t * C + (size_t)hd * d;
+                REAL top = 0;
                 for (int u = 0; u < kn; ++u) {
-                    const REAL *kv = k_g + ((size_t)i * kn + u) * C + (size_t)hd * d;
-                    REAL acc = 0;
-                    for (int c = 0; c < d; ++c) acc += qv[c] * kv[c];
-                    att[u] = acc * scale;
-                    if (u == 0 || att[u] > mx) mx = att[u];
+                    const REAL *kv = K + (size_t)keys[u] * C + (size_t)hd * d;
+                    REAL dot = 0;
+                    for (int c = 0; c < d; ++c) dot += q[c] * kv[c];
+                    w[u] = dot * scale;
+                    if (u == 0 || w[u] > top) top = w[u];
                 }
-                macs[2] += (int64_t)kn * d;
                 REAL den = 0;
                 for (int u = 0; u < kn; ++u) {
-                    att[u] = (REAL)exp((double)(att[u] - mx));
-                    den += att[u];
+                    w[u] = (REAL)exp((double)(w[u] - top));
+                    den += w[u];
                 }
-                for (int u = 0; u < kn; ++u) att[u] /= den;
-                if (P_out)
-                    memcpy(P_out + (((size_t)hd * R + i) * n + s) * kn, att, sizeof(REAL) * kn);
-                REAL *ov = out_r + ((size_t)i * n + s) * C + (size_t)hd * d;
+                for (int u = 0; u < kn; ++u) w[u] /= den;
+                if (P_out) {
+                    const int slot = (y % rh) * rw + x % rw;
+                    memcpy(P_out + (((size_t)hd * R + i) * n + slot) * kn, w, sizeof(REAL) * kn);
+                }
                 for (int c = 0; c < d; ++c) {
                     REAL acc = 0;
-                    for (int u = 0; u < kn; ++u)
-                        acc += att[u] * v_g[((size_t)i * kn + u) * C + (size_t)hd * d + c];
-                    ov[c] = acc;
+                    for (int u = 0; u < kn; ++u) acc += w[u] * V[(size_t)keys[u] * C + (size_t)hd * d + c];
+                    O[(size_t)t * C + (size_t)hd * d + c] = acc;
                 }
-                macs[2] += (int64_t)kn * d;
+                macs[2] += (int64_t)2 * kn * d;
             }
-    if (Oatt_out) FN(unpatchify_)(out_r, Oatt_out, H, W, C, S);
+        }
+    if (Oatt_out) memcpy(Oatt_out, O, sizeof(REAL) * NC);
 
-    /* local context enhancement: 5x5 depth-wise convolution of V on the image. */
-    FN(unpatchify_)(v, v_map, H, W, C, S);
+    /* LCE(V) of Eq. 7: 5x5 depth-wise correlation of V over the map, zero outside it. */
     for (int y = 0; y < H; ++y)
         for (int x = 0; x < W; ++x)
             for (int c = 0; c < C; ++c) {
                 REAL acc = 0;
                 for (int ky = 0; ky < 5; ++ky)
                     for (int kx = 0; kx < 5; ++kx) {
-                        int yy = y + ky - 2, xx = x + kx - 2;
+                        const int yy = y + ky - 2, xx = x + kx - 2;
                         if (yy < 0 || yy >= H || xx < 0 || xx >= W) continue;
-                        acc += Wlce[((size_t)c * 5 + ky) * 5 + kx] *
-                               v_map[((size_t)yy * W + xx) * C + c];
+                        acc += Wlce[((size_t)c * 5 + ky) * 5 + kx] * V[((size_t)yy * W + xx) * C + c];
                     }
-                lce_map[((size_t)y * W + x) * C + c] = acc;
+                if (Lce_out) Lce_out[((size_t)y * W + x) * C + c] = acc;
+                O[((size_t)y * W + x) * C + c] += acc;
             }
-    if (Lce_out) memcpy(Lce_out, lce_map, sizeof(REAL) * NC);
 
-    /* output = attention + dwconv(value), in region layout, then back to (H, W, C). */
-    FN(patchify_)(lce_map, lce_r, H, W, C, S);
-    for (size_t e = 0; e < NC; ++e) out_r[e] += lce_r[e];
-    FN(unpatchify_)(out_r, o_map, H, W, C, S);
+    /* Eq. 2: the heads' outputs side by side, times W^o. */
+    FN(project_)(O, Wo, C, 0, Y, N, C);
 
-    /* output projection W^o composing the heads (Eq. 2). */
-    FN(matmul_)(o_map, Wo, Y, N, C, C);
-
-    free(xr); free(qkv); free(q); free(kk); free(v); free(q_r); free(k_r); free(k_rT);
-    free(A_r); free(I_r); free(k_g); free(v_g); free(att); free(out_r); free(v_map);
-    free(lce_map); free(lce_r); free(o_map);
+    free(Q); free(K); free(V); free(Qr); free(Kr); free(Ar); free(Ir); free(keys); free(w); free(O);
 }
 
 /* Batched entry: images are independent (routing is per image).  `threads` > 1
