@@ -17,9 +17,10 @@ LayerNorm normalises each token over its C channels (biased variance, eps inside
 square root, affine gamma/beta); GELU is the exact form x Phi(x).
 
 Every step is plain numpy on float64 arrays; BRA is the C oracle called in float64.
-`store` names the storage type of the tensor that enters BRA ("bf16" rounds
-LayerNorm1's output to bf16, as a path that keeps its tensors in bf16 hands it over:
-the routing decision of Eq. 5 is then taken on the same values on both sides).
+`store="bf16"` rounds the tensor that enters BRA to bf16.  It exists for ONE purpose: a
+path that stores that tensor in bf16 takes the routing decision of Eq. 5 on the rounded
+values, so the affinities its index is judged against must come from the same values.
+Outputs are always compared against the default, `store="f64"` (no rounding anywhere).
 
 Pins: tests/test_oracle_block.py (library convolution / layer norm / GELU in float64,
 brute-force loops on tiny inputs, closed-form values, structural special cases).

@@ -595,7 +595,7 @@ int launch_mlp_stream(const Dims &D, int hidden, const bf16_t *X1, const bf16_t 
 // C = 64 .. 256 with any hidden that fits the LDS budget takes the block-streaming kernel.
 bool mlp_stream_shape(const Dims &D, int hidden)
 {
-    static const bool off = getenv("BRA_BLOCK_UNFUSED") != nullptr;
+    static const bool off = experiment_flag("BRA_BLOCK_UNFUSED");
     if (off || D.C % 64 || D.C > 256 || hidden % 64) return false;
     const size_t fixed[5] = {0, MlpStreamSmem<1>::v_off, MlpStreamSmem<2>::v_off, MlpStreamSmem<3>::v_off,
                              MlpStreamSmem<4>::v_off};
@@ -605,7 +605,7 @@ bool mlp_stream_shape(const Dims &D, int hidden)
 // The single-kernel MLP half exists for C = 64 and hidden = 64, 128, 192 or 256.
 bool mlp_fused_shape(const Dims &D, int hidden)
 {
-    static const bool off = getenv("BRA_BLOCK_UNFUSED") != nullptr;
+    static const bool off = experiment_flag("BRA_BLOCK_UNFUSED");
     return !off && D.C == 64 && hidden % 64 == 0 && hidden <= 256;
 }
 
@@ -637,7 +637,7 @@ int launch_token_ln(const Dims &D, const bf16_t *A, const bf16_t *Badd, const br
     const int G = g_one ? g_one : lanes_per_token(D.C), slots = 256 / G;
     const bool one = D.C / 8 <= G;
     // enough workgroups to fill the chip several times over, up to 8 token groups each
-    static const long target = getenv("BRA_LN_WGS") ? atol(getenv("BRA_LN_WGS")) : 2048;
+    static const long target = experiment_value("BRA_LN_WGS", 2048);
     long iters = tokens / ((long)slots * target);
     iters = iters < 1 ? 1 : (iters > 8 ? 8 : iters);
     const long grid = ((tokens + slots * iters - 1) / (slots * iters) + 7) / 8 * 8;      // whole rounds over the XCDs
@@ -683,7 +683,7 @@ BlockWs carve_block(const Dims &D, int hidden, size_t bra_bytes, void *ws)
 // everything else runs on the scalar kernels.
 static bool block_fast(const Dims &D, int hidden)
 {
-    static const bool off = getenv("BRA_BLOCK_GENERIC") != nullptr;
+    static const bool off = experiment_flag("BRA_BLOCK_GENERIC");
     return !off && D.dtype == BRA_BF16 && D.C % 64 == 0 && D.C <= 4096 && hidden % 64 == 0 && hidden <= (1 << 16);
 }
 

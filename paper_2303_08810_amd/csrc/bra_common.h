@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "../../include/bra.h"
 
@@ -62,6 +63,20 @@ __device__ __forceinline__ float gelu_f32(float t)
 }
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Switches for A/B measurements.  The shipped library is built without BRA_EXPERIMENT: the
+// switches are then compile-time constants and nothing is read from the environment.
+#ifdef BRA_EXPERIMENT
+inline long experiment_value(const char *name, long dflt)
+{
+    const char *v = getenv(name);
+    return v ? atol(v) : dflt;
+}
+inline bool experiment_flag(const char *name) { return getenv(name) != nullptr; }
+#else
+constexpr long experiment_value(const char *, long dflt) { return dflt; }
+constexpr bool experiment_flag(const char *) { return false; }
+#endif
 
 // A routing index as the kernels use it: entries of a caller-supplied index outside
 // [0, R) (never produced by the library) are clamped instead of addressing outside the map.

@@ -1141,7 +1141,7 @@ int halo_rows(const Dims &D)
 // The fused pipeline pays one extra K/V projection per routed key block.
 bool fused_ok(const Dims &D)
 {
-    static const bool disabled = getenv("BRA_DISABLE_FUSED") != nullptr;   // benchmarking aid
+    static const bool disabled = experiment_flag("BRA_DISABLE_FUSED");
     if (disabled || !fast_route_ok(D)) return false;
     if (D.C != 64) return false;
     return D.n == 64 && D.k == 1 && (D.rw == 8 || D.rw == 16);
@@ -1171,7 +1171,7 @@ MfmaWs carve(const Dims &D, void *ws)
     char *p = (char *)ws;
     size_t off = 0;
     auto take = [&](size_t bytes) { char *q = p ? p + off : nullptr; off += align256(bytes); return q; };
-    const size_t tok = (size_t)D.B * D.N;
+    const size_t tok = fused_ok(D) ? 0 : (size_t)D.B * D.N;     // the k = 1 kernel projects inside the workgroup
     w.q = (bf16_t *)take(tok * D.C * 2);
     w.k = (bf16_t *)take(tok * D.C * 2);
     w.v = (bf16_t *)take(tok * D.C * 2);
@@ -1205,7 +1205,7 @@ bool lds_opt_in(K kernel, bool &done)
 // (region, 8-channel chunk) pairs, and enough workgroups to fill the chip.
 int pool_group(const Dims &D)
 {
-    static const int forced = getenv("BRA_POOL_GROUP") ? atoi(getenv("BRA_POOL_GROUP")) : 0;   // benchmarking aid
+    static const int forced = (int)experiment_value("BRA_POOL_GROUP", 0);
     if (forced >= 1 && forced <= kPoolMaxGroup && forced * (D.C / 8) <= 256) return forced;
     const int chunks = D.n * (D.C / 8);
     int G = 2048 / chunks;
@@ -1248,7 +1248,7 @@ int launch_route_p(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, h
     // 8 query regions per workgroup (2 per wavefront) where two workgroups fit a compute unit
     // (the K^r tile takes C x 260 bytes of LDS): twice the workgroups, half the serial affinity /
     // top-k work in each.  Measured: C = 128 12.6 -> 10.8 us, C = 256 (one per unit) 17.3 -> 22.1 us.
-    static const int forced = getenv("BRA_ROUTE_ROWS") ? atoi(getenv("BRA_ROUTE_ROWS")) : 0;   // benchmarking aid
+    static const int forced = (int)experiment_value("BRA_ROUTE_ROWS", 0);
     const bool rows8 = forced ? forced == 8 : 2 * RouteSmem<C>::kq_bytes <= (size_t)kMaxLds;
     ProfScope ps(st, K_MFMA_ROUTE_ROWS);
     if (rows8) {
@@ -1278,7 +1278,7 @@ int launch_qkv(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const MfmaWs 
     // registers and the workgroup streams its share of the tokens
     const int gy = 3 * C / 64 / WPB;
     long tpw = (ntiles * gy + 255) / 256;
-    static const int forced = getenv("BRA_QKV_TPW") ? atoi(getenv("BRA_QKV_TPW")) : 0;       // benchmarking aid
+    static const int forced = (int)experiment_value("BRA_QKV_TPW", 0);
     if (forced >= 1 && forced <= 4096) tpw = forced;
     const int gx = (int)((ntiles + tpw - 1) / tpw);
     const int prep_blocks = (prep.elems + 64 * WPB - 1) / (64 * WPB);
@@ -1336,7 +1336,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     } else {
         // pool X and route before the rest, with the weight rearrangement in the same launch;
         // the pooled-projection pipelines need neither and rearrange next to the projection
-        static const bool route_launch = getenv("BRA_FUSED_ROUTE_LAUNCH") != nullptr;   // benchmarking aid
+        static const bool route_launch = experiment_flag("BRA_FUSED_ROUTE_LAUNCH");
         const bool inline_route = fused && !route_launch;     // the k = 1 kernel routes by itself, from the routing vectors
         const bool from_x = (fused || !pooled_projection(D)) && !Ir_in_opt;
         if (fused || from_x)
@@ -1391,8 +1391,8 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
         const size_t smem = AttnSmem<C>::bytes(hrows);
         ProfScope ps(st, K_MFMA_ATTENTION);
         if constexpr (C == 64) {
-            // few workgroups: twice the wavefronts each (benchmarking aid: BRA_ATTN_WAVES=4 / 8 forces)
-            static const int forced = getenv("BRA_ATTN_WAVES") ? atoi(getenv("BRA_ATTN_WAVES")) : 0;
+            // few workgroups: twice the wavefronts each
+            static const int forced = (int)experiment_value("BRA_ATTN_WAVES", 0);
             if (forced == 8 || (forced != 4 && A.total < 1024)) {
                 static bool opted8 = false;
                 if (!lds_opt_in(k_attn_big<64, 2>, opted8)) return BRA_ERR_LAUNCH;
@@ -1449,7 +1449,7 @@ bool attn_big_ok(const Dims &D)
 // Shapes of the kernels specialised by channel count.
 static bool specialised(const Dims &D)
 {
-    static const bool general_only = getenv("BRA_GENERAL_PIPELINE") != nullptr;   // benchmarking aid
+    static const bool general_only = experiment_flag("BRA_GENERAL_PIPELINE");
     if (general_only) return false;
     if (D.dtype != BRA_BF16 || D.d != 32) return false;
     if (D.C != 64 && D.C != 128 && D.C != 256) return false;
@@ -1460,7 +1460,14 @@ static bool specialised(const Dims &D)
 
 bool wide_shape(const Dims &D) { return !specialised(D); }
 
-bool mfma_supported(const Dims &D) { return specialised(D) || wide_supported(D); }
+// The matrix-core kernels address a token's channels within its image by 32-bit element
+// offsets and divide key / slot numbers with fast_div (exact below 2^20).
+static bool addressable(const Dims &D)
+{
+    return (long)D.N * D.C < (1L << 31) && D.n < (1 << 20) && (long)D.kn < (1L << 20);
+}
+
+bool mfma_supported(const Dims &D) { return addressable(D) && (specialised(D) || wide_supported(D)); }
 
 size_t mfma_workspace_bytes(const Dims &D)
 {

@@ -743,7 +743,7 @@ static bool map_attention(const Dims &D) { return map_smem(D) <= (size_t)kMaxLds
 // Parts per (image, head), so that small batches still fill the chip.
 static int map_split(const Dims &D)
 {
-    static const int forced = getenv("BRA_MAP_WGS") ? atoi(getenv("BRA_MAP_WGS")) : 0;   // benchmarking aid
+    static const int forced = (int)experiment_value("BRA_MAP_WGS", 0);
     const int target = forced >= 1 && forced <= 65536 ? forced : 512;
     const int wgs = D.B * (D.C / 32);
     const int split = (target + wgs - 1) / wgs;

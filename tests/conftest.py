@@ -12,9 +12,15 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def _asks_for_gpu(config) -> bool:
+    """True when the -m expression selects the gpu marker itself (not its negation)."""
+    expr = (config.getoption("-m") or "").strip()
+    return "gpu" in expr and "not gpu" not in expr
+
+
 def pytest_collection_modifyitems(config, items):
-    # GPU tests are skipped (not failed) when no device is present and the run did
-    # not ask for them explicitly with -m gpu.
+    # Without a device, GPU tests of an unfiltered run are skipped; a run that asked for
+    # them with -m gpu fails instead: a box whose GPU did not come up must not read as green.
     try:
         import torch
         has_gpu = torch.cuda.is_available()
@@ -22,6 +28,8 @@ def pytest_collection_modifyitems(config, items):
         has_gpu = False
     if has_gpu:
         return
+    if _asks_for_gpu(config) and any("gpu" in item.keywords for item in items):
+        pytest.exit("-m gpu was requested but torch.cuda.is_available() is False", returncode=3)
     skip = pytest.mark.skip(reason="no GPU in this process")
     for item in items:
         if "gpu" in item.keywords:

@@ -8,6 +8,8 @@ from synthetic_inputs import bf16_bits, bits_to_f32
 GAP = 1e-3          # affinity gap above which routing indices must match bit for bit
 TOL_F32_ABS = 1e-4  # max-abs bound on Y for float32 tensors
 TOL_BF16_REL = 2e-2 # bound on max|dY| / max|Y_ref| for bf16 tensors
+TOL_BF16_RMS = 8e-3 # bound on rms(dY) / rms(Y_ref) for bf16 tensors
+TOL_BF16_FRAC = 0.999   # share of elements with |dY| <= 2e-2 |Y_ref| + 2e-2 rms(Y_ref), at least
 
 
 def to_device(a, dtype):
@@ -62,10 +64,23 @@ def run_oracle(X, Wqkv, Wo, Wlce, cfgkw, Ir_in=None, threads=8, precision="f64",
 
 
 def check_output(Y_gpu, Y_ref, dtype):
-    err = float(np.abs(Y_gpu.astype(np.float64) - Y_ref).max())
+    """float32 tensors: max-abs bound.  bf16 tensors: three bounds.  The maximum norm is the stated
+    bar; the rms bound and the element-wise share catch what it lets through (a localised defect
+    of up to 2 % of max|Y|: one wrong tap at an image border, one mis-weighted key).  The bf16
+    roundings of the stored intermediates and of Y are independent errors of relative size 2^-9,
+    which puts the rms error at 3-4e-3 of rms(Y); 8e-3 leaves a factor of two."""
+    d = Y_gpu.astype(np.float64) - Y_ref
+    err = float(np.abs(d).max())
     if dtype == "f32":
         assert err <= TOL_F32_ABS, f"max-abs error {err:.3e} > {TOL_F32_ABS}"
-    else:
-        rel = err / float(np.abs(Y_ref).max())
-        assert rel <= TOL_BF16_REL, f"max|dY|/max|Y| = {rel:.3e} > {TOL_BF16_REL}"
+        return err
+    rel = err / float(np.abs(Y_ref).max())
+    assert rel <= TOL_BF16_REL, f"max|dY|/max|Y| = {rel:.3e} > {TOL_BF16_REL}"
+    ref_rms = float(np.sqrt(np.mean(Y_ref ** 2)))
+    if ref_rms > 0:
+        rms = float(np.sqrt(np.mean(d ** 2))) / ref_rms
+        frac = float(np.mean(np.abs(d) <= 2e-2 * np.abs(Y_ref) + 2e-2 * ref_rms))
+        print(f"  rms(dY)/rms(Y) = {rms:.3e}; share within 2e-2|Y| + 2e-2 rms(Y): {frac:.6f}", flush=True)
+        assert rms <= TOL_BF16_RMS, f"rms(dY)/rms(Y) = {rms:.3e} > {TOL_BF16_RMS}"
+        assert frac >= TOL_BF16_FRAC, f"only {frac:.6f} of the elements within 2e-2|Y| + 2e-2 rms(Y)"
     return err

@@ -10,7 +10,7 @@ import torch
 import paper_2303_08810_amd as bra
 from oracle import backward as obw
 from parity_util import to_device, to_numpy
-from synthetic_inputs import make_inputs, round_to_bf16
+from synthetic_inputs import CONFIGS, make_config_inputs, make_inputs, round_to_bf16
 
 pytestmark = pytest.mark.gpu
 
@@ -28,8 +28,13 @@ SHAPES = [
 
 @pytest.mark.parametrize("dtype,B,H,W,C,heads,S,k", SHAPES)
 def test_backward(dtype, B, H, W, C, heads, S, k):
-    print(f"backward case dtype={dtype} shape={(B, H, W, C)} heads={heads} S={S} k={k}", flush=True)
     Xn, Wqkvn, Won, Wlcen = make_inputs(B, H, W, C, seed=6000 + H * W + C + k, dtype=dtype)
+    compare_backward(Xn, Wqkvn, Won, Wlcen, dtype, heads, S, k)
+
+
+def compare_backward(Xn, Wqkvn, Won, Wlcen, dtype, heads, S, k):
+    B, H, W, C = Xn.shape
+    print(f"backward case dtype={dtype} shape={(B, H, W, C)} heads={heads} S={S} k={k}", flush=True)
     r = np.random.Generator(np.random.PCG64(6001 + C))
     dYn = r.standard_normal(Xn.shape).astype(np.float32)
     if dtype == "bf16":
@@ -68,6 +73,14 @@ def random_backward_shapes(count, seed):
 @pytest.mark.parametrize("dtype,B,H,W,C,heads,S,k", random_backward_shapes(12, seed=20230311))
 def test_backward_random_shapes(dtype, B, H, W, C, heads, S, k):
     test_backward(dtype, B, H, W, C, heads, S, k)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_backward_named_workloads_full_size(idx):
+    # the five named workloads at their full sizes (random routing index, given to both sides)
+    cfg = CONFIGS[idx]
+    Xn, Wqkvn, Won, Wlcen = make_config_inputs(cfg)
+    compare_backward(Xn, Wqkvn, Won, Wlcen, cfg.dtype, cfg.heads, cfg.S, cfg.k)
 
 
 def test_backward_after_forward_uses_its_routing():

@@ -1,11 +1,12 @@
 """GPU parity of the whole-block entry point (bra_block_forward, through the C ABI) against
 the float64 block oracle on the same seeded inputs.
 
-Bars: the routing index obeys parity_util.check_routing against the oracle's affinities
-(computed, like the kernel's, from LayerNorm1's output rounded to bf16); with the GPU's routing
-given to the oracle, the block's update Xout - X is within 2e-2 of max|Xout_ref - X| (the bf16
-bar, taken on the update so that the residual copy of X cannot hide an error in a branch), and its
-rms error within 8e-3 of the update's rms.
+Bars: the routing index obeys parity_util.check_routing against the affinities of an oracle run
+whose BRA input is LayerNorm1's output rounded to bf16 (the decision of Eq. 5 is taken on the
+stored tensor; that run serves the routing comparison only); with the GPU's routing given to the
+plain float64 oracle (no rounding anywhere), the block's update Xout - X is within 2e-2 of
+max|Xout_ref - X| (the bf16 bar, taken on the update so that the residual copy of X cannot hide
+an error in a branch), and its rms error within 8e-3 of the update's rms.
 """
 import numpy as np
 import pytest
@@ -43,13 +44,13 @@ def compare_block(Xn, P, S, k, heads, path="auto", images=None, in_place=False, 
     torch.cuda.synchronize()
     got, Ir = to_numpy(Xout), Ir.cpu().numpy()
     sel = np.arange(Xn.shape[0]) if images is None else np.asarray(images)
-    kw = dict(S=S, k=k, heads=heads, eps=EPS, store="bf16" if dtype == "bf16" else "f64", threads=8)
+    kw = dict(S=S, k=k, heads=heads, eps=EPS, threads=8)
     if forced is None:
-        free = ob.block_forward(Xn[sel], P, **kw)
+        free = ob.block_forward(Xn[sel], P, store="bf16" if dtype == "bf16" else "f64", **kw)
         check_routing(Ir[sel], free["Ar"], k)
     else:
         np.testing.assert_array_equal(Ir, forced)
-    ref = ob.block_forward(Xn[sel], P, Ir_in=Ir[sel], **kw)
+    ref = ob.block_forward(Xn[sel], P, Ir_in=Ir[sel], store="f64", **kw)
     if dtype == "f32":
         # float32 tensors: the bar of the float32 BRA path, max-abs 1e-4, on the block's output
         err = float(np.abs(got[sel].astype(np.float64) - ref["Xout"]).max())
@@ -181,8 +182,8 @@ def test_block_repeated_runs_are_bit_identical():
         np.testing.assert_array_equal(o, outs[0])
 
 
-@pytest.mark.parametrize("idx,images", [(2, [0, 31, 63]), (3, [0, 63]), (4, [5, 63]), (6, [0, 1, 62, 63]),
-                                        (8, [7])])
+@pytest.mark.parametrize("idx,images", [(2, [0, 31, 63]), (3, [0, 63]), (4, [5, 63]), (5, [1]),
+                                        (6, [0, 1, 62, 63]), (8, [7])])
 def test_block_named_workloads_full_size(idx, images):
     cfg = CONFIGS.get(idx) or NEXT_CONFIGS[idx]
     X, P = make_block_inputs(cfg)

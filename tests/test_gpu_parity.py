@@ -216,15 +216,12 @@ def test_forced_self_routing_is_window_attention():
 
 
 # The five named workloads at their full sizes, in the launch configuration that
-# bench.py times (path "auto"); the oracle checks a sample of whole images.
-FULL = {1: None, 2: [0, 31, 63], 3: [0, 17, 63], 4: [0, 1, 40, 63], 5: [1]}
-
-
+# bench.py times (path "auto"); the oracle checks every image.
 @pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
 def test_named_workloads_full_size(idx):
     cfg = CONFIGS[idx]
     X, Wqkv, Wo, Wlce = make_config_inputs(cfg)
-    compare(X, Wqkv, Wo, Wlce, cfg.dtype, cfg.S, cfg.k, cfg.heads, "auto", images=FULL[idx])
+    compare(X, Wqkv, Wo, Wlce, cfg.dtype, cfg.S, cfg.k, cfg.heads, "auto")
 
 
 @pytest.mark.parametrize("idx,images", [(6, [0, 33, 63]), (7, [5, 63]), (8, [7]), (9, [1])])
@@ -250,12 +247,15 @@ def test_named_workloads_smooth_inputs(idx):
     compare(X, Wqkv, Wo, Wlce, cfg.dtype, cfg.S, cfg.k, cfg.heads, "auto")
 
 
-def test_repeated_runs_are_bit_identical():
-    cfg = CONFIGS[3]
-    Xn, Wqkvn, Won, Wlcen = make_config_inputs(cfg, batch=4)
+@pytest.mark.parametrize("idx,batch", [(2, 8), (3, 4), (4, 4), (5, 2)])
+def test_repeated_runs_are_bit_identical(idx, batch):
+    # every specialised pipeline (k = 1 fused, 16-token regions, image-resident attention, 256-token
+    # regions): LDS races or an order-dependent reduction would show as differing bits
+    cfg = CONFIGS[idx]
+    Xn, Wqkvn, Won, Wlcen = make_config_inputs(cfg, batch=batch)
     X, Wqkv, Wo, Wlce = (to_device(a, cfg.dtype) for a in (Xn, Wqkvn, Won, Wlcen))
     outs = []
-    for _ in range(5):
+    for _ in range(20):
         Y, Ir = bra.bra_forward(X, Wqkv, Wo, Wlce, cfg.S, cfg.k, cfg.heads, want_Ir=True)
         torch.cuda.synchronize()
         outs.append((Y.view(torch.int16).cpu().numpy().copy(), Ir.cpu().numpy().copy()))
