@@ -67,7 +67,8 @@ enum {
     BRA_ERR_DTYPE = -4,       /* dtype or path is not one of the enums above */
     BRA_ERR_WORKSPACE = -5,   /* ws is NULL, misaligned (256 B) or too small */
     BRA_ERR_UNSUPPORTED = -6, /* valid shape outside what the kernels are built for */
-    BRA_ERR_LAUNCH = -7       /* the HIP runtime reported an error at enqueue time */
+    BRA_ERR_LAUNCH = -7,      /* the HIP runtime reported an error at enqueue time */
+    BRA_ERR_TOO_LARGE = -8    /* bra_forward_static: the shape needs more than BRA_STATIC_SCRATCH_BYTES */
 };
 
 typedef struct bra_shape {
@@ -100,6 +101,24 @@ int bra_route(const bra_shape *shape, const void *X, const void *Wqkv, int32_t *
 int bra_forward(const bra_shape *shape, const void *X, const void *Wqkv, const void *Wo,
                 const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
                 void *ws, size_t ws_bytes, void *hip_stream);
+
+/* bra_forward for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same
+ * arguments and results as bra_forward (bit for bit: the same kernels run), but the scratch
+ * memory is a buffer of BRA_STATIC_SCRATCH_BYTES inside the library's code object; every GPU the
+ * library runs on holds one such buffer from the time the library is loaded there until the
+ * process ends.  The call allocates and frees nothing.  The first call on each device looks up
+ * the buffer's address (hipGetSymbolAddress; no allocation, but not to be captured into a
+ * graph); later calls only enqueue kernels.  Shapes whose workspace (bra_workspace_bytes)
+ * exceeds the buffer are rejected with BRA_ERR_TOO_LARGE before anything is enqueued; the
+ * other errors are those of bra_forward.  The buffer keeps the previous call's contents (no
+ * kernel of the forward pass needs it zeroed).  All calls on one GPU share it: calls that may
+ * overlap on that GPU (different streams, or one stream from several threads) race; order them
+ * on one stream. */
+#define BRA_STATIC_SCRATCH_BYTES (32u << 20)
+int bra_forward_static(const bra_shape *shape, const void *X, const void *Wqkv, const void *Wo,
+                       const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
+                       void *hip_stream);
 
 /* BRA on a map whose sides S does not divide (appendix on the choice of S and k: S is picked
  * as a divisor of the training size so that no padding is needed; other sizes are padded).

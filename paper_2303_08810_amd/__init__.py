@@ -18,7 +18,9 @@ BRA_F32, BRA_BF16 = 0, 1
 PATH_AUTO, PATH_GENERIC, PATH_MFMA = 0, 1, 2
 _PATHS = {"auto": PATH_AUTO, "generic": PATH_GENERIC, "mfma": PATH_MFMA}
 
-EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_padded_workspace_bytes",
+STATIC_SCRATCH_BYTES = 32 << 20
+
+EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_forward_static", "bra_padded_workspace_bytes",
            "bra_forward_padded", "bra_backward_workspace_bytes", "bra_backward", "bra_block_workspace_bytes",
            "bra_block_forward", "bra_strerror", "bra_version",
            "bra_profile_begin", "bra_profile_end", "bra_kernel_name", "bra_util_copy",
@@ -63,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.bra_route.argtypes = [ctypes.POINTER(BraShape), vp, vp, vp, vp, vp, sz, vp]
         L.bra_forward.restype = ctypes.c_int
         L.bra_forward.argtypes = [ctypes.POINTER(BraShape), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.bra_forward_static.restype = ctypes.c_int
+        L.bra_forward_static.argtypes = [ctypes.POINTER(BraShape), vp, vp, vp, vp, vp, vp, vp, vp]
         L.bra_padded_workspace_bytes.restype = ctypes.c_int
         L.bra_padded_workspace_bytes.argtypes = [ctypes.POINTER(BraShape), ctypes.POINTER(sz)]
         L.bra_forward_padded.restype = ctypes.c_int
@@ -177,6 +181,19 @@ def bra_forward(X, Wqkv, Wo, Wlce, S, k, heads, *, scale=None, Ir_in=None, want_
     _check(lib().bra_forward(ctypes.byref(shape), _ptr(X), _ptr(Wqkv), _ptr(Wo), _ptr(Wlce), _ptr(Y),
                              _ptr(Ir), _ptr(Ir_in), _ptr(ws), ws.numel(), _stream(X.device)))
     return (Y, Ir) if want_Ir else Y
+
+
+def bra_forward_static(X, Wqkv, Wo, Wlce, S, k, heads, *, out, Ir_out=None, Ir_in=None, scale=None, path="auto"):
+    """bra_forward on the library's built-in scratch buffer: nothing is allocated, here or in the
+    library.  `out` [B, H, W, C] and, if wanted, `Ir_out` [B, S*S, k] (int32) are the caller's."""
+    B, H, W, C = _check_inputs(X, Wqkv, Wo, Wlce)
+    shape = make_shape(B, H, W, C, heads, S, k, X.dtype, scale, path)
+    for t, shp, dt in ((out, (B, H, W, C), X.dtype), (Ir_out, (B, S * S, k), torch.int32), (Ir_in, (B, S * S, k), torch.int32)):
+        if t is not None and not (t.is_cuda and t.is_contiguous() and t.dtype == dt and tuple(t.shape) == shp):
+            raise ValueError(f"expected a contiguous {dt} device tensor of shape {shp}")
+    _check(lib().bra_forward_static(ctypes.byref(shape), _ptr(X), _ptr(Wqkv), _ptr(Wo), _ptr(Wlce), _ptr(out),
+                                    _ptr(Ir_out), _ptr(Ir_in), _stream(X.device)))
+    return out
 
 
 def bra_forward_padded(X, Wqkv, Wo, Wlce, S, k, heads, *, scale=None, Ir_in=None, want_Ir=False, path="auto"):

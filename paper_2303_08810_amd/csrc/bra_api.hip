@@ -3,7 +3,33 @@
 
 #include <math.h>
 
+#include <mutex>
+
+// Scratch memory of bra_forward_static: one copy per GPU, held by the code object until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// address that kernels, copies and fills take is the one that call returns for the current device.
+static __device__ __align__(256) unsigned char scratch[BRA_STATIC_SCRATCH_BYTES];
+
 namespace bra {
+
+// Device address of `scratch` on the current device, looked up once per device.
+static int static_scratch(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *ptrs[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BRA_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return BRA_ERR_LAUNCH;
+        if ((uintptr_t)p % 256 != 0) return BRA_ERR_LAUNCH;
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return BRA_OK;
+}
 
 // Validates `s` and fills D.  Returns a BRA_* code.
 static int make_dims(const bra_shape *s, Dims &D)
@@ -99,6 +125,29 @@ int bra_forward(const bra_shape *shape, const void *X, const void *Wqkv, const v
     size_t need = (path == BRA_PATH_MFMA) ? mfma_workspace_bytes(D) : generic_workspace_bytes(D);
     if (!ws_ok(ws, ws_bytes, need)) return BRA_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
+    if (path == BRA_PATH_MFMA)
+        return mfma_forward(D, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, st);
+    return generic_forward(D, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, st);
+}
+
+int bra_forward_static(const bra_shape *shape, const void *X, const void *Wqkv, const void *Wo,
+                       const void *Wlce, void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt,
+                       void *hip_stream)
+{
+    Dims D;
+    int rc = make_dims(shape, D);
+    if (rc != BRA_OK) return rc;
+    if (!X || !Wqkv || !Wo || !Wlce || !Y) return BRA_ERR_NULL;
+    int path = pick_path(shape, D);
+    if (path < 0) return path;
+    const size_t need = (path == BRA_PATH_MFMA) ? mfma_workspace_bytes(D) : generic_workspace_bytes(D);
+    if (need > (size_t)BRA_STATIC_SCRATCH_BYTES) return BRA_ERR_TOO_LARGE;
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != BRA_OK) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // no kernel of the forward pass expects zeroed scratch (no counters, no accumulation into it):
+    // every buffer carved from it is written before it is read within the call
     if (path == BRA_PATH_MFMA)
         return mfma_forward(D, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, st);
     return generic_forward(D, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, ws, st);
@@ -210,6 +259,7 @@ const char *bra_strerror(int code)
     case BRA_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";
     case BRA_ERR_UNSUPPORTED: return "shape not supported by the requested kernel family";
     case BRA_ERR_LAUNCH: return "HIP runtime error while enqueueing";
+    case BRA_ERR_TOO_LARGE: return "shape needs more scratch memory than the library's built-in buffer holds";
     default: return "unknown error code";
     }
 }

@@ -47,7 +47,7 @@ def test_workspace_query_and_error_codes():
     assert ws_bytes(dtype=7)[0] == -4
     assert ws_bytes(path="mfma")[0] == -6    # matrix-core kernels are bf16 only
     assert bra.lib().bra_workspace_bytes(None, None) == -1
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         assert bra.strerror(code) != "unknown error code"
     assert bra.strerror(-99) == "unknown error code"
 
@@ -70,6 +70,10 @@ def test_kernel_family_selection_by_shape():
     assert mfma(B=2, H=21, W=14, C=64, heads=2, S=7, k=2) == 0         # regions of 6 tokens
     assert mfma(B=2, H=14, W=14, C=96, heads=3, S=7, k=4) == -6        # C not a multiple of 64
     assert mfma(B=2, H=14, W=14, C=128, heads=8, S=7, k=4) == -6       # heads of 16 channels
+    # maps beyond the 32-bit element offsets / exact divisions of the matrix-core kernels
+    assert mfma(B=1, H=8192, W=8192, C=64, heads=2, S=8, k=1) == -6    # 2^32 elements per image
+    assert mfma(B=1, H=4096, W=4096, C=64, heads=2, S=2, k=1) == -6    # 2^22 tokens per region
+    assert mfma(B=1, H=2048, W=2048, C=64, heads=2, S=8, k=64) == -6   # 2^22 keys per query
     # every rejected shape still runs on the generic family
     for kw in (dict(H=14, W=14, C=96, heads=3, S=7, k=4), dict(H=14, W=14, C=128, heads=8, S=7, k=4)):
         rc, n = ws_bytes(dtype=bra.BRA_BF16, path="auto", B=2, **kw)
@@ -91,6 +95,21 @@ def test_entry_points_reject_bad_arguments_before_launching():
     bad = bra.make_shape(1, 28, 28, 64, 2, 7, 50, bra.BRA_F32)
     assert L.bra_forward(ctypes.byref(bad), fake, fake, fake, fake, fake, None, None, fake, 1 << 30, None) == -3
     assert L.bra_forward(None, fake, fake, fake, fake, fake, None, None, fake, 1 << 30, None) == -1
+
+
+def test_static_scratch_entry_point_rejects_before_launching():
+    L = bra.lib()
+    fake = ctypes.c_void_p(4096)
+    ok = bra.make_shape(1, 28, 28, 64, 2, 7, 4, bra.BRA_F32)
+    assert L.bra_forward_static(ctypes.byref(ok), None, fake, fake, fake, fake, None, None, None) == -1
+    assert L.bra_forward_static(None, fake, fake, fake, fake, fake, None, None, None) == -1
+    bad = bra.make_shape(1, 28, 28, 64, 2, 7, 50, bra.BRA_F32)
+    assert L.bra_forward_static(ctypes.byref(bad), fake, fake, fake, fake, fake, None, None, None) == -3
+    # a batch whose workspace exceeds the built-in buffer: refused, nothing enqueued
+    big = bra.make_shape(64, 28, 28, 128, 4, 7, 4, bra.BRA_BF16)
+    assert ws_bytes(B=64, C=128, heads=4, dtype=bra.BRA_BF16)[1] > bra.STATIC_SCRATCH_BYTES
+    assert L.bra_forward_static(ctypes.byref(big), fake, fake, fake, fake, fake, None, None, None) == -8
+    assert "scratch" in bra.strerror(-8)
 
 
 def test_block_and_padded_workspace_queries():
