@@ -561,7 +561,7 @@ template <int C, int WPB, int NMAT>
 __global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, 2)))
 void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *__restrict__ Q,
            bf16_t *__restrict__ K, bf16_t *__restrict__ V, float *__restrict__ P, int group_log2, long M,
-           int tiles_per_wg, int gx, PrepArgs prep)
+           int tiles_per_wg, int gx, PrepArgs prep, float qscale)
 {
     constexpr int KS = C / 32, CH = C / 8, XP = C + 16, NTH = 64 * WPB;
     constexpr int NL = (64 * CH + NTH - 1) / NTH;       // 16-byte chunks of a tile per thread
@@ -662,7 +662,10 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
                 for (int tt = 0; tt < 4; ++tt) acc[tt] = mfma16(af[tt][ks], bf[ks], acc[tt]);
             const long t = tile * 64 + 16 * u + i;
             if (t < M) {
-                u32x2 p0 = pack4(acc[0]), p1 = pack4(acc[1]), p2 = pack4(acc[2]), p3 = pack4(acc[3]);
+                // Q may leave multiplied by a factor (the attention kernel that wants its scores in
+                // units of log2 passes scale * log2 e): one rounding, of the scaled value
+                const float os = sel == 0 ? qscale : 1.0f;
+                u32x2 p0 = pack4(acc[0] * os), p1 = pack4(acc[1] * os), p2 = pack4(acc[2] * os), p3 = pack4(acc[3] * os);
                 u32x4 *dst = (u32x4 *)(out + t * C + base + 16 * g);
                 dst[0] = u32x4{p0[0], p0[1], p1[0], p1[1]};
                 dst[1] = u32x4{p2[0], p2[1], p3[0], p3[1]};
@@ -1269,7 +1272,7 @@ int launch_route_p(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, h
 // with prep.elems > 0, extra workgroups rearrange the weights for the kernels that follow.
 template <int C>
 int launch_qkv(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const MfmaWs &w, bool pooled,
-               const PrepArgs &prep, hipStream_t st)
+               const PrepArgs &prep, hipStream_t st, float qscale = 1.0f)
 {
     const long M = (long)D.B * D.N;
     constexpr int WPB = (C == 256) ? 4 : 3 * C / 64;      // wavefronts (64-channel groups) per workgroup
@@ -1287,7 +1290,7 @@ int launch_qkv(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const MfmaWs 
     if (!lds_opt_in(k_qkv<C, WPB, 3>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_QKV);
     hipLaunchKernelGGL((k_qkv<C, WPB, 3>), dim3(gx + prep_blocks, gy), dim3(64 * WPB), smem, st, X, Wqkv, w.q,
-                       w.k, w.v, pooled ? w.p : nullptr, pool_group_log2(D), M, (int)tpw, gx, prep);
+                       w.k, w.v, pooled ? w.p : nullptr, pool_group_log2(D), M, (int)tpw, gx, prep, qscale);
     return BRA_OK;
 }
 
@@ -1306,7 +1309,7 @@ int launch_wo(const Dims &D, const bf16_t *O, const bf16_t *Wo, bf16_t *Y, hipSt
     if (!lds_opt_in(k_qkv<C, WPB, 1>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_WO);
     hipLaunchKernelGGL((k_qkv<C, WPB, 1>), dim3(gx, 1), dim3(64 * WPB), smem, st, O, Wo, Y, Y, Y, nullptr, 0, M,
-                       (int)tpw, gx, PrepArgs{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0});
+                       (int)tpw, gx, PrepArgs{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0}, 1.0f);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
@@ -1348,10 +1351,13 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
         }
         prep_pending = !(fused || from_x);
     }
+    // the many-block attention kernel takes Q in units of log2 of the softmax weights
+    const bool q32 = !fused && attn_big_ok(D) && attn_q32_ok(D) && !experiment_flag("BRA_ATTN_OLD");
+    const float c_exp = D.scale * 1.4426950408889634f;
     if (!fused) {
         const bool pooled = pooled_projection(D) && !Ir_in_opt;
         const PrepArgs prep = {Wqkv, Wo, Wlce, w.wt, w.wot, w.wa, w.wf, prep_pending ? prep_total(C) : 0};
-        int rc = launch_qkv<C>(D, X, Wqkv, w, pooled, prep, st);
+        int rc = launch_qkv<C>(D, X, Wqkv, w, pooled, prep, st, q32 ? c_exp : 1.0f);
         if (rc != BRA_OK) return rc;
         if (pooled) {
             rc = launch_route_p<C>(D, w, Ir_dst, nullptr, st);
@@ -1363,7 +1369,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     A.X = X; A.WT = w.wt; A.Q = w.q; A.K = w.k; A.V = w.v;
     A.Ir_src = Ir_src; A.Ir_out = Ir_out_opt; A.Wlce = Wlce; A.Wa = w.wa; A.WoF = w.wa + kLceOperandElems * C; A.WlT = A.WoF + C * C; A.Wf = w.wf; A.WoT = w.wot; A.Y = Y;
     A.Xr = w.xr; A.U = w.u;
-    A.c_exp = D.scale * 1.4426950408889634f;
+    A.c_exp = c_exp;
     A.total = D.B * D.R * (D.n / 64);
     const int grid = ((A.total + 7) / 8) * 8;
     const int hrows = halo_rows(D);
@@ -1387,6 +1393,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
         if (rc != BRA_OK || !small_needs_projection(D)) return rc;
         return launch_wo<C>(D, w.o, Wo, Y, st);
     }
+    if (q32) return launch_attn_q32(D, A, st);
     {
         const size_t smem = AttnSmem<C>::bytes(hrows);
         ProfScope ps(st, K_MFMA_ATTENTION);

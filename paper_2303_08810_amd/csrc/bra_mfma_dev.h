@@ -611,6 +611,11 @@ bool map_tail_supported(const Dims &D);
 int launch_map_tail(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st);
 int launch_lce_add_any(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st);   // O += LCE(V), any map, C % 64 == 0
 
+// Attention + LCE + W^o for regions of 64 n tokens with 32 queries per wavefront
+// (bra_mfma_attn.hip); A.Q must hold Q multiplied by scale * log2(e).
+bool attn_q32_ok(const Dims &D);
+int launch_attn_q32(const Dims &D, const mfma::AttnArgs &A, hipStream_t st);
+
 // Pipeline for other channel counts (bra_mfma_wide.hip): any multiple of 64 with heads of 32
 // channels, at most 64 regions of 1, 2, 4 or 8 tokens.
 bool wide_shape(const Dims &D);          // not one of the specialised channel counts
