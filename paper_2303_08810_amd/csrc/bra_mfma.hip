@@ -1371,6 +1371,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     A.Xr = w.xr; A.U = w.u;
     A.c_exp = c_exp;
     A.total = D.B * D.R * (D.n / 64);
+    A.trace = experiment_flag("BRA_Q32_TRACE");
     const int grid = ((A.total + 7) / 8) * 8;
     const int hrows = halo_rows(D);
 

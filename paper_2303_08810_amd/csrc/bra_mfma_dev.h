@@ -587,6 +587,7 @@ struct AttnArgs {
     const float *Xr, *U;            // region means and routing vectors (fused kernel, Ir_src == NULL)
     float c_exp;                    // softmax scale * log2(e)
     int total;                      // workgroups that have work
+    int trace = 0;                  // experiment builds: leave phase timestamps in Y
 };
 
 // Workgroup -> work item.  Consecutive block ids are dealt round-robin to the 8 XCDs;
