@@ -921,6 +921,13 @@ void k_fused(AttnArgs A, Dims D)
 
     const int wid = swizzled_block();
     if (wid >= A.total) return;
+#ifdef BRA_EXPERIMENT
+    unsigned long long trace_t[8];
+#define BRA_TRACE(k) if (A.trace) trace_t[k] = __builtin_amdgcn_s_memrealtime()
+#else
+#define BRA_TRACE(k)
+#endif
+    BRA_TRACE(0);
 
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
@@ -948,6 +955,7 @@ void k_fused(AttnArgs A, Dims D)
     u32x4 hreg[NBH];
     tile_load<C, NBH>(hreg, Ximg, y0 - 2, x0 - 2, HW, hw_inv, HROWS, D.H, D.W, 0);
     if (!A.Ir_src) j = route_row_k1(rl, D.R, (uint32_t *)(smem + SM::r_off), nullptr);
+    BRA_TRACE(1);
     auto fragment = [&](int rt, int ks) {
         return *(const bf16x8 *)(A.Wf + ((size_t)(rt * KS + ks) * kWave + lane) * 8);
     };
@@ -971,6 +979,7 @@ void k_fused(AttnArgs A, Dims D)
     tile_store<C, XS, NBH>(Hs, hreg, HROWS, 0);
     tile_store<C, XS, NBT>(Ks, kreg, 64, 0);
     __syncthreads();
+    BRA_TRACE(2);
 
     // Q of this wavefront's 16 queries, as the B operands of S^T = K Q^T.
     const int q = 16 * wave + i;
@@ -1026,6 +1035,7 @@ void k_fused(AttnArgs A, Dims D)
         vh[hu] = pack4(a);
     }
     __syncthreads();   // every X tile has been read
+    BRA_TRACE(3);
 
     // Tiles of this wavefront's channels: rows 16 (2 p + g % 2) + i, channels 8 (g / 2) ..
 #pragma unroll
@@ -1047,6 +1057,7 @@ void k_fused(AttnArgs A, Dims D)
     // late phases finish (and free their LDS for the next workgroup) sooner than they would
     // in a fair interleave with workgroups that have only just started.  Measured: -3 %.
     __builtin_amdgcn_s_setprio(2);
+    BRA_TRACE(4);
     // Attention of the 16 queries over the 64 keys (Eq. 1 with one routed block).
     SoftmaxState<HEADS> st;
     st.init();
@@ -1086,6 +1097,7 @@ void k_fused(AttnArgs A, Dims D)
             }
         }
     }
+    BRA_TRACE(5);
     __syncthreads();   // K and V have been read: the LCE tile may take their place
 #pragma unroll
     for (int yb = 0; yb < NYB; ++yb)
@@ -1094,6 +1106,7 @@ void k_fused(AttnArgs A, Dims D)
             *(f32x4 *)(Ls + (16 * wave + lb) * PL + (4 * yb + xi) * RW + 4 * xb) = lce[yb][xb];
     __syncthreads();
 
+    BRA_TRACE(6);
     // O = attention + LCE (Eq. 2, 7) in registers, then Y^T = Wo^T O^T for the 16 queries:
     // W^o row 4 g + jj of tile tt stands for output channel 16 g + 4 tt + jj, so a lane
     // ends up with 16 consecutive output channels of its query.
@@ -1122,6 +1135,17 @@ void k_fused(AttnArgs A, Dims D)
     dst[1] = u32x4{yp[2][0], yp[2][1], yp[3][0], yp[3][1]};
     // reported last: a store ahead of the barriers above would have to land before them
     if (A.Ir_out && A.Ir_out != A.Ir_src && threadIdx.x == 0) A.Ir_out[rrow] = A.Ir_src ? j_given : j;
+#ifdef BRA_EXPERIMENT
+    if (A.trace) {
+        BRA_TRACE(7);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned long long *out = (unsigned long long *)(A.Y + img_off + ((size_t)y0 * D.W + x0) * C);
+            for (int k = 0; k < 8; ++k) out[k] = trace_t[k];
+        }
+    }
+#endif
+#undef BRA_TRACE
 }
 
 // ---------------------------------------------------------------------------
@@ -1341,15 +1365,17 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
         // the pooled-projection pipelines need neither and rearrange next to the projection
         static const bool route_launch = experiment_flag("BRA_FUSED_ROUTE_LAUNCH");
         const bool inline_route = fused && !route_launch;     // the k = 1 kernel routes by itself, from the routing vectors
-        const bool from_x = (fused || !pooled_projection(D)) && !Ir_in_opt;
-        if (fused || from_x)
-            launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/from_x, prep_total(C), st, /*with_u=*/inline_route);
-        if (from_x && !inline_route) {
-            const int rc = launch_route<C>(D, w, Ir_dst, nullptr, st);
-            if (rc != BRA_OK) return rc;
-            Ir_src = Ir_dst;
+        {
+            const bool from_x = (fused || !pooled_projection(D)) && !Ir_in_opt;
+            if (fused || from_x)
+                launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/from_x, prep_total(C), st, /*with_u=*/inline_route);
+            if (from_x && !inline_route) {
+                const int rc = launch_route<C>(D, w, Ir_dst, nullptr, st);
+                if (rc != BRA_OK) return rc;
+                Ir_src = Ir_dst;
+            }
+            prep_pending = !(fused || from_x);
         }
-        prep_pending = !(fused || from_x);
     }
     // the many-block attention kernel takes Q in units of log2 of the softmax weights
     const bool q32 = !fused && attn_big_ok(D) && attn_q32_ok(D) && !experiment_flag("BRA_ATTN_OLD");
