@@ -31,7 +31,7 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 
 def measured_traffic(kernel, workload):
     """HBM bytes per launch of `kernel` on `workload` from the committed rocprofv3 counter
-    summary (profiles/hbm_traffic.txt, written by paper_2303_08810_amd/traffic_summary.py),
+    summary (profiles/hbm_traffic.txt, written by traffic_summary.py),
     or None if there is no entry."""
     try:
         with open(TRAFFIC_FILE) as f:
@@ -67,6 +67,12 @@ def kernel_model(name, cfg):
     unit = cfg.H * cfg.W * cfg.C * eb * cfg.B
     f = flops_per_image(cfg)
     B = cfg.B
+    # the attention kernels: priced on bytes where the routed keys are few (HBM / L2 gather bound),
+    # on matrix-core flops where the arithmetic intensity of their share of the layer lies beyond
+    # the ridge of the chip (many keys per query: the 128x128 and the S = 16 shapes)
+    attn_flops = B * (f["attn"] + f["lce"] + f["wo"])
+    ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    attn = ("mfma", attn_flops, MFMA_BF16_PEAK_TFLOPS) if attn_flops / (4.0 * unit) > ridge else ("hbm", 4 * unit, HBM_PEAK_GBS)
     table = {
         # generic (VALU float32) family
         "gen_pool": ("hbm", unit, HBM_PEAK_GBS),
@@ -82,7 +88,7 @@ def kernel_model(name, cfg):
         "mfma_route_rows": ("alu", B * f["aff"], VALU_F32_PEAK_TFLOPS),
         "mfma_route": ("alu", B * (4 * cfg.R * cfg.C * cfg.C + f["aff"]), VALU_F32_PEAK_TFLOPS),
         "mfma_qkv": ("hbm", 4 * unit, HBM_PEAK_GBS),                   # X in, Q K V out
-        "mfma_attention": ("hbm", 4 * unit, HBM_PEAK_GBS),             # Q K V in, Y out
+        "mfma_attention": attn,                                        # Q K V in, Y out
         "mfma_fused_k1": ("hbm", 2 * unit, HBM_PEAK_GBS),              # X in, Y out
         "mfma_attn_small": ("hbm", 4 * unit, HBM_PEAK_GBS),            # Q K V in, O out
         "mfma_lce_add": ("hbm", 3 * unit, HBM_PEAK_GBS),               # O V in, O out
@@ -357,9 +363,8 @@ def time_variants(cfg, steps, warmup):
 
 
 def measured_peaks():
-    """What plain probe kernels reach on this GPU, beside the published peaks the roofline
-    uses: a copy and a read of 512 MiB (twice the last-level cache), and a register-only loop
-    of dense bf16 matrix products."""
+    """What plain streaming kernels reach on this GPU, beside the published HBM peak the roofline
+    uses: a copy and a read of 512 MiB (twice the last-level cache)."""
     import torch
 
     import paper_2303_08810_amd as bra
@@ -383,10 +388,7 @@ def measured_peaks():
 
     t_copy = timed(lambda: bra.util_copy(dst, src), 20)
     t_read = timed(lambda: bra.util_read(src, scratch), 20)
-    wgs, iters = 256 * 8, 4000
-    t_mfma = timed(lambda: bra.util_mfma(wgs, iters, scratch), 5)
-    return {"hbm_copy_GBs": round(2 * nbytes / t_copy / 1e9, 1), "hbm_read_GBs": round(nbytes / t_read / 1e9, 1),
-            "mfma_bf16_TFLOPs": round(wgs * 4 * 8 * iters * 16384 / t_mfma / 1e12, 1)}
+    return {"hbm_copy_GBs": round(2 * nbytes / t_copy / 1e9, 1), "hbm_read_GBs": round(nbytes / t_read / 1e9, 1)}
 
 
 def roofline_of(cfg, kernels):
@@ -401,9 +403,33 @@ def roofline_of(cfg, kernels):
     else:
         achieved, unit = work / avg_s / 1e12, "TFLOP/s"
     roof = dict(kernel=name, bound=bound, achieved=round(achieved, 2), peak=peak, unit=unit,
-                frac=round(achieved / peak, 4), traffic=None,
+                frac=round(achieved / peak, 4), traffic=measured_traffic(name, cfg.name),
                 avg_us=round(avg_s * 1e6, 2), work_per_launch=work)
     return roof, summary
+
+
+def step_roofline(cfg, ms_per_step):
+    """The whole step against both roofs: the bytes a perfectly fused layer has to move (X in, Y
+    out) and the layer's flops, over the measured time of one step."""
+    eb = 2 if cfg.dtype == "bf16" else 4
+    nbytes = 2 * cfg.B * cfg.H * cfg.W * cfg.C * eb
+    flops = cfg.B * flops_per_image(cfg)["total"]
+    t = ms_per_step / 1e3
+    peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else VALU_F32_PEAK_TFLOPS
+    return {"min_bytes": nbytes, "hbm_frac": round(nbytes / t / 1e9 / HBM_PEAK_GBS, 4), "flops": flops,
+            "flops_frac": round(flops / t / 1e12 / peak, 4),
+            "flops_peak": "bf16 mfma" if cfg.dtype == "bf16" else "fp32 vector"}
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for ln in f:
+                if ln.lower().startswith("model name"):
+                    return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def cpu_baseline(cfg, host, budget_s=12.0):
@@ -430,9 +456,17 @@ def cpu_baseline(cfg, host, budget_s=12.0):
         oracle.bra_forward(Xs, Wqkv, Wo, Wlce, **kw)
     dt = time.perf_counter() - t0
     n_img = per_call * reps
+    # the same oracle on one thread, on a few images (about 3 s)
+    n1 = max(1, min(X.shape[0], int(3.0 / max(t_probe * threads / n0, 1e-3))))
+    t0 = time.perf_counter()
+    oracle.bra_forward(X[:n1], Wqkv, Wo, Wlce, S=cfg.S, k=cfg.k, heads=cfg.heads, precision="f32", threads=1)
+    dt1 = time.perf_counter() - t0
     return dict(value=round(n_img / dt, 3), unit="images/s", cores=threads, kind="oracle",
                 sample=f"{n_img} whole images of the same workload ({reps} passes over {per_call} images, "
-                       f"float32 oracle, OpenMP over images), {dt:.1f} s")
+                       f"float32 oracle, OpenMP over images), {dt:.1f} s",
+                cpu_model=cpu_model(), host_cpus=os.cpu_count(),
+                single_thread={"value": round(n1 / dt1, 3), "unit": "images/s", "cores": 1,
+                               "sample": f"{n1} whole images, {dt1:.1f} s"})
 
 
 def main():
@@ -471,8 +505,6 @@ def main():
     ms = res["ms_per_step"]
     value = cfg.B / (ms / 1e3)
     roof, summary = roofline_of(cfg, res["kernels"])
-    if roof:
-        roof["traffic"] = measured_traffic(roof["kernel"], cfg.name)
     eb = 2 if cfg.dtype == "bf16" else 4
     line = {
         "metric": METRIC, "value": round(value, 1), "unit": "images/s", "n_gpus": 1,
@@ -483,7 +515,7 @@ def main():
                                f"S={cfg.S} k={cfg.k} {cfg.dtype}", "rotating_input_sets": res["sets"]},
         "achieved_tflops": round(cfg.B * f["total"] / (ms / 1e3) / 1e12, 3),
         "min_traffic_gbs": round(2 * cfg.B * cfg.H * cfg.W * cfg.C * eb / (ms / 1e3) / 1e9, 1),
-        "roofline": roof, "kernels": {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2)}
+        "roofline": roof, "step_roofline": step_roofline(cfg, ms), "kernels": {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2)}
                                       for k, v in summary.items()},
     }
     if not args.no_variants:
@@ -503,6 +535,7 @@ def main():
                 "images_per_s": round(c.B / (r["ms_per_step"] / 1e3), 1),
                 "ms_per_step": round(r["ms_per_step"], 5),
                 "achieved_tflops": round(c.B * fo["total"] / (r["ms_per_step"] / 1e3) / 1e12, 3),
+                "step_roofline": step_roofline(c, r["ms_per_step"]),
                 "dominant": rf,
                 "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in sm.items()},
             }

@@ -133,6 +133,13 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
 
     const int wid = swizzled_block();
     if (wid >= A.total) return;
+#ifdef BRA_EXPERIMENT
+    unsigned long long trace_t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define BRA_TRACE(k) if (A.trace) trace_t[k] = __builtin_amdgcn_s_memrealtime()
+#else
+#define BRA_TRACE(k)
+#endif
+    BRA_TRACE(0);
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
     const int b = wid / D.R, reg = wid % D.R;
@@ -166,9 +173,12 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
     for (int t = 0; t < 25; ++t) wl[t] = *(const unsigned *)(A.WlT + (size_t)t * C + 2 * cpair);
 
     f32x4 oacc[HPW][2];     // normalised attention output of this wavefront's heads
+    BRA_TRACE(1);
     small_attention<C>(A, D, log2n, img_off, irp, qtok, Ks, Vs, oacc);
+    BRA_TRACE(2);
     __builtin_amdgcn_s_setprio(2);      // late phases first: the workgroup's LDS is freed sooner
     __syncthreads();        // the key blocks have been read: the halo tile takes their place
+    BRA_TRACE(3);
     tile_store<C, CS, NBH>(Hs, hreg, hrows, 0);
     for (int first = 256 * NBH; first < hrows * CH; first += 256 * NBH) {
         tile_load<C, NBH>(hreg, A.V + img_off, y0 - 2, x0 - 2, hw, hw_inv, hrows, D.H, D.W, first);
@@ -179,6 +189,7 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
     auto tap = [&](int ch, int t) { return ch ? bf16_hi(wl[t]) : bf16_lo(wl[t]); };
     float lce[kMaxLceTasks][2][4];
     __syncthreads();        // the halo tile is complete
+    BRA_TRACE(4);
 #pragma unroll
     for (int tk = 0; tk < kMaxLceTasks; ++tk) {
         const int task = threadIdx.x + 256 * tk;
@@ -223,6 +234,7 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
         }
     }
     __syncthreads();
+    BRA_TRACE(5);
     // O = attention + LCE, rounded to bf16 once: rows of the B operand of W^o
 #pragma unroll
     for (int hh = 0; hh < HPW; ++hh) {
@@ -253,6 +265,17 @@ __global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
         }
         if (i < n) *(u32x2 *)(yrow + 16 * ct + 4 * g) = pack4(ya);
     }
+#ifdef BRA_EXPERIMENT
+    if (A.trace) {
+        BRA_TRACE(6);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned long long *out = (unsigned long long *)(A.Y + img_off + ((size_t)y0 * D.W + x0) * C);
+            for (int k = 0; k < 8; ++k) out[k] = trace_t[k];
+        }
+    }
+#endif
+#undef BRA_TRACE
 }
 
 // ---------------------------------------------------------------------------

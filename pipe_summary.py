@@ -3,7 +3,7 @@
 Counters (one pass, 8 SQ counters): SQ_VALU_MFMA_BUSY_CYCLES SQ_ACTIVE_INST_VALU SQ_INSTS_VALU
 SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_WAIT_INST_ANY SQ_INSTS_LDS SQ_LDS_BANK_CONFLICT.
 
-usage: python -m paper_2303_08810_amd.pipe_summary <dir of the counter run> <workload name> <file with a bench line>
+usage: python pipe_summary.py <dir of the counter run> <workload name> <file with a bench line>
 The bench line comes from a run WITHOUT counters (under --pmc the profiler serialises the launches
 and the event times grow by 100 us); it may be the line of another workload, whose `other_workloads`
 entry is then used.  Prints the text kept as profiles/pipe_utilisation.txt: per kernel the average
@@ -25,7 +25,7 @@ import json
 import re
 import sys
 
-from .traffic_summary import NAMES
+from traffic_summary import NAMES
 
 MORE = {"k_gemm": "gemm", "k_token_ln": "block_ln", "k_mlp_fused64": "block_mlp_fused", "k_mlp_stream": "block_mlp_fused",
         "k_attn_gen": "mfma_attention", "k_pool_wide": "mfma_pool_qk", "k_route_qk": "mfma_route_rows"}

@@ -2,7 +2,7 @@
 into HBM bytes per kernel launch, scaled by what the same counters read for the plain
 copy kernel of known size (bra_util_copy, 64 MiB read + 64 MiB written per launch).
 
-usage: python -m paper_2303_08810_amd.traffic_summary <dir FETCH run> <dir WRITE run> <workload name>
+usage: python traffic_summary.py <dir FETCH run> <dir WRITE run> <workload name>
 Prints the text kept as profiles/hbm_traffic.txt.
 """
 from __future__ import annotations
@@ -17,7 +17,7 @@ COPY_BYTES = 64 << 20
 NAMES = {"k_fused": "mfma_fused_k1", "k_pool": "mfma_pool_qk", "k_route": "mfma_route_rows",
          "k_route_p": "mfma_route_rows", "k_route_u": "mfma_route_rows",
          "k_attn_map": "mfma_attn_small", "k_attn_map4": "mfma_attn_small",
-         "k_qkv": "mfma_qkv", "k_attn_big": "mfma_attention", "k_attn_small": "mfma_attn_small",
+         "k_qkv": "mfma_qkv", "k_attn_big": "mfma_attention", "k_attn_q32": "mfma_attention", "k_attn_small": "mfma_attn_small",
          "k_small": "mfma_attn_small", "k_lce_add": "mfma_lce_add", "k_prep_weights": "mfma_prep",
          "k_token_ln": "block_ln", "k_mlp_fused64": "block_mlp_fused", "k_mlp_stream": "block_mlp_fused",
          "k_util_copy": "copy"}
