@@ -2,12 +2,13 @@
  * libbra -- forward pass of Bi-Level Routing Attention (BRA) on AMD MI355X (gfx950).
  *
  * C ABI.  Every data pointer is CALLER-OWNED DEVICE memory (dense, row-major, no
- * strides); `shape` and `out_bytes` are host pointers.  The library never
- * allocates, frees or synchronises: scratch memory comes from `ws` (size from
+ * strides); `shape` and `out_bytes` are host pointers.  The compute entry points never
+ * allocate, free or synchronise: scratch memory comes from `ws` (size from
  * bra_workspace_bytes, 256-byte aligned) and all work is enqueued on `hip_stream`
  * (a hipStream_t passed as void*; NULL = the default stream).  Outputs are valid
  * once the caller has synchronised that stream.  Calls that share a workspace must
- * be ordered on one stream.
+ * be ordered on one stream.  (The measurement aid bra_profile_begin / bra_profile_end is
+ * the exception: it creates and destroys HIP events and waits for them.)
  *
  * What is computed (paper: "BiFormer: Vision Transformer with Bi-Level Routing
  * Attention", Sec. 3.2, Eq. 3-7, Algorithm 1; W^o from Eq. 2):
