@@ -24,14 +24,12 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False, out: str = LIB, defines=(), jobs: int | None = None) -> str:
-    """Always recompiles.  `defines`: extra -D names (BRA_EXPERIMENT makes the A/B switches of
-    the kernels readable from the environment; the shipped library is built without it)."""
+def compile_objects(tag="product", defines=(), extra_flags=(), opt="-O3", verbose=False, jobs=None):
+    """One object file per source, compiled in parallel; returns their paths."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tag = "_".join(defines) or "product"
     obj_dir = os.path.join(OBJ_DIR, tag)
     os.makedirs(obj_dir, exist_ok=True)
-    flags = HIPCC_FLAGS + ["-D" + d for d in defines]
+    flags = [f if f != "-O3" else opt for f in HIPCC_FLAGS] + ["-D" + d for d in defines] + list(extra_flags)
 
     def compile_one(src):
         obj = os.path.join(obj_dir, os.path.basename(src)[:-4] + ".o")
@@ -43,7 +41,14 @@ def build(verbose: bool = False, out: str = LIB, defines=(), jobs: int | None = 
 
     jobs = jobs or min(8, os.cpu_count() or 1)
     with ThreadPoolExecutor(max_workers=jobs) as pool:
-        objs = list(pool.map(compile_one, sources()))
+        return list(pool.map(compile_one, sources()))
+
+
+def build(verbose: bool = False, out: str = LIB, defines=(), jobs: int | None = None) -> str:
+    """Always recompiles.  `defines`: extra -D names (BRA_EXPERIMENT makes the A/B switches of
+    the kernels readable from the environment; the shipped library is built without it)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objs = compile_objects(tag="_".join(defines) or "product", defines=defines, verbose=verbose, jobs=jobs)
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
