@@ -25,6 +25,9 @@
 
 #include <stdlib.h>
 
+#include <algorithm>
+#include <type_traits>
+
 namespace bra {
 
 using namespace mfma;
@@ -114,6 +117,7 @@ struct PrepArgs {
     const bf16_t *Wqkv, *Wo, *Wlce;
     bf16_t *WT, *WoT, *Wa, *Wf;
     int elems;                      // leading prep elements to produce (0: none)
+    int trace = 0;                  // experiment builds: leave phase timestamps in Q
 };
 
 // `total` = prep_total(C) (all weights) or 3 C^2 (projection weights only; Wo and Wlce
@@ -558,7 +562,7 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
 // before the rounding to bf16, and written as P[token / group][2C] = [sum Q | sum K].  The
 // routing kernel adds the few partial sums of each region.
 template <int C, int WPB, int NMAT>
-__global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, 2)))
+__global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, C == 256 ? 2 : 4)))
 void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *__restrict__ Q,
            bf16_t *__restrict__ K, bf16_t *__restrict__ V, float *__restrict__ P, int group_log2, long M,
            int tiles_per_wg, int gx, PrepArgs prep, float qscale)
@@ -576,6 +580,18 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
         }
         return;
     }
+#ifdef BRA_EXPERIMENT
+    unsigned long long trace_t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define BRA_TRACE(k) if (prep.trace) trace_t[k] = __builtin_amdgcn_s_memrealtime()
+#else
+#define BRA_TRACE(k)
+#endif
+    BRA_TRACE(0);
+#ifdef BRA_EXPERIMENT
+    const int smode = (prep.trace >> 3) & 3;
+#else
+    constexpr int smode = 0;
+#endif
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
     const int grp = blockIdx.y * WPB + wave;            // 64-channel group among NMAT C / 64
@@ -583,16 +599,24 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
     bf16_t *__restrict__ out = sel == 0 ? Q : (sel == 1 ? K : V);
     const int group = 1 << group_log2;
 
+    // The products are v_mfma_f32_32x32x16_bf16 (twice the matrix-core rate of the 16x16x32 form on
+    // this chip): lane l = 32 h + c holds A[row c][k 8 h ..], B[k 8 h ..][col c] and
+    // D[rows 8 q + 4 h + j][col c] in result register 4 q + j.
     // This wavefront's weight slice W[:, sel C + base .. + 63] (row-major [C][NMAT C], as the
-    // caller holds it) -> MFMA A fragments with permuted rows: 64 input channels at a time
-    // are copied with coalesced loads into a wavefront-private LDS tile and come back through
-    // the transposing read (lane i of a 16-lane group supplies the address of 4 columns
-    // 16 (i % 4) + 4 tt .. of row i / 4 and receives column 16 (i / 4) + 4 tt + i % 4 of rows
-    // 0 .. 3).  LDS operations of one wavefront complete in order, so no barrier is needed.
-    bf16x8 af[4][KS];
+    // caller holds it) -> A fragments with permuted rows (row 8 q + 4 h' + j of a 32-row tile is
+    // output channel 16 h' + 4 q + j, so that a lane's 16 results are 16 consecutive channels of
+    // one token): 64 input channels at a time are copied with coalesced loads into a
+    // wavefront-private LDS tile and come back through the transposing read (lane s of a 16-lane
+    // group supplies the address of 4 columns of row s / 4, lane i receives column i % 4 of the
+    // chunk that the lanes s % 4 == i / 4 named, for rows 0 .. 3).  LDS operations of one
+    // wavefront complete in order, so no barrier is needed between its own writes and reads.
+    constexpr int KST = C / 16;                           // contraction steps
+    const int h = lane / 32, c32 = lane % 32;
+    bf16x8 af[2][KST];
     {
-        bf16_t *wb = (bf16_t *)(smem + (size_t)2 * 64 * XP * 2) + wave * 64 * WP;
+        bf16_t *wb = (bf16_t *)smem + wave * 64 * WP;      // in the X tiles' place: they are staged afterwards
         const bf16_t *wsrc = W + sel * C + base;
+        const int gg = c32 / 16;
 #pragma unroll
         for (int kc = 0; kc < C / 64; ++kc) {
             u32x4 wr[8];
@@ -607,83 +631,147 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
                 *(u32x4 *)(wb + (idx / 8) * WP + (idx % 8) * 8) = wr[u];
             }
 #pragma unroll
-            for (int kl = 0; kl < 2; ++kl)
+            for (int kl = 0; kl < 4; ++kl)
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt) {
-                    const bf16_t *src = wb + (32 * kl + 8 * g + i / 4) * WP + 16 * (i % 4) + 4 * tt;
+                for (int rt = 0; rt < 2; ++rt) {
+                    const bf16_t *src = wb + (16 * kl + 8 * h + i / 4) * WP + 32 * rt + 16 * ((i % 4) % 2) +
+                                        4 * (2 * gg + (i % 4) / 2);
                     const s16x4 v0 = lds_read_tr16(src), v1 = lds_read_tr16(src + 4 * WP);
                     const u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
                     const u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
-                    af[tt][2 * kc + kl] = __builtin_bit_cast(bf16x8, av);
+                    af[rt][4 * kc + kl] = __builtin_bit_cast(bf16x8, av);
                 }
         }
     }
 
+    __syncthreads();                                       // every wavefront has its fragments: the X tiles may come
+    BRA_TRACE(1);
     const long ntiles = (M + 63) / 64;
     const long tile0 = (long)blockIdx.x * tiles_per_wg;
     const long tile1 = tile0 + tiles_per_wg < ntiles ? tile0 + tiles_per_wg : ntiles;
     if (tile0 >= tile1) return;
-    u32x4 xr[NL];
-    auto fetch = [&](long tile) {            // rows past M repeat the last token; their results are not stored
+    // Requests and stores are laid out so that the wait for a tile's X leaves the stores of the tile
+    // before it pending: every tile of the main loop stores unconditionally (a ragged last tile is
+    // handled after the loop), and every iteration requests a tile (past the end: the last one again).
+    constexpr int ND = C >= 256 ? 1 : (NL <= 3 ? 4 : 2);     // tiles on their way in registers (a tile's X takes about five tiles' arithmetic to arrive)
+    u32x4 xr[ND][NL];
+    auto fetch = [&](long tile, u32x4 (&r)[NL]) {      // rows past M repeat the last token; their results are not stored
+        if (tile > tile1 - 1) tile = tile1 - 1;
 #pragma unroll
         for (int u = 0; u < NL; ++u) {
-            const int idx = threadIdx.x + NTH * u;
+            const int idx = min((int)threadIdx.x + NTH * u, 64 * CH - 1);
             long t = tile * 64 + idx / CH;
             if (t >= M) t = M - 1;
-            xr[u] = u32x4{0u, 0u, 0u, 0u};
-            if (idx < 64 * CH) xr[u] = *(const u32x4 *)(X + t * C + (idx % CH) * 8);
+            r[u] = *(const u32x4 *)(X + t * C + (idx % CH) * 8);
         }
     };
-    auto stage = [&](int b) {
+    auto stage = [&](int b, const u32x4 (&r)[NL]) {
 #pragma unroll
         for (int u = 0; u < NL; ++u) {
             const int idx = threadIdx.x + NTH * u;
-            if (idx < 64 * CH) *(u32x4 *)(xs0 + (b * 64 + idx / CH) * XP + (idx % CH) * 8) = xr[u];
+            if (idx < 64 * CH) *(u32x4 *)(xs0 + (b * 64 + idx / CH) * XP + (idx % CH) * 8) = r[u];
         }
     };
-    fetch(tile0);
-    stage(0);
-    __syncthreads();
-    int cur = 0;
-    for (long tile = tile0; tile < tile1; ++tile) {
-        const bool more = tile + 1 < tile1;
-        if (more) fetch(tile + 1);
+    // one tile of 64 tokens from buffer `cur`; FULL: all its tokens exist
+    auto project = [&](long tile, int cur, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            bf16x8 bf[KS];
+        for (int ct = 0; ct < 2; ++ct) {
+            f32x16 acc[2];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) bf[ks] = *(const bf16x8 *)(xs0 + (cur * 64 + 16 * u + i) * XP + 32 * ks + 8 * g);
-            f32x4 acc[4];
+            for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) acc[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int e = 0; e < 16; ++e) acc[rt][e] = 0.f;
+            const bf16_t *xrow = xs0 + (cur * 64 + 32 * ct + c32) * XP + 8 * h;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
+            for (int kst = 0; kst < KST; ++kst) {
+                const bf16x8 bfr = *(const bf16x8 *)(xrow + 16 * kst);
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt) acc[tt] = mfma16(af[tt][ks], bf[ks], acc[tt]);
-            const long t = tile * 64 + 16 * u + i;
-            if (t < M) {
+                for (int rt = 0; rt < 2; ++rt) acc[rt] = mfma32(af[rt][kst], bfr, acc[rt]);
+            }
+            const long t = tile * 64 + 32 * ct + c32;
+            if ((FULL || t < M) && !(prep.trace & 2)) {
                 // Q may leave multiplied by a factor (the attention kernel that wants its scores in
                 // units of log2 passes scale * log2 e): one rounding, of the scaled value
                 const float os = sel == 0 ? qscale : 1.0f;
-                u32x2 p0 = pack4(acc[0] * os), p1 = pack4(acc[1] * os), p2 = pack4(acc[2] * os), p3 = pack4(acc[3] * os);
-                u32x4 *dst = (u32x4 *)(out + t * C + base + 16 * g);
-                dst[0] = u32x4{p0[0], p0[1], p1[0], p1[1]};
-                dst[1] = u32x4{p2[0], p2[1], p3[0], p3[1]};
+#pragma unroll
+                for (int rt = 0; rt < 2; ++rt) {
+                    u32x4 *dst = (u32x4 *)(out + t * C + base + 32 * rt + 16 * h);
+                    const u32x4 lo = {pack_bf16(acc[rt][0] * os, acc[rt][1] * os), pack_bf16(acc[rt][2] * os, acc[rt][3] * os),
+                                      pack_bf16(acc[rt][4] * os, acc[rt][5] * os), pack_bf16(acc[rt][6] * os, acc[rt][7] * os)};
+                    const u32x4 hi = {pack_bf16(acc[rt][8] * os, acc[rt][9] * os), pack_bf16(acc[rt][10] * os, acc[rt][11] * os),
+                                      pack_bf16(acc[rt][12] * os, acc[rt][13] * os), pack_bf16(acc[rt][14] * os, acc[rt][15] * os)};
+                    if (smode == 1) { store16<1>(dst, lo); store16<1>(dst + 1, hi); }
+                    else if (smode == 2) { store16<2>(dst, lo); store16<2>(dst + 1, hi); }
+                    else { store16<0>(dst, lo); store16<0>(dst + 1, hi); }
+                }
             }
             if (P && sel < 2) {      // M is a multiple of the group: a group is whole or absent
-                if (group_log2 == 1) lane_group_sums<1>(acc);
-                else if (group_log2 == 2) lane_group_sums<2>(acc);
-                if (t < M && (i & (group - 1)) == 0) {
-                    f32x4 *dst = (f32x4 *)(P + (t >> group_log2) * 2 * C + sel * C + base + 16 * g);
+                // one branch around the whole sum, not one per element
+                if (group_log2 >= 2) {
 #pragma unroll
-                    for (int tt = 0; tt < 4; ++tt) dst[tt] = acc[tt];
+                    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            acc[rt][e] = dpp_fadd<0x4E>(dpp_fadd<0xB1>(acc[rt][e]));      // quad_perm [1,0,3,2], then [2,3,0,1]
+                } else if (group_log2 == 1) {
+#pragma unroll
+                    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) acc[rt][e] = dpp_fadd<0xB1>(acc[rt][e]);
+                }
+                if ((FULL || t < M) && (c32 & (group - 1)) == 0 && !(prep.trace & 4)) {
+#pragma unroll
+                    for (int rt = 0; rt < 2; ++rt) {
+                        f32x4 *dst = (f32x4 *)(P + (t >> group_log2) * 2 * C + sel * C + base + 32 * rt + 16 * h);
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            const f32x4 pv = {acc[rt][4 * q4], acc[rt][4 * q4 + 1], acc[rt][4 * q4 + 2], acc[rt][4 * q4 + 3]};
+                            const u32x4 pu = __builtin_bit_cast(u32x4, pv);
+                            if (smode == 1) store16<1>(dst + q4, pu);
+                            else if (smode == 2) store16<2>(dst + q4, pu);
+                            else store16<0>(dst + q4, pu);
+                        }
+                    }
                 }
             }
         }
-        if (more) stage(cur ^ 1);      // the other buffer was last read before the previous barrier
-        __syncthreads();
-        cur ^= 1;
+    };
+    // Tile tile0 + j travels in register set j % ND.  Every round requests a tile and hands one to
+    // LDS, whether or not it exists (past the end: the last tile again, into a buffer nobody reads).
+#pragma unroll
+    for (int d = 0; d < ND; ++d) fetch(tile0 + d, xr[d]);
+    stage(0, xr[0]);
+    fetch(tile0 + ND, xr[0]);
+    __syncthreads();
+    BRA_TRACE(2);
+    const long tfull = tile1 * 64 <= M ? tile1 : tile1 - 1;      // tiles below this one are full
+    for (long base_tile = tile0; base_tile < tfull; base_tile += ND) {
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+            const long tile = base_tile + d;
+            const int cur = (int)((tile - tile0) & 1);
+            if (tile < tfull) project(tile, cur, std::true_type{});
+            stage(cur ^ 1, xr[(d + 1) % ND]);      // the other buffer was last read before the previous barrier
+            fetch(tile + 1 + ND, xr[(d + 1) % ND]);
+            __syncthreads();
+            if (tile == tile0) BRA_TRACE(3);
+        }
     }
+    const int cur = (int)((tfull - tile0) & 1);
+    if (tfull < tile1) project(tfull, cur, std::false_type{});
+#ifdef BRA_EXPERIMENT
+    if (prep.trace) {
+        BRA_TRACE(4);
+        __syncthreads();
+        if (threadIdx.x == 0 && blockIdx.y == 0) {
+            unsigned long long *o = (unsigned long long *)(Q + tile0 * 64 * C);
+            for (int k = 0; k < 5; ++k) o[k] = trace_t[k];
+            o[5] = (unsigned long long)(tile1 - tile0);
+        }
+    }
+#endif
+#undef BRA_TRACE
 }
 
 // ---------------------------------------------------------------------------
@@ -1301,15 +1389,16 @@ int launch_qkv(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const MfmaWs 
     const long M = (long)D.B * D.N;
     constexpr int WPB = (C == 256) ? 4 : 3 * C / 64;      // wavefronts (64-channel groups) per workgroup
     const long ntiles = (M + 63) / 64;
-    // about one workgroup per compute unit: every wavefront keeps its weight slice in
-    // registers and the workgroup streams its share of the tokens
+    // about two workgroups per compute unit (what LDS and registers allow): every wavefront keeps
+    // its weight slice in registers and the workgroup streams its share of the tokens
     const int gy = 3 * C / 64 / WPB;
-    long tpw = (ntiles * gy + 255) / 256;
+    const long slots = experiment_value("BRA_QKV_SLOTS", 512);
+    long tpw = (ntiles * gy + slots - 1) / slots;
     static const int forced = (int)experiment_value("BRA_QKV_TPW", 0);
     if (forced >= 1 && forced <= 4096) tpw = forced;
     const int gx = (int)((ntiles + tpw - 1) / tpw);
     const int prep_blocks = (prep.elems + 64 * WPB - 1) / (64 * WPB);
-    const size_t smem = (size_t)2 * 64 * (C + 16) * 2 + (size_t)WPB * 64 * 72 * 2;
+    const size_t smem = std::max((size_t)2 * 64 * (C + 16) * 2, (size_t)WPB * 64 * 72 * 2);
     static bool opted = false;
     if (!lds_opt_in(k_qkv<C, WPB, 3>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_QKV);
@@ -1328,7 +1417,7 @@ int launch_wo(const Dims &D, const bf16_t *O, const bf16_t *Wo, bf16_t *Y, hipSt
     const long ntiles = (M + 63) / 64;
     const long tpw = (ntiles + 511) / 512;
     const int gx = (int)((ntiles + tpw - 1) / tpw);
-    const size_t smem = (size_t)2 * 64 * (C + 16) * 2 + (size_t)WPB * 64 * 72 * 2;
+    const size_t smem = std::max((size_t)2 * 64 * (C + 16) * 2, (size_t)WPB * 64 * 72 * 2);
     static bool opted = false;
     if (!lds_opt_in(k_qkv<C, WPB, 1>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_WO);
@@ -1382,7 +1471,8 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     const float c_exp = D.scale * 1.4426950408889634f;
     if (!fused) {
         const bool pooled = pooled_projection(D) && !Ir_in_opt;
-        const PrepArgs prep = {Wqkv, Wo, Wlce, w.wt, w.wot, w.wa, w.wf, prep_pending ? prep_total(C) : 0};
+        PrepArgs prep = {Wqkv, Wo, Wlce, w.wt, w.wot, w.wa, w.wf, prep_pending ? prep_total(C) : 0};
+        prep.trace = (int)experiment_value("BRA_QKV_TRACE", 0);
         int rc = launch_qkv<C>(D, X, Wqkv, w, pooled, prep, st, q32 ? c_exp : 1.0f);
         if (rc != BRA_OK) return rc;
         if (pooled) {
