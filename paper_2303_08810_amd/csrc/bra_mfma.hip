@@ -485,9 +485,11 @@ __global__ __launch_bounds__(256) void k_route(const float *__restrict__ Xr,
 // Q^r and K^r are the region means of Q and K (Sec. 3.2), i.e. the sum of a region's
 // rh x (rw / group) partial sums in a fixed order, divided by n.  Workgroup (b, rt) as in
 // k_route; no matrix products are left to do here.
+// With `whole` the projection kernel ran over region tiles and P[b R + r][2C] already holds the sums
+// over each region.
 template <int C, int NR>
 __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, int32_t *__restrict__ Ir,
-                                                 float *__restrict__ Ar, Dims D, int group_log2)
+                                                 float *__restrict__ Ar, Dims D, int group_log2, int whole)
 {
     constexpr int QS = C + 4, C4 = C / 4, QR = 4 * NR;     // query regions of a workgroup
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -499,6 +501,15 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
     const int b = wid / groups, myrt = wid % groups;
     const int pw = D.W >> group_log2, pc = D.rw >> group_log2;      // partial sums per image row / region row
     const float inv_n = 1.0f / (float)D.n;
+#ifdef BRA_EXPERIMENT
+    unsigned long long trace_t[4] = {0, 0, 0, 0};
+    const bool tracing = whole & 2;
+#define BRA_TRACE(k) if (tracing) trace_t[k] = __builtin_amdgcn_s_memrealtime()
+#else
+#define BRA_TRACE(k)
+#endif
+    whole &= 1;
+    BRA_TRACE(0);
     // Work items (region, 4 channels): all of K^r, then the QR query rows of Q^r.  A thread
     // takes its NI items at once so that their loads are in flight together; the partial sums of
     // an item are added in the order (row of the region, position in the row).
@@ -514,11 +525,13 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
             const int row = (isq ? idx - nk : idx) / C4, c4 = (isq ? idx - nk : idx) % C4;
             const int r = isq ? min(QR * myrt + row, D.R - 1) : row;     // rows past R repeat the last region; never used
             const int ry = r / D.S, rx = r % D.S;
-            src[u] = P + (((size_t)b * D.H + ry * D.rh) * pw + rx * pc) * 2 * C + (isq ? 0 : C) + 4 * c4;
+            src[u] = P + (whole ? (size_t)b * D.R + r : ((size_t)b * D.H + ry * D.rh) * pw + rx * pc) * 2 * C +
+                     (isq ? 0 : C) + 4 * c4;
             acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
-        for (int yy = 0; yy < D.rh; ++yy)
-            for (int cc = 0; cc < pc; ++cc) {
+        const int nyy = whole ? 1 : D.rh, ncc = whole ? 1 : pc;
+        for (int yy = 0; yy < nyy; ++yy)
+            for (int cc = 0; cc < ncc; ++cc) {
                 f32x4 v[NI];
 #pragma unroll
                 for (int u = 0; u < NI; ++u) v[u] = *(const f32x4 *)(src[u] + ((size_t)yy * pw + cc) * 2 * C);
@@ -540,14 +553,102 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
         }
     }
     __syncthreads();
+    BRA_TRACE(1);
     route_rows_from_lds<C, NR>(Kt, Qs, b, myrt, D, Ir, Ar);
+#ifdef BRA_EXPERIMENT
+    if (tracing && Ar) {
+        BRA_TRACE(2);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned long long *o = (unsigned long long *)(Ar + ((size_t)b * D.R + QR * myrt) * D.R);
+            for (int k = 0; k < 3; ++k) o[k] = trace_t[k];
+        }
+    }
+#endif
+#undef BRA_TRACE
 }
+
+// Routing from whole-region sums (the projection kernel ran over region tiles and left
+// P[b R + r][2C] = [sum Q | sum K] over the tokens of region r): A^r = Q^r (K^r)^T (Eq. 4) with
+// Q^r, K^r the sums divided by n (Sec. 3.2), and its row-wise top-k (Eq. 5).  Workgroup (b, rt)
+// owns the 16 query regions 16 rt .. 16 rt + 15 of image b (R <= 64); wavefront w forms their
+// affinities to the keys 16 w .. 16 w + 15 with float32 matrix-core products
+// (v_mfma_f32_16x16x4_f32: lane 16 g + i holds A[row i][k g], B[k g][col i] and
+// D[rows 4 g + j][col i]), its operands loaded straight from P with every request issued before the
+// first product; the four 16 x 16 blocks meet in LDS, then wavefront w ranks rows 4 w .. 4 w + 3.
+template <int C>
+__global__ __launch_bounds__(256) void k_route_w(const float *__restrict__ P, int32_t *__restrict__ Ir,
+                                                 float *__restrict__ Ar, Dims D)
+{
+    __shared__ float At[16][65];
+    const int groups = (D.R + 15) / 16;
+    const int wid = swizzled_block();          // the workgroups of an image share an XCD (and its L2)
+    if (wid >= D.B * groups) return;
+    const int b = wid / groups, myrt = wid % groups;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int g = lane / 16, i = lane % 16;
+    // rows past R repeat the last region; their results are never used
+    const float *qsrc = P + ((size_t)b * D.R + min(16 * myrt + i, D.R - 1)) * 2 * C + 4 * g;
+    const float *ksrc = P + ((size_t)b * D.R + min(16 * wave + i, D.R - 1)) * 2 * C + C + 4 * g;
+    f32x4 qv[C / 16], kv[C / 16];      // channels 16 s + 4 g + e: product e of step s contracts over {16 s + 4 g' + e}
+#pragma unroll
+    for (int s = 0; s < C / 16; ++s) {
+        qv[s] = *(const f32x4 *)(qsrc + 16 * s);
+        kv[s] = *(const f32x4 *)(ksrc + 16 * s);
+    }
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < C / 16; ++s)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qv[s][e], kv[s][e], acc, 0, 0, 0);
+    const float inv_n = 1.0f / (float)D.n, sc = inv_n * inv_n;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) At[4 * g + j][16 * wave + i] = acc[j] * sc;
+    __syncthreads();
+    float a[4];
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) a[rr] = At[4 * wave + rr][lane];
+    const int r0 = 16 * myrt + 4 * wave;
+    if (r0 >= D.R) return;
+    const int nrows = min(4, D.R - r0);
+    const size_t row0 = (size_t)b * D.R + r0;
+    if (Ar && lane < D.R) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+            if (rr < nrows) Ar[(row0 + rr) * D.R + lane] = a[rr];
+    }
+    wave_topk_rows<4>(a, nrows, lane, D.R, D.k, Ir + row0 * D.k);
+}
+
+// LDS of the projection kernel: two X tiles (rows of C + 16 bf16), in whose place every wavefront
+// first stages 64 rows of 32 RT + 8 bf16 of weights, then a table of 8 x 64 tokens.
+template <int C, int WPB, int RT>
+constexpr size_t kQkvTableOff = (size_t)2 * 64 * (C + 16) * 2 > (size_t)WPB * 64 * (32 * RT + 8) * 2
+                                    ? (size_t)2 * 64 * (C + 16) * 2
+                                    : (size_t)WPB * 64 * (32 * RT + 8) * 2;
+template <int C, int WPB, int RT>
+constexpr size_t kQkvSmem = kQkvTableOff<C, WPB, RT> + 8 * 64 * 4;
+
+// How the projection kernel's tiles of 64 "slots" map to tokens.  Plain (region_tiles = 0): slot s is
+// token s of the [B N] token list.  Region tiles (n divides 64, n <= 16): the slots run over the
+// regions in the order (image, region), n slots per region in row-major order inside the region, so
+// that a tile holds 64 / n whole regions and the sums over a region's tokens (Sec. 3.2: Q^r and K^r
+// are per-region means) are formed inside one tile.
+struct TileMap {
+    int region_tiles;
+    int sum_log2;       // accumulators are summed over aligned groups of 2^sum_log2 consecutive slots
+    int map_log2;       // region tiles: log2 n (a region = 2^map_log2 consecutive slots); plain: 0
+    int rw_log2;        // region tiles: log2 of the region width
+    int R, S, rh, rw, W, N;
+    int regions;        // region tiles: B R
+};
 
 // ---------------------------------------------------------------------------
 // Q, K, V = X [Wq | Wk | Wv]  (Eq. 3; NMAT = 3), or a single projection such as Y = O Wo
-// (Eq. 2; NMAT = 1, every output pointer the same).  Each wavefront owns 64 output channels of one
+// (Eq. 2; NMAT = 1, every output pointer the same).  Each wavefront owns 32 RT output channels of one
 // of the NMAT matrices and keeps its weight fragments in registers; a workgroup is
-// WPB such wavefronts (blockIdx.y selects which) and walks over `tiles_per_wg`
+// WPB such wavefronts (blockIdx.y selects which; a multiple of 4 per compute unit keeps its four
+// SIMDs equally busy) and walks over `tiles_per_wg`
 // consecutive tiles of 64 tokens (blockIdx.x < gx; workgroups beyond that rearrange the
 // weights for the kernels that follow).  A tile of X is fetched once per workgroup with
 // fully coalesced 16-byte loads (one tile ahead, held in registers while the current
@@ -557,19 +658,22 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
 // output channels of one token, i.e. one 32-byte store.
 //
 // Region pooling of Q and K (Sec. 3.2: Q^r, K^r are the per-region means of Q and K)
-// rides along when P is given: the float32 accumulators of `group` = min(rw, 4)
-// consecutive tokens, which always lie in one row of one region, are summed across lanes
-// before the rounding to bf16, and written as P[token / group][2C] = [sum Q | sum K].  The
-// routing kernel adds the few partial sums of each region.
-template <int C, int WPB, int NMAT>
-__global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, C == 256 ? 2 : 4)))
+// rides along when P is given: the float32 accumulators of aligned groups of 2^sum_log2
+// consecutive slots are summed across lanes before the rounding to bf16, and written as
+// P[slot >> sum_log2][2C] = [sum Q | sum K].  With region tiles a group is a whole region and the
+// routing kernel only divides by n; otherwise a group is min(rw, 4) consecutive tokens of one row of
+// one region, and the routing kernel adds the few partial sums of each region.
+template <int C, int WPB, int NMAT, int RT>
+__global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(C == 256 ? 2 : 3, 4)))
 void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *__restrict__ Q,
-           bf16_t *__restrict__ K, bf16_t *__restrict__ V, float *__restrict__ P, int group_log2, long M,
+           bf16_t *__restrict__ K, bf16_t *__restrict__ V, float *__restrict__ P, TileMap tm, long M,
            int tiles_per_wg, int gx, PrepArgs prep, float qscale)
 {
     constexpr int KS = C / 32, CH = C / 8, XP = C + 16, NTH = 64 * WPB;
+    constexpr size_t kTableOff = kQkvTableOff<C, WPB, RT>;  // region tiles: first tokens of the regions of 8 tiles
     constexpr int NL = (64 * CH + NTH - 1) / NTH;       // 16-byte chunks of a tile per thread
-    constexpr int WP = 64 + 8;                          // row pitch of a wavefront's weight staging tile
+    constexpr int CW = 32 * RT;                         // output channels of a wavefront
+    constexpr int WP = CW + 8;                          // row pitch of a wavefront's weight staging tile
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *xs0 = (bf16_t *)smem;
     if ((int)blockIdx.x >= gx) {                        // workgroups past the token tiles rearrange weights
@@ -594,74 +698,80 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
 #endif
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
-    const int grp = blockIdx.y * WPB + wave;            // 64-channel group among NMAT C / 64
-    const int sel = grp / (C / 64), base = (grp % (C / 64)) * 64;
+    const int grp = blockIdx.y * WPB + wave;            // channel group among NMAT C / CW
+    const int sel = grp / (C / CW), base = (grp % (C / CW)) * CW;
     bf16_t *__restrict__ out = sel == 0 ? Q : (sel == 1 ? K : V);
-    const int group = 1 << group_log2;
+    const int group_log2 = tm.sum_log2, group = 1 << group_log2;
+    const long ntiles = (M + 63) / 64;
+    const long tile0 = (long)blockIdx.x * tiles_per_wg;
+    const long tile1 = tile0 + tiles_per_wg < ntiles ? tile0 + tiles_per_wg : ntiles;
+    // rbase[(tile - tile0) % 8][j] = first token of region j of the tile (plain: token of slot j).  The
+    // entry of a tile is written (by the first 64 >> map_log2 threads) at least one barrier before its
+    // first use; tiles past the workgroup's last repeat it, regions (tokens) past the last one repeat
+    // that one.  Both modes look the token up: a branch between the matrix products and the first read
+    // of their results is best avoided.
+    int *rbase = (int *)(smem + kTableOff);
+    auto table_entry = [&](long it) {
+        const int rpt = 64 >> tm.map_log2;
+        if ((int)threadIdx.x < rpt) {
+            long tile = tile0 + it;
+            if (tile > tile1 - 1) tile = tile1 - 1;
+            long G = tile * rpt + (int)threadIdx.x;
+            int first;
+            if (tm.region_tiles) {
+                if (G > tm.regions - 1) G = tm.regions - 1;
+                const int b = (int)(G / tm.R), r = (int)(G - (long)b * tm.R);
+                const int gy = r / tm.S, gx_ = r - gy * tm.S;
+                first = b * tm.N + gy * tm.rh * tm.W + gx_ * tm.rw;
+            } else {
+                first = (int)(G < M ? G : M - 1);
+            }
+            rbase[(it & 7) * 64 + threadIdx.x] = first;
+        }
+    };
 
     // The products are v_mfma_f32_32x32x16_bf16 (twice the matrix-core rate of the 16x16x32 form on
     // this chip): lane l = 32 h + c holds A[row c][k 8 h ..], B[k 8 h ..][col c] and
     // D[rows 8 q + 4 h + j][col c] in result register 4 q + j.
-    // This wavefront's weight slice W[:, sel C + base .. + 63] (row-major [C][NMAT C], as the
+    // This wavefront's weight slice W[:, sel C + base .. + CW - 1] (row-major [C][NMAT C], as the
     // caller holds it) -> A fragments with permuted rows (row 8 q + 4 h' + j of a 32-row tile is
-    // output channel 16 h' + 4 q + j, so that a lane's 16 results are 16 consecutive channels of
-    // one token): 64 input channels at a time are copied with coalesced loads into a
+    // output channel 16 (q / 2) + 8 h' + 4 (q % 2) + j, so that a lane's results 0 .. 7 and 8 .. 15 are
+    // 8 consecutive channels each and the two half-waves together write 32 contiguous bytes of a
+    // token per store): 64 input channels at a time are copied with coalesced loads into a
     // wavefront-private LDS tile and come back through the transposing read (lane s of a 16-lane
     // group supplies the address of 4 columns of row s / 4, lane i receives column i % 4 of the
     // chunk that the lanes s % 4 == i / 4 named, for rows 0 .. 3).  LDS operations of one
     // wavefront complete in order, so no barrier is needed between its own writes and reads.
     constexpr int KST = C / 16;                           // contraction steps
     const int h = lane / 32, c32 = lane % 32;
-    bf16x8 af[2][KST];
-    {
-        bf16_t *wb = (bf16_t *)smem + wave * 64 * WP;      // in the X tiles' place: they are staged afterwards
-        const bf16_t *wsrc = W + sel * C + base;
-        const int gg = c32 / 16;
-#pragma unroll
-        for (int kc = 0; kc < C / 64; ++kc) {
-            u32x4 wr[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = lane + 64 * u;
-                wr[u] = *(const u32x4 *)(wsrc + (size_t)(64 * kc + idx / 8) * (NMAT * C) + (idx % 8) * 8);
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = lane + 64 * u;
-                *(u32x4 *)(wb + (idx / 8) * WP + (idx % 8) * 8) = wr[u];
-            }
-#pragma unroll
-            for (int kl = 0; kl < 4; ++kl)
-#pragma unroll
-                for (int rt = 0; rt < 2; ++rt) {
-                    const bf16_t *src = wb + (16 * kl + 8 * h + i / 4) * WP + 32 * rt + 16 * ((i % 4) % 2) +
-                                        4 * (2 * gg + (i % 4) / 2);
-                    const s16x4 v0 = lds_read_tr16(src), v1 = lds_read_tr16(src + 4 * WP);
-                    const u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
-                    const u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
-                    af[rt][4 * kc + kl] = __builtin_bit_cast(bf16x8, av);
-                }
-        }
-    }
+    bf16x8 af[RT][KST];
 
-    __syncthreads();                                       // every wavefront has its fragments: the X tiles may come
-    BRA_TRACE(1);
-    const long ntiles = (M + 63) / 64;
-    const long tile0 = (long)blockIdx.x * tiles_per_wg;
-    const long tile1 = tile0 + tiles_per_wg < ntiles ? tile0 + tiles_per_wg : ntiles;
+    constexpr int ND = C >= 256 ? 1 : (NL <= 3 ? 4 : 2);     // tiles on their way in registers (a tile's X takes about five tiles' arithmetic to arrive)
     if (tile0 >= tile1) return;
+    for (int it = 0; it < ND + 2; ++it) table_entry(it);
+    __syncthreads();
     // Requests and stores are laid out so that the wait for a tile's X leaves the stores of the tile
     // before it pending: every tile of the main loop stores unconditionally (a ragged last tile is
     // handled after the loop), and every iteration requests a tile (past the end: the last one again).
-    constexpr int ND = C >= 256 ? 1 : (NL <= 3 ? 4 : 2);     // tiles on their way in registers (a tile's X takes about five tiles' arithmetic to arrive)
     u32x4 xr[ND][NL];
+    // slot q of a tile: region q >> sum_log2 of the tile, token (row, column) of the region
+    auto in_region = [&](int q) {
+        const int e = q & ((1 << tm.map_log2) - 1);
+        return (e >> tm.rw_log2) * tm.W + (e & ((1 << tm.rw_log2) - 1));
+    };
+    int f_reg[NL], f_off[NL];                             // region tiles: where this thread's chunks of a tile come from
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+        const int q = min((int)threadIdx.x + NTH * u, 64 * CH - 1) / CH;
+        f_reg[u] = q >> tm.map_log2;
+        f_off[u] = in_region(q);
+    }
     auto fetch = [&](long tile, u32x4 (&r)[NL]) {      // rows past M repeat the last token; their results are not stored
-        if (tile > tile1 - 1) tile = tile1 - 1;
+        const int it = (int)(tile - tile0);
 #pragma unroll
         for (int u = 0; u < NL; ++u) {
             const int idx = min((int)threadIdx.x + NTH * u, 64 * CH - 1);
-            long t = tile * 64 + idx / CH;
-            if (t >= M) t = M - 1;
+            const long t = rbase[(it & 7) * 64 + f_reg[u]] + f_off[u];
             r[u] = *(const u32x4 *)(X + t * C + (idx % CH) * 8);
         }
     };
@@ -677,9 +787,9 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
         constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct) {
-            f32x16 acc[2];
+            f32x16 acc[RT];
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
+            for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[rt][e] = 0.f;
             const bf16_t *xrow = xs0 + (cur * 64 + 32 * ct + c32) * XP + 8 * h;
@@ -687,50 +797,73 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
             for (int kst = 0; kst < KST; ++kst) {
                 const bf16x8 bfr = *(const bf16x8 *)(xrow + 16 * kst);
 #pragma unroll
-                for (int rt = 0; rt < 2; ++rt) acc[rt] = mfma32(af[rt][kst], bfr, acc[rt]);
+                for (int rt = 0; rt < RT; ++rt) acc[rt] = mfma32(af[rt][kst], bfr, acc[rt]);
             }
-            const long t = tile * 64 + 32 * ct + c32;
-            if ((FULL || t < M) && !(prep.trace & 2)) {
+            // The results are first read on the far side of a branch: the wait that this takes
+            // (11 idle issue slots after an 8-pass product) is spelled out here, where no branch
+            // lies between.
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_nop 11");
+            __builtin_amdgcn_sched_barrier(0);
+            const long slot = tile * 64 + 32 * ct + c32;
+            const long t = rbase[((int)(tile - tile0) & 7) * 64 + ((32 * ct + c32) >> tm.map_log2)] + in_region(32 * ct + c32);
+            if ((FULL || slot < M) && !(prep.trace & 2)) {
                 // Q may leave multiplied by a factor (the attention kernel that wants its scores in
                 // units of log2 passes scale * log2 e): one rounding, of the scaled value
-                const float os = sel == 0 ? qscale : 1.0f;
+                auto put = [&](float os) {
 #pragma unroll
-                for (int rt = 0; rt < 2; ++rt) {
-                    u32x4 *dst = (u32x4 *)(out + t * C + base + 32 * rt + 16 * h);
-                    const u32x4 lo = {pack_bf16(acc[rt][0] * os, acc[rt][1] * os), pack_bf16(acc[rt][2] * os, acc[rt][3] * os),
-                                      pack_bf16(acc[rt][4] * os, acc[rt][5] * os), pack_bf16(acc[rt][6] * os, acc[rt][7] * os)};
-                    const u32x4 hi = {pack_bf16(acc[rt][8] * os, acc[rt][9] * os), pack_bf16(acc[rt][10] * os, acc[rt][11] * os),
-                                      pack_bf16(acc[rt][12] * os, acc[rt][13] * os), pack_bf16(acc[rt][14] * os, acc[rt][15] * os)};
-                    if (smode == 1) { store16<1>(dst, lo); store16<1>(dst + 1, hi); }
-                    else if (smode == 2) { store16<2>(dst, lo); store16<2>(dst + 1, hi); }
-                    else { store16<0>(dst, lo); store16<0>(dst + 1, hi); }
-                }
+                    for (int rt = 0; rt < RT; ++rt) {
+                        u32x4 *dst = (u32x4 *)(out + t * C + base + 32 * rt + 8 * h);
+                        const u32x4 lo = {pack_bf16(acc[rt][0] * os, acc[rt][1] * os), pack_bf16(acc[rt][2] * os, acc[rt][3] * os),
+                                          pack_bf16(acc[rt][4] * os, acc[rt][5] * os), pack_bf16(acc[rt][6] * os, acc[rt][7] * os)};
+                        const u32x4 hi = {pack_bf16(acc[rt][8] * os, acc[rt][9] * os), pack_bf16(acc[rt][10] * os, acc[rt][11] * os),
+                                          pack_bf16(acc[rt][12] * os, acc[rt][13] * os), pack_bf16(acc[rt][14] * os, acc[rt][15] * os)};
+                        if (smode == 1) { store16<1>(dst, lo); store16<1>(dst + 2, hi); }
+                        else if (smode == 2) { store16<2>(dst, lo); store16<2>(dst + 2, hi); }
+                        else { store16<0>(dst, lo); store16<0>(dst + 2, hi); }
+                    }
+                };
+                if (sel == 0 && qscale != 1.0f) put(qscale);
+                else put(1.0f);      // a constant: no multiplication is left
             }
             if (P && sel < 2) {      // M is a multiple of the group: a group is whole or absent
                 // one branch around the whole sum, not one per element
                 if (group_log2 >= 2) {
 #pragma unroll
-                    for (int rt = 0; rt < 2; ++rt)
+                    for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
                         for (int e = 0; e < 16; ++e)
                             acc[rt][e] = dpp_fadd<0x4E>(dpp_fadd<0xB1>(acc[rt][e]));      // quad_perm [1,0,3,2], then [2,3,0,1]
+                    if (group_log2 >= 3) {
+#pragma unroll
+                        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) acc[rt][e] = dpp_fadd<0x141>(acc[rt][e]);      // row_half_mirror: the other quad of 8 lanes
+                    }
+                    if (group_log2 >= 4) {
+#pragma unroll
+                        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) acc[rt][e] = dpp_fadd<0x140>(acc[rt][e]);      // row_mirror: the other half of 16 lanes
+                    }
                 } else if (group_log2 == 1) {
 #pragma unroll
-                    for (int rt = 0; rt < 2; ++rt)
+                    for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
                         for (int e = 0; e < 16; ++e) acc[rt][e] = dpp_fadd<0xB1>(acc[rt][e]);
                 }
-                if ((FULL || t < M) && (c32 & (group - 1)) == 0 && !(prep.trace & 4)) {
+                if ((FULL || slot < M) && (c32 & (group - 1)) == 0 && !(prep.trace & 4)) {
 #pragma unroll
-                    for (int rt = 0; rt < 2; ++rt) {
-                        f32x4 *dst = (f32x4 *)(P + (t >> group_log2) * 2 * C + sel * C + base + 32 * rt + 16 * h);
+                    for (int rt = 0; rt < RT; ++rt) {
+                        f32x4 *dst = (f32x4 *)(P + (slot >> group_log2) * 2 * C + sel * C + base + 32 * rt + 8 * h);
 #pragma unroll
                         for (int q4 = 0; q4 < 4; ++q4) {
                             const f32x4 pv = {acc[rt][4 * q4], acc[rt][4 * q4 + 1], acc[rt][4 * q4 + 2], acc[rt][4 * q4 + 3]};
                             const u32x4 pu = __builtin_bit_cast(u32x4, pv);
-                            if (smode == 1) store16<1>(dst + q4, pu);
-                            else if (smode == 2) store16<2>(dst + q4, pu);
-                            else store16<0>(dst + q4, pu);
+                            f32x4 *d4 = dst + q4 + 2 * (q4 / 2);      // results 8 .. 15: 16 channels on
+                            if (smode == 1) store16<1>(d4, pu);
+                            else if (smode == 2) store16<2>(d4, pu);
+                            else store16<0>(d4, pu);
                         }
                     }
                 }
@@ -741,6 +874,40 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
     // LDS, whether or not it exists (past the end: the last tile again, into a buffer nobody reads).
 #pragma unroll
     for (int d = 0; d < ND; ++d) fetch(tile0 + d, xr[d]);
+    // the weight fragments, while the first tiles are on their way
+    {
+        bf16_t *wb = (bf16_t *)smem + wave * 64 * WP;      // in the X tiles' place: they are staged afterwards
+        const bf16_t *wsrc = W + sel * C + base;
+        const int gg = c32 / 16;
+#pragma unroll
+        for (int kc = 0; kc < C / 64; ++kc) {
+            constexpr int WCH = CW / 8;                  // 16-byte chunks of a staged row
+            u32x4 wr[WCH];
+#pragma unroll
+            for (int u = 0; u < WCH; ++u) {
+                const int idx = lane + 64 * u;
+                wr[u] = *(const u32x4 *)(wsrc + (size_t)(64 * kc + idx / WCH) * (NMAT * C) + (idx % WCH) * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < WCH; ++u) {
+                const int idx = lane + 64 * u;
+                *(u32x4 *)(wb + (idx / WCH) * WP + (idx % WCH) * 8) = wr[u];
+            }
+#pragma unroll
+            for (int kl = 0; kl < 4; ++kl)
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    const bf16_t *src = wb + (16 * kl + 8 * h + i / 4) * WP + 32 * rt + 16 * gg + 8 * ((i % 4) % 2) +
+                                        4 * ((i % 4) / 2);
+                    const s16x4 v0 = lds_read_tr16(src), v1 = lds_read_tr16(src + 4 * WP);
+                    const u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+                    const u32x4 av = {a0[0], a0[1], a1[0], a1[1]};
+                    af[rt][4 * kc + kl] = __builtin_bit_cast(bf16x8, av);
+                }
+        }
+    }
+    __syncthreads();                                       // every wavefront has its fragments: the X tiles may take the weights' place
+    BRA_TRACE(1);
     stage(0, xr[0]);
     fetch(tile0 + ND, xr[0]);
     __syncthreads();
@@ -754,6 +921,7 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
             if (tile < tfull) project(tile, cur, std::true_type{});
             stage(cur ^ 1, xr[(d + 1) % ND]);      // the other buffer was last read before the previous barrier
             fetch(tile + 1 + ND, xr[(d + 1) % ND]);
+            table_entry(tile - tile0 + ND + 2);
             __syncthreads();
             if (tile == tile0) BRA_TRACE(3);
         }
@@ -1275,9 +1443,32 @@ int pool_group_log2(const Dims &D)
     return lg;
 }
 
+// The projection kernel can walk over whole regions (n a power of two, at most 16 tokens, so that a
+// region's sum is one reduction inside a row of 16 lanes).
+bool region_tiles_ok(const Dims &D)
+{
+    static const bool off = experiment_flag("BRA_NO_REGION_TILES");
+    return !off && D.n <= 16 && (D.n & (D.n - 1)) == 0 && (D.rw & (D.rw - 1)) == 0;
+}
+
+TileMap tile_map(const Dims &D, bool pooled)
+{
+    TileMap tm = {0, 0, 0, 0, D.R, D.S, D.rh, D.rw, D.W, D.N, D.B * D.R};
+    if (!pooled) return tm;
+    if (region_tiles_ok(D)) {
+        tm.region_tiles = 1;
+        while ((1 << tm.sum_log2) < D.n) ++tm.sum_log2;
+        while ((1 << tm.rw_log2) < D.rw) ++tm.rw_log2;
+        tm.map_log2 = tm.sum_log2;
+    } else {
+        tm.sum_log2 = pool_group_log2(D);
+    }
+    return tm;
+}
+
 bool pooled_projection(const Dims &D)
 {
-    return fast_route_ok(D) && D.rh * (D.rw >> pool_group_log2(D)) <= 8;
+    return fast_route_ok(D) && (region_tiles_ok(D) || D.rh * (D.rw >> pool_group_log2(D)) <= 8);
 }
 
 MfmaWs carve(const Dims &D, void *ws)
@@ -1363,6 +1554,12 @@ int launch_route_p(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, h
     // 8 query regions per workgroup (2 per wavefront) where two workgroups fit a compute unit
     // (the K^r tile takes C x 260 bytes of LDS): twice the workgroups, half the serial affinity /
     // top-k work in each.  Measured: C = 128 12.6 -> 10.8 us, C = 256 (one per unit) 17.3 -> 22.1 us.
+    if (region_tiles_ok(D) && !experiment_flag("BRA_ROUTE_OLD")) {
+        ProfScope ps(st, K_MFMA_ROUTE_ROWS);
+        hipLaunchKernelGGL((k_route_w<C>), dim3((D.B * ((D.R + 15) / 16) + 7) / 8 * 8), dim3(256), 0, st, w.p, Ir,
+                           Ar_opt, D);
+        return BRA_OK;
+    }
     static const int forced = (int)experiment_value("BRA_ROUTE_ROWS", 0);
     const bool rows8 = forced ? forced == 8 : 2 * RouteSmem<C>::kq_bytes <= (size_t)kMaxLds;
     ProfScope ps(st, K_MFMA_ROUTE_ROWS);
@@ -1370,12 +1567,14 @@ int launch_route_p(const Dims &D, const MfmaWs &w, int32_t *Ir, float *Ar_opt, h
         static bool opted = false;
         if (!lds_opt_in(k_route_p<C, 2>, opted)) return BRA_ERR_LAUNCH;
         hipLaunchKernelGGL((k_route_p<C, 2>), dim3((D.B * ((D.R + 7) / 8) + 7) / 8 * 8), dim3(256),
-                           RouteSmem<C>::kq_bytes, st, w.p, Ir, Ar_opt, D, pool_group_log2(D));
+                           RouteSmem<C>::kq_bytes, st, w.p, Ir, Ar_opt, D, pool_group_log2(D),
+                           (int)region_tiles_ok(D) | (experiment_flag("BRA_ROUTE_TRACE") ? 2 : 0));
     } else {
         static bool opted = false;
         if (!lds_opt_in(k_route_p<C, 4>, opted)) return BRA_ERR_LAUNCH;
         hipLaunchKernelGGL((k_route_p<C, 4>), dim3((D.B * ((D.R + 15) / 16) + 7) / 8 * 8), dim3(256),
-                           RouteSmem<C>::kq_bytes, st, w.p, Ir, Ar_opt, D, pool_group_log2(D));
+                           RouteSmem<C>::kq_bytes, st, w.p, Ir, Ar_opt, D, pool_group_log2(D),
+                           (int)region_tiles_ok(D) | (experiment_flag("BRA_ROUTE_TRACE") ? 2 : 0));
     }
     return BRA_OK;
 }
@@ -1387,23 +1586,25 @@ int launch_qkv(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const MfmaWs 
                const PrepArgs &prep, hipStream_t st, float qscale = 1.0f)
 {
     const long M = (long)D.B * D.N;
-    constexpr int WPB = (C == 256) ? 4 : 3 * C / 64;      // wavefronts (64-channel groups) per workgroup
+    constexpr int RT = 1;                                  // 32 output channels per wavefront
+    constexpr int WPB = (C == 256) ? 8 : 3 * C / 32;      // wavefronts per workgroup
     const long ntiles = (M + 63) / 64;
-    // about two workgroups per compute unit (what LDS and registers allow): every wavefront keeps
-    // its weight slice in registers and the workgroup streams its share of the tokens
-    const int gy = 3 * C / 64 / WPB;
-    const long slots = experiment_value("BRA_QKV_SLOTS", 512);
+    // one workgroup per compute unit (what the registers allow for the wider ones; a second round of
+    // workgroups would start when the first is done): every wavefront keeps its weight slice in
+    // registers and the workgroup streams its share of the tokens
+    const int gy = 3 * C / (32 * RT) / WPB;
+    const long slots = experiment_value("BRA_QKV_SLOTS", C == 64 ? 512 : 256);
     long tpw = (ntiles * gy + slots - 1) / slots;
     static const int forced = (int)experiment_value("BRA_QKV_TPW", 0);
     if (forced >= 1 && forced <= 4096) tpw = forced;
     const int gx = (int)((ntiles + tpw - 1) / tpw);
     const int prep_blocks = (prep.elems + 64 * WPB - 1) / (64 * WPB);
-    const size_t smem = std::max((size_t)2 * 64 * (C + 16) * 2, (size_t)WPB * 64 * 72 * 2);
+    const size_t smem = kQkvSmem<C, WPB, RT>;
     static bool opted = false;
-    if (!lds_opt_in(k_qkv<C, WPB, 3>, opted)) return BRA_ERR_LAUNCH;
+    if (!lds_opt_in(k_qkv<C, WPB, 3, RT>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_QKV);
-    hipLaunchKernelGGL((k_qkv<C, WPB, 3>), dim3(gx + prep_blocks, gy), dim3(64 * WPB), smem, st, X, Wqkv, w.q,
-                       w.k, w.v, pooled ? w.p : nullptr, pool_group_log2(D), M, (int)tpw, gx, prep, qscale);
+    hipLaunchKernelGGL((k_qkv<C, WPB, 3, RT>), dim3(gx + prep_blocks, gy), dim3(64 * WPB), smem, st, X, Wqkv, w.q,
+                       w.k, w.v, pooled ? w.p : nullptr, tile_map(D, pooled), M, (int)tpw, gx, prep, qscale);
     return BRA_OK;
 }
 
@@ -1413,15 +1614,16 @@ template <int C>
 int launch_wo(const Dims &D, const bf16_t *O, const bf16_t *Wo, bf16_t *Y, hipStream_t st)
 {
     const long M = (long)D.B * D.N;
-    constexpr int WPB = C / 64;
+    constexpr int RT = 1, WPB = C / (32 * RT);
     const long ntiles = (M + 63) / 64;
     const long tpw = (ntiles + 511) / 512;
     const int gx = (int)((ntiles + tpw - 1) / tpw);
-    const size_t smem = std::max((size_t)2 * 64 * (C + 16) * 2, (size_t)WPB * 64 * 72 * 2);
+    const size_t smem = kQkvSmem<C, WPB, RT>;
     static bool opted = false;
-    if (!lds_opt_in(k_qkv<C, WPB, 1>, opted)) return BRA_ERR_LAUNCH;
+    if (!lds_opt_in(k_qkv<C, WPB, 1, RT>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_WO);
-    hipLaunchKernelGGL((k_qkv<C, WPB, 1>), dim3(gx, 1), dim3(64 * WPB), smem, st, O, Wo, Y, Y, Y, nullptr, 0, M,
+    hipLaunchKernelGGL((k_qkv<C, WPB, 1, RT>), dim3(gx, 1), dim3(64 * WPB), smem, st, O, Wo, Y, Y, Y, nullptr,
+                       tile_map(D, false), M,
                        (int)tpw, gx, PrepArgs{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0}, 1.0f);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }

@@ -110,16 +110,20 @@ struct SmallSmem {
     static constexpr int CS = C + 8, XP = C + 16;
     static constexpr size_t kv_bytes = (size_t)2 * 64 * XP * 2;
     static constexpr size_t lt_bytes = (size_t)C * kLTP * 4;
-    __host__ __device__ static size_t o_off(int hrows)   // [16][CS] bf16: O = attention + LCE
+    __host__ __device__ static size_t o_off(int hrows)   // [16][CS] bf16: O = attention + LCE, behind the halo and LCE tiles
     {
-        const size_t second = (size_t)hrows * CS * 2 + lt_bytes;
+        return (size_t)hrows * CS * 2 + lt_bytes;
+    }
+    static size_t bytes(int hrows)
+    {
+        const size_t second = o_off(hrows) + (size_t)16 * CS * 2;
         return kv_bytes > second ? kv_bytes : second;
     }
-    static size_t bytes(int hrows) { return o_off(hrows) + (size_t)16 * CS * 2; }
 };
 
 template <int C>
-__global__ __launch_bounds__(256) void k_small(AttnArgs A, Dims D, int log2n)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(C <= 128 ? 4 : 2, 4)))
+void k_small(AttnArgs A, Dims D, int log2n)
 {
     typedef SmallSmem<C> SM;
     constexpr int HEADS = C / 32, HPW = (HEADS + 3) / 4, CS = SM::CS, XP = SM::XP, KS = C / 32, CH = C / 8;
