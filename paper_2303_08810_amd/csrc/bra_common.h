@@ -109,6 +109,14 @@ int generic_forward(const Dims &D, const void *X, const void *Wqkv, const void *
                     void *ws, hipStream_t st);
 bool generic_supported(const Dims &D);
 
+// float32 tensors with 4 x 4 regions, heads of 32 channels and at most 64 routed keys: two launches on
+// the float32 matrix-core instruction (bra_f32_small.hip).  qkv [B N, 3C], pq, pk [B R, C] float32.
+bool f32_small_ok(const Dims &D);
+int f32_small_forward(const Dims &D, const float *X, const float *Wqkv, const float *Wo, const float *Wlce, float *Y,
+                      int32_t *Ir_out_opt, const int32_t *Ir_in_opt, float *qkv, float *pq, float *pk, hipStream_t st);
+int f32_small_route(const Dims &D, const float *X, const float *Wqkv, int32_t *Ir, float *Ar_opt, float *qkv,
+                    float *pq, float *pk, hipStream_t st);
+
 size_t valu_route_scratch_bytes(const Dims &D);
 // Rows of A^r = Q^r (K^r)^T and their top-k from float32 Q^r, K^r [B, R, C] (any region count
 // that generic_supported accepts).

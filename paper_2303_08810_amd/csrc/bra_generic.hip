@@ -8,6 +8,7 @@
 // Region pooling uses mean(X^r) W = mean(X^r W), which is exact in real arithmetic
 // (the mean is linear; same argument as Appendix A).
 #include "bra_common.h"
+#include <type_traits>
 
 #include <math.h>
 
@@ -419,6 +420,10 @@ int forward_t(const Dims &D, const T *X, const T *Wqkv, const T *Wo, const T *Wl
               int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, hipStream_t st)
 {
     GenericWs w = carve(D, ws);
+    if constexpr (std::is_same<T, float>::value) {
+        if (f32_small_ok(D))
+            return f32_small_forward(D, X, Wqkv, Wo, Wlce, Y, Ir_out_opt, Ir_in_opt, w.qkv, w.qr, w.kr, st);
+    }
     const long M = (long)D.B * D.N;
     const int32_t *Ir = Ir_in_opt;
     if (!Ir_in_opt) {
@@ -969,6 +974,8 @@ int generic_route(const Dims &D, const void *X, const void *Wqkv, int32_t *Ir, f
                   void *ws, hipStream_t st)
 {
     GenericWs w = carve(D, ws);
+    if (f32_small_ok(D))      // the kernels that bra_forward runs for this shape, so that both give the same index
+        return f32_small_route(D, (const float *)X, (const float *)Wqkv, Ir, Ar_opt, w.qkv, w.qr, w.kr, st);
     if (D.dtype == BRA_F32)
         launch_route<float>(D, (const float *)X, (const float *)Wqkv, Ir, Ar_opt, w, st);
     else

@@ -669,7 +669,7 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
            bf16_t *__restrict__ K, bf16_t *__restrict__ V, float *__restrict__ P, TileMap tm, long M,
            int tiles_per_wg, int gx, PrepArgs prep, float qscale)
 {
-    constexpr int KS = C / 32, CH = C / 8, XP = C + 16, NTH = 64 * WPB;
+    constexpr int CH = C / 8, XP = C + 16, NTH = 64 * WPB;
     constexpr size_t kTableOff = kQkvTableOff<C, WPB, RT>;  // region tiles: first tokens of the regions of 8 tiles
     constexpr int NL = (64 * CH + NTH - 1) / NTH;       // 16-byte chunks of a tile per thread
     constexpr int CW = 32 * RT;                         // output channels of a wavefront
@@ -697,7 +697,7 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
     constexpr int smode = 0;
 #endif
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int g = lane / 16, i = lane % 16;
+    const int i = lane % 16;
     const int grp = blockIdx.y * WPB + wave;            // channel group among NMAT C / CW
     const int sel = grp / (C / CW), base = (grp % (C / CW)) * CW;
     bf16_t *__restrict__ out = sel == 0 ? Q : (sel == 1 ? K : V);

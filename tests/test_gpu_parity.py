@@ -66,6 +66,35 @@ def test_generic_path_small_shapes(B, H, W, C, heads, S, k, dtype):
     assert err < (1e-4 if dtype == "f32" else 4e-2)
 
 
+F32_SMALL = [  # float32, 4 x 4 regions, heads of 32 channels, k n <= 64: the two-launch float32 kernels
+    (1, 28, 28, 64, 2, 7, 4),
+    (2, 16, 16, 128, 4, 4, 3),
+    (3, 8, 8, 64, 2, 2, 1),
+    (2, 12, 12, 64, 2, 3, 4),      # image borders on every region
+    (1, 32, 32, 128, 4, 8, 2),     # R = 64
+    (2, 4, 4, 64, 2, 1, 1),        # S = 1: one region
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,S,k", F32_SMALL)
+def test_f32_small_regions(B, H, W, C, heads, S, k):
+    X, Wqkv, Wo, Wlce = make_inputs(B, H, W, C, seed=2000 + 3 * H + C + k, dtype="f32")
+    err = compare(X, Wqkv, Wo, Wlce, "f32", S, k, heads, "auto")
+    assert err < 1e-4
+    compare(X, Wqkv, Wo, Wlce, "f32", S, k, heads, "generic", scale=0.3)
+
+
+def test_f32_small_forced_routing():
+    B, H, W, C, heads, S, k = 2, 16, 16, 64, 2, 4, 3
+    X, Wqkv, Wo, Wlce = make_inputs(B, H, W, C, seed=2100, dtype="f32")
+    rng = np.random.default_rng(7)
+    Ir_in = np.stack([np.stack([rng.permutation(S * S)[:k] for _ in range(S * S)]) for _ in range(B)]).astype(np.int32)
+    Y, Ir, _, _ = gpu_forward(X, Wqkv, Wo, Wlce, "f32", S, k, heads, "auto", Ir_in=Ir_in)
+    assert np.array_equal(Ir, Ir_in)
+    ref = run_oracle(X, Wqkv, Wo, Wlce, dict(S=S, k=k, heads=heads, scale=None), Ir_in=Ir_in)
+    check_output(Y, ref["Y"], "f32")
+
+
 MFMA_SHAPES = [  # (B, H, W, C, heads, S, k): regions of n >= 64 tokens, d = 32
     (2, 16, 16, 64, 2, 2, 1),
     (2, 16, 16, 64, 2, 2, 3),
