@@ -1126,10 +1126,9 @@ void k_attn_big(AttnArgs A, Dims D)
 template <int RW>
 struct FusedSmem {
     static constexpr int C = 64;
-    static constexpr int XS = C + 8;                                  // routed X tile
-    static constexpr int HS = C;                                      // X halo tile: no padding, 16-byte chunk c of row r sits at c ^ ((r >> 1) & 7)
+    static constexpr int XS = C + 8;                                  // X tiles
     static constexpr int KP = C + 8;                                  // K tile
-    static constexpr int VP = C + 8;                                  // V tile
+    static constexpr int VP = C + 16;                                 // V tile
     static constexpr int PL = 68;                                     // LCE tile: floats per channel
     static constexpr int QH = 64 / RW;                                // rows of the query tile
     static constexpr int HW = RW + 4, HROWS = (QH + 4) * HW;          // halo tile
@@ -1140,10 +1139,10 @@ struct FusedSmem {
     static constexpr size_t v_off = k_off + (size_t)64 * XS * 2;      // V tile
     static constexpr size_t l_off = 0;                                // LCE tile, over K and V
     static constexpr size_t h_off = v_off + (size_t)64 * VP * 2;      // X halo -> V halo planes
-    static constexpr size_t xh_bytes = (size_t)NHT * 16 * HS * 2;
+    static constexpr size_t xh_bytes = (size_t)NHT * 16 * XS * 2;
     static constexpr size_t vt_bytes = (size_t)C * PS * 2;
-    static constexpr size_t r_off = v_off;                            // routing: 8 words, before V exists
-    static constexpr size_t bytes = h_off + (xh_bytes > vt_bytes ? xh_bytes : vt_bytes);   // 36 KB: four workgroups per compute unit
+    static constexpr size_t r_off = h_off + (xh_bytes > vt_bytes ? xh_bytes : vt_bytes);   // routing: 8 words
+    static constexpr size_t bytes = r_off + 32;
     static_assert(KP <= XS && (size_t)C * PL * 4 <= h_off, "tiles that share a slot must fit");
 };
 
@@ -1160,12 +1159,12 @@ __device__ __forceinline__ u32x4 pair_halves(u32x2 a, u32x2 b)
 }
 
 template <int RW>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(60)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4)))
 void k_fused(AttnArgs A, Dims D)
 {
     typedef FusedSmem<RW> SM;
     constexpr int C = 64, HEADS = C / 32, KS = C / 32, CH = C / 8, NCT = C / 16;
-    constexpr int XS = SM::XS, HS = SM::HS, KP = SM::KP, VP = SM::VP, PL = SM::PL;
+    constexpr int XS = SM::XS, KP = SM::KP, VP = SM::VP, PL = SM::PL;
     constexpr int QH = SM::QH, HW = SM::HW, HROWS = SM::HROWS, NHT = SM::NHT, PS = SM::PS;
     constexpr int NBH = (HROWS * CH + 255) / 256;      // halo chunks per thread
     constexpr int NBT = CH / 4;                 // chunks per thread of a 64-row tile
@@ -1224,16 +1223,16 @@ void k_fused(AttnArgs A, Dims D)
         wk[ks] = fragment(NCT + wave, ks);
         wv[ks] = fragment(2 * NCT + wave, ks);
     }
-    const int lb = lane / 4, xi = lane % 4;      // LCE: lane = (channel block lb, output offset xi)
+    // LCE weights as 4x4x4 A operands: lane = (channel block lb, output offset xi).
+    const int lb = lane / 4, xi = lane % 4;
+    s16x4 aw[5][2];
+#pragma unroll
+    for (int r = 0; r < 10; ++r)
+        aw[r / 2][r % 2] = *(const s16x4 *)(A.Wa + ((size_t)(wave * 10 + r) * kWave + lane) * 4);
     u32x4 kreg[NBT];
     const int jy = fast_div(j, s_inv);
     tile_load<C, NBT>(kreg, Ximg, jy * D.rh, (j - jy * D.S) * RW, RW, rw_inv, 64, D.H, D.W, 0);
-#pragma unroll
-    for (int u = 0; u < NBH; ++u) {
-        const int idx = (int)threadIdx.x + 256 * u;
-        const int row = idx / CH, cc = idx % CH;
-        if (row < HROWS) *(u32x4 *)(Hs + row * HS + ((cc ^ ((row >> 1) & 7)) * 8)) = hreg[u];
-    }
+    tile_store<C, XS, NBH>(Hs, hreg, HROWS, 0);
     tile_store<C, XS, NBT>(Ks, kreg, 64, 0);
     __syncthreads();
     BRA_TRACE(2);
@@ -1243,11 +1242,10 @@ void k_fused(AttnArgs A, Dims D)
     const int qy = fast_div(q, rw_inv);
     bf16x8 qb[HEADS];
     {
-        const int qrow = (qy + 2) * HW + q - qy * RW + 2;                          // query token in the halo
-        const bf16_t *xq = Hs + qrow * HS;
+        const bf16_t *xq = Hs + ((qy + 2) * HW + q - qy * RW + 2) * XS + 8 * g;   // query token in the halo
         bf16x8 bq[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) bq[ks] = *(const bf16x8 *)(xq + (((4 * ks + g) ^ ((qrow >> 1) & 7)) * 8));
+        for (int ks = 0; ks < KS; ++ks) bq[ks] = *(const bf16x8 *)(xq + 32 * ks);
 #pragma unroll
         for (int h = 0; h < HEADS; ++h) {
             f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f};
@@ -1260,6 +1258,13 @@ void k_fused(AttnArgs A, Dims D)
             qb[h] = pack8(v);
         }
     }
+    // W^o fragments (rows and contraction slots permuted) take over the registers of Wq.
+    bf16x8 wo[4][KS];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) wo[tt][ks] = fragment(3 * NCT + tt, ks);
+
     // K, V of the routed block: D^T[channel 16 w + 4 g + jj][token i], a lane ends up with
     // 4 consecutive channels of one token.  V halo: operands swapped, D[token 4 g + jj]
     // [channel i], 4 consecutive halo tokens of one channel.
@@ -1279,14 +1284,10 @@ void k_fused(AttnArgs A, Dims D)
     }
 #pragma unroll
     for (int hu = 0; hu < NHT; ++hu) {
-        const bf16_t *xh = Hs + (16 * hu + i) * HS;
+        const bf16_t *xh = Hs + (16 * hu + i) * XS + 8 * g;
         f32x4 a = {0.f, 0.f, 0.f, 0.f};
-#ifdef BRA_EXPERIMENT
-        if (A.trace & 2) { vh[hu] = u32x2{0u, 0u}; continue; }
-#endif
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            a = mfma16(*(const bf16x8 *)(xh + (((4 * ks + g) ^ ((i >> 1) & 7)) * 8)), wv[ks], a);
+        for (int ks = 0; ks < KS; ++ks) a = mfma16(*(const bf16x8 *)(xh + 32 * ks), wv[ks], a);
         vh[hu] = pack4(a);
     }
     __syncthreads();   // every X tile has been read
@@ -1313,19 +1314,6 @@ void k_fused(AttnArgs A, Dims D)
     // in a fair interleave with workgroups that have only just started.  Measured: -3 %.
     __builtin_amdgcn_s_setprio(2);
     BRA_TRACE(4);
-    // W^o fragments (rows and contraction slots permuted): requested now, needed after the LCE.
-    // (Requested any earlier they would lift the register count past the 120 that four
-    // workgroups per compute unit allow.)
-    bf16x8 wo[4][KS];
-#pragma unroll
-    for (int tt = 0; tt < 4; ++tt)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) wo[tt][ks] = fragment(3 * NCT + tt, ks);
-    // LCE weights as 4x4x4 A operands, likewise.
-    s16x4 aw[5][2];
-#pragma unroll
-    for (int r = 0; r < 10; ++r)
-        aw[r / 2][r % 2] = *(const s16x4 *)(A.Wa + ((size_t)(wave * 10 + r) * kWave + lane) * 4);
     // Attention of the 16 queries over the 64 keys (Eq. 1 with one routed block).
     SoftmaxState<HEADS> st;
     st.init();
@@ -1701,7 +1689,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     A.Xr = w.xr; A.U = w.u;
     A.c_exp = c_exp;
     A.total = D.B * D.R * (D.n / 64);
-    A.trace = (int)experiment_value("BRA_Q32_TRACE", 0);
+    A.trace = experiment_flag("BRA_Q32_TRACE");
     const int grid = ((A.total + 7) / 8) * 8;
     const int hrows = halo_rows(D);
 
