@@ -118,6 +118,13 @@ struct PrepArgs {
     bf16_t *WT, *WoT, *Wa, *Wf;
     int elems;                      // leading prep elements to produce (0: none)
     int trace = 0;                  // experiment builds: leave phase timestamps in Q
+    // The projection kernel can carry the routing from pooled X along (it needs WT, so not in a launch
+    // whose prep elements are still being produced): workgroups past the prep ones, one per
+    // (image, 16 query regions).
+    const float *Xr = nullptr;
+    int32_t *Ir = nullptr;
+    int route_items = 0;
+    Dims dims = {};
 };
 
 // `total` = prep_total(C) (all weights) or 3 C^2 (projection weights only; Wo and Wlce
@@ -384,21 +391,19 @@ struct RouteSmem {
     static constexpr size_t bytes = xs_bytes > kq_bytes ? xs_bytes : kq_bytes;
 };
 
+// Work item `wid` = (image, 16 query regions), by the first 256 threads of a workgroup (all of them
+// reach every barrier of this function); smem: RouteSmem<C>::bytes.
 template <int C>
-__global__ __launch_bounds__(256) void k_route(const float *__restrict__ Xr,
-                                               const bf16_t *__restrict__ WT,
-                                               int32_t *__restrict__ Ir, float *__restrict__ Ar,
-                                               Dims D)
+__device__ __forceinline__ void route_body(const float *__restrict__ Xr, const bf16_t *__restrict__ WT,
+                                           int32_t *__restrict__ Ir, float *__restrict__ Ar, const Dims &D,
+                                           char *smem, int wid)
 {
     typedef RouteSmem<C> SM;
     constexpr int CK = SM::CK, XP = SM::XP, QS = SM::QS, KSC = CK / 32, NCW = C / 64;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *xs = (bf16_t *)smem;                  // [3][64][XP]
     float *Kt = (float *)smem;                    // [C / 4][kRouteRS][4]
     float *Qs = Kt + C * kRouteRS;                // [16][QS]
     const int groups = (D.R + 15) / 16;
-    const int wid = swizzled_block();          // the workgroups of an image share an XCD (and its L2)
-    if (wid >= D.B * groups) return;
     const int b = wid / groups, myrt = wid % groups;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
@@ -478,6 +483,18 @@ __global__ __launch_bounds__(256) void k_route(const float *__restrict__ Xr,
     __syncthreads();
 
     route_rows_from_lds<C>(Kt, Qs, b, myrt, D, Ir, Ar);
+}
+
+template <int C>
+__global__ __launch_bounds__(256) void k_route(const float *__restrict__ Xr,
+                                               const bf16_t *__restrict__ WT,
+                                               int32_t *__restrict__ Ir, float *__restrict__ Ar,
+                                               Dims D)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int wid = swizzled_block();          // the workgroups of an image share an XCD (and its L2)
+    if (wid >= D.B * ((D.R + 15) / 16)) return;
+    route_body<C>(Xr, WT, Ir, Ar, D, smem, wid);
 }
 
 // Routing from the partial sums that the projection kernel leaves behind (P[token / group]
@@ -649,8 +666,9 @@ struct TileMap {
 // of the NMAT matrices and keeps its weight fragments in registers; a workgroup is
 // WPB such wavefronts (blockIdx.y selects which; a multiple of 4 per compute unit keeps its four
 // SIMDs equally busy) and walks over `tiles_per_wg`
-// consecutive tiles of 64 tokens (blockIdx.x < gx; workgroups beyond that rearrange the
-// weights for the kernels that follow).  A tile of X is fetched once per workgroup with
+// consecutive tiles of 64 tokens (gx such workgroups; those before them route from pooled X, those
+// after them rearrange the weights for the kernels that follow, when the launch carries such work).
+// A tile of X is fetched once per workgroup with
 // fully coalesced 16-byte loads (one tile ahead, held in registers while the current
 // tile is computed), staged in LDS, and read from there as MFMA operands by all the
 // wavefronts.  The product is formed transposed (rows = output channels, columns =
@@ -676,9 +694,18 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
     constexpr int WP = CW + 8;                          // row pitch of a wavefront's weight staging tile
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *xs0 = (bf16_t *)smem;
-    if ((int)blockIdx.x >= gx) {                        // workgroups past the token tiles rearrange weights
+    // The first workgroups route (a long chain of dependent steps: started first, it ends within the
+    // projection), the last ones rearrange weights.
+    if ((int)blockIdx.x < prep.route_items) {
+        // wavefronts past the fourth leave: a barrier waits for the surviving ones only
+        if (blockIdx.y == 0 && threadIdx.x < 256)
+            route_body<C>(prep.Xr, prep.WT, prep.Ir, nullptr, prep.dims, smem, (int)blockIdx.x);
+        return;
+    }
+    const int bx = (int)blockIdx.x - prep.route_items;
+    if (bx >= gx) {
         if (blockIdx.y == 0) {
-            const int e = ((int)blockIdx.x - gx) * NTH + (int)threadIdx.x;
+            const int e = (bx - gx) * NTH + (int)threadIdx.x;
             if (e < prep.elems)
                 prep_weight_element(prep.Wqkv, prep.Wo, prep.Wlce, prep.WT, prep.WoT, prep.Wa, prep.Wf, C, e);
         }
@@ -703,7 +730,7 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
     bf16_t *__restrict__ out = sel == 0 ? Q : (sel == 1 ? K : V);
     const int group_log2 = tm.sum_log2, group = 1 << group_log2;
     const long ntiles = (M + 63) / 64;
-    const long tile0 = (long)blockIdx.x * tiles_per_wg;
+    const long tile0 = (long)bx * tiles_per_wg;
     const long tile1 = tile0 + tiles_per_wg < ntiles ? tile0 + tiles_per_wg : ntiles;
     // rbase[(tile - tile0) % 8][j] = first token of region j of the tile (plain: token of slot j).  The
     // entry of a tile is written (by the first 64 >> map_log2 threads) at least one barrier before its
@@ -1598,8 +1625,8 @@ int launch_qkv(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const MfmaWs 
     static const int forced = (int)experiment_value("BRA_QKV_TPW", 0);
     if (forced >= 1 && forced <= 4096) tpw = forced;
     const int gx = (int)((ntiles + tpw - 1) / tpw);
-    const int prep_blocks = (prep.elems + 64 * WPB - 1) / (64 * WPB);
-    const size_t smem = kQkvSmem<C, WPB, RT>;
+    const int prep_blocks = (prep.elems + 64 * WPB - 1) / (64 * WPB) + prep.route_items;
+    const size_t smem = std::max(kQkvSmem<C, WPB, RT>, prep.route_items ? RouteSmem<C>::bytes : (size_t)0);
     static bool opted = false;
     if (!lds_opt_in(k_qkv<C, WPB, 3, RT>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_QKV);
@@ -1641,6 +1668,7 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
     int32_t *Ir_dst = Ir_out_opt ? Ir_out_opt : w.ir;
     const bool fused = C == 64 && fused_ok(D);
     bool prep_pending = false;      // the weights still have to be rearranged, next to the projection
+    bool route_with_qkv = false;    // the routing from pooled X rides in the projection kernel's launch
     if (!fast_route_ok(D)) {
         if (!Ir_in_opt) {
             int rc = valu_route(D, X, Wqkv, Ir_dst, nullptr, w.route, st);
@@ -1661,8 +1689,12 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
             if (fused || from_x)
                 launch_pool<C>(D, X, Wqkv, Wo, Wlce, w, /*pool=*/from_x, prep_total(C), st, /*with_u=*/inline_route);
             if (from_x && !inline_route) {
-                const int rc = launch_route<C>(D, w, Ir_dst, nullptr, st);
-                if (rc != BRA_OK) return rc;
+                // next to the projection (which does not depend on it) where there is one
+                route_with_qkv = !fused && !experiment_flag("BRA_ROUTE_LAUNCH");
+                if (!route_with_qkv) {
+                    const int rc = launch_route<C>(D, w, Ir_dst, nullptr, st);
+                    if (rc != BRA_OK) return rc;
+                }
                 Ir_src = Ir_dst;
             }
             prep_pending = !(fused || from_x);
@@ -1675,6 +1707,12 @@ int forward_c(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_t *
         const bool pooled = pooled_projection(D) && !Ir_in_opt;
         PrepArgs prep = {Wqkv, Wo, Wlce, w.wt, w.wot, w.wa, w.wf, prep_pending ? prep_total(C) : 0};
         prep.trace = (int)experiment_value("BRA_QKV_TRACE", 0);
+        if (route_with_qkv) {
+            prep.Xr = w.xr;
+            prep.Ir = Ir_dst;
+            prep.route_items = D.B * ((D.R + 15) / 16);
+            prep.dims = D;
+        }
         int rc = launch_qkv<C>(D, X, Wqkv, w, pooled, prep, st, q32 ? c_exp : 1.0f);
         if (rc != BRA_OK) return rc;
         if (pooled) {
