@@ -364,7 +364,9 @@ def time_variants(cfg, steps, warmup):
 
 def measured_peaks():
     """What plain streaming kernels reach on this GPU, beside the published HBM peak the roofline
-    uses: a copy and a read of 512 MiB (twice the last-level cache)."""
+    uses: a copy and a read of 512 MiB (twice the last-level cache); and what the matrix cores reach
+    on register operands with each of the two dense bf16 instruction shapes, beside the published
+    2.5 PFLOP/s."""
     import torch
 
     import paper_2303_08810_amd as bra
@@ -388,7 +390,13 @@ def measured_peaks():
 
     t_copy = timed(lambda: bra.util_copy(dst, src), 20)
     t_read = timed(lambda: bra.util_read(src, scratch), 20)
-    return {"hbm_copy_GBs": round(2 * nbytes / t_copy / 1e9, 1), "hbm_read_GBs": round(nbytes / t_read / 1e9, 1)}
+    # matrix cores: 8 workgroups of 4 wavefronts per compute unit, register operands only
+    wgs, iters = 256 * 8, 4000
+    t16 = timed(lambda: bra.util_mfma(wgs, iters, scratch), 3)
+    t32 = timed(lambda: bra.util_mfma32(wgs, iters, scratch), 3)
+    return {"hbm_copy_GBs": round(2 * nbytes / t_copy / 1e9, 1), "hbm_read_GBs": round(nbytes / t_read / 1e9, 1),
+            "mfma_bf16_16x16x32_TFLOPs": round(wgs * 4 * 8 * iters * 16384 / t16 / 1e12, 1),
+            "mfma_bf16_32x32x16_TFLOPs": round(wgs * 4 * 4 * iters * 32768 / t32 / 1e12, 1)}
 
 
 def roofline_of(cfg, kernels):

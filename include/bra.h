@@ -215,11 +215,13 @@ const char *bra_kernel_name(int id);
 int bra_util_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
 int bra_util_read(const void *src, size_t bytes, void *scratch4, void *hip_stream);
 
-/* Matrix-core throughput probe: `workgroups` workgroups of 4 wavefronts, each wavefront
- * issuing 8 * iters dense bf16 16x16x32 matrix products on register operands (16384 flops
- * each), enqueued on hip_stream; scratch4 as above.  The measured rate stands beside the
+/* Matrix-core throughput probes: `workgroups` workgroups of 4 wavefronts, each wavefront
+ * issuing 8 * iters dense bf16 16x16x32 matrix products (bra_util_mfma; 16384 flops each) or
+ * 4 * iters dense bf16 32x32x16 products (bra_util_mfma32; 32768 flops each) on register
+ * operands, enqueued on hip_stream; scratch4 as above.  The measured rates stand beside the
  * published peak in the benchmark line.  Errors: NULL, SHAPE, LAUNCH. */
 int bra_util_mfma(int workgroups, int iters, void *scratch4, void *hip_stream);
+int bra_util_mfma32(int workgroups, int iters, void *scratch4, void *hip_stream);
 
 /* Static, human-readable text for a return code. */
 const char *bra_strerror(int code);

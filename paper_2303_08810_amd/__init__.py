@@ -24,7 +24,7 @@ EXPORTS = ("bra_workspace_bytes", "bra_route", "bra_forward", "bra_forward_stati
            "bra_forward_padded", "bra_backward_workspace_bytes", "bra_backward", "bra_block_workspace_bytes",
            "bra_block_forward", "bra_strerror", "bra_version",
            "bra_profile_begin", "bra_profile_end", "bra_kernel_name", "bra_util_copy",
-           "bra_util_read", "bra_util_mfma")
+           "bra_util_read", "bra_util_mfma", "bra_util_mfma32")
 
 
 class BraShape(ctypes.Structure):
@@ -97,6 +97,8 @@ def lib() -> ctypes.CDLL:
         L.bra_util_read.argtypes = [vp, sz, vp, vp]
         L.bra_util_mfma.restype = ctypes.c_int
         L.bra_util_mfma.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
+        L.bra_util_mfma32.restype = ctypes.c_int
+        L.bra_util_mfma32.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
         _lib = L
     return _lib
 
@@ -295,6 +297,11 @@ def profile_end(max_records: int):
 def util_mfma(workgroups: int, iters: int, scratch: torch.Tensor) -> None:
     """Matrix-core throughput probe: workgroups x 4 wavefronts x 8 iters dense bf16 16x16x32 products."""
     _check(lib().bra_util_mfma(int(workgroups), int(iters), _ptr(scratch), _stream(scratch.device)))
+
+
+def util_mfma32(workgroups: int, iters: int, scratch: torch.Tensor) -> None:
+    """Matrix-core throughput probe: workgroups x 4 wavefronts x 4 iters dense bf16 32x32x16 products."""
+    _check(lib().bra_util_mfma32(int(workgroups), int(iters), _ptr(scratch), _stream(scratch.device)))
 
 
 def util_read(src: torch.Tensor, scratch: torch.Tensor) -> None:

@@ -591,13 +591,15 @@ __global__ __launch_bounds__(256) void k_route_p(const float *__restrict__ P, in
 // owns the 16 query regions 16 rt .. 16 rt + 15 of image b (R <= 64); wavefront w forms their
 // affinities to the keys 16 w .. 16 w + 15 with float32 matrix-core products
 // (v_mfma_f32_16x16x4_f32: lane 16 g + i holds A[row i][k g], B[k g][col i] and
-// D[rows 4 g + j][col i]), its operands loaded straight from P with every request issued before the
-// first product; the four 16 x 16 blocks meet in LDS, then wavefront w ranks rows 4 w .. 4 w + 3.
+// D[rows 4 g + j][col i]), its key operands loaded straight from P, the query rows (the same for the
+// four wavefronts) through LDS, every request issued before the first product; the four 16 x 16
+// blocks meet in LDS, then wavefront w ranks rows 4 w .. 4 w + 3.
 template <int C>
 __global__ __launch_bounds__(256) void k_route_w(const float *__restrict__ P, int32_t *__restrict__ Ir,
                                                  float *__restrict__ Ar, Dims D)
 {
     __shared__ float At[16][65];
+    __shared__ __attribute__((aligned(16))) float Qt[16][C + 4];      // the 16 query rows, shared by the wavefronts
     const int groups = (D.R + 15) / 16;
     const int wid = swizzled_block();          // the workgroups of an image share an XCD (and its L2)
     if (wid >= D.B * groups) return;
@@ -605,19 +607,29 @@ __global__ __launch_bounds__(256) void k_route_w(const float *__restrict__ P, in
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int g = lane / 16, i = lane % 16;
     // rows past R repeat the last region; their results are never used
-    const float *qsrc = P + ((size_t)b * D.R + min(16 * myrt + i, D.R - 1)) * 2 * C + 4 * g;
     const float *ksrc = P + ((size_t)b * D.R + min(16 * wave + i, D.R - 1)) * 2 * C + C + 4 * g;
-    f32x4 qv[C / 16], kv[C / 16];      // channels 16 s + 4 g + e: product e of step s contracts over {16 s + 4 g' + e}
+    constexpr int NQ = 16 * (C / 4) / 256;      // 16-byte chunks of the query rows per thread
+    f32x4 qr[NQ], kv[C / 16];      // channels 16 s + 4 g + e: product e of step s contracts over {16 s + 4 g' + e}
 #pragma unroll
-    for (int s = 0; s < C / 16; ++s) {
-        qv[s] = *(const f32x4 *)(qsrc + 16 * s);
-        kv[s] = *(const f32x4 *)(ksrc + 16 * s);
+    for (int u = 0; u < NQ; ++u) {
+        const int idx = threadIdx.x + 256 * u, row = idx / (C / 4), c4 = idx % (C / 4);
+        qr[u] = *(const f32x4 *)(P + ((size_t)b * D.R + min(16 * myrt + row, D.R - 1)) * 2 * C + 4 * c4);
     }
+#pragma unroll
+    for (int s = 0; s < C / 16; ++s) kv[s] = *(const f32x4 *)(ksrc + 16 * s);
+#pragma unroll
+    for (int u = 0; u < NQ; ++u) {
+        const int idx = threadIdx.x + 256 * u;
+        *(f32x4 *)&Qt[idx / (C / 4)][4 * (idx % (C / 4))] = qr[u];
+    }
+    __syncthreads();
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int s = 0; s < C / 16; ++s)
+    for (int s = 0; s < C / 16; ++s) {
+        const f32x4 qv = *(const f32x4 *)&Qt[i][16 * s + 4 * g];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qv[s][e], kv[s][e], acc, 0, 0, 0);
+        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qv[e], kv[s][e], acc, 0, 0, 0);
+    }
     const float inv_n = 1.0f / (float)D.n, sc = inv_n * inv_n;
 #pragma unroll
     for (int j = 0; j < 4; ++j) At[4 * g + j][16 * wave + i] = acc[j] * sc;

@@ -48,6 +48,28 @@ __global__ __launch_bounds__(256) void k_util_mfma(int iters, float *__restrict_
     if (s == 12345.678f) out[0] = s;       // practically never taken: keeps the chains alive
 }
 
+// The same with v_mfma_f32_32x32x16_bf16: 4 independent chains of 16 result registers each.
+typedef float f32x16v __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256) void k_util_mfma32(int iters, float *__restrict__ out)
+{
+    const u32x4 bits = {0x3f803f80u + threadIdx.x, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    const bf16x8v a = __builtin_bit_cast(bf16x8v, bits), b = a;
+    f32x16v acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) s += acc[c][0];
+    if (s == 12345.678f) out[0] = s;       // practically never taken: keeps the chains alive
+}
+
 }  // namespace
 }  // namespace bra
 
@@ -86,6 +108,15 @@ int bra_util_mfma(int workgroups, int iters, void *scratch4, void *hip_stream)
     if (!scratch4) return BRA_ERR_NULL;
     if (workgroups < 1 || iters < 1) return BRA_ERR_SHAPE;
     hipLaunchKernelGGL(k_util_mfma, dim3(workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters,
+                       (float *)scratch4);
+    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+int bra_util_mfma32(int workgroups, int iters, void *scratch4, void *hip_stream)
+{
+    if (!scratch4) return BRA_ERR_NULL;
+    if (workgroups < 1 || iters < 1) return BRA_ERR_SHAPE;
+    hipLaunchKernelGGL(k_util_mfma32, dim3(workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters,
                        (float *)scratch4);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
