@@ -45,14 +45,14 @@ namespace {
 // contiguous bytes.
 constexpr int kLceOperandElems = 160;   // per channel: 5 rows x 2 halves x 4 offsets x 4
 
-// For C = 64 the fused kernel reads all projection weights as ready-made MFMA fragments:
-// 16 "row tiles" x 2 contraction steps x 64 lanes x 8 elements, lane 16 g + i.
-//   row tiles 0..11 ([Wq | Wk | Wv]^T):  Wf = WT[16 rt + i][32 ks + 8 g + s]
-//   row tiles 12..15 (Wo^T, tile tt):    row i is output channel 16 (i / 4) + 4 tt + i % 4,
-//       slot s of lane group g is input channel 32 ks + 16 (s / 4) + 4 g + s % 4
-// (the order in which the fused kernel holds O^T, and the order that gives every lane 16
-// consecutive output channels).
-constexpr int kFusedFragElems = 16 * 2 * 64 * 8;
+// For C = 64 the fused kernel reads all projection weights as ready-made fragments of its
+// 32x32x16 products: 10 tiles x 4
+// contraction steps x 64 lanes x 8 elements, lane 32 h + c, element s = input channel
+// 16 kst + 8 h + s of output channel
+//   tiles 0..5: 32 (tile % 2) + prow(c) of Wq, Wk, Wv (tile / 2), prow(c) = 16 (c / 16) + 8 ((c / 4) % 2) +
+//               4 ((c / 8) % 2) + c % 4 (the row order that leaves a lane with two runs of 8 channels);
+//   tiles 6, 7: 32 (tile - 6) + c of Wv (as a B operand);  tiles 8, 9: 32 (tile - 8) + prow(c) of Wo.
+constexpr int kFusedFragElems = 10 * 4 * 64 * 8;
 
 // Elements of the small-region kernels' tables (Wo fragments, LCE weights tap-major).
 __host__ __device__ constexpr int small_table_elems(int C) { return C * C + 25 * C; }
@@ -81,15 +81,13 @@ __device__ inline void prep_weight_element(const bf16_t *__restrict__ Wqkv,
     }
     if (e >= base_elems) {                              // only when C == 64
         const int f = e - base_elems - small_table_elems(C);
-        const int s = f % 8, lane = (f / 8) % kWave, ks = (f / 512) % 2, rt = f / 1024;
-        const int g = lane / 16, i = lane % 16;
-        if (rt < 12) {
-            Wf[f] = Wqkv[(size_t)(32 * ks + 8 * g + s) * 3 * C + 16 * rt + i];
-        } else {
-            const int o = 16 * (i / 4) + 4 * (rt - 12) + i % 4;
-            const int c = 32 * ks + 16 * (s / 4) + 4 * g + s % 4;
-            Wf[f] = Wo[(size_t)c * C + o];
-        }
+        const int s = f % 8, lane = (f / 8) % kWave, kst = (f / 512) % 4, tile = f / 2048;
+        const int h = lane / 32, c = lane % 32;
+        const int prow = 16 * (c / 16) + 8 * ((c / 4) % 2) + 4 * ((c / 8) % 2) + c % 4;
+        const int in = 16 * kst + 8 * h + s;
+        if (tile < 6) Wf[f] = Wqkv[(size_t)in * 3 * C + (tile / 2) * C + 32 * (tile % 2) + prow];
+        else if (tile < 8) Wf[f] = Wqkv[(size_t)in * 3 * C + 2 * C + 32 * (tile - 6) + c];
+        else Wf[f] = Wo[(size_t)in * C + 32 * (tile - 8) + prow];
         return;
     }
     if (e >= 4 * C * C) {
@@ -165,11 +163,22 @@ __global__ __launch_bounds__(256) void k_pool(const bf16_t *__restrict__ X,
     __shared__ __attribute__((aligned(16))) bf16_t wqk[kWithU ? 2 * 64 * 64 : 8];   // Wq [e][c], Wk [f][c]
     __shared__ __attribute__((aligned(16))) float xs[kWithU ? kPoolMaxGroup * 64 : 4], qs[kWithU ? kPoolMaxGroup * 64 : 4];
     const int tid = threadIdx.x;
+#ifdef BRA_EXPERIMENT
+    const bool tracing = prep_elems < 0;
+    if (tracing) prep_elems = -prep_elems;
+#endif
     if ((int)blockIdx.x >= pool_blocks) {
         const int e = ((int)blockIdx.x - pool_blocks) * 256 + tid;
         if (e < prep_elems) prep_weight_element(Wqkv, Wo, Wlce, WT, WoT, Wa, Wf, C, e);
         return;
     }
+#ifdef BRA_EXPERIMENT
+    unsigned long long trace_t[4] = {0, 0, 0, 0};
+#define BRA_TRACE(k) if (tracing) trace_t[k] = __builtin_amdgcn_s_memrealtime()
+#else
+#define BRA_TRACE(k)
+#endif
+    BRA_TRACE(0);
     u32x4 wreg[4];
     if (kWithU && U) {
 #pragma unroll
@@ -207,6 +216,7 @@ __global__ __launch_bounds__(256) void k_pool(const bf16_t *__restrict__ X,
 #pragma unroll
         for (int e = 0; e < 8; ++e) part[(sub * items + item) * 8 + e] = acc[e];
     }
+    BRA_TRACE(1);
     __syncthreads();
     for (int e = tid; e < ng * C; e += 256) {
         const int gi = e / C, c = e % C;
@@ -262,6 +272,17 @@ __global__ __launch_bounds__(256) void k_pool(const bf16_t *__restrict__ X,
         if (i < ng) *(f32x4 *)(U + ((size_t)b * D.R + r0 + i) * C + 16 * wave + 4 * g) = acc;
         for (int e = tid; e < ng * C; e += 256) Xr[((size_t)b * D.R + r0) * C + e] = xs[e];
     }
+#ifdef BRA_EXPERIMENT
+    if (tracing && U) {
+        BRA_TRACE(2);
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long *o = (unsigned long long *)(U + ((size_t)b * D.R + r0) * C);
+            for (int k = 0; k < 3; ++k) o[k] = trace_t[k];
+        }
+    }
+#endif
+#undef BRA_TRACE
 }
 
 // Row `reg` of A^r of image b (Eq. 4) from the routing vector u of the region and the means
@@ -1133,20 +1154,7 @@ void k_attn_big(AttnArgs A, Dims D)
 // needed by the LCE are projected from X inside the workgroup (Eq. 3), so Q, K, V never
 // travel through memory.  X tiles are staged once through LDS.
 //
-// Work split over the four wavefronts:
-//   * Q, attention and W^o by token: wavefront w owns queries 16 w .. 16 w + 15.  Its Q
-//     comes out of the matrix cores as Q^T[channel 16 ct + 4 g + j][query i]; two such
-//     tiles packed together are the B operand of S^T = K Q^T for one head, with the 32
-//     contraction slots of lane group g standing for channels
-//         32 h + 4 g + (0..3)  and  32 h + 16 + 4 g + (0..3)
-//     instead of 32 h + 8 g + (0..7).  The K operand is read from LDS in the same order
-//     (two 8-byte reads), so Q never passes through LDS.  The attention output O^T has
-//     the same form and feeds Y^T = Wo^T O^T directly, with Wo's fragments permuted to
-//     match (a table the weight-prep blocks write).
-//   * K, V of the routed block, the V halo and the LCE by channel: wavefront w owns
-//     channels 16 w .. 16 w + 15 of all tokens; its weight slices stay in registers.
-//     Neighbouring lane groups swap halves (v_permlane16_swap) so that every lane
-//     writes 16 contiguous bytes of a K / V row or of a V halo plane.
+// Work split over the four wavefronts: see the kernel's own comment.
 //   * LCE (Eq. 7) runs on the matrix cores.  The V halo of a wavefront's channels is
 //     stored channel-major (a plane of halo tokens per channel) and the 5x5 depth-wise
 //     correlation of one channel is a chain of v_mfma_f32_4x4x4_16B_bf16 products:
@@ -1160,8 +1168,9 @@ void k_attn_big(AttnArgs A, Dims D)
 // LDS row pitches are chosen per access pattern (measured on gfx950): rows read with
 // the transposing read are fastest at 160 bytes, rows read 8 bytes per lane at 144 bytes,
 // the planes (8-byte reads, lane = channel x row offset) at a pitch of 8 x odd words.
-// The X tiles (16-byte reads) would also like 160 bytes, but at 144 bytes the whole map
-// stays under 40 KB and four workgroups fit a compute unit, which is worth more.
+// The X tiles (16-byte reads) would also like 160 bytes; at 144 bytes the whole map takes 40 KB and
+// three workgroups share a compute unit.  (A fourth needs 36 KB or less and at most 120 registers:
+// built with an unpadded, swizzled halo tile, it was measured no faster.)
 template <int RW>
 struct FusedSmem {
     static constexpr int C = 64;
@@ -1185,34 +1194,42 @@ struct FusedSmem {
     static_assert(KP <= XS && (size_t)C * PL * 4 <= h_off, "tiles that share a slot must fit");
 };
 
-// Lane groups g (16 lanes each) hold two 8-byte pieces a, b that continue in the
-// neighbouring group: afterwards {a, b} of an even group is its own a followed by the
-// odd neighbour's a, and {a, b} of an odd group is the even neighbour's b followed by its
-// own b (v_permlane16_swap exchanges the odd rows of its first operand with the even rows
-// of its second).
-__device__ __forceinline__ u32x4 pair_halves(u32x2 a, u32x2 b)
-{
-    const auto lo = __builtin_amdgcn_permlane16_swap(a[0], b[0], false, false);
-    const auto hi = __builtin_amdgcn_permlane16_swap(a[1], b[1], false, false);
-    return u32x4{lo[0], hi[0], lo[1], hi[1]};
-}
-
+// The products are v_mfma_f32_32x32x16_bf16 (twice the matrix-core rate of the 16x16x32 form
+// on this chip, and half the LDS operand bytes per flop): lane l = 32 h + c holds A[row c][k 8 h ..],
+// B[k 8 h ..][col c] and D[rows 8 q + 4 h + j][col c] in result register 4 q + j.
+// Wavefront w = (th = w % 2, ch = w / 2).  Projections are formed transposed (rows = output
+// channels ch-th half = head ch, columns = tokens th-th half) from ready-made weight fragments (a
+// table the weight-prep blocks write: one coalesced 16-byte load per lane and contraction step;
+// the same rows taken straight from the transposed weights, 32 scattered rows per load, cost 15 us
+// per launch), with the rows permuted so that
+// result registers 0 .. 7 and 8 .. 15 of a lane are the channels 8 h .. + 7 and 16 + 8 h .. + 7 of
+// its token: exactly the two B operands that the next product wants, so Q feeds S^T = K Q^T and
+// O feeds W^o without leaving the registers of a lane.  Attention: wavefront = (head ch, queries
+// of half th); a lane of S^T holds 32 of its query's 64 scores (the other half sits in lane
+// l ^ 32), and result registers 8 qq .. 8 qq + 7 of key tile t are the B operand of
+// O^T += V^T P^T for the keys 32 t + 16 qq + {4 h .. + 3, 8 + 4 h .. + 3}, which is also what the two
+// transposing reads of V deliver.  The V halo is projected with the operands swapped (rows =
+// halo tokens), 4 consecutive tokens of a channel per register group, into channel-major planes;
+// the LCE runs on them as described above.
 template <int RW>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void k_fused(AttnArgs A, Dims D)
 {
     typedef FusedSmem<RW> SM;
-    constexpr int C = 64, HEADS = C / 32, KS = C / 32, CH = C / 8, NCT = C / 16;
+    constexpr int C = 64, CH = C / 8, KST = C / 16;
     constexpr int XS = SM::XS, KP = SM::KP, VP = SM::VP, PL = SM::PL;
     constexpr int QH = SM::QH, HW = SM::HW, HROWS = SM::HROWS, NHT = SM::NHT, PS = SM::PS;
     constexpr int NBH = (HROWS * CH + 255) / 256;      // halo chunks per thread
     constexpr int NBT = CH / 4;                 // chunks per thread of a 64-row tile
     constexpr int NYB = QH / 4, NXB = RW / 4;   // 4x4 output blocks of the query tile
+    constexpr int NT32 = (HROWS + 31) / 32;     // 32-token tiles of the halo
+    constexpr int OP = C + 8;                   // row pitch of the O tile
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)(smem + SM::k_off);   // first the routed X tile
     bf16_t *Vs = (bf16_t *)(smem + SM::v_off);
-    bf16_t *Hs = (bf16_t *)(smem + SM::h_off);   // first the X halo tile, then the V planes
+    bf16_t *Hs = (bf16_t *)(smem + SM::h_off);   // first the X halo tile, then the V planes, then O
     float *Ls = (float *)(smem + SM::l_off);
+    static_assert((size_t)64 * OP * 2 <= SM::bytes - SM::h_off, "the O tile takes the planes' place");
 
     const int wid = swizzled_block();
     if (wid >= A.total) return;
@@ -1225,7 +1242,8 @@ void k_fused(AttnArgs A, Dims D)
     BRA_TRACE(0);
 
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int g = lane / 16, i = lane % 16;
+    const int h = lane / 32, c32 = lane % 32, i = lane % 16, gg = c32 / 16;
+    const int th = wave % 2, chh = wave / 2;
     const int b = wid / D.R, reg = wid % D.R;
     const float s_inv = 1.0f / (float)D.S;
     const int regy = fast_div(reg, s_inv);
@@ -1234,10 +1252,10 @@ void k_fused(AttnArgs A, Dims D)
     const bf16_t *Ximg = A.X + img_off;
     const float hw_inv = 1.0f / (float)HW, rw_inv = 1.0f / (float)RW;
 
-    // All requests up front: the routed region, X over the halo of the query tile (it
-    // contains the query tile) and over the routed region, the weight fragments.
-    // The routed region: given, or found here from this region's row of A^r; the requests
-    // for that row go first, so that they are back before the tiles.
+    // All requests up front: the routed region, X over the halo of the query tile (it contains the
+    // query tile) and over the routed region, the weight fragments.  The routed region: given, or
+    // found here from this region's row of A^r; the requests for that row go first, so that they are
+    // back before the tiles.
     const size_t rrow = (size_t)b * D.R + reg;
     RouteRowLoads rl;
     int j = 0;
@@ -1251,23 +1269,25 @@ void k_fused(AttnArgs A, Dims D)
     tile_load<C, NBH>(hreg, Ximg, y0 - 2, x0 - 2, HW, hw_inv, HROWS, D.H, D.W, 0);
     if (!A.Ir_src) j = route_row_k1(rl, D.R, (uint32_t *)(smem + SM::r_off), nullptr);
     BRA_TRACE(1);
-    auto fragment = [&](int rt, int ks) {
-        return *(const bf16x8 *)(A.Wf + ((size_t)(rt * KS + ks) * kWave + lane) * 8);
+    // weight rows: result row c of a 32-row tile is output channel prow of the tile
+    // (ready-made fragments: one coalesced 16-byte load per lane each)
+    auto fragment = [&](int tile, int kst) {
+#ifdef BRA_EXPERIMENT
+        if (A.trace & 4) {      // ablation: no weight traffic (wrong results)
+            const u32x4 c = {0x3c003c00u + (unsigned)tile, 0x3c003c00u, 0x3c003c00u + (unsigned)kst, 0x3c003c00u};
+            return __builtin_bit_cast(bf16x8, c);
+        }
+#endif
+        return *(const bf16x8 *)(A.Wf + ((size_t)(tile * KST + kst) * kWave + lane) * 8);
     };
-    bf16x8 wq[NCT][KS], wk[KS], wv[KS];
+    bf16x8 wq[KST], wk[KST], wv[KST], wvb[KST];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-        for (int ct = 0; ct < NCT; ++ct) wq[ct][ks] = fragment(ct, ks);
-        wk[ks] = fragment(NCT + wave, ks);
-        wv[ks] = fragment(2 * NCT + wave, ks);
+    for (int kst = 0; kst < KST; ++kst) {
+        wq[kst] = fragment(chh, kst);
+        wk[kst] = fragment(2 + chh, kst);
+        wv[kst] = fragment(4 + chh, kst);
+        wvb[kst] = fragment(6 + th, kst);      // as a B operand: column c
     }
-    // LCE weights as 4x4x4 A operands: lane = (channel block lb, output offset xi).
-    const int lb = lane / 4, xi = lane % 4;
-    s16x4 aw[5][2];
-#pragma unroll
-    for (int r = 0; r < 10; ++r)
-        aw[r / 2][r % 2] = *(const s16x4 *)(A.Wa + ((size_t)(wave * 10 + r) * kWave + lane) * 4);
     u32x4 kreg[NBT];
     const int jy = fast_div(j, s_inv);
     tile_load<C, NBT>(kreg, Ximg, jy * D.rh, (j - jy * D.S) * RW, RW, rw_inv, 64, D.H, D.W, 0);
@@ -1276,101 +1296,143 @@ void k_fused(AttnArgs A, Dims D)
     __syncthreads();
     BRA_TRACE(2);
 
-    // Q of this wavefront's 16 queries, as the B operands of S^T = K Q^T.
-    const int q = 16 * wave + i;
+    // Q of head chh for the queries 32 th .. + 31, kept as the B operands of S^T = K Q^T
+    const int q = 32 * th + c32;
     const int qy = fast_div(q, rw_inv);
-    bf16x8 qb[HEADS];
+    bf16x8 qb[2];
     {
-        const bf16_t *xq = Hs + ((qy + 2) * HW + q - qy * RW + 2) * XS + 8 * g;   // query token in the halo
-        bf16x8 bq[KS];
+        const bf16_t *xq = Hs + ((qy + 2) * HW + q - qy * RW + 2) * XS + 8 * h;   // query token in the halo
+        f32x16 a;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) bq[ks] = *(const bf16x8 *)(xq + 32 * ks);
+        for (int e = 0; e < 16; ++e) a[e] = 0.f;
 #pragma unroll
-        for (int h = 0; h < HEADS; ++h) {
-            f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f};
+        for (int kst = 0; kst < KST; ++kst) a = mfma32(wq[kst], *(const bf16x8 *)(xq + 16 * kst), a);
+        float v[16];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                a0 = mfma16(wq[2 * h][ks], bq[ks], a0);
-                a1 = mfma16(wq[2 * h + 1][ks], bq[ks], a1);
-            }
-            float v[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-            qb[h] = pack8(v);
-        }
+        for (int e = 0; e < 16; ++e) v[e] = a[e];
+        qb[0] = pack8(v);
+        qb[1] = pack8(v + 8);
     }
-    // W^o fragments (rows and contraction slots permuted) take over the registers of Wq.
-    bf16x8 wo[4][KS];
+    // K, V of the routed tokens 32 th .. + 31, channels of half chh
+    bf16x8 kp[2], vp[2];
+    {
+        const bf16_t *xk = Ks + (32 * th + c32) * XS + 8 * h;
+        f32x16 ka, va;
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt)
+        for (int e = 0; e < 16; ++e) ka[e] = va[e] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) wo[tt][ks] = fragment(3 * NCT + tt, ks);
-
-    // K, V of the routed block: D^T[channel 16 w + 4 g + jj][token i], a lane ends up with
-    // 4 consecutive channels of one token.  V halo: operands swapped, D[token 4 g + jj]
-    // [channel i], 4 consecutive halo tokens of one channel.
-    u32x2 vh[NHT], kk[4], vv[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const bf16_t *xk = Ks + (16 * u + i) * XS + 8 * g;
-        f32x4 ak = {0.f, 0.f, 0.f, 0.f}, av = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 bk = *(const bf16x8 *)(xk + 32 * ks);
-            ak = mfma16(wk[ks], bk, ak);
-            av = mfma16(wv[ks], bk, av);
+        for (int kst = 0; kst < KST; ++kst) {
+            const bf16x8 bk = *(const bf16x8 *)(xk + 16 * kst);
+            ka = mfma32(wk[kst], bk, ka);
+            va = mfma32(wv[kst], bk, va);
         }
-        kk[u] = pack4(ak);
-        vv[u] = pack4(av);
+        float v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = ka[e];
+        kp[0] = pack8(v);
+        kp[1] = pack8(v + 8);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = va[e];
+        vp[0] = pack8(v);
+        vp[1] = pack8(v + 8);
     }
+    // V halo: tasks (32-token tile T, channel half th), operands swapped: D[token 8 q + 4 h + j][channel c]
+    constexpr int NHU = (2 * NT32 + 3) / 4;
+    u32x2 vh[NHU][4];
 #pragma unroll
-    for (int hu = 0; hu < NHT; ++hu) {
-        const bf16_t *xh = Hs + (16 * hu + i) * XS + 8 * g;
-        f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    for (int u = 0; u < NHU; ++u) {
+        const int T = chh + 2 * u;      // task wave + 4 u = (T, th)
+        if (T < NT32) {
+            const bf16_t *xh = Hs + min(32 * T + c32, HROWS - 1) * XS + 8 * h;   // rows past the halo repeat the last one; never used
+            f32x16 a;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) a = mfma16(*(const bf16x8 *)(xh + 32 * ks), wv[ks], a);
-        vh[hu] = pack4(a);
+            for (int e = 0; e < 16; ++e) a[e] = 0.f;
+#pragma unroll
+            for (int kst = 0; kst < KST; ++kst) a = mfma32(*(const bf16x8 *)(xh + 16 * kst), wvb[kst], a);
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) vh[u][qq] = pack4(f32x4{a[4 * qq], a[4 * qq + 1], a[4 * qq + 2], a[4 * qq + 3]});
+        }
     }
     __syncthreads();   // every X tile has been read
     BRA_TRACE(3);
-
-    // Tiles of this wavefront's channels: rows 16 (2 p + g % 2) + i, channels 8 (g / 2) ..
+    {
+        bf16_t *kd = Ks + (32 * th + c32) * KP + 32 * chh + 8 * h, *vd = Vs + (32 * th + c32) * VP + 32 * chh + 8 * h;
+        *(bf16x8 *)kd = kp[0];
+        *(bf16x8 *)(kd + 16) = kp[1];
+        *(bf16x8 *)vd = vp[0];
+        *(bf16x8 *)(vd + 16) = vp[1];
+        bf16_t *plane = Hs + (32 * th + c32) * PS;      // plane of channel 32 th + c
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        const int row = 16 * (2 * p + (g & 1)) + i, col = 16 * wave + 8 * (g >> 1);
-        *(u32x4 *)(Ks + row * KP + col) = pair_halves(kk[2 * p], kk[2 * p + 1]);
-        *(u32x4 *)(Vs + row * VP + col) = pair_halves(vv[2 * p], vv[2 * p + 1]);
-    }
-    {   // plane of channel 16 w + i: halo tokens 16 (2 p + g % 2) + 8 (g / 2) ..
-        bf16_t *plane = Hs + (16 * wave + i) * PS;
+        for (int u = 0; u < NHU; ++u) {
+            const int T = chh + 2 * u;
+            if (T < NT32) {
 #pragma unroll
-        for (int p = 0; p < NHT / 2; ++p)
-            *(u32x4 *)(plane + 16 * (2 * p + (g & 1)) + 8 * (g >> 1)) = pair_halves(vh[2 * p], vh[2 * p + 1]);
-        if constexpr (NHT % 2) *(u32x2 *)(plane + 16 * (NHT - 1) + 4 * g) = vh[NHT - 1];
+                for (int qq = 0; qq < 4; ++qq) {
+                    const int tok = 32 * T + 8 * qq + 4 * h;
+                    if (tok < NHT * 16) *(u32x2 *)(plane + tok) = vh[u][qq];
+                }
+            }
+        }
     }
     __syncthreads();
-
-    // From here on this wavefront goes first among those of its SIMD: workgroups in their
-    // late phases finish (and free their LDS for the next workgroup) sooner than they would
-    // in a fair interleave with workgroups that have only just started.  Measured: -3 %.
     __builtin_amdgcn_s_setprio(2);
     BRA_TRACE(4);
-    // Attention of the 16 queries over the 64 keys (Eq. 1 with one routed block).
-    SoftmaxState<HEADS> st;
-    st.init();
+    // W^o rows (out channels of half chh) and the LCE operands: requested now, used after the attention
+    bf16x8 wo[KST];
 #pragma unroll
-    for (int h = 0; h < HEADS; ++h) {
-        f32x4 s[4];
+    for (int kst = 0; kst < KST; ++kst) wo[kst] = fragment(8 + chh, kst);
+    const int lb = lane / 4, xi = lane % 4;      // LCE: lane = (channel of the wavefront's 16, output row offset)
+    s16x4 aw[5][2];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const bf16_t *kr = Ks + (16 * t + i) * KP + 32 * h + 4 * g;
-            const u32x2 lo = *(const u32x2 *)kr, hi = *(const u32x2 *)(kr + 16);
-            const u32x4 kf = {lo[0], lo[1], hi[0], hi[1]};
-            s[t] = mfma16(__builtin_bit_cast(bf16x8, kf), qb[h], f32x4{0.f, 0.f, 0.f, 0.f});
-        }
-        softmax_pv_block<VP, true>(Vs, s, st, h, 32 * h, A.c_exp, g, i);      // the only key block
-    }
+    for (int r = 0; r < 10; ++r)
+        aw[r / 2][r % 2] = *(const s16x4 *)(A.Wa + ((size_t)(wave * 10 + r) * kWave + lane) * 4);
 
-    // LCE of this wavefront's channels from its own halo planes:
-    // lane = (channel block lb, output row offset yj = xi index of the lane).
+    // attention of head chh, queries 32 th .. + 31, over the 64 keys (Eq. 1 with one routed block)
+    float p[32];
+    {
+        f32x16 s0, s1;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s0[e] = s1[e] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const bf16_t *kr = Ks + c32 * KP + 32 * chh + 16 * s + 8 * h;
+            s0 = mfma32(*(const bf16x8 *)kr, qb[s], s0);
+            s1 = mfma32(*(const bf16x8 *)(kr + 32 * KP), qb[s], s1);
+        }
+        float m = s0[0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e) m = fmaxf(m, s0[e]);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) m = fmaxf(m, s1[e]);
+        m = fmaxf(m, __shfl_xor(m, 32));
+        const float mc = m * A.c_exp;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            p[e] = __builtin_amdgcn_exp2f(fmaf(s0[e], A.c_exp, -mc));
+            p[16 + e] = __builtin_amdgcn_exp2f(fmaf(s1[e], A.c_exp, -mc));
+        }
+    }
+    float lsum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) lsum += p[e];
+    lsum += __shfl_xor(lsum, 32);
+    f32x16 oacc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[e] = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int qq = 0; qq < 2; ++qq) {
+            const bf16_t *src = Vs + (32 * t + 16 * qq + 4 * h + i / 4) * VP + 32 * chh + 16 * gg + 8 * ((i % 4) % 2) +
+                                4 * ((i % 4) / 2);
+            const u32x2 v0 = __builtin_bit_cast(u32x2, lds_read_tr16(src));
+            const u32x2 v1 = __builtin_bit_cast(u32x2, lds_read_tr16(src + 8 * VP));
+            const bf16x8 vf = __builtin_bit_cast(bf16x8, u32x4{v0[0], v0[1], v1[0], v1[1]});
+            oacc = mfma32(vf, pack8(p + 16 * t + 8 * qq), oacc);
+        }
+    const float inv = 1.0f / lsum;
+
+    // LCE of this wavefront's 16 channels from its halo planes: lane = (channel lb, output row offset xi)
     f32x4 lce[NYB][NXB];
     {
         const bf16_t *plane = Hs + (16 * wave + lb) * PS;
@@ -1393,41 +1455,41 @@ void k_fused(AttnArgs A, Dims D)
         }
     }
     BRA_TRACE(5);
-    __syncthreads();   // K and V have been read: the LCE tile may take their place
+    __syncthreads();   // K, V and the planes have been read: the LCE tile and the O tile may take their place
 #pragma unroll
     for (int yb = 0; yb < NYB; ++yb)
 #pragma unroll
         for (int xb = 0; xb < NXB; ++xb)   // queries (row 4 yb + yj, columns 4 xb ..) of channel 16 w + lb
             *(f32x4 *)(Ls + (16 * wave + lb) * PL + (4 * yb + xi) * RW + 4 * xb) = lce[yb][xb];
     __syncthreads();
-
     BRA_TRACE(6);
-    // O = attention + LCE (Eq. 2, 7) in registers, then Y^T = Wo^T O^T for the 16 queries:
-    // W^o row 4 g + jj of tile tt stands for output channel 16 g + 4 tt + jj, so a lane
-    // ends up with 16 consecutive output channels of its query.
-    bf16x8 ob[HEADS];
+    // O = attention + LCE (Eq. 2, 7), rounded once, into the O tile [query][channel]
+    {
+        float v[16];
 #pragma unroll
-    for (int h = 0; h < HEADS; ++h) {
-        const float inv = 1.0f / st.denom(h);
-        float v[8];
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-                v[4 * dt + jj] = fmaf(st.acc[h][dt][jj], inv, Ls[(32 * h + 16 * dt + 4 * g + jj) * PL + q]);
-        ob[h] = pack8(v);
+        for (int e = 0; e < 8; ++e) {
+            v[e] = fmaf(oacc[e], inv, Ls[(32 * chh + 8 * h + e) * PL + q]);
+            v[8 + e] = fmaf(oacc[8 + e], inv, Ls[(32 * chh + 16 + 8 * h + e) * PL + q]);
+        }
+        bf16_t *od = Hs + q * OP + 32 * chh + 8 * h;
+        *(bf16x8 *)od = pack8(v);
+        *(bf16x8 *)(od + 16) = pack8(v + 8);
     }
-    u32x2 yp[4];
+    __syncthreads();
+    // Y^T = Wo^T O^T: out channels of half chh, queries of half th
+    {
+        f32x16 ya;
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt) {
-        f32x4 ya = {0.f, 0.f, 0.f, 0.f};
+        for (int e = 0; e < 16; ++e) ya[e] = 0.f;
 #pragma unroll
-        for (int h = 0; h < HEADS; ++h) ya = mfma16(wo[tt][h], ob[h], ya);
-        yp[tt] = pack4(ya);
+        for (int kst = 0; kst < KST; ++kst) ya = mfma32(wo[kst], *(const bf16x8 *)(Hs + q * OP + 16 * kst + 8 * h), ya);
+        float v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = ya[e];
+        bf16_t *dst = A.Y + img_off + ((size_t)(y0 + qy) * D.W + x0 + q - qy * RW) * C + 32 * chh + 8 * h;
+        *(bf16x8 *)dst = pack8(v);
+        *(bf16x8 *)(dst + 16) = pack8(v + 8);
     }
-    u32x4 *dst = (u32x4 *)(A.Y + img_off + ((size_t)(y0 + qy) * D.W + x0 + q - qy * RW) * C + 16 * g);
-    dst[0] = u32x4{yp[0][0], yp[0][1], yp[1][0], yp[1][1]};
-    dst[1] = u32x4{yp[2][0], yp[2][1], yp[3][0], yp[3][1]};
     // reported last: a store ahead of the barriers above would have to land before them
     if (A.Ir_out && A.Ir_out != A.Ir_src && threadIdx.x == 0) A.Ir_out[rrow] = A.Ir_src ? j_given : j;
 #ifdef BRA_EXPERIMENT
@@ -1572,7 +1634,8 @@ void launch_pool(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const bf16_
     if (pool_blocks + prep_blocks == 0) return;
     ProfScope ps(st, K_MFMA_POOL_QK);
     hipLaunchKernelGGL(k_pool<C>, dim3(pool_blocks + prep_blocks), dim3(256), 0, st, X, Wqkv, Wo, Wlce,
-                       w.xr, with_u ? w.u : nullptr, w.wt, w.wot, w.wa, w.wf, D, pool_blocks, G, prep_elems);
+                       w.xr, with_u ? w.u : nullptr, w.wt, w.wot, w.wa, w.wf, D, pool_blocks, G,
+                       experiment_flag("BRA_POOL_TRACE") ? -prep_elems : prep_elems);
 }
 
 template <int C>
