@@ -46,7 +46,7 @@ def main():
             if not m:
                 continue
             name = NAMES.get(m.group(1)) or MORE.get(m.group(1))
-            if re.search(r"k_qkv<\d+, \d+, 1>", row["Kernel_Name"]):
+            if re.search(r"k_qkv<\d+, \d+, 1, \d+>", row["Kernel_Name"]):
                 name = "mfma_wo"
             if name:
                 acc[name][row["Counter_Name"]].append(float(row["Counter_Value"]))

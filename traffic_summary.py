@@ -15,7 +15,7 @@ import sys
 
 COPY_BYTES = 64 << 20
 NAMES = {"k_fused": "mfma_fused_k1", "k_pool": "mfma_pool_qk", "k_route": "mfma_route_rows",
-         "k_route_p": "mfma_route_rows", "k_route_u": "mfma_route_rows",
+         "k_route_p": "mfma_route_rows", "k_route_u": "mfma_route_rows", "k_route_w": "mfma_route_rows",
          "k_attn_map": "mfma_attn_small", "k_attn_map4": "mfma_attn_small",
          "k_qkv": "mfma_qkv", "k_attn_big": "mfma_attention", "k_attn_q32": "mfma_attention", "k_attn_small": "mfma_attn_small",
          "k_small": "mfma_attn_small", "k_lce_add": "mfma_lce_add", "k_prep_weights": "mfma_prep",
@@ -32,7 +32,7 @@ def averages(directory, counter):
             m = re.search(r"(k_[a-z0-9_]+)", row["Kernel_Name"])
             if m and m.group(1) in NAMES:
                 name = NAMES[m.group(1)]
-                if re.search(r"k_qkv<\d+, \d+, 1>", row["Kernel_Name"]):   # the same kernel with Wo as its only matrix
+                if re.search(r"k_qkv<\d+, \d+, 1, \d+>", row["Kernel_Name"]):   # the same kernel with Wo as its only matrix
                     name = "mfma_wo"
                 if m.group(1) == "k_token_ln":                               # position encoding (0) or residual (1) + LayerNorm
                     name = "block_pos_ln" if "k_token_ln<0" in row["Kernel_Name"] else "block_add_ln"
