@@ -1696,7 +1696,9 @@ int launch_qkv(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const MfmaWs 
     // registers and the workgroup streams its share of the tokens
     const int gy = 3 * C / (32 * RT) / WPB;
     const long slots = experiment_value("BRA_QKV_SLOTS", C == 64 ? 512 : 256);
-    long tpw = (ntiles * gy + slots - 1) / slots;
+    // (routing workgroups take slots too: one workgroup too many would start a second round)
+    const long tile_slots = slots > 2 * prep.route_items ? slots - prep.route_items : slots;
+    long tpw = (ntiles * gy + tile_slots - 1) / tile_slots;
     static const int forced = (int)experiment_value("BRA_QKV_TPW", 0);
     if (forced >= 1 && forced <= 4096) tpw = forced;
     const int gx = (int)((ntiles + tpw - 1) / tpw);
