@@ -217,7 +217,7 @@ def bra_forward_padded(X, Wqkv, Wo, Wlce, S, k, heads, *, scale=None, Ir_in=None
     return (Y, Ir) if want_Ir else Y
 
 
-def bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, S, heads, *, scale=None, ws=None):
+def bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, S, heads, *, scale=None, path="auto", ws=None):
     """Gradients of the layer for fixed routing Ir [B, S*S, k] (see include/bra.h): returns
     (dX in X's dtype, dWqkv, dWo, dWlce in float32)."""
     B, H, W, C = _check_inputs(X, Wqkv, Wo, Wlce)
@@ -226,7 +226,7 @@ def bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, S, heads, *, scale=None, ws=None):
         raise ValueError("Ir must be a contiguous int32 [B, S*S, k] device tensor")
     if not (dY.is_cuda and dY.is_contiguous() and dY.dtype == X.dtype and dY.shape == X.shape):
         raise ValueError("dY must match X")
-    shape = make_shape(B, H, W, C, heads, S, k, X.dtype, scale, "auto")
+    shape = make_shape(B, H, W, C, heads, S, k, X.dtype, scale, path)
     if ws is None:
         need = ctypes.c_size_t(0)
         _check(lib().bra_backward_workspace_bytes(ctypes.byref(shape), ctypes.byref(need)))

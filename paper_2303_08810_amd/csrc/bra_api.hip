@@ -188,14 +188,25 @@ int bra_forward_padded(const bra_shape *shape, const void *X, const void *Wqkv, 
                           (hipStream_t)hip_stream);
 }
 
+// Kernel family of the backward pass: the matrix-core kernels where they apply (bf16, heads of
+// 32 channels, C = 64 or 128, at most 64 routed keys), else the scalar float32 kernels.
+static int pick_backward_path(const bra_shape *s, const Dims &D)
+{
+    const bool mfma_ok = mfma_backward_supported(D);
+    if (s->path == BRA_PATH_MFMA) return mfma_ok ? BRA_PATH_MFMA : BRA_ERR_UNSUPPORTED;
+    if (s->path == BRA_PATH_AUTO && mfma_ok) return BRA_PATH_MFMA;
+    return generic_backward_supported(D) ? BRA_PATH_GENERIC : BRA_ERR_UNSUPPORTED;
+}
+
 int bra_backward_workspace_bytes(const bra_shape *shape, size_t *out_bytes)
 {
     if (!out_bytes) return BRA_ERR_NULL;
     Dims D;
     int rc = make_dims(shape, D);
     if (rc != BRA_OK) return rc;
-    if (!generic_backward_supported(D)) return BRA_ERR_UNSUPPORTED;
-    *out_bytes = generic_backward_workspace_bytes(D);
+    const int path = pick_backward_path(shape, D);
+    if (path < 0) return path;
+    *out_bytes = (path == BRA_PATH_MFMA) ? mfma_backward_workspace_bytes(D) : generic_backward_workspace_bytes(D);
     return BRA_OK;
 }
 
@@ -207,7 +218,12 @@ int bra_backward(const bra_shape *shape, const void *X, const void *Wqkv, const 
     int rc = make_dims(shape, D);
     if (rc != BRA_OK) return rc;
     if (!X || !Wqkv || !Wo || !Wlce || !Ir || !dY || !dX || !dWqkv || !dWo || !dWlce) return BRA_ERR_NULL;
-    if (!generic_backward_supported(D)) return BRA_ERR_UNSUPPORTED;
+    const int path = pick_backward_path(shape, D);
+    if (path < 0) return path;
+    if (path == BRA_PATH_MFMA) {
+        if (!ws_ok(ws, ws_bytes, mfma_backward_workspace_bytes(D))) return BRA_ERR_WORKSPACE;
+        return mfma_backward(D, X, Wqkv, Wo, Wlce, Ir, dY, dX, dWqkv, dWo, dWlce, ws, (hipStream_t)hip_stream);
+    }
     if (!ws_ok(ws, ws_bytes, generic_backward_workspace_bytes(D))) return BRA_ERR_WORKSPACE;
     return generic_backward(D, X, Wqkv, Wo, Wlce, Ir, dY, dX, dWqkv, dWo, dWlce, ws, (hipStream_t)hip_stream);
 }

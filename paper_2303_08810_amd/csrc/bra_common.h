@@ -143,6 +143,19 @@ size_t padded_workspace_bytes(const Dims &Dp, size_t bra_bytes);
 int padded_forward(const Dims &Dp, int H, int W, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
                    void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, int path, hipStream_t st);
 
+// The projection kernels of bra_mfma.hip for other passes (bf16, C = 64, 128 or 256): Q, K, V = X Wqkv
+// into three token maps; Out = In W for one row-major C x C matrix.
+int mfma_project_qkv(const Dims &D, const void *X, const void *Wqkv, bf16_t *Q, bf16_t *K, bf16_t *V,
+                     hipStream_t st);
+int mfma_project(const Dims &D, const void *In, const bf16_t *W, bf16_t *Out, hipStream_t st);
+
+// Backward pass with fixed routing on the matrix cores (bra_mfma_bwd.hip).
+bool mfma_backward_supported(const Dims &D);
+size_t mfma_backward_workspace_bytes(const Dims &D);
+int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo, const void *Wlce,
+                  const int32_t *Ir, const void *dY, void *dX, float *dWqkv, float *dWo, float *dWlce, void *ws,
+                  hipStream_t st);
+
 // Backward pass with fixed routing, scalar float32 kernels (bra_generic.hip).
 bool generic_backward_supported(const Dims &D);
 size_t generic_backward_workspace_bytes(const Dims &D);

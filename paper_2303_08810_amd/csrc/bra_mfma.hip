@@ -1946,4 +1946,32 @@ int mfma_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo,
     }
 }
 
+// The projection kernels for the backward pass (bf16, C = 64, 128 or 256): Q, K, V = X Wqkv
+// (Eq. 3) into three token maps, and Out = In W for one C x C matrix.
+int mfma_project_qkv(const Dims &D, const void *X, const void *Wqkv, bf16_t *Q, bf16_t *K, bf16_t *V,
+                     hipStream_t st)
+{
+    MfmaWs w = {};
+    w.q = Q; w.k = K; w.v = V;
+    const PrepArgs none{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+    const bf16_t *x = (const bf16_t *)X, *wq = (const bf16_t *)Wqkv;
+    switch (D.C) {
+    case 64: return launch_qkv<64>(D, x, wq, w, false, none, st);
+    case 128: return launch_qkv<128>(D, x, wq, w, false, none, st);
+    case 256: return launch_qkv<256>(D, x, wq, w, false, none, st);
+    default: return BRA_ERR_UNSUPPORTED;
+    }
+}
+
+int mfma_project(const Dims &D, const void *In, const bf16_t *W, bf16_t *Out, hipStream_t st)
+{
+    const bf16_t *in = (const bf16_t *)In;
+    switch (D.C) {
+    case 64: return launch_wo<64>(D, in, W, Out, st);
+    case 128: return launch_wo<128>(D, in, W, Out, st);
+    case 256: return launch_wo<256>(D, in, W, Out, st);
+    default: return BRA_ERR_UNSUPPORTED;
+    }
+}
+
 }  // namespace bra
