@@ -4,16 +4,19 @@
 // Chain rule through Eq. 6-7 and Eq. 1-2, with O = Attention(Q, K^g, V^g) + LCE(V), Y = O Wo:
 //     dO = dY Wo^T                     projection kernel with Wo^T as its matrix
 //     P  = softmax(scale Q K^T)        recomputed per (region, head) from the re-projected Q, K
-//     dP = dO V^T,  dS = scale P o (dP - rowsum(P o dP))
-//     dQ = dS K,  dK += dS^T Q,  dV += P^T dO          k_attn_bwd
+//     dP = dO V^T,  dS = scale P o (dP - D),  D = rowsum(P o dP)
+//     dQ = dS K                        k_attn_bwd_q, one workgroup per query region; it also leaves the
+//                                      row statistics (log-sum-exp and D) and the attention output
+//     dK = dS^T Q,  dV = P^T dO        k_attn_bwd_kv, one workgroup per KEY region: it finds the query
+//                                      regions routed to it in Ir, recomputes their P and dS from the
+//                                      statistics and sums in registers, so no atomic adds are needed
 //     dV += LCE^T(dO)                  the forward's depth-wise kernel with the taps reversed
 //     dX = [dQ | dK | dV] Wqkv^T       one product with the transposed weights
 //     dWqkv = X^T [dQ | dK | dV],  dWo = O^T dY         k_gemm_tn (contraction over tokens)
 //     dWlce[c][ky][kx] = sum_t dO[t][c] V[t + (ky - 2, kx - 2)][c]       k_lce_bwd_w
 // All products take bf16 operands and accumulate in float32; dQ, dK, dV and dO are rounded to
-// bf16 between the kernels (they are matrix-core operands of the next product).  dK and dV of a
-// token collect contributions from every region routed to it: float32 atomic adds into
-// accumulators in the workspace, so results are reproducible to rounding, not bit for bit.
+// bf16 between the kernels (they are matrix-core operands of the next product).  The weight
+// gradients are summed from per-workgroup partial sums in a fixed order (k_reduce_parts).
 #include "bra_mfma_dev.h"
 
 namespace bra {
@@ -65,91 +68,99 @@ __device__ __forceinline__ void keys_contract(const bf16_t *T, int pitch, const 
 template <int C>
 struct BwdSmem {
     static constexpr int CS = C + 16;     // elements per row of the token tiles
-    static constexpr int PP = 64 + 8;     // elements per row of the P / dS tiles
+    static constexpr int HEADS = C / 32;
     static constexpr int tile = 64 * CS;
-    static constexpr int p_off = 4 * tile, ds_off = p_off + 64 * PP, tok_off = ds_off + 64 * PP;
-    static constexpr size_t bytes = (size_t)tok_off * 2 + 128 * sizeof(int);
+    static constexpr size_t tok_off = (size_t)4 * tile * 2;                  // int ktok[64], qtok[64]
+    static constexpr size_t q_bytes = tok_off + 128 * sizeof(int);           // k_attn_bwd_q
+    static constexpr size_t stat_off = q_bytes;                              // float lse[HEADS][64], dsum[HEADS][64]
+    static constexpr size_t list_off = stat_off + 2 * HEADS * 64 * sizeof(float);   // int count, pad, list[]
+    static size_t kv_bytes(int entries) { return list_off + 16 + (size_t)entries * sizeof(int); }
 };
 
+// Token (within the image) of slot s of region j (Sec. 3.2: regions tile the map row-major).
+__device__ __forceinline__ int region_token(const Dims &D, int region, int slot)
+{
+    const int ry = region / D.S, rx = region % D.S, sy = slot / D.rw, sx = slot % D.rw;
+    return (ry * D.rh + sy) * D.W + rx * D.rw + sx;
+}
+
+// Rows of a token map (row pitch C) named by tok[0..63] (-1: a row of zeros) -> LDS tile.
+template <int C>
+__device__ __forceinline__ void gather_rows(bf16_t *T0, bf16_t *T1, const bf16_t *__restrict__ M0,
+                                            const bf16_t *__restrict__ M1, size_t img, const int *tok)
+{
+    constexpr int CS = BwdSmem<C>::CS, CH8 = C / 8, NL = 64 * CH8 / 256;
+    u32x4 r0[NL], r1[NL];
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+        const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
+        const int t = tok[row];
+        r0[u] = u32x4{0u, 0u, 0u, 0u};
+        r1[u] = r0[u];
+        if (t >= 0) {
+            r0[u] = *(const u32x4 *)(M0 + (img + t) * C + c8 * 8);
+            r1[u] = *(const u32x4 *)(M1 + (img + t) * C + c8 * 8);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+        const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
+        *(u32x4 *)(T0 + row * CS + c8 * 8) = r0[u];
+        *(u32x4 *)(T1 + row * CS + c8 * 8) = r1[u];
+    }
+}
+
 // ---------------------------------------------------------------------------
-// Attention backward (derivative of Eq. 6 with Eq. 1) of one (image, region, block of up to 64
-// queries) over the region's k n <= 64 routed keys.  The workgroup copies the K, V rows of the
-// keys (found by index in the projected maps, Eq. 6) and the Q, dO rows of its queries into LDS.
-// Per head, wavefront w owns queries 16 w .. 16 w + 15:
+// Query side of the attention backward (derivative of Eq. 6 with Eq. 1) for one (image, region,
+// block of up to 64 queries) over the region's k n <= 64 routed keys.  The workgroup copies the K,
+// V rows of the keys (found by index in the projected maps, Eq. 6) and the Q, dO rows of its
+// queries into LDS.  A wavefront takes (16-query tile, head) pairs:
 //     S^T = K Q^T and dP^T = V dO^T          (A operand: key rows, B operand: the query's row)
 //     P = softmax over the keys, D = sum_j P_j dP_j, dS = scale P (dP - D)      (registers)
 //     O^T = V^T P^T (attention output, needed for dWo) and dQ^T = K^T dS^T      (stored as bf16)
-// then P and dS go to LDS as bf16 [query][key] and wavefront w, now owning keys 16 w .. + 15,
-// forms dV = P^T dO and dK = dS^T Q (both operands by transposing reads, contraction over the 64
-// queries) and adds them to the float32 accumulators of the keys' tokens.
+// and leaves lse = log2 of the softmax denominator (with the scaled maximum folded in, so that
+// P = exp2(scale log2(e) s - lse)) and D per (token, head) for the key-side kernel.
 // dQ has row pitch ldq (it is the first third of the [M][3C] gradient map).
 template <int C>
-__global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
-                                                  const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
-                                                  const int32_t *__restrict__ Ir, bf16_t *__restrict__ O,
-                                                  bf16_t *__restrict__ dQ, int ldq, float *__restrict__ dK,
-                                                  float *__restrict__ dV, Dims D, int qchunks)
+__global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                    const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
+                                                    const int32_t *__restrict__ Ir, bf16_t *__restrict__ O,
+                                                    bf16_t *__restrict__ dQ, int ldq, float *__restrict__ lse,
+                                                    float *__restrict__ dsum, Dims D, int qchunks)
 {
     using L = BwdSmem<C>;
-    constexpr int CS = L::CS, PP = L::PP, CH8 = C / 8, NL = 64 * CH8 / 256;
+    constexpr int CS = L::CS, HEADS = L::HEADS;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::tile, *Qs = Vs + L::tile, *dOs = Qs + L::tile;
-    bf16_t *Ps = Ks + L::p_off, *dSs = Ks + L::ds_off;
-    int *ktok = (int *)(Ks + L::tok_off), *qtok = ktok + 64;
+    int *ktok = (int *)(smem + L::tok_off), *qtok = ktok + 64;
 
     const int qc = blockIdx.x % qchunks, r = (blockIdx.x / qchunks) % D.R, b = blockIdx.x / (qchunks * D.R);
     const int nq = min(64, D.n - 64 * qc), kn = D.kn;
     const size_t img = (size_t)b * D.N;
-
-    // token (within the image) of slot s of region j (Sec. 3.2: regions tile the map row-major)
-    auto token = [&](int region, int slot) {
-        const int ry = region / D.S, rx = region % D.S, sy = slot / D.rw, sx = slot % D.rw;
-        return (ry * D.rh + sy) * D.W + rx * D.rw + sx;
-    };
     if (threadIdx.x < 64) {
         const int l = threadIdx.x;
         int t = -1;
         if (l < kn) {
             const int j = Ir[((size_t)b * D.R + r) * D.k + l / D.n];
-            t = token(min(max(j, 0), D.R - 1), l % D.n);
+            t = region_token(D, min(max(j, 0), D.R - 1), l % D.n);
         }
         ktok[l] = t;
     } else if (threadIdx.x < 128) {
         const int l = threadIdx.x - 64;
-        qtok[l] = l < nq ? token(r, 64 * qc + l) : -1;
+        qtok[l] = l < nq ? region_token(D, r, 64 * qc + l) : -1;
     }
     __syncthreads();
-#pragma unroll
-    for (int u = 0; u < NL; ++u) {
-        const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
-        const int kt = ktok[row], qt = qtok[row];
-        u32x4 kr = {0u, 0u, 0u, 0u}, vr = kr, qr = kr, gr = kr;
-        if (kt >= 0) {
-            kr = *(const u32x4 *)(K + (img + kt) * C + c8 * 8);
-            vr = *(const u32x4 *)(V + (img + kt) * C + c8 * 8);
-        }
-        if (qt >= 0) {
-            qr = *(const u32x4 *)(Q + (img + qt) * C + c8 * 8);
-            gr = *(const u32x4 *)(dO + (img + qt) * C + c8 * 8);
-        }
-        *(u32x4 *)(Ks + row * CS + c8 * 8) = kr;
-        *(u32x4 *)(Vs + row * CS + c8 * 8) = vr;
-        *(u32x4 *)(Qs + row * CS + c8 * 8) = qr;
-        *(u32x4 *)(dOs + row * CS + c8 * 8) = gr;
-    }
+    gather_rows<C>(Ks, Vs, K, V, img, ktok);
+    gather_rows<C>(Qs, dOs, Q, dO, img, qtok);
     __syncthreads();
 
     const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
-    const int q = 16 * w + i;
-    const int my_qtok = qtok[q];
     const float c_exp = D.scale * 1.4426950408889634f;
-    int my_ktok[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) my_ktok[j] = ktok[16 * w + 4 * g + j];
-
+    const int qtiles = (nq + 15) / 16;
 #pragma unroll 1
-    for (int h = 0; h < C / 32; ++h) {
-        const int col = 32 * h;
+    for (int task = w; task < qtiles * HEADS; task += 4) {
+        const int qt = task % qtiles, h = task / qtiles, col = 32 * h;
+        const int q = 16 * qt + i, my_qtok = qtok[q];
         const bf16x8 qf = *(const bf16x8 *)(Qs + q * CS + col + 8 * g);
         const bf16x8 gf = *(const bf16x8 *)(dOs + q * CS + col + 8 * g);
         f32x4 s[4], dp[4];
@@ -178,20 +189,21 @@ __global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t *__restrict__ Q, 
                 p[t][j] = __builtin_amdgcn_exp2f(fmaf(s[t][j], c_exp, -mc));
                 lsum += p[t][j];
             }
-        const float inv = (my_qtok >= 0) ? 1.0f / cross_row_sum(lsum) : 0.f;    // rows of missing queries: P = 0
-        float dsum = 0.f;
+        lsum = cross_row_sum(lsum);
+        const float inv = 1.0f / lsum;
+        float dd = 0.f;
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 p[t][j] *= inv;
-                dsum = fmaf(p[t][j], dp[t][j], dsum);
+                dd = fmaf(p[t][j], dp[t][j], dd);
             }
-        dsum = cross_row_sum(dsum);
+        dd = cross_row_sum(dd);
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) ds[t][j] = p[t][j] * (dp[t][j] - dsum) * D.scale;
+            for (int j = 0; j < 4; ++j) ds[t][j] = p[t][j] * (dp[t][j] - dd) * D.scale;
 
         f32x4 oacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
         f32x4 qacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
@@ -203,50 +215,158 @@ __global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t *__restrict__ Q, 
                 *(u32x2 *)(O + (img + my_qtok) * C + col + 16 * dt + 4 * g) = pack4(oacc[dt]);
                 *(u32x2 *)(dQ + (img + my_qtok) * (size_t)ldq + col + 16 * dt + 4 * g) = pack4(qacc[dt]);
             }
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            *(u32x2 *)(Ps + q * PP + 16 * t + 4 * g) = pack4(f32x4{p[t][0], p[t][1], p[t][2], p[t][3]});
-            *(u32x2 *)(dSs + q * PP + 16 * t + 4 * g) = pack4(f32x4{ds[t][0], ds[t][1], ds[t][2], ds[t][3]});
-        }
-        __syncthreads();
-
-        // keys 16 w .. 16 w + 15 against all 64 queries:
-        // dV[key 4 g + j][channel col + 16 dt + i] = sum_q P[q][key] dO[q][channel], dK likewise from dS, Q
-        f32x4 dv[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-        f32x4 dk[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const bf16x8 pa = tr_operand(Ps, PP, 32 * ks, 16 * w, g, i);
-            const bf16x8 da = tr_operand(dSs, PP, 32 * ks, 16 * w, g, i);
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt) {
-                dv[dt] = mfma16(pa, tr_operand(dOs, CS, 32 * ks, col + 16 * dt, g, i), dv[dt]);
-                dk[dt] = mfma16(da, tr_operand(Qs, CS, 32 * ks, col + 16 * dt, g, i), dk[dt]);
+            if (g == 0) {
+                lse[(img + my_qtok) * HEADS + h] = mc + __builtin_amdgcn_logf(lsum);     // v_log_f32: log2
+                dsum[(img + my_qtok) * HEADS + h] = dd;
             }
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (my_ktok[j] < 0) continue;
-            const size_t at = (img + my_ktok[j]) * C + col + i;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt) {
-                unsafeAtomicAdd(dV + at + 16 * dt, dv[dt][j]);
-                unsafeAtomicAdd(dK + at + 16 * dt, dk[dt][j]);
-            }
-        }
-        __syncthreads();      // the next head overwrites Ps, dSs
     }
 }
 
 // ---------------------------------------------------------------------------
-// Out[a0 + a][b0 + o] += sum_t A[t][a0 + a] Bm[t][b0 + o] over the workgroup's share of the M
-// tokens (the token contractions dWqkv = X^T dQKV and dWo = O^T dY): a 64 x 64 block of the
-// output per workgroup (blockIdx.y, blockIdx.z), both operands staged as [64 tokens][64 channels]
-// LDS tiles and read with transposing reads, float32 atomic adds at the end.  Out is zeroed
-// beforehand.  Wavefront w forms rows 16 w .. 16 w + 15 of the block.
+// Key side of the attention backward for one (image, key region j, block of up to 64 of its
+// tokens).  The workgroup collects the routing entries Ir[b][i][.] == j (every query region i
+// that attends to region j, once per entry), ordered by entry number when there are at most 256
+// (then the summation order, and so the result, is fixed).  The queries of those regions form one
+// list of rows, taken 64 at a time: their Q, dO rows and statistics go to LDS, and a wavefront
+// holding a (16-key tile, head) pair forms
+//     S = Q K^T and dP = dO V^T              (A operand: query rows, B operand: the key's row)
+//     P = exp2(scale log2(e) S - lse), dS = scale P (dP - D)               (registers)
+//     dV^T += dO^T P and dK^T += Q^T dS      (A operand by transposing reads, B = P, dS as they are)
+// in float32 registers across all query blocks; at the end dK, dV of its tokens are stored once as
+// bf16 into the second and third thirds of the [M][3C] gradient map (dKV points at the second).
+// Regions that no query attends to get zeros.
+template <int C>
+__global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                     const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
+                                                     const int32_t *__restrict__ Ir, const float *__restrict__ lse,
+                                                     const float *__restrict__ dsum, bf16_t *__restrict__ dKV,
+                                                     int ld, Dims D, int kchunks)
+{
+    using L = BwdSmem<C>;
+    constexpr int CS = L::CS, HEADS = L::HEADS;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::tile, *Qs = Vs + L::tile, *dOs = Qs + L::tile;
+    int *ktok = (int *)(smem + L::tok_off), *qtok = ktok + 64;
+    float *lse_s = (float *)(smem + L::stat_off), *dd_s = lse_s + HEADS * 64;
+    int *count = (int *)(smem + L::list_off), *list = count + 4;
+
+    const int kc = blockIdx.x % kchunks, jr = (blockIdx.x / kchunks) % D.R, b = blockIdx.x / (kchunks * D.R);
+    const int nk = min(64, D.n - 64 * kc);
+    const size_t img = (size_t)b * D.N;
+    if (threadIdx.x < 64) ktok[threadIdx.x] = (int)threadIdx.x < nk ? region_token(D, jr, 64 * kc + threadIdx.x) : -1;
+    if (threadIdx.x == 64) *count = 0;
+    __syncthreads();
+    const int entries = D.R * D.k;
+    const int32_t *irb = Ir + (size_t)b * entries;
+    for (int e = threadIdx.x; e < entries; e += 256)
+        if (min(max(irb[e], 0), D.R - 1) == jr) list[atomicAdd(count, 1)] = e;
+    gather_rows<C>(Ks, Vs, K, V, img, ktok);
+    __syncthreads();
+    const int m = *count;
+    if (m > 1 && m <= 256) {              // rank sort: entry numbers are distinct
+        const int mine = (int)threadIdx.x < m ? list[threadIdx.x] : 0;
+        int rank = 0;
+        for (int u = 0; u < m; ++u) rank += list[u] < mine;
+        __syncthreads();
+        if ((int)threadIdx.x < m) list[rank] = mine;
+    }
+
+    const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
+    const float c_exp = D.scale * 1.4426950408889634f;
+    const int ktiles = (nk + 15) / 16, ntasks = ktiles * HEADS;
+    f32x4 acc[HEADS][4];                  // per task of this wavefront: dV^T (2 channel tiles), dK^T (2)
+#pragma unroll
+    for (int u = 0; u < HEADS; ++u)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) acc[u][a] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int rows = m * D.n;
+    for (int r0 = 0; r0 < rows; r0 += 64) {
+        __syncthreads();                  // the list is in place; the previous block's readers are done
+        if (threadIdx.x < 64) {
+            const int rho = r0 + threadIdx.x;
+            int t = -1;
+            if (rho < rows) t = region_token(D, list[rho / D.n] / D.k, rho % D.n);
+            qtok[threadIdx.x] = t;
+        }
+        __syncthreads();
+        gather_rows<C>(Qs, dOs, Q, dO, img, qtok);
+        for (int idx = threadIdx.x; idx < 64 * HEADS; idx += 256) {
+            const int row = idx / HEADS, h = idx % HEADS, t = qtok[row];
+            // a missing row: P = exp2(-inf) = 0 and dS = 0
+            lse_s[h * 64 + row] = t >= 0 ? lse[(img + t) * HEADS + h] : INFINITY;
+            dd_s[h * 64 + row] = t >= 0 ? dsum[(img + t) * HEADS + h] : 0.f;
+        }
+        __syncthreads();
+        const int qtiles = (min(64, rows - r0) + 15) / 16;
+#pragma unroll
+        for (int u = 0; u < HEADS; ++u) {
+            const int task = w + 4 * u;
+            if (task >= ntasks) continue;
+            const int kt = task % ktiles, h = task / ktiles, col = 32 * h;
+            const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * kt + i) * CS + col + 8 * g);
+            const bf16x8 vf = *(const bf16x8 *)(Vs + (16 * kt + i) * CS + col + 8 * g);
+            float p[4][4], ds[4][4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (t < qtiles) {
+                    const bf16x8 qf = *(const bf16x8 *)(Qs + (16 * t + i) * CS + col + 8 * g);
+                    const bf16x8 gf = *(const bf16x8 *)(dOs + (16 * t + i) * CS + col + 8 * g);
+                    const f32x4 s = mfma16(qf, kf, f32x4{0.f, 0.f, 0.f, 0.f});    // S[query 16 t + 4 g + j][key i]
+                    const f32x4 dp = mfma16(gf, vf, f32x4{0.f, 0.f, 0.f, 0.f});
+                    const f32x4 l4 = *(const f32x4 *)(lse_s + h * 64 + 16 * t + 4 * g);
+                    const f32x4 d4 = *(const f32x4 *)(dd_s + h * 64 + 16 * t + 4 * g);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        p[t][j] = __builtin_amdgcn_exp2f(fmaf(s[j], c_exp, -l4[j]));
+                        ds[t][j] = p[t][j] * (dp[j] - d4[j]) * D.scale;
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) p[t][j] = ds[t][j] = 0.f;
+                }
+            }
+#pragma unroll
+            for (int tp = 0; tp < 2; ++tp) {
+                if (2 * tp >= qtiles) continue;
+                const float pv[8] = {p[2 * tp][0], p[2 * tp][1], p[2 * tp][2], p[2 * tp][3],
+                                     p[2 * tp + 1][0], p[2 * tp + 1][1], p[2 * tp + 1][2], p[2 * tp + 1][3]};
+                const float dv[8] = {ds[2 * tp][0], ds[2 * tp][1], ds[2 * tp][2], ds[2 * tp][3],
+                                     ds[2 * tp + 1][0], ds[2 * tp + 1][1], ds[2 * tp + 1][2], ds[2 * tp + 1][3]};
+                const bf16x8 pb = pack8(pv), db = pack8(dv);
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    acc[u][dt] = mfma16(tr_operand(dOs, CS, 32 * tp, col + 16 * dt, g, i), pb, acc[u][dt]);
+                    acc[u][2 + dt] = mfma16(tr_operand(Qs, CS, 32 * tp, col + 16 * dt, g, i), db, acc[u][2 + dt]);
+                }
+            }
+        }
+    }
+    // acc[u][.][j] = gradient of channel col + 16 dt + 4 g + j of key 16 kt + i
+#pragma unroll
+    for (int u = 0; u < HEADS; ++u) {
+        const int task = w + 4 * u;
+        if (task >= ntasks) continue;
+        const int kt = task % ktiles, h = task / ktiles, col = 32 * h;
+        const int t = ktok[16 * kt + i];
+        if (t < 0) continue;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+            *(u32x2 *)(dKV + (img + t) * (size_t)ld + col + 16 * dt + 4 * g) = pack4(acc[u][2 + dt]);
+            *(u32x2 *)(dKV + (img + t) * (size_t)ld + C + col + 16 * dt + 4 * g) = pack4(acc[u][dt]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Part[blockIdx.x][a][o] = sum_t A[t][a] Bm[t][o] over the workgroup's share of the M tokens (the
+// token contractions dWqkv = X^T dQKV and dWo = O^T dY): a 64 x 64 block (blockIdx.y, blockIdx.z)
+// of the [Ca][ldo] output per workgroup, both operands staged as [64 tokens][64 channels] LDS
+// tiles and read with transposing reads.  Wavefront w forms rows 16 w .. 16 w + 15 of the block.
+// k_reduce_parts then sums the partial matrices.
 __global__ __launch_bounds__(256) void k_gemm_tn(const bf16_t *__restrict__ A, int lda,
-                                                 const bf16_t *__restrict__ Bm, int ldb, float *__restrict__ Out,
+                                                 const bf16_t *__restrict__ Bm, int ldb, float *__restrict__ Part,
                                                  int ldo, long M, int tokens_per_wg)
 {
     constexpr int TP = 64 + 16;
@@ -289,12 +409,11 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const bf16_t *__restrict__ A, i
         }
         __syncthreads();
     }
-    if (t_begin >= t_end) return;
+    float *out = Part + (size_t)blockIdx.x * (64 * gridDim.y) * ldo;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            unsafeAtomicAdd(Out + (size_t)(a0 + 16 * w + 4 * g + j) * ldo + b0 + 16 * ct + i, acc[ct][j]);
+        for (int j = 0; j < 4; ++j) out[(size_t)(a0 + 16 * w + 4 * g + j) * ldo + b0 + 16 * ct + i] = acc[ct][j];
 }
 
 // ---------------------------------------------------------------------------
@@ -303,13 +422,13 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const bf16_t *__restrict__ A, i
 // with respect to its taps; V is zero outside the image).  A tile is kBwTileH x kBwTileW tokens of
 // one image and 64 channels: V with a 2-token halo in LDS, a thread handles a pair of channels
 // and 4-token row segments and keeps the 2 x 25 sums in registers; the workgroup reduces them
-// through LDS and adds them to dWlce (zeroed beforehand) with float32 atomics.
+// through LDS and writes its partial sums Part[tile group][C][25] for k_reduce_parts.
 constexpr int kBwTileH = 4, kBwTileW = 32, kBwPitch = 64 + 8;
 constexpr int kBwHaloRows = (kBwTileH + 4) * (kBwTileW + 4);
 constexpr size_t kBwSmem = std::max((size_t)kBwHaloRows * kBwPitch * 2, (size_t)4 * 32 * 50 * 4);
 
 __global__ __launch_bounds__(256) void k_lce_bwd_w(const bf16_t *__restrict__ dO, const bf16_t *__restrict__ V,
-                                                   float *__restrict__ dW, Dims D, int tiles_total,
+                                                   float *__restrict__ Part, Dims D, int tiles_total,
                                                    int tiles_per_wg)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -387,68 +506,96 @@ __global__ __launch_bounds__(256) void k_lce_bwd_w(const bf16_t *__restrict__ dO
     for (int idx = threadIdx.x; idx < 32 * 50; idx += 256) {
         const float v = Rs[idx] + Rs[32 * 50 + idx] + Rs[2 * 32 * 50 + idx] + Rs[3 * 32 * 50 + idx];
         // idx = cpair * 50 + 25 * (channel of the pair) + tap
-        unsafeAtomicAdd(dW + (size_t)(c0 + 2 * (idx / 50) + (idx % 50) / 25) * 25 + idx % 25, v);
+        Part[((size_t)(blockIdx.x / NCH) * C + c0 + 2 * (idx / 50) + (idx % 50) / 25) * 25 + idx % 25] = v;
     }
 }
 
 // ---------------------------------------------------------------------------
-// Small element-wise kernels.
-
 // WT[o][c] = Wqkv[c][o] ([3C][C]), WoT[o][c] = Wo[c][o], WlF[c][t] = Wlce[c][24 - t] (the taps
-// of the transposed correlation), and zeros in the three weight gradients.
+// of the transposed correlation).
 __global__ void k_bwd_prep(const bf16_t *__restrict__ Wqkv, const bf16_t *__restrict__ Wo,
                            const bf16_t *__restrict__ Wlce, bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT,
-                           bf16_t *__restrict__ WlF, float *__restrict__ dWqkv, float *__restrict__ dWo,
-                           float *__restrict__ dWlce, int C)
+                           bf16_t *__restrict__ WlF, int C)
 {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e < 3 * C * C) {
         const int o = e / C, c = e % C;
         WT[e] = Wqkv[(size_t)c * 3 * C + o];
-        dWqkv[e] = 0.f;
     } else if (e < 4 * C * C) {
         const int f = e - 3 * C * C, o = f / C, c = f % C;
         WoT[f] = Wo[(size_t)c * C + o];
-        dWo[f] = 0.f;
     } else if (e < 4 * C * C + 25 * C) {
         const int f = e - 4 * C * C, c = f / 25, t = f % 25;
         WlF[f] = Wlce[c * 25 + 24 - t];
-        dWlce[f] = 0.f;
     }
 }
 
-__global__ void k_zero16(u32x4 *__restrict__ p, size_t count)
-{
-    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e < count) p[e] = u32x4{0u, 0u, 0u, 0u};
-}
+// out[e] = sum_p part[p][e], p in a fixed order, for up to three arrays in one launch: 64
+// elements x 16 slices of p per workgroup, the slices summed through LDS.
+struct ReduceJob {
+    const float *part;
+    float *out;
+    int nparts, count, blocks;
+};
 
-// dQKV[t][C + c] = bf16(dK[t][c]), dQKV[t][2C + c] = bf16(dV[t][c] + G[t][c]) with G = LCE^T(dO):
-// 8 channels per thread.
-__global__ void k_bwd_pack(const float *__restrict__ dK, const float *__restrict__ dV,
-                           const bf16_t *__restrict__ G, bf16_t *__restrict__ dQKV, size_t chunks, int C)
+__global__ __launch_bounds__(1024) void k_reduce_parts(ReduceJob j0, ReduceJob j1, ReduceJob j2)
 {
-    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= chunks) return;
-    const int c8 = C / 8;
-    const size_t t = e / c8;
-    const int c = (int)(e % c8) * 8;
-    const f32x4 k0 = *(const f32x4 *)(dK + t * C + c), k1 = *(const f32x4 *)(dK + t * C + c + 4);
-    const f32x4 v0 = *(const f32x4 *)(dV + t * C + c), v1 = *(const f32x4 *)(dV + t * C + c + 4);
-    const u32x4 gv = *(const u32x4 *)(G + t * C + c);
-    const u32x4 ko = {pack_bf16(k0[0], k0[1]), pack_bf16(k0[2], k0[3]), pack_bf16(k1[0], k1[1]), pack_bf16(k1[2], k1[3])};
-    const u32x4 vo = {pack_bf16(v0[0] + bf16_lo(gv[0]), v0[1] + bf16_hi(gv[0])),
-                      pack_bf16(v0[2] + bf16_lo(gv[1]), v0[3] + bf16_hi(gv[1])),
-                      pack_bf16(v1[0] + bf16_lo(gv[2]), v1[1] + bf16_hi(gv[2])),
-                      pack_bf16(v1[2] + bf16_lo(gv[3]), v1[3] + bf16_hi(gv[3]))};
-    *(u32x4 *)(dQKV + t * 3 * C + C + c) = ko;
-    *(u32x4 *)(dQKV + t * 3 * C + 2 * C + c) = vo;
+    __shared__ float red[16][64];
+    int bi = blockIdx.x;
+    ReduceJob job = j0;
+    if (bi >= j0.blocks) {
+        bi -= j0.blocks;
+        job = j1;
+        if (bi >= j1.blocks) {
+            bi -= j1.blocks;
+            job = j2;
+        }
+    }
+    const int x = threadIdx.x % 64, y = threadIdx.x / 64, e = bi * 64 + x;
+    float sum = 0.f;
+    if (e < job.count)
+        for (int p = y; p < job.nparts; p += 16) sum += job.part[(size_t)p * job.count + e];
+    red[y][x] = sum;
+    __syncthreads();
+    if (y == 0 && e < job.count) {
+        float total = 0.f;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) total += red[u][x];
+        job.out[e] = total;
+    }
 }
 
 // ---------------------------------------------------------------------------
+// Token shares of k_gemm_tn: about 1024 workgroups over the 64 x 64 output blocks.
+struct TnPlan {
+    int gx, tokens_per_wg;
+};
+
+TnPlan tn_plan(long M, int Ca, int Cb)
+{
+    const long steps = (M + 63) / 64;
+    const long want = std::max(1L, 1024L / ((Ca / 64) * (Cb / 64)));
+    const long per_wg = (steps + want - 1) / want;
+    return TnPlan{(int)((steps + per_wg - 1) / per_wg), (int)(per_wg * 64)};
+}
+
+struct TapPlan {
+    int tiles, per_wg, groups;
+};
+
+TapPlan tap_plan(const Dims &D)
+{
+    const int ytiles = (D.H + kBwTileH - 1) / kBwTileH, xtiles = (D.W + kBwTileW - 1) / kBwTileW;
+    TapPlan t;
+    t.tiles = D.B * ytiles * xtiles;
+    t.per_wg = (t.tiles + 511) / 512;
+    t.groups = (t.tiles + t.per_wg - 1) / t.per_wg;
+    return t;
+}
+
 struct BwdWs {
-    bf16_t *q, *k, *v, *dO, *o, *g, *dqkv, *wt, *wot, *wlf;
-    float *dk, *dv;
+    bf16_t *q, *k, *v, *dO, *o, *dqkv, *wt, *wot, *wlf;
+    float *lse, *dsum, *part_qkv, *part_o, *part_lce;
     size_t bytes;
 };
 
@@ -461,7 +608,8 @@ BwdWs carve_bwd(const Dims &D, void *ws)
         off += (bytes + 255) & ~(size_t)255;
         return p;
     };
-    const size_t MC = (size_t)D.B * D.N * D.C, C = D.C;
+    const long M = (long)D.B * D.N;
+    const size_t MC = (size_t)M * D.C, C = D.C;
     BwdWs w;
     w.q = (bf16_t *)take(MC * 2);
     w.k = (bf16_t *)take(MC * 2);
@@ -469,11 +617,11 @@ BwdWs carve_bwd(const Dims &D, void *ws)
     w.dO = (bf16_t *)take(MC * 2);
     w.o = (bf16_t *)take(MC * 2);
     w.dqkv = (bf16_t *)take(MC * 6);
-    // dk, dv, g are zeroed by one fill: keep them adjacent (MC * 4 and MC * 2 are multiples of 256 or
-    // the fill covers the padding too)
-    w.dk = (float *)take(MC * 4);
-    w.dv = (float *)take(MC * 4);
-    w.g = (bf16_t *)take(MC * 2);
+    w.lse = (float *)take((size_t)M * (C / 32) * 4);
+    w.dsum = (float *)take((size_t)M * (C / 32) * 4);
+    w.part_qkv = (float *)take((size_t)tn_plan(M, D.C, 3 * D.C).gx * 3 * C * C * 4);
+    w.part_o = (float *)take((size_t)tn_plan(M, D.C, D.C).gx * C * C * 4);
+    w.part_lce = (float *)take((size_t)tap_plan(D).groups * 25 * C * 4);
     w.wt = (bf16_t *)take(3 * C * C * 2);
     w.wot = (bf16_t *)take(C * C * 2);
     w.wlf = (bf16_t *)take(25 * C * 2);
@@ -481,32 +629,38 @@ BwdWs carve_bwd(const Dims &D, void *ws)
     return w;
 }
 
+bool launched() { return hipGetLastError() == hipSuccess; }
+
 template <int C>
 int attn_bwd(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
-    static bool opted = false;
-    if (!opt_in(k_attn_bwd<C>, opted)) return BRA_ERR_LAUNCH;
-    const int qchunks = (D.n + 63) / 64;
-    const long blocks = (long)D.B * D.R * qchunks;
+    static bool opted[2] = {false, false};
+    if (!opt_in(k_attn_bwd_q<C>, opted[0]) || !opt_in(k_attn_bwd_kv<C>, opted[1])) return BRA_ERR_LAUNCH;
+    const int chunks = (D.n + 63) / 64;
+    const long blocks = (long)D.B * D.R * chunks;
+    {
+        ProfScope ps(st, K_GEN_BACKWARD);
+        hipLaunchKernelGGL(k_attn_bwd_q<C>, dim3((unsigned)blocks), dim3(256), BwdSmem<C>::q_bytes, st, w.q, w.k, w.v,
+                           w.dO, Ir, w.o, w.dqkv, 3 * C, w.lse, w.dsum, D, chunks);
+        if (!launched()) return BRA_ERR_LAUNCH;
+    }
     ProfScope ps(st, K_GEN_BACKWARD);
-    hipLaunchKernelGGL(k_attn_bwd<C>, dim3((unsigned)blocks), dim3(256), BwdSmem<C>::bytes, st, w.q, w.k, w.v, w.dO,
-                       Ir, w.o, w.dqkv, 3 * C, w.dk, w.dv, D, qchunks);
-    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+    hipLaunchKernelGGL(k_attn_bwd_kv<C>, dim3((unsigned)blocks), dim3(256), BwdSmem<C>::kv_bytes(D.R * D.k), st, w.q,
+                       w.k, w.v, w.dO, Ir, w.lse, w.dsum, w.dqkv + C, 3 * C, D, chunks);
+    return launched() ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
-int gemm_tn(const bf16_t *A, int lda, int Ca, const bf16_t *Bm, int ldb, int Cb, float *Out, int ldo, long M,
-            hipStream_t st)
+int gemm_tn(const bf16_t *A, int lda, int Ca, const bf16_t *Bm, int ldb, int Cb, float *Part, long M, hipStream_t st)
 {
-    const long steps = (M + 63) / 64;
-    const long per_wg = (steps + 383) / 384;             // about 384 token shares
-    const int gx = (int)((steps + per_wg - 1) / per_wg);
+    const TnPlan t = tn_plan(M, Ca, Cb);
     ProfScope ps(st, K_GEN_BACKWARD);
-    hipLaunchKernelGGL(k_gemm_tn, dim3(gx, Ca / 64, Cb / 64), dim3(256), 0, st, A, lda, Bm, ldb, Out, ldo, M,
-                       (int)(per_wg * 64));
-    return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
+    hipLaunchKernelGGL(k_gemm_tn, dim3(t.gx, Ca / 64, Cb / 64), dim3(256), 0, st, A, lda, Bm, ldb, Part, Cb, M,
+                       t.tokens_per_wg);
+    return launched() ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
-bool launched() { return hipGetLastError() == hipSuccess; }
+// The routing entries of an image must fit the key-side kernel's list in LDS.
+constexpr int kBwdMaxEntries = 4096;
 
 }  // namespace
 
@@ -514,6 +668,7 @@ bool mfma_backward_supported(const Dims &D)
 {
     static const bool off = experiment_flag("BRA_NO_MFMA_BACKWARD");
     if (off || D.dtype != BRA_BF16 || D.d != 32 || (D.C != 64 && D.C != 128) || D.kn > 64) return false;
+    if ((long)D.R * D.k > kBwdMaxEntries) return false;
     const long M = (long)D.B * D.N;
     return M * 3 * D.C < (1L << 40) && (long)D.B * D.R * ((D.n + 63) / 64) <= 0x7fffffffL && M <= 0x7fffffffL;
 }
@@ -527,56 +682,47 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
     const BwdWs w = carve_bwd(D, ws);
     const int C = D.C;
     const long M = (long)D.B * D.N;
-    const size_t MC = (size_t)M * C;
     {
         ProfScope ps(st, K_GEN_BACKWARD);
         const int total = 4 * C * C + 25 * C;
         hipLaunchKernelGGL(k_bwd_prep, dim3((total + 255) / 256), dim3(256), 0, st, (const bf16_t *)Wqkv,
-                           (const bf16_t *)Wo, (const bf16_t *)Wlce, w.wt, w.wot, w.wlf, dWqkv, dWo, dWlce, C);
-        if (!launched()) return BRA_ERR_LAUNCH;
-    }
-    {
-        ProfScope ps(st, K_GEN_BACKWARD);
-        const size_t count = (size_t)((char *)w.g - (char *)w.dk + MC * 2 + 15) / 16;   // dk | dv | g
-        hipLaunchKernelGGL(k_zero16, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, (u32x4 *)w.dk, count);
+                           (const bf16_t *)Wo, (const bf16_t *)Wlce, w.wt, w.wot, w.wlf, C);
         if (!launched()) return BRA_ERR_LAUNCH;
     }
     int rc = mfma_project_qkv(D, X, Wqkv, w.q, w.k, w.v, st);                 // Q, K, V once more (Eq. 3)
     if (rc != BRA_OK) return rc;
     rc = mfma_project(D, dY, w.wot, w.dO, st);                                // dO = dY Wo^T
     if (rc != BRA_OK) return rc;
-    rc = (C == 64) ? attn_bwd<64>(D, w, Ir, st) : attn_bwd<128>(D, w, Ir, st);
+    rc = (C == 64) ? attn_bwd<64>(D, w, Ir, st) : attn_bwd<128>(D, w, Ir, st);   // O, dQ; then dK, dV
     if (rc != BRA_OK) return rc;
     AttnArgs A = {};
     A.V = w.v; A.Wlce = (const bf16_t *)Wlce;
-    rc = launch_lce_add_any(D, A, w.o, st);                                   // O = attention + LCE(V)  (Eq. 7)
+    rc = launch_lce_add_any(D, A, w.o, st, C, true);                          // O = attention + LCE(V)  (Eq. 7)
     if (rc != BRA_OK) return rc;
     A.V = w.dO; A.Wlce = w.wlf;
-    rc = launch_lce_add_any(D, A, w.g, st);                                   // G = LCE^T(dO)
+    rc = launch_lce_add_any(D, A, w.dqkv + 2 * C, st, 3 * C, true);           // dV += LCE^T(dO)
     if (rc != BRA_OK) return rc;
-    {
-        ProfScope ps(st, K_GEN_BACKWARD);
-        const size_t chunks = MC / 8;
-        hipLaunchKernelGGL(k_bwd_pack, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, w.dk, w.dv, w.g,
-                           w.dqkv, chunks, C);
-        if (!launched()) return BRA_ERR_LAUNCH;
-    }
     rc = gemm_bf16(w.dqkv, w.wt, M, 3 * C, C, (bf16_t *)dX, nullptr, nullptr, false, K_GEN_BACKWARD, st);
     if (rc != BRA_OK) return rc;
-    rc = gemm_tn((const bf16_t *)X, C, C, w.dqkv, 3 * C, 3 * C, dWqkv, 3 * C, M, st);
+    rc = gemm_tn((const bf16_t *)X, C, C, w.dqkv, 3 * C, 3 * C, w.part_qkv, M, st);
     if (rc != BRA_OK) return rc;
-    rc = gemm_tn(w.o, C, C, (const bf16_t *)dY, C, C, dWo, C, M, st);
+    rc = gemm_tn(w.o, C, C, (const bf16_t *)dY, C, C, w.part_o, M, st);
     if (rc != BRA_OK) return rc;
+    const TapPlan tp = tap_plan(D);
     {
-        const int ytiles = (D.H + kBwTileH - 1) / kBwTileH, xtiles = (D.W + kBwTileW - 1) / kBwTileW;
-        const int tiles = D.B * ytiles * xtiles;
-        const int per_wg = (tiles + 511) / 512;
-        const int groups = (tiles + per_wg - 1) / per_wg;
         static bool opted = false;
         if (!opt_in(k_lce_bwd_w, opted)) return BRA_ERR_LAUNCH;
         ProfScope ps(st, K_GEN_BACKWARD);
-        hipLaunchKernelGGL(k_lce_bwd_w, dim3(groups * (C / 64)), dim3(256), kBwSmem, st, w.dO, w.v, dWlce, D, tiles,
-                           per_wg);
+        hipLaunchKernelGGL(k_lce_bwd_w, dim3(tp.groups * (C / 64)), dim3(256), kBwSmem, st, w.dO, w.v, w.part_lce, D,
+                           tp.tiles, tp.per_wg);
+        if (!launched()) return BRA_ERR_LAUNCH;
+    }
+    {
+        const ReduceJob j0{w.part_qkv, dWqkv, tn_plan(M, C, 3 * C).gx, 3 * C * C, (3 * C * C + 63) / 64};
+        const ReduceJob j1{w.part_o, dWo, tn_plan(M, C, C).gx, C * C, (C * C + 63) / 64};
+        const ReduceJob j2{w.part_lce, dWlce, tp.groups, 25 * C, (25 * C + 63) / 64};
+        ProfScope ps(st, K_GEN_BACKWARD);
+        hipLaunchKernelGGL(k_reduce_parts, dim3(j0.blocks + j1.blocks + j2.blocks), dim3(1024), 0, st, j0, j1, j2);
         if (!launched()) return BRA_ERR_LAUNCH;
     }
     return BRA_OK;

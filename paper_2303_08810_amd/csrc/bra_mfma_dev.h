@@ -631,7 +631,10 @@ int launch_small(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t 
 // (image-resident attention; A.Q/K/V, Ir_src, Ir_out, Wlce, c_exp set).
 bool map_tail_supported(const Dims &D);
 int launch_map_tail(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st);
-int launch_lce_add_any(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st);   // O += LCE(V), any map, C % 64 == 0
+// O += LCE(V) for any map, C % 64 == 0.  ldo: elements between rows of O (0: C); square_tiles: 4 x 32 token
+// tiles instead of full-width rows.
+int launch_lce_add_any(const Dims &D, const mfma::AttnArgs &A, bf16_t *O, hipStream_t st, int ldo = 0,
+                       bool square_tiles = false);
 
 // Attention + LCE + W^o for regions of 64 n tokens with 32 queries per wavefront
 // (bra_mfma_attn.hip); A.Q must hold Q multiplied by scale * log2(e).

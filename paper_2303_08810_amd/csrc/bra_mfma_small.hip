@@ -651,7 +651,7 @@ __global__ __launch_bounds__(kMapThreads) void k_attn_map4(AttnArgs A, bf16_t *_
 constexpr int kLceChunk = 64, kLcePitch = kLceChunk + 8;
 
 __global__ __launch_bounds__(256) void k_lce_add(bf16_t *__restrict__ O, const bf16_t *__restrict__ V,
-                                                 const bf16_t *__restrict__ Wlce, Dims D, int TH, int TW)
+                                                 const bf16_t *__restrict__ Wlce, Dims D, int TH, int TW, int ldo)
 {
     constexpr int CH8 = kLceChunk / 8, NBH = 6;
     const int C = D.C, NCH = C / kLceChunk;
@@ -720,13 +720,14 @@ __global__ __launch_bounds__(256) void k_lce_add(bf16_t *__restrict__ O, const b
                 }
             }
         }
-        unsigned *orow = (unsigned *)(O + img_off + ((size_t)(y0 + r) * D.W + x0 + seg * 4) * C + c0 + 2 * cpair);
+        // rows of O are ldo elements apart (C for a map of its own, more for a slice of a wider map)
+        unsigned *orow = (unsigned *)(O + ((size_t)b * D.N + (size_t)(y0 + r) * D.W + x0 + seg * 4) * ldo + c0 + 2 * cpair);
         unsigned o2[4];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) o2[x] = seg * 4 + x < tw ? orow[(size_t)x * (C / 2)] : 0u;
+        for (int x = 0; x < 4; ++x) o2[x] = seg * 4 + x < tw ? orow[(size_t)x * (ldo / 2)] : 0u;
 #pragma unroll
         for (int x = 0; x < 4; ++x)
-            if (seg * 4 + x < tw) orow[(size_t)x * (C / 2)] = pack_bf16(bf16_lo(o2[x]) + a0[x], bf16_hi(o2[x]) + a1[x]);
+            if (seg * 4 + x < tw) orow[(size_t)x * (ldo / 2)] = pack_bf16(bf16_lo(o2[x]) + a0[x], bf16_hi(o2[x]) + a1[x]);
     }
 }
 
@@ -837,15 +838,19 @@ static int launch_map(const Dims &D, AttnArgs A, bf16_t *O, int log2n, hipStream
 }
 
 // O += LCE(V) in place.
-static int launch_lce_add(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st)
+static int launch_lce_add(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st, int ldo = 0,
+                          bool square_tiles = false)
 {
     static bool opted = false;
     if (!opt_in(k_lce_add, opted)) return BRA_ERR_LAUNCH;
-    const int TH = tile_rows(D), TW = tile_cols(D);
+    // square_tiles: 4 rows x up to 32 columns, fewer halo rows per token than full-width rows
+    const int TH = square_tiles ? 4 : tile_rows(D), TW = square_tiles ? std::min(D.W, 32) : tile_cols(D);
     const long blocks = (long)D.B * ((D.H + TH - 1) / TH) * ((D.W + TW - 1) / TW) * (D.C / kLceChunk);
     if (blocks > 0x7fffffffL) return BRA_ERR_UNSUPPORTED;
+    const size_t smem = (size_t)(TH + 4) * (TW + 4) * kLcePitch * 2;
     ProfScope ps(st, K_MFMA_LCE_ADD);
-    hipLaunchKernelGGL(k_lce_add, dim3((unsigned)blocks), dim3(256), lce_add_smem(D), st, O, A.V, A.Wlce, D, TH, TW);
+    hipLaunchKernelGGL(k_lce_add, dim3((unsigned)blocks), dim3(256), smem, st, O, A.V, A.Wlce, D, TH, TW,
+                       ldo ? ldo : D.C);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
@@ -886,9 +891,9 @@ bool map_tail_supported(const Dims &D)
 }
 
 // O += LCE(V) in place for any map (C a multiple of 64).
-int launch_lce_add_any(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st)
+int launch_lce_add_any(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st, int ldo, bool square_tiles)
 {
-    return launch_lce_add(D, A, O, st);
+    return launch_lce_add(D, A, O, st, ldo, square_tiles);
 }
 
 int launch_map_tail(const Dims &D, const AttnArgs &A, bf16_t *O, hipStream_t st)
