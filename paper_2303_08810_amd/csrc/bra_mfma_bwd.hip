@@ -10,10 +10,10 @@
 //     dK = dS^T Q,  dV = P^T dO        k_attn_bwd_kv, one workgroup per KEY region: it finds the query
 //                                      regions routed to it in Ir, recomputes their P and dS from the
 //                                      statistics and sums in registers, so no atomic adds are needed
-//     dV += LCE^T(dO)                  the forward's depth-wise kernel with the taps reversed
+//     O += LCE(V), dV += LCE^T(dO) (the correlation with the taps reversed) and
+//     dWlce[c][ky][kx] = sum_t dO[t][c] V[t + (ky - 2, kx - 2)][c]       k_lce_bwd
 //     dX = [dQ | dK | dV] Wqkv^T       one product with the transposed weights
 //     dWqkv = X^T [dQ | dK | dV],  dWo = O^T dY         k_gemm_tn (contraction over tokens)
-//     dWlce[c][ky][kx] = sum_t dO[t][c] V[t + (ky - 2, kx - 2)][c]       k_lce_bwd_w
 // All products take bf16 operands and accumulate in float32; dQ, dK, dV and dO are rounded to
 // bf16 between the kernels (they are matrix-core operands of the next product).  The weight
 // gradients are summed from per-workgroup partial sums in a fixed order (k_reduce_parts).
@@ -417,56 +417,99 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const bf16_t *__restrict__ A, i
 }
 
 // ---------------------------------------------------------------------------
-// dWlce[c][ky][kx] += sum over the tokens (y, x) of the workgroup's tiles of
-// dO[y][x][c] V[y + ky - 2][x + kx - 2][c] (derivative of the depth-wise 5x5 correlation of Eq. 7
-// with respect to its taps; V is zero outside the image).  A tile is kBwTileH x kBwTileW tokens of
-// one image and 64 channels: V with a 2-token halo in LDS, a thread handles a pair of channels
-// and 4-token row segments and keeps the 2 x 25 sums in registers; the workgroup reduces them
-// through LDS and writes its partial sums Part[tile group][C][25] for k_reduce_parts.
-constexpr int kBwTileH = 4, kBwTileW = 32, kBwPitch = 64 + 8;
-constexpr int kBwHaloRows = (kBwTileH + 4) * (kBwTileW + 4);
-constexpr size_t kBwSmem = std::max((size_t)kBwHaloRows * kBwPitch * 2, (size_t)4 * 32 * 50 * 4);
+// The three uses of the depth-wise 5x5 correlation (Eq. 7) in the backward pass, in one kernel.
+// A tile is kLbTH x kLbTW tokens of one image and 64 channels; a thread handles a pair of channels
+// and 4-token row segments.
+//   phase 1, V with a 2-token halo in LDS:   O += LCE(V)  (the forward's O, for dWo) and the tap
+//            gradients dWlce[c][ky][kx] = sum_t dO[t][c] V[t + (ky - 2, kx - 2)][c], 2 x 25 sums
+//            kept in registers across the workgroup's tiles (V is zero outside the image)
+//   phase 2, dO with its halo in the same LDS buffer:
+//            dV += LCE^T(dO), the correlation with the taps reversed; dV has row pitch ldv
+// Three workgroups per compute unit hide each other's halo loads (a register prefetch of the next
+// halo does not fit beside the 50 tap sums).  At the end the workgroup reduces its tap sums through
+// LDS and writes Part[tile group][C][25] for k_reduce_parts.
+constexpr int kLbTH = 4, kLbTW = 32, kLbHW = kLbTW + 4, kLbRows = (kLbTH + 4) * kLbHW, kLbPitch = 64 + 8;
+constexpr int kLbLoads = kLbRows * 8 / 256;
+static_assert(kLbRows * 8 % 256 == 0, "halo chunks divide among the threads");
+constexpr size_t kLbSmem = std::max((size_t)kLbRows * kLbPitch * 2, (size_t)4 * 32 * 50 * 4);
 
-__global__ __launch_bounds__(256) void k_lce_bwd_w(const bf16_t *__restrict__ dO, const bf16_t *__restrict__ V,
-                                                   float *__restrict__ Part, Dims D, int tiles_total,
-                                                   int tiles_per_wg)
+__device__ __forceinline__ void halo_fetch(u32x4 (&h)[kLbLoads], const bf16_t *__restrict__ M, size_t img_off,
+                                           int y0, int x0, int c0, const Dims &D)
+{
+#pragma unroll
+    for (int u = 0; u < kLbLoads; ++u) {
+        const int idx = threadIdx.x + 256 * u, row = idx / 8, c8 = idx % 8;
+        const int y = y0 - 2 + row / kLbHW, x = x0 - 2 + row % kLbHW;
+        h[u] = u32x4{0u, 0u, 0u, 0u};
+        if (y >= 0 && y < D.H && x >= 0 && x < D.W)
+            h[u] = *(const u32x4 *)(M + img_off + ((size_t)y * D.W + x) * D.C + c0 + c8 * 8);
+    }
+}
+
+__device__ __forceinline__ void halo_store(bf16_t *Hs, const u32x4 (&h)[kLbLoads])
+{
+#pragma unroll
+    for (int u = 0; u < kLbLoads; ++u) {
+        const int idx = threadIdx.x + 256 * u;
+        *(u32x4 *)(Hs + (idx / 8) * kLbPitch + (idx % 8) * 8) = h[u];
+    }
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_lce_bwd(bf16_t *__restrict__ O, bf16_t *__restrict__ dVm, int ldv,
+                                                 const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
+                                                 const bf16_t *__restrict__ Wlce, float *__restrict__ Part, Dims D,
+                                                 int tiles_total, int tiles_per_wg)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Hs = (bf16_t *)smem;
     const int C = D.C, NCH = C / 64;
-    const int ytiles = (D.H + kBwTileH - 1) / kBwTileH, xtiles = (D.W + kBwTileW - 1) / kBwTileW;
+    const int ytiles = (D.H + kLbTH - 1) / kLbTH, xtiles = (D.W + kLbTW - 1) / kLbTW;
     const int cc = blockIdx.x % NCH, c0 = 64 * cc;
     const int first_tile = (blockIdx.x / NCH) * tiles_per_wg;
+    const int last_tile = min(tiles_total, first_tile + tiles_per_wg);
     const int cpair = threadIdx.x % 32, grp = threadIdx.x / 32;
-    constexpr int hw = kBwTileW + 4;
+    unsigned wl[25];        // [W(c, 0..24) | W(c + 1, 0..24)] as 25 packed pairs
+#pragma unroll
+    for (int e = 0; e < 25; ++e) wl[e] = *(const unsigned *)(Wlce + (size_t)(c0 + 2 * cpair) * 25 + 2 * e);
+    auto tap = [&](int ch, int t) {   // weight of tap t of channel c + ch
+        const int e = 25 * ch + t;
+        return (e & 1) ? bf16_hi(wl[e / 2]) : bf16_lo(wl[e / 2]);
+    };
     float g0[25], g1[25];
 #pragma unroll
     for (int e = 0; e < 25; ++e) g0[e] = g1[e] = 0.f;
 
-    for (int tile = first_tile; tile < min(tiles_total, first_tile + tiles_per_wg); ++tile) {
-        const int xt = tile % xtiles, yt = (tile / xtiles) % ytiles, b = tile / (xtiles * ytiles);
-        const int y0 = yt * kBwTileH, x0 = xt * kBwTileW;
-        const int th = min(kBwTileH, D.H - y0), tw = min(kBwTileW, D.W - x0);
-        const size_t img_off = (size_t)b * D.N * C;
+    auto origin = [&](int tile, int &b, int &y0, int &x0) {
+        b = tile / (xtiles * ytiles);
+        y0 = ((tile / xtiles) % ytiles) * kLbTH;
+        x0 = (tile % xtiles) * kLbTW;
+    };
+    for (int tile = first_tile; tile < last_tile; ++tile) {
+        int b, y0, x0;
+        origin(tile, b, y0, x0);
+        const int th = min(kLbTH, D.H - y0), tw = min(kLbTW, D.W - x0);
+        const size_t img_off = (size_t)b * D.N * C, img_tok = (size_t)b * D.N;
         __syncthreads();          // the previous tile's readers are done
-        for (int idx = threadIdx.x; idx < kBwHaloRows * 8; idx += 256) {
-            const int row = idx / 8, c8 = idx % 8;
-            const int y = y0 - 2 + row / hw, x = x0 - 2 + row % hw;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (y >= 0 && y < D.H && x >= 0 && x < D.W)
-                v = *(const u32x4 *)(V + img_off + ((size_t)y * D.W + x) * C + c0 + c8 * 8);
-            *(u32x4 *)(Hs + row * kBwPitch + c8 * 8) = v;
+        {
+            u32x4 h[kLbLoads];
+            halo_fetch(h, V, img_off, y0, x0, c0, D);
+            halo_store(Hs, h);
         }
         __syncthreads();
-        const int segs = (tw + 3) / 4;
-        for (int task = grp; task < th * segs; task += 8) {
-            const int seg = task % segs, r = task / segs;
-            float d0[4], d1[4];
+#pragma unroll 1
+        for (int task = grp; task < kLbTH * (kLbTW / 4); task += 8) {
+            const int seg = task % (kLbTW / 4), r = task / (kLbTW / 4);
+            if (r >= th || seg * 4 >= tw) continue;
+            const size_t tok = (size_t)(y0 + r) * D.W + x0 + seg * 4;
+            const unsigned *drow = (const unsigned *)(dO + img_off + tok * C + c0 + 2 * cpair);
+            unsigned *orow = (unsigned *)(O + img_off + tok * C + c0 + 2 * cpair);
+            unsigned o2[4];
+            float d0[4], d1[4], a0[4] = {0.f, 0.f, 0.f, 0.f}, a1[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                unsigned u = 0u;
-                if (seg * 4 + x < tw)
-                    u = *(const unsigned *)(dO + img_off + ((size_t)(y0 + r) * D.W + x0 + seg * 4 + x) * C + c0 + 2 * cpair);
+                const bool in = seg * 4 + x < tw;
+                const unsigned u = in ? drow[(size_t)x * (C / 2)] : 0u;
+                o2[x] = in ? orow[(size_t)x * (C / 2)] : 0u;
                 d0[x] = bf16_lo(u);
                 d1[x] = bf16_hi(u);
             }
@@ -475,18 +518,68 @@ __global__ __launch_bounds__(256) void k_lce_bwd_w(const bf16_t *__restrict__ dO
                 float v0[8], v1[8];
 #pragma unroll
                 for (int x = 0; x < 8; ++x) {
-                    const unsigned u = *(const unsigned *)(Hs + ((r + ky) * hw + seg * 4 + x) * kBwPitch + 2 * cpair);
+                    const unsigned u = *(const unsigned *)(Hs + ((r + ky) * kLbHW + seg * 4 + x) * kLbPitch + 2 * cpair);
                     v0[x] = bf16_lo(u);
                     v1[x] = bf16_hi(u);
                 }
 #pragma unroll
-                for (int kx = 0; kx < 5; ++kx)
+                for (int kx = 0; kx < 5; ++kx) {
+                    const float w0 = tap(0, ky * 5 + kx), w1 = tap(1, ky * 5 + kx);
 #pragma unroll
                     for (int x = 0; x < 4; ++x) {
+                        a0[x] = fmaf(w0, v0[x + kx], a0[x]);
+                        a1[x] = fmaf(w1, v1[x + kx], a1[x]);
                         g0[ky * 5 + kx] = fmaf(d0[x], v0[x + kx], g0[ky * 5 + kx]);
                         g1[ky * 5 + kx] = fmaf(d1[x], v1[x + kx], g1[ky * 5 + kx]);
                     }
+                }
+                __builtin_amdgcn_sched_barrier(0);      // one halo row at a time: the tap sums fill the registers
             }
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                if (seg * 4 + x < tw)
+                    orow[(size_t)x * (C / 2)] = pack_bf16(bf16_lo(o2[x]) + a0[x], bf16_hi(o2[x]) + a1[x]);
+        }
+        __syncthreads();
+        {
+            u32x4 h[kLbLoads];
+            halo_fetch(h, dO, img_off, y0, x0, c0, D);
+            halo_store(Hs, h);
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int task = grp; task < kLbTH * (kLbTW / 4); task += 8) {
+            const int seg = task % (kLbTW / 4), r = task / (kLbTW / 4);
+            if (r >= th || seg * 4 >= tw) continue;
+            const size_t tok = img_tok + (size_t)(y0 + r) * D.W + x0 + seg * 4;
+            unsigned *vrow = (unsigned *)(dVm + tok * ldv + c0 + 2 * cpair);
+            unsigned o2[4];
+            float a0[4] = {0.f, 0.f, 0.f, 0.f}, a1[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int x = 0; x < 4; ++x) o2[x] = seg * 4 + x < tw ? vrow[(size_t)x * (ldv / 2)] : 0u;
+#pragma unroll
+            for (int ky = 0; ky < 5; ++ky) {
+                float v0[8], v1[8];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    const unsigned u = *(const unsigned *)(Hs + ((r + ky) * kLbHW + seg * 4 + x) * kLbPitch + 2 * cpair);
+                    v0[x] = bf16_lo(u);
+                    v1[x] = bf16_hi(u);
+                }
+#pragma unroll
+                for (int kx = 0; kx < 5; ++kx) {
+                    const float w0 = tap(0, 24 - (ky * 5 + kx)), w1 = tap(1, 24 - (ky * 5 + kx));
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        a0[x] = fmaf(w0, v0[x + kx], a0[x]);
+                        a1[x] = fmaf(w1, v1[x + kx], a1[x]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                if (seg * 4 + x < tw)
+                    vrow[(size_t)x * (ldv / 2)] = pack_bf16(bf16_lo(o2[x]) + a0[x], bf16_hi(o2[x]) + a1[x]);
         }
     }
     // lanes l and l + 32 of a wavefront hold the same channel pair; then the four wavefronts through LDS
@@ -511,11 +604,9 @@ __global__ __launch_bounds__(256) void k_lce_bwd_w(const bf16_t *__restrict__ dO
 }
 
 // ---------------------------------------------------------------------------
-// WT[o][c] = Wqkv[c][o] ([3C][C]), WoT[o][c] = Wo[c][o], WlF[c][t] = Wlce[c][24 - t] (the taps
-// of the transposed correlation).
+// WT[o][c] = Wqkv[c][o] ([3C][C]), WoT[o][c] = Wo[c][o].
 __global__ void k_bwd_prep(const bf16_t *__restrict__ Wqkv, const bf16_t *__restrict__ Wo,
-                           const bf16_t *__restrict__ Wlce, bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT,
-                           bf16_t *__restrict__ WlF, int C)
+                           bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT, int C)
 {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e < 3 * C * C) {
@@ -524,9 +615,6 @@ __global__ void k_bwd_prep(const bf16_t *__restrict__ Wqkv, const bf16_t *__rest
     } else if (e < 4 * C * C) {
         const int f = e - 3 * C * C, o = f / C, c = f % C;
         WoT[f] = Wo[(size_t)c * C + o];
-    } else if (e < 4 * C * C + 25 * C) {
-        const int f = e - 4 * C * C, c = f / 25, t = f % 25;
-        WlF[f] = Wlce[c * 25 + 24 - t];
     }
 }
 
@@ -554,6 +642,7 @@ __global__ __launch_bounds__(1024) void k_reduce_parts(ReduceJob j0, ReduceJob j
     const int x = threadIdx.x % 64, y = threadIdx.x / 64, e = bi * 64 + x;
     float sum = 0.f;
     if (e < job.count)
+#pragma unroll 8
         for (int p = y; p < job.nparts; p += 16) sum += job.part[(size_t)p * job.count + e];
     red[y][x] = sum;
     __syncthreads();
@@ -583,18 +672,20 @@ struct TapPlan {
     int tiles, per_wg, groups;
 };
 
+// Tiles of k_lce_bwd per workgroup: all workgroups resident at once (3 per compute unit).
 TapPlan tap_plan(const Dims &D)
 {
-    const int ytiles = (D.H + kBwTileH - 1) / kBwTileH, xtiles = (D.W + kBwTileW - 1) / kBwTileW;
+    const int ytiles = (D.H + kLbTH - 1) / kLbTH, xtiles = (D.W + kLbTW - 1) / kLbTW;
+    const int slots = (int)experiment_value("BRA_LCE_SLOTS", 512) / (D.C / 64);
     TapPlan t;
     t.tiles = D.B * ytiles * xtiles;
-    t.per_wg = (t.tiles + 511) / 512;
+    t.per_wg = (t.tiles + slots - 1) / slots;
     t.groups = (t.tiles + t.per_wg - 1) / t.per_wg;
     return t;
 }
 
 struct BwdWs {
-    bf16_t *q, *k, *v, *dO, *o, *dqkv, *wt, *wot, *wlf;
+    bf16_t *q, *k, *v, *dO, *o, *dqkv, *wt, *wot;
     float *lse, *dsum, *part_qkv, *part_o, *part_lce;
     size_t bytes;
 };
@@ -624,7 +715,6 @@ BwdWs carve_bwd(const Dims &D, void *ws)
     w.part_lce = (float *)take((size_t)tap_plan(D).groups * 25 * C * 4);
     w.wt = (bf16_t *)take(3 * C * C * 2);
     w.wot = (bf16_t *)take(C * C * 2);
-    w.wlf = (bf16_t *)take(25 * C * 2);
     w.bytes = off;
     return w;
 }
@@ -684,9 +774,9 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
     const long M = (long)D.B * D.N;
     {
         ProfScope ps(st, K_GEN_BACKWARD);
-        const int total = 4 * C * C + 25 * C;
+        const int total = 4 * C * C;
         hipLaunchKernelGGL(k_bwd_prep, dim3((total + 255) / 256), dim3(256), 0, st, (const bf16_t *)Wqkv,
-                           (const bf16_t *)Wo, (const bf16_t *)Wlce, w.wt, w.wot, w.wlf, C);
+                           (const bf16_t *)Wo, w.wt, w.wot, C);
         if (!launched()) return BRA_ERR_LAUNCH;
     }
     int rc = mfma_project_qkv(D, X, Wqkv, w.q, w.k, w.v, st);                 // Q, K, V once more (Eq. 3)
@@ -695,28 +785,22 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
     if (rc != BRA_OK) return rc;
     rc = (C == 64) ? attn_bwd<64>(D, w, Ir, st) : attn_bwd<128>(D, w, Ir, st);   // O, dQ; then dK, dV
     if (rc != BRA_OK) return rc;
-    AttnArgs A = {};
-    A.V = w.v; A.Wlce = (const bf16_t *)Wlce;
-    rc = launch_lce_add_any(D, A, w.o, st, C, true);                          // O = attention + LCE(V)  (Eq. 7)
-    if (rc != BRA_OK) return rc;
-    A.V = w.dO; A.Wlce = w.wlf;
-    rc = launch_lce_add_any(D, A, w.dqkv + 2 * C, st, 3 * C, true);           // dV += LCE^T(dO)
-    if (rc != BRA_OK) return rc;
+    const TapPlan tp = tap_plan(D);
+    {
+        // O = attention + LCE(V) (Eq. 7), dV += LCE^T(dO), tap-gradient partial sums
+        static bool opted = false;
+        if (!opt_in(k_lce_bwd, opted)) return BRA_ERR_LAUNCH;
+        ProfScope ps(st, K_GEN_BACKWARD);
+        hipLaunchKernelGGL(k_lce_bwd, dim3(tp.groups * (C / 64)), dim3(256), kLbSmem, st, w.o, w.dqkv + 2 * C, 3 * C,
+                           w.v, w.dO, (const bf16_t *)Wlce, w.part_lce, D, tp.tiles, tp.per_wg);
+        if (!launched()) return BRA_ERR_LAUNCH;
+    }
     rc = gemm_bf16(w.dqkv, w.wt, M, 3 * C, C, (bf16_t *)dX, nullptr, nullptr, false, K_GEN_BACKWARD, st);
     if (rc != BRA_OK) return rc;
     rc = gemm_tn((const bf16_t *)X, C, C, w.dqkv, 3 * C, 3 * C, w.part_qkv, M, st);
     if (rc != BRA_OK) return rc;
     rc = gemm_tn(w.o, C, C, (const bf16_t *)dY, C, C, w.part_o, M, st);
     if (rc != BRA_OK) return rc;
-    const TapPlan tp = tap_plan(D);
-    {
-        static bool opted = false;
-        if (!opt_in(k_lce_bwd_w, opted)) return BRA_ERR_LAUNCH;
-        ProfScope ps(st, K_GEN_BACKWARD);
-        hipLaunchKernelGGL(k_lce_bwd_w, dim3(tp.groups * (C / 64)), dim3(256), kBwSmem, st, w.dO, w.v, w.part_lce, D,
-                           tp.tiles, tp.per_wg);
-        if (!launched()) return BRA_ERR_LAUNCH;
-    }
     {
         const ReduceJob j0{w.part_qkv, dWqkv, tn_plan(M, C, 3 * C).gx, 3 * C * C, (3 * C * C + 63) / 64};
         const ReduceJob j1{w.part_o, dWo, tn_plan(M, C, C).gx, C * C, (C * C + 63) / 64};
