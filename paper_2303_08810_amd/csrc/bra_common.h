@@ -144,9 +144,10 @@ int padded_forward(const Dims &Dp, int H, int W, const void *X, const void *Wqkv
                    void *Y, int32_t *Ir_out_opt, const int32_t *Ir_in_opt, void *ws, int path, hipStream_t st);
 
 // The projection kernels of bra_mfma.hip for other passes (bf16, C = 64, 128 or 256): Q, K, V = X Wqkv
-// into three token maps; Out = In W for one row-major C x C matrix.
+// into three token maps (with WT given, the same launch writes the transposed weights WT [3C][C] and
+// WoT [C][C] of Wqkv and Wo); Out = In W for one row-major C x C matrix.
 int mfma_project_qkv(const Dims &D, const void *X, const void *Wqkv, bf16_t *Q, bf16_t *K, bf16_t *V,
-                     hipStream_t st);
+                     hipStream_t st, const void *Wo = nullptr, bf16_t *WT = nullptr, bf16_t *WoT = nullptr);
 int mfma_project(const Dims &D, const void *In, const bf16_t *W, bf16_t *Out, hipStream_t st);
 
 // Backward pass with fixed routing on the matrix cores (bra_mfma_bwd.hip).

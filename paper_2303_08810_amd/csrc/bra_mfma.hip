@@ -1947,13 +1947,16 @@ int mfma_forward(const Dims &D, const void *X, const void *Wqkv, const void *Wo,
 }
 
 // The projection kernels for the backward pass (bf16, C = 64, 128 or 256): Q, K, V = X Wqkv
-// (Eq. 3) into three token maps, and Out = In W for one C x C matrix.
+// (Eq. 3) into three token maps (with WT given, the launch also writes WT[o][c] = Wqkv[c][o] and
+// WoT[o][c] = Wo[c][o]), and Out = In W for one C x C matrix.
 int mfma_project_qkv(const Dims &D, const void *X, const void *Wqkv, bf16_t *Q, bf16_t *K, bf16_t *V,
-                     hipStream_t st)
+                     hipStream_t st, const void *Wo, bf16_t *WT, bf16_t *WoT)
 {
     MfmaWs w = {};
     w.q = Q; w.k = K; w.v = V;
-    const PrepArgs none{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+    // extra workgroups leave the transposed weights WT [3C][C], WoT [C][C] when asked for
+    const PrepArgs none{(const bf16_t *)Wqkv, (const bf16_t *)Wo, nullptr, WT, WoT, nullptr, nullptr,
+                        WT ? 4 * D.C * D.C : 0};
     const bf16_t *x = (const bf16_t *)X, *wq = (const bf16_t *)Wqkv;
     switch (D.C) {
     case 64: return launch_qkv<64>(D, x, wq, w, false, none, st);

@@ -67,11 +67,12 @@ __device__ __forceinline__ void keys_contract(const bf16_t *T, int pitch, const 
 
 template <int C>
 struct BwdSmem {
-    static constexpr int CS = C + 16;     // elements per row of the token tiles
+    // elements per row of the token tiles: with C + 8 four workgroups of the C = 64 kernels share a
+    // compute unit's LDS (the 16-byte row reads and the transposing reads stay conflict-free)
+    static constexpr int CS = C + 8;
     static constexpr int HEADS = C / 32;
     static constexpr int tile = 64 * CS;
-    static constexpr size_t tok_off = (size_t)4 * tile * 2;                  // int ktok[64], qtok[64]
-    static constexpr size_t q_bytes = tok_off + 128 * sizeof(int);           // k_attn_bwd_q
+    static constexpr size_t q_bytes = (size_t)4 * tile * 2;                  // k_attn_bwd_q: the four tiles
     static constexpr size_t stat_off = q_bytes;                              // float lse[HEADS][64], dsum[HEADS][64]
     static constexpr size_t list_off = stat_off + 2 * HEADS * 64 * sizeof(float);   // int count, pad, list[]
     static size_t kv_bytes(int entries) { return list_off + 16 + (size_t)entries * sizeof(int); }
@@ -84,17 +85,18 @@ __device__ __forceinline__ int region_token(const Dims &D, int region, int slot)
     return (ry * D.rh + sy) * D.W + rx * D.rw + sx;
 }
 
-// Rows of a token map (row pitch C) named by tok[0..63] (-1: a row of zeros) -> LDS tile.
-template <int C>
+// Rows of two token maps (row pitch C) -> LDS tiles; tok(row) names the token of tile row 0..63
+// within the image (-1: a row of zeros).
+template <int C, typename Tok>
 __device__ __forceinline__ void gather_rows(bf16_t *T0, bf16_t *T1, const bf16_t *__restrict__ M0,
-                                            const bf16_t *__restrict__ M1, size_t img, const int *tok)
+                                            const bf16_t *__restrict__ M1, size_t img, Tok tok)
 {
     constexpr int CS = BwdSmem<C>::CS, CH8 = C / 8, NL = 64 * CH8 / 256;
     u32x4 r0[NL], r1[NL];
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
         const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
-        const int t = tok[row];
+        const int t = tok(row);
         r0[u] = u32x4{0u, 0u, 0u, 0u};
         r1[u] = r0[u];
         if (t >= 0) {
@@ -132,26 +134,18 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
     constexpr int CS = L::CS, HEADS = L::HEADS;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::tile, *Qs = Vs + L::tile, *dOs = Qs + L::tile;
-    int *ktok = (int *)(smem + L::tok_off), *qtok = ktok + 64;
 
     const int qc = blockIdx.x % qchunks, r = (blockIdx.x / qchunks) % D.R, b = blockIdx.x / (qchunks * D.R);
     const int nq = min(64, D.n - 64 * qc), kn = D.kn;
     const size_t img = (size_t)b * D.N;
-    if (threadIdx.x < 64) {
-        const int l = threadIdx.x;
-        int t = -1;
-        if (l < kn) {
-            const int j = Ir[((size_t)b * D.R + r) * D.k + l / D.n];
-            t = region_token(D, min(max(j, 0), D.R - 1), l % D.n);
-        }
-        ktok[l] = t;
-    } else if (threadIdx.x < 128) {
-        const int l = threadIdx.x - 64;
-        qtok[l] = l < nq ? region_token(D, r, 64 * qc + l) : -1;
-    }
-    __syncthreads();
-    gather_rows<C>(Ks, Vs, K, V, img, ktok);
-    gather_rows<C>(Qs, dOs, Q, dO, img, qtok);
+    const int32_t *irow = Ir + ((size_t)b * D.R + r) * D.k;
+    auto key_token = [&](int l) {          // key l of the gathered set (Eq. 6): slot l % n of routed region l / n
+        if (l >= kn) return -1;
+        return region_token(D, min(max(irow[l / D.n], 0), D.R - 1), l % D.n);
+    };
+    auto query_token = [&](int l) { return l < nq ? region_token(D, r, 64 * qc + l) : -1; };
+    gather_rows<C>(Ks, Vs, K, V, img, key_token);
+    gather_rows<C>(Qs, dOs, Q, dO, img, query_token);
     __syncthreads();
 
     const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
@@ -160,7 +154,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
 #pragma unroll 1
     for (int task = w; task < qtiles * HEADS; task += 4) {
         const int qt = task % qtiles, h = task / qtiles, col = 32 * h;
-        const int q = 16 * qt + i, my_qtok = qtok[q];
+        const int q = 16 * qt + i, my_qtok = query_token(q);
         const bf16x8 qf = *(const bf16x8 *)(Qs + q * CS + col + 8 * g);
         const bf16x8 gf = *(const bf16x8 *)(dOs + q * CS + col + 8 * g);
         f32x4 s[4], dp[4];
@@ -247,21 +241,20 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
     constexpr int CS = L::CS, HEADS = L::HEADS;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::tile, *Qs = Vs + L::tile, *dOs = Qs + L::tile;
-    int *ktok = (int *)(smem + L::tok_off), *qtok = ktok + 64;
     float *lse_s = (float *)(smem + L::stat_off), *dd_s = lse_s + HEADS * 64;
     int *count = (int *)(smem + L::list_off), *list = count + 4;
 
     const int kc = blockIdx.x % kchunks, jr = (blockIdx.x / kchunks) % D.R, b = blockIdx.x / (kchunks * D.R);
     const int nk = min(64, D.n - 64 * kc);
     const size_t img = (size_t)b * D.N;
-    if (threadIdx.x < 64) ktok[threadIdx.x] = (int)threadIdx.x < nk ? region_token(D, jr, 64 * kc + threadIdx.x) : -1;
-    if (threadIdx.x == 64) *count = 0;
+    auto key_token = [&](int l) { return l < nk ? region_token(D, jr, 64 * kc + l) : -1; };
+    if (threadIdx.x == 0) *count = 0;
     __syncthreads();
     const int entries = D.R * D.k;
     const int32_t *irb = Ir + (size_t)b * entries;
     for (int e = threadIdx.x; e < entries; e += 256)
         if (min(max(irb[e], 0), D.R - 1) == jr) list[atomicAdd(count, 1)] = e;
-    gather_rows<C>(Ks, Vs, K, V, img, ktok);
+    gather_rows<C>(Ks, Vs, K, V, img, key_token);
     __syncthreads();
     const int m = *count;
     if (m > 1 && m <= 256) {              // rank sort: entry numbers are distinct
@@ -284,16 +277,13 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
     const int rows = m * D.n;
     for (int r0 = 0; r0 < rows; r0 += 64) {
         __syncthreads();                  // the list is in place; the previous block's readers are done
-        if (threadIdx.x < 64) {
-            const int rho = r0 + threadIdx.x;
-            int t = -1;
-            if (rho < rows) t = region_token(D, list[rho / D.n] / D.k, rho % D.n);
-            qtok[threadIdx.x] = t;
-        }
-        __syncthreads();
-        gather_rows<C>(Qs, dOs, Q, dO, img, qtok);
+        auto query_token = [&](int l) {   // row r0 + l of the list of queries: slot .. % n of the region of entry .. / n
+            const int rho = r0 + l;
+            return rho < rows ? region_token(D, list[rho / D.n] / D.k, rho % D.n) : -1;
+        };
+        gather_rows<C>(Qs, dOs, Q, dO, img, query_token);
         for (int idx = threadIdx.x; idx < 64 * HEADS; idx += 256) {
-            const int row = idx / HEADS, h = idx % HEADS, t = qtok[row];
+            const int row = idx / HEADS, h = idx % HEADS, t = query_token(row);
             // a missing row: P = exp2(-inf) = 0 and dS = 0
             lse_s[h * 64 + row] = t >= 0 ? lse[(img + t) * HEADS + h] : INFINITY;
             dd_s[h * 64 + row] = t >= 0 ? dsum[(img + t) * HEADS + h] : 0.f;
@@ -349,7 +339,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
         const int task = w + 4 * u;
         if (task >= ntasks) continue;
         const int kt = task % ktiles, h = task / ktiles, col = 32 * h;
-        const int t = ktok[16 * kt + i];
+        const int t = key_token(16 * kt + i);
         if (t < 0) continue;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
@@ -425,8 +415,9 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const bf16_t *__restrict__ A, i
 //            kept in registers across the workgroup's tiles (V is zero outside the image)
 //   phase 2, dO with its halo in the same LDS buffer:
 //            dV += LCE^T(dO), the correlation with the taps reversed; dV has row pitch ldv
-// Three workgroups per compute unit hide each other's halo loads (a register prefetch of the next
-// halo does not fit beside the 50 tap sums).  At the end the workgroup reduces its tap sums through
+// Two workgroups per compute unit (the 50 tap sums, the unpacked weights and the halo rows in flight
+// take that register budget; fetching the next phase's halo into registers ahead of time was
+// measured slower, 92 against 68 us on a 64 x 56 x 56 x 64 map).  At the end the workgroup reduces its tap sums through
 // LDS and writes Part[tile group][C][25] for k_reduce_parts.
 constexpr int kLbTH = 4, kLbTW = 32, kLbHW = kLbTW + 4, kLbRows = (kLbTH + 4) * kLbHW, kLbPitch = 64 + 8;
 constexpr int kLbLoads = kLbRows * 8 / 256;
@@ -604,20 +595,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 }
 
 // ---------------------------------------------------------------------------
-// WT[o][c] = Wqkv[c][o] ([3C][C]), WoT[o][c] = Wo[c][o].
-__global__ void k_bwd_prep(const bf16_t *__restrict__ Wqkv, const bf16_t *__restrict__ Wo,
-                           bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT, int C)
-{
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e < 3 * C * C) {
-        const int o = e / C, c = e % C;
-        WT[e] = Wqkv[(size_t)c * 3 * C + o];
-    } else if (e < 4 * C * C) {
-        const int f = e - 3 * C * C, o = f / C, c = f % C;
-        WoT[f] = Wo[(size_t)c * C + o];
-    }
-}
-
 // out[e] = sum_p part[p][e], p in a fixed order, for up to three arrays in one launch: 64
 // elements x 16 slices of p per workgroup, the slices summed through LDS.
 struct ReduceJob {
@@ -772,14 +749,8 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
     const BwdWs w = carve_bwd(D, ws);
     const int C = D.C;
     const long M = (long)D.B * D.N;
-    {
-        ProfScope ps(st, K_GEN_BACKWARD);
-        const int total = 4 * C * C;
-        hipLaunchKernelGGL(k_bwd_prep, dim3((total + 255) / 256), dim3(256), 0, st, (const bf16_t *)Wqkv,
-                           (const bf16_t *)Wo, w.wt, w.wot, C);
-        if (!launched()) return BRA_ERR_LAUNCH;
-    }
-    int rc = mfma_project_qkv(D, X, Wqkv, w.q, w.k, w.v, st);                 // Q, K, V once more (Eq. 3)
+    // Q, K, V once more (Eq. 3); the launch also leaves Wqkv^T and Wo^T
+    int rc = mfma_project_qkv(D, X, Wqkv, w.q, w.k, w.v, st, Wo, w.wt, w.wot);
     if (rc != BRA_OK) return rc;
     rc = mfma_project(D, dY, w.wot, w.dO, st);                                // dO = dY Wo^T
     if (rc != BRA_OK) return rc;
