@@ -12,8 +12,8 @@
 //                                      statistics and sums in registers, so no atomic adds are needed
 //     O += LCE(V), dV += LCE^T(dO) (the correlation with the taps reversed) and
 //     dWlce[c][ky][kx] = sum_t dO[t][c] V[t + (ky - 2, kx - 2)][c]       k_lce_bwd
-//     dX = [dQ | dK | dV] Wqkv^T       one product with the transposed weights
-//     dWqkv = X^T [dQ | dK | dV],  dWo = O^T dY         k_gemm_tn (contraction over tokens)
+//     dX = [dQ | dK | dV] Wqkv^T,  dWqkv = X^T [dQ | dK | dV]      k_bwd_proj, one pass over the gradient map
+//     dWo = O^T dY                     k_gemm_tn (contraction over tokens)
 // All products take bf16 operands and accumulate in float32; dQ, dK, dV and dO are rounded to
 // bf16 between the kernels (they are matrix-core operands of the next product).  The weight
 // gradients are summed from per-workgroup partial sums in a fixed order (k_reduce_parts).
@@ -85,31 +85,51 @@ __device__ __forceinline__ int region_token(const Dims &D, int region, int slot)
     return (ry * D.rh + sy) * D.W + rx * D.rw + sx;
 }
 
-// Rows of two token maps (row pitch C) -> LDS tiles; tok(row) names the token of tile row 0..63
-// within the image (-1: a row of zeros).
+// Rows of two token maps (row pitch C) -> registers -> LDS tiles; tok(row) names the token of tile
+// row 0..63 within the image (-1: a row of zeros).
+template <int C>
+struct RowRegs {
+    static constexpr int NL = 64 * (C / 8) / 256;
+    u32x4 r0[NL], r1[NL];
+};
+
+template <int C, typename Tok>
+__device__ __forceinline__ void fetch_rows(RowRegs<C> &R, const bf16_t *__restrict__ M0,
+                                           const bf16_t *__restrict__ M1, size_t img, Tok tok)
+{
+    constexpr int CH8 = C / 8;
+#pragma unroll
+    for (int u = 0; u < RowRegs<C>::NL; ++u) {
+        const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
+        const int t = tok(row);
+        R.r0[u] = u32x4{0u, 0u, 0u, 0u};
+        R.r1[u] = R.r0[u];
+        if (t >= 0) {
+            R.r0[u] = *(const u32x4 *)(M0 + (img + t) * C + c8 * 8);
+            R.r1[u] = *(const u32x4 *)(M1 + (img + t) * C + c8 * 8);
+        }
+    }
+}
+
+template <int C>
+__device__ __forceinline__ void store_rows(bf16_t *T0, bf16_t *T1, const RowRegs<C> &R)
+{
+    constexpr int CS = BwdSmem<C>::CS, CH8 = C / 8;
+#pragma unroll
+    for (int u = 0; u < RowRegs<C>::NL; ++u) {
+        const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
+        *(u32x4 *)(T0 + row * CS + c8 * 8) = R.r0[u];
+        *(u32x4 *)(T1 + row * CS + c8 * 8) = R.r1[u];
+    }
+}
+
 template <int C, typename Tok>
 __device__ __forceinline__ void gather_rows(bf16_t *T0, bf16_t *T1, const bf16_t *__restrict__ M0,
                                             const bf16_t *__restrict__ M1, size_t img, Tok tok)
 {
-    constexpr int CS = BwdSmem<C>::CS, CH8 = C / 8, NL = 64 * CH8 / 256;
-    u32x4 r0[NL], r1[NL];
-#pragma unroll
-    for (int u = 0; u < NL; ++u) {
-        const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
-        const int t = tok(row);
-        r0[u] = u32x4{0u, 0u, 0u, 0u};
-        r1[u] = r0[u];
-        if (t >= 0) {
-            r0[u] = *(const u32x4 *)(M0 + (img + t) * C + c8 * 8);
-            r1[u] = *(const u32x4 *)(M1 + (img + t) * C + c8 * 8);
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < NL; ++u) {
-        const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
-        *(u32x4 *)(T0 + row * CS + c8 * 8) = r0[u];
-        *(u32x4 *)(T1 + row * CS + c8 * 8) = r1[u];
-    }
+    RowRegs<C> R;
+    fetch_rows<C>(R, M0, M1, img, tok);
+    store_rows<C>(T0, T1, R);
 }
 
 // ---------------------------------------------------------------------------
@@ -144,8 +164,14 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
         return region_token(D, min(max(irow[l / D.n], 0), D.R - 1), l % D.n);
     };
     auto query_token = [&](int l) { return l < nq ? region_token(D, r, 64 * qc + l) : -1; };
-    gather_rows<C>(Ks, Vs, K, V, img, key_token);
-    gather_rows<C>(Qs, dOs, Q, dO, img, query_token);
+    {
+        // the query rows do not wait for the routing index: ask for them first
+        RowRegs<C> qr, kr;
+        fetch_rows<C>(qr, Q, dO, img, query_token);
+        fetch_rows<C>(kr, K, V, img, key_token);
+        store_rows<C>(Qs, dOs, qr);
+        store_rows<C>(Ks, Vs, kr);
+    }
     __syncthreads();
 
     const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
@@ -252,9 +278,13 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
     __syncthreads();
     const int entries = D.R * D.k;
     const int32_t *irb = Ir + (size_t)b * entries;
-    for (int e = threadIdx.x; e < entries; e += 256)
-        if (min(max(irb[e], 0), D.R - 1) == jr) list[atomicAdd(count, 1)] = e;
-    gather_rows<C>(Ks, Vs, K, V, img, key_token);
+    {
+        RowRegs<C> kr;                    // in flight while the routing index is searched
+        fetch_rows<C>(kr, K, V, img, key_token);
+        for (int e = threadIdx.x; e < entries; e += 256)
+            if (min(max(irb[e], 0), D.R - 1) == jr) list[atomicAdd(count, 1)] = e;
+        store_rows<C>(Ks, Vs, kr);
+    }
     __syncthreads();
     const int m = *count;
     if (m > 1 && m <= 256) {              // rank sort: entry numbers are distinct
@@ -275,20 +305,35 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
         for (int a = 0; a < 4; ++a) acc[u][a] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int rows = m * D.n;
-    for (int r0 = 0; r0 < rows; r0 += 64) {
-        __syncthreads();                  // the list is in place; the previous block's readers are done
-        auto query_token = [&](int l) {   // row r0 + l of the list of queries: slot .. % n of the region of entry .. / n
-            const int rho = r0 + l;
-            return rho < rows ? region_token(D, list[rho / D.n] / D.k, rho % D.n) : -1;
-        };
-        gather_rows<C>(Qs, dOs, Q, dO, img, query_token);
-        for (int idx = threadIdx.x; idx < 64 * HEADS; idx += 256) {
-            const int row = idx / HEADS, h = idx % HEADS, t = query_token(row);
+    // row r0 + l of the list of queries: slot .. % n of the query region of entry .. / n
+    auto query_token = [&](int r0, int l) {
+        const int rho = r0 + l;
+        return rho < rows ? region_token(D, list[rho / D.n] / D.k, rho % D.n) : -1;
+    };
+    // the next block's rows and statistics travel to registers while the current block is worked on
+    RowRegs<C> next;
+    float next_lse = INFINITY, next_dd = 0.f;
+    const int srow = threadIdx.x / HEADS, sh = threadIdx.x % HEADS;      // statistics: one (row, head) per thread
+    auto fetch_block = [&](int r0) {
+        fetch_rows<C>(next, Q, dO, img, [&](int l) { return query_token(r0, l); });
+        if ((int)threadIdx.x < 64 * HEADS) {
+            const int t = query_token(r0, srow);
             // a missing row: P = exp2(-inf) = 0 and dS = 0
-            lse_s[h * 64 + row] = t >= 0 ? lse[(img + t) * HEADS + h] : INFINITY;
-            dd_s[h * 64 + row] = t >= 0 ? dsum[(img + t) * HEADS + h] : 0.f;
+            next_lse = t >= 0 ? lse[(img + t) * HEADS + sh] : INFINITY;
+            next_dd = t >= 0 ? dsum[(img + t) * HEADS + sh] : 0.f;
+        }
+    };
+    __syncthreads();                      // the list is in place
+    if (rows > 0) fetch_block(0);
+    for (int r0 = 0; r0 < rows; r0 += 64) {
+        if (r0 > 0) __syncthreads();      // the previous block's readers are done
+        store_rows<C>(Qs, dOs, next);
+        if ((int)threadIdx.x < 64 * HEADS) {
+            lse_s[sh * 64 + srow] = next_lse;
+            dd_s[sh * 64 + srow] = next_dd;
         }
         __syncthreads();
+        if (r0 + 64 < rows) fetch_block(r0 + 64);
         const int qtiles = (min(64, rows - r0) + 15) / 16;
 #pragma unroll
         for (int u = 0; u < HEADS; ++u) {
@@ -407,6 +452,93 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const bf16_t *__restrict__ A, i
 }
 
 // ---------------------------------------------------------------------------
+// The two products that read the gradient map G = [dQ | dK | dV] ([M][3C]), in one pass over it:
+//     dX = G Wqkv^T                    (derivative of Eq. 3 with respect to X)
+//     dWqkv = X^T G                    (with respect to the weights; contraction over tokens)
+// A workgroup of C / 16 wavefronts streams 64-token tiles of G and X through LDS (the next tile
+// travels to registers meanwhile).  Wavefront w holds rows 16 w .. 16 w + 15 of Wqkv as A
+// operands and forms dX^T[channel][token] = Wqkv G^T tile by tile (B operand: a token's row of G);
+// and it keeps rows 16 w .. 16 w + 15 of dWqkv as 3C / 16 accumulators over all its tiles (both
+// operands by transposing reads), written at the end as Part[workgroup][C][3C] for k_reduce_parts.
+template <int C>
+struct ProjSmem {
+    static constexpr int GS = 3 * C + 8, XS = C + 8;
+    static constexpr size_t bytes = (size_t)64 * (GS + XS) * 2;
+};
+
+template <int C>
+__global__ __launch_bounds__(4 * C) void k_bwd_proj(const bf16_t *__restrict__ G, const bf16_t *__restrict__ X,
+                                                    const bf16_t *__restrict__ Wqkv, bf16_t *__restrict__ dX,
+                                                    float *__restrict__ Part, long M, int tiles, int tiles_per_wg)
+{
+    constexpr int NT = 4 * C, GS = ProjSmem<C>::GS, XS = ProjSmem<C>::XS, KS = 3 * C / 32, CT = 3 * C / 16;
+    constexpr int GCH = 3 * C / 8, XCH = C / 8, GL = 64 * GCH / NT, XL = 64 * XCH / NT;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *Gs = (bf16_t *)smem, *Xs = Gs + 64 * GS;
+    const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
+    bf16x8 wf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) wf[ks] = *(const bf16x8 *)(Wqkv + (size_t)(16 * w + i) * 3 * C + 32 * ks + 8 * g);
+    f32x4 acc[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    u32x4 gr[GL], xr[XL];
+    auto fetch = [&](long tile) {
+#pragma unroll
+        for (int u = 0; u < GL; ++u) {
+            const int idx = threadIdx.x + NT * u;
+            const long t = tile * 64 + idx / GCH;
+            gr[u] = u32x4{0u, 0u, 0u, 0u};
+            if (t < M) gr[u] = *(const u32x4 *)(G + (size_t)t * 3 * C + (idx % GCH) * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < XL; ++u) {
+            const int idx = threadIdx.x + NT * u;
+            const long t = tile * 64 + idx / XCH;
+            xr[u] = u32x4{0u, 0u, 0u, 0u};
+            if (t < M) xr[u] = *(const u32x4 *)(X + (size_t)t * C + (idx % XCH) * 8);
+        }
+    };
+    const int first = blockIdx.x * tiles_per_wg, last = min(tiles, first + tiles_per_wg);
+    if (first < last) fetch(first);
+    for (int tile = first; tile < last; ++tile) {
+        if (tile > first) __syncthreads();          // the previous tile's readers are done
+#pragma unroll
+        for (int u = 0; u < GL; ++u) {
+            const int idx = threadIdx.x + NT * u;
+            *(u32x4 *)(Gs + (idx / GCH) * GS + (idx % GCH) * 8) = gr[u];
+        }
+#pragma unroll
+        for (int u = 0; u < XL; ++u) {
+            const int idx = threadIdx.x + NT * u;
+            *(u32x4 *)(Xs + (idx / XCH) * XS + (idx % XCH) * 8) = xr[u];
+        }
+        __syncthreads();
+        if (tile + 1 < last) fetch(tile + 1);
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+            f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                a = mfma16(wf[ks], *(const bf16x8 *)(Gs + (16 * rt + i) * GS + 32 * ks + 8 * g), a);
+            const long t = (long)tile * 64 + 16 * rt + i;       // a[j] = dX[token t][channel 16 w + 4 g + j]
+            if (t < M) *(u32x2 *)(dX + (size_t)t * C + 16 * w + 4 * g) = pack4(a);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const bf16x8 xa = tr_operand(Xs, XS, 32 * ks, 16 * w, g, i);
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) acc[ct] = mfma16(xa, tr_operand(Gs, GS, 32 * ks, 16 * ct, g, i), acc[ct]);
+        }
+    }
+    float *out = Part + (size_t)blockIdx.x * C * 3 * C;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[(size_t)(16 * w + 4 * g + j) * 3 * C + 16 * ct + i] = acc[ct][j];
+}
+
+// ---------------------------------------------------------------------------
 // The three uses of the depth-wise 5x5 correlation (Eq. 7) in the backward pass, in one kernel.
 // A tile is kLbTH x kLbTW tokens of one image and 64 channels; a thread handles a pair of channels
 // and 4-token row segments.
@@ -420,8 +552,7 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const bf16_t *__restrict__ A, i
 // measured slower, 92 against 68 us on a 64 x 56 x 56 x 64 map).  At the end the workgroup reduces its tap sums through
 // LDS and writes Part[tile group][C][25] for k_reduce_parts.
 constexpr int kLbTH = 4, kLbTW = 32, kLbHW = kLbTW + 4, kLbRows = (kLbTH + 4) * kLbHW, kLbPitch = 64 + 8;
-constexpr int kLbLoads = kLbRows * 8 / 256;
-static_assert(kLbRows * 8 % 256 == 0, "halo chunks divide among the threads");
+constexpr int kLbLoads = (kLbRows * 8 + 255) / 256;
 constexpr size_t kLbSmem = std::max((size_t)kLbRows * kLbPitch * 2, (size_t)4 * 32 * 50 * 4);
 
 __device__ __forceinline__ void halo_fetch(u32x4 (&h)[kLbLoads], const bf16_t *__restrict__ M, size_t img_off,
@@ -432,7 +563,7 @@ __device__ __forceinline__ void halo_fetch(u32x4 (&h)[kLbLoads], const bf16_t *_
         const int idx = threadIdx.x + 256 * u, row = idx / 8, c8 = idx % 8;
         const int y = y0 - 2 + row / kLbHW, x = x0 - 2 + row % kLbHW;
         h[u] = u32x4{0u, 0u, 0u, 0u};
-        if (y >= 0 && y < D.H && x >= 0 && x < D.W)
+        if (idx < kLbRows * 8 && y >= 0 && y < D.H && x >= 0 && x < D.W)
             h[u] = *(const u32x4 *)(M + img_off + ((size_t)y * D.W + x) * D.C + c0 + c8 * 8);
     }
 }
@@ -442,7 +573,7 @@ __device__ __forceinline__ void halo_store(bf16_t *Hs, const u32x4 (&h)[kLbLoads
 #pragma unroll
     for (int u = 0; u < kLbLoads; ++u) {
         const int idx = threadIdx.x + 256 * u;
-        *(u32x4 *)(Hs + (idx / 8) * kLbPitch + (idx % 8) * 8) = h[u];
+        if (idx < kLbRows * 8) *(u32x4 *)(Hs + (idx / 8) * kLbPitch + (idx % 8) * 8) = h[u];
     }
 }
 
@@ -645,6 +776,21 @@ TnPlan tn_plan(long M, int Ca, int Cb)
     return TnPlan{(int)((steps + per_wg - 1) / per_wg), (int)(per_wg * 64)};
 }
 
+// Tiles of k_bwd_proj per workgroup: all workgroups resident at once.
+struct ProjPlan {
+    int tiles, per_wg, groups;
+};
+
+ProjPlan proj_plan(long M, int C)
+{
+    ProjPlan p;
+    p.tiles = (int)((M + 63) / 64);
+    const int slots = C == 64 ? 512 : 256;
+    p.per_wg = (p.tiles + slots - 1) / slots;
+    p.groups = (p.tiles + p.per_wg - 1) / p.per_wg;
+    return p;
+}
+
 struct TapPlan {
     int tiles, per_wg, groups;
 };
@@ -687,7 +833,7 @@ BwdWs carve_bwd(const Dims &D, void *ws)
     w.dqkv = (bf16_t *)take(MC * 6);
     w.lse = (float *)take((size_t)M * (C / 32) * 4);
     w.dsum = (float *)take((size_t)M * (C / 32) * 4);
-    w.part_qkv = (float *)take((size_t)tn_plan(M, D.C, 3 * D.C).gx * 3 * C * C * 4);
+    w.part_qkv = (float *)take((size_t)proj_plan(M, D.C).groups * 3 * C * C * 4);
     w.part_o = (float *)take((size_t)tn_plan(M, D.C, D.C).gx * C * C * 4);
     w.part_lce = (float *)take((size_t)tap_plan(D).groups * 25 * C * 4);
     w.wt = (bf16_t *)take(3 * C * C * 2);
@@ -766,14 +912,24 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
                            w.v, w.dO, (const bf16_t *)Wlce, w.part_lce, D, tp.tiles, tp.per_wg);
         if (!launched()) return BRA_ERR_LAUNCH;
     }
-    rc = gemm_bf16(w.dqkv, w.wt, M, 3 * C, C, (bf16_t *)dX, nullptr, nullptr, false, K_GEN_BACKWARD, st);
-    if (rc != BRA_OK) return rc;
-    rc = gemm_tn((const bf16_t *)X, C, C, w.dqkv, 3 * C, 3 * C, w.part_qkv, M, st);
-    if (rc != BRA_OK) return rc;
+    const ProjPlan pp = proj_plan(M, C);
+    {
+        // dX = [dQ | dK | dV] Wqkv^T and the partial sums of dWqkv = X^T [dQ | dK | dV]
+        static bool opted[2] = {false, false};
+        if (!(C == 64 ? opt_in(k_bwd_proj<64>, opted[0]) : opt_in(k_bwd_proj<128>, opted[1]))) return BRA_ERR_LAUNCH;
+        ProfScope ps(st, K_GEN_BACKWARD);
+        if (C == 64)
+            hipLaunchKernelGGL(k_bwd_proj<64>, dim3(pp.groups), dim3(256), ProjSmem<64>::bytes, st, w.dqkv,
+                               (const bf16_t *)X, (const bf16_t *)Wqkv, (bf16_t *)dX, w.part_qkv, M, pp.tiles, pp.per_wg);
+        else
+            hipLaunchKernelGGL(k_bwd_proj<128>, dim3(pp.groups), dim3(512), ProjSmem<128>::bytes, st, w.dqkv,
+                               (const bf16_t *)X, (const bf16_t *)Wqkv, (bf16_t *)dX, w.part_qkv, M, pp.tiles, pp.per_wg);
+        if (!launched()) return BRA_ERR_LAUNCH;
+    }
     rc = gemm_tn(w.o, C, C, (const bf16_t *)dY, C, C, w.part_o, M, st);
     if (rc != BRA_OK) return rc;
     {
-        const ReduceJob j0{w.part_qkv, dWqkv, tn_plan(M, C, 3 * C).gx, 3 * C * C, (3 * C * C + 63) / 64};
+        const ReduceJob j0{w.part_qkv, dWqkv, pp.groups, 3 * C * C, (3 * C * C + 63) / 64};
         const ReduceJob j1{w.part_o, dWo, tn_plan(M, C, C).gx, C * C, (C * C + 63) / 64};
         const ReduceJob j2{w.part_lce, dWlce, tp.groups, 25 * C, (25 * C + 63) / 64};
         ProfScope ps(st, K_GEN_BACKWARD);

@@ -495,7 +495,8 @@ int launch_gemm(const void *In, const bf16_t *W, int ldw, long M, int K, int Nou
     // tiles would leave the chip under-filled; measured: the narrow tile wins below a few hundred
     // wide tiles and loses above about a thousand
     static const long narrow_below = experiment_value("BRA_GEMM_NARROW", 400);
-    if (((M + 63) / 64) * ((Nout + 127) / 128) < narrow_below)
+    // (and where the output is at most 64 columns wide: half of a wide tile would be idle)
+    if (Nout <= 64 || ((M + 63) / 64) * ((Nout + 127) / 128) < narrow_below)
         return launch_gemm_tile<SPLIT, F32OUT, 2>(In, W, ldw, M, K, Nout, out, kernel_id, st);
     return launch_gemm_tile<SPLIT, F32OUT, 4>(In, W, ldw, M, K, Nout, out, kernel_id, st);
 }
