@@ -275,9 +275,12 @@ def time_padded(steps, warmup):
 
 
 def time_backward(cfg, steps, warmup):
-    """bra_backward (fixed routing, scalar float32 kernels) at a named workload's shape: context,
-    never `value`."""
-    import numpy as np
+    """bra_backward (fixed routing) at a named workload's shape, with the workspace allocated once
+    and HIP events around the timed calls: context, never `value`.  bf16 workloads with heads of 32
+    channels, C = 64 or 128 and at most 64 routed keys run on the matrix-core kernels, the others on
+    the scalar float32 ones."""
+    import ctypes
+
     import torch
 
     import paper_2303_08810_amd as bra
@@ -285,25 +288,30 @@ def time_backward(cfg, steps, warmup):
     host, Xs, Ys, Wqkv, Wo, Wlce = device_inputs(cfg, 2)
     X = Xs[0]
     Y, Ir = bra.bra_forward(X, Wqkv, Wo, Wlce, cfg.S, cfg.k, cfg.heads, want_Ir=True)
-    dY = torch.ones_like(Y)
+    dY = torch.randn_like(Y.float()).to(Y.dtype)
     shape = bra.make_shape(cfg.B, cfg.H, cfg.W, cfg.C, cfg.heads, cfg.S, cfg.k, X.dtype)
-    import ctypes
     need = ctypes.c_size_t(0)
     bra._check(bra.lib().bra_backward_workspace_bytes(ctypes.byref(shape), ctypes.byref(need)))
     ws = torch.empty(need.value, dtype=torch.uint8, device="cuda")
     for _ in range(warmup):
         bra.bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, cfg.S, cfg.heads, ws=ws)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
     for _ in range(steps):
         bra.bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, cfg.S, cfg.heads, ws=ws)
+    e1.record()
     torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
+    ms = e0.elapsed_time(e1) / steps
     f = flops_per_image(cfg)
+    n = (cfg.H // cfg.S) * (cfg.W // cfg.S)
+    mfma = cfg.dtype == "bf16" and cfg.C in (64, 128) and cfg.C // cfg.heads == 32 and cfg.k * n <= 64
     # the backward pass recomputes the forward (1x) and does about twice its arithmetic again
     return {"images_per_s": round(cfg.B / (ms / 1e3), 1), "ms_per_step": round(ms, 4),
             "achieved_tflops": round(3 * cfg.B * f["total"] / (ms / 1e3) / 1e12, 3),
-            "note": "scalar float32 kernels with atomic scatter-add; includes the binding's output allocations"}
+            "kernels": "matrix-core (bf16 operands, float32 sums)" if mfma
+                       else "scalar float32 with atomic scatter-add",
+            "note": "includes the binding's output allocations"}
 
 
 def time_variants(cfg, steps, warmup):
@@ -585,7 +593,7 @@ def main():
         line["block_forward"] = blocks
         if not args.block_same:
             line["padded_forward"] = time_padded(max(20, args.steps // 4), max(20, args.steps // 4))
-        line["backward"] = {CONFIGS[i].name: time_backward(CONFIGS[i], 5, 2)
+        line["backward"] = {CONFIGS[i].name: time_backward(CONFIGS[i], 30, 10)
                             for i in ((args.workload,) if args.block_same else (1, 2, 3))}
     if args.calibrate:
         src = torch.empty(CALIBRATION_BYTES, dtype=torch.uint8, device="cuda").random_()

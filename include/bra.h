@@ -184,9 +184,18 @@ int bra_block_forward(const bra_shape *shape, int32_t hidden, float eps, const v
  *     dX = [dQ|dK|dV] Wqkv^T,  dWqkv = X^T [dQ|dK|dV].
  * The forward intermediates are recomputed from X.  dX [B,H,W,C] has shape->dtype; the weight
  * gradients dWqkv [C,3C], dWo [C,C], dWlce [C,5,5] are float32, summed over the batch and
- * OVERWRITTEN.  Sums over tokens use float32 atomic adds: results are reproducible to rounding,
- * not bit for bit.  Scalar float32 kernels (any dtype; heads up to 64 channels wide);
- * shape->path is ignored.  Errors as bra_forward. */
+ * OVERWRITTEN.  Two kernel families, chosen by shape->path as in bra_forward:
+ *   BRA_PATH_MFMA     bf16 tensors, heads of 32 channels, C = 64 or 128, at most 64 routed keys
+ *                     per query (k n <= 64) and S*S*k <= 4096: matrix-core kernels with bf16
+ *                     operands and float32 sums; Q, K, V, dO, P, dS, dQ, dK, dV are rounded to
+ *                     bf16 between the products.  No atomic adds: dK, dV are summed per key
+ *                     region in registers, the weight gradients from per-workgroup partial sums in
+ *                     a fixed order, so a repeat gives the same bits as long as no key region is
+ *                     routed to by more than 256 index entries of one image.
+ *   BRA_PATH_GENERIC  any dtype, heads up to 64 channels wide: scalar float32 kernels; sums over
+ *                     tokens use float32 atomic adds, reproducible to rounding, not bit for bit.
+ *   BRA_PATH_AUTO     the first where it applies, else the second.
+ * Index values outside [0, S*S) are clamped.  Errors as bra_forward. */
 int bra_backward_workspace_bytes(const bra_shape *shape, size_t *out_bytes);
 int bra_backward(const bra_shape *shape, const void *X, const void *Wqkv, const void *Wo,
                  const void *Wlce, const int32_t *Ir, const void *dY, void *dX, float *dWqkv,

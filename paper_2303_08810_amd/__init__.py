@@ -219,7 +219,8 @@ def bra_forward_padded(X, Wqkv, Wo, Wlce, S, k, heads, *, scale=None, Ir_in=None
 
 def bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, S, heads, *, scale=None, path="auto", ws=None):
     """Gradients of the layer for fixed routing Ir [B, S*S, k] (see include/bra.h): returns
-    (dX in X's dtype, dWqkv, dWo, dWlce in float32)."""
+    (dX in X's dtype, dWqkv, dWo, dWlce in float32).  path: "auto", "generic" (scalar float32
+    kernels) or "mfma" (matrix-core kernels; raises if the shape is outside their range)."""
     B, H, W, C = _check_inputs(X, Wqkv, Wo, Wlce)
     k = int(Ir.shape[-1])
     if not (Ir.is_cuda and Ir.is_contiguous() and Ir.dtype == torch.int32 and tuple(Ir.shape) == (B, S * S, k)):

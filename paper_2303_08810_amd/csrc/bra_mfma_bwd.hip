@@ -65,16 +65,19 @@ __device__ __forceinline__ void keys_contract(const bf16_t *T, int pitch, const 
     }
 }
 
-template <int C>
+// The attention kernels take HPW heads per workgroup: all C / 32 of them for small regions (a
+// (16-token tile, head) pair per wavefront), one where a region fills four tiles by itself, so that
+// more, lighter workgroups share a compute unit.  CW = 32 HPW channels of each row are staged.
+template <int C, int HPW>
 struct BwdSmem {
-    // elements per row of the token tiles: with C + 8 four workgroups of the C = 64 kernels share a
-    // compute unit's LDS (the 16-byte row reads and the transposing reads stay conflict-free)
-    static constexpr int CS = C + 8;
-    static constexpr int HEADS = C / 32;
+    static constexpr int HEADS = C / 32, CW = 32 * HPW;
+    // elements per row of the token tiles: the 16-byte row reads and the transposing reads stay
+    // conflict-free, and four workgroups of the C = 64 kernels share a compute unit's LDS
+    static constexpr int CS = CW + 8;
     static constexpr int tile = 64 * CS;
     static constexpr size_t q_bytes = (size_t)4 * tile * 2;                  // k_attn_bwd_q: the four tiles
-    static constexpr size_t stat_off = q_bytes;                              // float lse[HEADS][64], dsum[HEADS][64]
-    static constexpr size_t list_off = stat_off + 2 * HEADS * 64 * sizeof(float);   // int count, pad, list[]
+    static constexpr size_t stat_off = q_bytes;                              // float lse[HPW][64], dsum[HPW][64]
+    static constexpr size_t list_off = stat_off + 2 * HPW * 64 * sizeof(float);   // int count, pad, list[]
     static size_t kv_bytes(int entries) { return list_off + 16 + (size_t)entries * sizeof(int); }
 };
 
@@ -85,51 +88,42 @@ __device__ __forceinline__ int region_token(const Dims &D, int region, int slot)
     return (ry * D.rh + sy) * D.W + rx * D.rw + sx;
 }
 
-// Rows of two token maps (row pitch C) -> registers -> LDS tiles; tok(row) names the token of tile
-// row 0..63 within the image (-1: a row of zeros).
-template <int C>
+// Channels c0 .. c0 + CW - 1 of rows of two token maps (row pitch C) -> registers -> LDS tiles of
+// pitch CW + 8; tok(row) names the token of tile row 0..63 within the image (-1: a row of zeros).
+template <int CW>
 struct RowRegs {
-    static constexpr int NL = 64 * (C / 8) / 256;
+    static constexpr int NL = 64 * (CW / 8) / 256;
     u32x4 r0[NL], r1[NL];
 };
 
-template <int C, typename Tok>
-__device__ __forceinline__ void fetch_rows(RowRegs<C> &R, const bf16_t *__restrict__ M0,
-                                           const bf16_t *__restrict__ M1, size_t img, Tok tok)
+template <int C, int CW, typename Tok>
+__device__ __forceinline__ void fetch_rows(RowRegs<CW> &R, const bf16_t *__restrict__ M0,
+                                           const bf16_t *__restrict__ M1, size_t img, int c0, Tok tok)
 {
-    constexpr int CH8 = C / 8;
+    constexpr int CH8 = CW / 8;
 #pragma unroll
-    for (int u = 0; u < RowRegs<C>::NL; ++u) {
+    for (int u = 0; u < RowRegs<CW>::NL; ++u) {
         const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
         const int t = tok(row);
         R.r0[u] = u32x4{0u, 0u, 0u, 0u};
         R.r1[u] = R.r0[u];
         if (t >= 0) {
-            R.r0[u] = *(const u32x4 *)(M0 + (img + t) * C + c8 * 8);
-            R.r1[u] = *(const u32x4 *)(M1 + (img + t) * C + c8 * 8);
+            R.r0[u] = *(const u32x4 *)(M0 + (img + t) * C + c0 + c8 * 8);
+            R.r1[u] = *(const u32x4 *)(M1 + (img + t) * C + c0 + c8 * 8);
         }
     }
 }
 
-template <int C>
-__device__ __forceinline__ void store_rows(bf16_t *T0, bf16_t *T1, const RowRegs<C> &R)
+template <int CW>
+__device__ __forceinline__ void store_rows(bf16_t *T0, bf16_t *T1, const RowRegs<CW> &R)
 {
-    constexpr int CS = BwdSmem<C>::CS, CH8 = C / 8;
+    constexpr int CS = CW + 8, CH8 = CW / 8;
 #pragma unroll
-    for (int u = 0; u < RowRegs<C>::NL; ++u) {
+    for (int u = 0; u < RowRegs<CW>::NL; ++u) {
         const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
         *(u32x4 *)(T0 + row * CS + c8 * 8) = R.r0[u];
         *(u32x4 *)(T1 + row * CS + c8 * 8) = R.r1[u];
     }
-}
-
-template <int C, typename Tok>
-__device__ __forceinline__ void gather_rows(bf16_t *T0, bf16_t *T1, const bf16_t *__restrict__ M0,
-                                            const bf16_t *__restrict__ M1, size_t img, Tok tok)
-{
-    RowRegs<C> R;
-    fetch_rows<C>(R, M0, M1, img, tok);
-    store_rows<C>(T0, T1, R);
 }
 
 // ---------------------------------------------------------------------------
@@ -143,19 +137,20 @@ __device__ __forceinline__ void gather_rows(bf16_t *T0, bf16_t *T1, const bf16_t
 // and leaves lse = log2 of the softmax denominator (with the scaled maximum folded in, so that
 // P = exp2(scale log2(e) s - lse)) and D per (token, head) for the key-side kernel.
 // dQ has row pitch ldq (it is the first third of the [M][3C] gradient map).
-template <int C>
+template <int C, int HPW>
 __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                     const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                     const int32_t *__restrict__ Ir, bf16_t *__restrict__ O,
                                                     bf16_t *__restrict__ dQ, int ldq, float *__restrict__ lse,
-                                                    float *__restrict__ dsum, Dims D, int qchunks)
+                                                    float *__restrict__ dsum, Dims D, int qchunks, int ablate)
 {
-    using L = BwdSmem<C>;
-    constexpr int CS = L::CS, HEADS = L::HEADS;
+    using L = BwdSmem<C, HPW>;
+    constexpr int CS = L::CS, HEADS = L::HEADS, CW = L::CW, HG = HEADS / HPW;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::tile, *Qs = Vs + L::tile, *dOs = Qs + L::tile;
 
-    const int qc = blockIdx.x % qchunks, r = (blockIdx.x / qchunks) % D.R, b = blockIdx.x / (qchunks * D.R);
+    const int h0 = ((int)blockIdx.x % HG) * HPW, bx = blockIdx.x / HG;       // first head of this workgroup
+    const int qc = bx % qchunks, r = (bx / qchunks) % D.R, b = bx / (qchunks * D.R);
     const int nq = min(64, D.n - 64 * qc), kn = D.kn;
     const size_t img = (size_t)b * D.N;
     const int32_t *irow = Ir + ((size_t)b * D.R + r) * D.k;
@@ -166,20 +161,23 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
     auto query_token = [&](int l) { return l < nq ? region_token(D, r, 64 * qc + l) : -1; };
     {
         // the query rows do not wait for the routing index: ask for them first
-        RowRegs<C> qr, kr;
-        fetch_rows<C>(qr, Q, dO, img, query_token);
-        fetch_rows<C>(kr, K, V, img, key_token);
-        store_rows<C>(Qs, dOs, qr);
-        store_rows<C>(Ks, Vs, kr);
+        RowRegs<CW> qr, kr;
+        fetch_rows<C, CW>(qr, Q, dO, img, 32 * h0, query_token);
+        fetch_rows<C, CW>(kr, K, V, img, 32 * h0, key_token);
+        store_rows<CW>(Qs, dOs, qr);
+        store_rows<CW>(Ks, Vs, kr);
     }
     __syncthreads();
 
     const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
     const float c_exp = D.scale * 1.4426950408889634f;
     const int qtiles = (nq + 15) / 16;
+#ifdef BRA_EXPERIMENT
+    if (ablate & 1) return;               // timing experiment: the gather alone
+#endif
 #pragma unroll 1
-    for (int task = w; task < qtiles * HEADS; task += 4) {
-        const int qt = task % qtiles, h = task / qtiles, col = 32 * h;
+    for (int task = w; task < qtiles * HPW; task += 4) {
+        const int qt = task % qtiles, hl = task / qtiles, h = h0 + hl, col = 32 * hl;   // col: within the tiles
         const int q = 16 * qt + i, my_qtok = query_token(q);
         const bf16x8 qf = *(const bf16x8 *)(Qs + q * CS + col + 8 * g);
         const bf16x8 gf = *(const bf16x8 *)(dOs + q * CS + col + 8 * g);
@@ -191,49 +189,56 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
             s[t] = mfma16(kf, qf, f32x4{0.f, 0.f, 0.f, 0.f});     // S^T[key 16 t + 4 g + j][query i]
             dp[t] = mfma16(vf, gf, f32x4{0.f, 0.f, 0.f, 0.f});    // dP^T, same layout
         }
-        float mx = -INFINITY;
+        if (kn < 64) {                    // a ragged key block: the missing keys get no weight
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (16 * t + 4 * g + j >= kn) s[t][j] = -INFINITY;
+        }
+        float mx = s[0][0];
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (16 * t + 4 * g + j >= kn) s[t][j] = -INFINITY;
-                mx = fmaxf(mx, s[t][j]);
-            }
+            for (int j = 0; j < 4; ++j) mx = fmaxf(mx, s[t][j]);
         mx = cross_row_max(mx);           // key 0 exists, so the maximum is finite
         const float mc = mx * c_exp;
-        float p[4][4], ds[4][4], lsum = 0.f;
+        // the products below take the unnormalised e = exp(s - max): the factors 1 / sum and scale are
+        // applied to their 8 results per lane instead of to the 16 weights
+        float p[4][4], ds[4][4], lsum = 0.f, dd = 0.f;
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 p[t][j] = __builtin_amdgcn_exp2f(fmaf(s[t][j], c_exp, -mc));
                 lsum += p[t][j];
+                dd = fmaf(p[t][j], dp[t][j], dd);
             }
         lsum = cross_row_sum(lsum);
         const float inv = 1.0f / lsum;
-        float dd = 0.f;
+        dd = cross_row_sum(dd) * inv;     // D = sum_j P_j dP_j
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                p[t][j] *= inv;
-                dd = fmaf(p[t][j], dp[t][j], dd);
-            }
-        dd = cross_row_sum(dd);
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) ds[t][j] = p[t][j] * (dp[t][j] - dd) * D.scale;
+            for (int j = 0; j < 4; ++j) ds[t][j] = p[t][j] * (dp[t][j] - dd);
 
         f32x4 oacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
         f32x4 qacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
         keys_contract(Vs, CS, p, col, g, i, oacc);       // O^T[channel col + 16 dt + 4 g + j][query i]
         keys_contract(Ks, CS, ds, col, g, i, qacc);      // dQ^T, same layout
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+            oacc[dt] *= inv;
+            qacc[dt] *= inv * D.scale;
+        }
+#ifdef BRA_EXPERIMENT
+        if ((ablate & 2) && oacc[0][0] != 123.f) continue;      // timing experiment: no stores
+#endif
         if (my_qtok >= 0) {
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt) {
-                *(u32x2 *)(O + (img + my_qtok) * C + col + 16 * dt + 4 * g) = pack4(oacc[dt]);
-                *(u32x2 *)(dQ + (img + my_qtok) * (size_t)ldq + col + 16 * dt + 4 * g) = pack4(qacc[dt]);
+                *(u32x2 *)(O + (img + my_qtok) * C + 32 * h + 16 * dt + 4 * g) = pack4(oacc[dt]);
+                *(u32x2 *)(dQ + (img + my_qtok) * (size_t)ldq + 32 * h + 16 * dt + 4 * g) = pack4(qacc[dt]);
             }
             if (g == 0) {
                 lse[(img + my_qtok) * HEADS + h] = mc + __builtin_amdgcn_logf(lsum);     // v_log_f32: log2
@@ -256,21 +261,22 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
 // in float32 registers across all query blocks; at the end dK, dV of its tokens are stored once as
 // bf16 into the second and third thirds of the [M][3C] gradient map (dKV points at the second).
 // Regions that no query attends to get zeros.
-template <int C>
+template <int C, int HPW>
 __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                      const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                      const int32_t *__restrict__ Ir, const float *__restrict__ lse,
                                                      const float *__restrict__ dsum, bf16_t *__restrict__ dKV,
                                                      int ld, Dims D, int kchunks)
 {
-    using L = BwdSmem<C>;
-    constexpr int CS = L::CS, HEADS = L::HEADS;
+    using L = BwdSmem<C, HPW>;
+    constexpr int CS = L::CS, HEADS = L::HEADS, CW = L::CW, HG = HEADS / HPW;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::tile, *Qs = Vs + L::tile, *dOs = Qs + L::tile;
-    float *lse_s = (float *)(smem + L::stat_off), *dd_s = lse_s + HEADS * 64;
+    float *lse_s = (float *)(smem + L::stat_off), *dd_s = lse_s + HPW * 64;
     int *count = (int *)(smem + L::list_off), *list = count + 4;
 
-    const int kc = blockIdx.x % kchunks, jr = (blockIdx.x / kchunks) % D.R, b = blockIdx.x / (kchunks * D.R);
+    const int h0 = ((int)blockIdx.x % HG) * HPW, bx = blockIdx.x / HG;       // first head of this workgroup
+    const int kc = bx % kchunks, jr = (bx / kchunks) % D.R, b = bx / (kchunks * D.R);
     const int nk = min(64, D.n - 64 * kc);
     const size_t img = (size_t)b * D.N;
     auto key_token = [&](int l) { return l < nk ? region_token(D, jr, 64 * kc + l) : -1; };
@@ -279,11 +285,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
     const int entries = D.R * D.k;
     const int32_t *irb = Ir + (size_t)b * entries;
     {
-        RowRegs<C> kr;                    // in flight while the routing index is searched
-        fetch_rows<C>(kr, K, V, img, key_token);
+        RowRegs<CW> kr;                   // in flight while the routing index is searched
+        fetch_rows<C, CW>(kr, K, V, img, 32 * h0, key_token);
         for (int e = threadIdx.x; e < entries; e += 256)
             if (min(max(irb[e], 0), D.R - 1) == jr) list[atomicAdd(count, 1)] = e;
-        store_rows<C>(Ks, Vs, kr);
+        store_rows<CW>(Ks, Vs, kr);
     }
     __syncthreads();
     const int m = *count;
@@ -297,10 +303,10 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
 
     const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
     const float c_exp = D.scale * 1.4426950408889634f;
-    const int ktiles = (nk + 15) / 16, ntasks = ktiles * HEADS;
-    f32x4 acc[HEADS][4];                  // per task of this wavefront: dV^T (2 channel tiles), dK^T (2)
+    const int ktiles = (nk + 15) / 16, ntasks = ktiles * HPW;
+    f32x4 acc[HPW][4];                    // per task of this wavefront: dV^T (2 channel tiles), dK^T (2)
 #pragma unroll
-    for (int u = 0; u < HEADS; ++u)
+    for (int u = 0; u < HPW; ++u)
 #pragma unroll
         for (int a = 0; a < 4; ++a) acc[u][a] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -311,24 +317,24 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
         return rho < rows ? region_token(D, list[rho / D.n] / D.k, rho % D.n) : -1;
     };
     // the next block's rows and statistics travel to registers while the current block is worked on
-    RowRegs<C> next;
+    RowRegs<CW> next;
     float next_lse = INFINITY, next_dd = 0.f;
-    const int srow = threadIdx.x / HEADS, sh = threadIdx.x % HEADS;      // statistics: one (row, head) per thread
+    const int srow = threadIdx.x / HPW, sh = threadIdx.x % HPW;          // statistics: one (row, head) per thread
     auto fetch_block = [&](int r0) {
-        fetch_rows<C>(next, Q, dO, img, [&](int l) { return query_token(r0, l); });
-        if ((int)threadIdx.x < 64 * HEADS) {
+        fetch_rows<C, CW>(next, Q, dO, img, 32 * h0, [&](int l) { return query_token(r0, l); });
+        if ((int)threadIdx.x < 64 * HPW) {
             const int t = query_token(r0, srow);
             // a missing row: P = exp2(-inf) = 0 and dS = 0
-            next_lse = t >= 0 ? lse[(img + t) * HEADS + sh] : INFINITY;
-            next_dd = t >= 0 ? dsum[(img + t) * HEADS + sh] : 0.f;
+            next_lse = t >= 0 ? lse[(img + t) * HEADS + h0 + sh] : INFINITY;
+            next_dd = t >= 0 ? dsum[(img + t) * HEADS + h0 + sh] : 0.f;
         }
     };
     __syncthreads();                      // the list is in place
     if (rows > 0) fetch_block(0);
     for (int r0 = 0; r0 < rows; r0 += 64) {
         if (r0 > 0) __syncthreads();      // the previous block's readers are done
-        store_rows<C>(Qs, dOs, next);
-        if ((int)threadIdx.x < 64 * HEADS) {
+        store_rows<CW>(Qs, dOs, next);
+        if ((int)threadIdx.x < 64 * HPW) {
             lse_s[sh * 64 + srow] = next_lse;
             dd_s[sh * 64 + srow] = next_dd;
         }
@@ -336,10 +342,10 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
         if (r0 + 64 < rows) fetch_block(r0 + 64);
         const int qtiles = (min(64, rows - r0) + 15) / 16;
 #pragma unroll
-        for (int u = 0; u < HEADS; ++u) {
+        for (int u = 0; u < HPW; ++u) {
             const int task = w + 4 * u;
             if (task >= ntasks) continue;
-            const int kt = task % ktiles, h = task / ktiles, col = 32 * h;
+            const int kt = task % ktiles, h = task / ktiles, col = 32 * h;      // h, col: within the workgroup's heads
             const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * kt + i) * CS + col + 8 * g);
             const bf16x8 vf = *(const bf16x8 *)(Vs + (16 * kt + i) * CS + col + 8 * g);
             float p[4][4], ds[4][4];
@@ -355,7 +361,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         p[t][j] = __builtin_amdgcn_exp2f(fmaf(s[j], c_exp, -l4[j]));
-                        ds[t][j] = p[t][j] * (dp[j] - d4[j]) * D.scale;
+                        ds[t][j] = p[t][j] * (dp[j] - d4[j]);      // the factor scale: on the sums, at the end
                     }
                 } else {
 #pragma unroll
@@ -380,15 +386,15 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
     }
     // acc[u][.][j] = gradient of channel col + 16 dt + 4 g + j of key 16 kt + i
 #pragma unroll
-    for (int u = 0; u < HEADS; ++u) {
+    for (int u = 0; u < HPW; ++u) {
         const int task = w + 4 * u;
         if (task >= ntasks) continue;
-        const int kt = task % ktiles, h = task / ktiles, col = 32 * h;
+        const int kt = task % ktiles, h = task / ktiles, col = 32 * (h0 + h);
         const int t = key_token(16 * kt + i);
         if (t < 0) continue;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
-            *(u32x2 *)(dKV + (img + t) * (size_t)ld + col + 16 * dt + 4 * g) = pack4(acc[u][2 + dt]);
+            *(u32x2 *)(dKV + (img + t) * (size_t)ld + col + 16 * dt + 4 * g) = pack4(acc[u][2 + dt] * D.scale);
             *(u32x2 *)(dKV + (img + t) * (size_t)ld + C + col + 16 * dt + 4 * g) = pack4(acc[u][dt]);
         }
     }
@@ -726,17 +732,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 }
 
 // ---------------------------------------------------------------------------
-// out[e] = sum_p part[p][e], p in a fixed order, for up to three arrays in one launch: 64
-// elements x 16 slices of p per workgroup, the slices summed through LDS.
+// out[e] = sum_p part[p][e], p in a fixed order, for up to three arrays in one launch: 32
+// elements x 32 slices of p per workgroup, the slices summed through LDS.
 struct ReduceJob {
     const float *part;
     float *out;
     int nparts, count, blocks;
 };
 
+constexpr int kReduceElems = 32, kReduceSlices = 32;
+
 __global__ __launch_bounds__(1024) void k_reduce_parts(ReduceJob j0, ReduceJob j1, ReduceJob j2)
 {
-    __shared__ float red[16][64];
+    __shared__ float red[kReduceSlices][kReduceElems + 1];
     int bi = blockIdx.x;
     ReduceJob job = j0;
     if (bi >= j0.blocks) {
@@ -747,23 +755,23 @@ __global__ __launch_bounds__(1024) void k_reduce_parts(ReduceJob j0, ReduceJob j
             job = j2;
         }
     }
-    const int x = threadIdx.x % 64, y = threadIdx.x / 64, e = bi * 64 + x;
+    const int x = threadIdx.x % kReduceElems, y = threadIdx.x / kReduceElems, e = bi * kReduceElems + x;
     float sum = 0.f;
     if (e < job.count)
 #pragma unroll 8
-        for (int p = y; p < job.nparts; p += 16) sum += job.part[(size_t)p * job.count + e];
+        for (int p = y; p < job.nparts; p += kReduceSlices) sum += job.part[(size_t)p * job.count + e];
     red[y][x] = sum;
     __syncthreads();
     if (y == 0 && e < job.count) {
         float total = 0.f;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) total += red[u][x];
+        for (int u = 0; u < kReduceSlices; ++u) total += red[u][x];
         job.out[e] = total;
     }
 }
 
 // ---------------------------------------------------------------------------
-// Token shares of k_gemm_tn: about 1024 workgroups over the 64 x 64 output blocks.
+// Token shares of k_gemm_tn: about 384 workgroups over the 64 x 64 output blocks.
 struct TnPlan {
     int gx, tokens_per_wg;
 };
@@ -771,7 +779,7 @@ struct TnPlan {
 TnPlan tn_plan(long M, int Ca, int Cb)
 {
     const long steps = (M + 63) / 64;
-    const long want = std::max(1L, 1024L / ((Ca / 64) * (Cb / 64)));
+    const long want = std::max(1L, 384L / ((Ca / 64) * (Cb / 64)));
     const long per_wg = (steps + want - 1) / want;
     return TnPlan{(int)((steps + per_wg - 1) / per_wg), (int)(per_wg * 64)};
 }
@@ -844,23 +852,45 @@ BwdWs carve_bwd(const Dims &D, void *ws)
 
 bool launched() { return hipGetLastError() == hipSuccess; }
 
+template <int C, int HPW>
+int attn_bwd_q(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
+{
+    static bool opted = false;
+    if (!opt_in(k_attn_bwd_q<C, HPW>, opted)) return BRA_ERR_LAUNCH;
+    using L = BwdSmem<C, HPW>;
+    const int chunks = (D.n + 63) / 64;
+    const long blocks = (long)D.B * D.R * chunks * (L::HEADS / HPW);
+    ProfScope ps(st, K_GEN_BACKWARD);
+    hipLaunchKernelGGL((k_attn_bwd_q<C, HPW>), dim3((unsigned)blocks), dim3(256), L::q_bytes, st, w.q, w.k, w.v, w.dO,
+                       Ir, w.o, w.dqkv, 3 * C, w.lse, w.dsum, D, chunks, (int)experiment_value("BRA_BWD_ABLATE", 0));
+    return launched() ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+template <int C, int HPW>
+int attn_bwd_kv(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
+{
+    static bool opted = false;
+    if (!opt_in(k_attn_bwd_kv<C, HPW>, opted)) return BRA_ERR_LAUNCH;
+    using L = BwdSmem<C, HPW>;
+    const int chunks = (D.n + 63) / 64;
+    const long blocks = (long)D.B * D.R * chunks * (L::HEADS / HPW);
+    ProfScope ps(st, K_GEN_BACKWARD);
+    hipLaunchKernelGGL((k_attn_bwd_kv<C, HPW>), dim3((unsigned)blocks), dim3(256), L::kv_bytes(D.R * D.k), st, w.q,
+                       w.k, w.v, w.dO, Ir, w.lse, w.dsum, w.dqkv + C, 3 * C, D, chunks);
+    return launched() ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+// Query side with all heads in one workgroup; key side with one head per workgroup where a region's
+// tokens alone make three or four 16-token tiles (measured on a 64 x 56 x 56 x 64 map with regions
+// of 64 tokens: query side 40 us whole against 45 us split, key side 55 us whole against 52.5 us split).
 template <int C>
 int attn_bwd(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
-    static bool opted[2] = {false, false};
-    if (!opt_in(k_attn_bwd_q<C>, opted[0]) || !opt_in(k_attn_bwd_kv<C>, opted[1])) return BRA_ERR_LAUNCH;
-    const int chunks = (D.n + 63) / 64;
-    const long blocks = (long)D.B * D.R * chunks;
-    {
-        ProfScope ps(st, K_GEN_BACKWARD);
-        hipLaunchKernelGGL(k_attn_bwd_q<C>, dim3((unsigned)blocks), dim3(256), BwdSmem<C>::q_bytes, st, w.q, w.k, w.v,
-                           w.dO, Ir, w.o, w.dqkv, 3 * C, w.lse, w.dsum, D, chunks);
-        if (!launched()) return BRA_ERR_LAUNCH;
-    }
-    ProfScope ps(st, K_GEN_BACKWARD);
-    hipLaunchKernelGGL(k_attn_bwd_kv<C>, dim3((unsigned)blocks), dim3(256), BwdSmem<C>::kv_bytes(D.R * D.k), st, w.q,
-                       w.k, w.v, w.dO, Ir, w.lse, w.dsum, w.dqkv + C, 3 * C, D, chunks);
-    return launched() ? BRA_OK : BRA_ERR_LAUNCH;
+    static const long split_above = experiment_value("BRA_BWD_HEAD_SPLIT", 32);
+    const int rc = attn_bwd_q<C, C / 32>(D, w, Ir, st);
+    if (rc != BRA_OK) return rc;
+    if (D.n > split_above) return attn_bwd_kv<C, 1>(D, w, Ir, st);
+    return attn_bwd_kv<C, C / 32>(D, w, Ir, st);
 }
 
 int gemm_tn(const bf16_t *A, int lda, int Ca, const bf16_t *Bm, int ldb, int Cb, float *Part, long M, hipStream_t st)
@@ -929,9 +959,10 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
     rc = gemm_tn(w.o, C, C, (const bf16_t *)dY, C, C, w.part_o, M, st);
     if (rc != BRA_OK) return rc;
     {
-        const ReduceJob j0{w.part_qkv, dWqkv, pp.groups, 3 * C * C, (3 * C * C + 63) / 64};
-        const ReduceJob j1{w.part_o, dWo, tn_plan(M, C, C).gx, C * C, (C * C + 63) / 64};
-        const ReduceJob j2{w.part_lce, dWlce, tp.groups, 25 * C, (25 * C + 63) / 64};
+        const int per = kReduceElems;
+        const ReduceJob j0{w.part_qkv, dWqkv, pp.groups, 3 * C * C, (3 * C * C + per - 1) / per};
+        const ReduceJob j1{w.part_o, dWo, tn_plan(M, C, C).gx, C * C, (C * C + per - 1) / per};
+        const ReduceJob j2{w.part_lce, dWlce, tp.groups, 25 * C, (25 * C + per - 1) / per};
         ProfScope ps(st, K_GEN_BACKWARD);
         hipLaunchKernelGGL(k_reduce_parts, dim3(j0.blocks + j1.blocks + j2.blocks), dim3(1024), 0, st, j0, j1, j2);
         if (!launched()) return BRA_ERR_LAUNCH;

@@ -122,3 +122,40 @@ def test_backward_after_forward_uses_its_routing():
     assert np.abs(to_numpy(Y) - ref["Y"]).max() < 1e-4
     assert np.abs(to_numpy(dX) - ref["dX"]).max() <= 1e-4 * np.abs(ref["dX"]).max()
     assert np.abs(to_numpy(dWo) - ref["dWo"]).max() <= 1e-4 * np.abs(ref["dWo"]).max()
+
+
+def test_backward_matrix_cores_repeats_bit_identical():
+    # no atomic adds on this path: dK, dV are summed per key region in registers, in the order of the
+    # routing entries, and the weight gradients from partial sums in a fixed order
+    for (B, H, W, C, heads, S, k) in [(2, 56, 56, 64, 2, 7, 1), (2, 28, 28, 128, 4, 7, 4)]:
+        Xn, Wqkvn, Won, Wlcen = make_inputs(B, H, W, C, seed=6200 + C, dtype="bf16")
+        r = np.random.Generator(np.random.PCG64(6201))
+        dYn = round_to_bf16(r.standard_normal(Xn.shape).astype(np.float32))
+        # a skewed routing: half of the query regions attend to region 0
+        Irn = np.stack([np.stack([r.permutation(S * S)[:k] for _ in range(S * S)]) for _ in range(B)]).astype(np.int32)
+        for b in range(B):
+            for i in range(0, S * S, 2):
+                Irn[b, i] = np.concatenate(([0], 1 + r.permutation(S * S - 1)[:k - 1]))
+        X, Wqkv, Wo, Wlce, dY = (to_device(a, "bf16") for a in (Xn, Wqkvn, Won, Wlcen, dYn))
+        Ir = torch.from_numpy(Irn).cuda()
+        first = [g.clone() for g in bra.bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, S, heads, path="mfma")]
+        for _ in range(3):
+            again = bra.bra_backward(X, Wqkv, Wo, Wlce, Ir, dY, S, heads, path="mfma")
+            torch.cuda.synchronize()
+            for a, b in zip(first, again):
+                assert torch.equal(a, b)
+        ref = obw.bra_backward(Xn, Wqkvn, Won, Wlcen, dYn, Irn, S=S, heads=heads)
+        for name, g in zip(("dX", "dWqkv", "dWo", "dWlce"), first):
+            gn = to_numpy(g).astype(np.float64).reshape(ref[name].shape)
+            rel = float(np.abs(gn - ref[name]).max() / np.abs(ref[name]).max())
+            assert rel <= (2e-2 if name == "dX" else 1e-2), f"{name}: {rel:.3e}"
+
+
+def test_backward_matrix_cores_refuses_other_shapes():
+    X = torch.zeros((1, 8, 8, 96), dtype=torch.bfloat16, device="cuda")
+    Wqkv = torch.zeros((96, 288), dtype=torch.bfloat16, device="cuda")
+    Wo = torch.zeros((96, 96), dtype=torch.bfloat16, device="cuda")
+    Wlce = torch.zeros((96, 5, 5), dtype=torch.bfloat16, device="cuda")
+    Ir = torch.zeros((1, 4, 1), dtype=torch.int32, device="cuda")
+    with pytest.raises(bra.BraError):
+        bra.bra_backward(X, Wqkv, Wo, Wlce, Ir, X, 2, 3, path="mfma")
