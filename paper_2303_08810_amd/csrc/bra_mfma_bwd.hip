@@ -466,29 +466,35 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const bf16_t *__restrict__ A, i
 // operands and forms dX^T[channel][token] = Wqkv G^T tile by tile (B operand: a token's row of G);
 // and it keeps rows 16 w .. 16 w + 15 of dWqkv as 3C / 16 accumulators over all its tiles (both
 // operands by transposing reads), written at the end as Part[workgroup][C][3C] for k_reduce_parts.
-template <int C>
+// With WO the same pass also streams O and dY and keeps dWo = O^T dY (rows 16 w .. 16 w + 15, C / 16
+// accumulators more: taken where the registers allow it, C = 64).
+template <int C, bool WO>
 struct ProjSmem {
     static constexpr int GS = 3 * C + 8, XS = C + 8;
-    static constexpr size_t bytes = (size_t)64 * (GS + XS) * 2;
+    static constexpr size_t bytes = (size_t)64 * (GS + (WO ? 3 : 1) * XS) * 2;
 };
 
-template <int C>
+template <int C, bool WO>
 __global__ __launch_bounds__(4 * C) void k_bwd_proj(const bf16_t *__restrict__ G, const bf16_t *__restrict__ X,
                                                     const bf16_t *__restrict__ Wqkv, bf16_t *__restrict__ dX,
-                                                    float *__restrict__ Part, long M, int tiles, int tiles_per_wg)
+                                                    float *__restrict__ Part, const bf16_t *__restrict__ O,
+                                                    const bf16_t *__restrict__ dY, float *__restrict__ PartO, long M,
+                                                    int tiles, int tiles_per_wg)
 {
-    constexpr int NT = 4 * C, GS = ProjSmem<C>::GS, XS = ProjSmem<C>::XS, KS = 3 * C / 32, CT = 3 * C / 16;
-    constexpr int GCH = 3 * C / 8, XCH = C / 8, GL = 64 * GCH / NT, XL = 64 * XCH / NT;
+    constexpr int NT = 4 * C, GS = ProjSmem<C, WO>::GS, XS = ProjSmem<C, WO>::XS, KS = 3 * C / 32, CT = 3 * C / 16;
+    constexpr int GCH = 3 * C / 8, XCH = C / 8, GL = 64 * GCH / NT, XL = 64 * XCH / NT, OT = WO ? C / 16 : 1;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16_t *Gs = (bf16_t *)smem, *Xs = Gs + 64 * GS;
+    bf16_t *Gs = (bf16_t *)smem, *Xs = Gs + 64 * GS, *Os = Xs + 64 * XS, *Ys = Os + 64 * XS;
     const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
     bf16x8 wf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) wf[ks] = *(const bf16x8 *)(Wqkv + (size_t)(16 * w + i) * 3 * C + 32 * ks + 8 * g);
-    f32x4 acc[CT];
+    f32x4 acc[CT], acco[OT];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-    u32x4 gr[GL], xr[XL];
+#pragma unroll
+    for (int ct = 0; ct < OT; ++ct) acco[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    u32x4 gr[GL], xr[XL], orr[WO ? XL : 1], yr[WO ? XL : 1];
     auto fetch = [&](long tile) {
 #pragma unroll
         for (int u = 0; u < GL; ++u) {
@@ -502,7 +508,14 @@ __global__ __launch_bounds__(4 * C) void k_bwd_proj(const bf16_t *__restrict__ G
             const int idx = threadIdx.x + NT * u;
             const long t = tile * 64 + idx / XCH;
             xr[u] = u32x4{0u, 0u, 0u, 0u};
-            if (t < M) xr[u] = *(const u32x4 *)(X + (size_t)t * C + (idx % XCH) * 8);
+            if (WO) orr[u] = yr[u] = xr[u];
+            if (t < M) {
+                xr[u] = *(const u32x4 *)(X + (size_t)t * C + (idx % XCH) * 8);
+                if (WO) {
+                    orr[u] = *(const u32x4 *)(O + (size_t)t * C + (idx % XCH) * 8);
+                    yr[u] = *(const u32x4 *)(dY + (size_t)t * C + (idx % XCH) * 8);
+                }
+            }
         }
     };
     const int first = blockIdx.x * tiles_per_wg, last = min(tiles, first + tiles_per_wg);
@@ -518,6 +531,10 @@ __global__ __launch_bounds__(4 * C) void k_bwd_proj(const bf16_t *__restrict__ G
         for (int u = 0; u < XL; ++u) {
             const int idx = threadIdx.x + NT * u;
             *(u32x4 *)(Xs + (idx / XCH) * XS + (idx % XCH) * 8) = xr[u];
+            if (WO) {
+                *(u32x4 *)(Os + (idx / XCH) * XS + (idx % XCH) * 8) = orr[u];
+                *(u32x4 *)(Ys + (idx / XCH) * XS + (idx % XCH) * 8) = yr[u];
+            }
         }
         __syncthreads();
         if (tile + 1 < last) fetch(tile + 1);
@@ -535,6 +552,12 @@ __global__ __launch_bounds__(4 * C) void k_bwd_proj(const bf16_t *__restrict__ G
             const bf16x8 xa = tr_operand(Xs, XS, 32 * ks, 16 * w, g, i);
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) acc[ct] = mfma16(xa, tr_operand(Gs, GS, 32 * ks, 16 * ct, g, i), acc[ct]);
+            if (WO) {
+                const bf16x8 oa = tr_operand(Os, XS, 32 * ks, 16 * w, g, i);
+#pragma unroll
+                for (int ct = 0; ct < OT; ++ct)
+                    acco[ct] = mfma16(oa, tr_operand(Ys, XS, 32 * ks, 16 * ct, g, i), acco[ct]);
+            }
         }
     }
     float *out = Part + (size_t)blockIdx.x * C * 3 * C;
@@ -542,6 +565,13 @@ __global__ __launch_bounds__(4 * C) void k_bwd_proj(const bf16_t *__restrict__ G
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
         for (int j = 0; j < 4; ++j) out[(size_t)(16 * w + 4 * g + j) * 3 * C + 16 * ct + i] = acc[ct][j];
+    if (WO) {
+        float *outo = PartO + (size_t)blockIdx.x * C * C;
+#pragma unroll
+        for (int ct = 0; ct < OT; ++ct)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) outo[(size_t)(16 * w + 4 * g + j) * C + 16 * ct + i] = acco[ct][j];
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -842,7 +872,7 @@ BwdWs carve_bwd(const Dims &D, void *ws)
     w.lse = (float *)take((size_t)M * (C / 32) * 4);
     w.dsum = (float *)take((size_t)M * (C / 32) * 4);
     w.part_qkv = (float *)take((size_t)proj_plan(M, D.C).groups * 3 * C * C * 4);
-    w.part_o = (float *)take((size_t)tn_plan(M, D.C, D.C).gx * C * C * 4);
+    w.part_o = (float *)take((size_t)std::max(tn_plan(M, D.C, D.C).gx, proj_plan(M, D.C).groups) * C * C * 4);
     w.part_lce = (float *)take((size_t)tap_plan(D).groups * 25 * C * 4);
     w.wt = (bf16_t *)take(3 * C * C * 2);
     w.wot = (bf16_t *)take(C * C * 2);
@@ -925,7 +955,8 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
     const BwdWs w = carve_bwd(D, ws);
     const int C = D.C;
     const long M = (long)D.B * D.N;
-    // Q, K, V once more (Eq. 3); the launch also leaves Wqkv^T and Wo^T
+    // Q, K, V once more (Eq. 3); the launch also leaves Wqkv^T and Wo^T (a launch of its own for Wo^T
+    // alone was measured 4 us slower)
     int rc = mfma_project_qkv(D, X, Wqkv, w.q, w.k, w.v, st, Wo, w.wt, w.wot);
     if (rc != BRA_OK) return rc;
     rc = mfma_project(D, dY, w.wot, w.dO, st);                                // dO = dY Wo^T
@@ -943,25 +974,31 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
         if (!launched()) return BRA_ERR_LAUNCH;
     }
     const ProjPlan pp = proj_plan(M, C);
+    const bool with_o = C == 64;          // dWo = O^T dY rides in the same pass where the registers allow it
     {
-        // dX = [dQ | dK | dV] Wqkv^T and the partial sums of dWqkv = X^T [dQ | dK | dV]
+        // dX = [dQ | dK | dV] Wqkv^T and the partial sums of dWqkv = X^T [dQ | dK | dV] (and of dWo)
         static bool opted[2] = {false, false};
-        if (!(C == 64 ? opt_in(k_bwd_proj<64>, opted[0]) : opt_in(k_bwd_proj<128>, opted[1]))) return BRA_ERR_LAUNCH;
+        if (!(C == 64 ? opt_in(k_bwd_proj<64, true>, opted[0]) : opt_in(k_bwd_proj<128, false>, opted[1])))
+            return BRA_ERR_LAUNCH;
         ProfScope ps(st, K_GEN_BACKWARD);
         if (C == 64)
-            hipLaunchKernelGGL(k_bwd_proj<64>, dim3(pp.groups), dim3(256), ProjSmem<64>::bytes, st, w.dqkv,
-                               (const bf16_t *)X, (const bf16_t *)Wqkv, (bf16_t *)dX, w.part_qkv, M, pp.tiles, pp.per_wg);
+            hipLaunchKernelGGL((k_bwd_proj<64, true>), dim3(pp.groups), dim3(256), (ProjSmem<64, true>::bytes), st,
+                               w.dqkv, (const bf16_t *)X, (const bf16_t *)Wqkv, (bf16_t *)dX, w.part_qkv, w.o,
+                               (const bf16_t *)dY, w.part_o, M, pp.tiles, pp.per_wg);
         else
-            hipLaunchKernelGGL(k_bwd_proj<128>, dim3(pp.groups), dim3(512), ProjSmem<128>::bytes, st, w.dqkv,
-                               (const bf16_t *)X, (const bf16_t *)Wqkv, (bf16_t *)dX, w.part_qkv, M, pp.tiles, pp.per_wg);
+            hipLaunchKernelGGL((k_bwd_proj<128, false>), dim3(pp.groups), dim3(512), (ProjSmem<128, false>::bytes), st,
+                               w.dqkv, (const bf16_t *)X, (const bf16_t *)Wqkv, (bf16_t *)dX, w.part_qkv, nullptr,
+                               nullptr, nullptr, M, pp.tiles, pp.per_wg);
         if (!launched()) return BRA_ERR_LAUNCH;
     }
-    rc = gemm_tn(w.o, C, C, (const bf16_t *)dY, C, C, w.part_o, M, st);
-    if (rc != BRA_OK) return rc;
+    if (!with_o) {
+        rc = gemm_tn(w.o, C, C, (const bf16_t *)dY, C, C, w.part_o, M, st);
+        if (rc != BRA_OK) return rc;
+    }
     {
         const int per = kReduceElems;
         const ReduceJob j0{w.part_qkv, dWqkv, pp.groups, 3 * C * C, (3 * C * C + per - 1) / per};
-        const ReduceJob j1{w.part_o, dWo, tn_plan(M, C, C).gx, C * C, (C * C + per - 1) / per};
+        const ReduceJob j1{w.part_o, dWo, with_o ? pp.groups : tn_plan(M, C, C).gx, C * C, (C * C + per - 1) / per};
         const ReduceJob j2{w.part_lce, dWlce, tp.groups, 25 * C, (25 * C + per - 1) / per};
         ProfScope ps(st, K_GEN_BACKWARD);
         hipLaunchKernelGGL(k_reduce_parts, dim3(j0.blocks + j1.blocks + j2.blocks), dim3(1024), 0, st, j0, j1, j2);
