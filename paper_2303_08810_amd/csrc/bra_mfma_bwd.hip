@@ -1,5 +1,5 @@
-// Backward pass of the layer on the matrix cores (bf16 tensors, heads of 32 channels, C = 64 or
-// 128, at most 64 routed keys per query: k n <= 64), with the routing index held fixed.
+// Backward pass of the layer on the matrix cores (bf16 tensors, heads of 32 channels, C = 64, 128
+// or 256, at most 64 routed keys per query: k n <= 64), with the routing index held fixed.
 //
 // Chain rule through Eq. 6-7 and Eq. 1-2, with O = Attention(Q, K^g, V^g) + LCE(V), Y = O Wo:
 //     dO = dY Wo^T                     projection kernel with Wo^T as its matrix
@@ -845,6 +845,10 @@ TapPlan tap_plan(const Dims &D)
     return t;
 }
 
+// k_bwd_proj keeps 3C / 16 accumulators per wavefront: up to C = 128; wider layers take the plain
+// product for dX and k_gemm_tn for dWqkv.
+bool fused_projection(int C) { return C <= 128; }
+
 struct BwdWs {
     bf16_t *q, *k, *v, *dO, *o, *dqkv, *wt, *wot;
     float *lse, *dsum, *part_qkv, *part_o, *part_lce;
@@ -871,7 +875,8 @@ BwdWs carve_bwd(const Dims &D, void *ws)
     w.dqkv = (bf16_t *)take(MC * 6);
     w.lse = (float *)take((size_t)M * (C / 32) * 4);
     w.dsum = (float *)take((size_t)M * (C / 32) * 4);
-    w.part_qkv = (float *)take((size_t)proj_plan(M, D.C).groups * 3 * C * C * 4);
+    w.part_qkv = (float *)take((size_t)(fused_projection(D.C) ? proj_plan(M, D.C).groups : tn_plan(M, D.C, 3 * D.C).gx) *
+                               3 * C * C * 4);
     w.part_o = (float *)take((size_t)std::max(tn_plan(M, D.C, D.C).gx, proj_plan(M, D.C).groups) * C * C * 4);
     w.part_lce = (float *)take((size_t)tap_plan(D).groups * 25 * C * 4);
     w.wt = (bf16_t *)take(3 * C * C * 2);
@@ -917,10 +922,11 @@ template <int C>
 int attn_bwd(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
     static const long split_above = experiment_value("BRA_BWD_HEAD_SPLIT", 32);
-    const int rc = attn_bwd_q<C, C / 32>(D, w, Ir, st);
+    constexpr int HPW = C / 32 < 4 ? C / 32 : 4;       // the tiles of four heads fill the LDS of half a compute unit
+    const int rc = attn_bwd_q<C, HPW>(D, w, Ir, st);
     if (rc != BRA_OK) return rc;
     if (D.n > split_above) return attn_bwd_kv<C, 1>(D, w, Ir, st);
-    return attn_bwd_kv<C, C / 32>(D, w, Ir, st);
+    return attn_bwd_kv<C, HPW>(D, w, Ir, st);
 }
 
 int gemm_tn(const bf16_t *A, int lda, int Ca, const bf16_t *Bm, int ldb, int Cb, float *Part, long M, hipStream_t st)
@@ -940,7 +946,7 @@ constexpr int kBwdMaxEntries = 4096;
 bool mfma_backward_supported(const Dims &D)
 {
     static const bool off = experiment_flag("BRA_NO_MFMA_BACKWARD");
-    if (off || D.dtype != BRA_BF16 || D.d != 32 || (D.C != 64 && D.C != 128) || D.kn > 64) return false;
+    if (off || D.dtype != BRA_BF16 || D.d != 32 || (D.C != 64 && D.C != 128 && D.C != 256) || D.kn > 64) return false;
     if ((long)D.R * D.k > kBwdMaxEntries) return false;
     const long M = (long)D.B * D.N;
     return M * 3 * D.C < (1L << 40) && (long)D.B * D.R * ((D.n + 63) / 64) <= 0x7fffffffL && M <= 0x7fffffffL;
@@ -961,7 +967,7 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
     if (rc != BRA_OK) return rc;
     rc = mfma_project(D, dY, w.wot, w.dO, st);                                // dO = dY Wo^T
     if (rc != BRA_OK) return rc;
-    rc = (C == 64) ? attn_bwd<64>(D, w, Ir, st) : attn_bwd<128>(D, w, Ir, st);   // O, dQ; then dK, dV
+    rc = C == 64 ? attn_bwd<64>(D, w, Ir, st) : C == 128 ? attn_bwd<128>(D, w, Ir, st) : attn_bwd<256>(D, w, Ir, st);   // O, dQ; then dK, dV
     if (rc != BRA_OK) return rc;
     const TapPlan tp = tap_plan(D);
     {
@@ -975,7 +981,7 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
     }
     const ProjPlan pp = proj_plan(M, C);
     const bool with_o = C == 64;          // dWo = O^T dY rides in the same pass where the registers allow it
-    {
+    if (fused_projection(C)) {
         // dX = [dQ | dK | dV] Wqkv^T and the partial sums of dWqkv = X^T [dQ | dK | dV] (and of dWo)
         static bool opted[2] = {false, false};
         if (!(C == 64 ? opt_in(k_bwd_proj<64, true>, opted[0]) : opt_in(k_bwd_proj<128, false>, opted[1])))
@@ -990,6 +996,11 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
                                w.dqkv, (const bf16_t *)X, (const bf16_t *)Wqkv, (bf16_t *)dX, w.part_qkv, nullptr,
                                nullptr, nullptr, M, pp.tiles, pp.per_wg);
         if (!launched()) return BRA_ERR_LAUNCH;
+    } else {
+        rc = gemm_bf16(w.dqkv, w.wt, M, 3 * C, C, (bf16_t *)dX, nullptr, nullptr, false, K_GEN_BACKWARD, st);
+        if (rc != BRA_OK) return rc;
+        rc = gemm_tn((const bf16_t *)X, C, C, w.dqkv, 3 * C, 3 * C, w.part_qkv, M, st);
+        if (rc != BRA_OK) return rc;
     }
     if (!with_o) {
         rc = gemm_tn(w.o, C, C, (const bf16_t *)dY, C, C, w.part_o, M, st);
@@ -997,7 +1008,8 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
     }
     {
         const int per = kReduceElems;
-        const ReduceJob j0{w.part_qkv, dWqkv, pp.groups, 3 * C * C, (3 * C * C + per - 1) / per};
+        const ReduceJob j0{w.part_qkv, dWqkv, fused_projection(C) ? pp.groups : tn_plan(M, C, 3 * C).gx, 3 * C * C,
+                           (3 * C * C + per - 1) / per};
         const ReduceJob j1{w.part_o, dWo, with_o ? pp.groups : tn_plan(M, C, C).gx, C * C, (C * C + per - 1) / per};
         const ReduceJob j2{w.part_lce, dWlce, tp.groups, 25 * C, (25 * C + per - 1) / per};
         ProfScope ps(st, K_GEN_BACKWARD);

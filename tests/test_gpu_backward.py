@@ -31,7 +31,7 @@ SHAPES = [
 ]
 
 
-# bf16 shapes of the matrix-core backward (heads of 32 channels, C = 64 or 128, k n <= 64): a full
+# bf16 shapes of the matrix-core backward (heads of 32 channels, C = 64, 128 or 256, k n <= 64): a full
 # 64-key block, ragged key and query blocks (n = 49; k n = 48, 36, 2), one token per region, maps
 # wider than one tile of the tap-gradient kernel with a ragged last tile (W = 56, 40)
 MFMA_SHAPES = [
@@ -43,6 +43,8 @@ MFMA_SHAPES = [
     ("bf16", 3, 4, 40, 128, 4, 4, 2),
     ("bf16", 1, 12, 20, 64, 2, 4, 4),
     ("bf16", 2, 7, 7, 128, 4, 7, 49),
+    ("bf16", 2, 14, 14, 256, 8, 7, 16),
+    ("bf16", 1, 16, 16, 256, 8, 2, 1),
 ]
 
 
@@ -105,9 +107,9 @@ def test_backward_named_workloads_full_size(idx):
     # the five named workloads at their full sizes (random routing index, given to both sides)
     cfg = CONFIGS[idx]
     Xn, Wqkvn, Won, Wlcen = make_config_inputs(cfg)
-    # workloads 2 and 3 (bf16, 64 routed keys) run on the matrix-core kernels, the others on the scalar ones
+    # workloads 2, 3 and 4 (bf16, 64 routed keys) run on the matrix-core kernels, the others on the scalar ones
     compare_backward(Xn, Wqkvn, Won, Wlcen, cfg.dtype, cfg.heads, cfg.S, cfg.k,
-                     path="mfma" if idx in (2, 3) else "generic")
+                     path="mfma" if idx in (2, 3, 4) else "generic")
 
 
 def test_backward_after_forward_uses_its_routing():
