@@ -1,5 +1,5 @@
 // Backward pass of the layer on the matrix cores (bf16 tensors, heads of 32 channels, C = 64, 128
-// or 256, at most 64 routed keys per query: k n <= 64), with the routing index held fixed.
+// or 256, at most 4096 routing entries per image), with the routing index held fixed.
 //
 // Chain rule through Eq. 6-7 and Eq. 1-2, with O = Attention(Q, K^g, V^g) + LCE(V), Y = O Wo:
 //     dO = dY Wo^T                     projection kernel with Wo^T as its matrix
@@ -189,13 +189,12 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
             s[t] = mfma16(kf, qf, f32x4{0.f, 0.f, 0.f, 0.f});     // S^T[key 16 t + 4 g + j][query i]
             dp[t] = mfma16(vf, gf, f32x4{0.f, 0.f, 0.f, 0.f});    // dP^T, same layout
         }
-        if (kn < 64) {                    // a ragged key block: the missing keys get no weight
+        // a ragged key block: the missing keys get no weight (selects, not a branch between the matrix
+        // instructions and the first read of their results)
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (16 * t + 4 * g + j >= kn) s[t][j] = -INFINITY;
-        }
+            for (int j = 0; j < 4; ++j) s[t][j] = (16 * t + 4 * g + j >= kn) ? -INFINITY : s[t][j];
         float mx = s[0][0];
 #pragma unroll
         for (int t = 0; t < 4; ++t)
@@ -243,6 +242,157 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
             if (g == 0) {
                 lse[(img + my_qtok) * HEADS + h] = mc + __builtin_amdgcn_logf(lsum);     // v_log_f32: log2
                 dsum[(img + my_qtok) * HEADS + h] = dd;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The query side for more than 64 routed keys per query: the keys are taken in blocks of 64, twice.
+// First sweep, per (16-query tile, head) of a wavefront: the running maximum m, the sum l of
+// e = exp(s - m), the unnormalised sums O~ = sum e V and D~ = sum e dP, all rescaled when m grows
+// (the online softmax of the forward kernels); at its end O = O~ / l, D = D~ / l and
+// lse = log2(l) + scale log2(e) m are final and stored.  Second sweep: P = exp2(scale log2(e) s - lse),
+// dS = P (dP - D), dQ^T += K^T dS^T; dQ = scale dQ^T at the end.  The next block's K, V rows travel
+// to registers while the current block is worked on.  A wavefront keeps the state of up to HPW pairs.
+template <int C, int HPW>
+__global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                           const bf16_t *__restrict__ V,
+                                                           const bf16_t *__restrict__ dO,
+                                                           const int32_t *__restrict__ Ir, bf16_t *__restrict__ O,
+                                                           bf16_t *__restrict__ dQ, int ldq, float *__restrict__ lse,
+                                                           float *__restrict__ dsum, Dims D, int qchunks)
+{
+    using L = BwdSmem<C, HPW>;
+    constexpr int CS = L::CS, HEADS = L::HEADS, CW = L::CW, HG = HEADS / HPW;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::tile, *Qs = Vs + L::tile, *dOs = Qs + L::tile;
+
+    const int h0 = ((int)blockIdx.x % HG) * HPW, bx = blockIdx.x / HG;
+    const int qc = bx % qchunks, r = (bx / qchunks) % D.R, b = bx / (qchunks * D.R);
+    const int nq = min(64, D.n - 64 * qc), kn = D.kn, nblocks = (kn + 63) / 64;
+    const size_t img = (size_t)b * D.N;
+    const int32_t *irow = Ir + ((size_t)b * D.R + r) * D.k;
+    auto key_token = [&](int l) {          // key l of the gathered set (Eq. 6): slot l % n of routed region l / n
+        if (l >= kn) return -1;
+        return region_token(D, min(max(irow[l / D.n], 0), D.R - 1), l % D.n);
+    };
+    auto query_token = [&](int l) { return l < nq ? region_token(D, r, 64 * qc + l) : -1; };
+    RowRegs<CW> kr;
+    auto fetch_keys = [&](int kb) {
+        fetch_rows<C, CW>(kr, K, V, img, 32 * h0, [&](int l) { return key_token(64 * kb + l); });
+    };
+    {
+        RowRegs<CW> qr;
+        fetch_rows<C, CW>(qr, Q, dO, img, 32 * h0, query_token);
+        fetch_keys(0);
+        store_rows<CW>(Qs, dOs, qr);
+    }
+    const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
+    const float c_exp = D.scale * 1.4426950408889634f;
+    const int qtiles = (nq + 15) / 16, ntasks = qtiles * HPW;
+
+    float m[HPW], l[HPW], dd[HPW];        // per pair: maximum, sum, D~ (first sweep); then lse in m, D in dd
+    f32x4 acc[HPW][2];                    // O~^T, then dQ^T: [channel 16 dt + 4 g + j of the head][query i]
+#pragma unroll
+    for (int u = 0; u < HPW; ++u) {
+        m[u] = -INFINITY;
+        l[u] = dd[u] = 0.f;
+        acc[u][0] = acc[u][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll 1
+    for (int sweep = 0; sweep < 2; ++sweep) {
+#pragma unroll 1
+        for (int kb = 0; kb < nblocks; ++kb) {
+            __syncthreads();              // the previous block's readers are done
+            store_rows<CW>(Ks, Vs, kr);
+            __syncthreads();
+            if (kb + 1 < nblocks) fetch_keys(kb + 1);
+            else if (sweep == 0) fetch_keys(0);
+#pragma unroll
+            for (int u = 0; u < HPW; ++u) {
+                const int task = w + 4 * u;
+                if (task >= ntasks) continue;
+                const int qt = task % qtiles, col = 32 * (task / qtiles), q = 16 * qt + i;
+                const bf16x8 qf = *(const bf16x8 *)(Qs + q * CS + col + 8 * g);
+                const bf16x8 gf = *(const bf16x8 *)(dOs + q * CS + col + 8 * g);
+                f32x4 s[4], dp[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + col + 8 * g);
+                    const bf16x8 vf = *(const bf16x8 *)(Vs + (16 * t + i) * CS + col + 8 * g);
+                    s[t] = mfma16(kf, qf, f32x4{0.f, 0.f, 0.f, 0.f});     // S^T[key 16 t + 4 g + j][query i]
+                    dp[t] = mfma16(vf, gf, f32x4{0.f, 0.f, 0.f, 0.f});    // dP^T, same layout
+                }
+                // the ragged last block: the missing keys get no weight (selects, not a branch between the
+                // matrix instructions and the first read of their results)
+                const int left = kn - 64 * kb;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) s[t][j] = (16 * t + 4 * g + j >= left) ? -INFINITY : s[t][j];
+                float e[4][4];
+                if (sweep == 0) {
+                    float mx = s[0][0];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) mx = fmaxf(mx, s[t][j]);
+                    const float m_new = fmaxf(m[u], cross_row_max(mx));       // finite: key 64 kb exists
+                    const float alpha = __builtin_amdgcn_exp2f((m[u] - m_new) * c_exp);   // 0 on the first block
+                    m[u] = m_new;
+                    const float mc = m_new * c_exp;
+                    float ls = 0.f, ds = 0.f;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            e[t][j] = __builtin_amdgcn_exp2f(fmaf(s[t][j], c_exp, -mc));
+                            ls += e[t][j];
+                            ds = fmaf(e[t][j], dp[t][j], ds);
+                        }
+                    l[u] = fmaf(l[u], alpha, cross_row_sum(ls));
+                    dd[u] = fmaf(dd[u], alpha, cross_row_sum(ds));
+                    acc[u][0] *= alpha;
+                    acc[u][1] *= alpha;
+                    keys_contract(Vs, CS, e, col, g, i, acc[u]);
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            e[t][j] = __builtin_amdgcn_exp2f(fmaf(s[t][j], c_exp, -m[u])) * (dp[t][j] - dd[u]);
+                    keys_contract(Ks, CS, e, col, g, i, acc[u]);
+                }
+            }
+        }
+        // end of a sweep: store O and the statistics, or dQ
+#pragma unroll
+        for (int u = 0; u < HPW; ++u) {
+            const int task = w + 4 * u;
+            if (task >= ntasks) continue;
+            const int qt = task % qtiles, h = h0 + task / qtiles;
+            const int tok = query_token(16 * qt + i);
+            if (sweep == 0) {
+                const float inv = 1.0f / l[u];
+                const float lse2 = fmaf(m[u], c_exp, __builtin_amdgcn_logf(l[u]));      // v_log_f32: log2
+                const float dfin = dd[u] * inv;
+                if (tok >= 0) {
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt)
+                        *(u32x2 *)(O + (img + tok) * C + 32 * h + 16 * dt + 4 * g) = pack4(acc[u][dt] * inv);
+                    if (g == 0) {
+                        lse[(img + tok) * HEADS + h] = lse2;
+                        dsum[(img + tok) * HEADS + h] = dfin;
+                    }
+                }
+                m[u] = lse2;
+                dd[u] = dfin;
+                acc[u][0] = acc[u][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            } else if (tok >= 0) {
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+                    *(u32x2 *)(dQ + (img + tok) * (size_t)ldq + 32 * h + 16 * dt + 4 * g) = pack4(acc[u][dt] * D.scale);
             }
         }
     }
@@ -902,6 +1052,20 @@ int attn_bwd_q(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 }
 
 template <int C, int HPW>
+int attn_bwd_q_blocks(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
+{
+    static bool opted = false;
+    if (!opt_in(k_attn_bwd_q_blocks<C, HPW>, opted)) return BRA_ERR_LAUNCH;
+    using L = BwdSmem<C, HPW>;
+    const int chunks = (D.n + 63) / 64;
+    const long blocks = (long)D.B * D.R * chunks * (L::HEADS / HPW);
+    ProfScope ps(st, K_GEN_BACKWARD);
+    hipLaunchKernelGGL((k_attn_bwd_q_blocks<C, HPW>), dim3((unsigned)blocks), dim3(256), L::q_bytes, st, w.q, w.k, w.v,
+                       w.dO, Ir, w.o, w.dqkv, 3 * C, w.lse, w.dsum, D, chunks);
+    return launched() ? BRA_OK : BRA_ERR_LAUNCH;
+}
+
+template <int C, int HPW>
 int attn_bwd_kv(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
     static bool opted = false;
@@ -923,7 +1087,7 @@ int attn_bwd(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
     static const long split_above = experiment_value("BRA_BWD_HEAD_SPLIT", 32);
     constexpr int HPW = C / 32 < 4 ? C / 32 : 4;       // the tiles of four heads fill the LDS of half a compute unit
-    const int rc = attn_bwd_q<C, HPW>(D, w, Ir, st);
+    const int rc = D.kn <= 64 ? attn_bwd_q<C, HPW>(D, w, Ir, st) : attn_bwd_q_blocks<C, HPW>(D, w, Ir, st);
     if (rc != BRA_OK) return rc;
     if (D.n > split_above) return attn_bwd_kv<C, 1>(D, w, Ir, st);
     return attn_bwd_kv<C, HPW>(D, w, Ir, st);
@@ -946,10 +1110,11 @@ constexpr int kBwdMaxEntries = 4096;
 bool mfma_backward_supported(const Dims &D)
 {
     static const bool off = experiment_flag("BRA_NO_MFMA_BACKWARD");
-    if (off || D.dtype != BRA_BF16 || D.d != 32 || (D.C != 64 && D.C != 128 && D.C != 256) || D.kn > 64) return false;
+    if (off || D.dtype != BRA_BF16 || D.d != 32 || (D.C != 64 && D.C != 128 && D.C != 256)) return false;
     if ((long)D.R * D.k > kBwdMaxEntries) return false;
     const long M = (long)D.B * D.N;
-    return M * 3 * D.C < (1L << 40) && (long)D.B * D.R * ((D.n + 63) / 64) <= 0x7fffffffL && M <= 0x7fffffffL;
+    return M * 3 * D.C < (1L << 40) && (long)D.B * D.R * ((D.n + 63) / 64) * (D.C / 32) <= 0x7fffffffL &&
+           M <= 0x7fffffffL;
 }
 
 size_t mfma_backward_workspace_bytes(const Dims &D) { return carve_bwd(D, nullptr).bytes; }

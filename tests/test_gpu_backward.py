@@ -31,9 +31,9 @@ SHAPES = [
 ]
 
 
-# bf16 shapes of the matrix-core backward (heads of 32 channels, C = 64, 128 or 256, k n <= 64): a full
-# 64-key block, ragged key and query blocks (n = 49; k n = 48, 36, 2), one token per region, maps
-# wider than one tile of the tap-gradient kernel with a ragged last tile (W = 56, 40)
+# bf16 shapes of the matrix-core backward (heads of 32 channels, C = 64, 128 or 256): a full 64-key
+# block, ragged key and query blocks (n = 49; k n = 48, 36, 2), one token per region, maps wider than
+# one tile of the depth-wise kernel with a ragged last tile (W = 56, 40)
 MFMA_SHAPES = [
     ("bf16", 2, 14, 14, 64, 2, 7, 4),
     ("bf16", 1, 56, 56, 64, 2, 7, 1),
@@ -45,6 +45,12 @@ MFMA_SHAPES = [
     ("bf16", 2, 7, 7, 128, 4, 7, 49),
     ("bf16", 2, 14, 14, 256, 8, 7, 16),
     ("bf16", 1, 16, 16, 256, 8, 2, 1),
+    # more than 64 routed keys: key blocks taken twice by the query side; regions of more than 64 tokens
+    ("bf16", 1, 32, 32, 64, 2, 4, 3),
+    ("bf16", 2, 12, 20, 64, 2, 4, 16),
+    ("bf16", 1, 20, 36, 128, 4, 2, 2),
+    ("bf16", 1, 16, 24, 256, 8, 4, 5),
+    ("bf16", 2, 7, 7, 64, 2, 7, 49),
 ]
 
 
@@ -107,9 +113,9 @@ def test_backward_named_workloads_full_size(idx):
     # the five named workloads at their full sizes (random routing index, given to both sides)
     cfg = CONFIGS[idx]
     Xn, Wqkvn, Won, Wlcen = make_config_inputs(cfg)
-    # workloads 2, 3 and 4 (bf16, 64 routed keys) run on the matrix-core kernels, the others on the scalar ones
+    # the bf16 workloads run on the matrix-core kernels, the float32 one on the scalar ones
     compare_backward(Xn, Wqkvn, Won, Wlcen, cfg.dtype, cfg.heads, cfg.S, cfg.k,
-                     path="mfma" if idx in (2, 3, 4) else "generic")
+                     path="mfma" if cfg.dtype == "bf16" else "generic")
 
 
 def test_backward_after_forward_uses_its_routing():
