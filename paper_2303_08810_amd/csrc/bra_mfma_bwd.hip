@@ -1087,7 +1087,10 @@ int attn_bwd(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
     static const long split_above = experiment_value("BRA_BWD_HEAD_SPLIT", 32);
     constexpr int HPW = C / 32 < 4 ? C / 32 : 4;       // the tiles of four heads fill the LDS of half a compute unit
-    const int rc = D.kn <= 64 ? attn_bwd_q<C, HPW>(D, w, Ir, st) : attn_bwd_q_blocks<C, HPW>(D, w, Ir, st);
+    int rc;
+    if (D.kn <= 64) rc = attn_bwd_q<C, HPW>(D, w, Ir, st);
+    else if (D.n > split_above) rc = attn_bwd_q_blocks<C, 1>(D, w, Ir, st);
+    else rc = attn_bwd_q_blocks<C, HPW>(D, w, Ir, st);
     if (rc != BRA_OK) return rc;
     if (D.n > split_above) return attn_bwd_kv<C, 1>(D, w, Ir, st);
     return attn_bwd_kv<C, HPW>(D, w, Ir, st);

@@ -108,6 +108,28 @@ def test_backward_random_shapes(dtype, B, H, W, C, heads, S, k):
     test_backward(dtype, B, H, W, C, heads, S, k)
 
 
+def random_matrix_core_shapes(count, seed):
+    import random
+    rng = random.Random(seed)
+    out = []
+    while len(out) < count:
+        S = rng.choice([1, 2, 3, 4, 5, 7])
+        H, W = S * rng.choice([1, 2, 3, 4, 5, 9, 12]), S * rng.choice([1, 2, 3, 4, 6, 11])
+        heads = rng.choice([2, 4, 8])
+        C = 32 * heads
+        k = rng.choice([1, 2, 3, min(S * S, 5), S * S])
+        n = (H // S) * (W // S)
+        if k > S * S or H * W * C > 150000 or H * W * k * n * C > 6e7:
+            continue
+        out.append(("bf16", rng.choice([1, 2, 3]), H, W, C, heads, S, k))
+    return out
+
+
+@pytest.mark.parametrize("dtype,B,H,W,C,heads,S,k", random_matrix_core_shapes(16, seed=20230312))
+def test_backward_matrix_cores_random_shapes(dtype, B, H, W, C, heads, S, k):
+    test_backward(dtype, B, H, W, C, heads, S, k, path="mfma")
+
+
 @pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
 def test_backward_named_workloads_full_size(idx):
     # the five named workloads at their full sizes (random routing index, given to both sides)
