@@ -277,7 +277,7 @@ def time_padded(steps, warmup):
 def time_backward(cfg, steps, warmup):
     """bra_backward (fixed routing) at a named workload's shape, with the workspace allocated once
     and HIP events around the timed calls: context, never `value`.  bf16 workloads with heads of 32
-    channels, C = 64, 128 or 256 and at most 64 routed keys run on the matrix-core kernels, the others on
+    channels, C = 64, 128 or 256 and at most 4096 routing entries per image run on the matrix-core kernels, the others on
     the scalar float32 ones."""
     import ctypes
 
@@ -304,8 +304,8 @@ def time_backward(cfg, steps, warmup):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / steps
     f = flops_per_image(cfg)
-    n = (cfg.H // cfg.S) * (cfg.W // cfg.S)
-    mfma = cfg.dtype == "bf16" and cfg.C in (64, 128, 256) and cfg.C // cfg.heads == 32 and cfg.k * n <= 64
+    mfma = (cfg.dtype == "bf16" and cfg.C in (64, 128, 256) and cfg.C // cfg.heads == 32
+            and cfg.S * cfg.S * cfg.k <= 4096)
     # the backward pass recomputes the forward (1x) and does about twice its arithmetic again
     return {"images_per_s": round(cfg.B / (ms / 1e3), 1), "ms_per_step": round(ms, 4),
             "achieved_tflops": round(3 * cfg.B * f["total"] / (ms / 1e3) / 1e12, 3),
@@ -594,7 +594,7 @@ def main():
         if not args.block_same:
             line["padded_forward"] = time_padded(max(20, args.steps // 4), max(20, args.steps // 4))
         line["backward"] = {CONFIGS[i].name: time_backward(CONFIGS[i], 30, 10)
-                            for i in ((args.workload,) if args.block_same else (1, 2, 3))}
+                            for i in ((args.workload,) if args.block_same else (1, 2, 3, 4, 5))}
     if args.calibrate:
         src = torch.empty(CALIBRATION_BYTES, dtype=torch.uint8, device="cuda").random_()
         dst = torch.empty_like(src)
