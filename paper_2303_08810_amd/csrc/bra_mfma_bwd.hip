@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
                                                     const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                     const int32_t *__restrict__ Ir, bf16_t *__restrict__ O,
                                                     bf16_t *__restrict__ dQ, int ldq, float *__restrict__ lse,
-                                                    float *__restrict__ dsum, Dims D, int qchunks, int ablate)
+                                                    float *__restrict__ dsum, Dims D, int qchunks)
 {
     using L = BwdSmem<C, HPW>;
     constexpr int CS = L::CS, HEADS = L::HEADS, CW = L::CW, HG = HEADS / HPW;
@@ -172,9 +172,6 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
     const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
     const float c_exp = D.scale * 1.4426950408889634f;
     const int qtiles = (nq + 15) / 16;
-#ifdef BRA_EXPERIMENT
-    if (ablate & 1) return;               // timing experiment: the gather alone
-#endif
 #pragma unroll 1
     for (int task = w; task < qtiles * HPW; task += 4) {
         const int qt = task % qtiles, hl = task / qtiles, h = h0 + hl, col = 32 * hl;   // col: within the tiles
@@ -230,9 +227,6 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
             oacc[dt] *= inv;
             qacc[dt] *= inv * D.scale;
         }
-#ifdef BRA_EXPERIMENT
-        if ((ablate & 2) && oacc[0][0] != 123.f) continue;      // timing experiment: no stores
-#endif
         if (my_qtok >= 0) {
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt) {
@@ -1047,7 +1041,7 @@ int attn_bwd_q(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
     const long blocks = (long)D.B * D.R * chunks * (L::HEADS / HPW);
     ProfScope ps(st, K_GEN_BACKWARD);
     hipLaunchKernelGGL((k_attn_bwd_q<C, HPW>), dim3((unsigned)blocks), dim3(256), L::q_bytes, st, w.q, w.k, w.v, w.dO,
-                       Ir, w.o, w.dqkv, 3 * C, w.lse, w.dsum, D, chunks, (int)experiment_value("BRA_BWD_ABLATE", 0));
+                       Ir, w.o, w.dqkv, 3 * C, w.lse, w.dsum, D, chunks);
     return launched() ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
