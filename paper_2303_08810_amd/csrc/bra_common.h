@@ -150,6 +150,9 @@ int mfma_project_qkv(const Dims &D, const void *X, const void *Wqkv, bf16_t *Q, 
                      hipStream_t st, const void *Wo = nullptr, bf16_t *WT = nullptr, bf16_t *WoT = nullptr);
 int mfma_project(const Dims &D, const void *In, const bf16_t *W, bf16_t *Out, hipStream_t st);
 
+// The same projection for any C that is a multiple of 64 (bra_mfma_wide.hip).
+int wide_project_qkv(const Dims &D, const void *X, const void *Wqkv, bf16_t *Q, bf16_t *K, bf16_t *V, hipStream_t st);
+
 // Backward pass with fixed routing on the matrix cores (bra_mfma_bwd.hip).
 bool mfma_backward_supported(const Dims &D);
 size_t mfma_backward_workspace_bytes(const Dims &D);

@@ -1,5 +1,5 @@
-// Backward pass of the layer on the matrix cores (bf16 tensors, heads of 32 channels, C = 64, 128
-// or 256, at most 4096 routing entries per image), with the routing index held fixed.
+// Backward pass of the layer on the matrix cores (bf16 tensors, heads of 32 channels, C = 64, 128,
+// 256, 384 or 512, at most 4096 routing entries per image), with the routing index held fixed.
 //
 // Chain rule through Eq. 6-7 and Eq. 1-2, with O = Attention(Q, K^g, V^g) + LCE(V), Y = O Wo:
 //     dO = dY Wo^T                     projection kernel with Wo^T as its matrix
@@ -906,6 +906,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 }
 
 // ---------------------------------------------------------------------------
+// WT[o][c] = Wqkv[c][o] ([3C][C]) and WoT[o][c] = Wo[c][o], for the channel counts whose projection
+// launch does not carry the rearrangement along.
+__global__ void k_bwd_transpose(const bf16_t *__restrict__ Wqkv, const bf16_t *__restrict__ Wo,
+                                bf16_t *__restrict__ WT, bf16_t *__restrict__ WoT, int C)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < 3 * C * C) WT[e] = Wqkv[(size_t)(e % C) * 3 * C + e / C];
+    else if (e < 4 * C * C) WoT[e - 3 * C * C] = Wo[(size_t)((e - 3 * C * C) % C) * C + (e - 3 * C * C) / C];
+}
+
 // out[e] = sum_p part[p][e], p in a fixed order, for up to three arrays in one launch: 32
 // elements x 32 slices of p per workgroup, the slices summed through LDS.
 struct ReduceJob {
@@ -1104,10 +1114,16 @@ constexpr int kBwdMaxEntries = 4096;
 
 }  // namespace
 
+// Channel counts the attention kernels are instantiated for.
+static bool bwd_channels_ok(int C) { return C == 64 || C == 128 || C == 256 || C == 384 || C == 512; }
+
+// The projection kernels specialised by channel count (they also carry the weight transposes along).
+static bool narrow_projection(int C) { return C == 64 || C == 128 || C == 256; }
+
 bool mfma_backward_supported(const Dims &D)
 {
     static const bool off = experiment_flag("BRA_NO_MFMA_BACKWARD");
-    if (off || D.dtype != BRA_BF16 || D.d != 32 || (D.C != 64 && D.C != 128 && D.C != 256)) return false;
+    if (off || D.dtype != BRA_BF16 || D.d != 32 || !bwd_channels_ok(D.C)) return false;
     if ((long)D.R * D.k > kBwdMaxEntries) return false;
     const long M = (long)D.B * D.N;
     return M * 3 * D.C < (1L << 40) && (long)D.B * D.R * ((D.n + 63) / 64) * (D.C / 32) <= 0x7fffffffL &&
@@ -1123,13 +1139,32 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
     const BwdWs w = carve_bwd(D, ws);
     const int C = D.C;
     const long M = (long)D.B * D.N;
-    // Q, K, V once more (Eq. 3); the launch also leaves Wqkv^T and Wo^T (a launch of its own for Wo^T
-    // alone was measured 4 us slower)
-    int rc = mfma_project_qkv(D, X, Wqkv, w.q, w.k, w.v, st, Wo, w.wt, w.wot);
+    int rc;
+    if (narrow_projection(C)) {
+        // Q, K, V once more (Eq. 3); the launch also leaves Wqkv^T and Wo^T (a launch of its own for Wo^T
+        // alone was measured 4 us slower)
+        rc = mfma_project_qkv(D, X, Wqkv, w.q, w.k, w.v, st, Wo, w.wt, w.wot);
+        if (rc != BRA_OK) return rc;
+        rc = mfma_project(D, dY, w.wot, w.dO, st);                            // dO = dY Wo^T
+    } else {
+        {
+            ProfScope ps(st, K_GEN_BACKWARD);
+            hipLaunchKernelGGL(k_bwd_transpose, dim3((4 * C * C + 255) / 256), dim3(256), 0, st, (const bf16_t *)Wqkv,
+                               (const bf16_t *)Wo, w.wt, w.wot, C);
+            if (!launched()) return BRA_ERR_LAUNCH;
+        }
+        rc = wide_project_qkv(D, X, Wqkv, w.q, w.k, w.v, st);
+        if (rc != BRA_OK) return rc;
+        rc = gemm_bf16((const bf16_t *)dY, w.wot, M, C, C, w.dO, nullptr, nullptr, false, K_GEN_BACKWARD, st);
+    }
     if (rc != BRA_OK) return rc;
-    rc = mfma_project(D, dY, w.wot, w.dO, st);                                // dO = dY Wo^T
-    if (rc != BRA_OK) return rc;
-    rc = C == 64 ? attn_bwd<64>(D, w, Ir, st) : C == 128 ? attn_bwd<128>(D, w, Ir, st) : attn_bwd<256>(D, w, Ir, st);   // O, dQ; then dK, dV
+    switch (C) {                                                                  // O, dQ; then dK, dV
+    case 64: rc = attn_bwd<64>(D, w, Ir, st); break;
+    case 128: rc = attn_bwd<128>(D, w, Ir, st); break;
+    case 256: rc = attn_bwd<256>(D, w, Ir, st); break;
+    case 384: rc = attn_bwd<384>(D, w, Ir, st); break;
+    default: rc = attn_bwd<512>(D, w, Ir, st); break;
+    }
     if (rc != BRA_OK) return rc;
     const TapPlan tp = tap_plan(D);
     {

@@ -552,6 +552,16 @@ int gemm_bf16(const bf16_t *In, const bf16_t *W, long M, int K, int Nout, bf16_t
     return launch_gemm<false>(In, W, Nout, M, K, Nout, out, kernel_id, st);
 }
 
+// Q, K, V = X Wqkv into three token maps (Eq. 3) for any C that is a multiple of 64: the projection of
+// the wide pipeline, for the backward pass.
+int wide_project_qkv(const Dims &D, const void *X, const void *Wqkv, bf16_t *Q, bf16_t *K, bf16_t *V, hipStream_t st)
+{
+    const long M = (long)D.B * D.N;
+    if (D.C % 64 || M > 0x7fffffffL) return BRA_ERR_UNSUPPORTED;
+    return launch_gemm<false>(X, (const bf16_t *)Wqkv, 3 * D.C, M, D.C, 3 * D.C,
+                              GemmOut{{Q, K, V}, D.C, {nullptr, nullptr}}, K_MFMA_QKV, st);
+}
+
 bool wide_supported(const Dims &D)
 {
     if (D.dtype != BRA_BF16 || D.C % 64 != 0 || D.C > 4096) return false;

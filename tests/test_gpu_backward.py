@@ -31,7 +31,7 @@ SHAPES = [
 ]
 
 
-# bf16 shapes of the matrix-core backward (heads of 32 channels, C = 64, 128 or 256): a full 64-key
+# bf16 shapes of the matrix-core backward (heads of 32 channels, C = 64 .. 512): a full 64-key
 # block, ragged key and query blocks (n = 49; k n = 48, 36, 2), one token per region, maps wider than
 # one tile of the depth-wise kernel with a ragged last tile (W = 56, 40)
 MFMA_SHAPES = [
@@ -51,6 +51,10 @@ MFMA_SHAPES = [
     ("bf16", 1, 20, 36, 128, 4, 2, 2),
     ("bf16", 1, 16, 24, 256, 8, 4, 5),
     ("bf16", 2, 7, 7, 64, 2, 7, 49),
+    # wider layers: plain products for the projections
+    ("bf16", 2, 14, 14, 384, 12, 7, 16),
+    ("bf16", 1, 16, 24, 512, 16, 4, 3),
+    ("bf16", 2, 7, 7, 512, 16, 7, 49),
 ]
 
 
@@ -138,6 +142,15 @@ def test_backward_named_workloads_full_size(idx):
     # the bf16 workloads run on the matrix-core kernels, the float32 one on the scalar ones
     compare_backward(Xn, Wqkvn, Won, Wlcen, cfg.dtype, cfg.heads, cfg.S, cfg.k,
                      path="mfma" if cfg.dtype == "bf16" else "generic")
+
+
+@pytest.mark.parametrize("idx", [6, 7])
+def test_backward_wide_workloads_full_size(idx):
+    # the two next-step shapes with heads of 32 channels (C = 512 and 384) at their full sizes
+    from synthetic_inputs import NEXT_CONFIGS
+    cfg = NEXT_CONFIGS[idx]
+    Xn, Wqkvn, Won, Wlcen = make_config_inputs(cfg)
+    compare_backward(Xn, Wqkvn, Won, Wlcen, cfg.dtype, cfg.heads, cfg.S, cfg.k, path="mfma")
 
 
 def test_backward_after_forward_uses_its_routing():
