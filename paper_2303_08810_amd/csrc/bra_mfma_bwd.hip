@@ -266,22 +266,28 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
     const int qc = bx % qchunks, r = (bx / qchunks) % D.R, b = bx / (qchunks * D.R);
     const int nq = min(64, D.n - 64 * qc), kn = D.kn, nblocks = (kn + 63) / 64;
     const size_t img = (size_t)b * D.N;
-    const int32_t *irow = Ir + ((size_t)b * D.R + r) * D.k;
+    // the region's routing row in LDS: key addresses need it block after block
+    int *ir_s = (int *)(smem + L::q_bytes);
+    for (int e = threadIdx.x; e < D.k; e += 256) ir_s[e] = min(max(Ir[((size_t)b * D.R + r) * D.k + e], 0), D.R - 1);
     auto key_token = [&](int l) {          // key l of the gathered set (Eq. 6): slot l % n of routed region l / n
-        if (l >= kn) return -1;
-        return region_token(D, min(max(irow[l / D.n], 0), D.R - 1), l % D.n);
+        return l < kn ? region_token(D, ir_s[l / D.n], l % D.n) : -1;
     };
     auto query_token = [&](int l) { return l < nq ? region_token(D, r, 64 * qc + l) : -1; };
-    RowRegs<CW> kr;
-    auto fetch_keys = [&](int kb) {
-        fetch_rows<C, CW>(kr, K, V, img, 32 * h0, [&](int l) { return key_token(64 * kb + l); });
-    };
+    // DEPTH blocks of K, V rows are in flight in registers.  One is enough: the sweeps are bound by
+    // their vector work (about 200 instructions per pair and block), and with three blocks in flight
+    // the kernel was slower (99 against 90 us on a 2 x 128 x 128 x 64 map with 1024 keys per query)
+    constexpr int DEPTH = 1;
+    const int total = 2 * nblocks;        // both sweeps, as one sequence of blocks
+    RowRegs<CW> kr[DEPTH];
     {
         RowRegs<CW> qr;
         fetch_rows<C, CW>(qr, Q, dO, img, 32 * h0, query_token);
-        fetch_keys(0);
         store_rows<CW>(Qs, dOs, qr);
     }
+    __syncthreads();                      // ir_s is in place
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+        if (d < total) fetch_rows<C, CW>(kr[d], K, V, img, 32 * h0, [&](int l) { return key_token(64 * (d % nblocks) + l); });
     const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
     const float c_exp = D.scale * 1.4426950408889634f;
     const int qtiles = (nq + 15) / 16, ntasks = qtiles * HPW;
@@ -295,14 +301,19 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
         acc[u][0] = acc[u][1] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 #pragma unroll 1
-    for (int sweep = 0; sweep < 2; ++sweep) {
-#pragma unroll 1
-        for (int kb = 0; kb < nblocks; ++kb) {
+    for (int t0 = 0; t0 < total; t0 += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const int step = t0 + d;
+            if (step >= total) break;
+            const int sweep = step >= nblocks ? 1 : 0, kb = step - sweep * nblocks;
             __syncthreads();              // the previous block's readers are done
-            store_rows<CW>(Ks, Vs, kr);
+            store_rows<CW>(Ks, Vs, kr[d]);
             __syncthreads();
-            if (kb + 1 < nblocks) fetch_keys(kb + 1);
-            else if (sweep == 0) fetch_keys(0);
+            if (step + DEPTH < total) {
+                const int nb = (step + DEPTH) % nblocks;
+                fetch_rows<C, CW>(kr[d], K, V, img, 32 * h0, [&](int l) { return key_token(64 * nb + l); });
+            }
 #pragma unroll
             for (int u = 0; u < HPW; ++u) {
                 const int task = w + 4 * u;
@@ -359,34 +370,36 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
                     keys_contract(Ks, CS, e, col, g, i, acc[u]);
                 }
             }
-        }
-        // end of a sweep: store O and the statistics, or dQ
+            if (kb + 1 < nblocks) continue;
+            // end of a sweep: store O and the statistics, or dQ
 #pragma unroll
-        for (int u = 0; u < HPW; ++u) {
-            const int task = w + 4 * u;
-            if (task >= ntasks) continue;
-            const int qt = task % qtiles, h = h0 + task / qtiles;
-            const int tok = query_token(16 * qt + i);
-            if (sweep == 0) {
-                const float inv = 1.0f / l[u];
-                const float lse2 = fmaf(m[u], c_exp, __builtin_amdgcn_logf(l[u]));      // v_log_f32: log2
-                const float dfin = dd[u] * inv;
-                if (tok >= 0) {
+            for (int u = 0; u < HPW; ++u) {
+                const int task = w + 4 * u;
+                if (task >= ntasks) continue;
+                const int qt = task % qtiles, h = h0 + task / qtiles;
+                const int tok = query_token(16 * qt + i);
+                if (sweep == 0) {
+                    const float inv = 1.0f / l[u];
+                    const float lse2 = fmaf(m[u], c_exp, __builtin_amdgcn_logf(l[u]));      // v_log_f32: log2
+                    const float dfin = dd[u] * inv;
+                    if (tok >= 0) {
+#pragma unroll
+                        for (int dt = 0; dt < 2; ++dt)
+                            *(u32x2 *)(O + (img + tok) * C + 32 * h + 16 * dt + 4 * g) = pack4(acc[u][dt] * inv);
+                        if (g == 0) {
+                            lse[(img + tok) * HEADS + h] = lse2;
+                            dsum[(img + tok) * HEADS + h] = dfin;
+                        }
+                    }
+                    m[u] = lse2;
+                    dd[u] = dfin;
+                    acc[u][0] = acc[u][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                } else if (tok >= 0) {
 #pragma unroll
                     for (int dt = 0; dt < 2; ++dt)
-                        *(u32x2 *)(O + (img + tok) * C + 32 * h + 16 * dt + 4 * g) = pack4(acc[u][dt] * inv);
-                    if (g == 0) {
-                        lse[(img + tok) * HEADS + h] = lse2;
-                        dsum[(img + tok) * HEADS + h] = dfin;
-                    }
+                        *(u32x2 *)(dQ + (img + tok) * (size_t)ldq + 32 * h + 16 * dt + 4 * g) =
+                            pack4(acc[u][dt] * D.scale);
                 }
-                m[u] = lse2;
-                dd[u] = dfin;
-                acc[u][0] = acc[u][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-            } else if (tok >= 0) {
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-                    *(u32x2 *)(dQ + (img + tok) * (size_t)ldq + 32 * h + 16 * dt + 4 * g) = pack4(acc[u][dt] * D.scale);
             }
         }
     }
@@ -1064,8 +1077,9 @@ int attn_bwd_q_blocks(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStrea
     const int chunks = (D.n + 63) / 64;
     const long blocks = (long)D.B * D.R * chunks * (L::HEADS / HPW);
     ProfScope ps(st, K_GEN_BACKWARD);
-    hipLaunchKernelGGL((k_attn_bwd_q_blocks<C, HPW>), dim3((unsigned)blocks), dim3(256), L::q_bytes, st, w.q, w.k, w.v,
-                       w.dO, Ir, w.o, w.dqkv, 3 * C, w.lse, w.dsum, D, chunks);
+    hipLaunchKernelGGL((k_attn_bwd_q_blocks<C, HPW>), dim3((unsigned)blocks), dim3(256),
+                       L::q_bytes + (size_t)D.k * sizeof(int), st, w.q, w.k, w.v, w.dO, Ir, w.o, w.dqkv, 3 * C, w.lse,
+                       w.dsum, D, chunks);
     return launched() ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
