@@ -68,14 +68,16 @@ __device__ __forceinline__ void keys_contract(const bf16_t *T, int pitch, const 
 // The attention kernels take HPW heads per workgroup: all C / 32 of them for small regions (a
 // (16-token tile, head) pair per wavefront), one where a region fills four tiles by itself, so that
 // more, lighter workgroups share a compute unit.  CW = 32 HPW channels of each row are staged.
-template <int C, int HPW>
+template <int C, int HPW, int QR = 64, int KR = 64>
 struct BwdSmem {
     static constexpr int HEADS = C / 32, CW = 32 * HPW;
     // elements per row of the token tiles: the 16-byte row reads and the transposing reads stay
     // conflict-free, and four workgroups of the C = 64 kernels share a compute unit's LDS
     static constexpr int CS = CW + 8;
-    static constexpr int tile = 64 * CS;
-    static constexpr size_t q_bytes = (size_t)4 * tile * 2;                  // k_attn_bwd_q: the four tiles
+    // K, V tiles of KR rows, then Q, dO tiles of QR rows: 64 each, or 16 on the side that holds one
+    // region's tokens when a region has at most 16 (a third workgroup then fits beside two)
+    static constexpr int ktile = KR * CS, qtile = QR * CS;
+    static constexpr size_t q_bytes = (size_t)2 * (ktile + qtile) * 2;       // the four tiles
     static constexpr size_t stat_off = q_bytes;                              // float lse[HPW][64], dsum[HPW][64]
     static constexpr size_t list_off = stat_off + 2 * HPW * 64 * sizeof(float);   // int count, pad, list[]
     static size_t kv_bytes(int entries) { return list_off + 16 + (size_t)entries * sizeof(int); }
@@ -88,23 +90,23 @@ __device__ __forceinline__ int region_token(const Dims &D, int region, int slot)
     return (ry * D.rh + sy) * D.W + rx * D.rw + sx;
 }
 
-// Channels c0 .. c0 + CW - 1 of rows of two token maps (row pitch C) -> registers -> LDS tiles of
-// pitch CW + 8; tok(row) names the token of tile row 0..63 within the image (-1: a row of zeros).
-template <int CW>
+// Channels c0 .. c0 + CW - 1 of ROWS rows of two token maps (row pitch C) -> registers -> LDS tiles
+// of pitch CW + 8; tok(row) names the token of a tile row within the image (-1: a row of zeros).
+template <int CW, int ROWS = 64>
 struct RowRegs {
-    static constexpr int NL = 64 * (CW / 8) / 256;
+    static constexpr int CHUNKS = ROWS * (CW / 8), NL = (CHUNKS + 255) / 256;
     u32x4 r0[NL], r1[NL];
 };
 
-template <int C, int CW, typename Tok>
-__device__ __forceinline__ void fetch_rows(RowRegs<CW> &R, const bf16_t *__restrict__ M0,
+template <int C, int CW, int ROWS, typename Tok>
+__device__ __forceinline__ void fetch_rows(RowRegs<CW, ROWS> &R, const bf16_t *__restrict__ M0,
                                            const bf16_t *__restrict__ M1, size_t img, int c0, Tok tok)
 {
     constexpr int CH8 = CW / 8;
 #pragma unroll
-    for (int u = 0; u < RowRegs<CW>::NL; ++u) {
+    for (int u = 0; u < RowRegs<CW, ROWS>::NL; ++u) {
         const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
-        const int t = tok(row);
+        const int t = idx < RowRegs<CW, ROWS>::CHUNKS ? tok(row) : -1;
         R.r0[u] = u32x4{0u, 0u, 0u, 0u};
         R.r1[u] = R.r0[u];
         if (t >= 0) {
@@ -114,15 +116,17 @@ __device__ __forceinline__ void fetch_rows(RowRegs<CW> &R, const bf16_t *__restr
     }
 }
 
-template <int CW>
-__device__ __forceinline__ void store_rows(bf16_t *T0, bf16_t *T1, const RowRegs<CW> &R)
+template <int CW, int ROWS>
+__device__ __forceinline__ void store_rows(bf16_t *T0, bf16_t *T1, const RowRegs<CW, ROWS> &R)
 {
     constexpr int CS = CW + 8, CH8 = CW / 8;
 #pragma unroll
-    for (int u = 0; u < RowRegs<CW>::NL; ++u) {
+    for (int u = 0; u < RowRegs<CW, ROWS>::NL; ++u) {
         const int idx = threadIdx.x + 256 * u, row = idx / CH8, c8 = idx % CH8;
-        *(u32x4 *)(T0 + row * CS + c8 * 8) = R.r0[u];
-        *(u32x4 *)(T1 + row * CS + c8 * 8) = R.r1[u];
+        if (idx < RowRegs<CW, ROWS>::CHUNKS) {
+            *(u32x4 *)(T0 + row * CS + c8 * 8) = R.r0[u];
+            *(u32x4 *)(T1 + row * CS + c8 * 8) = R.r1[u];
+        }
     }
 }
 
@@ -137,21 +141,21 @@ __device__ __forceinline__ void store_rows(bf16_t *T0, bf16_t *T1, const RowRegs
 // and leaves lse = log2 of the softmax denominator (with the scaled maximum folded in, so that
 // P = exp2(scale log2(e) s - lse)) and D per (token, head) for the key-side kernel.
 // dQ has row pitch ldq (it is the first third of the [M][3C] gradient map).
-template <int C, int HPW>
+template <int C, int HPW, int QR>
 __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                     const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                     const int32_t *__restrict__ Ir, bf16_t *__restrict__ O,
                                                     bf16_t *__restrict__ dQ, int ldq, float *__restrict__ lse,
                                                     float *__restrict__ dsum, Dims D, int qchunks)
 {
-    using L = BwdSmem<C, HPW>;
+    using L = BwdSmem<C, HPW, QR, 64>;
     constexpr int CS = L::CS, HEADS = L::HEADS, CW = L::CW, HG = HEADS / HPW;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::tile, *Qs = Vs + L::tile, *dOs = Qs + L::tile;
+    bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::ktile, *Qs = Vs + L::ktile, *dOs = Qs + L::qtile;
 
     const int h0 = ((int)blockIdx.x % HG) * HPW, bx = blockIdx.x / HG;       // first head of this workgroup
     const int qc = bx % qchunks, r = (bx / qchunks) % D.R, b = bx / (qchunks * D.R);
-    const int nq = min(64, D.n - 64 * qc), kn = D.kn;
+    const int nq = min(QR, D.n - 64 * qc), kn = D.kn;      // QR = 16: regions of at most 16 tokens
     const size_t img = (size_t)b * D.N;
     const int32_t *irow = Ir + ((size_t)b * D.R + r) * D.k;
     auto key_token = [&](int l) {          // key l of the gathered set (Eq. 6): slot l % n of routed region l / n
@@ -161,11 +165,12 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
     auto query_token = [&](int l) { return l < nq ? region_token(D, r, 64 * qc + l) : -1; };
     {
         // the query rows do not wait for the routing index: ask for them first
-        RowRegs<CW> qr, kr;
-        fetch_rows<C, CW>(qr, Q, dO, img, 32 * h0, query_token);
-        fetch_rows<C, CW>(kr, K, V, img, 32 * h0, key_token);
-        store_rows<CW>(Qs, dOs, qr);
-        store_rows<CW>(Ks, Vs, kr);
+        RowRegs<CW, QR> qr;
+        RowRegs<CW, 64> kr;
+        fetch_rows<C, CW, QR>(qr, Q, dO, img, 32 * h0, query_token);
+        fetch_rows<C, CW, 64>(kr, K, V, img, 32 * h0, key_token);
+        store_rows<CW, QR>(Qs, dOs, qr);
+        store_rows<CW, 64>(Ks, Vs, kr);
     }
     __syncthreads();
 
@@ -260,7 +265,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
     using L = BwdSmem<C, HPW>;
     constexpr int CS = L::CS, HEADS = L::HEADS, CW = L::CW, HG = HEADS / HPW;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::tile, *Qs = Vs + L::tile, *dOs = Qs + L::tile;
+    bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::ktile, *Qs = Vs + L::ktile, *dOs = Qs + L::qtile;
 
     const int h0 = ((int)blockIdx.x % HG) * HPW, bx = blockIdx.x / HG;
     const int qc = bx % qchunks, r = (bx / qchunks) % D.R, b = bx / (qchunks * D.R);
@@ -278,16 +283,16 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
     // the kernel was slower (99 against 90 us on a 2 x 128 x 128 x 64 map with 1024 keys per query)
     constexpr int DEPTH = 1;
     const int total = 2 * nblocks;        // both sweeps, as one sequence of blocks
-    RowRegs<CW> kr[DEPTH];
+    RowRegs<CW, 64> kr[DEPTH];
     {
-        RowRegs<CW> qr;
-        fetch_rows<C, CW>(qr, Q, dO, img, 32 * h0, query_token);
-        store_rows<CW>(Qs, dOs, qr);
+        RowRegs<CW, 64> qr;
+        fetch_rows<C, CW, 64>(qr, Q, dO, img, 32 * h0, query_token);
+        store_rows<CW, 64>(Qs, dOs, qr);
     }
     __syncthreads();                      // ir_s is in place
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
-        if (d < total) fetch_rows<C, CW>(kr[d], K, V, img, 32 * h0, [&](int l) { return key_token(64 * (d % nblocks) + l); });
+        if (d < total) fetch_rows<C, CW, 64>(kr[d], K, V, img, 32 * h0, [&](int l) { return key_token(64 * (d % nblocks) + l); });
     const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
     const float c_exp = D.scale * 1.4426950408889634f;
     const int qtiles = (nq + 15) / 16, ntasks = qtiles * HPW;
@@ -308,11 +313,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
             if (step >= total) break;
             const int sweep = step >= nblocks ? 1 : 0, kb = step - sweep * nblocks;
             __syncthreads();              // the previous block's readers are done
-            store_rows<CW>(Ks, Vs, kr[d]);
+            store_rows<CW, 64>(Ks, Vs, kr[d]);
             __syncthreads();
             if (step + DEPTH < total) {
                 const int nb = (step + DEPTH) % nblocks;
-                fetch_rows<C, CW>(kr[d], K, V, img, 32 * h0, [&](int l) { return key_token(64 * nb + l); });
+                fetch_rows<C, CW, 64>(kr[d], K, V, img, 32 * h0, [&](int l) { return key_token(64 * nb + l); });
             }
 #pragma unroll
             for (int u = 0; u < HPW; ++u) {
@@ -418,23 +423,23 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
 // in float32 registers across all query blocks; at the end dK, dV of its tokens are stored once as
 // bf16 into the second and third thirds of the [M][3C] gradient map (dKV points at the second).
 // Regions that no query attends to get zeros.
-template <int C, int HPW>
+template <int C, int HPW, int KR>
 __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                      const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                      const int32_t *__restrict__ Ir, const float *__restrict__ lse,
                                                      const float *__restrict__ dsum, bf16_t *__restrict__ dKV,
                                                      int ld, Dims D, int kchunks)
 {
-    using L = BwdSmem<C, HPW>;
+    using L = BwdSmem<C, HPW, 64, KR>;
     constexpr int CS = L::CS, HEADS = L::HEADS, CW = L::CW, HG = HEADS / HPW;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::tile, *Qs = Vs + L::tile, *dOs = Qs + L::tile;
+    bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::ktile, *Qs = Vs + L::ktile, *dOs = Qs + L::qtile;
     float *lse_s = (float *)(smem + L::stat_off), *dd_s = lse_s + HPW * 64;
     int *count = (int *)(smem + L::list_off), *list = count + 4;
 
     const int h0 = ((int)blockIdx.x % HG) * HPW, bx = blockIdx.x / HG;       // first head of this workgroup
     const int kc = bx % kchunks, jr = (bx / kchunks) % D.R, b = bx / (kchunks * D.R);
-    const int nk = min(64, D.n - 64 * kc);
+    const int nk = min(KR, D.n - 64 * kc);                  // KR = 16: regions of at most 16 tokens
     const size_t img = (size_t)b * D.N;
     auto key_token = [&](int l) { return l < nk ? region_token(D, jr, 64 * kc + l) : -1; };
     if (threadIdx.x == 0) *count = 0;
@@ -442,11 +447,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
     const int entries = D.R * D.k;
     const int32_t *irb = Ir + (size_t)b * entries;
     {
-        RowRegs<CW> kr;                   // in flight while the routing index is searched
-        fetch_rows<C, CW>(kr, K, V, img, 32 * h0, key_token);
+        RowRegs<CW, KR> kr;               // in flight while the routing index is searched
+        fetch_rows<C, CW, KR>(kr, K, V, img, 32 * h0, key_token);
         for (int e = threadIdx.x; e < entries; e += 256)
             if (min(max(irb[e], 0), D.R - 1) == jr) list[atomicAdd(count, 1)] = e;
-        store_rows<CW>(Ks, Vs, kr);
+        store_rows<CW, KR>(Ks, Vs, kr);
     }
     __syncthreads();
     const int m = *count;
@@ -474,11 +479,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
         return rho < rows ? region_token(D, list[rho / D.n] / D.k, rho % D.n) : -1;
     };
     // the next block's rows and statistics travel to registers while the current block is worked on
-    RowRegs<CW> next;
+    RowRegs<CW, 64> next;
     float next_lse = INFINITY, next_dd = 0.f;
     const int srow = threadIdx.x / HPW, sh = threadIdx.x % HPW;          // statistics: one (row, head) per thread
     auto fetch_block = [&](int r0) {
-        fetch_rows<C, CW>(next, Q, dO, img, 32 * h0, [&](int l) { return query_token(r0, l); });
+        fetch_rows<C, CW, 64>(next, Q, dO, img, 32 * h0, [&](int l) { return query_token(r0, l); });
         if ((int)threadIdx.x < 64 * HPW) {
             const int t = query_token(r0, srow);
             // a missing row: P = exp2(-inf) = 0 and dS = 0
@@ -490,7 +495,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
     if (rows > 0) fetch_block(0);
     for (int r0 = 0; r0 < rows; r0 += 64) {
         if (r0 > 0) __syncthreads();      // the previous block's readers are done
-        store_rows<CW>(Qs, dOs, next);
+        store_rows<CW, 64>(Qs, dOs, next);
         if ((int)threadIdx.x < 64 * HPW) {
             lse_s[sh * 64 + srow] = next_lse;
             dd_s[sh * 64 + srow] = next_dd;
@@ -1054,16 +1059,16 @@ BwdWs carve_bwd(const Dims &D, void *ws)
 
 bool launched() { return hipGetLastError() == hipSuccess; }
 
-template <int C, int HPW>
+template <int C, int HPW, int QR>
 int attn_bwd_q(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
     static bool opted = false;
-    if (!opt_in(k_attn_bwd_q<C, HPW>, opted)) return BRA_ERR_LAUNCH;
-    using L = BwdSmem<C, HPW>;
+    if (!opt_in(k_attn_bwd_q<C, HPW, QR>, opted)) return BRA_ERR_LAUNCH;
+    using L = BwdSmem<C, HPW, QR, 64>;
     const int chunks = (D.n + 63) / 64;
     const long blocks = (long)D.B * D.R * chunks * (L::HEADS / HPW);
     ProfScope ps(st, K_GEN_BACKWARD);
-    hipLaunchKernelGGL((k_attn_bwd_q<C, HPW>), dim3((unsigned)blocks), dim3(256), L::q_bytes, st, w.q, w.k, w.v, w.dO,
+    hipLaunchKernelGGL((k_attn_bwd_q<C, HPW, QR>), dim3((unsigned)blocks), dim3(256), L::q_bytes, st, w.q, w.k, w.v, w.dO,
                        Ir, w.o, w.dqkv, 3 * C, w.lse, w.dsum, D, chunks);
     return launched() ? BRA_OK : BRA_ERR_LAUNCH;
 }
@@ -1083,16 +1088,16 @@ int attn_bwd_q_blocks(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStrea
     return launched() ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
-template <int C, int HPW>
+template <int C, int HPW, int KR>
 int attn_bwd_kv(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
     static bool opted = false;
-    if (!opt_in(k_attn_bwd_kv<C, HPW>, opted)) return BRA_ERR_LAUNCH;
-    using L = BwdSmem<C, HPW>;
+    if (!opt_in(k_attn_bwd_kv<C, HPW, KR>, opted)) return BRA_ERR_LAUNCH;
+    using L = BwdSmem<C, HPW, 64, KR>;
     const int chunks = (D.n + 63) / 64;
     const long blocks = (long)D.B * D.R * chunks * (L::HEADS / HPW);
     ProfScope ps(st, K_GEN_BACKWARD);
-    hipLaunchKernelGGL((k_attn_bwd_kv<C, HPW>), dim3((unsigned)blocks), dim3(256), L::kv_bytes(D.R * D.k), st, w.q,
+    hipLaunchKernelGGL((k_attn_bwd_kv<C, HPW, KR>), dim3((unsigned)blocks), dim3(256), L::kv_bytes(D.R * D.k), st, w.q,
                        w.k, w.v, w.dO, Ir, w.lse, w.dsum, w.dqkv + C, 3 * C, D, chunks);
     return launched() ? BRA_OK : BRA_ERR_LAUNCH;
 }
@@ -1106,12 +1111,13 @@ int attn_bwd(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
     static const long split_above = experiment_value("BRA_BWD_HEAD_SPLIT", 32);
     constexpr int HPW = C / 32 < 4 ? C / 32 : 4;       // the tiles of four heads fill the LDS of half a compute unit
     int rc;
-    if (D.kn <= 64) rc = attn_bwd_q<C, HPW>(D, w, Ir, st);
+    const bool small = D.n <= 16;         // a region's tokens fit one 16-row tile
+    if (D.kn <= 64) rc = small ? attn_bwd_q<C, HPW, 16>(D, w, Ir, st) : attn_bwd_q<C, HPW, 64>(D, w, Ir, st);
     else if (D.n > split_above) rc = attn_bwd_q_blocks<C, 1>(D, w, Ir, st);
     else rc = attn_bwd_q_blocks<C, HPW>(D, w, Ir, st);
     if (rc != BRA_OK) return rc;
-    if (D.n > split_above) return attn_bwd_kv<C, 1>(D, w, Ir, st);
-    return attn_bwd_kv<C, HPW>(D, w, Ir, st);
+    if (D.n > split_above) return attn_bwd_kv<C, 1, 64>(D, w, Ir, st);
+    return small ? attn_bwd_kv<C, HPW, 16>(D, w, Ir, st) : attn_bwd_kv<C, HPW, 64>(D, w, Ir, st);
 }
 
 int gemm_tn(const bf16_t *A, int lda, int Ca, const bf16_t *Bm, int ldb, int Cb, float *Part, long M, hipStream_t st)
