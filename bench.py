@@ -277,8 +277,8 @@ def time_padded(steps, warmup):
 def time_backward(cfg, steps, warmup):
     """bra_backward (fixed routing) at a named workload's shape, with the workspace allocated once
     and HIP events around the timed calls: context, never `value`.  bf16 workloads with heads of 32
-    channels, C = 64, 128, 256, 384 or 512 and at most 4096 routing entries per image run on the matrix-core kernels, the others on
-    the scalar float32 ones."""
+    or 64 channels, C a multiple of 64 and at most 4096 routing entries per image run on the
+    matrix-core kernels, the others on the scalar float32 ones."""
     import ctypes
 
     import torch
@@ -304,7 +304,7 @@ def time_backward(cfg, steps, warmup):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / steps
     f = flops_per_image(cfg)
-    mfma = (cfg.dtype == "bf16" and cfg.C in (64, 128, 256, 384, 512) and cfg.C // cfg.heads == 32
+    mfma = (cfg.dtype == "bf16" and cfg.C % 64 == 0 and cfg.C // cfg.heads in (32, 64)
             and cfg.S * cfg.S * cfg.k <= 4096)
     # the backward pass recomputes the forward (1x) and does about twice its arithmetic again
     return {"images_per_s": round(cfg.B / (ms / 1e3), 1), "ms_per_step": round(ms, 4),

@@ -185,7 +185,7 @@ int bra_block_forward(const bra_shape *shape, int32_t hidden, float eps, const v
  * The forward intermediates are recomputed from X.  dX [B,H,W,C] has shape->dtype; the weight
  * gradients dWqkv [C,3C], dWo [C,C], dWlce [C,5,5] are float32, summed over the batch and
  * OVERWRITTEN.  Two kernel families, chosen by shape->path as in bra_forward:
- *   BRA_PATH_MFMA     bf16 tensors, heads of 32 channels, C = 64, 128, 256, 384 or 512 and
+ *   BRA_PATH_MFMA     bf16 tensors, heads of 32 or 64 channels, C a multiple of 64 and
  *                     S*S*k <= 4096 routing entries per image: matrix-core kernels with bf16
  *                     operands and float32 sums; Q, K, V, dO, P, dS, dQ, dK, dV are rounded to
  *                     bf16 between the products.  No atomic adds: dK, dV are summed per key

@@ -189,7 +189,7 @@ int bra_forward_padded(const bra_shape *shape, const void *X, const void *Wqkv, 
 }
 
 // Kernel family of the backward pass: the matrix-core kernels where they apply (bf16, heads of
-// 32 channels, C = 64, 128, 256, 384 or 512, at most 4096 routing entries per image), else the scalar
+// 32 or 64 channels, C a multiple of 64, at most 4096 routing entries per image), else the scalar
 // float32 kernels.
 static int pick_backward_path(const bra_shape *s, const Dims &D)
 {

@@ -1,5 +1,5 @@
-// Backward pass of the layer on the matrix cores (bf16 tensors, heads of 32 channels, C = 64, 128,
-// 256, 384 or 512, at most 4096 routing entries per image), with the routing index held fixed.
+// Backward pass of the layer on the matrix cores (bf16 tensors, heads of 32 or 64 channels, C a
+// multiple of 64 up to 4096, at most 4096 routing entries per image), with the routing index held fixed.
 //
 // Chain rule through Eq. 6-7 and Eq. 1-2, with O = Attention(Q, K^g, V^g) + LCE(V), Y = O Wo:
 //     dO = dY Wo^T                     projection kernel with Wo^T as its matrix
@@ -50,9 +50,11 @@ __device__ __forceinline__ bf16x8 tr_operand(const bf16_t *T, int pitch, int row
 }
 
 // acc[dt] = T^T[channel col + 16 dt + 4 g + j][..] x vals: T a 64-row tile (keys), vals[t][j] the
-// value of key 16 t + 4 g + j for this lane's query (accumulator layout of S^T = K Q^T).
+// value of key 16 t + 4 g + j for this lane's query (accumulator layout of S^T = K Q^T); NDT tiles of
+// 16 channels (a head).
+template <int NDT>
 __device__ __forceinline__ void keys_contract(const bf16_t *T, int pitch, const float (&vals)[4][4], int col,
-                                              int g, int i, f32x4 (&acc)[2])
+                                              int g, int i, f32x4 (&acc)[NDT])
 {
 #pragma unroll
     for (int tp = 0; tp < 2; ++tp) {
@@ -60,17 +62,19 @@ __device__ __forceinline__ void keys_contract(const bf16_t *T, int pitch, const 
                              vals[2 * tp + 1][0], vals[2 * tp + 1][1], vals[2 * tp + 1][2], vals[2 * tp + 1][3]};
         const bf16x8 pb = pack8(pv);
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
+        for (int dt = 0; dt < NDT; ++dt)
             acc[dt] = mfma16(tr_operand(T, pitch, 32 * tp, col + 16 * dt, g, i), pb, acc[dt]);
     }
 }
 
-// The attention kernels take HPW heads per workgroup: all C / 32 of them for small regions (a
-// (16-token tile, head) pair per wavefront), one where a region fills four tiles by itself, so that
-// more, lighter workgroups share a compute unit.  CW = 32 HPW channels of each row are staged.
-template <int C, int HPW, int QR = 64, int KR = 64>
+// The attention kernels are built for heads of DH = 32 or 64 channels and take HPW heads per
+// workgroup: up to 128 channels' worth for small regions (a (16-token tile, head) pair per
+// wavefront), one head where a region fills several tiles by itself, so that more, lighter workgroups
+// share a compute unit.  CW = DH HPW channels of each row are staged; the layer's C and its number
+// of heads are run-time values (row pitch of the maps, HPW divides the number of heads).
+template <int DH, int HPW, int QR = 64, int KR = 64>
 struct BwdSmem {
-    static constexpr int HEADS = C / 32, CW = 32 * HPW;
+    static constexpr int CW = DH * HPW;
     // elements per row of the token tiles: the 16-byte row reads and the transposing reads stay
     // conflict-free, and four workgroups of the C = 64 kernels share a compute unit's LDS
     static constexpr int CS = CW + 8;
@@ -98,9 +102,9 @@ struct RowRegs {
     u32x4 r0[NL], r1[NL];
 };
 
-template <int C, int CW, int ROWS, typename Tok>
+template <int CW, int ROWS, typename Tok>
 __device__ __forceinline__ void fetch_rows(RowRegs<CW, ROWS> &R, const bf16_t *__restrict__ M0,
-                                           const bf16_t *__restrict__ M1, size_t img, int c0, Tok tok)
+                                           const bf16_t *__restrict__ M1, size_t img, int C, int c0, Tok tok)
 {
     constexpr int CH8 = CW / 8;
 #pragma unroll
@@ -141,15 +145,16 @@ __device__ __forceinline__ void store_rows(bf16_t *T0, bf16_t *T1, const RowRegs
 // and leaves lse = log2 of the softmax denominator (with the scaled maximum folded in, so that
 // P = exp2(scale log2(e) s - lse)) and D per (token, head) for the key-side kernel.
 // dQ has row pitch ldq (it is the first third of the [M][3C] gradient map).
-template <int C, int HPW, int QR>
+template <int DH, int HPW, int QR>
 __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                     const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                     const int32_t *__restrict__ Ir, bf16_t *__restrict__ O,
                                                     bf16_t *__restrict__ dQ, int ldq, float *__restrict__ lse,
                                                     float *__restrict__ dsum, Dims D, int qchunks)
 {
-    using L = BwdSmem<C, HPW, QR, 64>;
-    constexpr int CS = L::CS, HEADS = L::HEADS, CW = L::CW, HG = HEADS / HPW;
+    using L = BwdSmem<DH, HPW, QR, 64>;
+    constexpr int CS = L::CS, CW = L::CW, NDT = DH / 16, NKS = DH / 32;
+    const int C = D.C, HEADS = D.heads, HG = HEADS / HPW;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::ktile, *Qs = Vs + L::ktile, *dOs = Qs + L::qtile;
 
@@ -167,8 +172,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
         // the query rows do not wait for the routing index: ask for them first
         RowRegs<CW, QR> qr;
         RowRegs<CW, 64> kr;
-        fetch_rows<C, CW, QR>(qr, Q, dO, img, 32 * h0, query_token);
-        fetch_rows<C, CW, 64>(kr, K, V, img, 32 * h0, key_token);
+        fetch_rows<CW, QR>(qr, Q, dO, img, C, DH * h0, query_token);
+        fetch_rows<CW, 64>(kr, K, V, img, C, DH * h0, key_token);
         store_rows<CW, QR>(Qs, dOs, qr);
         store_rows<CW, 64>(Ks, Vs, kr);
     }
@@ -179,17 +184,25 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
     const int qtiles = (nq + 15) / 16;
 #pragma unroll 1
     for (int task = w; task < qtiles * HPW; task += 4) {
-        const int qt = task % qtiles, hl = task / qtiles, h = h0 + hl, col = 32 * hl;   // col: within the tiles
+        const int qt = task % qtiles, hl = task / qtiles, h = h0 + hl, col = DH * hl;   // col: within the tiles
         const int q = 16 * qt + i, my_qtok = query_token(q);
-        const bf16x8 qf = *(const bf16x8 *)(Qs + q * CS + col + 8 * g);
-        const bf16x8 gf = *(const bf16x8 *)(dOs + q * CS + col + 8 * g);
+        bf16x8 qf[NKS], gf[NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            qf[ks] = *(const bf16x8 *)(Qs + q * CS + col + 32 * ks + 8 * g);
+            gf[ks] = *(const bf16x8 *)(dOs + q * CS + col + 32 * ks + 8 * g);
+        }
         f32x4 s[4], dp[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + col + 8 * g);
-            const bf16x8 vf = *(const bf16x8 *)(Vs + (16 * t + i) * CS + col + 8 * g);
-            s[t] = mfma16(kf, qf, f32x4{0.f, 0.f, 0.f, 0.f});     // S^T[key 16 t + 4 g + j][query i]
-            dp[t] = mfma16(vf, gf, f32x4{0.f, 0.f, 0.f, 0.f});    // dP^T, same layout
+            s[t] = dp[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + col + 32 * ks + 8 * g);
+                const bf16x8 vf = *(const bf16x8 *)(Vs + (16 * t + i) * CS + col + 32 * ks + 8 * g);
+                s[t] = mfma16(kf, qf[ks], s[t]);      // S^T[key 16 t + 4 g + j][query i]
+                dp[t] = mfma16(vf, gf[ks], dp[t]);    // dP^T, same layout
+            }
         }
         // a ragged key block: the missing keys get no weight (selects, not a branch between the matrix
         // instructions and the first read of their results)
@@ -223,20 +236,21 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
 #pragma unroll
             for (int j = 0; j < 4; ++j) ds[t][j] = p[t][j] * (dp[t][j] - dd);
 
-        f32x4 oacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-        f32x4 qacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+        f32x4 oacc[NDT], qacc[NDT];
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) oacc[dt] = qacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
         keys_contract(Vs, CS, p, col, g, i, oacc);       // O^T[channel col + 16 dt + 4 g + j][query i]
         keys_contract(Ks, CS, ds, col, g, i, qacc);      // dQ^T, same layout
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
+        for (int dt = 0; dt < NDT; ++dt) {
             oacc[dt] *= inv;
             qacc[dt] *= inv * D.scale;
         }
         if (my_qtok >= 0) {
 #pragma unroll
-            for (int dt = 0; dt < 2; ++dt) {
-                *(u32x2 *)(O + (img + my_qtok) * C + 32 * h + 16 * dt + 4 * g) = pack4(oacc[dt]);
-                *(u32x2 *)(dQ + (img + my_qtok) * (size_t)ldq + 32 * h + 16 * dt + 4 * g) = pack4(qacc[dt]);
+            for (int dt = 0; dt < NDT; ++dt) {
+                *(u32x2 *)(O + (img + my_qtok) * C + DH * h + 16 * dt + 4 * g) = pack4(oacc[dt]);
+                *(u32x2 *)(dQ + (img + my_qtok) * (size_t)ldq + DH * h + 16 * dt + 4 * g) = pack4(qacc[dt]);
             }
             if (g == 0) {
                 lse[(img + my_qtok) * HEADS + h] = mc + __builtin_amdgcn_logf(lsum);     // v_log_f32: log2
@@ -254,7 +268,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(const bf16_t *__restrict__ Q
 // lse = log2(l) + scale log2(e) m are final and stored.  Second sweep: P = exp2(scale log2(e) s - lse),
 // dS = P (dP - D), dQ^T += K^T dS^T; dQ = scale dQ^T at the end.  The next block's K, V rows travel
 // to registers while the current block is worked on.  A wavefront keeps the state of up to HPW pairs.
-template <int C, int HPW>
+template <int DH, int HPW>
 __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                            const bf16_t *__restrict__ V,
                                                            const bf16_t *__restrict__ dO,
@@ -262,8 +276,9 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
                                                            bf16_t *__restrict__ dQ, int ldq, float *__restrict__ lse,
                                                            float *__restrict__ dsum, Dims D, int qchunks)
 {
-    using L = BwdSmem<C, HPW>;
-    constexpr int CS = L::CS, HEADS = L::HEADS, CW = L::CW, HG = HEADS / HPW;
+    using L = BwdSmem<DH, HPW>;
+    constexpr int CS = L::CS, CW = L::CW, NDT = DH / 16, NKS = DH / 32;
+    const int C = D.C, HEADS = D.heads, HG = HEADS / HPW;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::ktile, *Qs = Vs + L::ktile, *dOs = Qs + L::qtile;
 
@@ -286,24 +301,25 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
     RowRegs<CW, 64> kr[DEPTH];
     {
         RowRegs<CW, 64> qr;
-        fetch_rows<C, CW, 64>(qr, Q, dO, img, 32 * h0, query_token);
+        fetch_rows<CW, 64>(qr, Q, dO, img, C, DH * h0, query_token);
         store_rows<CW, 64>(Qs, dOs, qr);
     }
     __syncthreads();                      // ir_s is in place
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
-        if (d < total) fetch_rows<C, CW, 64>(kr[d], K, V, img, 32 * h0, [&](int l) { return key_token(64 * (d % nblocks) + l); });
+        if (d < total) fetch_rows<CW, 64>(kr[d], K, V, img, C, DH * h0, [&](int l) { return key_token(64 * (d % nblocks) + l); });
     const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
     const float c_exp = D.scale * 1.4426950408889634f;
     const int qtiles = (nq + 15) / 16, ntasks = qtiles * HPW;
 
     float m[HPW], l[HPW], dd[HPW];        // per pair: maximum, sum, D~ (first sweep); then lse in m, D in dd
-    f32x4 acc[HPW][2];                    // O~^T, then dQ^T: [channel 16 dt + 4 g + j of the head][query i]
+    f32x4 acc[HPW][NDT];                  // O~^T, then dQ^T: [channel 16 dt + 4 g + j of the head][query i]
 #pragma unroll
     for (int u = 0; u < HPW; ++u) {
         m[u] = -INFINITY;
         l[u] = dd[u] = 0.f;
-        acc[u][0] = acc[u][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) acc[u][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 #pragma unroll 1
     for (int t0 = 0; t0 < total; t0 += DEPTH) {
@@ -317,22 +333,30 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
             __syncthreads();
             if (step + DEPTH < total) {
                 const int nb = (step + DEPTH) % nblocks;
-                fetch_rows<C, CW, 64>(kr[d], K, V, img, 32 * h0, [&](int l) { return key_token(64 * nb + l); });
+                fetch_rows<CW, 64>(kr[d], K, V, img, C, DH * h0, [&](int l) { return key_token(64 * nb + l); });
             }
 #pragma unroll
             for (int u = 0; u < HPW; ++u) {
                 const int task = w + 4 * u;
                 if (task >= ntasks) continue;
-                const int qt = task % qtiles, col = 32 * (task / qtiles), q = 16 * qt + i;
-                const bf16x8 qf = *(const bf16x8 *)(Qs + q * CS + col + 8 * g);
-                const bf16x8 gf = *(const bf16x8 *)(dOs + q * CS + col + 8 * g);
+                const int qt = task % qtiles, col = DH * (task / qtiles), q = 16 * qt + i;
+                bf16x8 qf[NKS], gf[NKS];
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) {
+                    qf[ks] = *(const bf16x8 *)(Qs + q * CS + col + 32 * ks + 8 * g);
+                    gf[ks] = *(const bf16x8 *)(dOs + q * CS + col + 32 * ks + 8 * g);
+                }
                 f32x4 s[4], dp[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + col + 8 * g);
-                    const bf16x8 vf = *(const bf16x8 *)(Vs + (16 * t + i) * CS + col + 8 * g);
-                    s[t] = mfma16(kf, qf, f32x4{0.f, 0.f, 0.f, 0.f});     // S^T[key 16 t + 4 g + j][query i]
-                    dp[t] = mfma16(vf, gf, f32x4{0.f, 0.f, 0.f, 0.f});    // dP^T, same layout
+                    s[t] = dp[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < NKS; ++ks) {
+                        const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * t + i) * CS + col + 32 * ks + 8 * g);
+                        const bf16x8 vf = *(const bf16x8 *)(Vs + (16 * t + i) * CS + col + 32 * ks + 8 * g);
+                        s[t] = mfma16(kf, qf[ks], s[t]);      // S^T[key 16 t + 4 g + j][query i]
+                        dp[t] = mfma16(vf, gf[ks], dp[t]);    // dP^T, same layout
+                    }
                 }
                 // the ragged last block: the missing keys get no weight (selects, not a branch between the
                 // matrix instructions and the first read of their results)
@@ -363,8 +387,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
                         }
                     l[u] = fmaf(l[u], alpha, cross_row_sum(ls));
                     dd[u] = fmaf(dd[u], alpha, cross_row_sum(ds));
-                    acc[u][0] *= alpha;
-                    acc[u][1] *= alpha;
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt) acc[u][dt] *= alpha;
                     keys_contract(Vs, CS, e, col, g, i, acc[u]);
                 } else {
 #pragma unroll
@@ -389,8 +413,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
                     const float dfin = dd[u] * inv;
                     if (tok >= 0) {
 #pragma unroll
-                        for (int dt = 0; dt < 2; ++dt)
-                            *(u32x2 *)(O + (img + tok) * C + 32 * h + 16 * dt + 4 * g) = pack4(acc[u][dt] * inv);
+                        for (int dt = 0; dt < NDT; ++dt)
+                            *(u32x2 *)(O + (img + tok) * C + DH * h + 16 * dt + 4 * g) = pack4(acc[u][dt] * inv);
                         if (g == 0) {
                             lse[(img + tok) * HEADS + h] = lse2;
                             dsum[(img + tok) * HEADS + h] = dfin;
@@ -398,11 +422,12 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
                     }
                     m[u] = lse2;
                     dd[u] = dfin;
-                    acc[u][0] = acc[u][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt) acc[u][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
                 } else if (tok >= 0) {
 #pragma unroll
-                    for (int dt = 0; dt < 2; ++dt)
-                        *(u32x2 *)(dQ + (img + tok) * (size_t)ldq + 32 * h + 16 * dt + 4 * g) =
+                    for (int dt = 0; dt < NDT; ++dt)
+                        *(u32x2 *)(dQ + (img + tok) * (size_t)ldq + DH * h + 16 * dt + 4 * g) =
                             pack4(acc[u][dt] * D.scale);
                 }
             }
@@ -423,15 +448,16 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q_blocks(const bf16_t *__restr
 // in float32 registers across all query blocks; at the end dK, dV of its tokens are stored once as
 // bf16 into the second and third thirds of the [M][3C] gradient map (dKV points at the second).
 // Regions that no query attends to get zeros.
-template <int C, int HPW, int KR>
+template <int DH, int HPW, int KR>
 __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                      const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                      const int32_t *__restrict__ Ir, const float *__restrict__ lse,
                                                      const float *__restrict__ dsum, bf16_t *__restrict__ dKV,
                                                      int ld, Dims D, int kchunks)
 {
-    using L = BwdSmem<C, HPW, 64, KR>;
-    constexpr int CS = L::CS, HEADS = L::HEADS, CW = L::CW, HG = HEADS / HPW;
+    using L = BwdSmem<DH, HPW, 64, KR>;
+    constexpr int CS = L::CS, CW = L::CW, NDT = DH / 16, NKS = DH / 32;
+    const int C = D.C, HEADS = D.heads, HG = HEADS / HPW;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *Ks = (bf16_t *)smem, *Vs = Ks + L::ktile, *Qs = Vs + L::ktile, *dOs = Qs + L::qtile;
     float *lse_s = (float *)(smem + L::stat_off), *dd_s = lse_s + HPW * 64;
@@ -448,7 +474,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
     const int32_t *irb = Ir + (size_t)b * entries;
     {
         RowRegs<CW, KR> kr;               // in flight while the routing index is searched
-        fetch_rows<C, CW, KR>(kr, K, V, img, 32 * h0, key_token);
+        fetch_rows<CW, KR>(kr, K, V, img, C, DH * h0, key_token);
         for (int e = threadIdx.x; e < entries; e += 256)
             if (min(max(irb[e], 0), D.R - 1) == jr) list[atomicAdd(count, 1)] = e;
         store_rows<CW, KR>(Ks, Vs, kr);
@@ -466,11 +492,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
     const int w = threadIdx.x / 64, lane = threadIdx.x % 64, g = lane / 16, i = lane % 16;
     const float c_exp = D.scale * 1.4426950408889634f;
     const int ktiles = (nk + 15) / 16, ntasks = ktiles * HPW;
-    f32x4 acc[HPW][4];                    // per task of this wavefront: dV^T (2 channel tiles), dK^T (2)
+    f32x4 acc[HPW][2 * NDT];              // per task of this wavefront: dV^T (NDT channel tiles), then dK^T
 #pragma unroll
     for (int u = 0; u < HPW; ++u)
 #pragma unroll
-        for (int a = 0; a < 4; ++a) acc[u][a] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int a = 0; a < 2 * NDT; ++a) acc[u][a] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int rows = m * D.n;
     // row r0 + l of the list of queries: slot .. % n of the query region of entry .. / n
@@ -483,7 +509,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
     float next_lse = INFINITY, next_dd = 0.f;
     const int srow = threadIdx.x / HPW, sh = threadIdx.x % HPW;          // statistics: one (row, head) per thread
     auto fetch_block = [&](int r0) {
-        fetch_rows<C, CW, 64>(next, Q, dO, img, 32 * h0, [&](int l) { return query_token(r0, l); });
+        fetch_rows<CW, 64>(next, Q, dO, img, C, DH * h0, [&](int l) { return query_token(r0, l); });
         if ((int)threadIdx.x < 64 * HPW) {
             const int t = query_token(r0, srow);
             // a missing row: P = exp2(-inf) = 0 and dS = 0
@@ -507,17 +533,25 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
         for (int u = 0; u < HPW; ++u) {
             const int task = w + 4 * u;
             if (task >= ntasks) continue;
-            const int kt = task % ktiles, h = task / ktiles, col = 32 * h;      // h, col: within the workgroup's heads
-            const bf16x8 kf = *(const bf16x8 *)(Ks + (16 * kt + i) * CS + col + 8 * g);
-            const bf16x8 vf = *(const bf16x8 *)(Vs + (16 * kt + i) * CS + col + 8 * g);
+            const int kt = task % ktiles, h = task / ktiles, col = DH * h;      // h, col: within the workgroup's heads
+            bf16x8 kf[NKS], vf[NKS];
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                kf[ks] = *(const bf16x8 *)(Ks + (16 * kt + i) * CS + col + 32 * ks + 8 * g);
+                vf[ks] = *(const bf16x8 *)(Vs + (16 * kt + i) * CS + col + 32 * ks + 8 * g);
+            }
             float p[4][4], ds[4][4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 if (t < qtiles) {
-                    const bf16x8 qf = *(const bf16x8 *)(Qs + (16 * t + i) * CS + col + 8 * g);
-                    const bf16x8 gf = *(const bf16x8 *)(dOs + (16 * t + i) * CS + col + 8 * g);
-                    const f32x4 s = mfma16(qf, kf, f32x4{0.f, 0.f, 0.f, 0.f});    // S[query 16 t + 4 g + j][key i]
-                    const f32x4 dp = mfma16(gf, vf, f32x4{0.f, 0.f, 0.f, 0.f});
+                    f32x4 s = {0.f, 0.f, 0.f, 0.f}, dp = s;
+#pragma unroll
+                    for (int ks = 0; ks < NKS; ++ks) {
+                        const bf16x8 qf = *(const bf16x8 *)(Qs + (16 * t + i) * CS + col + 32 * ks + 8 * g);
+                        const bf16x8 gf = *(const bf16x8 *)(dOs + (16 * t + i) * CS + col + 32 * ks + 8 * g);
+                        s = mfma16(qf, kf[ks], s);        // S[query 16 t + 4 g + j][key i]
+                        dp = mfma16(gf, vf[ks], dp);
+                    }
                     const f32x4 l4 = *(const f32x4 *)(lse_s + h * 64 + 16 * t + 4 * g);
                     const f32x4 d4 = *(const f32x4 *)(dd_s + h * 64 + 16 * t + 4 * g);
 #pragma unroll
@@ -539,9 +573,9 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
                                      ds[2 * tp + 1][0], ds[2 * tp + 1][1], ds[2 * tp + 1][2], ds[2 * tp + 1][3]};
                 const bf16x8 pb = pack8(pv), db = pack8(dv);
 #pragma unroll
-                for (int dt = 0; dt < 2; ++dt) {
+                for (int dt = 0; dt < NDT; ++dt) {
                     acc[u][dt] = mfma16(tr_operand(dOs, CS, 32 * tp, col + 16 * dt, g, i), pb, acc[u][dt]);
-                    acc[u][2 + dt] = mfma16(tr_operand(Qs, CS, 32 * tp, col + 16 * dt, g, i), db, acc[u][2 + dt]);
+                    acc[u][NDT + dt] = mfma16(tr_operand(Qs, CS, 32 * tp, col + 16 * dt, g, i), db, acc[u][NDT + dt]);
                 }
             }
         }
@@ -551,12 +585,12 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(const bf16_t *__restrict__ 
     for (int u = 0; u < HPW; ++u) {
         const int task = w + 4 * u;
         if (task >= ntasks) continue;
-        const int kt = task % ktiles, h = task / ktiles, col = 32 * (h0 + h);
+        const int kt = task % ktiles, h = task / ktiles, col = DH * (h0 + h);
         const int t = key_token(16 * kt + i);
         if (t < 0) continue;
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-            *(u32x2 *)(dKV + (img + t) * (size_t)ld + col + 16 * dt + 4 * g) = pack4(acc[u][2 + dt] * D.scale);
+        for (int dt = 0; dt < NDT; ++dt) {
+            *(u32x2 *)(dKV + (img + t) * (size_t)ld + col + 16 * dt + 4 * g) = pack4(acc[u][NDT + dt] * D.scale);
             *(u32x2 *)(dKV + (img + t) * (size_t)ld + C + col + 16 * dt + 4 * g) = pack4(acc[u][dt]);
         }
     }
@@ -1045,8 +1079,8 @@ BwdWs carve_bwd(const Dims &D, void *ws)
     w.dO = (bf16_t *)take(MC * 2);
     w.o = (bf16_t *)take(MC * 2);
     w.dqkv = (bf16_t *)take(MC * 6);
-    w.lse = (float *)take((size_t)M * (C / 32) * 4);
-    w.dsum = (float *)take((size_t)M * (C / 32) * 4);
+    w.lse = (float *)take((size_t)M * D.heads * 4);
+    w.dsum = (float *)take((size_t)M * D.heads * 4);
     w.part_qkv = (float *)take((size_t)(fused_projection(D.C) ? proj_plan(M, D.C).groups : tn_plan(M, D.C, 3 * D.C).gx) *
                                3 * C * C * 4);
     w.part_o = (float *)take((size_t)std::max(tn_plan(M, D.C, D.C).gx, proj_plan(M, D.C).groups) * C * C * 4);
@@ -1059,65 +1093,86 @@ BwdWs carve_bwd(const Dims &D, void *ws)
 
 bool launched() { return hipGetLastError() == hipSuccess; }
 
-template <int C, int HPW, int QR>
+template <int DH, int HPW, int QR>
 int attn_bwd_q(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
     static bool opted = false;
-    if (!opt_in(k_attn_bwd_q<C, HPW, QR>, opted)) return BRA_ERR_LAUNCH;
-    using L = BwdSmem<C, HPW, QR, 64>;
+    if (!opt_in(k_attn_bwd_q<DH, HPW, QR>, opted)) return BRA_ERR_LAUNCH;
+    using L = BwdSmem<DH, HPW, QR, 64>;
     const int chunks = (D.n + 63) / 64;
-    const long blocks = (long)D.B * D.R * chunks * (L::HEADS / HPW);
+    const long blocks = (long)D.B * D.R * chunks * (D.heads / HPW);
     ProfScope ps(st, K_GEN_BACKWARD);
-    hipLaunchKernelGGL((k_attn_bwd_q<C, HPW, QR>), dim3((unsigned)blocks), dim3(256), L::q_bytes, st, w.q, w.k, w.v, w.dO,
-                       Ir, w.o, w.dqkv, 3 * C, w.lse, w.dsum, D, chunks);
+    hipLaunchKernelGGL((k_attn_bwd_q<DH, HPW, QR>), dim3((unsigned)blocks), dim3(256), L::q_bytes, st, w.q, w.k, w.v,
+                       w.dO, Ir, w.o, w.dqkv, 3 * D.C, w.lse, w.dsum, D, chunks);
     return launched() ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
-template <int C, int HPW>
+template <int DH, int HPW>
 int attn_bwd_q_blocks(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
     static bool opted = false;
-    if (!opt_in(k_attn_bwd_q_blocks<C, HPW>, opted)) return BRA_ERR_LAUNCH;
-    using L = BwdSmem<C, HPW>;
+    if (!opt_in(k_attn_bwd_q_blocks<DH, HPW>, opted)) return BRA_ERR_LAUNCH;
+    using L = BwdSmem<DH, HPW>;
     const int chunks = (D.n + 63) / 64;
-    const long blocks = (long)D.B * D.R * chunks * (L::HEADS / HPW);
+    const long blocks = (long)D.B * D.R * chunks * (D.heads / HPW);
     ProfScope ps(st, K_GEN_BACKWARD);
-    hipLaunchKernelGGL((k_attn_bwd_q_blocks<C, HPW>), dim3((unsigned)blocks), dim3(256),
-                       L::q_bytes + (size_t)D.k * sizeof(int), st, w.q, w.k, w.v, w.dO, Ir, w.o, w.dqkv, 3 * C, w.lse,
+    hipLaunchKernelGGL((k_attn_bwd_q_blocks<DH, HPW>), dim3((unsigned)blocks), dim3(256),
+                       L::q_bytes + (size_t)D.k * sizeof(int), st, w.q, w.k, w.v, w.dO, Ir, w.o, w.dqkv, 3 * D.C, w.lse,
                        w.dsum, D, chunks);
     return launched() ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
-template <int C, int HPW, int KR>
+template <int DH, int HPW, int KR>
 int attn_bwd_kv(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
     static bool opted = false;
-    if (!opt_in(k_attn_bwd_kv<C, HPW, KR>, opted)) return BRA_ERR_LAUNCH;
-    using L = BwdSmem<C, HPW, 64, KR>;
+    if (!opt_in(k_attn_bwd_kv<DH, HPW, KR>, opted)) return BRA_ERR_LAUNCH;
+    using L = BwdSmem<DH, HPW, 64, KR>;
     const int chunks = (D.n + 63) / 64;
-    const long blocks = (long)D.B * D.R * chunks * (L::HEADS / HPW);
+    const long blocks = (long)D.B * D.R * chunks * (D.heads / HPW);
     ProfScope ps(st, K_GEN_BACKWARD);
-    hipLaunchKernelGGL((k_attn_bwd_kv<C, HPW, KR>), dim3((unsigned)blocks), dim3(256), L::kv_bytes(D.R * D.k), st, w.q,
-                       w.k, w.v, w.dO, Ir, w.lse, w.dsum, w.dqkv + C, 3 * C, D, chunks);
+    hipLaunchKernelGGL((k_attn_bwd_kv<DH, HPW, KR>), dim3((unsigned)blocks), dim3(256), L::kv_bytes(D.R * D.k), st, w.q,
+                       w.k, w.v, w.dO, Ir, w.lse, w.dsum, w.dqkv + D.C, 3 * D.C, D, chunks);
     return launched() ? BRA_OK : BRA_ERR_LAUNCH;
 }
 
-// Query side with all heads in one workgroup; key side with one head per workgroup where a region's
-// tokens alone make three or four 16-token tiles (measured on a 64 x 56 x 56 x 64 map with regions
-// of 64 tokens: query side 40 us whole against 45 us split, key side 55 us whole against 52.5 us split).
-template <int C>
-int attn_bwd(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
+// Both attention kernels with HPW heads per workgroup (HPW divides the number of heads, DH HPW <= 128
+// channels: the tiles then fill the LDS of half a compute unit at most).  Where a region's tokens
+// alone make three or four 16-token tiles, the key side and the multi-block query side take one
+// head per workgroup (measured on a 64 x 56 x 56 x 64 map with regions of 64 tokens: query side 40 us
+// whole against 45 us split, key side 55 us whole against 52.5 us split).
+template <int DH, int HPW>
+int attn_bwd_heads(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
 {
     static const long split_above = experiment_value("BRA_BWD_HEAD_SPLIT", 32);
-    constexpr int HPW = C / 32 < 4 ? C / 32 : 4;       // the tiles of four heads fill the LDS of half a compute unit
     int rc;
     const bool small = D.n <= 16;         // a region's tokens fit one 16-row tile
-    if (D.kn <= 64) rc = small ? attn_bwd_q<C, HPW, 16>(D, w, Ir, st) : attn_bwd_q<C, HPW, 64>(D, w, Ir, st);
-    else if (D.n > split_above) rc = attn_bwd_q_blocks<C, 1>(D, w, Ir, st);
-    else rc = attn_bwd_q_blocks<C, HPW>(D, w, Ir, st);
+    if (D.kn <= 64) rc = small ? attn_bwd_q<DH, HPW, 16>(D, w, Ir, st) : attn_bwd_q<DH, HPW, 64>(D, w, Ir, st);
+    else if (D.n > split_above) rc = attn_bwd_q_blocks<DH, 1>(D, w, Ir, st);
+    else rc = attn_bwd_q_blocks<DH, HPW>(D, w, Ir, st);
     if (rc != BRA_OK) return rc;
-    if (D.n > split_above) return attn_bwd_kv<C, 1, 64>(D, w, Ir, st);
-    return small ? attn_bwd_kv<C, HPW, 16>(D, w, Ir, st) : attn_bwd_kv<C, HPW, 64>(D, w, Ir, st);
+    if (D.n > split_above) return attn_bwd_kv<DH, 1, 64>(D, w, Ir, st);
+    return small ? attn_bwd_kv<DH, HPW, 16>(D, w, Ir, st) : attn_bwd_kv<DH, HPW, 64>(D, w, Ir, st);
+}
+
+// Heads per workgroup: the largest of 4, 2, 1 that divides the number of heads and keeps DH HPW <= 128.
+int heads_per_workgroup(const Dims &D)
+{
+    for (int hpw = 4; hpw > 1; hpw /= 2)
+        if (D.heads % hpw == 0 && D.d * hpw <= 128) return hpw;
+    return 1;
+}
+
+int attn_bwd(const Dims &D, const BwdWs &w, const int32_t *Ir, hipStream_t st)
+{
+    const int hpw = heads_per_workgroup(D);
+    if (D.d == 32) {
+        if (hpw == 4) return attn_bwd_heads<32, 4>(D, w, Ir, st);
+        if (hpw == 2) return attn_bwd_heads<32, 2>(D, w, Ir, st);
+        return attn_bwd_heads<32, 1>(D, w, Ir, st);
+    }
+    if (hpw == 2) return attn_bwd_heads<64, 2>(D, w, Ir, st);
+    return attn_bwd_heads<64, 1>(D, w, Ir, st);
 }
 
 int gemm_tn(const bf16_t *A, int lda, int Ca, const bf16_t *Bm, int ldb, int Cb, float *Part, long M, hipStream_t st)
@@ -1134,19 +1189,16 @@ constexpr int kBwdMaxEntries = 4096;
 
 }  // namespace
 
-// Channel counts the attention kernels are instantiated for.
-static bool bwd_channels_ok(int C) { return C == 64 || C == 128 || C == 256 || C == 384 || C == 512; }
-
 // The projection kernels specialised by channel count (they also carry the weight transposes along).
 static bool narrow_projection(int C) { return C == 64 || C == 128 || C == 256; }
 
 bool mfma_backward_supported(const Dims &D)
 {
     static const bool off = experiment_flag("BRA_NO_MFMA_BACKWARD");
-    if (off || D.dtype != BRA_BF16 || D.d != 32 || !bwd_channels_ok(D.C)) return false;
+    if (off || D.dtype != BRA_BF16 || (D.d != 32 && D.d != 64) || D.C % 64 != 0 || D.C > 4096) return false;
     if ((long)D.R * D.k > kBwdMaxEntries) return false;
     const long M = (long)D.B * D.N;
-    return M * 3 * D.C < (1L << 40) && (long)D.B * D.R * ((D.n + 63) / 64) * (D.C / 32) <= 0x7fffffffL &&
+    return M * 3 * D.C < (1L << 40) && (long)D.B * D.R * ((D.n + 63) / 64) * D.heads <= 0x7fffffffL &&
            M <= 0x7fffffffL;
 }
 
@@ -1178,13 +1230,7 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
         rc = gemm_bf16((const bf16_t *)dY, w.wot, M, C, C, w.dO, nullptr, nullptr, false, K_GEN_BACKWARD, st);
     }
     if (rc != BRA_OK) return rc;
-    switch (C) {                                                                  // O, dQ; then dK, dV
-    case 64: rc = attn_bwd<64>(D, w, Ir, st); break;
-    case 128: rc = attn_bwd<128>(D, w, Ir, st); break;
-    case 256: rc = attn_bwd<256>(D, w, Ir, st); break;
-    case 384: rc = attn_bwd<384>(D, w, Ir, st); break;
-    default: rc = attn_bwd<512>(D, w, Ir, st); break;
-    }
+    rc = attn_bwd(D, w, Ir, st);                                              // O, dQ; then dK, dV
     if (rc != BRA_OK) return rc;
     const TapPlan tp = tap_plan(D);
     {

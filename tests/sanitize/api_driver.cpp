@@ -33,8 +33,8 @@ int main()
     };
     for (const bra_shape &s : shapes) {
         EXPECT(bra_workspace_bytes(&s, &n), BRA_OK);
-        // the matrix-core backward is built for heads of 32 channels and C up to 512 only
-        const bool bwd_ok = s.path != BRA_PATH_MFMA || (s.C <= 512 && s.C / s.heads == 32);
+        // the matrix-core backward covers heads of 32 and 64 channels, C a multiple of 64
+        const bool bwd_ok = s.path != BRA_PATH_MFMA || (s.C % 64 == 0 && (s.C / s.heads == 32 || s.C / s.heads == 64));
         EXPECT(bra_backward_workspace_bytes(&s, &n), bwd_ok ? BRA_OK : BRA_ERR_UNSUPPORTED);
         EXPECT(bra_padded_workspace_bytes(&s, &n), BRA_OK);
         if (s.path != BRA_PATH_GENERIC || s.dtype == BRA_F32) EXPECT(bra_block_workspace_bytes(&s, 3 * s.C, &n), BRA_OK);

@@ -31,7 +31,7 @@ SHAPES = [
 ]
 
 
-# bf16 shapes of the matrix-core backward (heads of 32 channels, C = 64 .. 512): a full 64-key
+# bf16 shapes of the matrix-core backward (heads of 32 or 64 channels, C a multiple of 64): a full 64-key
 # block, ragged key and query blocks (n = 49; k n = 48, 36, 2), one token per region, maps wider than
 # one tile of the depth-wise kernel with a ragged last tile (W = 56, 40)
 MFMA_SHAPES = [
@@ -55,6 +55,13 @@ MFMA_SHAPES = [
     ("bf16", 2, 14, 14, 384, 12, 7, 16),
     ("bf16", 1, 16, 24, 512, 16, 4, 3),
     ("bf16", 2, 7, 7, 512, 16, 7, 49),
+    # other head counts (two heads or one per workgroup) and heads of 64 channels
+    ("bf16", 2, 8, 8, 192, 6, 2, 2),
+    ("bf16", 1, 12, 12, 320, 10, 3, 4),
+    ("bf16", 2, 14, 14, 128, 2, 7, 4),
+    ("bf16", 1, 16, 16, 64, 1, 2, 1),
+    ("bf16", 1, 16, 24, 256, 4, 4, 5),
+    ("bf16", 1, 20, 36, 192, 3, 2, 2),
 ]
 
 
@@ -144,9 +151,9 @@ def test_backward_named_workloads_full_size(idx):
                      path="mfma" if cfg.dtype == "bf16" else "generic")
 
 
-@pytest.mark.parametrize("idx", [6, 7])
+@pytest.mark.parametrize("idx", [6, 7, 8])
 def test_backward_wide_workloads_full_size(idx):
-    # the two next-step shapes with heads of 32 channels (C = 512 and 384) at their full sizes
+    # the next-step shapes with C = 512, 384 (heads of 32 channels) and 768 (heads of 64) at their full sizes
     from synthetic_inputs import NEXT_CONFIGS
     cfg = NEXT_CONFIGS[idx]
     Xn, Wqkvn, Won, Wlcen = make_config_inputs(cfg)
