@@ -62,6 +62,8 @@ MFMA_SHAPES = [
     ("bf16", 1, 16, 16, 64, 1, 2, 1),
     ("bf16", 1, 16, 24, 256, 4, 4, 5),
     ("bf16", 1, 20, 36, 192, 3, 2, 2),
+    # 256 regions per image (1024 routing entries)
+    ("bf16", 1, 32, 48, 64, 2, 16, 4),
 ]
 
 
@@ -126,8 +128,10 @@ def random_matrix_core_shapes(count, seed):
     while len(out) < count:
         S = rng.choice([1, 2, 3, 4, 5, 7])
         H, W = S * rng.choice([1, 2, 3, 4, 5, 9, 12]), S * rng.choice([1, 2, 3, 4, 6, 11])
-        heads = rng.choice([2, 4, 8])
-        C = 32 * heads
+        heads, d = rng.choice([1, 2, 3, 4, 6, 8]), rng.choice([32, 32, 64])
+        C = d * heads
+        if C % 64:
+            continue
         k = rng.choice([1, 2, 3, min(S * S, 5), S * S])
         n = (H // S) * (W // S)
         if k > S * S or H * W * C > 150000 or H * W * k * n * C > 6e7:
@@ -136,7 +140,7 @@ def random_matrix_core_shapes(count, seed):
     return out
 
 
-@pytest.mark.parametrize("dtype,B,H,W,C,heads,S,k", random_matrix_core_shapes(16, seed=20230312))
+@pytest.mark.parametrize("dtype,B,H,W,C,heads,S,k", random_matrix_core_shapes(24, seed=20230312))
 def test_backward_matrix_cores_random_shapes(dtype, B, H, W, C, heads, S, k):
     test_backward(dtype, B, H, W, C, heads, S, k, path="mfma")
 
