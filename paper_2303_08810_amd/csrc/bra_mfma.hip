@@ -697,7 +697,7 @@ struct TileMap {
 // Q, K, V = X [Wq | Wk | Wv]  (Eq. 3; NMAT = 3), or a single projection such as Y = O Wo
 // (Eq. 2; NMAT = 1, every output pointer the same).  Each wavefront owns 32 RT output channels of one
 // of the NMAT matrices and keeps its weight fragments in registers; a workgroup is
-// WPB such wavefronts (blockIdx.y selects which; a multiple of 4 per compute unit keeps its four
+// WPB such wavefronts (the column group of the workgroup selects which; a multiple of 4 per compute unit keeps its four
 // SIMDs equally busy) and walks over `tiles_per_wg`
 // consecutive tiles of 64 tokens (gx such workgroups; those before them route from pooled X, those
 // after them rearrange the weights for the kernels that follow, when the launch carries such work).
@@ -731,18 +731,28 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
     // projection), the last ones rearrange weights.
     if ((int)blockIdx.x < prep.route_items) {
         // wavefronts past the fourth leave: a barrier waits for the surviving ones only
-        if (blockIdx.y == 0 && threadIdx.x < 256)
+        if (threadIdx.x < 256)
             route_body<C>(prep.Xr, prep.WT, prep.Ir, nullptr, prep.dims, smem, (int)blockIdx.x);
         return;
     }
-    const int bx = (int)blockIdx.x - prep.route_items;
-    if (bx >= gx) {
-        if (blockIdx.y == 0) {
-            const int e = (bx - gx) * NTH + (int)threadIdx.x;
-            if (e < prep.elems)
-                prep_weight_element(prep.Wqkv, prep.Wo, prep.Wlce, prep.WT, prep.WoT, prep.Wa, prep.Wf, C, e);
-        }
+    // GY workgroups (column groups of the outputs) share every token range.  The grid is one-dimensional
+    // and consecutive workgroups go to the 8 XCDs in turn: the column groups of a range get numbers 8
+    // apart, so that they run on one XCD at about the same time and the range's tokens are fetched
+    // from memory once instead of GY times.
+    constexpr int GY = NMAT * C / (32 * RT) / WPB;
+    const int tw = (int)blockIdx.x - prep.route_items;
+    if (tw >= gx * GY) {
+        const int e = (tw - gx * GY) * NTH + (int)threadIdx.x;
+        if (e < prep.elems)
+            prep_weight_element(prep.Wqkv, prep.Wo, prep.Wlce, prep.WT, prep.WoT, prep.Wa, prep.Wf, C, e);
         return;
+    }
+    int bx = tw, by = 0;
+    if (GY > 1) {
+        const int first = tw / (8 * GY) * 8, within = tw % (8 * GY);
+        const int ranges = gx - first < 8 ? gx - first : 8;       // the last group may hold fewer than 8 ranges
+        by = within / ranges;
+        bx = first + within % ranges;
     }
 #ifdef BRA_EXPERIMENT
     unsigned long long trace_t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -758,7 +768,7 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
 #endif
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int i = lane % 16;
-    const int grp = blockIdx.y * WPB + wave;            // channel group among NMAT C / CW
+    const int grp = by * WPB + wave;                    // channel group among NMAT C / CW
     const int sel = grp / (C / CW), base = (grp % (C / CW)) * CW;
     bf16_t *__restrict__ out = sel == 0 ? Q : (sel == 1 ? K : V);
     const int group_log2 = tm.sum_log2, group = 1 << group_log2;
@@ -992,7 +1002,7 @@ void k_qkv(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W, bf16_t *_
     if (prep.trace) {
         BRA_TRACE(4);
         __syncthreads();
-        if (threadIdx.x == 0 && blockIdx.y == 0) {
+        if (threadIdx.x == 0 && by == 0) {
             unsigned long long *o = (unsigned long long *)(Q + tile0 * 64 * C);
             for (int k = 0; k < 5; ++k) o[k] = trace_t[k];
             o[5] = (unsigned long long)(tile1 - tile0);
@@ -1707,7 +1717,7 @@ int launch_qkv(const Dims &D, const bf16_t *X, const bf16_t *Wqkv, const MfmaWs 
     static bool opted = false;
     if (!lds_opt_in(k_qkv<C, WPB, 3, RT>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_QKV);
-    hipLaunchKernelGGL((k_qkv<C, WPB, 3, RT>), dim3(gx + prep_blocks, gy), dim3(64 * WPB), smem, st, X, Wqkv, w.q,
+    hipLaunchKernelGGL((k_qkv<C, WPB, 3, RT>), dim3(gx * gy + prep_blocks), dim3(64 * WPB), smem, st, X, Wqkv, w.q,
                        w.k, w.v, pooled ? w.p : nullptr, tile_map(D, pooled), M, (int)tpw, gx, prep, qscale);
     return BRA_OK;
 }
@@ -1726,7 +1736,7 @@ int launch_wo(const Dims &D, const bf16_t *O, const bf16_t *Wo, bf16_t *Y, hipSt
     static bool opted = false;
     if (!lds_opt_in(k_qkv<C, WPB, 1, RT>, opted)) return BRA_ERR_LAUNCH;
     ProfScope ps(st, K_MFMA_WO);
-    hipLaunchKernelGGL((k_qkv<C, WPB, 1, RT>), dim3(gx, 1), dim3(64 * WPB), smem, st, O, Wo, Y, Y, Y, nullptr,
+    hipLaunchKernelGGL((k_qkv<C, WPB, 1, RT>), dim3(gx), dim3(64 * WPB), smem, st, O, Wo, Y, Y, Y, nullptr,
                        tile_map(D, false), M,
                        (int)tpw, gx, PrepArgs{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0}, 1.0f);
     return hipGetLastError() == hipSuccess ? BRA_OK : BRA_ERR_LAUNCH;
