@@ -968,19 +968,26 @@ __global__ void k_bwd_transpose(const bf16_t *__restrict__ Wqkv, const bf16_t *_
     else if (e < 4 * C * C) WoT[e - 3 * C * C] = Wo[(size_t)((e - 3 * C * C) % C) * C + (e - 3 * C * C) / C];
 }
 
-// out[e] = sum_p part[p][e], p in a fixed order, for up to three arrays in one launch: 32
-// elements x 32 slices of p per workgroup, the slices summed through LDS.
+// out[e] = sum_p part[p][e], p in a fixed order, for up to three arrays in one launch.  A workgroup
+// of 1024 threads takes 1024 / slices elements x `slices` slices of p (a power of two up to 32, about
+// the number of partial arrays), the slices summed through LDS.
 struct ReduceJob {
     const float *part;
     float *out;
-    int nparts, count, blocks;
+    int nparts, count, slices, blocks;
 };
 
-constexpr int kReduceElems = 32, kReduceSlices = 32;
+ReduceJob reduce_job(const float *part, float *out, int nparts, int count)
+{
+    int slices = 1;
+    while (slices < 32 && slices < nparts) slices *= 2;
+    const int elems = 1024 / slices;
+    return ReduceJob{part, out, nparts, count, slices, (count + elems - 1) / elems};
+}
 
 __global__ __launch_bounds__(1024) void k_reduce_parts(ReduceJob j0, ReduceJob j1, ReduceJob j2)
 {
-    __shared__ float red[kReduceSlices][kReduceElems + 1];
+    __shared__ float red[1024];
     int bi = blockIdx.x;
     ReduceJob job = j0;
     if (bi >= j0.blocks) {
@@ -991,17 +998,17 @@ __global__ __launch_bounds__(1024) void k_reduce_parts(ReduceJob j0, ReduceJob j
             job = j2;
         }
     }
-    const int x = threadIdx.x % kReduceElems, y = threadIdx.x / kReduceElems, e = bi * kReduceElems + x;
+    const int elems = 1024 / job.slices;
+    const int x = threadIdx.x % elems, y = threadIdx.x / elems, e = bi * elems + x;
     float sum = 0.f;
     if (e < job.count)
 #pragma unroll 8
-        for (int p = y; p < job.nparts; p += kReduceSlices) sum += job.part[(size_t)p * job.count + e];
-    red[y][x] = sum;
+        for (int p = y; p < job.nparts; p += job.slices) sum += job.part[(size_t)p * job.count + e];
+    red[y * elems + x] = sum;
     __syncthreads();
     if (y == 0 && e < job.count) {
         float total = 0.f;
-#pragma unroll
-        for (int u = 0; u < kReduceSlices; ++u) total += red[u][x];
+        for (int u = 0; u < job.slices; ++u) total += red[u * elems + x];
         job.out[e] = total;
     }
 }
@@ -1270,11 +1277,10 @@ int mfma_backward(const Dims &D, const void *X, const void *Wqkv, const void *Wo
         if (rc != BRA_OK) return rc;
     }
     {
-        const int per = kReduceElems;
-        const ReduceJob j0{w.part_qkv, dWqkv, fused_projection(C) ? pp.groups : tn_plan(M, C, 3 * C).gx, 3 * C * C,
-                           (3 * C * C + per - 1) / per};
-        const ReduceJob j1{w.part_o, dWo, with_o ? pp.groups : tn_plan(M, C, C).gx, C * C, (C * C + per - 1) / per};
-        const ReduceJob j2{w.part_lce, dWlce, tp.groups, 25 * C, (25 * C + per - 1) / per};
+        const ReduceJob j0 = reduce_job(w.part_qkv, dWqkv, fused_projection(C) ? pp.groups : tn_plan(M, C, 3 * C).gx,
+                                        3 * C * C);
+        const ReduceJob j1 = reduce_job(w.part_o, dWo, with_o ? pp.groups : tn_plan(M, C, C).gx, C * C);
+        const ReduceJob j2 = reduce_job(w.part_lce, dWlce, tp.groups, 25 * C);
         ProfScope ps(st, K_GEN_BACKWARD);
         hipLaunchKernelGGL(k_reduce_parts, dim3(j0.blocks + j1.blocks + j2.blocks), dim3(1024), 0, st, j0, j1, j2);
         if (!launched()) return BRA_ERR_LAUNCH;
